@@ -1,0 +1,538 @@
+/*
+ * lmk_ref.c -- CPU oracle for tile-based 3D Gaussian splatting (forward).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU renderer is checked against.  It shares no code, header, table or
+ * constant generator with the HIP library, and nothing in the product path may
+ * import, link or call it.
+ *
+ * What it follows (LandMarkSystem technical report):
+ *   Sec. 2.2 Eq. 7   the 3D Gaussian primitive G(x)
+ *   Sec. 2.2 Eq. 8   covariance from rotation and scale, Sigma = R S S^T R^T
+ *   Sec. 2.2 (text)  SH colour + opacity per primitive; EWA projection to a 2D
+ *                    Gaussian ("splatting"); depth sort; blending per screen tile
+ *   Sec. 2.2 Eq. 9-10  front-to-back compositing with sigma_i = alpha_i G'_i(x')
+ *   Sec. 4.2.1       the rasteriser stages named there: per-primitive projection,
+ *                    duplication into (tile, depth) keys, sort, per-tile blend
+ *
+ * The report prints no constants (tile size, thresholds, SH basis, pixel
+ * centres, key layout).  The readings taken here are listed at each step and
+ * marked [reading].
+ *
+ * Precision.  Everything that decides an integer (depth bits in the sort key,
+ * the tile rectangle, every cull) is evaluated in IEEE fp32, one rounding per
+ * written operation, left to right, no fused multiply-add (compile with
+ * -ffp-contract=off).  The GPU side evaluates the same formulas in the same
+ * precision, so keys and rectangles are unique.  Everything else (SH colour,
+ * the blend) is evaluated in fp64 from those fp32 inputs; the two blend
+ * decisions (alpha below 1/255, transmittance below 1e-4) are taken on the
+ * value rounded to fp32, the precision the kernel decides in.
+ *
+ * Pins (tests/test_oracle_*.py): closed-form isotropic footprint, single and
+ * double splat closed forms, SH orthonormality and addition theorem against a
+ * library routine, brute-force per-pixel compositing over all primitives,
+ * tile-size independence, transmittance monotonicity, sort/CSR invariants.
+ * No function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifndef M_PI
+#define M_PI 3.14159265358979323846
+#endif
+
+typedef struct {
+    float view[12];   /* row-major 3x4 world->camera [R|t]; +x right, +y down, +z forward */
+    float cam_pos[3]; /* camera centre in world space */
+    float fx, fy, cx, cy;
+    uint32_t width, height, tile;
+    float near_z;
+    float lowpass;    /* h: added to the diagonal of the 2D covariance, px^2 */
+    float bg[3];
+} ref_camera;
+
+/* cull stage recorded per primitive */
+enum { REF_VISIBLE = 0, REF_CULL_NEAR = 1, REF_CULL_DET = 2, REF_CULL_OPACITY = 3, REF_CULL_OFFSCREEN = 4 };
+
+#define REF_TAU 11.09f            /* [reading] support: q <= tau, a hair above 2 ln 255 */
+#define REF_ALPHA_MIN (1.0f / 255.0f)
+#define REF_ALPHA_MAX 0.99f
+#define REF_T_MIN 1e-4f
+
+static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+/* clamp that sends NaN to lo */
+static float clampf_lo(float v, float lo, float hi) { return !(v > lo) ? lo : (v > hi ? hi : v); }
+
+/* ------------------------------------------------------------------ */
+/* Sec. 2.2 Eq. 8: rotation matrix from a (w,x,y,z) quaternion [reading: order] */
+static void quat_to_rot(const float q[4], float R[3][3])
+{
+    float n = sqrtf(q[0] * q[0] + q[1] * q[1] + q[2] * q[2] + q[3] * q[3]);
+    float w = q[0] / n, x = q[1] / n, y = q[2] / n, z = q[3] / n;
+    R[0][0] = 1.0f - 2.0f * (y * y + z * z);
+    R[0][1] = 2.0f * (x * y - w * z);
+    R[0][2] = 2.0f * (x * z + w * y);
+    R[1][0] = 2.0f * (x * y + w * z);
+    R[1][1] = 1.0f - 2.0f * (x * x + z * z);
+    R[1][2] = 2.0f * (y * z - w * x);
+    R[2][0] = 2.0f * (x * z - w * y);
+    R[2][1] = 2.0f * (y * z + w * x);
+    R[2][2] = 1.0f - 2.0f * (x * x + y * y);
+}
+
+/* Sec. 2.2 Eq. 8: Sigma = (R S)(R S)^T, S = diag(s) */
+static void covariance3d(const float q[4], const float s[3], float Sigma[3][3])
+{
+    float R[3][3], M[3][3];
+    quat_to_rot(q, R);
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j)
+            M[i][j] = R[i][j] * s[j];
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j)
+            Sigma[i][j] = M[i][0] * M[j][0] + M[i][1] * M[j][1] + M[i][2] * M[j][2];
+}
+
+/* exported for the pins */
+void lmk_ref_covariance3d(const float q[4], const float s[3], float out9[9])
+{
+    float S[3][3];
+    covariance3d(q, s, S);
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j)
+            out9[3 * i + j] = S[i][j];
+}
+
+/* ------------------------------------------------------------------ */
+/* Real spherical harmonics up to degree 3 at unit direction d.
+ * [reading] order and signs: within each degree, m = -l..l, with the sign
+ * (-1)^m of the usual real basis dropped on odd m (the convention in common
+ * use for splat colours).  Constants come from their closed forms. */
+void lmk_ref_sh_basis(const double d[3], double Y[16])
+{
+    const double x = d[0], y = d[1], z = d[2];
+    const double xx = x * x, yy = y * y, zz = z * z;
+    const double k0 = 0.5 * sqrt(1.0 / M_PI);
+    const double k1 = sqrt(3.0 / (4.0 * M_PI));
+    const double k2 = 0.5 * sqrt(15.0 / M_PI);
+    const double k20 = 0.25 * sqrt(5.0 / M_PI);
+    const double k33 = 0.25 * sqrt(35.0 / (2.0 * M_PI));
+    const double k32 = 0.5 * sqrt(105.0 / M_PI);
+    const double k31 = 0.25 * sqrt(21.0 / (2.0 * M_PI));
+    const double k30 = 0.25 * sqrt(7.0 / M_PI);
+    const double k32b = 0.25 * sqrt(105.0 / M_PI);
+    Y[0] = k0;
+    Y[1] = -k1 * y;
+    Y[2] = k1 * z;
+    Y[3] = -k1 * x;
+    Y[4] = k2 * x * y;
+    Y[5] = -k2 * y * z;
+    Y[6] = k20 * (2.0 * zz - xx - yy);
+    Y[7] = -k2 * x * z;
+    Y[8] = 0.5 * k2 * (xx - yy);
+    Y[9] = -k33 * y * (3.0 * xx - yy);
+    Y[10] = k32 * x * y * z;
+    Y[11] = -k31 * y * (4.0 * zz - xx - yy);
+    Y[12] = k30 * z * (2.0 * zz - 3.0 * xx - 3.0 * yy);
+    Y[13] = -k31 * x * (4.0 * zz - xx - yy);
+    Y[14] = k32b * z * (xx - yy);
+    Y[15] = -k33 * x * (xx - 3.0 * yy);
+}
+
+/* ------------------------------------------------------------------ */
+/* Per-primitive projection (Sec. 2.2 text: EWA splatting; Sec. 4.2.1 first stage).
+ *
+ * Inputs are structure-of-arrays, each plane n floats: mean[3], scale[3]
+ * (linear, > 0), rot[4] (w,x,y,z, any norm), opacity in [0,1], sh laid out
+ * [(deg+1)^2][3][n].
+ * Outputs, all length n (planes where several): stage (see enum), depth,
+ * mean2d u/v, cov2d a/b/c (with low-pass), conic A/B/C, rect (x0,y0,x1,y1
+ * interleaved, tile units, half-open), tiles_touched, rgb (3 planes, fp64).
+ * For stage 1..3 only `stage` and tiles_touched (=0) are meaningful.
+ */
+void lmk_ref_preprocess(uint32_t n,
+                        const float *mean, const float *scale, const float *rot,
+                        const float *opacity, const float *sh, uint32_t sh_degree,
+                        const ref_camera *cam,
+                        uint8_t *stage, float *depth, float *mean2d, float *cov2d,
+                        float *conic, uint16_t *rect, uint32_t *tiles_touched, double *rgb)
+{
+    const size_t N = n;
+    const float TS = (float)cam->tile;
+    const uint32_t TX = (cam->width + cam->tile - 1) / cam->tile;
+    const uint32_t TY = (cam->height + cam->tile - 1) / cam->tile;
+    const float lim_x = 1.3f * ((0.5f * (float)cam->width) / cam->fx);
+    const float lim_y = 1.3f * ((0.5f * (float)cam->height) / cam->fy);
+    const float *V = cam->view;
+    const uint32_t ncoef = (sh_degree + 1) * (sh_degree + 1);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t ii = 0; ii < (int64_t)n; ++ii) {
+        const size_t i = (size_t)ii;
+        tiles_touched[i] = 0;
+        depth[i] = 0.0f;
+        mean2d[i] = mean2d[N + i] = 0.0f;
+        cov2d[i] = cov2d[N + i] = cov2d[2 * N + i] = 0.0f;
+        conic[i] = conic[N + i] = conic[2 * N + i] = 0.0f;
+        rect[4 * i] = rect[4 * i + 1] = rect[4 * i + 2] = rect[4 * i + 3] = 0;
+        rgb[i] = rgb[N + i] = rgb[2 * N + i] = 0.0;
+
+        /* 1. camera-space position; cull unless z > near [reading] */
+        const float mx = mean[i], my = mean[N + i], mz = mean[2 * N + i];
+        const float px = V[0] * mx + V[1] * my + V[2] * mz + V[3];
+        const float py = V[4] * mx + V[5] * my + V[6] * mz + V[7];
+        const float pz = V[8] * mx + V[9] * my + V[10] * mz + V[11];
+        if (!(pz > cam->near_z)) { stage[i] = REF_CULL_NEAR; continue; }
+
+        /* 2. Sigma = R S S^T R^T (Eq. 8) */
+        const float q[4] = { rot[i], rot[N + i], rot[2 * N + i], rot[3 * N + i] };
+        const float s[3] = { scale[i], scale[N + i], scale[2 * N + i] };
+        float Sigma[3][3];
+        covariance3d(q, s, Sigma);
+
+        /* 3. EWA: local affine approximation of the perspective map at the
+         * (guard-band clamped) camera-space mean [reading: formula not printed];
+         * Sigma' = (J W) Sigma (J W)^T + h I */
+        const float txz = clampf_lo(px / pz, -lim_x, lim_x) * pz;
+        const float tyz = clampf_lo(py / pz, -lim_y, lim_y) * pz;
+        float J[2][3];
+        J[0][0] = cam->fx / pz; J[0][1] = 0.0f;        J[0][2] = -(cam->fx * txz) / (pz * pz);
+        J[1][0] = 0.0f;        J[1][1] = cam->fy / pz; J[1][2] = -(cam->fy * tyz) / (pz * pz);
+        float Tm[2][3], U[2][3];
+        for (int r = 0; r < 2; ++r)
+            for (int c = 0; c < 3; ++c)
+                Tm[r][c] = J[r][0] * V[c] + J[r][1] * V[4 + c] + J[r][2] * V[8 + c];
+        for (int r = 0; r < 2; ++r)
+            for (int c = 0; c < 3; ++c)
+                U[r][c] = Tm[r][0] * Sigma[0][c] + Tm[r][1] * Sigma[1][c] + Tm[r][2] * Sigma[2][c];
+        const float a = (U[0][0] * Tm[0][0] + U[0][1] * Tm[0][1] + U[0][2] * Tm[0][2]) + cam->lowpass;
+        const float b = U[0][0] * Tm[1][0] + U[0][1] * Tm[1][1] + U[0][2] * Tm[1][2];
+        const float c = (U[1][0] * Tm[1][0] + U[1][1] * Tm[1][1] + U[1][2] * Tm[1][2]) + cam->lowpass;
+
+        /* 4. invert; cull unless det > 0 (also rejects NaN) */
+        const float det = a * c - b * b;
+        if (!(det > 0.0f)) { stage[i] = REF_CULL_DET; continue; }
+        const float cA = c / det, cB = -b / det, cC = a / det;
+
+        /* 5. centre in pixels; pixel (i,j) has centre (i+0.5, j+0.5) [reading] */
+        const float u = (cam->fx * px) / pz + cam->cx;
+        const float v = (cam->fy * py) / pz + cam->cy;
+
+        /* 6. can never reach alpha >= 1/255 [reading] */
+        const float o = opacity[i];
+        if (o < REF_ALPHA_MIN) { stage[i] = REF_CULL_OPACITY; continue; }
+
+        /* 7. axis-aligned bounding box of the ellipse q <= tau [reading] */
+        const float hx = sqrtf(REF_TAU * a);
+        const float hy = sqrtf(REF_TAU * c);
+
+        /* 8. tile rectangle, clamped in float before conversion */
+        const float fTX = (float)TX, fTY = (float)TY;
+        const uint32_t x0 = (uint32_t)clampf_lo(floorf((u - hx) / TS), 0.0f, fTX);
+        const uint32_t x1 = (uint32_t)clampf_lo(floorf((u + hx) / TS) + 1.0f, 0.0f, fTX);
+        const uint32_t y0 = (uint32_t)clampf_lo(floorf((v - hy) / TS), 0.0f, fTY);
+        const uint32_t y1 = (uint32_t)clampf_lo(floorf((v + hy) / TS) + 1.0f, 0.0f, fTY);
+        const uint32_t cnt = (x1 > x0 && y1 > y0) ? (x1 - x0) * (y1 - y0) : 0u;
+
+        depth[i] = pz;
+        mean2d[i] = u; mean2d[N + i] = v;
+        cov2d[i] = a; cov2d[N + i] = b; cov2d[2 * N + i] = c;
+        conic[i] = cA; conic[N + i] = cB; conic[2 * N + i] = cC;
+
+        /* 9. view-dependent colour from SH, fp64:
+         * rgb = max(0, 0.5 + sum_k Y_k(dir) sh_k) [reading: offset and clamp] */
+        double dir[3] = { (double)mx - (double)cam->cam_pos[0],
+                          (double)my - (double)cam->cam_pos[1],
+                          (double)mz - (double)cam->cam_pos[2] };
+        const double len = sqrt(dir[0] * dir[0] + dir[1] * dir[1] + dir[2] * dir[2]);
+        dir[0] /= len; dir[1] /= len; dir[2] /= len;
+        double Y[16];
+        lmk_ref_sh_basis(dir, Y);
+        for (int ch = 0; ch < 3; ++ch) {
+            double acc = 0.5;
+            for (uint32_t k = 0; k < ncoef; ++k)
+                acc += Y[k] * (double)sh[((size_t)k * 3 + ch) * N + i];
+            rgb[ch * N + i] = acc > 0.0 ? acc : 0.0;
+        }
+
+        if (cnt == 0) { stage[i] = REF_CULL_OFFSCREEN; continue; }
+        stage[i] = REF_VISIBLE;
+        rect[4 * i] = (uint16_t)x0; rect[4 * i + 1] = (uint16_t)y0;
+        rect[4 * i + 2] = (uint16_t)x1; rect[4 * i + 3] = (uint16_t)y1;
+        tiles_touched[i] = cnt;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Exclusive prefix sum of tiles_touched; offsets has n+1 entries; returns D. */
+uint64_t lmk_ref_scan(uint32_t n, const uint32_t *tiles_touched, uint64_t *offsets)
+{
+    uint64_t run = 0;
+    for (uint32_t i = 0; i < n; ++i) { offsets[i] = run; run += tiles_touched[i]; }
+    offsets[n] = run;
+    return run;
+}
+
+/* One (key,value) per (primitive, tile of its rectangle), rectangle walked
+ * row-major, primitives in index order.
+ * [reading] key = tile_id << 32 | bits(depth); value = primitive index. */
+void lmk_ref_emit(uint32_t n, const uint32_t *tiles_touched, const uint16_t *rect,
+                  const float *depth, const uint64_t *offsets, uint32_t tiles_x,
+                  uint64_t *keys, uint32_t *vals)
+{
+    for (uint32_t i = 0; i < n; ++i) {
+        if (tiles_touched[i] == 0) continue;
+        uint64_t o = offsets[i];
+        for (uint32_t ty = rect[4 * i + 1]; ty < rect[4 * i + 3]; ++ty)
+            for (uint32_t tx = rect[4 * i]; tx < rect[4 * i + 2]; ++tx) {
+                keys[o] = ((uint64_t)(ty * tiles_x + tx) << 32) | f32_bits(depth[i]);
+                vals[o] = i;
+                ++o;
+            }
+    }
+}
+
+typedef struct { uint64_t key; uint32_t val; } ref_pair;
+
+static int pair_cmp(const void *pa, const void *pb)
+{
+    const ref_pair *a = (const ref_pair *)pa, *b = (const ref_pair *)pb;
+    if (a->key != b->key) return a->key < b->key ? -1 : 1;
+    if (a->val != b->val) return a->val < b->val ? -1 : 1;
+    return 0;
+}
+
+/* Sort ascending by (tile, depth bits, primitive index) [reading: index as the
+ * tie-break, which makes the order unique].  In place. */
+void lmk_ref_sort(uint64_t count, uint64_t *keys, uint32_t *vals)
+{
+    ref_pair *p = (ref_pair *)malloc((size_t)(count ? count : 1) * sizeof(ref_pair));
+    for (uint64_t i = 0; i < count; ++i) { p[i].key = keys[i]; p[i].val = vals[i]; }
+    qsort(p, (size_t)count, sizeof(ref_pair), pair_cmp);
+    for (uint64_t i = 0; i < count; ++i) { keys[i] = p[i].key; vals[i] = p[i].val; }
+    free(p);
+}
+
+/* tile_offsets[t] = number of sorted pairs whose tile id is < t, t = 0..T
+ * [reading: an empty tile has start == end]. */
+void lmk_ref_ranges(uint64_t count, const uint64_t *keys, uint32_t num_tiles, uint64_t *tile_offsets)
+{
+    for (uint32_t t = 0; t <= num_tiles; ++t) tile_offsets[t] = 0;
+    for (uint64_t i = 0; i < count; ++i) {
+        uint64_t t = keys[i] >> 32;
+        if (t + 1 <= num_tiles) tile_offsets[t + 1] += 1;
+    }
+    for (uint32_t t = 0; t < num_tiles; ++t) tile_offsets[t + 1] += tile_offsets[t];
+}
+
+/* ------------------------------------------------------------------ */
+/* Eq. 9-10 for one pixel: walk `count` primitives (indices in list, already in
+ * front-to-back order) and composite.
+ *   q = A dx^2 + 2 B dx dy + C dy^2, dx = u - px, dy = v - py
+ *   alpha = min(0.99, o exp(min(0, -q/2)))            [reading: both clamps]
+ *   skip when alpha < 1/255                            [reading]
+ *   stop, without compositing, when T (1-alpha) < 1e-4 [reading]
+ * Also counts E (entries visited, including the one that stopped the walk) and
+ * C (entries composited), and two ambiguity budgets: how far the pixel could
+ * move if a decision that is within rounding of its threshold went the other
+ * way (see DESIGN: image tolerance rule).
+ */
+typedef struct {
+    double rgb[3]; double T; uint32_t E, C; double beta, beta_T;
+} ref_pixel;
+
+static void composite_pixel(double pxc, double pyc, const uint32_t *list, uint64_t count,
+                            size_t N, const float *mean2d, const float *conic,
+                            const float *opacity, const double *rgb, double cmax,
+                            const float bg[3], ref_pixel *out, double *trace, uint32_t trace_cap)
+{
+    double T = 1.0, acc[3] = { 0.0, 0.0, 0.0 };
+    uint32_t E = 0, C = 0;
+    double beta = 0.0, beta_T = 0.0;
+    for (uint64_t k = 0; k < count; ++k) {
+        const size_t g = list[k];
+        ++E;
+        const double dx = (double)mean2d[g] - pxc;
+        const double dy = (double)mean2d[N + g] - pyc;
+        const double A = conic[g], B = conic[N + g], Cc = conic[2 * N + g];
+        const double q = A * dx * dx + 2.0 * B * dx * dy + Cc * dy * dy;
+        double power = -0.5 * q;
+        if (power > 0.0) power = 0.0;
+        double alpha = (double)opacity[g] * exp(power);
+        if (alpha > (double)REF_ALPHA_MAX) alpha = (double)REF_ALPHA_MAX;
+        if (fabs(255.0 * alpha - 1.0) <= 1e-4) { beta += 2.0 * alpha * T * cmax; beta_T += alpha * T; }
+        if ((float)alpha < REF_ALPHA_MIN) {
+            if (trace && E <= trace_cap) trace[E - 1] = T;
+            continue;
+        }
+        const double Tn = T * (1.0 - alpha);
+        if (fabs(Tn / (double)REF_T_MIN - 1.0) <= 1e-3) { beta += (alpha * T + Tn) * cmax; beta_T += T; }
+        if ((float)Tn < REF_T_MIN) {
+            if (trace && E <= trace_cap) trace[E - 1] = T;
+            break;
+        }
+        const double w = alpha * T;
+        acc[0] += rgb[g] * w;
+        acc[1] += rgb[N + g] * w;
+        acc[2] += rgb[2 * N + g] * w;
+        T = Tn;
+        ++C;
+        if (trace && E <= trace_cap) trace[E - 1] = T;
+    }
+    out->rgb[0] = acc[0] + T * (double)bg[0];
+    out->rgb[1] = acc[1] + T * (double)bg[1];
+    out->rgb[2] = acc[2] + T * (double)bg[2];
+    out->T = T; out->E = E; out->C = C; out->beta = beta; out->beta_T = beta_T;
+}
+
+static double max_rgb(uint32_t n, const uint8_t *stage, const double *rgb)
+{
+    double m = 1.0;
+    for (size_t i = 0; i < (size_t)n; ++i)
+        if (stage[i] == REF_VISIBLE || stage[i] == REF_CULL_OFFSCREEN)
+            for (int ch = 0; ch < 3; ++ch)
+                if (rgb[ch * (size_t)n + i] > m) m = rgb[ch * (size_t)n + i];
+    return m;
+}
+
+/* Tile pipeline render: every pixel walks the sorted slice of its tile.
+ * out_rgb [3][H][W], out_T [H][W], out_E/out_C [H][W], beta/beta_T [H][W]. */
+void lmk_ref_render(uint32_t n, const uint8_t *stage, const float *mean2d, const float *conic,
+                    const float *opacity, const double *rgb,
+                    const uint32_t *sorted_vals, const uint64_t *tile_offsets,
+                    const ref_camera *cam,
+                    double *out_rgb, double *out_T, uint32_t *out_E, uint32_t *out_C,
+                    double *out_beta, double *out_beta_T)
+{
+    const uint32_t W = cam->width, H = cam->height, TS = cam->tile;
+    const uint32_t TX = (W + TS - 1) / TS;
+    const double cmax = max_rgb(n, stage, rgb);
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t jj = 0; jj < (int64_t)H; ++jj) {
+        const uint32_t j = (uint32_t)jj;
+        for (uint32_t i = 0; i < W; ++i) {
+            const uint32_t t = (j / TS) * TX + (i / TS);
+            ref_pixel r;
+            composite_pixel((double)i + 0.5, (double)j + 0.5,
+                            sorted_vals + tile_offsets[t], tile_offsets[t + 1] - tile_offsets[t],
+                            n, mean2d, conic, opacity, rgb, cmax, cam->bg, &r, NULL, 0);
+            const size_t p = (size_t)j * W + i;
+            for (int ch = 0; ch < 3; ++ch) out_rgb[(size_t)ch * H * W + p] = r.rgb[ch];
+            out_T[p] = r.T; out_E[p] = r.E; out_C[p] = r.C;
+            out_beta[p] = r.beta; out_beta_T[p] = r.beta_T;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* The definition the tile pipeline must reach: front-to-back order of ALL
+ * primitives that pass the per-primitive culls 1, 4 and 6 (their rectangle is
+ * ignored, so off-screen ones are included), by (depth bits, index).
+ * Writes the order to `order` (capacity n) and returns its length. */
+typedef struct { uint32_t bits, idx; } ref_di;
+static int di_cmp(const void *pa, const void *pb)
+{
+    const ref_di *a = (const ref_di *)pa, *b = (const ref_di *)pb;
+    if (a->bits != b->bits) return a->bits < b->bits ? -1 : 1;
+    if (a->idx != b->idx) return a->idx < b->idx ? -1 : 1;
+    return 0;
+}
+
+uint32_t lmk_ref_depth_order(uint32_t n, const uint8_t *stage, const float *depth, uint32_t *order)
+{
+    ref_di *p = (ref_di *)malloc(((size_t)n + 1) * sizeof(ref_di));
+    uint32_t m = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        if (stage[i] == REF_VISIBLE || stage[i] == REF_CULL_OFFSCREEN) {
+            p[m].bits = f32_bits(depth[i]); p[m].idx = i; ++m;
+        }
+    qsort(p, m, sizeof(ref_di), di_cmp);
+    for (uint32_t k = 0; k < m; ++k) order[k] = p[k].idx;
+    free(p);
+    return m;
+}
+
+/* Brute force at chosen pixels: each walks the whole depth order.
+ * xs, ys: integer pixel coordinates; outputs are per sample:
+ * out_rgb [npix][3], out_T, out_C, out_beta, out_beta_T [npix]. */
+void lmk_ref_render_pixels_brute(uint32_t n, const uint8_t *stage, const float *mean2d,
+                                 const float *conic, const float *opacity, const double *rgb,
+                                 const uint32_t *order, uint32_t order_len, const ref_camera *cam,
+                                 uint32_t npix, const uint32_t *xs, const uint32_t *ys,
+                                 double *out_rgb, double *out_T, uint32_t *out_C,
+                                 double *out_beta, double *out_beta_T)
+{
+    const double cmax = max_rgb(n, stage, rgb);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t kk = 0; kk < (int64_t)npix; ++kk) {
+        const size_t k = (size_t)kk;
+        ref_pixel r;
+        composite_pixel((double)xs[k] + 0.5, (double)ys[k] + 0.5, order, order_len,
+                        n, mean2d, conic, opacity, rgb, cmax, cam->bg, &r, NULL, 0);
+        for (int ch = 0; ch < 3; ++ch) out_rgb[3 * k + ch] = r.rgb[ch];
+        out_T[k] = r.T; out_C[k] = r.C; out_beta[k] = r.beta; out_beta_T[k] = r.beta_T;
+    }
+}
+
+/* The sorted list of one tile, straight from the definition: every primitive
+ * whose rectangle contains the tile, ordered by (depth bits, index).
+ * out_vals has capacity cap; returns the list length (which may exceed cap,
+ * in which case only cap entries were written). */
+uint64_t lmk_ref_tile_list(uint32_t n, const uint32_t *tiles_touched, const uint16_t *rect,
+                           const float *depth, uint32_t tile_x, uint32_t tile_y,
+                           uint32_t *out_vals, uint64_t cap)
+{
+    uint64_t m = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        if (tiles_touched[i] && rect[4 * i] <= tile_x && tile_x < rect[4 * i + 2] &&
+            rect[4 * i + 1] <= tile_y && tile_y < rect[4 * i + 3])
+            ++m;
+    ref_di *p = (ref_di *)malloc((size_t)(m + 1) * sizeof(ref_di));
+    uint64_t k = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        if (tiles_touched[i] && rect[4 * i] <= tile_x && tile_x < rect[4 * i + 2] &&
+            rect[4 * i + 1] <= tile_y && tile_y < rect[4 * i + 3]) {
+            p[k].bits = f32_bits(depth[i]); p[k].idx = i; ++k;
+        }
+    qsort(p, (size_t)m, sizeof(ref_di), di_cmp);
+    for (uint64_t j = 0; j < m && j < cap; ++j) out_vals[j] = p[j].idx;
+    free(p);
+    return m;
+}
+
+/* Walk an explicit list at chosen pixels (used with lmk_ref_tile_list to check
+ * tiles of a frame too large to bin whole on the host). */
+void lmk_ref_render_pixels_list(uint32_t n, const uint8_t *stage, const float *mean2d,
+                                const float *conic, const float *opacity, const double *rgb,
+                                const uint32_t *list, uint64_t list_len, const ref_camera *cam,
+                                uint32_t npix, const uint32_t *xs, const uint32_t *ys,
+                                double *out_rgb, double *out_T, uint32_t *out_E, uint32_t *out_C,
+                                double *out_beta, double *out_beta_T)
+{
+    const double cmax = max_rgb(n, stage, rgb);
+    for (size_t k = 0; k < (size_t)npix; ++k) {
+        ref_pixel r;
+        composite_pixel((double)xs[k] + 0.5, (double)ys[k] + 0.5, list, list_len,
+                        n, mean2d, conic, opacity, rgb, cmax, cam->bg, &r, NULL, 0);
+        for (int ch = 0; ch < 3; ++ch) out_rgb[3 * k + ch] = r.rgb[ch];
+        out_T[k] = r.T; out_E[k] = r.E; out_C[k] = r.C;
+        out_beta[k] = r.beta; out_beta_T[k] = r.beta_T;
+    }
+}
+
+/* Transmittance after each visited entry of one pixel's walk over `list`
+ * (for the monotonicity pin); returns the number of entries visited. */
+uint32_t lmk_ref_trace_pixel(uint32_t n, const float *mean2d, const float *conic,
+                             const float *opacity, const double *rgb,
+                             const uint32_t *list, uint64_t count,
+                             uint32_t x, uint32_t y, double *trace, uint32_t cap)
+{
+    const float bg[3] = { 0.0f, 0.0f, 0.0f };
+    ref_pixel r;
+    composite_pixel((double)x + 0.5, (double)y + 0.5, list, count, n, mean2d, conic,
+                    opacity, rgb, 1.0, bg, &r, trace, cap);
+    return r.E;
+}

@@ -1,0 +1,523 @@
+"""Pins of the CPU oracle against what the report's equations and plain
+mathematics fix -- never against the oracle itself and never against the GPU.
+
+Sec. 2.2 Eq. 7-8 (primitive, covariance), the EWA projection named in Sec. 2.2,
+Eq. 9-10 (compositing).  The report prints no worked numeric example, so the
+pins are closed forms, library routines, sampling, invariants and brute force.
+"""
+import math
+
+import numpy as np
+import pytest
+from scipy.spatial.transform import Rotation
+from scipy.special import sph_harm_y
+
+from oracle import ref
+from paper_2503_21364_amd import scenes
+
+TAU = np.float32(11.09)
+
+
+def front_camera(width=128, height=96, fov=60.0, dist=4.0, h=0.0, bg=(0, 0, 0), tile=16):
+    eye = (0.0, 0.0, dist)
+    return scenes.make_camera(scenes.look_at(eye, (0, 0, 0), (0, 1, 0)), eye, width, height, fov,
+                              bg=bg, lowpass=h, tile=tile)
+
+
+# --------------------------------------------------------------- Eq. 8
+def test_covariance_isotropic_is_s2_identity():
+    rng = np.random.default_rng(1)
+    for _ in range(20):
+        q = rng.standard_normal(4) * rng.uniform(0.1, 5)     # any norm
+        s = np.full(3, rng.uniform(0.01, 3.0))
+        S = ref.covariance3d(q, s)
+        np.testing.assert_allclose(S, np.eye(3) * s[0] ** 2, rtol=2e-6, atol=1e-6 * s[0] ** 2)
+
+
+def test_covariance_matches_library_rotation_and_eigenvalues():
+    rng = np.random.default_rng(2)
+    for _ in range(50):
+        q = rng.standard_normal(4)
+        s = np.exp(rng.normal(-1, 1, 3))
+        S = ref.covariance3d(q, s).astype(np.float64)
+        # scipy wants (x, y, z, w); the oracle's reading is (w, x, y, z)
+        R = Rotation.from_quat([q[1], q[2], q[3], q[0]]).as_matrix()
+        expect = R @ np.diag(s ** 2) @ R.T
+        np.testing.assert_allclose(S, expect, rtol=0, atol=5e-6 * (s ** 2).max())
+        assert np.allclose(S, S.T)
+        np.testing.assert_allclose(np.sort(np.linalg.eigvalsh(S)), np.sort(s ** 2),
+                                   rtol=0, atol=5e-6 * (s ** 2).max())
+
+
+def test_axis_rotation_sense():
+    # 90 degrees about +z maps the x axis onto the y axis: a primitive long in x
+    # becomes long in y.
+    q = [math.cos(math.pi / 4), 0, 0, math.sin(math.pi / 4)]
+    S = ref.covariance3d(q, [2.0, 1.0, 0.5])
+    np.testing.assert_allclose(np.diag(S), [1.0, 4.0, 0.25], atol=1e-5)
+
+
+# --------------------------------------------------------------- EWA projection
+@pytest.mark.parametrize("h", [0.0, 0.3])
+def test_isotropic_on_axis_footprint(h):
+    d, s = 4.0, 0.05
+    cam = front_camera(h=h, dist=d)
+    sc = scenes.hand_placed_scene([(0, 0, 0)], [(s, s, s)], rot=(0.3, -0.5, 0.7, 0.2))
+    pre = ref.preprocess(sc, cam)
+    sig2 = (float(cam["fx"]) * s / d) ** 2
+    assert pre.stage[0] == ref.VISIBLE
+    np.testing.assert_allclose(pre.cov2d[:, 0], [sig2 + h, 0.0, sig2 + h], rtol=1e-5, atol=1e-5)
+    np.testing.assert_allclose(pre.mean2d[:, 0], [cam["cx"], cam["cy"]], atol=1e-4)
+    np.testing.assert_allclose(pre.depth[0], d, rtol=1e-6)
+    np.testing.assert_allclose(pre.conic[:, 0], [1 / (sig2 + h), 0, 1 / (sig2 + h)], rtol=1e-5, atol=1e-6)
+
+
+def test_projection_matches_sampled_pinhole_covariance():
+    """Project samples of a small anisotropic 3D Gaussian through the exact pinhole
+    map: their 2D covariance must approach Sigma' (the affine approximation is the
+    first-order term), and their mean must approach (u, v)."""
+    rng = np.random.default_rng(3)
+    eye = (3.0, -2.0, 5.0)
+    view = scenes.look_at(eye, (0.2, 0.1, -0.3), (0, 1, 0))
+    cam = scenes.make_camera(view, eye, 640, 480, 55.0, lowpass=0.0)
+    mean = np.array([0.9, 0.6, -0.4])
+    q = np.array([0.8, 0.1, -0.5, 0.3])
+    s = np.array([0.004, 0.012, 0.002])
+    sc = scenes.hand_placed_scene([mean], [s], rot=q)
+    pre = ref.preprocess(sc, cam)
+    R = Rotation.from_quat([q[1], q[2], q[3], q[0]]).as_matrix()
+    pts = mean + (rng.standard_normal((400_000, 3)) * s) @ R.T
+    V = view
+    pc = pts @ V[:, :3].T + V[:, 3]
+    uv = np.stack([float(cam["fx"]) * pc[:, 0] / pc[:, 2] + float(cam["cx"]),
+                   float(cam["fy"]) * pc[:, 1] / pc[:, 2] + float(cam["cy"])], axis=1)
+    emp = np.cov(uv.T)
+    a, b, c = pre.cov2d[:, 0].astype(np.float64)
+    np.testing.assert_allclose([a, b, c], [emp[0, 0], emp[0, 1], emp[1, 1]], rtol=0.02,
+                               atol=0.01 * max(emp[0, 0], emp[1, 1]))
+    np.testing.assert_allclose(pre.mean2d[:, 0], uv.mean(axis=0), atol=0.02)
+    # conic is the inverse of Sigma'
+    M = np.array([[a, b], [b, c]])
+    Ci = np.array([[pre.conic[0, 0], pre.conic[1, 0]], [pre.conic[1, 0], pre.conic[2, 0]]], dtype=np.float64)
+    np.testing.assert_allclose(Ci @ M, np.eye(2), atol=1e-4)
+
+
+def test_jacobian_is_derivative_of_pinhole_map():
+    """Sigma' for an off-axis primitive equals Jn Sigma_cam Jn^T with Jn the
+    numerically differentiated pinhole projection."""
+    eye = (0.0, 0.0, 6.0)
+    view = scenes.look_at(eye, (0, 0, 0), (0, 1, 0))
+    cam = scenes.make_camera(view, eye, 800, 600, 60.0, lowpass=0.0)
+    mean = np.array([1.3, -0.8, 0.5])
+    q = np.array([0.9, 0.2, 0.3, -0.1]); s = np.array([0.05, 0.02, 0.08])
+    pre = ref.preprocess(scenes.hand_placed_scene([mean], [s], rot=q), cam)
+    R = Rotation.from_quat([q[1], q[2], q[3], q[0]]).as_matrix()
+    Sig_cam = view[:, :3] @ (R @ np.diag(s ** 2) @ R.T) @ view[:, :3].T
+    p0 = view[:, :3] @ mean + view[:, 3]
+    fx, fy = float(cam["fx"]), float(cam["fy"])
+    proj = lambda p: np.array([fx * p[0] / p[2], fy * p[1] / p[2]])
+    Jn = np.zeros((2, 3))
+    for k in range(3):
+        e = np.zeros(3); e[k] = 1e-6
+        Jn[:, k] = (proj(p0 + e) - proj(p0 - e)) / 2e-6
+    exp = Jn @ Sig_cam @ Jn.T
+    np.testing.assert_allclose(pre.cov2d[:, 0], [exp[0, 0], exp[0, 1], exp[1, 1]], rtol=2e-4)
+
+
+def test_guard_band_clamps_the_jacobian_far_off_axis():
+    # beyond 1.3x the half-frustum the affine map is taken at the clamped ray
+    eye = (0.0, 0.0, 5.0)
+    view = scenes.look_at(eye, (0, 0, 0), (0, 1, 0))
+    cam = scenes.make_camera(view, eye, 200, 200, 60.0, lowpass=0.0)
+    s = 0.05
+    lim = 1.3 * (0.5 * 200 / float(cam["fx"]))
+    z = 5.0
+    x_far = 3.0 * lim * z
+    pre = ref.preprocess(scenes.hand_placed_scene([(x_far, 0, 0)], [(s, s, s)]), cam)
+    fx = float(cam["fx"])
+    # isotropic Sigma: a = s^2 (fx/z)^2 (1 + xt^2), xt clamped to lim
+    a_expect = s * s * (fx / z) ** 2 * (1 + lim ** 2)
+    np.testing.assert_allclose(pre.cov2d[0, 0], a_expect, rtol=1e-4)
+    assert pre.stage[0] == ref.CULL_OFFSCREEN
+
+
+# --------------------------------------------------------------- extent / rectangle
+def test_extent_and_rect_closed_form_and_tile_shift():
+    d, s = 4.0, 0.03
+    cam = front_camera(width=256, height=256, dist=d, h=0.0)
+    fx = float(cam["fx"])
+    sig = fx * s / d
+    half = math.sqrt(11.09) * sig
+    for k in (0, 1, 3, -2):
+        # move the primitive so its centre shifts by k tiles (16 px) in x and y
+        x = 16 * k * d / fx
+        pre = ref.preprocess(scenes.hand_placed_scene([(x, -x, 0)], [(s, s, s)]), cam)
+        u, v = pre.mean2d[:, 0]
+        np.testing.assert_allclose([u, v], [128 + 16 * k, 128 + 16 * k], atol=1e-3)
+        x0, x1 = math.floor((u - half) / 16), math.floor((u + half) / 16) + 1
+        y0, y1 = math.floor((v - half) / 16), math.floor((v + half) / 16) + 1
+        assert list(pre.rect[0]) == [x0, y0, x1, y1]
+        assert pre.tiles_touched[0] == (x1 - x0) * (y1 - y0)
+    # rect is clamped to the grid and culled when fully outside
+    pre = ref.preprocess(scenes.hand_placed_scene([(-2.25, 0, 0), (-30.0, 0, 0)], [(s, s, s)]), cam)
+    assert pre.rect[0][0] == 0 and pre.tiles_touched[0] > 0
+    assert pre.tiles_touched[1] == 0 and pre.stage[1] == ref.CULL_OFFSCREEN
+
+
+def test_support_radius_covers_every_contributing_pixel():
+    # q <= 2 ln 255 < tau: alpha >= 1/255 is impossible outside the rectangle
+    assert 2 * math.log(255.0) < 11.09
+    sc = scenes.make_scene(0, n=300, seed=5)
+    cam = scenes.make_cameras(0, 64, 64)[0]
+    pre = ref.preprocess(sc, cam)
+    ys, xs = np.mgrid[0:64, 0:64]
+    for g in np.nonzero(pre.stage == ref.VISIBLE)[0][:100]:
+        dx = pre.mean2d[0, g].astype(np.float64) - (xs + 0.5)
+        dy = pre.mean2d[1, g].astype(np.float64) - (ys + 0.5)
+        A, B, Cc = pre.conic[:, g].astype(np.float64)
+        alpha = pre.opacity[g] * np.exp(-0.5 * (A * dx * dx + 2 * B * dx * dy + Cc * dy * dy))
+        x0, y0, x1, y1 = pre.rect[g].astype(int) * 16
+        inside = (xs >= x0) & (xs < x1) & (ys >= y0) & (ys < y1)
+        assert not np.any((alpha >= 1 / 255) & ~inside)
+
+
+# --------------------------------------------------------------- culls
+def test_culls():
+    cam = front_camera()
+    sc = scenes.hand_placed_scene([(0, 0, 0), (0, 0, 3.9), (0, 0, 5.0), (0, 0, 0)],
+                                  [(0.05,) * 3], opacity=[0.5, 0.5, 0.5, 0.003])
+    pre = ref.preprocess(sc, cam)
+    # 0 visible; 1 at z=0.1 < near; 2 behind the camera; 3 opacity below 1/255
+    assert list(pre.stage) == [ref.VISIBLE, ref.CULL_NEAR, ref.CULL_NEAR, ref.CULL_OPACITY]
+    assert list(pre.tiles_touched[1:]) == [0, 0, 0]
+    b = ref.bin_sort(pre, cam)
+    assert b.D == pre.tiles_touched[0]
+
+
+def test_everything_behind_camera_gives_background():
+    sc = scenes.make_scene(0, n=500, seed=9)
+    eye = (0.0, 0.0, 4.0)
+    cam = scenes.make_camera(scenes.look_at(eye, (0, 0, 8.0), (0, 1, 0)), eye, 64, 48, 60.0, bg=(0.2, 0.4, 0.6))
+    fr = ref.render_frame(sc, cam)
+    assert fr.binned.D == 0 and np.all(fr.binned.tile_offsets == 0)
+    assert np.all(fr.img.T == 1.0)
+    for ch, v in enumerate((0.2, 0.4, 0.6)):
+        np.testing.assert_allclose(fr.img.rgb[ch], np.float32(v), rtol=0, atol=0)
+
+
+def test_removing_culled_primitives_leaves_the_image_unchanged():
+    sc = scenes.make_scene(0, n=3000, seed=11)
+    cam = scenes.make_cameras(0, 96, 80)[0]
+    cam["view"] = scenes.look_at((0.5, 0.2, 1.5), (0.0, 0.0, 0.0), (0, 1, 0)).astype(np.float32).reshape(12)
+    cam["cam_pos"] = np.array([0.5, 0.2, 1.5], np.float32)
+    fr = ref.render_frame(sc, cam)
+    keep = fr.pre.tiles_touched > 0
+    assert 0 < keep.sum() < sc["n"]
+    sub = dict(mean=sc["mean"][:, keep], scale=sc["scale"][:, keep], rot=sc["rot"][:, keep],
+               opacity=sc["opacity"][keep], sh=sc["sh"][:, :, keep], sh_degree=3, n=int(keep.sum()))
+    sub = {k: (np.ascontiguousarray(v) if isinstance(v, np.ndarray) else v) for k, v in sub.items()}
+    fr2 = ref.render_frame(sub, cam)
+    assert np.array_equal(fr.img.rgb, fr2.img.rgb) and np.array_equal(fr.img.T, fr2.img.T)
+
+
+# --------------------------------------------------------------- SH colour
+def _quadrature(nt=40, nphi=80):
+    x, w = np.polynomial.legendre.leggauss(nt)
+    phi = (np.arange(nphi) + 0.5) * 2 * np.pi / nphi
+    ct, ph = np.meshgrid(x, phi, indexing="ij")
+    st = np.sqrt(1 - ct ** 2)
+    dirs = np.stack([st * np.cos(ph), st * np.sin(ph), ct], axis=-1).reshape(-1, 3)
+    wts = (w[:, None] * np.full(nphi, 2 * np.pi / nphi)[None, :]).reshape(-1)
+    return dirs, wts
+
+
+def test_sh_orthonormal_and_addition_theorem():
+    dirs, wts = _quadrature()
+    Y = np.stack([ref.sh_basis(d) for d in dirs])
+    G = (Y * wts[:, None]).T @ Y
+    np.testing.assert_allclose(G, np.eye(16), atol=1e-12)
+    for l in range(4):
+        band = Y[:, l * l:(l + 1) * (l + 1)]
+        np.testing.assert_allclose((band ** 2).sum(axis=1), (2 * l + 1) / (4 * np.pi), rtol=1e-12)
+
+
+def test_sh_matches_library_harmonics_up_to_the_stated_signs():
+    """Real harmonics built from scipy's complex ones.  The reading's basis is the
+    standard real basis (with Condon-Shortley phase) times (-1)^m, i.e. with the
+    phase removed: odd m flips sign."""
+    rng = np.random.default_rng(4)
+    for _ in range(25):
+        d = rng.standard_normal(3); d /= np.linalg.norm(d)
+        theta, phi = math.acos(d[2]), math.atan2(d[1], d[0])
+        Y = ref.sh_basis(d)
+        k = 0
+        for l in range(4):
+            for m in range(-l, l + 1):
+                c = sph_harm_y(l, abs(m), theta, phi)
+                if m == 0:
+                    std = c.real
+                elif m > 0:
+                    std = math.sqrt(2) * (-1) ** m * c.real
+                else:
+                    std = math.sqrt(2) * (-1) ** m * c.imag
+                # std: real SH without Condon-Shortley phase; reading adds (-1)^m
+                np.testing.assert_allclose(Y[k], (-1) ** m * std, atol=1e-12)
+                k += 1
+
+
+def test_dc_only_colour_and_clamp():
+    cam = front_camera()
+    y00 = 0.5 * math.sqrt(1 / math.pi)
+    sc = scenes.hand_placed_scene([(0.3, -0.2, 0.1)] * 2, [(0.05,) * 3],
+                                  sh_dc=[(1.0, -0.5, 0.25), (-3.0, 0.0, 4.0)])
+    pre = ref.preprocess(sc, cam)
+    np.testing.assert_allclose(pre.rgb[:, 0], 0.5 + y00 * np.array([1.0, -0.5, 0.25]), rtol=1e-12)
+    np.testing.assert_allclose(pre.rgb[:, 1], [0.0, 0.5, 0.5 + 4 * y00], rtol=1e-12)
+
+
+def test_colour_uses_direction_from_camera_to_primitive():
+    # a pure degree-1 coefficient on the 'z' slot gives 0.5 + k1 * dir_z
+    eye = np.array([1.0, 2.0, 3.0])
+    mean = np.array([0.5, -1.0, 0.2])
+    cam = scenes.make_camera(scenes.look_at(eye, mean, (0, 1, 0)), eye, 64, 64, 60.0)
+    sc = scenes.hand_placed_scene([mean], [(0.05,) * 3])
+    sc["sh"][2, :, 0] = [1.0, 0.5, -0.25]
+    sc["sh"][3, 0, 0] = 0.7      # 'x' slot, red only
+    pre = ref.preprocess(sc, cam)
+    d = (mean - eye) / np.linalg.norm(mean - eye)
+    k1 = math.sqrt(3 / (4 * math.pi))
+    np.testing.assert_allclose(pre.rgb[:, 0],
+                               [0.5 + k1 * d[2] * 1.0 - k1 * d[0] * 0.7, 0.5 + k1 * d[2] * 0.5,
+                                max(0.0, 0.5 - k1 * d[2] * 0.25)], rtol=1e-6)
+
+
+# --------------------------------------------------------------- Eq. 9-10
+def test_single_splat_alpha_closed_form():
+    d, s, o = 4.0, 0.06, 0.8
+    cam = front_camera(width=96, height=64, dist=d, h=0.0)
+    y00 = 0.5 * math.sqrt(1 / math.pi)
+    col = np.array([0.9, 0.3, 0.6])
+    sc = scenes.hand_placed_scene([(0.1, -0.05, 0)], [(s,) * 3], opacity=o, sh_dc=(col - 0.5) / y00)
+    fr = ref.render_frame(sc, cam)
+    fx = float(cam["fx"])
+    # isotropic Sigma = s^2 I gives Sigma' = s^2 J J^T; off axis J J^T is not quite a
+    # multiple of I: with tx = x/z, ty = y/z it is (fx/z)^2 [[1+tx^2, tx ty],[tx ty, 1+ty^2]]
+    tx, ty = 0.1 / d, 0.05 / d                         # +y is down: world -0.05 -> below centre
+    Sp = (fx * s / d) ** 2 * np.array([[1 + tx * tx, tx * ty], [tx * ty, 1 + ty * ty]])
+    Ci = np.linalg.inv(Sp)
+    u, v = 48 + fx * tx, 32 + fx * ty
+    ys, xs = np.mgrid[0:64, 0:96]
+    dx, dy = u - (xs + 0.5), v - (ys + 0.5)
+    qf = Ci[0, 0] * dx * dx + 2 * Ci[0, 1] * dx * dy + Ci[1, 1] * dy * dy
+    alpha = np.minimum(0.99, o * np.exp(-0.5 * qf))
+    alpha[alpha < 1 / 255] = 0.0
+    near_thr = np.abs(255 * o * np.exp(-0.5 * qf) - 1) < 1e-3
+    ok = ~near_thr
+    for ch in range(3):
+        np.testing.assert_allclose(fr.img.rgb[ch][ok], (col[ch] * alpha)[ok], atol=3e-5)
+    np.testing.assert_allclose(fr.img.T[ok], (1 - alpha)[ok], atol=3e-5)
+    assert fr.img.C.max() == 1 and (fr.img.C[ok] == (alpha[ok] > 0)).all()
+
+
+def test_alpha_is_capped_at_099_and_uses_the_opacity():
+    cam = front_camera(width=32, height=32, dist=4.0, h=0.0)
+    sc = scenes.hand_placed_scene([(0, 0, 0)], [(5.0,) * 3], opacity=1.0)
+    fr = ref.render_frame(sc, cam)
+    np.testing.assert_allclose(fr.img.T[16, 16], 1 - np.float64(np.float32(0.99)), rtol=1e-6)
+    sc = scenes.hand_placed_scene([(0, 0, 0)], [(5.0,) * 3], opacity=0.25)
+    fr = ref.render_frame(sc, cam)
+    sig2 = (float(cam["fx"]) * 5.0 / 4.0) ** 2
+    np.testing.assert_allclose(fr.img.T[16, 16], 1 - 0.25 * math.exp(-0.25 / sig2), rtol=1e-6)
+
+
+def test_two_splats_order_and_formula():
+    d = 4.0
+    cam = front_camera(width=64, height=64, dist=d, h=0.0, bg=(0.1, 0.2, 0.3))
+    y00 = 0.5 * math.sqrt(1 / math.pi)
+    c1, c2 = np.array([1.0, 0.2, 0.1]), np.array([0.1, 0.3, 0.9])
+    o1, o2, s1, s2 = 0.6, 0.7, 0.2, 0.3
+    fx = float(cam["fx"])
+
+    def expect(zf, zb, cf, cb, of, ob, sf, sb):
+        # on-axis isotropic: alpha at the image centre pixel (offset 0.5 px)
+        r2 = 0.5
+        af = of * math.exp(-0.5 * r2 / (fx * sf / (d - zf)) ** 2)
+        ab = ob * math.exp(-0.5 * r2 / (fx * sb / (d - zb)) ** 2)
+        T = (1 - af) * (1 - ab)
+        return cf * af + cb * ab * (1 - af) + T * np.array([0.1, 0.2, 0.3]), T
+
+    # primitive 1 nearer the camera (world z larger since the camera sits at +z)
+    sc = scenes.hand_placed_scene([(0, 0, 0.5), (0, 0, -0.5)], [(s1,) * 3, (s2,) * 3],
+                                  opacity=[o1, o2], sh_dc=[(c1 - 0.5) / y00, (c2 - 0.5) / y00])
+    fr = ref.render_frame(sc, cam)
+    e, T = expect(0.5, -0.5, c1, c2, o1, o2, s1, s2)
+    np.testing.assert_allclose(fr.img.rgb[:, 32, 32], e, atol=2e-6)
+    np.testing.assert_allclose(fr.img.T[32, 32], T, atol=2e-6)
+    # swap depths: roles swap
+    sc = scenes.hand_placed_scene([(0, 0, -0.5), (0, 0, 0.5)], [(s1,) * 3, (s2,) * 3],
+                                  opacity=[o1, o2], sh_dc=[(c1 - 0.5) / y00, (c2 - 0.5) / y00])
+    fr = ref.render_frame(sc, cam)
+    e, T = expect(0.5, -0.5, c2, c1, o2, o1, s2, s1)
+    np.testing.assert_allclose(fr.img.rgb[:, 32, 32], e, atol=2e-6)
+
+
+def test_equal_depth_ties_break_by_index():
+    cam = front_camera(width=32, height=32, dist=4.0, h=0.0)
+    y00 = 0.5 * math.sqrt(1 / math.pi)
+    cols = [np.array([1.0, 0.0, 0.0]), np.array([0.0, 1.0, 0.0])]
+    sc = scenes.hand_placed_scene([(0, 0, 0), (0, 0, 0)], [(0.3,) * 3], opacity=[0.5, 0.5],
+                                  sh_dc=[(c - 0.5) / y00 for c in cols])
+    fr = ref.render_frame(sc, cam)
+    a = 0.5 * math.exp(-0.5 * 0.5 / (float(cam["fx"]) * 0.3 / 4.0) ** 2)
+    np.testing.assert_allclose(fr.img.rgb[:, 16, 16], [a, a * (1 - a), 0.0], atol=2e-6)
+
+
+def test_stop_rule_leaves_T_at_or_above_1e_4_and_skips_the_stopping_entry():
+    cam = front_camera(width=32, height=32, dist=10.0, h=0.0)
+    n = 6
+    zs = np.linspace(2.0, -2.0, n)           # front to back
+    sc = scenes.hand_placed_scene([(0, 0, z) for z in zs], [(2.0,) * 3], opacity=0.9)
+    fr = ref.render_frame(sc, cam)
+    # alpha ~ 0.9 each: T = 0.1^k; 0.1^4 = 1e-4 rounds to just at/above the bound in
+    # exact arithmetic but alpha is a hair under 0.9 off-centre, so 4 composite, the
+    # 5th would give ~1e-5 < 1e-4 and stops the walk without being composited.
+    assert fr.img.C[16, 16] == 4 and fr.img.E[16, 16] == 5
+    assert 1e-4 <= fr.img.T[16, 16] < 2e-4
+
+
+# --------------------------------------------------------------- scan / sort / ranges
+def test_scan_emit_sort_ranges_against_library_routines():
+    sc = scenes.make_scene(0, n=4000, seed=21)
+    cam = scenes.make_cameras(0, 200, 120)[0]       # ragged: 13 x 8 tiles, partial last ones
+    pre = ref.preprocess(sc, cam)
+    b = ref.bin_sort(pre, cam, keep_unsorted=True)
+    tt = pre.tiles_touched.astype(np.uint64)
+    assert b.D == int(tt.sum())
+    np.testing.assert_array_equal(b.offsets, np.concatenate([[0], np.cumsum(tt)]).astype(np.uint64))
+    # emission: primitive i owns [offsets[i], offsets[i+1]) with its rectangle row-major
+    TX = b.tiles_x
+    for i in np.nonzero(pre.tiles_touched)[0][:200]:
+        x0, y0, x1, y1 = pre.rect[i].astype(int)
+        tiles = [ty * TX + tx for ty in range(y0, y1) for tx in range(x0, x1)]
+        sl = slice(int(b.offsets[i]), int(b.offsets[i + 1]))
+        assert list(b.keys_unsorted[sl] >> np.uint64(32)) == tiles
+        assert np.all((b.keys_unsorted[sl] & np.uint64(0xFFFFFFFF)) == pre.depth[i:i + 1].view(np.uint32)[0])
+        assert np.all(b.vals_unsorted[sl] == i)
+    # sorted = stable sort by key of the index-ordered emission
+    perm = np.argsort(b.keys_unsorted, kind="stable")
+    np.testing.assert_array_equal(b.keys, b.keys_unsorted[perm])
+    np.testing.assert_array_equal(b.vals, b.vals_unsorted[perm])
+    # ties exist only where depth bits are equal and are then index-ordered
+    same = b.keys[1:] == b.keys[:-1]
+    assert np.all(b.vals[1:][same] > b.vals[:-1][same])
+    # CSR ranges
+    T = b.tiles_x * b.tiles_y
+    tiles_sorted = (b.keys >> np.uint64(32)).astype(np.int64)
+    np.testing.assert_array_equal(b.tile_offsets, np.searchsorted(tiles_sorted, np.arange(T + 1), side="left"))
+    assert b.tile_offsets[T] == b.D
+    # a tile's slice equals the list built from the definition
+    for (tx, ty) in [(0, 0), (6, 4), (12, 7), (3, 2)]:
+        t = ty * TX + tx
+        sl = b.vals[int(b.tile_offsets[t]):int(b.tile_offsets[t + 1])]
+        np.testing.assert_array_equal(sl, ref.tile_list(pre, tx, ty))
+
+
+def test_depth_bits_order_equals_numeric_order():
+    z = np.array([0.2000001, 0.25, 1.0, 1.0000001, 77.0, 1e6], dtype=np.float32)
+    assert np.all(np.diff(z.view(np.uint32).astype(np.int64)) > 0)
+
+
+# --------------------------------------------------------------- image = definition
+@pytest.mark.parametrize("seed,n,w,h", [(31, 1500, 64, 48), (32, 2000, 50, 37)])
+def test_tile_pipeline_equals_brute_force_over_all_primitives(seed, n, w, h):
+    sc = scenes.make_scene(0, n=n, seed=seed)
+    sc["scale"] *= np.float32(2.0)            # fatter splats: more overlap per pixel
+    cam = scenes.make_cameras(0, w, h)[0]
+    cam["bg"] = np.array([0.3, 0.1, 0.2], np.float32)
+    fr = ref.render_frame(sc, cam)
+    ys, xs = np.mgrid[0:h, 0:w]
+    br = ref.render_pixels_brute(fr.pre, cam, xs.ravel(), ys.ravel())
+    assert np.array_equal(br.rgb.T.reshape(3, h, w), fr.img.rgb)
+    assert np.array_equal(br.T.reshape(h, w), fr.img.T)
+    assert np.array_equal(br.C.reshape(h, w), fr.img.C)
+    assert fr.img.C.max() > 10
+
+
+def test_brute_force_matches_numpy_definition_of_eq_9_10():
+    """Independent numpy evaluation of Eq. 9-10 with the reading's three rules on a
+    handful of pixels, from the oracle's per-primitive outputs."""
+    sc = scenes.make_scene(0, n=800, seed=41)
+    sc["scale"] *= np.float32(3.0)
+    cam = scenes.make_cameras(0, 40, 40)[0]
+    fr = ref.render_frame(sc, cam)
+    pre = fr.pre
+    idx = np.nonzero((pre.stage == ref.VISIBLE) | (pre.stage == ref.CULL_OFFSCREEN))[0]
+    order = idx[np.lexsort((idx, pre.depth[idx].view(np.uint32)))]
+    for (x, y) in [(20, 20), (3, 35), (39, 0), (11, 27)]:
+        T, col = 1.0, np.zeros(3)
+        for g in order:
+            dx = float(pre.mean2d[0, g]) - (x + 0.5); dy = float(pre.mean2d[1, g]) - (y + 0.5)
+            A, B, Cc = (float(t) for t in pre.conic[:, g])
+            q = A * dx * dx + 2 * B * dx * dy + Cc * dy * dy
+            alpha = min(float(np.float32(0.99)), float(pre.opacity[g]) * math.exp(min(0.0, -0.5 * q)))
+            if np.float32(alpha) < np.float32(1.0) / np.float32(255.0):
+                continue
+            if np.float32(T * (1 - alpha)) < np.float32(1e-4):
+                break
+            col += pre.rgb[:, g] * alpha * T
+            T *= (1 - alpha)
+        np.testing.assert_allclose(fr.img.rgb[:, y, x], col, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(fr.img.T[y, x], T, rtol=1e-12)
+
+
+def test_image_independent_of_tile_size():
+    sc = scenes.make_scene(0, n=2500, seed=51)
+    sc["scale"] *= np.float32(1.5)
+    ref_img = None
+    for ts in (8, 16, 32, 64):
+        cam = scenes.make_cameras(0, 120, 72)[0]
+        cam["tile"] = ts
+        fr = ref.render_frame(sc, cam)
+        if ref_img is None:
+            ref_img = fr.img
+        else:
+            assert np.array_equal(fr.img.rgb, ref_img.rgb)
+            assert np.array_equal(fr.img.T, ref_img.T)
+            assert np.array_equal(fr.img.C, ref_img.C)
+
+
+def test_transmittance_invariants():
+    sc = scenes.make_scene(0, n=3000, seed=61)
+    sc["scale"] *= np.float32(2.5)
+    cam = scenes.make_cameras(0, 64, 64)[0]
+    fr = ref.render_frame(sc, cam)
+    img, b = fr.img, fr.binned
+    assert img.T.min() >= 1e-4 * (1 - 1e-6) and img.T.max() <= 1.0
+    assert np.array_equal(img.T == 1.0, img.C == 0)
+    assert np.all(img.C <= img.E)
+    assert (img.T < 1e-3).any(), "scene should saturate some pixels"
+    for (x, y) in [(32, 32), (5, 60), (50, 10)]:
+        t = (y // 16) * b.tiles_x + x // 16
+        lst = b.vals[int(b.tile_offsets[t]):int(b.tile_offsets[t + 1])]
+        tr = ref.trace_pixel(fr.pre, lst, x, y)
+        assert len(tr) == img.E[y, x]
+        assert np.all(np.diff(np.concatenate([[1.0], tr])) <= 0)
+        assert tr[-1] == img.T[y, x] if len(tr) else img.T[y, x] == 1.0
+
+
+def test_partial_tiles_and_non_multiple_image_sizes():
+    sc = scenes.make_scene(0, n=1000, seed=71)
+    cam = scenes.make_cameras(0, 37, 23)[0]
+    fr = ref.render_frame(sc, cam)
+    assert fr.binned.tiles_x == 3 and fr.binned.tiles_y == 2
+    assert fr.img.rgb.shape == (3, 23, 37)
+    ys, xs = np.mgrid[0:23, 0:37]
+    br = ref.render_pixels_brute(fr.pre, cam, xs.ravel(), ys.ravel())
+    assert np.array_equal(br.rgb.T.reshape(3, 23, 37), fr.img.rgb)
+
+
+def test_empty_scene():
+    sc = scenes.make_scene(0, n=0, seed=1)
+    cam = scenes.make_cameras(0, 32, 32)[0]
+    fr = ref.render_frame(sc, cam)
+    assert fr.binned.D == 0 and np.all(fr.img.T == 1.0) and np.all(fr.img.rgb == 0.0)
