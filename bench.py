@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the splatting forward path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 2] [--no-cpu-baseline]
+
+A step is one frame: lmk_gs_preprocess + lmk_gs_bin_sort + lmk_gs_render for one
+viewpoint, all enqueued on one stream with no host synchronisation; steps cycle
+through the configuration's seeded viewpoints.  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line (metric = frames/s) that also
+carries Gaussian-pixel blends/s, per-stage times, the roofline of the dominant
+kernel and of the HBM-bound stages, and the CPU oracle timed on the same
+workload as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+FP32_PEAK_TFLOPS = 157.3     # 256 CU x 128 lanes x 2 flop x 2.4 GHz (vector FP32, packed-FMA rate)
+
+
+def algorithmic_bytes(n, n_near, n_bin, D, tiles, passes):
+    """HBM bytes the method itself must move in preprocess + bin_sort (per frame).
+
+    preprocess: mean 12 B + tiles_touched 4 B for every primitive; scale, rotation,
+    opacity 32 B for those past the near plane; SH 192 B + outputs 64 B (depth 4,
+    rect 8, feature record 48, reread count 4) for binned ones.
+    scan: block sums only (negligible).  emit: 16 B per binned primitive + 12 B per pair.
+    sort: per pass, histogram read 8 B + scatter read 12 B + write 12 B per pair.
+    ranges: 8 B per pair + 8 B per tile.
+    """
+    b_pre = 16 * n + 32 * n_near + 256 * n_bin
+    b_emit = 4 * n + 16 * n_bin + 12 * D
+    b_sort = D * 32 * passes
+    b_ranges = 8 * D + 8 * (tiles + 1)
+    return dict(preprocess=b_pre, emit=b_emit, sort=b_sort, ranges=b_ranges,
+                total=b_pre + b_emit + b_sort + b_ranges)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=160)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--cfg", type=int, default=2, help="configuration 0-4 (2 is the headline: 3M Gaussians, 1080p)")
+    ap.add_argument("--n", type=int, default=None, help="override the primitive count (reported in config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (no blends/s either)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2503_21364_amd import binding as B
+    from paper_2503_21364_amd import scenes
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()   # fails loudly if the HIP library is not built
+    spec = scenes.CONFIGS[args.cfg]
+    n = spec["n"] if args.n is None else args.n
+    W, H = spec["width"], spec["height"]
+    scene = scenes.make_scene(args.cfg, n=n)
+    cams = scenes.make_cameras(args.cfg)
+    ccams = [B.make_camera(c) for c in cams]
+    dev = B.Scene(scene)
+    tiles = ((W + 15) // 16) * ((H + 15) // 16)
+    passes = (32 + max(1, (tiles - 1).bit_length()) + 7) // 8
+
+    # size the pair buffers from a dry run of every viewpoint (not timed)
+    probe_cap = 64_000_000 if args.cfg != 4 else 7_000_000_000
+    fr = B.Frame(n, W, H, probe_cap)
+    Ds, stats = [], []
+    for cc in ccams:
+        B.preprocess(dev, cc, fr)
+        D, status = B.read_status(fr)
+        tt = fr.tiles_touched[:n]
+        n_bin = int((tt > 0).sum().item())
+        Ds.append(D)
+        stats.append(dict(D=D, n_bin=n_bin))
+    del fr
+    torch.cuda.empty_cache()
+    capacity = int(max(Ds) * 1.25) + 4096
+    fr = B.Frame(n, W, H, capacity)
+
+    nviews = len(ccams)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for i in range(args.warmup):
+        B.render_frame(dev, ccams[i % nviews], fr)
+    torch.cuda.synchronize()
+    D_chk, status = B.read_status(fr)
+    assert status == B.OK, f"status {status}"
+
+    marks = [[ev(), ev(), ev(), ev()] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        cc = ccams[i % nviews]
+        m = marks[i]
+        m[0].record()
+        B.preprocess(dev, cc, fr)
+        m[1].record()
+        B.bin_sort(cc, fr)
+        m[2].record()
+        B.render(cc, fr)
+        m[3].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    total_s = t1 - t0
+    ms_per_step = 1e3 * total_s / args.steps
+    fps = args.steps / total_s
+    _, status = B.read_status(fr)
+    assert status == B.OK, f"status {status}"
+
+    t_pre = np.array([m[0].elapsed_time(m[1]) for m in marks])
+    t_sort = np.array([m[1].elapsed_time(m[2]) for m in marks])
+    t_blend = np.array([m[2].elapsed_time(m[3]) for m in marks])
+    view_of = np.arange(args.steps) % nviews
+
+    # ---- CPU oracle: counts E, C (algorithmic pairs) and the baseline time
+    cpu = None
+    E = C = None
+    n_near = None
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        E, C, n_near, cpu_t = [], [], [], []
+        sample_views = list(range(nviews))
+        for v in sample_views:
+            c0 = time.perf_counter()
+            ofr = ref.render_frame(scene, cams[v])
+            cpu_t.append(time.perf_counter() - c0)
+            assert ofr.binned.D == stats[v]["D"], "GPU and oracle disagree on the pair count"
+            E.append(int(ofr.img.E.sum())); C.append(int(ofr.img.C.sum()))
+            n_near.append(int((ofr.pre.stage != ref.CULL_NEAR).sum()))
+            del ofr
+        cores = len(os.sched_getaffinity(0))
+        omp = os.environ.get("OMP_NUM_THREADS")
+        threads = min(cores, int(omp)) if omp and omp.isdigit() else cores
+        cpu = dict(value=len(sample_views) / sum(cpu_t), unit="frames/s", cores=threads, kind="oracle",
+                   sample=f"cfg {args.cfg}: one whole frame (preprocess, bin+sort, blend) for each of its "
+                          f"{len(sample_views)} viewpoints, {sum(cpu_t):.1f} s of oracle time",
+                   blends_per_s=sum(E) / sum(cpu_t))
+
+    out = {
+        "metric": "frames/s, 1080p render of 3M Gaussians (whole forward path: preprocess + bin/sort + blend)"
+                  if args.cfg == 2 and args.n is None else f"frames/s, config {args.cfg}",
+        "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.cfg}: {n} Gaussians, {W}x{H}, 16x16 tiles, SH degree 3, "
+                               f"{nviews} seeded viewpoints rendered back-to-back",
+                   "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity},
+        "stage_ms": {"preprocess": float(t_pre.mean()), "bin_sort": float(t_sort.mean()),
+                     "render": float(t_blend.mean())},
+    }
+    if E is not None:
+        Ev = np.array(E, dtype=np.float64); Cv = np.array(C, dtype=np.float64)
+        # blends/s: algorithmic evaluated pairs of each step's view over that step's render time
+        blends = Ev[view_of].sum() / (t_blend.sum() * 1e-3)
+        flops = (14.0 * Ev + 10.0 * Cv)[view_of].sum()
+        tf = flops / (t_blend.sum() * 1e-3) / 1e12
+        out["blends_per_s"] = blends
+        out["roofline"] = {"kernel": "blend_kernel", "bound": "alu", "achieved": tf, "peak": FP32_PEAK_TFLOPS,
+                           "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": None,
+                           "avg_launch_ms": float(t_blend.mean()),
+                           "flops_per_launch": float(flops / args.steps)}
+        byts = []
+        for v in range(nviews):
+            byts.append(algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles, passes)["total"])
+        byts = np.array(byts, dtype=np.float64)
+        gbs = byts[view_of].sum() / ((t_pre.sum() + t_sort.sum()) * 1e-3) / 1e9
+        out["roofline_hbm_stages"] = {"kernels": "preprocess + scan + emit + radix passes + ranges",
+                                      "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                      "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                                      "bytes_per_frame": float(byts.mean())}
+        out["cpu_baseline"] = cpu
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

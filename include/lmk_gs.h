@@ -1,0 +1,145 @@
+/*
+ * lmk_gs.h -- C ABI of the MI355X (gfx950) tile-based Gaussian-splatting
+ * forward rasteriser.
+ *
+ * The path is the rasteriser of the LandMarkSystem report: primitives defined
+ * by Sec. 2.2 Eq. 7-8 (mean, rotation, scale, SH colour, opacity) are projected
+ * to 2D Gaussians (EWA splatting, Sec. 2.2), duplicated into (tile | depth)
+ * keys and depth-sorted per screen tile (Sec. 2.2; Sec. 4.2.1 names the stages),
+ * then composited front to back per pixel (Sec. 2.2 Eq. 9-10).
+ *
+ * General rules
+ *  - Every pointer inside the structs below is a DEVICE pointer owned by the
+ *    caller.  The library allocates and frees nothing and keeps no state
+ *    between calls apart from the last HIP error code.
+ *  - All work is enqueued on the caller's HIP stream (`stream`, a hipStream_t
+ *    passed as void*; NULL is the default stream).  No call synchronises except
+ *    lmk_gs_read_status.  Buffers must stay valid until the stream has drained.
+ *  - Arguments are validated on the host before the first HIP call; a
+ *    validation failure enqueues nothing.
+ *  - Return value: LMK_GS_OK or a negative LMK_GS_ERR_* code.
+ *  - Structure-of-arrays inputs: an attribute with k components is k
+ *    consecutive planes of n floats (component-major, plane stride n).
+ */
+#ifndef LMK_GS_H
+#define LMK_GS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LMK_GS_OK 0
+#define LMK_GS_ERR_INVALID (-1)     /* NULL pointer, bad size, unsupported tile, non-finite camera */
+#define LMK_GS_ERR_CAPACITY (-2)    /* more (primitive, tile) pairs than `capacity`, or scratch too small */
+#define LMK_GS_ERR_HIP (-3)         /* a HIP call failed; see lmk_gs_last_hip_error */
+#define LMK_GS_ERR_UNSUPPORTED (-4)
+
+#define LMK_GS_TILE 16u             /* pixels per tile edge; the only supported value */
+#define LMK_GS_FEAT_STRIDE 12u      /* floats per primitive in lmk_gs_projected.feat */
+
+/* The scene (Sec. 2.2 Eq. 7-8 and the text after Eq. 8). */
+typedef struct lmk_gs_gaussians {
+    const float *mean;     /* [3][n]  world-space centre mu                         */
+    const float *scale;    /* [3][n]  diagonal of S, linear and > 0                 */
+    const float *rot;      /* [4][n]  quaternion (w,x,y,z) of R, any non-zero norm  */
+    const float *opacity;  /* [n]     alpha in [0,1]                                */
+    const float *sh;       /* [(sh_degree+1)^2][3][n] real SH colour coefficients   */
+    uint32_t n;            /* number of primitives (0 is allowed)                   */
+    uint32_t sh_degree;    /* 0..3                                                  */
+} lmk_gs_gaussians;
+
+/* Pinhole camera.  Passed by value to the kernels (kernel arguments live in
+ * scalar registers on CDNA, the counterpart of the constant-memory argument
+ * passing listed in Sec. 4.2.1). */
+typedef struct lmk_gs_camera {
+    float view[12];        /* row-major 3x4 world->camera [R|t]; +x right, +y down, +z forward */
+    float cam_pos[3];      /* camera centre in world space (for the SH view direction) */
+    float fx, fy, cx, cy;  /* focal lengths and principal point in pixels; pixel (i,j) has centre (i+.5, j+.5) */
+    uint32_t width, height;
+    uint32_t tile;         /* must equal LMK_GS_TILE */
+    float near_z;          /* primitives with camera z <= near_z are culled; must be > 0 */
+    float lowpass;         /* added to the diagonal of the 2D covariance (px^2), >= 0 */
+    float bg[3];           /* background colour composited behind everything */
+} lmk_gs_camera;
+
+/* Per-primitive results of lmk_gs_preprocess.  For a primitive with
+ * tiles_touched == 0 (culled) the other arrays hold unspecified values. */
+typedef struct lmk_gs_projected {
+    float *depth;             /* [n]     camera-space z                                       */
+    uint32_t *tiles_touched;  /* [n]     tiles overlapped by the support rectangle; 0 = culled */
+    uint16_t *rect;           /* [n][4]  x0,y0,x1,y1 in tile units, half-open                  */
+    float *feat;              /* [n][12] u, v, conic A, B, C, opacity, r, g, b, 0, 0, 0;
+                                         16-byte aligned                                       */
+    uint64_t *offsets;        /* [n+1]   exclusive prefix sum of tiles_touched; optional (may be
+                                         NULL), written by lmk_gs_bin_sort when present        */
+} lmk_gs_projected;
+
+/* Results of lmk_gs_bin_sort. */
+typedef struct lmk_gs_binned {
+    uint64_t *keys;           /* [capacity] sorted keys: tile id << 32 | bits of depth          */
+    uint32_t *vals;           /* [capacity] primitive index of each sorted key                  */
+    uint64_t *keys_alt;       /* [capacity] ping-pong buffer, contents unspecified on return    */
+    uint32_t *vals_alt;       /* [capacity] ping-pong buffer                                    */
+    uint64_t capacity;        /* pairs each buffer can hold                                     */
+    uint64_t *tile_offsets;   /* [tiles+1]  CSR: pairs of tile t are [tile_offsets[t], tile_offsets[t+1]) */
+} lmk_gs_binned;
+
+/* Bytes of device scratch the three calls need for n primitives, a
+ * width x height image and `capacity` pairs.  The same scratch buffer
+ * (256-byte aligned) must be passed to preprocess and bin_sort of one frame.
+ * Its first 16 bytes are {uint64 pair count D, int32 status, int32 pad}. */
+int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height,
+                               uint64_t capacity, size_t *scratch_bytes);
+
+/* Stage 1 (Sec. 2.2 Eq. 8 + EWA projection + SH colour; the per-primitive
+ * kernel of Sec. 4.2.1).  For each primitive: camera-space position and
+ * near-plane cull; Sigma = R S S^T R^T; Sigma' = J W Sigma W^T J^T + lowpass*I;
+ * conic = Sigma'^-1 (culled unless det > 0); pixel centre; cull if opacity <
+ * 1/255; support rectangle of the ellipse d^T conic d <= 11.09 in tiles,
+ * clamped to the grid (empty = culled); rgb = max(0, 0.5 + SH(dir)).
+ * Also accumulates per-block tile counts into scratch and clears the status
+ * word.  Writes every array of `out` except `offsets`. */
+int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
+                          const lmk_gs_projected *out,
+                          void *scratch, size_t scratch_bytes, void *stream);
+
+/* Stage 2 (duplication into keys, depth sort at tile granularity, Sec. 2.2 and
+ * Sec. 4.2.1).  Prefix-sums tiles_touched, emits one (key, value) per
+ * (primitive, tile of its rectangle) -- primitives in index order, rectangle
+ * row-major -- sorts all pairs ascending by (tile, depth bits, primitive
+ * index) with a stable LSD radix sort, and extracts the per-tile ranges.
+ * If the pair count exceeds `capacity`, only the first `capacity` emitted
+ * pairs are processed and the status word becomes LMK_GS_ERR_CAPACITY. */
+int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,
+                        const lmk_gs_binned *out,
+                        void *scratch, size_t scratch_bytes, void *stream);
+
+/* Stage 3 (Sec. 2.2 Eq. 9-10).  Each pixel walks its tile's list front to back:
+ * alpha = min(0.99, o * exp(-q/2)), pairs with alpha < 1/255 are skipped, the
+ * walk stops before the pair that would take T below 1e-4.
+ * out_rgb is [3][height][width] (planar), out_transmittance [height][width]:
+ * rgb = sum c_i alpha_i T_i + T_final * bg. */
+int32_t lmk_gs_render(const lmk_gs_projected *proj, const lmk_gs_binned *binned,
+                      const lmk_gs_camera *cam,
+                      float *out_rgb, float *out_transmittance, void *stream);
+
+/* Copies {pair count D, status} of the frame from scratch to the host.
+ * Synchronises `stream`.  Either output pointer may be NULL. */
+int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream);
+
+/* Text for an LMK_GS_* code; never NULL. */
+const char *lmk_gs_strerror(int32_t code);
+
+/* The hipError_t value of the last failed HIP call in this process (0 if none). */
+int32_t lmk_gs_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+uint32_t lmk_gs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LMK_GS_H */

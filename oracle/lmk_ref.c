@@ -336,12 +336,19 @@ void lmk_ref_ranges(uint64_t count, const uint64_t *keys, uint32_t num_tiles, ui
  *   skip when alpha < 1/255                            [reading]
  *   stop, without compositing, when T (1-alpha) < 1e-4 [reading]
  * Also counts E (entries visited, including the one that stopped the walk) and
- * C (entries composited), and two ambiguity budgets: how far the pixel could
- * move if a decision that is within rounding of its threshold went the other
- * way (see DESIGN: image tolerance rule).
+ * C (entries composited), and the pixel's error budget for an fp32 renderer
+ * (image tolerance rule):
+ *   - rounding: an fp32 evaluation of q carries an absolute error of up to
+ *     about 8 * 2^-24 * (|A| dx^2 + 2 |B dx dy| + |C| dy^2), which matters when
+ *     the terms are large and cancel (long thin splats far from their centre);
+ *     it is propagated to first order through alpha and T;
+ *   - ambiguity: a pair whose alpha (or whose T') is within that rounding of
+ *     its threshold may be decided the other way, which moves the pixel by the
+ *     pair's whole contribution.  `amb` counts such decisions.
+ * beta bounds the colour error from both, beta_T the transmittance error.
  */
 typedef struct {
-    double rgb[3]; double T; uint32_t E, C; double beta, beta_T;
+    double rgb[3]; double T; uint32_t E, C, amb; double beta, beta_T;
 } ref_pixel;
 
 static void composite_pixel(double pxc, double pyc, const uint32_t *list, uint64_t count,
@@ -351,7 +358,10 @@ static void composite_pixel(double pxc, double pyc, const uint32_t *list, uint64
 {
     double T = 1.0, acc[3] = { 0.0, 0.0, 0.0 };
     uint32_t E = 0, C = 0;
+    uint32_t amb = 0;
     double beta = 0.0, beta_T = 0.0;
+    double relT = 0.0;                 /* first-order bound on the relative error of an fp32 T */
+    const double EPS = 1.0 / 16777216.0;   /* 2^-24 */
     for (uint64_t k = 0; k < count; ++k) {
         const size_t g = list[k];
         ++E;
@@ -361,15 +371,24 @@ static void composite_pixel(double pxc, double pyc, const uint32_t *list, uint64
         const double q = A * dx * dx + 2.0 * B * dx * dy + Cc * dy * dy;
         double power = -0.5 * q;
         if (power > 0.0) power = 0.0;
-        double alpha = (double)opacity[g] * exp(power);
+        const double raw = (double)opacity[g] * exp(power);
+        double alpha = raw;
         if (alpha > (double)REF_ALPHA_MAX) alpha = (double)REF_ALPHA_MAX;
-        if (fabs(255.0 * alpha - 1.0) <= 1e-4) { beta += 2.0 * alpha * T * cmax; beta_T += alpha * T; }
+        /* error budget of this pair */
+        const double mag = fabs(A) * dx * dx + 2.0 * fabs(B * dx * dy) + fabs(Cc) * dy * dy;
+        const double dalpha = 0.5 * 8.0 * EPS * mag + 8.0 * EPS;   /* relative error of an fp32 alpha */
+        if (fabs(log(255.0 * raw)) <= dalpha + 1e-6) {
+            ++amb; beta += 2.0 * alpha * T * cmax; beta_T += alpha * T;
+        }
         if ((float)alpha < REF_ALPHA_MIN) {
             if (trace && E <= trace_cap) trace[E - 1] = T;
             continue;
         }
         const double Tn = T * (1.0 - alpha);
-        if (fabs(Tn / (double)REF_T_MIN - 1.0) <= 1e-3) { beta += (alpha * T + Tn) * cmax; beta_T += T; }
+        const double relTn = relT + alpha * dalpha / (1.0 - alpha) + 2.0 * EPS;
+        if (fabs(Tn / (double)REF_T_MIN - 1.0) <= relTn + 1e-6) {
+            ++amb; beta += (alpha * T + Tn) * cmax; beta_T += T;
+        }
         if ((float)Tn < REF_T_MIN) {
             if (trace && E <= trace_cap) trace[E - 1] = T;
             break;
@@ -378,14 +397,21 @@ static void composite_pixel(double pxc, double pyc, const uint32_t *list, uint64
         acc[0] += rgb[g] * w;
         acc[1] += rgb[N + g] * w;
         acc[2] += rgb[2 * N + g] * w;
+        double cg = rgb[g];
+        if (rgb[N + g] > cg) cg = rgb[N + g];
+        if (rgb[2 * N + g] > cg) cg = rgb[2 * N + g];
+        beta += w * cg * (dalpha + relT + 4.0 * EPS);
         T = Tn;
+        relT = relTn;
         ++C;
         if (trace && E <= trace_cap) trace[E - 1] = T;
     }
+    beta += T * relT * cmax;           /* cmax >= 1 >= |bg| is assumed by the tests */
+    beta_T += T * relT;
     out->rgb[0] = acc[0] + T * (double)bg[0];
     out->rgb[1] = acc[1] + T * (double)bg[1];
     out->rgb[2] = acc[2] + T * (double)bg[2];
-    out->T = T; out->E = E; out->C = C; out->beta = beta; out->beta_T = beta_T;
+    out->T = T; out->E = E; out->C = C; out->amb = amb; out->beta = beta; out->beta_T = beta_T;
 }
 
 static double max_rgb(uint32_t n, const uint8_t *stage, const double *rgb)
@@ -399,13 +425,13 @@ static double max_rgb(uint32_t n, const uint8_t *stage, const double *rgb)
 }
 
 /* Tile pipeline render: every pixel walks the sorted slice of its tile.
- * out_rgb [3][H][W], out_T [H][W], out_E/out_C [H][W], beta/beta_T [H][W]. */
+ * out_rgb [3][H][W], out_T [H][W], out_E/out_C [H][W], beta/beta_T/amb [H][W]. */
 void lmk_ref_render(uint32_t n, const uint8_t *stage, const float *mean2d, const float *conic,
                     const float *opacity, const double *rgb,
                     const uint32_t *sorted_vals, const uint64_t *tile_offsets,
                     const ref_camera *cam,
                     double *out_rgb, double *out_T, uint32_t *out_E, uint32_t *out_C,
-                    double *out_beta, double *out_beta_T)
+                    double *out_beta, double *out_beta_T, uint32_t *out_amb)
 {
     const uint32_t W = cam->width, H = cam->height, TS = cam->tile;
     const uint32_t TX = (W + TS - 1) / TS;
@@ -422,7 +448,7 @@ void lmk_ref_render(uint32_t n, const uint8_t *stage, const float *mean2d, const
             const size_t p = (size_t)j * W + i;
             for (int ch = 0; ch < 3; ++ch) out_rgb[(size_t)ch * H * W + p] = r.rgb[ch];
             out_T[p] = r.T; out_E[p] = r.E; out_C[p] = r.C;
-            out_beta[p] = r.beta; out_beta_T[p] = r.beta_T;
+            out_beta[p] = r.beta; out_beta_T[p] = r.beta_T; out_amb[p] = r.amb;
         }
     }
 }
@@ -457,13 +483,13 @@ uint32_t lmk_ref_depth_order(uint32_t n, const uint8_t *stage, const float *dept
 
 /* Brute force at chosen pixels: each walks the whole depth order.
  * xs, ys: integer pixel coordinates; outputs are per sample:
- * out_rgb [npix][3], out_T, out_C, out_beta, out_beta_T [npix]. */
+ * out_rgb [npix][3], out_T, out_C, out_beta, out_beta_T, out_amb [npix]. */
 void lmk_ref_render_pixels_brute(uint32_t n, const uint8_t *stage, const float *mean2d,
                                  const float *conic, const float *opacity, const double *rgb,
                                  const uint32_t *order, uint32_t order_len, const ref_camera *cam,
                                  uint32_t npix, const uint32_t *xs, const uint32_t *ys,
                                  double *out_rgb, double *out_T, uint32_t *out_C,
-                                 double *out_beta, double *out_beta_T)
+                                 double *out_beta, double *out_beta_T, uint32_t *out_amb)
 {
     const double cmax = max_rgb(n, stage, rgb);
 #pragma omp parallel for schedule(dynamic, 1)
@@ -473,7 +499,7 @@ void lmk_ref_render_pixels_brute(uint32_t n, const uint8_t *stage, const float *
         composite_pixel((double)xs[k] + 0.5, (double)ys[k] + 0.5, order, order_len,
                         n, mean2d, conic, opacity, rgb, cmax, cam->bg, &r, NULL, 0);
         for (int ch = 0; ch < 3; ++ch) out_rgb[3 * k + ch] = r.rgb[ch];
-        out_T[k] = r.T; out_C[k] = r.C; out_beta[k] = r.beta; out_beta_T[k] = r.beta_T;
+        out_T[k] = r.T; out_C[k] = r.C; out_beta[k] = r.beta; out_beta_T[k] = r.beta_T; out_amb[k] = r.amb;
     }
 }
 
@@ -510,7 +536,7 @@ void lmk_ref_render_pixels_list(uint32_t n, const uint8_t *stage, const float *m
                                 const uint32_t *list, uint64_t list_len, const ref_camera *cam,
                                 uint32_t npix, const uint32_t *xs, const uint32_t *ys,
                                 double *out_rgb, double *out_T, uint32_t *out_E, uint32_t *out_C,
-                                double *out_beta, double *out_beta_T)
+                                double *out_beta, double *out_beta_T, uint32_t *out_amb)
 {
     const double cmax = max_rgb(n, stage, rgb);
     for (size_t k = 0; k < (size_t)npix; ++k) {
@@ -519,7 +545,7 @@ void lmk_ref_render_pixels_list(uint32_t n, const uint8_t *stage, const float *m
                         n, mean2d, conic, opacity, rgb, cmax, cam->bg, &r, NULL, 0);
         for (int ch = 0; ch < 3; ++ch) out_rgb[3 * k + ch] = r.rgb[ch];
         out_T[k] = r.T; out_E[k] = r.E; out_C[k] = r.C;
-        out_beta[k] = r.beta; out_beta_T[k] = r.beta_T;
+        out_beta[k] = r.beta; out_beta_T[k] = r.beta_T; out_amb[k] = r.amb;
     }
 }
 

@@ -141,13 +141,14 @@ def render(pre: SimpleNamespace, binned: SimpleNamespace, cam: dict) -> SimpleNa
     H, W = int(cam["height"]), int(cam["width"])
     out = SimpleNamespace(rgb=np.empty((3, H, W), np.float64), T=np.empty((H, W), np.float64),
                           E=np.empty((H, W), np.uint32), C=np.empty((H, W), np.uint32),
-                          beta=np.empty((H, W), np.float64), beta_T=np.empty((H, W), np.float64))
+                          beta=np.empty((H, W), np.float64), beta_T=np.empty((H, W), np.float64),
+                          amb=np.empty((H, W), np.uint32))
     cc = _camera(cam)
     vals = binned.vals if binned.D else np.zeros(1, np.uint32)
     lib().lmk_ref_render(C.c_uint32(pre.n), _p(pre.stage), _p(pre.mean2d), _p(pre.conic),
                          _p(pre.opacity), _p(pre.rgb), _p(vals), _p(binned.tile_offsets),
                          C.byref(cc), _p(out.rgb), _p(out.T), _p(out.E), _p(out.C),
-                         _p(out.beta), _p(out.beta_T))
+                         _p(out.beta), _p(out.beta_T), _p(out.amb))
     return out
 
 
@@ -166,13 +167,13 @@ def render_pixels_brute(pre: SimpleNamespace, cam: dict, xs, ys, order=None) -> 
     k = xs.size
     out = SimpleNamespace(rgb=np.empty((k, 3), np.float64), T=np.empty(k, np.float64),
                           C=np.empty(k, np.uint32), beta=np.empty(k, np.float64),
-                          beta_T=np.empty(k, np.float64))
+                          beta_T=np.empty(k, np.float64), amb=np.empty(k, np.uint32))
     cc = _camera(cam)
     o = order if order.size else np.zeros(1, np.uint32)
     lib().lmk_ref_render_pixels_brute(C.c_uint32(pre.n), _p(pre.stage), _p(pre.mean2d), _p(pre.conic),
                                       _p(pre.opacity), _p(pre.rgb), _p(o), C.c_uint32(order.size),
                                       C.byref(cc), C.c_uint32(k), _p(xs), _p(ys),
-                                      _p(out.rgb), _p(out.T), _p(out.C), _p(out.beta), _p(out.beta_T))
+                                      _p(out.rgb), _p(out.T), _p(out.C), _p(out.beta), _p(out.beta_T), _p(out.amb))
     return out
 
 
@@ -195,14 +196,15 @@ def render_pixels_list(pre: SimpleNamespace, cam: dict, lst: np.ndarray, xs, ys)
     k = xs.size
     out = SimpleNamespace(rgb=np.empty((k, 3), np.float64), T=np.empty(k, np.float64),
                           E=np.empty(k, np.uint32), C=np.empty(k, np.uint32),
-                          beta=np.empty(k, np.float64), beta_T=np.empty(k, np.float64))
+                          beta=np.empty(k, np.float64), beta_T=np.empty(k, np.float64),
+                          amb=np.empty(k, np.uint32))
     cc = _camera(cam)
     l = np.ascontiguousarray(lst, dtype=np.uint32) if len(lst) else np.zeros(1, np.uint32)
     lib().lmk_ref_render_pixels_list(C.c_uint32(pre.n), _p(pre.stage), _p(pre.mean2d), _p(pre.conic),
                                      _p(pre.opacity), _p(pre.rgb), _p(l), C.c_uint64(len(lst)),
                                      C.byref(cc), C.c_uint32(k), _p(xs), _p(ys),
                                      _p(out.rgb), _p(out.T), _p(out.E), _p(out.C),
-                                     _p(out.beta), _p(out.beta_T))
+                                     _p(out.beta), _p(out.beta_T), _p(out.amb))
     return out
 
 

@@ -1,0 +1,200 @@
+"""Thin ctypes binding of liblmk_gs.so (include/lmk_gs.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels
+behind the C ABI.  torch is used for device memory and streams.  There is no
+CPU fallback: if the library is missing, import of the symbols fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch  # must be imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblmk_gs.so")
+
+OK, ERR_INVALID, ERR_CAPACITY, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
+TILE = 16
+FEAT_STRIDE = 12
+
+EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
+           "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version")
+
+
+class Gaussians(C.Structure):
+    _fields_ = [("mean", C.c_void_p), ("scale", C.c_void_p), ("rot", C.c_void_p),
+                ("opacity", C.c_void_p), ("sh", C.c_void_p), ("n", C.c_uint32), ("sh_degree", C.c_uint32)]
+
+
+class Camera(C.Structure):
+    _fields_ = [("view", C.c_float * 12), ("cam_pos", C.c_float * 3),
+                ("fx", C.c_float), ("fy", C.c_float), ("cx", C.c_float), ("cy", C.c_float),
+                ("width", C.c_uint32), ("height", C.c_uint32), ("tile", C.c_uint32),
+                ("near_z", C.c_float), ("lowpass", C.c_float), ("bg", C.c_float * 3)]
+
+
+class Projected(C.Structure):
+    _fields_ = [("depth", C.c_void_p), ("tiles_touched", C.c_void_p), ("rect", C.c_void_p),
+                ("feat", C.c_void_p), ("offsets", C.c_void_p)]
+
+
+class Binned(C.Structure):
+    _fields_ = [("keys", C.c_void_p), ("vals", C.c_void_p), ("keys_alt", C.c_void_p),
+                ("vals_alt", C.c_void_p), ("capacity", C.c_uint64), ("tile_offsets", C.c_void_p)]
+
+
+class LmkGsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})"
+                         + (f", hipError {last_hip_error()}" if code == ERR_HIP else ""))
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the HIP library.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_21364_amd.build` "
+                               "(the renderer has no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        l.lmk_gs_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint64, C.POINTER(C.c_size_t)]
+        l.lmk_gs_preprocess.argtypes = [C.POINTER(Gaussians), C.POINTER(Camera), C.POINTER(Projected),
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
+        l.lmk_gs_bin_sort.argtypes = [C.POINTER(Projected), C.c_uint32, C.POINTER(Camera), C.POINTER(Binned),
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
+        l.lmk_gs_render.argtypes = [C.POINTER(Projected), C.POINTER(Binned), C.POINTER(Camera),
+                                    C.c_void_p, C.c_void_p, C.c_void_p]
+        l.lmk_gs_read_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_void_p]
+        l.lmk_gs_strerror.argtypes = [C.c_int32]
+        l.lmk_gs_strerror.restype = C.c_char_p
+        for name in ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
+                     "lmk_gs_read_status", "lmk_gs_last_hip_error"):
+            getattr(l, name).restype = C.c_int32
+        l.lmk_gs_version.restype = C.c_uint32
+        _lib = l
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().lmk_gs_strerror(code).decode()
+
+
+def last_hip_error() -> int:
+    return int(lib().lmk_gs_last_hip_error())
+
+
+def make_camera(cam: dict) -> Camera:
+    c = Camera()
+    c.view[:] = [float(x) for x in np.asarray(cam["view"], dtype=np.float32).reshape(12)]
+    c.cam_pos[:] = [float(x) for x in np.asarray(cam["cam_pos"], dtype=np.float32)]
+    c.fx, c.fy, c.cx, c.cy = (float(np.float32(cam[k])) for k in ("fx", "fy", "cx", "cy"))
+    c.width, c.height, c.tile = int(cam["width"]), int(cam["height"]), int(cam["tile"])
+    c.near_z, c.lowpass = float(np.float32(cam["near_z"])), float(np.float32(cam["lowpass"]))
+    c.bg[:] = [float(x) for x in np.asarray(cam["bg"], dtype=np.float32)]
+    return c
+
+
+def workspace_bytes(n: int, width: int, height: int, capacity: int) -> int:
+    out = C.c_size_t(0)
+    rc = lib().lmk_gs_workspace_bytes(n, width, height, capacity, C.byref(out))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_workspace_bytes")
+    return int(out.value)
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> int | None:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class Scene:
+    """Device-resident primitives (structure of arrays, see include/lmk_gs.h)."""
+
+    def __init__(self, scene: dict, device="cuda:0"):
+        self.n = int(scene["n"])
+        self.sh_degree = int(scene["sh_degree"])
+        f = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+        self.mean, self.scale, self.rot = f(scene["mean"]), f(scene["scale"]), f(scene["rot"])
+        self.opacity = f(scene["opacity"])
+        ncoef = (self.sh_degree + 1) ** 2
+        self.sh = f(scene["sh"][:ncoef])
+        self.c = Gaussians(_ptr(self.mean), _ptr(self.scale), _ptr(self.rot), _ptr(self.opacity),
+                           _ptr(self.sh), self.n, self.sh_degree)
+
+
+class Frame:
+    """All device buffers of one frame in flight: per-primitive outputs, pair
+    buffers for `capacity` pairs, scratch, and the image."""
+
+    def __init__(self, n: int, width: int, height: int, capacity: int, device="cuda:0",
+                 want_offsets: bool = False):
+        self.n, self.width, self.height, self.capacity = n, width, height, int(capacity)
+        self.tiles_x = (width + TILE - 1) // TILE
+        self.tiles_y = (height + TILE - 1) // TILE
+        dev = device
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        self.depth = e((max(n, 1),), torch.float32)
+        self.tiles_touched = e((max(n, 1),), torch.int32)
+        self.rect = e((max(n, 1), 4), torch.int16)
+        self.feat = e((max(n, 1), FEAT_STRIDE), torch.float32)
+        self.offsets = e((n + 1,), torch.int64) if want_offsets else None
+        cap = max(self.capacity, 1)
+        self.keys, self.keys_alt = e((cap,), torch.int64), e((cap,), torch.int64)
+        self.vals, self.vals_alt = e((cap,), torch.int32), e((cap,), torch.int32)
+        self.tile_offsets = e((self.tiles_x * self.tiles_y + 1,), torch.int64)
+        self.scratch_bytes = workspace_bytes(n, width, height, self.capacity)
+        self.scratch = e((self.scratch_bytes,), torch.uint8)
+        self.out_rgb = e((3, height, width), torch.float32)
+        self.out_T = e((height, width), torch.float32)
+        self.proj = Projected(_ptr(self.depth), _ptr(self.tiles_touched), _ptr(self.rect),
+                              _ptr(self.feat), _ptr(self.offsets))
+        self.binned = Binned(_ptr(self.keys), _ptr(self.vals), _ptr(self.keys_alt), _ptr(self.vals_alt),
+                             self.capacity, _ptr(self.tile_offsets))
+
+
+def preprocess(scene: Scene, cam: Camera, frame: Frame, stream=None) -> None:
+    rc = lib().lmk_gs_preprocess(C.byref(scene.c), C.byref(cam), C.byref(frame.proj),
+                                 _ptr(frame.scratch), frame.scratch_bytes, _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_preprocess")
+
+
+def bin_sort(cam: Camera, frame: Frame, stream=None) -> None:
+    rc = lib().lmk_gs_bin_sort(C.byref(frame.proj), frame.n, C.byref(cam), C.byref(frame.binned),
+                               _ptr(frame.scratch), frame.scratch_bytes, _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_bin_sort")
+
+
+def render(cam: Camera, frame: Frame, stream=None) -> None:
+    rc = lib().lmk_gs_render(C.byref(frame.proj), C.byref(frame.binned), C.byref(cam),
+                             _ptr(frame.out_rgb), _ptr(frame.out_T), _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_render")
+
+
+def read_status(frame: Frame, stream=None) -> tuple[int, int]:
+    """(pair count D, status) of the frame; synchronises the stream."""
+    d, s = C.c_uint64(0), C.c_int32(0)
+    rc = lib().lmk_gs_read_status(_ptr(frame.scratch), C.byref(d), C.byref(s), _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_read_status")
+    return int(d.value), int(s.value)
+
+
+def render_frame(scene: Scene, cam: Camera, frame: Frame, stream=None) -> None:
+    """The whole hot path for one view: three asynchronous calls on one stream."""
+    preprocess(scene, cam, frame, stream)
+    bin_sort(cam, frame, stream)
+    render(cam, frame, stream)

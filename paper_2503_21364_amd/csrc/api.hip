@@ -1,0 +1,159 @@
+// extern "C" entry points of liblmk_gs.so: argument validation on the host,
+// then kernel launches on the caller's stream.  See include/lmk_gs.h for the
+// contract of each call.
+#include "lmk_gs_internal.h"
+
+#include <atomic>
+#include <cmath>
+
+using namespace lmk;
+
+namespace {
+
+std::atomic<int32_t> g_last_hip_error{0};
+
+int32_t hip_fail(hipError_t e)
+{
+    g_last_hip_error.store((int32_t)e);
+    return LMK_GS_ERR_HIP;
+}
+
+bool finite_all(const float *p, int n)
+{
+    for (int i = 0; i < n; ++i)
+        if (!std::isfinite(p[i])) return false;
+    return true;
+}
+
+constexpr uint32_t kMaxTilesPerAxis = 4096;      // 65536 pixels per axis
+constexpr uint32_t kMaxTiles = 1u << 22;         // keeps a workgroup's tile count inside 32 bits
+
+int32_t check_camera(const lmk_gs_camera *cam, ProjParams *pp)
+{
+    if (!cam) return LMK_GS_ERR_INVALID;
+    if (cam->tile != LMK_GS_TILE) return LMK_GS_ERR_UNSUPPORTED;
+    if (cam->width == 0 || cam->height == 0) return LMK_GS_ERR_INVALID;
+    if (!finite_all(cam->view, 12) || !finite_all(cam->cam_pos, 3) || !finite_all(cam->bg, 3) ||
+        !finite_all(&cam->fx, 4) || !std::isfinite(cam->near_z) || !std::isfinite(cam->lowpass))
+        return LMK_GS_ERR_INVALID;
+    if (!(cam->fx > 0.0f) || !(cam->fy > 0.0f) || !(cam->near_z > 0.0f) || !(cam->lowpass >= 0.0f))
+        return LMK_GS_ERR_INVALID;
+    const uint32_t tx = (cam->width + LMK_GS_TILE - 1) / LMK_GS_TILE;
+    const uint32_t ty = (cam->height + LMK_GS_TILE - 1) / LMK_GS_TILE;
+    if (tx > kMaxTilesPerAxis || ty > kMaxTilesPerAxis || (uint64_t)tx * ty > kMaxTiles)
+        return LMK_GS_ERR_UNSUPPORTED;
+    pp->cam = *cam;
+    // guard band of the EWA Jacobian: 1.3 x the half-frustum tangent
+    pp->lim_x = 1.3f * ((0.5f * (float)cam->width) / cam->fx);
+    pp->lim_y = 1.3f * ((0.5f * (float)cam->height) / cam->fy);
+    pp->tiles_x = tx;
+    pp->tiles_y = ty;
+    return LMK_GS_OK;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height, uint64_t capacity,
+                               size_t *scratch_bytes)
+{
+    if (!scratch_bytes || width == 0 || height == 0) return LMK_GS_ERR_INVALID;
+    const uint32_t tx = (width + LMK_GS_TILE - 1) / LMK_GS_TILE;
+    const uint32_t ty = (height + LMK_GS_TILE - 1) / LMK_GS_TILE;
+    if (tx > kMaxTilesPerAxis || ty > kMaxTilesPerAxis || (uint64_t)tx * ty > kMaxTiles)
+        return LMK_GS_ERR_UNSUPPORTED;
+    *scratch_bytes = scratch_layout(n, capacity).total;
+    return LMK_GS_OK;
+}
+
+int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
+                          const lmk_gs_projected *out, void *scratch, size_t scratch_bytes,
+                          void *stream)
+{
+    ProjParams pp;
+    const int32_t rc = check_camera(cam, &pp);
+    if (rc != LMK_GS_OK) return rc;
+    if (!g || !out || !scratch) return LMK_GS_ERR_INVALID;
+    if (g->sh_degree > 3) return LMK_GS_ERR_INVALID;
+    if (g->n > 0) {
+        if (!g->mean || !g->scale || !g->rot || !g->opacity || !g->sh) return LMK_GS_ERR_INVALID;
+        if (!out->depth || !out->tiles_touched || !out->rect || !out->feat) return LMK_GS_ERR_INVALID;
+        if (!aligned(out->feat, 16) || !aligned(out->rect, 8)) return LMK_GS_ERR_INVALID;
+    }
+    if (!aligned(scratch, 256)) return LMK_GS_ERR_INVALID;
+    // the part of the scratch this call touches does not depend on the pair capacity
+    const ScratchLayout L = scratch_layout(g->n, 0);
+    if (scratch_bytes < L.table) return LMK_GS_ERR_CAPACITY;
+    const hipError_t e = launch_preprocess(*g, pp, *out, static_cast<char *>(scratch), L,
+                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
+int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,
+                        const lmk_gs_binned *out, void *scratch, size_t scratch_bytes, void *stream)
+{
+    ProjParams pp;
+    const int32_t rc = check_camera(cam, &pp);
+    if (rc != LMK_GS_OK) return rc;
+    if (!proj || !out || !scratch) return LMK_GS_ERR_INVALID;
+    if (n > 0 && (!proj->depth || !proj->tiles_touched || !proj->rect)) return LMK_GS_ERR_INVALID;
+    if (!out->tile_offsets) return LMK_GS_ERR_INVALID;
+    if (out->capacity > 0 && (!out->keys || !out->vals || !out->keys_alt || !out->vals_alt))
+        return LMK_GS_ERR_INVALID;
+    if (!aligned(scratch, 256) || !aligned(proj->rect, 8)) return LMK_GS_ERR_INVALID;
+    const ScratchLayout L = scratch_layout(n, out->capacity);
+    if (scratch_bytes < L.total) return LMK_GS_ERR_CAPACITY;
+    const hipError_t e = launch_bin_sort(*proj, n, pp, *out, static_cast<char *>(scratch), L,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
+int32_t lmk_gs_render(const lmk_gs_projected *proj, const lmk_gs_binned *binned,
+                      const lmk_gs_camera *cam, float *out_rgb, float *out_transmittance,
+                      void *stream)
+{
+    ProjParams pp;
+    const int32_t rc = check_camera(cam, &pp);
+    if (rc != LMK_GS_OK) return rc;
+    if (!proj || !binned || !out_rgb || !out_transmittance) return LMK_GS_ERR_INVALID;
+    if (!binned->tile_offsets) return LMK_GS_ERR_INVALID;
+    if (binned->capacity > 0 && (!binned->vals || !proj->feat)) return LMK_GS_ERR_INVALID;
+    if (!aligned(proj->feat, 16)) return LMK_GS_ERR_INVALID;
+    const hipError_t e = launch_render(*proj, *binned, pp, out_rgb, out_transmittance,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
+int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream)
+{
+    if (!scratch) return LMK_GS_ERR_INVALID;
+    ScratchHeader h;
+    hipError_t e = hipMemcpyAsync(&h, scratch, sizeof(h), hipMemcpyDeviceToHost,
+                                  static_cast<hipStream_t>(stream));
+    if (e == hipSuccess) e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    if (dup_count) *dup_count = h.dup_count;
+    if (status) *status = h.status;
+    return LMK_GS_OK;
+}
+
+const char *lmk_gs_strerror(int32_t code)
+{
+    switch (code) {
+    case LMK_GS_OK: return "ok";
+    case LMK_GS_ERR_INVALID: return "invalid argument";
+    case LMK_GS_ERR_CAPACITY: return "capacity exceeded";
+    case LMK_GS_ERR_HIP: return "HIP runtime error";
+    case LMK_GS_ERR_UNSUPPORTED: return "unsupported configuration";
+    default: return "unknown error code";
+    }
+}
+
+int32_t lmk_gs_last_hip_error(void) { return g_last_hip_error.load(); }
+
+uint32_t lmk_gs_version(void) { return 100; }
+
+}  // extern "C"

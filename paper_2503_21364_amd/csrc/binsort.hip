@@ -1,0 +1,376 @@
+// Stage 2: duplication of primitives into (tile | depth) keys, stable LSD radix
+// sort of the pairs, per-tile range extraction (the "depth sorting ... at the
+// granularity of tiles" of Sec. 2.2; duplication with keys is the second
+// kernel named in Sec. 4.2.1).
+//
+// All of it is integer work bound by HBM traffic.  The kernels read the pair
+// count D from device memory, so the host never waits for it: grids are sized
+// from the caller's capacity and surplus workgroups leave at once.
+//
+//   emit     one workgroup per 256 primitives; a load-balanced expansion: the
+//            workgroup's output slots are dealt round-robin to its threads and
+//            each slot finds its primitive by binary search in an LDS prefix
+//            array, so stores are contiguous whatever the rectangle sizes are.
+//   sort     8-bit digits, least significant first.  Per pass: (1) digit
+//            histogram of every 4096-pair sort tile, (2) prefix sums giving each
+//            (digit, sort tile) its output offset, (3) scatter: wavefront
+//            match-any ranking (ballots over the digit bits) keeps the order of
+//            equal digits, the tile is sorted by digit in LDS and written out in
+//            contiguous runs.
+//   ranges   tile_offsets[t] = first sorted position whose tile id is >= t.
+#include "lmk_gs_internal.h"
+
+namespace lmk {
+
+__device__ __forceinline__ u64 load_D(const ScratchHeader *h, u64 capacity)
+{
+    const u64 d = h->dup_count;
+    return d < capacity ? d : capacity;
+}
+
+// ---------------------------------------------------------------- emit
+__global__ __launch_bounds__(kPreBlock) void emit_kernel(
+    const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
+    const float *__restrict__ depth, const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
+    u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
+    ScratchHeader *__restrict__ header, u64 *__restrict__ digit_totals)
+{
+    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of tiles_touched inside the workgroup
+    __shared__ ushort4 s_rect[kPreBlock];
+    __shared__ u32 s_depth[kPreBlock];
+    __shared__ u32 s_wave[kPreBlock / kWave];
+
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 i = blockIdx.x * kPreBlock + tid;
+    const u32 cnt = i < n ? tiles_touched[i] : 0u;
+    if (cnt) {
+        s_rect[tid] = rect[i];
+        s_depth[tid] = __float_as_uint(depth[i]);
+    }
+    u32 incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const u32 t = __shfl_up(incl, o, 64);
+        if ((int)lane >= o) incl += t;
+    }
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    u32 wave_base = 0, total = 0;
+#pragma unroll
+    for (u32 k = 0; k < kPreBlock / kWave; ++k) {
+        const u32 w = s_wave[k];
+        if (k < wv) wave_base += w;
+        total += w;
+    }
+    const u32 excl = wave_base + incl - cnt;
+    s_excl[tid] = excl;
+    const u64 base = block_offsets[blockIdx.x];
+    if (offsets) {
+        if (i < n) offsets[i] = base + excl;
+        if (i == n - 1) offsets[n] = base + total;
+    }
+    if (blockIdx.x == 0) {
+        // the sort's global digit histograms start from zero every frame
+        for (u32 k = tid; k < kMaxPasses * kRadix; k += kPreBlock) digit_totals[k] = 0;
+        if (tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
+    }
+    __syncthreads();
+
+    for (u32 j = tid; j < total; j += kPreBlock) {
+        // owner = last primitive whose exclusive prefix is <= j (primitives with
+        // zero tiles share a prefix with their successor and are skipped by "last")
+        u32 lo = 0, hi = kPreBlock - 1;
+        while (lo < hi) {
+            const u32 mid = (lo + hi + 1) >> 1;
+            if (s_excl[mid] <= j) lo = mid; else hi = mid - 1;
+        }
+        const ushort4 r = s_rect[lo];
+        const u32 local = j - s_excl[lo];
+        const u32 w = (u32)r.z - (u32)r.x;
+        const u32 row = local / w;
+        const u32 tx = (u32)r.x + (local - row * w);
+        const u32 ty = (u32)r.y + row;
+        const u64 pos = base + j;
+        if (pos < capacity) {
+            keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)s_depth[lo];
+            vals[pos] = blockIdx.x * kPreBlock + lo;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- radix sort
+// (1) per-sort-tile digit histogram -> table[digit][tile], and global digit totals
+__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
+    const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
+    u32 shift, u64 *__restrict__ table, u64 table_stride, u64 *__restrict__ digit_totals)
+{
+    __shared__ u32 s_hist[kRadix];
+    const u64 D = load_D(header, capacity);
+    const u64 ntiles = (D + kSortTile - 1) / kSortTile;
+    const u32 tid = threadIdx.x;
+    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        s_hist[tid] = 0;
+        __syncthreads();
+        const u64 t0 = tile * kSortTile;
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u64 idx = t0 + (u64)j * kSortThreads + tid;
+            if (idx < D) atomicAdd(&s_hist[(u32)(keys[idx] >> shift) & (kRadix - 1)], 1u);
+        }
+        __syncthreads();
+        const u32 c = s_hist[tid];
+        table[(u64)tid * table_stride + tile] = c;
+        if (c) atomicAdd(&digit_totals[tid], (u64)c);
+        __syncthreads();
+    }
+}
+
+// (2) one workgroup per digit: exclusive scan of its row of the table, offset by
+// the total of all smaller digits.
+__global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
+    const ScratchHeader *__restrict__ header, u64 capacity, u64 *__restrict__ table,
+    u64 table_stride, const u64 *__restrict__ digit_totals)
+{
+    __shared__ u64 s_wave[kSortThreads / kWave];
+    __shared__ u64 s_carry;
+    const u64 D = load_D(header, capacity);
+    const u64 ntiles = (D + kSortTile - 1) / kSortTile;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 digit = blockIdx.x;
+
+    // base = sum of totals of digits below mine
+    u64 part = tid < digit ? digit_totals[tid] : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
+    if (lane == 0) s_wave[wv] = part;
+    __syncthreads();
+    if (tid == 0) {
+        u64 b = 0;
+        for (u32 k = 0; k < kSortThreads / kWave; ++k) b += s_wave[k];
+        s_carry = b;
+    }
+    __syncthreads();
+
+    u64 *row = table + (u64)digit * table_stride;
+    for (u64 base = 0; base < ntiles; base += kSortThreads) {
+        const u64 idx = base + tid;
+        const u64 v = idx < ntiles ? row[idx] : 0;
+        u64 incl = v;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const u64 t = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += t;
+        }
+        __syncthreads();                       // s_wave free again
+        if (lane == kWave - 1) s_wave[wv] = incl;
+        __syncthreads();
+        u64 wave_base = 0;
+        for (u32 k = 0; k < wv; ++k) wave_base += s_wave[k];
+        const u64 carry = s_carry;
+        if (idx < ntiles) row[idx] = carry + wave_base + incl - v;
+        __syncthreads();
+        if (tid == kSortThreads - 1) s_carry = carry + wave_base + incl;
+        __syncthreads();
+    }
+}
+
+// (3) stable scatter of one digit
+__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
+    const u64 *__restrict__ keys_in, const u32 *__restrict__ vals_in,
+    u64 *__restrict__ keys_out, u32 *__restrict__ vals_out,
+    const ScratchHeader *__restrict__ header, u64 capacity, u32 shift,
+    const u64 *__restrict__ table, u64 table_stride)
+{
+    constexpr u32 kWaves = kSortThreads / kWave;
+    constexpr u32 kPerWave = kSortItems * kWave;       // 1024 consecutive pairs per wavefront
+    __shared__ u32 s_wave_hist[kWaves][kRadix];        // per-wavefront digit counters, then bases
+    __shared__ u32 s_digit_start[kRadix];              // first local position of each digit
+    __shared__ u64 s_gofs[kRadix];                     // global offset minus local start
+    __shared__ u32 s_scan[kWaves];
+    __shared__ u64 s_keys[kSortTile];
+    __shared__ u32 s_vals[kSortTile];
+
+    const u64 D = load_D(header, capacity);
+    const u64 ntiles = (D + kSortTile - 1) / kSortTile;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u64 lane_lt = (1ull << lane) - 1ull;
+
+    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+#pragma unroll
+        for (u32 k = 0; k < kWaves; ++k) s_wave_hist[k][tid] = 0;
+        __syncthreads();
+
+        const u64 t0 = tile * kSortTile + (u64)wv * kPerWave;
+        u64 key[kSortItems];
+        u32 val[kSortItems];
+        u32 rank[kSortItems];
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u64 idx = t0 + (u64)j * kWave + lane;
+            const bool valid = idx < D;
+            key[j] = valid ? keys_in[idx] : ~0ull;
+            val[j] = valid ? vals_in[idx] : 0u;
+        }
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u64 idx = t0 + (u64)j * kWave + lane;
+            const bool valid = idx < D;
+            const u32 digit = (u32)(key[j] >> shift) & (kRadix - 1);
+            // lanes of this wavefront holding the same digit (match-any by ballots)
+            u64 peers = __ballot(valid);
+#pragma unroll
+            for (u32 b = 0; b < kRadixBits; ++b) {
+                const bool bit = (digit >> b) & 1u;
+                const u64 bal = __ballot(bit);
+                peers &= bit ? bal : ~bal;
+            }
+            const u32 before = __popcll(peers & lane_lt);
+            u32 old = 0;
+            if (valid && before == 0)                  // lowest peer lane adds for the group
+                old = atomicAdd(&s_wave_hist[wv][digit], (u32)__popcll(peers));
+            const int leader = valid ? (__ffsll((long long)peers) - 1) : (int)lane;
+            old = __shfl(old, leader, 64);
+            rank[j] = old + before;                    // position among this wavefront's equal digits
+        }
+        __syncthreads();
+
+        // digit totals of the tile, per-wavefront bases, local digit starts
+        {
+            u32 run = 0;
+#pragma unroll
+            for (u32 k = 0; k < kWaves; ++k) {
+                const u32 c = s_wave_hist[k][tid];
+                s_wave_hist[k][tid] = run;
+                run += c;
+            }
+            // exclusive scan of `run` over the 256 digits
+            u32 incl = run;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const u32 t = __shfl_up(incl, o, 64);
+                if ((int)lane >= o) incl += t;
+            }
+            if (lane == kWave - 1) s_scan[wv] = incl;
+            __syncthreads();
+            u32 wave_base = 0;
+#pragma unroll
+            for (u32 k = 0; k < kWaves; ++k) if (k < wv) wave_base += s_scan[k];
+            const u32 start = wave_base + incl - run;
+            s_digit_start[tid] = start;
+            s_gofs[tid] = table[(u64)tid * table_stride + tile] - (u64)start;
+        }
+        __syncthreads();
+
+        // sort the tile by digit in LDS
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u64 idx = t0 + (u64)j * kWave + lane;
+            if (idx < D) {
+                const u32 digit = (u32)(key[j] >> shift) & (kRadix - 1);
+                const u32 p = s_digit_start[digit] + s_wave_hist[wv][digit] + rank[j];
+                s_keys[p] = key[j];
+                s_vals[p] = val[j];
+            }
+        }
+        __syncthreads();
+
+        // contiguous runs out
+        const u64 tile_base = tile * kSortTile;
+        const u32 count = (u32)((D - tile_base) < (u64)kSortTile ? (D - tile_base) : (u64)kSortTile);
+        for (u32 p = tid; p < count; p += kSortThreads) {
+            const u64 k = s_keys[p];
+            const u32 digit = (u32)(k >> shift) & (kRadix - 1);
+            const u64 pos = s_gofs[digit] + p;
+            keys_out[pos] = k;
+            vals_out[pos] = s_vals[p];
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------- ranges
+__global__ __launch_bounds__(256) void tile_ranges_kernel(
+    const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
+    u32 num_tiles, u64 *__restrict__ tile_offsets, u64 *__restrict__ offsets_if_empty)
+{
+    // with no primitives the emit kernel never runs: the one-entry prefix sum is written here
+    if (offsets_if_empty && blockIdx.x == 0 && threadIdx.x == 0) offsets_if_empty[0] = 0;
+    const u64 D = load_D(header, capacity);
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    const u64 first = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    if (D == 0) {
+        for (u64 t = first; t <= num_tiles; t += stride) tile_offsets[t] = 0;
+        return;
+    }
+    for (u64 i = first; i < D; i += stride) {
+        u64 t = keys[i] >> 32;
+        if (t > num_tiles) t = num_tiles;
+        u64 tp;     // tiles in (tp, t] start at i
+        if (i == 0) {
+            for (u64 k = 0; k <= t; ++k) tile_offsets[k] = 0;
+        } else {
+            tp = keys[i - 1] >> 32;
+            if (tp > num_tiles) tp = num_tiles;
+            for (u64 k = tp + 1; k <= t; ++k) tile_offsets[k] = i;
+        }
+        if (i == D - 1)
+            for (u64 k = t + 1; k <= num_tiles; ++k) tile_offsets[k] = D;
+    }
+}
+
+// ---------------------------------------------------------------- launcher
+static inline u32 grid_for(u64 work_items, u32 cap)
+{
+    if (work_items < 1) work_items = 1;
+    return (u32)(work_items < (u64)cap ? work_items : (u64)cap);
+}
+
+hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams &pp, const lmk_gs_binned &out,
+                           char *scratch, const ScratchLayout &L, hipStream_t stream)
+{
+    ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
+    u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
+    u64 *digit_totals = reinterpret_cast<u64 *>(scratch + L.digit_totals);
+    u64 *table = reinterpret_cast<u64 *>(scratch + L.table);
+    const u32 num_tiles = pp.tiles_x * pp.tiles_y;
+    const u32 passes = sort_passes(num_tiles);
+
+    // ping-pong so that the last pass lands in keys/vals
+    u64 *kin = (passes & 1u) ? out.keys_alt : out.keys;
+    u32 *vin = (passes & 1u) ? out.vals_alt : out.vals;
+    u64 *kout = (passes & 1u) ? out.keys : out.keys_alt;
+    u32 *vout = (passes & 1u) ? out.vals : out.vals_alt;
+
+    if (L.pre_blocks > 0) {
+        hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                           proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
+                           block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header, digit_totals);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+
+    // enough resident workgroups to fill 256 CUs several times over; each loops over sort tiles
+    const u32 grid = grid_for(L.sort_tiles, 256u * 16u);
+    for (u32 p = 0; p < passes; ++p) {
+        const u32 shift = p * kRadixBits;
+        u64 *totals = digit_totals + (size_t)p * kRadix;
+        hipLaunchKernelGGL(radix_hist_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
+                           kin, header, out.capacity, shift, table, L.sort_tiles, totals);
+        hipLaunchKernelGGL(radix_scan_kernel, dim3(kRadix), dim3(kSortThreads), 0, stream,
+                           header, out.capacity, table, L.sort_tiles, totals);
+        hipLaunchKernelGGL(radix_scatter_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
+                           kin, vin, kout, vout, header, out.capacity, shift, table, L.sort_tiles);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        u64 *tk = kin; kin = kout; kout = tk;
+        u32 *tv = vin; vin = vout; vout = tv;
+    }
+    // after the swap `kin` is the sorted buffer == out.keys
+    const u32 rgrid = grid_for((out.capacity + 255) / 256, 256u * 16u);
+    hipLaunchKernelGGL(tile_ranges_kernel, dim3(rgrid), dim3(256), 0, stream,
+                       out.keys, header, out.capacity, num_tiles, out.tile_offsets,
+                       n == 0 ? proj.offsets : nullptr);
+    return hipGetLastError();
+}
+
+}  // namespace lmk

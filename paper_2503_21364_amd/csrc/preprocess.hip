@@ -1,0 +1,255 @@
+// Stage 1: per-primitive projection, culling, support rectangle and SH colour
+// (Sec. 2.2 Eq. 8, the EWA projection and SH colour of Sec. 2.2; the
+// per-primitive kernel named in Sec. 4.2.1), plus the prefix sum over
+// workgroup tile counts that fixes the pair count D.
+//
+// This translation unit is compiled with -ffp-contract=off and correctly
+// rounded fp32 divide/sqrt: everything that decides an integer (depth bits,
+// rectangle, culls) is evaluated one IEEE fp32 operation at a time in the
+// written order, so those outputs are unique.
+//
+// HBM-bound: one thread per primitive, every load/store is a plane access
+// that is contiguous across the wavefront.  The SH planes (192 of the 240
+// bytes a visible primitive needs) are read only by lanes that survive the
+// culls.
+#include "lmk_gs_internal.h"
+
+#include <cmath>
+
+namespace lmk {
+
+struct ShConsts { float k0, k1, k2, k20, k33, k32, k31, k30, k32b; };
+
+static ShConsts make_sh_consts()
+{
+    const double pi = 3.14159265358979323846;
+    ShConsts k;
+    k.k0 = (float)(0.5 * std::sqrt(1.0 / pi));
+    k.k1 = (float)std::sqrt(3.0 / (4.0 * pi));
+    k.k2 = (float)(0.5 * std::sqrt(15.0 / pi));
+    k.k20 = (float)(0.25 * std::sqrt(5.0 / pi));
+    k.k33 = (float)(0.25 * std::sqrt(35.0 / (2.0 * pi)));
+    k.k32 = (float)(0.5 * std::sqrt(105.0 / pi));
+    k.k31 = (float)(0.25 * std::sqrt(21.0 / (2.0 * pi)));
+    k.k30 = (float)(0.25 * std::sqrt(7.0 / pi));
+    k.k32b = (float)(0.25 * std::sqrt(105.0 / pi));
+    return k;
+}
+
+__device__ __forceinline__ float clamp_nan_lo(float v, float lo, float hi)
+{
+    return !(v > lo) ? lo : (v > hi ? hi : v);
+}
+
+__device__ __forceinline__ u32 wave_sum(u32 v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;   // valid in lane 0
+}
+
+__global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
+    const float *__restrict__ mean, const float *__restrict__ scale, const float *__restrict__ rot,
+    const float *__restrict__ opacity, const float *__restrict__ sh, u32 n, u32 sh_degree,
+    ProjParams pp, ShConsts kc,
+    float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
+    float4 *__restrict__ feat, u32 *__restrict__ block_sums)
+{
+    __shared__ u32 s_part[kPreBlock / kWave];
+    const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
+    const size_t N = n;
+    u32 cnt = 0;
+
+    if (i < n) {
+        const float *V = pp.cam.view;
+        const float mx = mean[i], my = mean[N + i], mz = mean[2 * N + i];
+        const float px = V[0] * mx + V[1] * my + V[2] * mz + V[3];
+        const float py = V[4] * mx + V[5] * my + V[6] * mz + V[7];
+        const float pz = V[8] * mx + V[9] * my + V[10] * mz + V[11];
+        if (pz > pp.cam.near_z) {
+            // Sigma = (R S)(R S)^T from the normalised quaternion
+            const float qw0 = rot[i], qx0 = rot[N + i], qy0 = rot[2 * N + i], qz0 = rot[3 * N + i];
+            const float qn = sqrtf(qw0 * qw0 + qx0 * qx0 + qy0 * qy0 + qz0 * qz0);
+            const float w = qw0 / qn, x = qx0 / qn, y = qy0 / qn, z = qz0 / qn;
+            const float s0 = scale[i], s1 = scale[N + i], s2 = scale[2 * N + i];
+            const float M00 = (1.0f - 2.0f * (y * y + z * z)) * s0;
+            const float M01 = (2.0f * (x * y - w * z)) * s1;
+            const float M02 = (2.0f * (x * z + w * y)) * s2;
+            const float M10 = (2.0f * (x * y + w * z)) * s0;
+            const float M11 = (1.0f - 2.0f * (x * x + z * z)) * s1;
+            const float M12 = (2.0f * (y * z - w * x)) * s2;
+            const float M20 = (2.0f * (x * z - w * y)) * s0;
+            const float M21 = (2.0f * (y * z + w * x)) * s1;
+            const float M22 = (1.0f - 2.0f * (x * x + y * y)) * s2;
+            const float S00 = M00 * M00 + M01 * M01 + M02 * M02;
+            const float S01 = M00 * M10 + M01 * M11 + M02 * M12;
+            const float S02 = M00 * M20 + M01 * M21 + M02 * M22;
+            const float S11 = M10 * M10 + M11 * M11 + M12 * M12;
+            const float S12 = M10 * M20 + M11 * M21 + M12 * M22;
+            const float S22 = M20 * M20 + M21 * M21 + M22 * M22;
+
+            // EWA: Jacobian of the pinhole map at the guard-band clamped mean, times W
+            const float txz = clamp_nan_lo(px / pz, -pp.lim_x, pp.lim_x) * pz;
+            const float tyz = clamp_nan_lo(py / pz, -pp.lim_y, pp.lim_y) * pz;
+            const float J00 = pp.cam.fx / pz, J02 = -(pp.cam.fx * txz) / (pz * pz);
+            const float J11 = pp.cam.fy / pz, J12 = -(pp.cam.fy * tyz) / (pz * pz);
+            // the zero entries of J are kept as written products so that every
+            // sum has the same terms (and zero signs) as the plain 2x3 * 3x3 product
+            const float T00 = J00 * V[0] + 0.0f * V[4] + J02 * V[8];
+            const float T01 = J00 * V[1] + 0.0f * V[5] + J02 * V[9];
+            const float T02 = J00 * V[2] + 0.0f * V[6] + J02 * V[10];
+            const float T10 = 0.0f * V[0] + J11 * V[4] + J12 * V[8];
+            const float T11 = 0.0f * V[1] + J11 * V[5] + J12 * V[9];
+            const float T12 = 0.0f * V[2] + J11 * V[6] + J12 * V[10];
+            const float U00 = T00 * S00 + T01 * S01 + T02 * S02;
+            const float U01 = T00 * S01 + T01 * S11 + T02 * S12;
+            const float U02 = T00 * S02 + T01 * S12 + T02 * S22;
+            const float U10 = T10 * S00 + T11 * S01 + T12 * S02;
+            const float U11 = T10 * S01 + T11 * S11 + T12 * S12;
+            const float U12 = T10 * S02 + T11 * S12 + T12 * S22;
+            const float a = (U00 * T00 + U01 * T01 + U02 * T02) + pp.cam.lowpass;
+            const float b = U00 * T10 + U01 * T11 + U02 * T12;
+            const float c = (U10 * T10 + U11 * T11 + U12 * T12) + pp.cam.lowpass;
+
+            const float det = a * c - b * b;
+            const float o = opacity[i];
+            if (det > 0.0f && !(o < 1.0f / 255.0f)) {
+                const float cA = c / det, cB = -b / det, cC = a / det;
+                const float u = (pp.cam.fx * px) / pz + pp.cam.cx;
+                const float v = (pp.cam.fy * py) / pz + pp.cam.cy;
+                const float hx = sqrtf(11.09f * a);
+                const float hy = sqrtf(11.09f * c);
+                const float TS = (float)LMK_GS_TILE;
+                const float fTX = (float)pp.tiles_x, fTY = (float)pp.tiles_y;
+                const u32 x0 = (u32)clamp_nan_lo(floorf((u - hx) / TS), 0.0f, fTX);
+                const u32 x1 = (u32)clamp_nan_lo(floorf((u + hx) / TS) + 1.0f, 0.0f, fTX);
+                const u32 y0 = (u32)clamp_nan_lo(floorf((v - hy) / TS), 0.0f, fTY);
+                const u32 y1 = (u32)clamp_nan_lo(floorf((v + hy) / TS) + 1.0f, 0.0f, fTY);
+                cnt = (x1 > x0 && y1 > y0) ? (x1 - x0) * (y1 - y0) : 0u;
+                if (cnt) {
+                    // view-dependent colour: 0.5 + sum_k Y_k(dir) sh_k, clamped at 0
+                    float dx = mx - pp.cam.cam_pos[0], dy = my - pp.cam.cam_pos[1], dz = mz - pp.cam.cam_pos[2];
+                    const float inv = 1.0f / sqrtf(dx * dx + dy * dy + dz * dz);
+                    dx *= inv; dy *= inv; dz *= inv;
+                    const float *c0 = sh + i;      // plane (k*3 + ch) starts at c0 + (k*3+ch)*N
+                    float Y[16];
+                    Y[0] = kc.k0;
+                    u32 ncoef = 1;
+                    if (sh_degree > 0) {
+                        Y[1] = -kc.k1 * dy; Y[2] = kc.k1 * dz; Y[3] = -kc.k1 * dx;
+                        ncoef = 4;
+                    }
+                    const float xx = dx * dx, yy = dy * dy, zz = dz * dz;
+                    if (sh_degree > 1) {
+                        Y[4] = kc.k2 * dx * dy; Y[5] = -kc.k2 * dy * dz;
+                        Y[6] = kc.k20 * (2.0f * zz - xx - yy);
+                        Y[7] = -kc.k2 * dx * dz; Y[8] = 0.5f * kc.k2 * (xx - yy);
+                        ncoef = 9;
+                    }
+                    if (sh_degree > 2) {
+                        Y[9] = -kc.k33 * dy * (3.0f * xx - yy);
+                        Y[10] = kc.k32 * dx * dy * dz;
+                        Y[11] = -kc.k31 * dy * (4.0f * zz - xx - yy);
+                        Y[12] = kc.k30 * dz * (2.0f * zz - 3.0f * xx - 3.0f * yy);
+                        Y[13] = -kc.k31 * dx * (4.0f * zz - xx - yy);
+                        Y[14] = kc.k32b * dz * (xx - yy);
+                        Y[15] = -kc.k33 * dx * (xx - 3.0f * yy);
+                        ncoef = 16;
+                    }
+                    float r = 0.5f, g = 0.5f, bl = 0.5f;
+#pragma unroll
+                    for (u32 k = 0; k < 16; ++k) {
+                        if (k < ncoef) {
+                            r += Y[k] * c0[(size_t)(3 * k + 0) * N];
+                            g += Y[k] * c0[(size_t)(3 * k + 1) * N];
+                            bl += Y[k] * c0[(size_t)(3 * k + 2) * N];
+                        }
+                    }
+                    r = fmaxf(r, 0.0f); g = fmaxf(g, 0.0f); bl = fmaxf(bl, 0.0f);
+
+                    depth[i] = pz;
+                    rect[i] = make_ushort4((unsigned short)x0, (unsigned short)y0,
+                                           (unsigned short)x1, (unsigned short)y1);
+                    float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
+                    f[0] = make_float4(u, v, cA, cB);
+                    f[1] = make_float4(cC, o, r, g);
+                    f[2] = make_float4(bl, 0.0f, 0.0f, 0.0f);
+                }
+            }
+        }
+        tiles_touched[i] = cnt;
+    }
+
+    // tile count of this workgroup (input of the prefix sum that places its pairs)
+    const u32 ws = wave_sum(cnt);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = ws;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 t = 0;
+#pragma unroll
+        for (u32 k = 0; k < kPreBlock / kWave; ++k) t += s_part[k];
+        block_sums[blockIdx.x] = t;
+    }
+}
+
+// Exclusive prefix sum (u64) over the workgroup tile counts; one workgroup.
+// Also publishes D and clears the status word.
+constexpr u32 kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void scan_block_sums_kernel(
+    const u32 *__restrict__ block_sums, u32 nb, u64 *__restrict__ block_offsets,
+    ScratchHeader *__restrict__ header)
+{
+    __shared__ u64 s_wave[kScanThreads / kWave];
+    __shared__ u64 s_carry;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (u32 base = 0; base < nb; base += kScanThreads) {
+        const u32 idx = base + tid;
+        const u64 v = idx < nb ? (u64)block_sums[idx] : 0;
+        u64 incl = v;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const u64 t = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += t;
+        }
+        if (lane == kWave - 1) s_wave[wv] = incl;
+        __syncthreads();
+        u64 wave_base = 0;
+        for (u32 k = 0; k < wv; ++k) wave_base += s_wave[k];
+        const u64 carry = s_carry;
+        if (idx < nb) block_offsets[idx] = carry + wave_base + incl - v;
+        __syncthreads();
+        if (tid == kScanThreads - 1) s_carry = carry + wave_base + incl;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        block_offsets[nb] = s_carry;
+        header->dup_count = s_carry;
+        header->status = LMK_GS_OK;
+        header->pad = 0;
+    }
+}
+
+hipError_t launch_preprocess(const lmk_gs_gaussians &g, const ProjParams &pp, const lmk_gs_projected &out,
+                             char *scratch, const ScratchLayout &L, hipStream_t stream)
+{
+    static const ShConsts kc = make_sh_consts();
+    u32 *block_sums = reinterpret_cast<u32 *>(scratch + L.block_sums);
+    u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
+    ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
+    if (L.pre_blocks > 0) {
+        hipLaunchKernelGGL(preprocess_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                           g.mean, g.scale, g.rot, g.opacity, g.sh, g.n, g.sh_degree, pp, kc,
+                           out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
+                           reinterpret_cast<float4 *>(out.feat), block_sums);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(1), dim3(kScanThreads), 0, stream,
+                       block_sums, L.pre_blocks, block_offsets, header);
+    return hipGetLastError();
+}
+
+}  // namespace lmk

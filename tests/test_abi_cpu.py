@@ -1,0 +1,166 @@
+"""No-GPU checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments on the host before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2503_21364_amd import binding as B
+from paper_2503_21364_amd import scenes
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in os.listdir(inc):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(lmk_gs_[a-z_0-9]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    declared = _declared_symbols()
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.lmk_gs_version() >= 100
+
+
+def test_struct_layouts_match_the_header():
+    # plain 4- and 8-byte fields in declaration order, no padding surprises
+    assert C.sizeof(B.Camera) == 4 * (12 + 3 + 4 + 3 + 2 + 3)
+    assert C.sizeof(B.Gaussians) == 5 * 8 + 2 * 4
+    assert C.sizeof(B.Projected) == 5 * 8
+    assert C.sizeof(B.Binned) == 6 * 8
+    assert B.Binned.capacity.offset == 32 and B.Binned.tile_offsets.offset == 40
+
+
+def test_strerror_covers_all_codes():
+    seen = {B.strerror(c) for c in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and "ok" in seen
+    assert B.strerror(-99) == "unknown error code"
+
+
+def test_workspace_bytes_grows_with_inputs_and_rejects_bad_sizes():
+    a = B.workspace_bytes(1000, 640, 480, 10_000)
+    b = B.workspace_bytes(100_000, 640, 480, 10_000)
+    c = B.workspace_bytes(100_000, 640, 480, 10_000_000)
+    assert 0 < a < b < c and a % 256 == 0
+    out = C.c_size_t(0)
+    assert B.lib().lmk_gs_workspace_bytes(10, 0, 480, 10, C.byref(out)) == B.ERR_INVALID
+    assert B.lib().lmk_gs_workspace_bytes(10, 640, 480, 10, None) == B.ERR_INVALID
+    assert B.lib().lmk_gs_workspace_bytes(10, 1 << 20, 480, 10, C.byref(out)) == B.ERR_UNSUPPORTED
+
+
+def _good_camera():
+    return B.make_camera(scenes.make_cameras(0)[0])
+
+
+def _fake(ptr=0x1000):
+    return C.c_void_p(ptr)
+
+
+def _args():
+    """Argument set that passes validation up to the pointer checks; pointers are
+    fake non-NULL values, so every test below must fail validation before launch."""
+    g = B.Gaussians(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 10, 3)
+    proj = B.Projected(0x1000, 0x1000, 0x1000, 0x1000, None)
+    binned = B.Binned(0x1000, 0x1000, 0x1000, 0x1000, 100, 0x1000)
+    return g, proj, binned
+
+
+def test_preprocess_rejects_bad_arguments_without_touching_the_gpu():
+    lib = B.lib()
+    g, proj, _ = _args()
+    cam = _good_camera()
+    scratch = C.c_void_p(0x10000)
+    call = lambda g_, c_, p_, s_=scratch, sb=1 << 20: lib.lmk_gs_preprocess(
+        None if g_ is None else C.byref(g_), None if c_ is None else C.byref(c_),
+        None if p_ is None else C.byref(p_), s_, sb, None)
+    assert call(None, cam, proj) == B.ERR_INVALID
+    assert call(g, None, proj) == B.ERR_INVALID
+    assert call(g, cam, None) == B.ERR_INVALID
+    assert call(g, cam, proj, None) == B.ERR_INVALID
+    assert call(g, cam, proj, C.c_void_p(0x10010)) == B.ERR_INVALID        # scratch not 256-aligned
+    assert call(g, cam, proj, scratch, 16) == B.ERR_CAPACITY                # scratch too small
+    bad = _good_camera(); bad.tile = 8
+    assert call(g, bad, proj) == B.ERR_UNSUPPORTED
+    bad = _good_camera(); bad.width = 0
+    assert call(g, bad, proj) == B.ERR_INVALID
+    bad = _good_camera(); bad.fx = float("nan")
+    assert call(g, bad, proj) == B.ERR_INVALID
+    bad = _good_camera(); bad.view[5] = float("inf")
+    assert call(g, bad, proj) == B.ERR_INVALID
+    bad = _good_camera(); bad.near_z = 0.0
+    assert call(g, bad, proj) == B.ERR_INVALID
+    g2, _, _ = _args(); g2.sh_degree = 4
+    assert call(g2, cam, proj) == B.ERR_INVALID
+    g2, _, _ = _args(); g2.sh = None
+    assert call(g2, cam, proj) == B.ERR_INVALID
+    p2 = B.Projected(0x1000, 0x1000, 0x1000, None, None)
+    assert call(g, cam, p2) == B.ERR_INVALID
+    p2 = B.Projected(0x1000, 0x1000, 0x1000, 0x1004, None)                 # feat not 16-byte aligned
+    assert call(g, cam, p2) == B.ERR_INVALID
+
+
+def test_bin_sort_and_render_reject_bad_arguments():
+    lib = B.lib()
+    _, proj, binned = _args()
+    cam = _good_camera()
+    scratch = C.c_void_p(0x10000)
+    need = B.workspace_bytes(10, cam.width, cam.height, 100)
+    bs = lambda p_, c_, b_, s_=scratch, sb=need: lib.lmk_gs_bin_sort(
+        None if p_ is None else C.byref(p_), 10, None if c_ is None else C.byref(c_),
+        None if b_ is None else C.byref(b_), s_, sb, None)
+    assert bs(None, cam, binned) == B.ERR_INVALID
+    assert bs(proj, None, binned) == B.ERR_INVALID
+    assert bs(proj, cam, None) == B.ERR_INVALID
+    assert bs(proj, cam, binned, None) == B.ERR_INVALID
+    assert bs(proj, cam, binned, scratch, need - 256) == B.ERR_CAPACITY
+    b2 = B.Binned(0x1000, 0x1000, None, 0x1000, 100, 0x1000)
+    assert bs(proj, cam, b2) == B.ERR_INVALID
+    b2 = B.Binned(0x1000, 0x1000, 0x1000, 0x1000, 100, None)
+    assert bs(proj, cam, b2) == B.ERR_INVALID
+    rd = lambda p_, b_, c_, o1=_fake(), o2=_fake(): lib.lmk_gs_render(
+        None if p_ is None else C.byref(p_), None if b_ is None else C.byref(b_),
+        None if c_ is None else C.byref(c_), o1, o2, None)
+    assert rd(None, binned, cam) == B.ERR_INVALID
+    assert rd(proj, None, cam) == B.ERR_INVALID
+    assert rd(proj, binned, None) == B.ERR_INVALID
+    assert rd(proj, binned, cam, None) == B.ERR_INVALID
+    assert rd(proj, binned, cam, _fake(), None) == B.ERR_INVALID
+    bad = _good_camera(); bad.tile = 32
+    assert rd(proj, binned, bad) == B.ERR_UNSUPPORTED
+    assert lib.lmk_gs_read_status(None, None, None, None) == B.ERR_INVALID
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()
+
+
+def test_scene_generator_shapes_and_determinism():
+    a = scenes.make_scene(2, n=1000)
+    b = scenes.make_scene(2, n=1000)
+    for k in ("mean", "scale", "rot", "opacity", "sh"):
+        assert a[k].dtype == np.float32 and np.array_equal(a[k], b[k])
+    assert a["sh"].shape == (16, 3, 1000) and a["rot"].shape == (4, 1000)
+    assert np.all(a["scale"] > 0) and np.all((a["opacity"] >= 0) & (a["opacity"] <= 1))
+    for cfg in range(5):
+        cams = scenes.make_cameras(cfg)
+        assert len(cams) == scenes.CONFIGS[cfg]["views"]
+        for c in cams:
+            R = c["view"].reshape(3, 4)[:, :3].astype(np.float64)
+            np.testing.assert_allclose(R @ R.T, np.eye(3), atol=1e-6)
+            assert np.linalg.det(R) > 0.999          # right-handed: x right, y down, z forward
+            np.testing.assert_allclose(R @ c["cam_pos"].astype(np.float64) + c["view"].reshape(3, 4)[:, 3],
+                                       0, atol=1e-3)

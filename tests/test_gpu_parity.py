@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs (bars in tests/parity.py)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2503_21364_amd import binding as B
+from paper_2503_21364_amd import scenes
+
+import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _report(name, stats):
+    print(f"[parity] {name}: " + ", ".join(f"{k}={v:.3e}" if isinstance(v, float) else f"{k}={v}"
+                                            for k, v in stats.items()), flush=True)
+
+
+# ------------------------------------------------------------------ configs
+def test_cfg0_full():
+    sc = scenes.make_scene(0)
+    cam = scenes.make_cameras(0)[0]
+    r = P.full_compare(sc, cam)
+    _report("cfg0", r.stats)
+    assert r.stats["D"] > 30000
+
+
+@pytest.mark.parametrize("w,h,n,seed,scale_mul", [
+    (37, 23, 1000, 71, 1.0),        # partial tiles on both edges
+    (200, 120, 4000, 21, 1.0),      # 13 x 8 tiles
+    (256, 256, 257, 5, 4.0),        # one primitive past a workgroup boundary, fat splats
+    (640, 360, 30011, 6, 2.0),      # several sort tiles with a ragged tail
+    (16, 16, 500, 8, 6.0),          # a single tile holding everything
+])
+def test_small_ragged(w, h, n, seed, scale_mul):
+    sc = scenes.make_scene(0, n=n, seed=seed)
+    sc["scale"] *= np.float32(scale_mul)
+    cam = scenes.make_cameras(0, w, h)[0]
+    cam["bg"] = np.array([0.25, 0.5, 0.125], np.float32)
+    r = P.full_compare(sc, cam)
+    _report(f"ragged {w}x{h} n={n}", r.stats)
+
+
+@pytest.mark.parametrize("view", [0, 5])
+def test_cfg1_full_size(view):
+    sc = scenes.make_scene(1)
+    cam = scenes.make_cameras(1)[view]
+    r = P.full_compare(sc, cam)
+    _report(f"cfg1 view {view}", r.stats)
+    assert r.stats["D"] > 3_000_000
+
+
+def test_cfg2_full_size_exterior_and_interior():
+    sc = scenes.make_scene(2)
+    dev = B.Scene(sc)
+    cams = scenes.make_cameras(2)
+    for view in (0, 5):
+        r = P.full_compare(sc, cams[view], scene_dev=dev)
+        _report(f"cfg2 view {view}", r.stats)
+        del r
+    torch.cuda.empty_cache()
+
+
+def test_cfg3_full_size_one_view():
+    sc = scenes.make_scene(3)
+    cam = scenes.make_cameras(3)[0]
+    r = P.full_compare(sc, cam)
+    _report("cfg3 view 0", r.stats)
+    assert r.stats["visible"] < 0.5 * sc["n"]       # most primitives are frustum-culled
+    del r
+    torch.cuda.empty_cache()
+
+
+def test_cfg4_distributions_reduced_count():
+    # the heavy-overlap distributions at 1/100 of the primitives and 1080p, so
+    # that the oracle can bin the whole frame (full size: test_gpu_large.py)
+    sc = scenes.make_scene(4, n=20_000)
+    cam = scenes.make_cameras(4, 1920, 1080)[0]
+    r = P.full_compare(sc, cam)
+    _report("cfg4 reduced", r.stats)
+    assert r.stats["D"] / r.stats["visible"] > 300   # hundreds of tiles per primitive
+
+
+# ------------------------------------------------------------------ degenerate inputs
+def test_empty_scene():
+    sc = scenes.make_scene(0, n=0)
+    cam = scenes.make_cameras(0, 64, 48)[0]
+    cam["bg"] = np.array([0.1, 0.2, 0.3], np.float32)
+    r = P.full_compare(sc, cam)
+    assert r.stats["D"] == 0
+    assert torch.all(r.gpu.out_T == 1.0)
+
+
+def test_everything_culled():
+    sc = scenes.make_scene(0, n=5000, seed=9)
+    eye = (0.0, 0.0, 4.0)
+    cam = scenes.make_camera(scenes.look_at(eye, (0, 0, 8.0), (0, 1, 0)), eye, 100, 60, 60.0, bg=(0.2, 0.4, 0.6))
+    r = P.full_compare(sc, cam)
+    assert r.stats["D"] == 0 and r.stats["visible"] == 0
+    np.testing.assert_array_equal(P.to_np(r.gpu.out_rgb[1]), np.float32(0.4))
+
+
+def test_single_primitive_covering_many_tiles():
+    sc = scenes.hand_placed_scene([(0.1, -0.2, 0.0)], [(0.8, 0.3, 0.5)], rot=(0.9, 0.1, 0.3, -0.2),
+                                  opacity=0.7, sh_dc=(1.0, 0.2, -0.4))
+    cam = scenes.make_cameras(0, 320, 200)[0]
+    r = P.full_compare(sc, cam)
+    assert r.stats["D"] > 100 and r.stats["visible"] == 1
+
+
+@pytest.mark.parametrize("deg", [0, 1, 2])
+def test_lower_sh_degrees(deg):
+    sc = scenes.make_scene(0, n=3000, seed=13)
+    sc["sh_degree"] = deg
+    cam = scenes.make_cameras(0, 128, 128)[0]
+    r = P.full_compare(sc, cam)
+    _report(f"sh degree {deg}", r.stats)
+
+
+def test_equal_depths_are_ordered_by_index():
+    # many primitives on one plane facing the camera: identical depth bits inside a tile
+    rng = np.random.default_rng(3)
+    n = 3000
+    mean = np.stack([rng.uniform(-1, 1, n), rng.uniform(-1, 1, n), np.zeros(n)], axis=1)
+    sc = scenes.hand_placed_scene(mean, [(0.05, 0.05, 0.05)], opacity=0.5,
+                                  sh_dc=rng.uniform(-1, 1, (n, 3)))
+    cam = scenes.make_cameras(0, 128, 128)[0]
+    r = P.full_compare(sc, cam)
+    keys = r.oracle.binned.keys
+    assert (keys[1:] == keys[:-1]).sum() > 1000
+
+
+def test_capacity_overflow_sets_status_and_stays_in_bounds():
+    sc = scenes.make_scene(0, n=5000, seed=17)
+    cam = scenes.make_cameras(0, 128, 128)[0]
+    ofr = ref.render_frame(sc, cam)
+    cap = ofr.binned.D // 2
+    fr = P.gpu_frame(B.Scene(sc), cam, cap)
+    D, status = B.read_status(fr)
+    assert D == ofr.binned.D and status == B.ERR_CAPACITY
+    # the truncated run sorted exactly the first `cap` emitted pairs
+    b = ref.bin_sort(ofr.pre, cam, keep_unsorted=True)
+    perm = np.argsort(b.keys_unsorted[:cap], kind="stable")
+    np.testing.assert_array_equal(P.to_np(fr.keys[:cap]).view(np.uint64), b.keys_unsorted[:cap][perm])
+    np.testing.assert_array_equal(P.to_np(fr.vals[:cap]).view(np.uint32), b.vals_unsorted[:cap][perm])
+    to = P.to_np(fr.tile_offsets).view(np.uint64)
+    assert to[-1] == cap and np.all(np.diff(to.astype(np.int64)) >= 0)
+
+
+# ------------------------------------------------------------------ stage isolation
+def _upload_projected(fr, pre):
+    n = pre.n
+    fr.depth[:n] = torch.from_numpy(pre.depth).cuda()
+    fr.tiles_touched[:n] = torch.from_numpy(pre.tiles_touched.view(np.int32)).cuda()
+    fr.rect[:n] = torch.from_numpy(pre.rect.view(np.int16)).cuda()
+    feat = np.zeros((n, B.FEAT_STRIDE), np.float32)
+    feat[:, 0:2] = pre.mean2d.T
+    feat[:, 2:5] = pre.conic.T
+    feat[:, 5] = pre.opacity
+    feat[:, 6:9] = pre.rgb.T.astype(np.float32)
+    fr.feat[:n] = torch.from_numpy(feat).cuda()
+
+
+def test_bin_sort_alone_from_oracle_projection():
+    sc = scenes.make_scene(0, n=20000, seed=23)
+    sc["scale"] *= np.float32(2.0)
+    cam = scenes.make_cameras(0, 300, 200)[0]
+    ofr = ref.render_frame(sc, cam)
+    dev = B.Scene(sc)
+    c = B.make_camera(cam)
+    fr = B.Frame(dev.n, 300, 200, ofr.binned.D + 7, want_offsets=True)
+    B.preprocess(dev, c, fr)          # fills the workgroup tile counts in scratch
+    _upload_projected(fr, ofr.pre)    # then the oracle's arrays replace the GPU's
+    B.bin_sort(c, fr)
+    torch.cuda.synchronize()
+    P.compare_binned(fr, ofr.binned)
+
+
+def test_render_alone_from_oracle_lists():
+    sc = scenes.make_scene(0, n=8000, seed=29)
+    sc["scale"] *= np.float32(2.5)
+    cam = scenes.make_cameras(0, 200, 136)[0]
+    cam["bg"] = np.array([0.5, 0.25, 0.75], np.float32)
+    ofr = ref.render_frame(sc, cam)
+    fr = B.Frame(sc["n"], 200, 136, ofr.binned.D + 1)
+    _upload_projected(fr, ofr.pre)
+    D = ofr.binned.D
+    fr.vals[:D] = torch.from_numpy(ofr.binned.vals.view(np.int32)).cuda()
+    fr.tile_offsets[:] = torch.from_numpy(ofr.binned.tile_offsets.view(np.int64)).cuda()
+    B.render(B.make_camera(cam), fr)
+    torch.cuda.synchronize()
+    st = P.compare_image(fr, ofr.img, cam)
+    _report("render alone", st)
+
+
+def test_two_runs_are_bytewise_identical():
+    sc = scenes.make_scene(1, n=100_000)
+    cam = scenes.make_cameras(1, 960, 540)[3]
+    dev = B.Scene(sc)
+    outs = []
+    for _ in range(2):
+        fr = P.gpu_frame(dev, cam, 2_000_000)
+        D, status = B.read_status(fr)
+        assert status == B.OK
+        outs.append((D, fr.keys[:D].clone(), fr.vals[:D].clone(), fr.tile_offsets.clone(),
+                     fr.out_rgb.clone(), fr.out_T.clone()))
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1:], outs[1][1:]):
+        assert torch.equal(a, b)
+
+
+def test_runs_on_a_side_stream():
+    sc = scenes.make_scene(0, n=5000, seed=31)
+    cam = scenes.make_cameras(0, 160, 96)[0]
+    ofr = ref.render_frame(sc, cam)
+    dev = B.Scene(sc)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    fr = B.Frame(dev.n, 160, 96, ofr.binned.D + 5)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        B.render_frame(dev, B.make_camera(cam), fr, stream=s)
+    s.synchronize()
+    P.compare_binned(fr, ofr.binned)
+    P.compare_image(fr, ofr.img, cam)
