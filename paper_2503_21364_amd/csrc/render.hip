@@ -1,14 +1,30 @@
 // Stage 3: per-tile front-to-back alpha compositing (Sec. 2.2 Eq. 9-10; the
 // blend kernel whose share of render time Sec. 4.2.1 reports).
 //
-// One workgroup of 256 threads (4 wavefronts) per 16x16 tile, one pixel per
-// lane; wavefront w owns rows 4w..4w+3 of the tile.  The tile's sorted list is
-// consumed in batches of 256 entries: each thread fetches one entry's feature
-// record (48 bytes, three 16-byte loads) and stages it in LDS with the conic
-// pre-multiplied by -0.5*log2(e), so the inner loop is a handful of FMAs and
-// one v_exp_f32 per (pixel, entry).  A wavefront whose 64 pixels have all
-// stopped skips the rest of a batch; the tile leaves when all four have.
-// Bound by FP32 VALU issue; LDS reads are wavefront-wide broadcasts.
+// One workgroup (4 wavefronts) per 16x16 tile; each wavefront owns a compact
+// 8x8 pixel block, one pixel per lane.  The tile's sorted list is consumed in
+// batches of 256 entries staged in LDS (each thread fetches one 48-byte feature
+// record; the next batch's records are already in flight while the current
+// batch is composited -- the software pipelining of Sec. 4.2.1).
+//
+// Per batch a wavefront works in two phases:
+//  1. lane = entry.  64 entries at a time are tested against the wavefront's
+//     pixel block: the maximum of the splat's exponent over the (continuous)
+//     block is found in closed form -- the exponent is a concave quadratic, so
+//     the maximum sits at the centre if that is inside, else on an edge facing
+//     it -- and compared with the entry's threshold -log2(255 opacity), below
+//     which alpha < 1/255 everywhere in the block.  This is the exact
+//     splat/block intersection ("intersection operations for each tile",
+//     Sec. 4.2.1) at 8x8 granularity, costing well under one vector instruction
+//     per entry; LDS is read lane-distinct, not broadcast.
+//  2. lane = pixel.  Only the surviving entries (a 64-bit ballot, walked in
+//     order with scalar bit scans) are evaluated per pixel: two LDS broadcasts,
+//     seven FP32 operations for the exponent, v_exp_f32, the alpha test and the
+//     compositing update under the lane mask.
+// A wavefront whose 64 pixels have all stopped skips the rest (per-wavefront
+// progress, Sec. 4.2.1); the tile leaves when all four have.  Bound by FP32
+// VALU issue and LDS broadcast bandwidth; HBM traffic is the 52 bytes per list
+// entry of the gather.
 #include "lmk_gs_internal.h"
 
 namespace lmk {
@@ -22,61 +38,124 @@ struct BlendParams {
     float bg0, bg1, bg2;
 };
 
+struct Rec { float4 a, b, c; };
+
+__device__ __forceinline__ Rec fetch_record(const u32 *__restrict__ vals, const float4 *__restrict__ feat,
+                                            u64 pos, bool valid)
+{
+    Rec r;
+    if (valid) {
+        const u32 g = vals[pos];
+        const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
+        r.a = f[0]; r.b = f[1]; r.c = f[2];
+    } else {
+        r.a = r.b = r.c = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    return r;
+}
+
+__device__ __forceinline__ float clamp_pm(float v, float h) { return __builtin_amdgcn_fmed3f(v, -h, h); }
+
 __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const u64 *__restrict__ tile_offsets, const u32 *__restrict__ vals,
     const float4 *__restrict__ feat, BlendParams bp,
     float *__restrict__ out_rgb, float *__restrict__ out_T)
 {
-    __shared__ float4 s_geo[kBatch];    // u, v, A', B'   (A' = -0.5*log2e*A, B' = -log2e*B)
-    __shared__ float4 s_col[kBatch];    // C', opacity, r, g
-    __shared__ float s_blue[kBatch];
+    // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C: log2 of the falloff is
+    // A' dx^2 + B' dx dy + C' dy^2.  (du, dv) = splat centre relative to the centre of block 0.
+    __shared__ float4 s_geo[kBatch];    // du, dv, A', B'
+    __shared__ float4 s_cop[kBatch];    // C', opacity, r, g
+    __shared__ float4 s_tst[kBatch];    // threshold, -B'/(2A'), -B'/(2C'), b
 
     // consecutive workgroup ids land on different XCDs; give each XCD one
     // contiguous band of tiles so neighbouring tiles share that XCD's L2
     const u32 tile = (blockIdx.x % kXcds) * bp.tiles_per_xcd + blockIdx.x / kXcds;
     if (blockIdx.x / kXcds >= bp.tiles_per_xcd || tile >= bp.num_tiles) return;
 
-    const u32 tid = threadIdx.x;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 tx = tile % bp.tiles_x, ty = tile / bp.tiles_x;
-    const u32 pxi = tx * LMK_GS_TILE + (tid & 15u), pyi = ty * LMK_GS_TILE + (tid >> 4);
+    const u32 li = (wv & 1u) * 8u + (lane & 7u), lj = (wv >> 1) * 8u + (lane >> 3);
+    const u32 pxi = tx * LMK_GS_TILE + li, pyi = ty * LMK_GS_TILE + lj;
     const bool inside = pxi < bp.width && pyi < bp.height;
-    const float px = (float)pxi + 0.5f, py = (float)pyi + 0.5f;
+    // this wavefront's block centre relative to block 0's, and this lane's pixel centre
+    // relative to its block centre
+    const float bx = (float)((wv & 1u) * 8u), by = (float)((wv >> 1) * 8u);
+    const float fi = (float)(lane & 7u) - 3.5f, fj = (float)(lane >> 3) - 3.5f;
+    const float X0 = (float)(tx * LMK_GS_TILE) + 4.0f, Y0 = (float)(ty * LMK_GS_TILE) + 4.0f;
+    const float kHalf = 3.5f;           // pixel centres of a block span [-3.5, 3.5]^2 about its centre
 
     const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
     float T = 1.0f, cr = 0.0f, cg = 0.0f, cb = 0.0f;
     bool done = !inside;
+    u64 live = __builtin_amdgcn_ballot_w64(inside);     // pixels of this wavefront still walking
     const float kL2E = 1.4426950408889634f;
+    const float kMargin = 1.5e-4f;      // block test passes alpha down to 0.99990 / 255
+    const float kRelMargin = -2e-6f;    // times (A' ex^2 + C' ey^2) <= 0: covers fp32 rounding of the test
+
+    Rec next = fetch_record(vals, feat, start + tid, start + tid < end);
 
     for (u64 base = start; base < end; base += kBatch) {
-        if (__syncthreads_and(done)) break;
+        if (__syncthreads_and(done)) break;        // also: everyone is past the previous batch
         const u32 cnt = (u32)((end - base) < (u64)kBatch ? (end - base) : (u64)kBatch);
-        if (tid < cnt) {
-            const u32 g = vals[base + tid];
-            const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
-            const float4 f0 = f[0], f1 = f[1], f2 = f[2];
-            s_geo[tid] = make_float4(f0.x, f0.y, -0.5f * kL2E * f0.z, -kL2E * f0.w);
-            s_col[tid] = make_float4(-0.5f * kL2E * f1.x, f1.y, f1.z, f1.w);
-            s_blue[tid] = f2.x;
+        {
+            // every thread stages one slot; slots past the end of the list can never pass a test
+            const bool valid = tid < cnt;
+            const float A = -0.5f * kL2E * next.a.z, Bq = -kL2E * next.a.w, Cq = -0.5f * kL2E * next.b.x;
+            const float o = next.b.y;
+            s_geo[tid] = make_float4(next.a.x - X0, next.a.y - Y0, A, Bq);
+            s_cop[tid] = make_float4(Cq, o, next.b.z, next.b.w);
+            s_tst[tid] = make_float4(valid ? -__log2f(255.0f * o) - kMargin : __builtin_inff(),
+                                     valid ? -Bq / (2.0f * A) : 0.0f, valid ? -Bq / (2.0f * Cq) : 0.0f,
+                                     next.c.x);
         }
         __syncthreads();
-        for (u32 j = 0; j < cnt; ++j) {
-            // wavefront-wide vote at a uniform point: leave the batch once all 64 pixels stopped
-            if (__ballot(!done) == 0ull) break;
-            const float4 ge = s_geo[j];
-            const float4 co = s_col[j];
-            const float dx = ge.x - px, dy = ge.y - py;
-            // log2 of the Gaussian falloff: A' dx^2 + B' dx dy + C' dy^2  (<= 0 up to rounding)
-            float p = dx * (ge.z * dx + ge.w * dy) + co.x * dy * dy;
-            p = fminf(p, 0.0f);
-            const float alpha = fminf(0.99f, co.y * __builtin_amdgcn_exp2f(p));
-            const float Tn = T * (1.0f - alpha);
-            const bool hit = !done && !(alpha < 1.0f / 255.0f);
-            const bool stop = hit && Tn < 1e-4f;
-            done = done || stop;
-            if (hit && !stop) {
-                const float w = alpha * T;
-                cr += co.z * w; cg += co.w * w; cb += s_blue[j] * w;
-                T = Tn;
+        {
+            const u64 npos = base + kBatch + tid;
+            next = fetch_record(vals, feat, npos, npos < end);    // in flight during the loops below
+        }
+        for (u32 c0 = 0; c0 < cnt && live != 0ull; c0 += kWave) {
+            // ---- phase 1: lane = entry; does the splat reach this wavefront's block at all?
+            u64 mask;
+            {
+                const float4 g = s_geo[c0 + lane];
+                const float4 t = s_tst[c0 + lane];
+                const float Cq = s_cop[c0 + lane].x;
+                const float xs = g.x - bx, ys = g.y - by;          // splat centre in block coordinates
+                // candidate 1: x clamped into the block, best y on that vertical line
+                const float ex1 = clamp_pm(xs, kHalf) - xs;
+                const float ey1 = clamp_pm(fmaf(t.z, ex1, ys), kHalf) - ys;
+                const float m1 = fmaf(g.z * ex1, ex1, Cq * ey1 * ey1);
+                const float p1 = fmaf(g.w * ex1, ey1, m1);
+                // candidate 2: y clamped, best x on that horizontal line
+                const float ey2 = clamp_pm(ys, kHalf) - ys;
+                const float ex2 = clamp_pm(fmaf(t.y, ey2, xs), kHalf) - xs;
+                const float m2 = fmaf(g.z * ex2, ex2, Cq * ey2 * ey2);
+                const float p2 = fmaf(g.w * ex2, ey2, m2);
+                const float best = fmaxf(fmaf(m1, kRelMargin, p1), fmaf(m2, kRelMargin, p2));
+                mask = __builtin_amdgcn_ballot_w64(best >= t.x);
+            }
+            // ---- phase 2: lane = pixel; composite the survivors in list order
+            while (mask != 0ull && live != 0ull) {
+                const u32 j = c0 + (u32)__builtin_ctzll(mask);
+                mask &= mask - 1ull;
+                const float4 g = s_geo[j];
+                const float4 co = s_cop[j];
+                const float dx = (g.x - bx) - fi, dy = (g.y - by) - fj;
+                const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), co.x * dy * dy);
+                const float alpha = fminf(0.99f, co.y * __builtin_amdgcn_exp2f(p));
+                const bool hit = !done && !(alpha < 1.0f / 255.0f);
+                if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+                    const float blue = s_tst[j].w;
+                    const float Tn = fmaf(-T, alpha, T);
+                    const bool stop = hit && Tn < 1e-4f;
+                    done = done || stop;
+                    if (hit && !stop) {
+                        const float w = alpha * T;
+                        cr = fmaf(co.z, w, cr); cg = fmaf(co.w, w, cg); cb = fmaf(blue, w, cb);
+                        T = Tn;
+                    }
+                    live &= ~__builtin_amdgcn_ballot_w64(stop);
+                }
             }
         }
     }
