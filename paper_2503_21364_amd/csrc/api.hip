@@ -86,7 +86,7 @@ int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
     if (!aligned(scratch, 256)) return LMK_GS_ERR_INVALID;
     // the part of the scratch this call touches does not depend on the pair capacity
     const ScratchLayout L = scratch_layout(g->n, 0);
-    if (scratch_bytes < L.table) return LMK_GS_ERR_CAPACITY;
+    if (scratch_bytes < L.digit_totals) return LMK_GS_ERR_CAPACITY;
     const hipError_t e = launch_preprocess(*g, pp, *out, static_cast<char *>(scratch), L,
                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);

@@ -11,12 +11,17 @@
 //            workgroup's output slots are dealt round-robin to its threads and
 //            each slot finds its primitive by binary search in an LDS prefix
 //            array, so stores are contiguous whatever the rectangle sizes are.
-//   sort     8-bit digits, least significant first.  Per pass: (1) digit
-//            histogram of every 4096-pair sort tile, (2) prefix sums giving each
-//            (digit, sort tile) its output offset, (3) scatter: wavefront
-//            match-any ranking (ballots over the digit bits) keeps the order of
-//            equal digits, the tile is sorted by digit in LDS and written out in
-//            contiguous runs.
+//   sort     stable LSD radix sort, digits of up to 9 bits (5 passes at 1080p).
+//            One up-front kernel reads the keys once and builds the global digit
+//            histogram of every pass (so every pass knows where each digit's
+//            output starts).  Per pass: (1) digit counts of every 4096-pair sort
+//            tile, (2) one workgroup per digit turns its row of counts into
+//            output offsets, (3) scatter: wavefront match-any ranking (ballots
+//            over the digit bits) keeps equal digits in order, the tile is
+//            sorted by digit in LDS and written out in contiguous runs.
+//            (A single-kernel pass with a chained scan over tiles was measured
+//            slower here: with 512 counters per tile the look-back chain costs
+//            more than the two extra small kernels.)
 //   ranges   tile_offsets[t] = first sorted position whose tile id is >= t.
 #include "lmk_gs_internal.h"
 
@@ -33,7 +38,7 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
     const float *__restrict__ depth, const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
-    ScratchHeader *__restrict__ header, u64 *__restrict__ digit_totals)
+    ScratchHeader *__restrict__ header)
 {
     __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of tiles_touched inside the workgroup
     __shared__ ushort4 s_rect[kPreBlock];
@@ -69,11 +74,7 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
         if (i < n) offsets[i] = base + excl;
         if (i == n - 1) offsets[n] = base + total;
     }
-    if (blockIdx.x == 0) {
-        // the sort's global digit histograms start from zero every frame
-        for (u32 k = tid; k < kMaxPasses * kRadix; k += kPreBlock) digit_totals[k] = 0;
-        if (tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
-    }
+    if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
     __syncthreads();
 
     for (u32 j = tid; j < total; j += kPreBlock) {
@@ -99,37 +100,99 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
 }
 
 // ---------------------------------------------------------------- radix sort
-// (1) per-sort-tile digit histogram -> table[digit][tile], and global digit totals
+// (0a) one read of the keys: digit histograms of every pass, one partial per workgroup
+constexpr u32 kPrehistUnroll = 8;
+
+__global__ __launch_bounds__(kSortThreads) void sort_prehist_kernel(
+    const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
+    SortPlan plan, u32 *__restrict__ partials, u64 *__restrict__ digit_totals)
+{
+    __shared__ u32 s_hist[kMaxPasses][kMaxRadix];
+    const u64 D = load_D(header, capacity);
+    const u32 tid = threadIdx.x;
+    for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kSortThreads) (&s_hist[0][0])[k] = 0;
+    if (blockIdx.x == 0)
+        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kSortThreads) digit_totals[k] = 0;
+    __syncthreads();
+    const u64 chunk = (u64)kSortThreads * kPrehistUnroll;
+    for (u64 base = (u64)blockIdx.x * chunk; base < D; base += (u64)gridDim.x * chunk) {
+        u64 k[kPrehistUnroll];
+#pragma unroll
+        for (u32 j = 0; j < kPrehistUnroll; ++j) {
+            const u64 i = base + (u64)j * kSortThreads + tid;
+            k[j] = i < D ? keys[i] : 0ull;
+        }
+#pragma unroll
+        for (u32 j = 0; j < kPrehistUnroll; ++j) {
+            const u64 i = base + (u64)j * kSortThreads + tid;
+            if (i < D) {
+#pragma unroll
+                for (u32 p = 0; p < kMaxPasses; ++p)
+                    if (p < plan.passes)
+                        atomicAdd(&s_hist[p][(u32)(k[j] >> plan.shift[p]) & ((1u << plan.bits[p]) - 1u)], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    u32 *out = partials + (size_t)blockIdx.x * kMaxPasses * kMaxRadix;
+    for (u32 k = tid; k < plan.passes * kMaxRadix; k += kSortThreads) out[k] = (&s_hist[0][0])[k];
+}
+
+// (0b) sums the partial histograms: workgroup (pass, slice) adds its slice of partials and
+// contributes one atomic per digit.
+constexpr u32 kReduceSlices = 32;
+
+__global__ __launch_bounds__(kMaxRadix) void sort_reduce_kernel(
+    const u32 *__restrict__ partials, u32 nblocks, u64 *__restrict__ digit_totals)
+{
+    const u32 d = threadIdx.x, pass = blockIdx.x / kReduceSlices, slice = blockIdx.x % kReduceSlices;
+    const u32 per = (nblocks + kReduceSlices - 1) / kReduceSlices;
+    const u32 b0 = slice * per, b1 = (b0 + per) < nblocks ? (b0 + per) : nblocks;
+    u64 total = 0;
+#pragma unroll 16
+    for (u32 b = b0; b < b1; ++b)
+        total += partials[((size_t)b * kMaxPasses + pass) * kMaxRadix + d];
+    if (total) atomicAdd(reinterpret_cast<unsigned long long *>(&digit_totals[(size_t)pass * kMaxRadix + d]),
+                         (unsigned long long)total);
+}
+
+// (1) digit counts of every sort tile of this pass -> table[digit][tile]
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
-    u32 shift, u64 *__restrict__ table, u64 table_stride, u64 *__restrict__ digit_totals)
+    u32 shift, u32 bits, u32 *__restrict__ table, u64 table_stride)
 {
-    __shared__ u32 s_hist[kRadix];
+    __shared__ u32 s_hist[kMaxRadix];
     const u64 D = load_D(header, capacity);
     const u64 ntiles = (D + kSortTile - 1) / kSortTile;
     const u32 tid = threadIdx.x;
+    const u32 dmask = (1u << bits) - 1u;
     for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        s_hist[tid] = 0;
+        s_hist[tid] = 0; s_hist[tid + kSortThreads] = 0;
         __syncthreads();
         const u64 t0 = tile * kSortTile;
+        u64 k[kSortItems];
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kSortThreads + tid;
-            if (idx < D) atomicAdd(&s_hist[(u32)(keys[idx] >> shift) & (kRadix - 1)], 1u);
+            k[j] = idx < D ? keys[idx] : 0ull;
+        }
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u64 idx = t0 + (u64)j * kSortThreads + tid;
+            if (idx < D) atomicAdd(&s_hist[(u32)(k[j] >> shift) & dmask], 1u);
         }
         __syncthreads();
-        const u32 c = s_hist[tid];
-        table[(u64)tid * table_stride + tile] = c;
-        if (c) atomicAdd(&digit_totals[tid], (u64)c);
+        table[(u64)tid * table_stride + tile] = s_hist[tid];
+        table[(u64)(tid + kSortThreads) * table_stride + tile] = s_hist[tid + kSortThreads];
         __syncthreads();
     }
 }
 
-// (2) one workgroup per digit: exclusive scan of its row of the table, offset by
-// the total of all smaller digits.
+// (2) one workgroup per digit: exclusive scan of its row of counts, offset by the total of
+// all smaller digits -> offsets[digit][tile] (u64)
 __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
-    const ScratchHeader *__restrict__ header, u64 capacity, u64 *__restrict__ table,
-    u64 table_stride, const u64 *__restrict__ digit_totals)
+    const ScratchHeader *__restrict__ header, u64 capacity, const u32 *__restrict__ table,
+    u64 *__restrict__ offsets, u64 table_stride, const u64 *__restrict__ digit_totals)
 {
     __shared__ u64 s_wave[kSortThreads / kWave];
     __shared__ u64 s_carry;
@@ -138,8 +201,10 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 digit = blockIdx.x;
 
-    // base = sum of totals of digits below mine
-    u64 part = tid < digit ? digit_totals[tid] : 0;
+    // base = total of the digits below mine
+    u64 part = 0;
+    if (tid < digit) part += digit_totals[tid];
+    if (tid + kSortThreads < digit) part += digit_totals[tid + kSortThreads];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
     if (lane == 0) s_wave[wv] = part;
@@ -151,10 +216,11 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
     }
     __syncthreads();
 
-    u64 *row = table + (u64)digit * table_stride;
+    const u32 *row = table + (u64)digit * table_stride;
+    u64 *orow = offsets + (u64)digit * table_stride;
     for (u64 base = 0; base < ntiles; base += kSortThreads) {
         const u64 idx = base + tid;
-        const u64 v = idx < ntiles ? row[idx] : 0;
+        const u64 v = idx < ntiles ? (u64)row[idx] : 0;
         u64 incl = v;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -167,7 +233,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
         u64 wave_base = 0;
         for (u32 k = 0; k < wv; ++k) wave_base += s_wave[k];
         const u64 carry = s_carry;
-        if (idx < ntiles) row[idx] = carry + wave_base + incl - v;
+        if (idx < ntiles) orow[idx] = carry + wave_base + incl - v;
         __syncthreads();
         if (tid == kSortThreads - 1) s_carry = carry + wave_base + incl;
         __syncthreads();
@@ -178,26 +244,25 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
     const u64 *__restrict__ keys_in, const u32 *__restrict__ vals_in,
     u64 *__restrict__ keys_out, u32 *__restrict__ vals_out,
-    const ScratchHeader *__restrict__ header, u64 capacity, u32 shift,
-    const u64 *__restrict__ table, u64 table_stride)
+    const ScratchHeader *__restrict__ header, u64 capacity, u32 shift, u32 bits,
+    const u64 *__restrict__ offsets, u64 table_stride)
 {
     constexpr u32 kWaves = kSortThreads / kWave;
     constexpr u32 kPerWave = kSortItems * kWave;       // 1024 consecutive pairs per wavefront
-    __shared__ u32 s_wave_hist[kWaves][kRadix];        // per-wavefront digit counters, then bases
-    __shared__ u32 s_digit_start[kRadix];              // first local position of each digit
-    __shared__ u64 s_gofs[kRadix];                     // global offset minus local start
+    __shared__ u32 s_wave_hist[kWaves][kMaxRadix];     // per-wavefront digit counters, then bases
+    __shared__ u32 s_digit_start[kMaxRadix];           // first local position of each digit
+    __shared__ u64 s_gofs[kMaxRadix];                  // global offset minus local start
     __shared__ u32 s_scan[kWaves];
-    __shared__ u64 s_keys[kSortTile];
-    __shared__ u32 s_vals[kSortTile];
+    __shared__ u64 s_stage[kSortTile];                 // keys, then (reused) values
 
     const u64 D = load_D(header, capacity);
     const u64 ntiles = (D + kSortTile - 1) / kSortTile;
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u64 lane_lt = (1ull << lane) - 1ull;
+    const u32 radix = 1u << bits, dmask = radix - 1u;
 
     for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-#pragma unroll
-        for (u32 k = 0; k < kWaves; ++k) s_wave_hist[k][tid] = 0;
+        for (u32 k = tid; k < kWaves * kMaxRadix; k += kSortThreads) (&s_wave_hist[0][0])[k] = 0;
         __syncthreads();
 
         const u64 t0 = tile * kSortTile + (u64)wv * kPerWave;
@@ -215,14 +280,16 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kWave + lane;
             const bool valid = idx < D;
-            const u32 digit = (u32)(key[j] >> shift) & (kRadix - 1);
+            const u32 digit = (u32)(key[j] >> shift) & dmask;
             // lanes of this wavefront holding the same digit (match-any by ballots)
-            u64 peers = __ballot(valid);
+            u64 peers = __builtin_amdgcn_ballot_w64(valid);
 #pragma unroll
-            for (u32 b = 0; b < kRadixBits; ++b) {
-                const bool bit = (digit >> b) & 1u;
-                const u64 bal = __ballot(bit);
-                peers &= bit ? bal : ~bal;
+            for (u32 b = 0; b < kMaxRadixBits; ++b) {
+                if (b < bits) {
+                    const bool bit = (digit >> b) & 1u;
+                    const u64 bal = __builtin_amdgcn_ballot_w64(bit);
+                    peers &= bit ? bal : ~bal;
+                }
             }
             const u32 before = __popcll(peers & lane_lt);
             u32 old = 0;
@@ -234,17 +301,23 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
         }
         __syncthreads();
 
-        // digit totals of the tile, per-wavefront bases, local digit starts
+        // thread t owns digits 2t and 2t+1: tile totals, per-wavefront bases, local starts
         {
-            u32 run = 0;
+            u32 cnt[2];
 #pragma unroll
-            for (u32 k = 0; k < kWaves; ++k) {
-                const u32 c = s_wave_hist[k][tid];
-                s_wave_hist[k][tid] = run;
-                run += c;
+            for (u32 h = 0; h < 2; ++h) {
+                const u32 d = 2 * tid + h;
+                u32 run = 0;
+#pragma unroll
+                for (u32 k = 0; k < kWaves; ++k) {
+                    const u32 c = s_wave_hist[k][d];
+                    s_wave_hist[k][d] = run;
+                    run += c;
+                }
+                cnt[h] = run;
             }
-            // exclusive scan of `run` over the 256 digits
-            u32 incl = run;
+            const u32 pair = cnt[0] + cnt[1];
+            u32 incl = pair;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const u32 t = __shfl_up(incl, o, 64);
@@ -255,34 +328,51 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
             u32 wave_base = 0;
 #pragma unroll
             for (u32 k = 0; k < kWaves; ++k) if (k < wv) wave_base += s_scan[k];
-            const u32 start = wave_base + incl - run;
-            s_digit_start[tid] = start;
-            s_gofs[tid] = table[(u64)tid * table_stride + tile] - (u64)start;
-        }
-        __syncthreads();
-
-        // sort the tile by digit in LDS
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u64 idx = t0 + (u64)j * kWave + lane;
-            if (idx < D) {
-                const u32 digit = (u32)(key[j] >> shift) & (kRadix - 1);
-                const u32 p = s_digit_start[digit] + s_wave_hist[wv][digit] + rank[j];
-                s_keys[p] = key[j];
-                s_vals[p] = val[j];
+            const u32 start0 = wave_base + incl - pair;
+            s_digit_start[2 * tid] = start0;
+            s_digit_start[2 * tid + 1] = start0 + cnt[0];
+            if (2 * tid < radix) {
+                s_gofs[2 * tid] = offsets[(u64)(2 * tid) * table_stride + tile] - (u64)start0;
+                s_gofs[2 * tid + 1] = offsets[(u64)(2 * tid + 1) * table_stride + tile] - (u64)(start0 + cnt[0]);
             }
         }
         __syncthreads();
 
-        // contiguous runs out
+        // sort the tile by digit in LDS: keys first, then the values through the same slots
         const u64 tile_base = tile * kSortTile;
         const u32 count = (u32)((D - tile_base) < (u64)kSortTile ? (D - tile_base) : (u64)kSortTile);
-        for (u32 p = tid; p < count; p += kSortThreads) {
-            const u64 k = s_keys[p];
-            const u32 digit = (u32)(k >> shift) & (kRadix - 1);
-            const u64 pos = s_gofs[digit] + p;
-            keys_out[pos] = k;
-            vals_out[pos] = s_vals[p];
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u64 idx = t0 + (u64)j * kWave + lane;
+            if (idx < D) {
+                const u32 digit = (u32)(key[j] >> shift) & dmask;
+                rank[j] = s_digit_start[digit] + s_wave_hist[wv][digit] + rank[j];
+                s_stage[rank[j]] = key[j];
+            }
+        }
+        __syncthreads();
+        u64 pos[kSortItems];
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u32 p = j * kSortThreads + tid;
+            if (p < count) {
+                const u64 k = s_stage[p];
+                pos[j] = s_gofs[(u32)(k >> shift) & dmask] + p;
+                keys_out[pos[j]] = k;
+            }
+        }
+        __syncthreads();
+        u32 *s_vals = reinterpret_cast<u32 *>(s_stage);
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u64 idx = t0 + (u64)j * kWave + lane;
+            if (idx < D) s_vals[rank[j]] = val[j];
+        }
+        __syncthreads();
+#pragma unroll
+        for (u32 j = 0; j < kSortItems; ++j) {
+            const u32 p = j * kSortThreads + tid;
+            if (p < count) vals_out[pos[j]] = s_vals[p];
         }
         __syncthreads();
     }
@@ -331,41 +421,50 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
     u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
     u64 *digit_totals = reinterpret_cast<u64 *>(scratch + L.digit_totals);
-    u64 *table = reinterpret_cast<u64 *>(scratch + L.table);
+    u32 *partials = reinterpret_cast<u32 *>(scratch + L.partials);
+    u32 *table = reinterpret_cast<u32 *>(scratch + L.table);
+    u64 *offsets = reinterpret_cast<u64 *>(scratch + L.offsets);
     const u32 num_tiles = pp.tiles_x * pp.tiles_y;
-    const u32 passes = sort_passes(num_tiles);
+    const SortPlan plan = sort_plan(num_tiles);
 
     // ping-pong so that the last pass lands in keys/vals
-    u64 *kin = (passes & 1u) ? out.keys_alt : out.keys;
-    u32 *vin = (passes & 1u) ? out.vals_alt : out.vals;
-    u64 *kout = (passes & 1u) ? out.keys : out.keys_alt;
-    u32 *vout = (passes & 1u) ? out.vals : out.vals_alt;
+    u64 *kin = (plan.passes & 1u) ? out.keys_alt : out.keys;
+    u32 *vin = (plan.passes & 1u) ? out.vals_alt : out.vals;
+    u64 *kout = (plan.passes & 1u) ? out.keys : out.keys_alt;
+    u32 *vout = (plan.passes & 1u) ? out.vals : out.vals_alt;
 
     if (L.pre_blocks > 0) {
         hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                            proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                           block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header, digit_totals);
+                           block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
 
+    const u32 hist_blocks = (u32)(L.sort_tiles < kHistBlocks ? L.sort_tiles : kHistBlocks);
+    hipLaunchKernelGGL(sort_prehist_kernel, dim3(hist_blocks), dim3(kSortThreads), 0, stream,
+                       kin, header, out.capacity, plan, partials, digit_totals);
+    hipLaunchKernelGGL(sort_reduce_kernel, dim3(plan.passes * kReduceSlices), dim3(kMaxRadix), 0, stream,
+                       partials, hist_blocks, digit_totals);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     // enough resident workgroups to fill 256 CUs several times over; each loops over sort tiles
     const u32 grid = grid_for(L.sort_tiles, 256u * 16u);
-    for (u32 p = 0; p < passes; ++p) {
-        const u32 shift = p * kRadixBits;
-        u64 *totals = digit_totals + (size_t)p * kRadix;
+    for (u32 p = 0; p < plan.passes; ++p) {
+        const u64 *totals = digit_totals + (size_t)p * kMaxRadix;
         hipLaunchKernelGGL(radix_hist_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
-                           kin, header, out.capacity, shift, table, L.sort_tiles, totals);
-        hipLaunchKernelGGL(radix_scan_kernel, dim3(kRadix), dim3(kSortThreads), 0, stream,
-                           header, out.capacity, table, L.sort_tiles, totals);
+                           kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles);
+        hipLaunchKernelGGL(radix_scan_kernel, dim3(1u << plan.bits[p]), dim3(kSortThreads), 0, stream,
+                           header, out.capacity, table, offsets, L.sort_tiles, totals);
         hipLaunchKernelGGL(radix_scatter_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
-                           kin, vin, kout, vout, header, out.capacity, shift, table, L.sort_tiles);
-        hipError_t e = hipGetLastError();
+                           kin, vin, kout, vout, header, out.capacity, plan.shift[p], plan.bits[p],
+                           offsets, L.sort_tiles);
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
         u64 *tk = kin; kin = kout; kout = tk;
         u32 *tv = vin; vin = vout; vout = tv;
     }
-    // after the swap `kin` is the sorted buffer == out.keys
+    // after the last swap `kin` is the sorted buffer == out.keys
     const u32 rgrid = grid_for((out.capacity + 255) / 256, 256u * 16u);
     hipLaunchKernelGGL(tile_ranges_kernel, dim3(rgrid), dim3(256), 0, stream,
                        out.keys, header, out.capacity, num_tiles, out.tile_offsets,

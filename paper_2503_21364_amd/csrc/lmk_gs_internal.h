@@ -17,9 +17,10 @@ constexpr u32 kPreBlock = 256;          // primitives per preprocess / emit work
 constexpr u32 kSortThreads = 256;       // radix sort workgroup
 constexpr u32 kSortItems = 16;          // keys per thread
 constexpr u32 kSortTile = kSortThreads * kSortItems;   // 4096 pairs per workgroup pass
-constexpr u32 kRadixBits = 8;
-constexpr u32 kRadix = 1u << kRadixBits;
+constexpr u32 kMaxRadixBits = 9;         // digits are 7..9 bits wide, chosen per frame
+constexpr u32 kMaxRadix = 1u << kMaxRadixBits;
 constexpr u32 kMaxPasses = 8;
+constexpr u32 kHistBlocks = 512;         // workgroups of the up-front digit histogram
 
 // Header at the start of the scratch buffer.
 struct ScratchHeader {
@@ -33,11 +34,13 @@ struct ScratchLayout {
     size_t header;        // ScratchHeader
     size_t block_sums;    // u32 [pre_blocks]      tile counts per preprocess workgroup
     size_t block_offsets; // u64 [pre_blocks + 1]  their exclusive prefix sum
-    size_t digit_totals;  // u64 [kMaxPasses][256] global digit histograms of each pass
-    size_t table;         // u64 [256][sort_tiles] per-(digit, sort tile) counts, then offsets
+    size_t digit_totals;  // u64 [kMaxPasses][512] global digit histogram of each pass
+    size_t partials;      // u32 [kHistBlocks][kMaxPasses][512] per-workgroup digit counts
+    size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
+    size_t offsets;       // u64 [512][sort_tiles] their output offsets
     size_t total;
     u32 pre_blocks;
-    u64 sort_tiles;       // ceil(capacity / kSortTile), row stride of `table`
+    u64 sort_tiles;       // ceil(capacity / kSortTile)
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -52,19 +55,38 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity)
     L.header = o;        o += align256(sizeof(ScratchHeader));
     L.block_sums = o;    o += align256(sizeof(u32) * (size_t)(L.pre_blocks + 1));
     L.block_offsets = o; o += align256(sizeof(u64) * ((size_t)L.pre_blocks + 1));
-    L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kRadix);
-    L.table = o;         o += align256(sizeof(u64) * kRadix * (size_t)L.sort_tiles);
+    L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kMaxRadix);
+    L.partials = o;      o += align256(sizeof(u32) * (size_t)kHistBlocks * kMaxPasses * kMaxRadix);
+    L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
+    L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
     L.total = o;
     return L;
 }
 
-// Number of 8-bit passes for keys of 32 depth bits + ceil(log2(tiles)) tile bits.
-inline u32 sort_passes(u32 tiles)
+// Digit plan of the LSD radix sort: keys carry 32 depth bits + ceil(log2(tiles)) tile bits;
+// they are cut into the fewest digits of at most 9 bits, as evenly as possible
+// (1080p: 45 bits -> 5 x 9; 2160p: 47 bits -> 5 x 8 + 7; 256 x 256: 40 bits -> 5 x 8).
+struct SortPlan {
+    u32 passes;
+    u32 shift[kMaxPasses];
+    u32 bits[kMaxPasses];
+};
+
+inline SortPlan sort_plan(u32 tiles)
 {
     u32 tile_bits = 0;
     while ((1ull << tile_bits) < (u64)tiles) ++tile_bits;
-    u32 bits = 32 + tile_bits;
-    return (bits + kRadixBits - 1) / kRadixBits;
+    const u32 total = 32 + tile_bits;
+    SortPlan P;
+    P.passes = (total + kMaxRadixBits - 1) / kMaxRadixBits;
+    const u32 base = total / P.passes, extra = total % P.passes;
+    u32 at = 0;
+    for (u32 p = 0; p < kMaxPasses; ++p) {
+        P.shift[p] = at;
+        P.bits[p] = p < P.passes ? base + (p < extra ? 1u : 0u) : 0u;
+        at += P.bits[p];
+    }
+    return P;
 }
 
 // Camera-derived kernel arguments (host-computed, passed by value).
