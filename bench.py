@@ -34,12 +34,12 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, passes):
     opacity 32 B for those past the near plane; SH 192 B + outputs 64 B (depth 4,
     rect 8, feature record 48, reread count 4) for binned ones.
     scan: block sums only (negligible).  emit: 16 B per binned primitive + 12 B per pair.
-    sort: per pass, histogram read 8 B + scatter read 12 B + write 12 B per pair.
-    ranges: 8 B per pair + 8 B per tile.
+    sort: one up-front histogram read of 8 B per pair, then per pass histogram read 8 B +
+    scatter read 12 B + write 12 B per pair.  ranges: 8 B per pair + 8 B per tile.
     """
     b_pre = 16 * n + 32 * n_near + 256 * n_bin
     b_emit = 4 * n + 16 * n_bin + 12 * D
-    b_sort = D * 32 * passes
+    b_sort = D * (8 + 32 * passes)
     b_ranges = 8 * D + 8 * (tiles + 1)
     return dict(preprocess=b_pre, emit=b_emit, sort=b_sort, ranges=b_ranges,
                 total=b_pre + b_emit + b_sort + b_ranges)
@@ -74,7 +74,7 @@ def main():
     ccams = [B.make_camera(c) for c in cams]
     dev = B.Scene(scene)
     tiles = ((W + 15) // 16) * ((H + 15) // 16)
-    passes = (32 + max(1, (tiles - 1).bit_length()) + 7) // 8
+    passes = (32 + (tiles - 1).bit_length() + 8) // 9      # digits of up to 9 bits
 
     # size the pair buffers from a dry run of every viewpoint (not timed)
     probe_cap = 64_000_000 if args.cfg != 4 else 7_000_000_000
