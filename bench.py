@@ -161,6 +161,11 @@ def main():
                    "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity},
         "stage_ms": {"preprocess": float(t_pre.mean()), "bin_sort": float(t_sort.mean()),
                      "render": float(t_blend.mean())},
+        "per_view": [{"pairs": int(Ds[v]), "binned": stats[v]["n_bin"],
+                      "preprocess_ms": float(t_pre[view_of == v].mean()),
+                      "bin_sort_ms": float(t_sort[view_of == v].mean()),
+                      "render_ms": float(t_blend[view_of == v].mean())} for v in range(nviews)
+                     if (view_of == v).any()],
     }
     if E is not None:
         Ev = np.array(E, dtype=np.float64); Cv = np.array(C, dtype=np.float64)

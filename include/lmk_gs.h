@@ -85,6 +85,9 @@ typedef struct lmk_gs_binned {
     uint32_t *vals_alt;       /* [capacity] ping-pong buffer                                    */
     uint64_t capacity;        /* pairs each buffer can hold                                     */
     uint64_t *tile_offsets;   /* [tiles+1]  CSR: pairs of tile t are [tile_offsets[t], tile_offsets[t+1]) */
+    uint32_t *tile_order;     /* [tiles]    optional (may be NULL): tile ids by descending list length,
+                                            a scheduling hint that lmk_gs_render uses to start the
+                                            longest lists first; ties in unspecified order        */
 } lmk_gs_binned;
 
 /* Bytes of device scratch the three calls need for n primitives, a

@@ -42,7 +42,8 @@ class Projected(C.Structure):
 
 class Binned(C.Structure):
     _fields_ = [("keys", C.c_void_p), ("vals", C.c_void_p), ("keys_alt", C.c_void_p),
-                ("vals_alt", C.c_void_p), ("capacity", C.c_uint64), ("tile_offsets", C.c_void_p)]
+                ("vals_alt", C.c_void_p), ("capacity", C.c_uint64), ("tile_offsets", C.c_void_p),
+                ("tile_order", C.c_void_p)]
 
 
 class LmkGsError(RuntimeError):
@@ -138,7 +139,7 @@ class Frame:
     buffers for `capacity` pairs, scratch, and the image."""
 
     def __init__(self, n: int, width: int, height: int, capacity: int, device="cuda:0",
-                 want_offsets: bool = False):
+                 want_offsets: bool = False, tile_order: bool = True):
         self.n, self.width, self.height, self.capacity = n, width, height, int(capacity)
         self.tiles_x = (width + TILE - 1) // TILE
         self.tiles_y = (height + TILE - 1) // TILE
@@ -153,6 +154,7 @@ class Frame:
         self.keys, self.keys_alt = e((cap,), torch.int64), e((cap,), torch.int64)
         self.vals, self.vals_alt = e((cap,), torch.int32), e((cap,), torch.int32)
         self.tile_offsets = e((self.tiles_x * self.tiles_y + 1,), torch.int64)
+        self.tile_order = e((self.tiles_x * self.tiles_y,), torch.int32) if tile_order else None
         self.scratch_bytes = workspace_bytes(n, width, height, self.capacity)
         self.scratch = e((self.scratch_bytes,), torch.uint8)
         self.out_rgb = e((3, height, width), torch.float32)
@@ -160,7 +162,7 @@ class Frame:
         self.proj = Projected(_ptr(self.depth), _ptr(self.tiles_touched), _ptr(self.rect),
                               _ptr(self.feat), _ptr(self.offsets))
         self.binned = Binned(_ptr(self.keys), _ptr(self.vals), _ptr(self.keys_alt), _ptr(self.vals_alt),
-                             self.capacity, _ptr(self.tile_offsets))
+                             self.capacity, _ptr(self.tile_offsets), _ptr(self.tile_order))
 
 
 def preprocess(scene: Scene, cam: Camera, frame: Frame, stream=None) -> None:

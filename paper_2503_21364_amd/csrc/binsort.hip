@@ -408,6 +408,35 @@ __global__ __launch_bounds__(256) void tile_ranges_kernel(
     }
 }
 
+// ---------------------------------------------------------------- schedule hint
+// Tile ids by descending list length, bucketed by the position of the length's top bit
+// (one workgroup; within a bucket the order is whatever the atomics give -- it only
+// decides which workgroup of the blend kernel starts first, never a result).
+__global__ __launch_bounds__(1024) void tile_order_kernel(
+    const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order)
+{
+    __shared__ u32 s_cnt[65];
+    const u32 tid = threadIdx.x;
+    if (tid < 65) s_cnt[tid] = 0;
+    __syncthreads();
+    for (u32 t = tid; t < num_tiles; t += 1024) {
+        const u64 len = tile_offsets[t + 1] - tile_offsets[t];
+        const u32 b = len ? 64u - (u32)__builtin_clzll(len) : 0u;     // 0..64
+        atomicAdd(&s_cnt[64 - b], 1u);                                 // long lists first
+    }
+    __syncthreads();
+    if (tid == 0) {
+        u32 run = 0;
+        for (u32 k = 0; k < 65; ++k) { const u32 c = s_cnt[k]; s_cnt[k] = run; run += c; }
+    }
+    __syncthreads();
+    for (u32 t = tid; t < num_tiles; t += 1024) {
+        const u64 len = tile_offsets[t + 1] - tile_offsets[t];
+        const u32 b = len ? 64u - (u32)__builtin_clzll(len) : 0u;
+        order[atomicAdd(&s_cnt[64 - b], 1u)] = t;
+    }
+}
+
 // ---------------------------------------------------------------- launcher
 static inline u32 grid_for(u64 work_items, u32 cap)
 {
@@ -469,6 +498,9 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     hipLaunchKernelGGL(tile_ranges_kernel, dim3(rgrid), dim3(256), 0, stream,
                        out.keys, header, out.capacity, num_tiles, out.tile_offsets,
                        n == 0 ? proj.offsets : nullptr);
+    if (out.tile_order)
+        hipLaunchKernelGGL(tile_order_kernel, dim3(1), dim3(1024), 0, stream,
+                           out.tile_offsets, num_tiles, out.tile_order);
     return hipGetLastError();
 }
 

@@ -33,6 +33,8 @@ constexpr u32 kBlendThreads = 256;
 constexpr u32 kBatch = 256;
 constexpr u32 kXcds = 8;     // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
+constexpr u32 kSurv = 4;     // survivors evaluated together (independent exponentials in flight)
+
 struct BlendParams {
     u32 width, height, tiles_x, num_tiles, tiles_per_xcd;
     float bg0, bg1, bg2;
@@ -57,8 +59,8 @@ __device__ __forceinline__ Rec fetch_record(const u32 *__restrict__ vals, const 
 __device__ __forceinline__ float clamp_pm(float v, float h) { return __builtin_amdgcn_fmed3f(v, -h, h); }
 
 __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
-    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ vals,
-    const float4 *__restrict__ feat, BlendParams bp,
+    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ tile_order,
+    const u32 *__restrict__ vals, const float4 *__restrict__ feat, BlendParams bp,
     float *__restrict__ out_rgb, float *__restrict__ out_T)
 {
     // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C: log2 of the falloff is
@@ -67,10 +69,19 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     __shared__ float4 s_cop[kBatch];    // C', opacity, r, g
     __shared__ float4 s_tst[kBatch];    // threshold, -B'/(2A'), -B'/(2C'), b
 
-    // consecutive workgroup ids land on different XCDs; give each XCD one
-    // contiguous band of tiles so neighbouring tiles share that XCD's L2
-    const u32 tile = (blockIdx.x % kXcds) * bp.tiles_per_xcd + blockIdx.x / kXcds;
-    if (blockIdx.x / kXcds >= bp.tiles_per_xcd || tile >= bp.num_tiles) return;
+    u32 tile;
+    if (tile_order) {
+        // tiles by descending list length: the longest lists start first, and consecutive
+        // workgroup ids (dealt round-robin to the XCDs) spread them over all dies
+        if (blockIdx.x >= bp.num_tiles) return;
+        tile = tile_order[blockIdx.x];
+        if (tile >= bp.num_tiles) return;          // never index past the grid on a corrupt hint
+    } else {
+        // consecutive workgroup ids land on different XCDs; give each XCD one
+        // contiguous band of tiles so neighbouring tiles share that XCD's L2
+        tile = (blockIdx.x % kXcds) * bp.tiles_per_xcd + blockIdx.x / kXcds;
+        if (blockIdx.x / kXcds >= bp.tiles_per_xcd || tile >= bp.num_tiles) return;
+    }
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 tx = tile % bp.tiles_x, ty = tile / bp.tiles_x;
@@ -80,7 +91,7 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     // this wavefront's block centre relative to block 0's, and this lane's pixel centre
     // relative to its block centre
     const float bx = (float)((wv & 1u) * 8u), by = (float)((wv >> 1) * 8u);
-    const float fi = (float)(lane & 7u) - 3.5f, fj = (float)(lane >> 3) - 3.5f;
+    const float ox = bx + ((float)(lane & 7u) - 3.5f), oy = by + ((float)(lane >> 3) - 3.5f);
     const float X0 = (float)(tx * LMK_GS_TILE) + 4.0f, Y0 = (float)(ty * LMK_GS_TILE) + 4.0f;
     const float kHalf = 3.5f;           // pixel centres of a block span [-3.5, 3.5]^2 about its centre
 
@@ -134,27 +145,45 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
                 const float best = fmaxf(fmaf(m1, kRelMargin, p1), fmaf(m2, kRelMargin, p2));
                 mask = __builtin_amdgcn_ballot_w64(best >= t.x);
             }
-            // ---- phase 2: lane = pixel; composite the survivors in list order
+            // ---- phase 2: lane = pixel; composite the survivors in list order, kSurv at a time
+            // (their exponentials are independent; the compositing updates stay in order)
             while (mask != 0ull && live != 0ull) {
-                const u32 j = c0 + (u32)__builtin_ctzll(mask);
-                mask &= mask - 1ull;
-                const float4 g = s_geo[j];
-                const float4 co = s_cop[j];
-                const float dx = (g.x - bx) - fi, dy = (g.y - by) - fj;
-                const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), co.x * dy * dy);
-                const float alpha = fminf(0.99f, co.y * __builtin_amdgcn_exp2f(p));
-                const bool hit = !done && !(alpha < 1.0f / 255.0f);
-                if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
-                    const float blue = s_tst[j].w;
-                    const float Tn = fmaf(-T, alpha, T);
-                    const bool stop = hit && Tn < 1e-4f;
-                    done = done || stop;
-                    if (hit && !stop) {
-                        const float w = alpha * T;
-                        cr = fmaf(co.z, w, cr); cg = fmaf(co.w, w, cg); cb = fmaf(blue, w, cb);
-                        T = Tn;
+                u32 j[kSurv];
+                bool have[kSurv];
+#pragma unroll
+                for (u32 k = 0; k < kSurv; ++k) {
+                    have[k] = mask != 0ull;
+                    j[k] = have[k] ? c0 + (u32)__builtin_ctzll(mask) : j[0];
+                    mask &= mask - 1ull;
+                }
+                float alpha[kSurv];
+                float4 co[kSurv];
+#pragma unroll
+                for (u32 k = 0; k < kSurv; ++k) {
+                    const float4 g = s_geo[j[k]];
+                    co[k] = s_cop[j[k]];
+                    const float dx = g.x - ox, dy = g.y - oy;
+                    const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), co[k].x * dy * dy);
+                    alpha[k] = fminf(0.99f, co[k].y * __builtin_amdgcn_exp2f(p));
+                }
+#pragma unroll
+                for (u32 k = 0; k < kSurv; ++k) {
+                    if (!have[k]) break;
+                    const bool ge = !(alpha[k] < 1.0f / 255.0f);
+                    if ((__builtin_amdgcn_ballot_w64(ge) & live) != 0ull) {
+                        const float blue = s_tst[j[k]].w;
+                        const float Tn = fmaf(-T, alpha[k], T);
+                        const bool hit = ge && !done;
+                        const bool stop = hit && Tn < 1e-4f;
+                        if (hit && !stop) {
+                            const float w = alpha[k] * T;
+                            cr = fmaf(co[k].z, w, cr); cg = fmaf(co[k].w, w, cg); cb = fmaf(blue, w, cb);
+                            T = Tn;
+                        }
+                        done = done || stop;
+                        live &= ~__builtin_amdgcn_ballot_w64(stop);
+                        if (live == 0ull) break;
                     }
-                    live &= ~__builtin_amdgcn_ballot_w64(stop);
                 }
             }
         }
@@ -178,8 +207,8 @@ hipError_t launch_render(const lmk_gs_projected &proj, const lmk_gs_binned &binn
     bp.tiles_per_xcd = (bp.num_tiles + kXcds - 1) / kXcds;
     bp.bg0 = pp.cam.bg[0]; bp.bg1 = pp.cam.bg[1]; bp.bg2 = pp.cam.bg[2];
     hipLaunchKernelGGL(blend_kernel, dim3(bp.tiles_per_xcd * kXcds), dim3(kBlendThreads), 0, stream,
-                       binned.tile_offsets, binned.vals, reinterpret_cast<const float4 *>(proj.feat), bp,
-                       out_rgb, out_T);
+                       binned.tile_offsets, binned.tile_order, binned.vals,
+                       reinterpret_cast<const float4 *>(proj.feat), bp, out_rgb, out_T);
     return hipGetLastError();
 }
 

@@ -38,7 +38,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(B.Camera) == 4 * (12 + 3 + 4 + 3 + 2 + 3)
     assert C.sizeof(B.Gaussians) == 5 * 8 + 2 * 4
     assert C.sizeof(B.Projected) == 5 * 8
-    assert C.sizeof(B.Binned) == 6 * 8
+    assert C.sizeof(B.Binned) == 7 * 8
     assert B.Binned.capacity.offset == 32 and B.Binned.tile_offsets.offset == 40
 
 
@@ -72,7 +72,7 @@ def _args():
     fake non-NULL values, so every test below must fail validation before launch."""
     g = B.Gaussians(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 10, 3)
     proj = B.Projected(0x1000, 0x1000, 0x1000, 0x1000, None)
-    binned = B.Binned(0x1000, 0x1000, 0x1000, 0x1000, 100, 0x1000)
+    binned = B.Binned(0x1000, 0x1000, 0x1000, 0x1000, 100, 0x1000, None)
     return g, proj, binned
 
 
@@ -124,9 +124,9 @@ def test_bin_sort_and_render_reject_bad_arguments():
     assert bs(proj, cam, None) == B.ERR_INVALID
     assert bs(proj, cam, binned, None) == B.ERR_INVALID
     assert bs(proj, cam, binned, scratch, need - 256) == B.ERR_CAPACITY
-    b2 = B.Binned(0x1000, 0x1000, None, 0x1000, 100, 0x1000)
+    b2 = B.Binned(0x1000, 0x1000, None, 0x1000, 100, 0x1000, None)
     assert bs(proj, cam, b2) == B.ERR_INVALID
-    b2 = B.Binned(0x1000, 0x1000, 0x1000, 0x1000, 100, None)
+    b2 = B.Binned(0x1000, 0x1000, 0x1000, 0x1000, 100, None, None)
     assert bs(proj, cam, b2) == B.ERR_INVALID
     rd = lambda p_, b_, c_, o1=_fake(), o2=_fake(): lib.lmk_gs_render(
         None if p_ is None else C.byref(p_), None if b_ is None else C.byref(b_),

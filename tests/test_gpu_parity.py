@@ -184,7 +184,7 @@ def test_render_alone_from_oracle_lists():
     cam = scenes.make_cameras(0, 200, 136)[0]
     cam["bg"] = np.array([0.5, 0.25, 0.75], np.float32)
     ofr = ref.render_frame(sc, cam)
-    fr = B.Frame(sc["n"], 200, 136, ofr.binned.D + 1)
+    fr = B.Frame(sc["n"], 200, 136, ofr.binned.D + 1, tile_order=False)   # bin_sort never runs here
     _upload_projected(fr, ofr.pre)
     D = ofr.binned.D
     fr.vals[:D] = torch.from_numpy(ofr.binned.vals.view(np.int32)).cuda()
@@ -193,6 +193,24 @@ def test_render_alone_from_oracle_lists():
     torch.cuda.synchronize()
     st = P.compare_image(fr, ofr.img, cam)
     _report("render alone", st)
+
+
+def test_tile_order_is_a_permutation_by_descending_length_class():
+    sc = scenes.make_scene(0, n=20000, seed=37)
+    sc["scale"] *= np.float32(2.0)
+    cam = scenes.make_cameras(0, 400, 240)[0]
+    fr = P.gpu_frame(B.Scene(sc), cam, 2_000_000)
+    order = P.to_np(fr.tile_order).view(np.uint32).astype(np.int64)
+    T = fr.tiles_x * fr.tiles_y
+    assert np.array_equal(np.sort(order), np.arange(T))
+    lens = np.diff(P.to_np(fr.tile_offsets).view(np.uint64).astype(np.int64))[order]
+    cls = np.where(lens > 0, np.floor(np.log2(np.maximum(lens, 1))).astype(np.int64) + 1, 0)
+    assert np.all(np.diff(cls) <= 0)
+    # and the image does not depend on the hint
+    fr2 = B.Frame(sc["n"], 400, 240, 2_000_000, tile_order=False)
+    B.render_frame(B.Scene(sc), B.make_camera(cam), fr2)
+    torch.cuda.synchronize()
+    assert torch.equal(fr.out_rgb, fr2.out_rgb) and torch.equal(fr.out_T, fr2.out_T)
 
 
 def test_two_runs_are_bytewise_identical():
