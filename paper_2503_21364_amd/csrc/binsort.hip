@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     const u32 tid = threadIdx.x;
     const u32 dmask = (1u << bits) - 1u;
     for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        s_hist[tid] = 0; s_hist[tid + kSortThreads] = 0;
+        for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_hist[d] = 0;
         __syncthreads();
         const u64 t0 = tile * kSortTile;
         u64 k[kSortItems];
@@ -182,8 +182,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
             if (idx < D) atomicAdd(&s_hist[(u32)(k[j] >> shift) & dmask], 1u);
         }
         __syncthreads();
-        table[(u64)tid * table_stride + tile] = s_hist[tid];
-        table[(u64)(tid + kSortThreads) * table_stride + tile] = s_hist[tid + kSortThreads];
+        for (u32 d = tid; d < kMaxRadix; d += kSortThreads) table[(u64)d * table_stride + tile] = s_hist[d];
         __syncthreads();
     }
 }
@@ -203,8 +202,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
 
     // base = total of the digits below mine
     u64 part = 0;
-    if (tid < digit) part += digit_totals[tid];
-    if (tid + kSortThreads < digit) part += digit_totals[tid + kSortThreads];
+    for (u32 d = tid; d < digit; d += kSortThreads) part += digit_totals[d];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
     if (lane == 0) s_wave[wv] = part;
@@ -301,12 +299,14 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
         }
         __syncthreads();
 
-        // thread t owns digits 2t and 2t+1: tile totals, per-wavefront bases, local starts
+        // thread t owns kDPT consecutive digits: tile totals, per-wavefront bases, local starts
         {
-            u32 cnt[2];
+            constexpr u32 kDPT = kMaxRadix / kSortThreads;
+            u32 cnt[kDPT];
+            u32 mine = 0;
 #pragma unroll
-            for (u32 h = 0; h < 2; ++h) {
-                const u32 d = 2 * tid + h;
+            for (u32 h = 0; h < kDPT; ++h) {
+                const u32 d = kDPT * tid + h;
                 u32 run = 0;
 #pragma unroll
                 for (u32 k = 0; k < kWaves; ++k) {
@@ -315,9 +315,9 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
                     run += c;
                 }
                 cnt[h] = run;
+                mine += run;
             }
-            const u32 pair = cnt[0] + cnt[1];
-            u32 incl = pair;
+            u32 incl = mine;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const u32 t = __shfl_up(incl, o, 64);
@@ -325,15 +325,15 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
             }
             if (lane == kWave - 1) s_scan[wv] = incl;
             __syncthreads();
-            u32 wave_base = 0;
+            u32 start = incl - mine;
 #pragma unroll
-            for (u32 k = 0; k < kWaves; ++k) if (k < wv) wave_base += s_scan[k];
-            const u32 start0 = wave_base + incl - pair;
-            s_digit_start[2 * tid] = start0;
-            s_digit_start[2 * tid + 1] = start0 + cnt[0];
-            if (2 * tid < radix) {
-                s_gofs[2 * tid] = offsets[(u64)(2 * tid) * table_stride + tile] - (u64)start0;
-                s_gofs[2 * tid + 1] = offsets[(u64)(2 * tid + 1) * table_stride + tile] - (u64)(start0 + cnt[0]);
+            for (u32 k = 0; k < kWaves; ++k) if (k < wv) start += s_scan[k];
+#pragma unroll
+            for (u32 h = 0; h < kDPT; ++h) {
+                const u32 d = kDPT * tid + h;
+                s_digit_start[d] = start;
+                if (d < radix) s_gofs[d] = offsets[(u64)d * table_stride + tile] - (u64)start;
+                start += cnt[h];
             }
         }
         __syncthreads();
@@ -351,14 +351,14 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
             }
         }
         __syncthreads();
-        u64 pos[kSortItems];
+        u32 dg[kSortItems];                            // digit of the key that ended up in slot p
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u32 p = j * kSortThreads + tid;
             if (p < count) {
                 const u64 k = s_stage[p];
-                pos[j] = s_gofs[(u32)(k >> shift) & dmask] + p;
-                keys_out[pos[j]] = k;
+                dg[j] = (u32)(k >> shift) & dmask;
+                keys_out[s_gofs[dg[j]] + p] = k;
             }
         }
         __syncthreads();
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u32 p = j * kSortThreads + tid;
-            if (p < count) vals_out[pos[j]] = s_vals[p];
+            if (p < count) vals_out[s_gofs[dg[j]] + p] = s_vals[p];
         }
         __syncthreads();
     }

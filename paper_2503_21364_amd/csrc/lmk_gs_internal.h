@@ -17,7 +17,7 @@ constexpr u32 kPreBlock = 256;          // primitives per preprocess / emit work
 constexpr u32 kSortThreads = 256;       // radix sort workgroup
 constexpr u32 kSortItems = 16;          // keys per thread
 constexpr u32 kSortTile = kSortThreads * kSortItems;   // 4096 pairs per workgroup pass
-constexpr u32 kMaxRadixBits = 9;         // digits are 7..9 bits wide, chosen per frame
+constexpr u32 kMaxRadixBits = 9;         // digits are at most 9 bits wide, chosen per frame
 constexpr u32 kMaxRadix = 1u << kMaxRadixBits;
 constexpr u32 kMaxPasses = 8;
 constexpr u32 kHistBlocks = 512;         // workgroups of the up-front digit histogram
