@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the primitive count (reported in config)")
     ap.add_argument("--views", type=int, default=None, help="use only the first K viewpoints of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (no blends/s either)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="before timing, run four plain device copies of 1 GiB (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -94,6 +97,15 @@ def main():
     torch.cuda.empty_cache()
     capacity = int(max(Ds) * 1.25) + 4096
     fr = B.Frame(n, W, H, capacity)
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     nviews = len(ccams)
     ev = lambda: torch.cuda.Event(enable_timing=True)

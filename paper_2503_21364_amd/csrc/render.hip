@@ -16,15 +16,18 @@
 //     which alpha < 1/255 everywhere in the block.  This is the exact
 //     splat/block intersection ("intersection operations for each tile",
 //     Sec. 4.2.1) at 8x8 granularity, costing well under one vector instruction
-//     per entry; LDS is read lane-distinct, not broadcast.
-//  2. lane = pixel.  Only the surviving entries (a 64-bit ballot, walked in
-//     order with scalar bit scans) are evaluated per pixel: two LDS broadcasts,
-//     seven FP32 operations for the exponent, v_exp_f32, the alpha test and the
-//     compositing update under the lane mask.
+//     per entry; LDS is read lane-distinct, not broadcast.  Survivors append
+//     their LDS offsets, in list order, to a per-wavefront survivor list
+//     (ballot + mbcnt ranks).
+//  2. lane = pixel.  The survivor list is walked four entries at a time: one
+//     16-byte LDS read yields four record offsets, the four exponentials are
+//     independent, the compositing updates follow in order under per-lane
+//     select masks.  The loop body has no data-dependent scalar control flow
+//     (the scalar unit, shared by the CU's four SIMDs, was as loaded as the
+//     vector units when survivors were walked with scalar bit scans).
 // A wavefront whose 64 pixels have all stopped skips the rest (per-wavefront
 // progress, Sec. 4.2.1); the tile leaves when all four have.  Bound by FP32
-// VALU issue and LDS broadcast bandwidth; HBM traffic is the 52 bytes per list
-// entry of the gather.
+// VALU issue; HBM traffic is the 52 bytes per list entry of the gather.
 #include "lmk_gs_internal.h"
 
 namespace lmk {
@@ -63,11 +66,13 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const u32 *__restrict__ vals, const float4 *__restrict__ feat, BlendParams bp,
     float *__restrict__ out_rgb, float *__restrict__ out_T)
 {
-    // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C: log2 of the falloff is
-    // A' dx^2 + B' dx dy + C' dy^2.  (du, dv) = splat centre relative to the centre of block 0.
-    __shared__ float4 s_geo[kBatch];    // du, dv, A', B'
-    __shared__ float4 s_cop[kBatch];    // C', opacity, r, g
-    __shared__ float4 s_tst[kBatch];    // threshold, -B'/(2A'), -B'/(2C'), b
+    // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C, lo = log2(opacity):
+    // log2(alpha) = A' dx^2 + B' dx dy + C' dy^2 + lo.  (du, dv) = splat centre relative to
+    // the centre of block 0.  Slot kBatch is a null record that can never contribute.
+    __shared__ float4 s_geo[kBatch + 1];    // du, dv, A', B'
+    __shared__ float4 s_cop[kBatch + 1];    // C', lo, r, g
+    __shared__ float4 s_tst[kBatch + 1];    // -B'/(2A'), -B'/(2C'), b, -
+    __shared__ __attribute__((aligned(16))) u32 s_list[kBlendThreads / kWave][kBatch + kSurv];
 
     u32 tile;
     if (tile_order) {
@@ -89,7 +94,6 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const u32 pxi = tx * LMK_GS_TILE + li, pyi = ty * LMK_GS_TILE + lj;
     const bool inside = pxi < bp.width && pyi < bp.height;
     // this wavefront's block centre relative to block 0's, and this lane's pixel centre
-    // relative to its block centre
     const float bx = (float)((wv & 1u) * 8u), by = (float)((wv >> 1) * 8u);
     const float ox = bx + ((float)(lane & 7u) - 3.5f), oy = by + ((float)(lane >> 3) - 3.5f);
     const float X0 = (float)(tx * LMK_GS_TILE) + 4.0f, Y0 = (float)(ty * LMK_GS_TILE) + 4.0f;
@@ -98,11 +102,17 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
     float T = 1.0f, cr = 0.0f, cg = 0.0f, cb = 0.0f;
     bool done = !inside;
-    u64 live = __builtin_amdgcn_ballot_w64(inside);     // pixels of this wavefront still walking
     const float kL2E = 1.4426950408889634f;
-    const float kMargin = 1.5e-4f;      // block test passes alpha down to 0.99990 / 255
+    // block test: log2(alpha_max) >= log2(1/255) - margin, i.e. alpha down to 0.99990/255 passes
+    const float kPass = -7.994353436858858f - 1.5e-4f;
     const float kRelMargin = -2e-6f;    // times (A' ex^2 + C' ey^2) <= 0: covers fp32 rounding of the test
+    constexpr u32 kNullOfs = kBatch * 16u;
 
+    if (tid == 0) {
+        s_geo[kBatch] = make_float4(0.f, 0.f, 0.f, 0.f);
+        s_cop[kBatch] = make_float4(0.f, -1000.0f, 0.f, 0.f);
+        s_tst[kBatch] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     Rec next = fetch_record(vals, feat, start + tid, start + tid < end);
 
     for (u64 base = start; base < end; base += kBatch) {
@@ -112,80 +122,71 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
             // every thread stages one slot; slots past the end of the list can never pass a test
             const bool valid = tid < cnt;
             const float A = -0.5f * kL2E * next.a.z, Bq = -kL2E * next.a.w, Cq = -0.5f * kL2E * next.b.x;
-            const float o = next.b.y;
             s_geo[tid] = make_float4(next.a.x - X0, next.a.y - Y0, A, Bq);
-            s_cop[tid] = make_float4(Cq, o, next.b.z, next.b.w);
-            s_tst[tid] = make_float4(valid ? -__log2f(255.0f * o) - kMargin : __builtin_inff(),
-                                     valid ? -Bq / (2.0f * A) : 0.0f, valid ? -Bq / (2.0f * Cq) : 0.0f,
-                                     next.c.x);
+            s_cop[tid] = make_float4(Cq, valid ? __log2f(next.b.y) : -1000.0f, next.b.z, next.b.w);
+            s_tst[tid] = make_float4(valid ? -Bq / (2.0f * A) : 0.0f, valid ? -Bq / (2.0f * Cq) : 0.0f,
+                                     next.c.x, 0.0f);
         }
         __syncthreads();
         {
             const u64 npos = base + kBatch + tid;
             next = fetch_record(vals, feat, npos, npos < end);    // in flight during the loops below
         }
-        for (u32 c0 = 0; c0 < cnt && live != 0ull; c0 += kWave) {
-            // ---- phase 1: lane = entry; does the splat reach this wavefront's block at all?
-            u64 mask;
-            {
-                const float4 g = s_geo[c0 + lane];
-                const float4 t = s_tst[c0 + lane];
-                const float Cq = s_cop[c0 + lane].x;
-                const float xs = g.x - bx, ys = g.y - by;          // splat centre in block coordinates
-                // candidate 1: x clamped into the block, best y on that vertical line
-                const float ex1 = clamp_pm(xs, kHalf) - xs;
-                const float ey1 = clamp_pm(fmaf(t.z, ex1, ys), kHalf) - ys;
-                const float m1 = fmaf(g.z * ex1, ex1, Cq * ey1 * ey1);
-                const float p1 = fmaf(g.w * ex1, ey1, m1);
-                // candidate 2: y clamped, best x on that horizontal line
-                const float ey2 = clamp_pm(ys, kHalf) - ys;
-                const float ex2 = clamp_pm(fmaf(t.y, ey2, xs), kHalf) - xs;
-                const float m2 = fmaf(g.z * ex2, ex2, Cq * ey2 * ey2);
-                const float p2 = fmaf(g.w * ex2, ey2, m2);
-                const float best = fmaxf(fmaf(m1, kRelMargin, p1), fmaf(m2, kRelMargin, p2));
-                mask = __builtin_amdgcn_ballot_w64(best >= t.x);
+        if (__builtin_amdgcn_ballot_w64(!done) == 0ull) continue;  // this wavefront is finished
+
+        // ---- phase 1: lane = entry; which splats reach this wavefront's block at all?
+        u32 nsurv = 0;
+        for (u32 c0 = 0; c0 < cnt; c0 += kWave) {
+            const float4 g = s_geo[c0 + lane];
+            const float4 t = s_tst[c0 + lane];
+            const float4 co = s_cop[c0 + lane];
+            const float xs = g.x - bx, ys = g.y - by;          // splat centre in block coordinates
+            // candidate 1: x clamped into the block, best y on that vertical line
+            const float ex1 = clamp_pm(xs, kHalf) - xs;
+            const float ey1 = clamp_pm(fmaf(t.y, ex1, ys), kHalf) - ys;
+            const float m1 = fmaf(g.z * ex1, ex1, co.x * ey1 * ey1);
+            const float p1 = fmaf(g.w * ex1, ey1, m1);
+            // candidate 2: y clamped, best x on that horizontal line
+            const float ey2 = clamp_pm(ys, kHalf) - ys;
+            const float ex2 = clamp_pm(fmaf(t.x, ey2, xs), kHalf) - xs;
+            const float m2 = fmaf(g.z * ex2, ex2, co.x * ey2 * ey2);
+            const float p2 = fmaf(g.w * ex2, ey2, m2);
+            const float best = fmaxf(fmaf(m1, kRelMargin, p1), fmaf(m2, kRelMargin, p2));
+            const bool pass = best + co.y >= kPass;
+            const u64 mask = __builtin_amdgcn_ballot_w64(pass);
+            const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+            if (pass) s_list[wv][nsurv + rank] = (c0 + lane) * 16u;
+            nsurv += (u32)__builtin_popcountll(mask);
+        }
+        if (lane < kSurv) s_list[wv][nsurv + lane] = kNullOfs;   // pad the last group with the null record
+
+        // ---- phase 2: lane = pixel; composite the survivors in list order, kSurv at a time
+        for (u32 k = 0; k < nsurv; k += kSurv) {
+            const uint4 ofs4 = *reinterpret_cast<const uint4 *>(&s_list[wv][k]);
+            const u32 ofs[kSurv] = { ofs4.x, ofs4.y, ofs4.z, ofs4.w };
+            float alpha[kSurv];
+            float4 co[kSurv];
+#pragma unroll
+            for (u32 q = 0; q < kSurv; ++q) {
+                const float4 g = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_geo) + ofs[q]);
+                co[q] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_cop) + ofs[q]);
+                const float dx = g.x - ox, dy = g.y - oy;
+                const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co[q].x * dy, dy, co[q].y));
+                alpha[q] = fminf(0.99f, __builtin_amdgcn_exp2f(p));
             }
-            // ---- phase 2: lane = pixel; composite the survivors in list order, kSurv at a time
-            // (their exponentials are independent; the compositing updates stay in order)
-            while (mask != 0ull && live != 0ull) {
-                u32 j[kSurv];
-                bool have[kSurv];
 #pragma unroll
-                for (u32 k = 0; k < kSurv; ++k) {
-                    have[k] = mask != 0ull;
-                    j[k] = have[k] ? c0 + (u32)__builtin_ctzll(mask) : j[0];
-                    mask &= mask - 1ull;
-                }
-                float alpha[kSurv];
-                float4 co[kSurv];
-#pragma unroll
-                for (u32 k = 0; k < kSurv; ++k) {
-                    const float4 g = s_geo[j[k]];
-                    co[k] = s_cop[j[k]];
-                    const float dx = g.x - ox, dy = g.y - oy;
-                    const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), co[k].x * dy * dy);
-                    alpha[k] = fminf(0.99f, co[k].y * __builtin_amdgcn_exp2f(p));
-                }
-#pragma unroll
-                for (u32 k = 0; k < kSurv; ++k) {
-                    if (!have[k]) break;
-                    const bool ge = !(alpha[k] < 1.0f / 255.0f);
-                    if ((__builtin_amdgcn_ballot_w64(ge) & live) != 0ull) {
-                        const float blue = s_tst[j[k]].w;
-                        const float Tn = fmaf(-T, alpha[k], T);
-                        const bool hit = ge && !done;
-                        const bool stop = hit && Tn < 1e-4f;
-                        if (hit && !stop) {
-                            const float w = alpha[k] * T;
-                            cr = fmaf(co[k].z, w, cr); cg = fmaf(co[k].w, w, cg); cb = fmaf(blue, w, cb);
-                            T = Tn;
-                        }
-                        done = done || stop;
-                        live &= ~__builtin_amdgcn_ballot_w64(stop);
-                        if (live == 0ull) break;
-                    }
-                }
+            for (u32 q = 0; q < kSurv; ++q) {
+                const float blue = reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_tst) + ofs[q])->z;
+                const float Tn = fmaf(-T, alpha[q], T);
+                const bool hit = !(alpha[q] < 1.0f / 255.0f) && !done;
+                const bool stop = hit && Tn < 1e-4f;
+                const bool upd = hit && !stop;
+                const float w = upd ? alpha[q] * T : 0.0f;
+                cr = fmaf(co[q].z, w, cr); cg = fmaf(co[q].w, w, cg); cb = fmaf(blue, w, cb);
+                T = upd ? Tn : T;
+                done = done || stop;
             }
+            if (__builtin_amdgcn_ballot_w64(!done) == 0ull) break;     // all 64 pixels stopped
         }
     }
     if (inside) {
