@@ -216,10 +216,16 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
 
     const u32 *row = table + (u64)digit * table_stride;
     u64 *orow = offsets + (u64)digit * table_stride;
-    for (u64 base = 0; base < ntiles; base += kSortThreads) {
-        const u64 idx = base + tid;
-        const u64 v = idx < ntiles ? (u64)row[idx] : 0;
-        u64 incl = v;
+    constexpr u32 kItems = 8;                  // consecutive sort tiles per thread, loaded together
+    for (u64 base = 0; base < ntiles; base += (u64)kSortThreads * kItems) {
+        const u64 first = base + (u64)tid * kItems;
+        u32 v[kItems];
+        u64 mine = 0;
+#pragma unroll
+        for (u32 k = 0; k < kItems; ++k) v[k] = first + k < ntiles ? row[first + k] : 0u;
+#pragma unroll
+        for (u32 k = 0; k < kItems; ++k) mine += v[k];
+        u64 incl = mine;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const u64 t = __shfl_up(incl, o, 64);
@@ -228,12 +234,15 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
         __syncthreads();                       // s_wave free again
         if (lane == kWave - 1) s_wave[wv] = incl;
         __syncthreads();
-        u64 wave_base = 0;
-        for (u32 k = 0; k < wv; ++k) wave_base += s_wave[k];
-        const u64 carry = s_carry;
-        if (idx < ntiles) orow[idx] = carry + wave_base + incl - v;
+        u64 run = s_carry + incl - mine;
+        for (u32 k = 0; k < wv; ++k) run += s_wave[k];
+#pragma unroll
+        for (u32 k = 0; k < kItems; ++k) {
+            if (first + k < ntiles) orow[first + k] = run;
+            run += v[k];
+        }
         __syncthreads();
-        if (tid == kSortThreads - 1) s_carry = carry + wave_base + incl;
+        if (tid == kSortThreads - 1) s_carry = run;
         __syncthreads();
     }
 }

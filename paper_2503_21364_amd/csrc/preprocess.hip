@@ -195,6 +195,7 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
 // Exclusive prefix sum (u64) over the workgroup tile counts; one workgroup.
 // Also publishes D and clears the status word.
 constexpr u32 kScanThreads = 1024;
+constexpr u32 kScanItems = 16;          // consecutive entries per thread, loaded together
 
 __global__ __launch_bounds__(kScanThreads) void scan_block_sums_kernel(
     const u32 *__restrict__ block_sums, u32 nb, u64 *__restrict__ block_offsets,
@@ -205,10 +206,15 @@ __global__ __launch_bounds__(kScanThreads) void scan_block_sums_kernel(
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     if (tid == 0) s_carry = 0;
     __syncthreads();
-    for (u32 base = 0; base < nb; base += kScanThreads) {
-        const u32 idx = base + tid;
-        const u64 v = idx < nb ? (u64)block_sums[idx] : 0;
-        u64 incl = v;
+    for (u32 base = 0; base < nb; base += kScanThreads * kScanItems) {
+        const u32 first = base + tid * kScanItems;
+        u32 v[kScanItems];
+        u64 mine = 0;
+#pragma unroll
+        for (u32 k = 0; k < kScanItems; ++k) v[k] = first + k < nb ? block_sums[first + k] : 0u;
+#pragma unroll
+        for (u32 k = 0; k < kScanItems; ++k) mine += v[k];
+        u64 incl = mine;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const u64 t = __shfl_up(incl, o, 64);
@@ -216,12 +222,15 @@ __global__ __launch_bounds__(kScanThreads) void scan_block_sums_kernel(
         }
         if (lane == kWave - 1) s_wave[wv] = incl;
         __syncthreads();
-        u64 wave_base = 0;
-        for (u32 k = 0; k < wv; ++k) wave_base += s_wave[k];
-        const u64 carry = s_carry;
-        if (idx < nb) block_offsets[idx] = carry + wave_base + incl - v;
+        u64 run = s_carry + incl - mine;
+        for (u32 k = 0; k < wv; ++k) run += s_wave[k];
+#pragma unroll
+        for (u32 k = 0; k < kScanItems; ++k) {
+            if (first + k < nb) block_offsets[first + k] = run;
+            run += v[k];
+        }
         __syncthreads();
-        if (tid == kScanThreads - 1) s_carry = carry + wave_base + incl;
+        if (tid == kScanThreads - 1) s_carry = run;
         __syncthreads();
     }
     if (tid == 0) {
