@@ -51,6 +51,7 @@ typedef struct {
     float near_z;
     float lowpass;    /* h: added to the diagonal of the 2D covariance, px^2 */
     float bg[3];
+    uint32_t binning; /* 0: every tile of the support rectangle; 1: only tiles the splat can reach */
 } ref_camera;
 
 /* cull stage recorded per primitive */
@@ -62,6 +63,74 @@ enum { REF_VISIBLE = 0, REF_CULL_NEAR = 1, REF_CULL_DET = 2, REF_CULL_OPACITY = 
 #define REF_T_MIN 1e-4f
 
 static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+/* ------------------------------------------------------------------ */
+/* Binning rule 1 ("intersection operations for each tile", Sec. 4.2.1) [reading]:
+ * a tile of the support rectangle is kept only if the splat can reach alpha >=
+ * 1/255 somewhere on the square spanned by the tile's pixel centres.
+ *
+ * q(d) = d^T conic d is convex, so its minimum over the square sits at the splat
+ * centre if that is inside, else on an edge facing it: clamp one coordinate into
+ * the square, minimise along that line (clamped), and take the better of the
+ * two choices.  A pair contributes only if q <= 2 ln(255 o); tau bounds that from
+ * above using only the exponent and the top three mantissa bits of o
+ * (o < (1 + (k+1)/8) 2^E), so that no logarithm of a run-time value is needed
+ * and the decision is reproducible bit for bit.  All fp32, one rounding per
+ * operation.  The 0.01 added to tau and the 4e-6 m subtracted from q keep the
+ * rule conservative under rounding (m = A ex^2 + C ey^2 bounds the magnitude
+ * of every term of q). */
+static float tau_table[8];
+static int tau_table_ready = 0;
+
+static void init_tau_table(void)
+{
+    if (tau_table_ready) return;
+    for (int k = 0; k < 8; ++k)
+        tau_table[k] = (float)(2.0 * (log(255.0) + log(1.0 + (k + 1) / 8.0)) + 0.01);
+    tau_table_ready = 1;
+}
+
+static float opacity_tau(float o)
+{
+    uint32_t bits; memcpy(&bits, &o, 4);
+    const int E = (int)((bits >> 23) & 0xffu) - 127;
+    const uint32_t k = (bits >> 20) & 7u;
+    return tau_table[k] + (float)E * 1.3862944f;
+}
+
+static float clampf(float v, float lo, float hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+static float quad_adj(float A, float B, float C, float ex, float ey)
+{
+    const float m = A * ex * ex + C * ey * ey;
+    const float q = m + 2.0f * B * ex * ey;
+    return q - 4e-6f * m;
+}
+
+static int tile_kept(float u, float v, float A, float B, float C, float tau,
+                     uint32_t tx, uint32_t ty, uint32_t ts)
+{
+    const float h = 0.5f * (float)ts - 0.5f;                       /* 7.5 for 16-pixel tiles */
+    const float xs = u - ((float)(tx * ts) + 0.5f * (float)ts);    /* splat centre in square coordinates */
+    const float ys = v - ((float)(ty * ts) + 0.5f * (float)ts);
+    const float ex1 = clampf(xs, -h, h) - xs;
+    const float ey1 = clampf(ys + (-B / C) * ex1, -h, h) - ys;
+    const float ey2 = clampf(ys, -h, h) - ys;
+    const float ex2 = clampf(xs + (-B / A) * ey2, -h, h) - xs;
+    const float q1 = quad_adj(A, B, C, ex1, ey1);
+    const float q2 = quad_adj(A, B, C, ex2, ey2);
+    const float qmin = q1 < q2 ? q1 : q2;
+    return qmin <= tau;
+}
+
+/* exported for the pins */
+float lmk_ref_opacity_tau(float o) { init_tau_table(); return opacity_tau(o); }
+int lmk_ref_tile_kept(float u, float v, float A, float B, float C, float o,
+                      uint32_t tx, uint32_t ty, uint32_t ts)
+{
+    init_tau_table();
+    return tile_kept(u, v, A, B, C, opacity_tau(o), tx, ty, ts);
+}
 
 /* clamp that sends NaN to lo */
 static float clampf_lo(float v, float lo, float hi) { return !(v > lo) ? lo : (v > hi ? hi : v); }
@@ -168,6 +237,7 @@ void lmk_ref_preprocess(uint32_t n,
     const float lim_y = 1.3f * ((0.5f * (float)cam->height) / cam->fy);
     const float *V = cam->view;
     const uint32_t ncoef = (sh_degree + 1) * (sh_degree + 1);
+    init_tau_table();
 
 #pragma omp parallel for schedule(static)
     for (int64_t ii = 0; ii < (int64_t)n; ++ii) {
@@ -235,7 +305,14 @@ void lmk_ref_preprocess(uint32_t n,
         const uint32_t x1 = (uint32_t)clampf_lo(floorf((u + hx) / TS) + 1.0f, 0.0f, fTX);
         const uint32_t y0 = (uint32_t)clampf_lo(floorf((v - hy) / TS), 0.0f, fTY);
         const uint32_t y1 = (uint32_t)clampf_lo(floorf((v + hy) / TS) + 1.0f, 0.0f, fTY);
-        const uint32_t cnt = (x1 > x0 && y1 > y0) ? (x1 - x0) * (y1 - y0) : 0u;
+        uint32_t cnt = (x1 > x0 && y1 > y0) ? (x1 - x0) * (y1 - y0) : 0u;
+        if (cnt && cam->binning == 1) {
+            const float tau = opacity_tau(o);
+            cnt = 0;
+            for (uint32_t ty = y0; ty < y1; ++ty)
+                for (uint32_t tx = x0; tx < x1; ++tx)
+                    cnt += (uint32_t)tile_kept(u, v, cA, cB, cC, tau, tx, ty, cam->tile);
+        }
 
         depth[i] = pz;
         mean2d[i] = u; mean2d[N + i] = v;
@@ -276,18 +353,26 @@ uint64_t lmk_ref_scan(uint32_t n, const uint32_t *tiles_touched, uint64_t *offse
     return run;
 }
 
-/* One (key,value) per (primitive, tile of its rectangle), rectangle walked
- * row-major, primitives in index order.
+/* One (key,value) per (primitive, kept tile of its rectangle), rectangle walked
+ * row-major, primitives in index order.  Under binning rule 0 every tile of the
+ * rectangle is kept; under rule 1 only those passing tile_kept().
  * [reading] key = tile_id << 32 | bits(depth); value = primitive index. */
 void lmk_ref_emit(uint32_t n, const uint32_t *tiles_touched, const uint16_t *rect,
                   const float *depth, const uint64_t *offsets, uint32_t tiles_x,
-                  uint64_t *keys, uint32_t *vals)
+                  uint32_t binning, uint32_t ts, const float *mean2d, const float *conic,
+                  const float *opacity, uint64_t *keys, uint32_t *vals)
 {
+    const size_t N = n;
+    init_tau_table();
     for (uint32_t i = 0; i < n; ++i) {
         if (tiles_touched[i] == 0) continue;
         uint64_t o = offsets[i];
+        const float tau = binning == 1 ? opacity_tau(opacity[i]) : 0.0f;
         for (uint32_t ty = rect[4 * i + 1]; ty < rect[4 * i + 3]; ++ty)
             for (uint32_t tx = rect[4 * i]; tx < rect[4 * i + 2]; ++tx) {
+                if (binning == 1 && !tile_kept(mean2d[i], mean2d[N + i], conic[i], conic[N + i],
+                                               conic[2 * N + i], tau, tx, ty, ts))
+                    continue;
                 keys[o] = ((uint64_t)(ty * tiles_x + tx) << 32) | f32_bits(depth[i]);
                 vals[o] = i;
                 ++o;
@@ -509,20 +594,29 @@ void lmk_ref_render_pixels_brute(uint32_t n, const uint8_t *stage, const float *
  * in which case only cap entries were written). */
 uint64_t lmk_ref_tile_list(uint32_t n, const uint32_t *tiles_touched, const uint16_t *rect,
                            const float *depth, uint32_t tile_x, uint32_t tile_y,
-                           uint32_t *out_vals, uint64_t cap)
+                           uint32_t binning, uint32_t ts, const float *mean2d, const float *conic,
+                           const float *opacity, uint32_t *out_vals, uint64_t cap)
 {
-    uint64_t m = 0;
-    for (uint32_t i = 0; i < n; ++i)
-        if (tiles_touched[i] && rect[4 * i] <= tile_x && tile_x < rect[4 * i + 2] &&
-            rect[4 * i + 1] <= tile_y && tile_y < rect[4 * i + 3])
-            ++m;
-    ref_di *p = (ref_di *)malloc((size_t)(m + 1) * sizeof(ref_di));
-    uint64_t k = 0;
-    for (uint32_t i = 0; i < n; ++i)
-        if (tiles_touched[i] && rect[4 * i] <= tile_x && tile_x < rect[4 * i + 2] &&
-            rect[4 * i + 1] <= tile_y && tile_y < rect[4 * i + 3]) {
-            p[k].bits = f32_bits(depth[i]); p[k].idx = i; ++k;
+    const size_t N = n;
+    init_tau_table();
+    ref_di *p = NULL;
+    uint64_t m = 0, have = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        uint64_t k = 0;
+        for (uint32_t i = 0; i < n; ++i) {
+            if (!(tiles_touched[i] && rect[4 * i] <= tile_x && tile_x < rect[4 * i + 2] &&
+                  rect[4 * i + 1] <= tile_y && tile_y < rect[4 * i + 3]))
+                continue;
+            if (binning == 1 && !tile_kept(mean2d[i], mean2d[N + i], conic[i], conic[N + i],
+                                           conic[2 * N + i], opacity_tau(opacity[i]), tile_x, tile_y, ts))
+                continue;
+            if (pass == 1) { p[k].bits = f32_bits(depth[i]); p[k].idx = i; }
+            ++k;
         }
+        if (pass == 0) { m = k; p = (ref_di *)malloc((size_t)(m + 1) * sizeof(ref_di)); }
+        else have = k;
+    }
+    (void)have;
     qsort(p, (size_t)m, sizeof(ref_di), di_cmp);
     for (uint64_t j = 0; j < m && j < cap; ++j) out_vals[j] = p[j].idx;
     free(p);

@@ -37,7 +37,8 @@ class RefCamera(C.Structure):
     _fields_ = [("view", C.c_float * 12), ("cam_pos", C.c_float * 3),
                 ("fx", C.c_float), ("fy", C.c_float), ("cx", C.c_float), ("cy", C.c_float),
                 ("width", C.c_uint32), ("height", C.c_uint32), ("tile", C.c_uint32),
-                ("near_z", C.c_float), ("lowpass", C.c_float), ("bg", C.c_float * 3)]
+                ("near_z", C.c_float), ("lowpass", C.c_float), ("bg", C.c_float * 3),
+                ("binning", C.c_uint32)]
 
 
 def _camera(cam: dict) -> RefCamera:
@@ -48,6 +49,7 @@ def _camera(cam: dict) -> RefCamera:
     c.width, c.height, c.tile = int(cam["width"]), int(cam["height"]), int(cam["tile"])
     c.near_z, c.lowpass = float(np.float32(cam["near_z"])), float(np.float32(cam["lowpass"]))
     c.bg[:] = [float(x) for x in np.asarray(cam["bg"], dtype=np.float32)]
+    c.binning = int(cam.get("binning", 0))
     return c
 
 
@@ -62,6 +64,10 @@ def lib():
         _lib.lmk_ref_depth_order.restype = C.c_uint32
         _lib.lmk_ref_tile_list.restype = C.c_uint64
         _lib.lmk_ref_trace_pixel.restype = C.c_uint32
+        _lib.lmk_ref_opacity_tau.restype = C.c_float
+        _lib.lmk_ref_opacity_tau.argtypes = [C.c_float]
+        _lib.lmk_ref_tile_kept.restype = C.c_int
+        _lib.lmk_ref_tile_kept.argtypes = [C.c_float] * 6 + [C.c_uint32] * 3
     return _lib
 
 
@@ -124,7 +130,9 @@ def bin_sort(pre: SimpleNamespace, cam: dict, keep_unsorted: bool = False) -> Si
     keys = np.empty(max(D, 1), np.uint64)
     vals = np.empty(max(D, 1), np.uint32)
     lib().lmk_ref_emit(C.c_uint32(n), _p(pre.tiles_touched), _p(pre.rect), _p(pre.depth),
-                       _p(offsets), C.c_uint32(tx), _p(keys), _p(vals))
+                       _p(offsets), C.c_uint32(tx), C.c_uint32(int(cam.get("binning", 0))),
+                       C.c_uint32(int(cam["tile"])), _p(pre.mean2d), _p(pre.conic), _p(pre.opacity),
+                       _p(keys), _p(vals))
     out = SimpleNamespace(D=D, offsets=offsets, tiles_x=tx, tiles_y=ty)
     if keep_unsorted:
         out.keys_unsorted = keys[:D].copy()
@@ -177,14 +185,27 @@ def render_pixels_brute(pre: SimpleNamespace, cam: dict, xs, ys, order=None) -> 
     return out
 
 
-def tile_list(pre: SimpleNamespace, tile_x: int, tile_y: int) -> np.ndarray:
-    """Sorted primitive list of one tile, straight from the definition."""
+def opacity_tau(o: float) -> float:
+    return float(lib().lmk_ref_opacity_tau(float(np.float32(o))))
+
+
+def tile_kept(u, v, A, B, Cc, o, tx, ty, ts=16) -> bool:
+    f = lambda x: float(np.float32(x))
+    return bool(lib().lmk_ref_tile_kept(f(u), f(v), f(A), f(B), f(Cc), f(o), int(tx), int(ty), int(ts)))
+
+
+def tile_list(pre: SimpleNamespace, tile_x: int, tile_y: int, cam: dict | None = None) -> np.ndarray:
+    """Sorted primitive list of one tile, straight from the definition (under the
+    camera's binning rule; rule 0 when no camera is given)."""
+    binning = int(cam.get("binning", 0)) if cam is not None else 0
+    ts = int(cam["tile"]) if cam is not None else 16
     cap = 1 << 16
     while True:
         out = np.empty(cap, np.uint32)
         m = int(lib().lmk_ref_tile_list(C.c_uint32(pre.n), _p(pre.tiles_touched), _p(pre.rect),
                                         _p(pre.depth), C.c_uint32(tile_x), C.c_uint32(tile_y),
-                                        _p(out), C.c_uint64(cap)))
+                                        C.c_uint32(binning), C.c_uint32(ts), _p(pre.mean2d), _p(pre.conic),
+                                        _p(pre.opacity), _p(out), C.c_uint64(cap)))
         if m <= cap:
             return out[:m].copy()
         cap = m

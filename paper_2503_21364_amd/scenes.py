@@ -16,7 +16,8 @@ Layout of a scene (all float32, structure of arrays, N contiguous last):
     opacity (N,)     in [0, 1] (already passed through the sigmoid)
     sh      (16, 3, N)  spherical-harmonic coefficients, degree 3
 Camera: dict with view (3x4 row-major world->camera, +x right, +y down,
-+z forward), cam_pos, fx, fy, cx, cy, width, height, tile, near_z, lowpass, bg.
++z forward), cam_pos, fx, fy, cx, cy, width, height, tile, near_z, lowpass, bg,
+binning (0: every tile of the support rectangle, 1: only tiles the splat can reach).
 """
 from __future__ import annotations
 
@@ -129,7 +130,7 @@ def look_at(eye, target, up):
 
 
 def make_camera(view34, eye, width, height, fov_deg, bg=(0.0, 0.0, 0.0),
-                tile=TILE, near=NEAR, lowpass=LOWPASS) -> dict:
+                tile=TILE, near=NEAR, lowpass=LOWPASS, binning=0) -> dict:
     """Pinhole camera; fov is the vertical field of view, square pixels."""
     f = height / (2.0 * math.tan(math.radians(fov_deg) / 2.0))
     return dict(view=np.asarray(view34, dtype=np.float32).reshape(12),
@@ -138,7 +139,7 @@ def make_camera(view34, eye, width, height, fov_deg, bg=(0.0, 0.0, 0.0),
                 cx=np.float32(width / 2.0), cy=np.float32(height / 2.0),
                 width=int(width), height=int(height), tile=int(tile),
                 near_z=np.float32(near), lowpass=np.float32(lowpass),
-                bg=np.asarray(bg, dtype=np.float32))
+                bg=np.asarray(bg, dtype=np.float32), binning=int(binning))
 
 
 def make_cameras(cfg: int, width: int | None = None, height: int | None = None) -> list[dict]:
