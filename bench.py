@@ -27,18 +27,19 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP32_PEAK_TFLOPS = 157.3     # 256 CU x 128 lanes x 2 flop x 2.4 GHz (vector FP32, packed-FMA rate)
 
 
-def algorithmic_bytes(n, n_near, n_bin, D, tiles, passes):
+def algorithmic_bytes(n, n_near, n_bin, D, tiles, passes, binning=0):
     """HBM bytes the method itself must move in preprocess + bin_sort (per frame).
 
     preprocess: mean 12 B + tiles_touched 4 B for every primitive; scale, rotation,
     opacity 32 B for those past the near plane; SH 192 B + outputs 64 B (depth 4,
     rect 8, feature record 48, reread count 4) for binned ones.
-    scan: block sums only (negligible).  emit: 16 B per binned primitive + 12 B per pair.
+    scan: block sums only (negligible).  emit: 16 B per binned primitive (+ 32 B of its
+    feature record under binning rule 1) + 12 B per pair.
     sort: one up-front histogram read of 8 B per pair, then per pass histogram read 8 B +
     scatter read 12 B + write 12 B per pair.  ranges: 8 B per pair + 8 B per tile.
     """
     b_pre = 16 * n + 32 * n_near + 256 * n_bin
-    b_emit = 4 * n + 16 * n_bin + 12 * D
+    b_emit = 4 * n + (48 if binning else 16) * n_bin + 12 * D
     b_sort = D * (8 + 32 * passes)
     b_ranges = 8 * D + 8 * (tiles + 1)
     return dict(preprocess=b_pre, emit=b_emit, sort=b_sort, ranges=b_ranges,
@@ -52,6 +53,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--cfg", type=int, default=2, help="configuration 0-4 (2 is the headline: 3M Gaussians, 1080p)")
     ap.add_argument("--n", type=int, default=None, help="override the primitive count (reported in config)")
+    ap.add_argument("--binning", type=int, default=1, choices=(0, 1),
+                    help="0: a pair for every tile of a support rectangle; 1 (default): only for tiles the "
+                         "splat can reach (same image, fewer pairs)")
     ap.add_argument("--views", type=int, default=None, help="use only the first K viewpoints of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (no blends/s either)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -77,6 +81,7 @@ def main():
     cams = scenes.make_cameras(args.cfg)
     if args.views is not None:
         cams = cams[:max(1, args.views)]
+    cams = [dict(c, binning=args.binning) for c in cams]
     ccams = [B.make_camera(c) for c in cams]
     dev = B.Scene(scene)
     tiles = ((W + 15) // 16) * ((H + 15) // 16)
@@ -173,7 +178,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg{args.cfg}: {n} Gaussians, {W}x{H}, 16x16 tiles, SH degree 3, "
                                f"{nviews} seeded viewpoints rendered back-to-back",
-                   "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity},
+                   "binning": args.binning, "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity},
         "stage_ms": {"preprocess": float(t_pre.mean()), "bin_sort": float(t_sort.mean()),
                      "render": float(t_blend.mean())},
         "per_view": [{"pairs": int(Ds[v]), "binned": stats[v]["n_bin"],
@@ -195,7 +200,8 @@ def main():
                            "flops_per_launch": float(flops / args.steps)}
         byts = []
         for v in range(nviews):
-            byts.append(algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles, passes)["total"])
+            byts.append(algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles, passes,
+                                          args.binning)["total"])
         byts = np.array(byts, dtype=np.float64)
         gbs = byts[view_of].sum() / ((t_pre.sum() + t_sort.sum()) * 1e-3) / 1e9
         out["roofline_hbm_stages"] = {"kernels": "preprocess + scan + emit + radix passes + ranges",

@@ -63,13 +63,22 @@ typedef struct lmk_gs_camera {
     float near_z;          /* primitives with camera z <= near_z are culled; must be > 0 */
     float lowpass;         /* added to the diagonal of the 2D covariance (px^2), >= 0 */
     float bg[3];           /* background colour composited behind everything */
+    uint32_t binning;      /* which tiles of a primitive's support rectangle get a (key, value) pair:
+                              0 = all of them;
+                              1 = only tiles on whose pixel-centre square the splat can reach
+                                  alpha >= 1/255 (the per-tile intersection test of Sec. 4.2.1):
+                                  min over the square of d^T conic d, in closed form, against an
+                                  upper bound of 2 ln(255 opacity) taken from the exponent and the
+                                  top three mantissa bits of the opacity.  The image is the same
+                                  under both rules; only pairs that can never contribute are dropped. */
 } lmk_gs_camera;
 
 /* Per-primitive results of lmk_gs_preprocess.  For a primitive with
  * tiles_touched == 0 (culled) the other arrays hold unspecified values. */
 typedef struct lmk_gs_projected {
     float *depth;             /* [n]     camera-space z                                       */
-    uint32_t *tiles_touched;  /* [n]     tiles overlapped by the support rectangle; 0 = culled */
+    uint32_t *tiles_touched;  /* [n]     tiles of the support rectangle that get a pair (see
+                                         lmk_gs_camera.binning); 0 = culled                    */
     uint16_t *rect;           /* [n][4]  x0,y0,x1,y1 in tile units, half-open                  */
     float *feat;              /* [n][12] u, v, conic A, B, C, opacity, r, g, b, 0, 0, 0;
                                          16-byte aligned                                       */

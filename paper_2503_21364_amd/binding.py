@@ -32,7 +32,8 @@ class Camera(C.Structure):
     _fields_ = [("view", C.c_float * 12), ("cam_pos", C.c_float * 3),
                 ("fx", C.c_float), ("fy", C.c_float), ("cx", C.c_float), ("cy", C.c_float),
                 ("width", C.c_uint32), ("height", C.c_uint32), ("tile", C.c_uint32),
-                ("near_z", C.c_float), ("lowpass", C.c_float), ("bg", C.c_float * 3)]
+                ("near_z", C.c_float), ("lowpass", C.c_float), ("bg", C.c_float * 3),
+                ("binning", C.c_uint32)]
 
 
 class Projected(C.Structure):
@@ -98,6 +99,7 @@ def make_camera(cam: dict) -> Camera:
     c.width, c.height, c.tile = int(cam["width"]), int(cam["height"]), int(cam["tile"])
     c.near_z, c.lowpass = float(np.float32(cam["near_z"])), float(np.float32(cam["lowpass"]))
     c.bg[:] = [float(x) for x in np.asarray(cam["bg"], dtype=np.float32)]
+    c.binning = int(cam.get("binning", 0))
     return c
 
 

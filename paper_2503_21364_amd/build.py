@@ -3,9 +3,10 @@
     python -m paper_2503_21364_amd.build
 
 Every translation unit is compiled with packed-FP32 instruction selection
-switched off.  preprocess.hip and api.hip additionally run with floating-point
-contraction off and correctly rounded divide/sqrt, because they hold the
-arithmetic that decides integers (depth bits, tile rectangles, culls).
+switched off.  preprocess.hip, binsort.hip and api.hip additionally run with
+floating-point contraction off and correctly rounded divide/sqrt, because they
+hold the arithmetic that decides integers (depth bits, tile rectangles, culls,
+the tile intersection test).
 """
 from __future__ import annotations
 
@@ -28,7 +29,7 @@ EXACT = ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"]
 UNITS = {
     "api.hip": EXACT,
     "preprocess.hip": EXACT,
-    "binsort.hip": [],
+    "binsort.hip": EXACT,       # the tile intersection test of binning rule 1 decides integers too
     "render.hip": [],
 }
 

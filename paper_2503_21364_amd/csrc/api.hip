@@ -48,6 +48,9 @@ int32_t check_camera(const lmk_gs_camera *cam, ProjParams *pp)
     pp->lim_y = 1.3f * ((0.5f * (float)cam->height) / cam->fy);
     pp->tiles_x = tx;
     pp->tiles_y = ty;
+    if (cam->binning > 1u) return LMK_GS_ERR_INVALID;
+    for (int k = 0; k < 8; ++k)
+        pp->tau_tab[k] = (float)(2.0 * (std::log(255.0) + std::log(1.0 + (k + 1) / 8.0)) + 0.01);
     return LMK_GS_OK;
 }
 
@@ -100,6 +103,7 @@ int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_c
     if (rc != LMK_GS_OK) return rc;
     if (!proj || !out || !scratch) return LMK_GS_ERR_INVALID;
     if (n > 0 && (!proj->depth || !proj->tiles_touched || !proj->rect)) return LMK_GS_ERR_INVALID;
+    if (n > 0 && cam->binning == 1u && (!proj->feat || !aligned(proj->feat, 16))) return LMK_GS_ERR_INVALID;
     if (!out->tile_offsets) return LMK_GS_ERR_INVALID;
     if (out->capacity > 0 && (!out->keys || !out->vals || !out->keys_alt || !out->vals_alt))
         return LMK_GS_ERR_INVALID;

@@ -99,6 +99,135 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     }
 }
 
+// ---------------------------------------------------------------- emit, binning rule 1
+// Same expansion over the slots of every support rectangle, but each slot is first put
+// through the splat/tile intersection test of lmk_gs_camera.binning == 1 (identical
+// arithmetic to the count in the preprocess kernel; this translation unit is compiled
+// without floating-point contraction for that reason) and the kept slots are compacted:
+// the output position of a kept slot is the workgroup's base plus the number of kept
+// slots before it, so pairs still come out in (primitive, row-major tile) order.
+struct EmitTest { float u, v, A, B, C, rx, ry, tau; };
+
+__device__ __forceinline__ float emit_clampf(float v, float lo, float hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+__device__ __forceinline__ float emit_quad_adj(float A, float B, float C, float ex, float ey)
+{
+    const float m = A * ex * ex + C * ey * ey;
+    const float q = m + 2.0f * B * ex * ey;
+    return q - 4e-6f * m;
+}
+
+__global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
+    const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
+    const float *__restrict__ depth, const float4 *__restrict__ feat, ProjParams pp,
+    const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
+    u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
+    ScratchHeader *__restrict__ header)
+{
+    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of rectangle areas inside the workgroup
+    __shared__ ushort4 s_rect[kPreBlock];
+    __shared__ u32 s_depth[kPreBlock];
+    __shared__ float4 s_t0[kPreBlock];    // u, v, A, B
+    __shared__ float4 s_t1[kPreBlock];    // C, rx, ry, tau
+    __shared__ u32 s_wave[kPreBlock / kWave];
+    __shared__ u32 s_wave2[kPreBlock / kWave];
+
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 i = blockIdx.x * kPreBlock + tid;
+    const u32 kept_cnt = i < n ? tiles_touched[i] : 0u;
+    u32 area = 0;
+    if (kept_cnt) {
+        const ushort4 r = rect[i];
+        s_rect[tid] = r;
+        area = ((u32)r.z - (u32)r.x) * ((u32)r.w - (u32)r.y);
+        s_depth[tid] = __float_as_uint(depth[i]);
+        const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
+        const float4 f0 = f[0], f1 = f[1];
+        const u32 bits = __float_as_uint(f1.y);
+        const int E = (int)((bits >> 23) & 0xffu) - 127;
+        const float tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
+        s_t0[tid] = f0;
+        s_t1[tid] = make_float4(f1.x, -f0.w / f0.z, -f0.w / f1.x, tau);
+    }
+    // prefix sums over the workgroup: rectangle areas (slot ownership) and kept counts (offsets[])
+    u32 incl = area, incl2 = kept_cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const u32 t = __shfl_up(incl, o, 64), t2 = __shfl_up(incl2, o, 64);
+        if ((int)lane >= o) { incl += t; incl2 += t2; }
+    }
+    if (lane == kWave - 1) { s_wave[wv] = incl; s_wave2[wv] = incl2; }
+    __syncthreads();
+    u32 wave_base = 0, total = 0, wave_base2 = 0, total2 = 0;
+#pragma unroll
+    for (u32 k = 0; k < kPreBlock / kWave; ++k) {
+        const u32 w = s_wave[k], w2 = s_wave2[k];
+        if (k < wv) { wave_base += w; wave_base2 += w2; }
+        total += w; total2 += w2;
+    }
+    s_excl[tid] = wave_base + incl - area;
+    const u64 base = block_offsets[blockIdx.x];
+    if (offsets) {
+        if (i < n) offsets[i] = base + (wave_base2 + incl2 - kept_cnt);
+        if (i == n - 1) offsets[n] = base + total2;
+    }
+    if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
+    __syncthreads();
+
+    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
+    u32 running = 0;                                       // kept slots of earlier rounds (uniform)
+    for (u32 j0 = 0; j0 < total; j0 += kPreBlock) {
+        const u32 j = j0 + tid;
+        bool keep = false;
+        u32 lo = 0, tile = 0;
+        if (j < total) {
+            u32 hi = kPreBlock - 1;
+            while (lo < hi) {
+                const u32 mid = (lo + hi + 1) >> 1;
+                if (s_excl[mid] <= j) lo = mid; else hi = mid - 1;
+            }
+            const ushort4 r = s_rect[lo];
+            const u32 local = j - s_excl[lo];
+            const u32 w = (u32)r.z - (u32)r.x;
+            const u32 row = local / w;
+            const u32 tx = (u32)r.x + (local - row * w);
+            const u32 ty = (u32)r.y + row;
+            tile = ty * tiles_x + tx;
+            const float4 t0 = s_t0[lo], t1 = s_t1[lo];
+            const float xs = t0.x - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+            const float ys = t0.y - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+            const float ex1 = emit_clampf(xs, -h, h) - xs;
+            const float ey1 = emit_clampf(ys + t1.z * ex1, -h, h) - ys;
+            const float ey2 = emit_clampf(ys, -h, h) - ys;
+            const float ex2 = emit_clampf(xs + t1.y * ey2, -h, h) - xs;
+            const float q1 = emit_quad_adj(t0.z, t0.w, t1.x, ex1, ey1);
+            const float q2 = emit_quad_adj(t0.z, t0.w, t1.x, ex2, ey2);
+            const float qmin = q1 < q2 ? q1 : q2;
+            keep = qmin <= t1.w;
+        }
+        const u64 mask = __builtin_amdgcn_ballot_w64(keep);
+        const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+        __syncthreads();                                   // s_wave free again
+        if (lane == 0) s_wave[wv] = (u32)__builtin_popcountll(mask);
+        __syncthreads();
+        u32 before = 0, round_total = 0;
+#pragma unroll
+        for (u32 k = 0; k < kPreBlock / kWave; ++k) {
+            const u32 c = s_wave[k];
+            if (k < wv) before += c;
+            round_total += c;
+        }
+        if (keep) {
+            const u64 pos = base + running + before + rank;
+            if (pos < capacity) {
+                keys[pos] = ((u64)tile << 32) | (u64)s_depth[lo];
+                vals[pos] = blockIdx.x * kPreBlock + lo;
+            }
+        }
+        running += round_total;
+    }
+}
+
 // ---------------------------------------------------------------- radix sort
 // (0a) one read of the keys: digit histograms of every pass, one partial per workgroup
 constexpr u32 kPrehistUnroll = 8;
@@ -472,9 +601,15 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     u32 *vout = (plan.passes & 1u) ? out.vals : out.vals_alt;
 
     if (L.pre_blocks > 0) {
-        hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
-                           proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                           block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header);
+        if (pp.cam.binning == 1u)
+            hipLaunchKernelGGL(emit_tight_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                               proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
+                               reinterpret_cast<const float4 *>(proj.feat), pp,
+                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header);
+        else
+            hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                               proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
+                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

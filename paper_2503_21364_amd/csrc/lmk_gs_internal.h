@@ -94,6 +94,7 @@ struct ProjParams {
     lmk_gs_camera cam;
     float lim_x, lim_y;   // guard band on x/z, y/z for the EWA Jacobian
     u32 tiles_x, tiles_y;
+    float tau_tab[8];     // binning rule 1: 2 (ln 255 + ln(1 + (k+1)/8)) + 0.01, k = top 3 mantissa bits of opacity
 };
 
 // Launchers (each returns the hipError_t of its launches).

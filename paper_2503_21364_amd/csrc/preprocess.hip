@@ -41,6 +41,53 @@ __device__ __forceinline__ float clamp_nan_lo(float v, float lo, float hi)
     return !(v > lo) ? lo : (v > hi ? hi : v);
 }
 
+// ---- binning rule 1: can the splat reach alpha >= 1/255 on the square spanned by a tile's
+// pixel centres?  q(d) = d^T conic d is convex: its minimum over the square is at the splat
+// centre if inside, else on an edge facing it (clamp one coordinate, minimise along that line).
+// Contributing needs q <= 2 ln(255 o); tau bounds that from above from the exponent and the top
+// three mantissa bits of o (table from the host), so no run-time logarithm decides an integer.
+// Same fp32 operation sequence as the CPU definition of the rule; see include/lmk_gs.h.
+struct TileTest { float u, v, A, B, C, rx, ry, tau; };
+
+__device__ __forceinline__ float opacity_tau(const ProjParams &pp, float o)
+{
+    const u32 bits = __float_as_uint(o);
+    const int E = (int)((bits >> 23) & 0xffu) - 127;
+    return pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
+}
+
+__device__ __forceinline__ TileTest make_tile_test(float u, float v, float A, float B, float C, float tau)
+{
+    TileTest t;
+    t.u = u; t.v = v; t.A = A; t.B = B; t.C = C; t.tau = tau;
+    t.rx = -B / A; t.ry = -B / C;
+    return t;
+}
+
+__device__ __forceinline__ float clampf3(float v, float lo, float hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+__device__ __forceinline__ float quad_adj(const TileTest &t, float ex, float ey)
+{
+    const float m = t.A * ex * ex + t.C * ey * ey;
+    const float q = m + 2.0f * t.B * ex * ey;
+    return q - 4e-6f * m;
+}
+
+__device__ __forceinline__ bool tile_kept(const TileTest &t, u32 tx, u32 ty)
+{
+    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
+    const float xs = t.u - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+    const float ys = t.v - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+    const float ex1 = clampf3(xs, -h, h) - xs;
+    const float ey1 = clampf3(ys + t.ry * ex1, -h, h) - ys;
+    const float ey2 = clampf3(ys, -h, h) - ys;
+    const float ex2 = clampf3(xs + t.rx * ey2, -h, h) - xs;
+    const float q1 = quad_adj(t, ex1, ey1);
+    const float q2 = quad_adj(t, ex2, ey2);
+    const float qmin = q1 < q2 ? q1 : q2;
+    return qmin <= t.tau;
+}
+
 __device__ __forceinline__ u32 wave_sum(u32 v)
 {
 #pragma unroll
@@ -58,14 +105,17 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     __shared__ u32 s_part[kPreBlock / kWave];
     const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
     const size_t N = n;
-    u32 cnt = 0;
+    u32 cnt = 0;            // tiles of the support rectangle (then: tiles kept)
+    float mx = 0.f, my = 0.f, mz = 0.f, pz = 0.f, o = 0.f;
+    float u = 0.f, v = 0.f, cA = 1.f, cB = 0.f, cC = 1.f;
+    u32 x0 = 0, y0 = 0, x1 = 0, y1 = 0;
 
     if (i < n) {
         const float *V = pp.cam.view;
-        const float mx = mean[i], my = mean[N + i], mz = mean[2 * N + i];
+        mx = mean[i]; my = mean[N + i]; mz = mean[2 * N + i];
         const float px = V[0] * mx + V[1] * my + V[2] * mz + V[3];
         const float py = V[4] * mx + V[5] * my + V[6] * mz + V[7];
-        const float pz = V[8] * mx + V[9] * my + V[10] * mz + V[11];
+        pz = V[8] * mx + V[9] * my + V[10] * mz + V[11];
         if (pz > pp.cam.near_z) {
             // Sigma = (R S)(R S)^T from the normalised quaternion
             const float qw0 = rot[i], qx0 = rot[N + i], qy0 = rot[2 * N + i], qz0 = rot[3 * N + i];
@@ -112,20 +162,62 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
             const float c = (U10 * T10 + U11 * T11 + U12 * T12) + pp.cam.lowpass;
 
             const float det = a * c - b * b;
-            const float o = opacity[i];
+            o = opacity[i];
             if (det > 0.0f && !(o < 1.0f / 255.0f)) {
-                const float cA = c / det, cB = -b / det, cC = a / det;
-                const float u = (pp.cam.fx * px) / pz + pp.cam.cx;
-                const float v = (pp.cam.fy * py) / pz + pp.cam.cy;
+                cA = c / det; cB = -b / det; cC = a / det;
+                u = (pp.cam.fx * px) / pz + pp.cam.cx;
+                v = (pp.cam.fy * py) / pz + pp.cam.cy;
                 const float hx = sqrtf(11.09f * a);
                 const float hy = sqrtf(11.09f * c);
                 const float TS = (float)LMK_GS_TILE;
                 const float fTX = (float)pp.tiles_x, fTY = (float)pp.tiles_y;
-                const u32 x0 = (u32)clamp_nan_lo(floorf((u - hx) / TS), 0.0f, fTX);
-                const u32 x1 = (u32)clamp_nan_lo(floorf((u + hx) / TS) + 1.0f, 0.0f, fTX);
-                const u32 y0 = (u32)clamp_nan_lo(floorf((v - hy) / TS), 0.0f, fTY);
-                const u32 y1 = (u32)clamp_nan_lo(floorf((v + hy) / TS) + 1.0f, 0.0f, fTY);
+                x0 = (u32)clamp_nan_lo(floorf((u - hx) / TS), 0.0f, fTX);
+                x1 = (u32)clamp_nan_lo(floorf((u + hx) / TS) + 1.0f, 0.0f, fTX);
+                y0 = (u32)clamp_nan_lo(floorf((v - hy) / TS), 0.0f, fTY);
+                y1 = (u32)clamp_nan_lo(floorf((v + hy) / TS) + 1.0f, 0.0f, fTY);
                 cnt = (x1 > x0 && y1 > y0) ? (x1 - x0) * (y1 - y0) : 0u;
+            }
+        }
+    }
+
+    // binning rule 1: count only the tiles of the rectangle that the splat can reach.
+    // Small rectangles are walked by their own lane; large ones one at a time by the whole
+    // wavefront (64 tiles per step), so that one huge splat does not stall 63 idle lanes.
+    if (pp.cam.binning == 1u) {
+        const TileTest tt = make_tile_test(u, v, cA, cB, cC, opacity_tau(pp, o));
+        const u32 area = cnt, w = x1 - x0;
+        constexpr u32 kOwn = 16;
+        u32 kept = 0;
+        if (area > 0 && area <= kOwn) {
+            for (u32 ty = y0; ty < y1; ++ty)
+                for (u32 tx = x0; tx < x1; ++tx) kept += tile_kept(tt, tx, ty) ? 1u : 0u;
+        }
+        u64 big = __builtin_amdgcn_ballot_w64(area > kOwn);
+        const u32 lane = threadIdx.x & (kWave - 1);
+        while (big != 0ull) {
+            const int src = (int)__builtin_ctzll(big);
+            big &= big - 1ull;
+            TileTest bt;
+            bt.u = __shfl(tt.u, src, 64); bt.v = __shfl(tt.v, src, 64);
+            bt.A = __shfl(tt.A, src, 64); bt.B = __shfl(tt.B, src, 64); bt.C = __shfl(tt.C, src, 64);
+            bt.rx = __shfl(tt.rx, src, 64); bt.ry = __shfl(tt.ry, src, 64); bt.tau = __shfl(tt.tau, src, 64);
+            const u32 bx0 = __shfl(x0, src, 64), by0 = __shfl(y0, src, 64);
+            const u32 bw = __shfl(w, src, 64), barea = __shfl(area, src, 64);
+            u32 c = 0;
+            for (u32 t = lane; t < barea; t += kWave) {
+                const u32 row = t / bw;
+                c += tile_kept(bt, bx0 + (t - row * bw), by0 + row) ? 1u : 0u;
+            }
+#pragma unroll
+            for (int o2 = 32; o2 > 0; o2 >>= 1) c += __shfl_xor(c, o2, 64);
+            if ((int)lane == src) kept = c;
+        }
+        cnt = kept;
+    }
+
+    if (i < n) {
+        {
+            {
                 if (cnt) {
                     // view-dependent colour: 0.5 + sum_k Y_k(dir) sh_k, clamped at 0
                     float dx = mx - pp.cam.cam_pos[0], dy = my - pp.cam.cam_pos[1], dz = mz - pp.cam.cam_pos[2];

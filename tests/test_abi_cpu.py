@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_the_header():
     # plain 4- and 8-byte fields in declaration order, no padding surprises
-    assert C.sizeof(B.Camera) == 4 * (12 + 3 + 4 + 3 + 2 + 3)
+    assert C.sizeof(B.Camera) == 4 * (12 + 3 + 4 + 3 + 2 + 3 + 1)
     assert C.sizeof(B.Gaussians) == 5 * 8 + 2 * 4
     assert C.sizeof(B.Projected) == 5 * 8
     assert C.sizeof(B.Binned) == 7 * 8
@@ -99,6 +99,8 @@ def test_preprocess_rejects_bad_arguments_without_touching_the_gpu():
     bad = _good_camera(); bad.view[5] = float("inf")
     assert call(g, bad, proj) == B.ERR_INVALID
     bad = _good_camera(); bad.near_z = 0.0
+    assert call(g, bad, proj) == B.ERR_INVALID
+    bad = _good_camera(); bad.binning = 2
     assert call(g, bad, proj) == B.ERR_INVALID
     g2, _, _ = _args(); g2.sh_degree = 4
     assert call(g2, cam, proj) == B.ERR_INVALID

@@ -28,17 +28,18 @@ def _tile_counts_from_rects(pre, tx, ty):
     return diff.cumsum(axis=0).cumsum(axis=1)[:ty, :tx]
 
 
-def test_cfg4_full_size_sampled():
+@pytest.mark.parametrize("binning", [0, 1])
+def test_cfg4_full_size_sampled(binning):
     free, _ = torch.cuda.mem_get_info()
     if free < 180 * 2**30:
         pytest.skip(f"needs ~165 GB of free device memory, {free / 2**30:.0f} GB available")
     sc = scenes.make_scene(4)
-    cam = scenes.make_cameras(4)[0]
+    cam = dict(scenes.make_cameras(4)[0], binning=binning)
     W, H = int(cam["width"]), int(cam["height"])
     pre = ref.preprocess(sc, cam)
     D = int(pre.tiles_touched.astype(np.uint64).sum())
-    assert D > 5_000_000_000
-    print(f"[parity] cfg4 full: D={D}", flush=True)
+    assert D > (5_000_000_000 if binning == 0 else 2_000_000_000)
+    print(f"[parity] cfg4 full, binning {binning}: D={D}", flush=True)
 
     dev = B.Scene(sc)
     fr = B.Frame(dev.n, W, H, D + 4096, want_offsets=False)
@@ -50,10 +51,13 @@ def test_cfg4_full_size_sampled():
     P.compare_projected(fr, pre)
 
     tx, ty = fr.tiles_x, fr.tiles_y
-    counts = _tile_counts_from_rects(pre, tx, ty).reshape(-1)
-    expect_offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.uint64)
     tile_offsets = P.to_np(fr.tile_offsets).view(np.uint64)
-    np.testing.assert_array_equal(tile_offsets, expect_offsets)
+    assert tile_offsets[0] == 0 and tile_offsets[-1] == D
+    assert np.all(np.diff(tile_offsets.astype(np.int64)) >= 0)
+    if binning == 0:
+        counts = _tile_counts_from_rects(pre, tx, ty).reshape(-1)
+        expect_offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.uint64)
+        np.testing.assert_array_equal(tile_offsets, expect_offsets)
 
     rng = np.random.default_rng(44)
     tiles = [(0, 0), (tx - 1, ty - 1), (tx // 2, ty // 2)] + \
@@ -61,7 +65,7 @@ def test_cfg4_full_size_sampled():
     worst = 0.0
     for (cx, cy) in tiles:
         t = cy * tx + cx
-        lst = ref.tile_list(pre, cx, cy)
+        lst = ref.tile_list(pre, cx, cy, cam)
         a, b = int(tile_offsets[t]), int(tile_offsets[t + 1])
         assert b - a == len(lst)
         np.testing.assert_array_equal(P.to_np(fr.vals[a:b]).view(np.uint32), lst, err_msg=f"tile {cx},{cy} values")

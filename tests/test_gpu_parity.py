@@ -83,6 +83,43 @@ def test_cfg4_distributions_reduced_count():
     assert r.stats["D"] / r.stats["visible"] > 300   # hundreds of tiles per primitive
 
 
+# ------------------------------------------------------------------ binning rule 1
+def _tight(cam):
+    return dict(cam, binning=1)
+
+
+@pytest.mark.parametrize("w,h,n,seed,scale_mul", [
+    (37, 23, 1000, 71, 1.0),
+    (256, 256, 257, 5, 4.0),        # rectangles of a few dozen tiles: the wavefront-cooperative count
+    (640, 360, 30011, 6, 2.0),
+    (16, 16, 500, 8, 6.0),
+])
+def test_binning1_small_ragged(w, h, n, seed, scale_mul):
+    sc = scenes.make_scene(0, n=n, seed=seed)
+    sc["scale"] *= np.float32(scale_mul)
+    cam = _tight(scenes.make_cameras(0, w, h)[0])
+    cam["bg"] = np.array([0.25, 0.5, 0.125], np.float32)
+    r = P.full_compare(sc, cam)
+    _report(f"binning1 ragged {w}x{h} n={n}", r.stats)
+
+
+def test_binning1_configs_and_image_equal_to_rule0():
+    for cfg, view, n, wh in [(0, 0, None, None), (1, 0, None, None), (2, 0, None, None), (2, 5, None, None),
+                             (4, 0, 20_000, (1920, 1080))]:
+        sc = scenes.make_scene(cfg, n=n)
+        cam0 = scenes.make_cameras(cfg, *(wh or (None, None)))[view]
+        dev = B.Scene(sc)
+        r1 = P.full_compare(sc, _tight(cam0), scene_dev=dev)
+        _report(f"binning1 cfg{cfg} view {view}", r1.stats)
+        fr0 = P.gpu_frame(dev, cam0, r1.stats["D"] * 3 + 1000)
+        D0, _ = B.read_status(fr0)
+        assert r1.stats["D"] < D0
+        # dropping pairs that cannot contribute leaves every pixel exactly as it was
+        assert torch.equal(fr0.out_rgb, r1.gpu.out_rgb) and torch.equal(fr0.out_T, r1.gpu.out_T)
+        del r1, fr0, dev
+        torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ degenerate inputs
 def test_empty_scene():
     sc = scenes.make_scene(0, n=0)
