@@ -112,16 +112,20 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
 
     if (i < n) {
         const float *V = pp.cam.view;
-        mx = mean[i]; my = mean[N + i]; mz = mean[2 * N + i];
+        // inputs are read exactly once per frame: stream them past the caches
+        mx = __builtin_nontemporal_load(mean + i); my = __builtin_nontemporal_load(mean + N + i);
+        mz = __builtin_nontemporal_load(mean + 2 * N + i);
         const float px = V[0] * mx + V[1] * my + V[2] * mz + V[3];
         const float py = V[4] * mx + V[5] * my + V[6] * mz + V[7];
         pz = V[8] * mx + V[9] * my + V[10] * mz + V[11];
         if (pz > pp.cam.near_z) {
             // Sigma = (R S)(R S)^T from the normalised quaternion
-            const float qw0 = rot[i], qx0 = rot[N + i], qy0 = rot[2 * N + i], qz0 = rot[3 * N + i];
+            const float qw0 = __builtin_nontemporal_load(rot + i), qx0 = __builtin_nontemporal_load(rot + N + i);
+            const float qy0 = __builtin_nontemporal_load(rot + 2 * N + i), qz0 = __builtin_nontemporal_load(rot + 3 * N + i);
             const float qn = sqrtf(qw0 * qw0 + qx0 * qx0 + qy0 * qy0 + qz0 * qz0);
             const float w = qw0 / qn, x = qx0 / qn, y = qy0 / qn, z = qz0 / qn;
-            const float s0 = scale[i], s1 = scale[N + i], s2 = scale[2 * N + i];
+            const float s0 = __builtin_nontemporal_load(scale + i), s1 = __builtin_nontemporal_load(scale + N + i);
+            const float s2 = __builtin_nontemporal_load(scale + 2 * N + i);
             const float M00 = (1.0f - 2.0f * (y * y + z * z)) * s0;
             const float M01 = (2.0f * (x * y - w * z)) * s1;
             const float M02 = (2.0f * (x * z + w * y)) * s2;
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
             const float c = (U10 * T10 + U11 * T11 + U12 * T12) + pp.cam.lowpass;
 
             const float det = a * c - b * b;
-            o = opacity[i];
+            o = __builtin_nontemporal_load(opacity + i);
             if (det > 0.0f && !(o < 1.0f / 255.0f)) {
                 cA = c / det; cB = -b / det; cC = a / det;
                 u = (pp.cam.fx * px) / pz + pp.cam.cx;
@@ -252,9 +256,9 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
 #pragma unroll
                     for (u32 k = 0; k < 16; ++k) {
                         if (k < ncoef) {
-                            r += Y[k] * c0[(size_t)(3 * k + 0) * N];
-                            g += Y[k] * c0[(size_t)(3 * k + 1) * N];
-                            bl += Y[k] * c0[(size_t)(3 * k + 2) * N];
+                            r += Y[k] * __builtin_nontemporal_load(c0 + (size_t)(3 * k + 0) * N);
+                            g += Y[k] * __builtin_nontemporal_load(c0 + (size_t)(3 * k + 1) * N);
+                            bl += Y[k] * __builtin_nontemporal_load(c0 + (size_t)(3 * k + 2) * N);
                         }
                     }
                     r = fmaxf(r, 0.0f); g = fmaxf(g, 0.0f); bl = fmaxf(bl, 0.0f);
