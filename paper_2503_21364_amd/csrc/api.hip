@@ -68,7 +68,7 @@ int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height, uint
     const uint32_t ty = (height + LMK_GS_TILE - 1) / LMK_GS_TILE;
     if (tx > kMaxTilesPerAxis || ty > kMaxTilesPerAxis || (uint64_t)tx * ty > kMaxTiles)
         return LMK_GS_ERR_UNSUPPORTED;
-    *scratch_bytes = scratch_layout(n, capacity).total;
+    *scratch_bytes = scratch_layout(n, capacity, tx * ty).total;
     return LMK_GS_OK;
 }
 
@@ -88,7 +88,7 @@ int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
     }
     if (!aligned(scratch, 256)) return LMK_GS_ERR_INVALID;
     // the part of the scratch this call touches does not depend on the pair capacity
-    const ScratchLayout L = scratch_layout(g->n, 0);
+    const ScratchLayout L = scratch_layout(g->n, 0, 0);
     if (scratch_bytes < L.digit_totals) return LMK_GS_ERR_CAPACITY;
     const hipError_t e = launch_preprocess(*g, pp, *out, static_cast<char *>(scratch), L,
                                            static_cast<hipStream_t>(stream));
@@ -108,7 +108,7 @@ int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_c
     if (out->capacity > 0 && (!out->keys || !out->vals || !out->keys_alt || !out->vals_alt))
         return LMK_GS_ERR_INVALID;
     if (!aligned(scratch, 256) || !aligned(proj->rect, 8)) return LMK_GS_ERR_INVALID;
-    const ScratchLayout L = scratch_layout(n, out->capacity);
+    const ScratchLayout L = scratch_layout(n, out->capacity, pp.tiles_x * pp.tiles_y);
     if (scratch_bytes < L.total) return LMK_GS_ERR_CAPACITY;
     const hipError_t e = launch_bin_sort(*proj, n, pp, *out, static_cast<char *>(scratch), L,
                                          static_cast<hipStream_t>(stream));

@@ -11,18 +11,24 @@
 //            workgroup's output slots are dealt round-robin to its threads and
 //            each slot finds its primitive by binary search in an LDS prefix
 //            array, so stores are contiguous whatever the rectangle sizes are.
-//   sort     stable LSD radix sort, digits of up to 9 bits (5 passes at 1080p).
-//            One up-front kernel reads the keys once and builds the global digit
-//            histogram of every pass (so every pass knows where each digit's
-//            output starts).  Per pass: (1) digit counts of every 4096-pair sort
-//            tile, (2) one workgroup per digit turns its row of counts into
-//            output offsets, (3) scatter: wavefront match-any ranking (ballots
-//            over the digit bits) keeps equal digits in order, the tile is
-//            sorted by digit in LDS and written out in contiguous runs.
-//            (A single-kernel pass with a chained scan over tiles was measured
-//            slower here: with 512 counters per tile the look-back chain costs
-//            more than the two extra small kernels.)
-//   ranges   tile_offsets[t] = first sorted position whose tile id is >= t.
+//   partition  stable LSD radix sort over the TILE bits of the keys only (two passes
+//            of 7 + 6 bits at 1080p).  One up-front kernel builds the global digit
+//            histogram of both passes; per pass: (1) digit counts of every 4096-pair
+//            sort tile, (2) one workgroup per digit turns its row of counts into
+//            output offsets, (3) scatter: wavefront match-any ranking (ballots over
+//            the digit bits) keeps equal digits in order, the tile is sorted by
+//            digit in LDS and written out in contiguous runs (128 or fewer bins, so
+//            runs are long and writes fill whole cache lines).
+//   ranges   tile_offsets[t] = first position whose tile id is >= t.
+//   order    tile ids by descending list length; chunk table (4096-pair chunks).
+//   tile sort  every chunk of every tile's list is sorted by (depth bits, index)
+//            in LDS by one workgroup (bitonic network on 64-bit composites; the
+//            order is total, so no stability is needed).  Lists of up to 4096
+//            pairs -- all but a few hundred tiles at 1080p -- are finished here.
+//   merge    a tile whose list is longer merges its sorted chunks pairwise,
+//            ping-ponging between the two pair buffers, one workgroup per tile.
+//            Sorting 32 depth bits this way costs one read and one write of the
+//            pairs instead of four radix passes over all of them.
 #include "lmk_gs_internal.h"
 
 namespace lmk {
@@ -546,16 +552,21 @@ __global__ __launch_bounds__(256) void tile_ranges_kernel(
     }
 }
 
-// ---------------------------------------------------------------- schedule hint
+// ---------------------------------------------------------------- order + chunk table
 // Tile ids by descending list length, bucketed by the position of the length's top bit
-// (one workgroup; within a bucket the order is whatever the atomics give -- it only
-// decides which workgroup of the blend kernel starts first, never a result).
+// (within a bucket the order is whatever the atomics give -- it only decides which
+// workgroup starts first, never a result), and the exclusive prefix of chunks per tile.
+// One workgroup.
 __global__ __launch_bounds__(1024) void tile_order_kernel(
-    const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order)
+    const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order,
+    u32 *__restrict__ order_copy, u32 *__restrict__ chunk_start)
 {
     __shared__ u32 s_cnt[65];
-    const u32 tid = threadIdx.x;
+    __shared__ u32 s_wave[1024 / kWave];
+    __shared__ u32 s_carry;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     if (tid < 65) s_cnt[tid] = 0;
+    if (tid == 0) s_carry = 0;
     __syncthreads();
     for (u32 t = tid; t < num_tiles; t += 1024) {
         const u64 len = tile_offsets[t + 1] - tile_offsets[t];
@@ -571,7 +582,243 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
     for (u32 t = tid; t < num_tiles; t += 1024) {
         const u64 len = tile_offsets[t + 1] - tile_offsets[t];
         const u32 b = len ? 64u - (u32)__builtin_clzll(len) : 0u;
-        order[atomicAdd(&s_cnt[64 - b], 1u)] = t;
+        const u32 slot = atomicAdd(&s_cnt[64 - b], 1u);
+        order[slot] = t;
+        if (order_copy) order_copy[slot] = t;
+    }
+    // chunk_start[t] = number of chunks of the tiles before t
+    for (u32 base = 0; base < num_tiles; base += 1024) {
+        const u32 t = base + tid;
+        u32 c = 0;
+        if (t < num_tiles) {
+            const u64 len = tile_offsets[t + 1] - tile_offsets[t];
+            c = len > 512 ? (u32)((len + kChunk - 1) / kChunk) : 0u;   // short lists go to the one-wavefront sort
+        }
+        u32 incl = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const u32 v = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += v;
+        }
+        __syncthreads();
+        if (lane == kWave - 1) s_wave[wv] = incl;
+        __syncthreads();
+        u32 run = s_carry + incl - c;
+        for (u32 k = 0; k < wv; ++k) run += s_wave[k];
+        if (t < num_tiles) chunk_start[t] = run;
+        __syncthreads();
+        if (tid == 1023) s_carry = run + c;
+        __syncthreads();
+    }
+    if (tid == 0) chunk_start[num_tiles] = s_carry;
+}
+
+// ---------------------------------------------------------------- per-tile sort
+// Sorts up to THREADS * ITEMS pairs of one tile by (depth bits, index) with a merge sort:
+// each thread sorts ITEMS composites in registers (a fixed network, no memory traffic),
+// then the sorted runs are merged pairwise through LDS, run length doubling: a thread finds
+// where its ITEMS outputs start in the two runs (merge-path binary search) and merges them
+// sequentially.  About 25 LDS accesses per element, against ~150 for a bitonic network over
+// the whole chunk.  Runs are stored with one padding slot per 16 elements so that the
+// strided accesses of neighbouring threads spread over the LDS banks.  Two instances:
+// 64 threads x 8 (one wavefront per short list, which is most tiles) and 256 x 16.
+__device__ __forceinline__ u32 ts_slot(u32 p) { return p + (p >> 4); }
+
+__device__ __forceinline__ void ts_cswap(u64 &a, u64 &b)
+{
+    const u64 lo = a < b ? a : b, hi = a < b ? b : a;
+    a = lo; b = hi;
+}
+
+template <u32 THREADS, u32 ITEMS>
+__device__ __forceinline__ void sort_pairs_in_lds(u64 *__restrict__ keys, u32 *__restrict__ vals,
+                                                  u64 beg, u32 n, u32 tile, u64 *s)
+{
+    constexpr u32 CAP = THREADS * ITEMS;
+    const u32 tid = threadIdx.x;
+    const u32 m = (n + ITEMS - 1) / ITEMS * ITEMS;          // elements in play: n rounded up to whole runs
+    // coalesced load into LDS; composites beyond n are the maximum value and sort to the end
+    for (u32 i = tid; i < m; i += THREADS)
+        s[ts_slot(i)] = i < n ? ((keys[beg + i] << 32) | (u64)vals[beg + i]) : ~0ull;
+    __syncthreads();
+    const u32 o0 = tid * ITEMS;
+    const bool active = o0 < m;
+    u64 e[ITEMS];
+    if (active) {
+#pragma unroll
+        for (u32 k = 0; k < ITEMS; ++k) e[k] = s[ts_slot(o0 + k)];
+        // sort the run in registers (bitonic network)
+#pragma unroll
+        for (u32 k = 2; k <= ITEMS; k <<= 1) {
+#pragma unroll
+            for (u32 j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+                for (u32 i = 0; i < ITEMS; ++i) {
+                    const u32 l = i ^ j;
+                    if (l > i) {
+                        if ((i & k) == 0) ts_cswap(e[i], e[l]); else ts_cswap(e[l], e[i]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (u32 k = 0; k < ITEMS; ++k) s[ts_slot(o0 + k)] = e[k];
+    }
+    __syncthreads();
+
+    for (u32 run = ITEMS; run < m && run < CAP; run <<= 1) {
+        if (active) {
+            // outputs [o0, o0 + ITEMS) of the pair of runs holding them: A = [a0, a1), B = [a1, b1)
+            const u32 a0 = (o0 / (2 * run)) * (2 * run);
+            const u32 a1 = a0 + run < m ? a0 + run : m;
+            const u32 b1 = a0 + 2 * run < m ? a0 + 2 * run : m;
+            const u32 lenA = a1 - a0, lenB = b1 - a1;
+            const u32 diag = o0 - a0;
+            u32 l0 = diag > lenB ? diag - lenB : 0, h0 = diag < lenA ? diag : lenA;
+            while (l0 < h0) {
+                const u32 mid = (l0 + h0) >> 1;
+                if (s[ts_slot(a0 + mid)] < s[ts_slot(a1 + diag - 1 - mid)]) l0 = mid + 1; else h0 = mid;
+            }
+            u32 i = a0 + l0, j = a1 + (diag - l0);
+            u64 ka = i < a1 ? s[ts_slot(i)] : ~0ull;
+            u64 kb = j < b1 ? s[ts_slot(j)] : ~0ull;
+#pragma unroll
+            for (u32 k = 0; k < ITEMS; ++k) {
+                // ties only occur between padding values, where the side does not matter,
+                // as long as an exhausted run is never read
+                const bool takeA = j >= b1 || (i < a1 && ka <= kb);
+                if (takeA) {
+                    e[k] = ka; ++i;
+                    ka = i < a1 ? s[ts_slot(i)] : ~0ull;
+                } else {
+                    e[k] = kb; ++j;
+                    kb = j < b1 ? s[ts_slot(j)] : ~0ull;
+                }
+            }
+        }
+        __syncthreads();
+        if (active) {
+#pragma unroll
+            for (u32 k = 0; k < ITEMS; ++k) s[ts_slot(o0 + k)] = e[k];
+        }
+        __syncthreads();
+    }
+    const u64 hi_bits = (u64)tile << 32;
+    for (u32 p = tid; p < n; p += THREADS) {
+        const u64 c = s[ts_slot(p)];
+        keys[beg + p] = hi_bits | (c >> 32);
+        vals[beg + p] = (u32)c;
+    }
+}
+
+constexpr u32 kSmallThreads = 64, kSmallItems = 8, kSmallCap = kSmallThreads * kSmallItems;   // 512
+constexpr u32 kBigThreads = 256, kBigItems = kChunk / kBigThreads;                            // 16
+
+// short lists (2 .. 512 pairs): one wavefront each, walking `order` from its short end
+__global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
+    u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ tile_offsets,
+    const u32 *__restrict__ order, u32 num_tiles)
+{
+    __shared__ u64 s[kSmallCap + kSmallCap / 16];
+    if (blockIdx.x >= num_tiles) return;
+    const u32 tile = order[num_tiles - 1 - blockIdx.x];
+    if (tile >= num_tiles) return;
+    const u64 beg = tile_offsets[tile];
+    const u64 len = tile_offsets[tile + 1] - beg;
+    if (len < 2 || len > (u64)kSmallCap) return;
+    sort_pairs_in_lds<kSmallThreads, kSmallItems>(keys, vals, beg, (u32)len, tile, s);
+}
+
+// longer lists: one workgroup per chunk of up to kChunk pairs (chunk table from tile_order_kernel)
+__global__ __launch_bounds__(kBigThreads) void tile_sort_kernel(
+    u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ tile_offsets,
+    const u32 *__restrict__ chunk_start, u32 num_tiles)
+{
+    __shared__ u64 s[kChunk + kChunk / 16];
+    const u32 total = chunk_start[num_tiles];
+    const u32 b = blockIdx.x;
+    if (b >= total) return;
+    // the tile owning chunk b: last t with chunk_start[t] <= b (tiles without chunks share a
+    // start with their successor and are skipped by "last")
+    u32 lo = 0, hi = num_tiles - 1;
+    while (lo < hi) {
+        const u32 mid = (lo + hi + 1) >> 1;
+        if (chunk_start[mid] <= b) lo = mid; else hi = mid - 1;
+    }
+    const u32 tile = lo;
+    const u64 beg = tile_offsets[tile] + (u64)(b - chunk_start[tile]) * kChunk;
+    const u64 tile_end = tile_offsets[tile + 1];
+    if (beg >= tile_end) return;                               // cannot happen with a consistent table
+    const u32 n = (u32)((tile_end - beg) < (u64)kChunk ? (tile_end - beg) : (u64)kChunk);
+    if (n < 2) return;
+    sort_pairs_in_lds<kBigThreads, kBigItems>(keys, vals, beg, n, tile, s);
+}
+
+// ---------------------------------------------------------------- merge of long lists
+// One workgroup per tile whose list is longer than a chunk: its sorted chunks are merged
+// pairwise (run length doubling) between the two pair buffers; the result ends in keys/vals.
+__device__ __forceinline__ bool pair_less(u64 ka, u32 va, u64 kb, u32 vb)
+{
+    return ka < kb || (ka == kb && va < vb);
+}
+
+__global__ __launch_bounds__(256) void tile_merge_kernel(
+    u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ keys_alt, u32 *__restrict__ vals_alt,
+    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, u32 num_tiles)
+{
+    if (blockIdx.x >= num_tiles) return;
+    const u32 tile = order[blockIdx.x];
+    if (tile >= num_tiles) return;
+    const u64 beg = tile_offsets[tile];
+    const u64 L = tile_offsets[tile + 1] - beg;
+    if (L <= (u64)kChunk) return;
+    const u32 tid = threadIdx.x;
+    const u64 ipt = (L + 255) / 256;                       // outputs per thread and round
+    const u64 o_beg = (u64)tid * ipt < L ? (u64)tid * ipt : L;
+    const u64 o_end = o_beg + ipt < L ? o_beg + ipt : L;
+
+    u64 *sk = keys + beg, *dk = keys_alt + beg;
+    u32 *sv = vals + beg, *dv = vals_alt + beg;
+    bool in_alt = false;
+    for (u64 run = kChunk; run < L; run <<= 1) {
+        u64 o = o_beg;
+        while (o < o_end) {
+            // the pair of runs holding output o: A = [a0, a1), B = [a1, b1)
+            const u64 a0 = (o / (2 * run)) * (2 * run);
+            const u64 a1 = a0 + run < L ? a0 + run : L;
+            const u64 b1 = a0 + 2 * run < L ? a0 + 2 * run : L;
+            const u64 stop = o_end < b1 ? o_end : b1;       // this thread's outputs inside the pair
+            const u64 lenA = a1 - a0, lenB = b1 - a1;
+            const u64 diag = o - a0;                        // outputs of the pair before o
+            // merge-path split: i elements of A and diag - i of B precede output o
+            u64 lo = diag > lenB ? diag - lenB : 0, hi = diag < lenA ? diag : lenA;
+            while (lo < hi) {
+                const u64 mid = (lo + hi) >> 1;
+                const u64 jb = a1 + (diag - 1 - mid);
+                if (pair_less(sk[a0 + mid], sv[a0 + mid], sk[jb], sv[jb])) lo = mid + 1; else hi = mid;
+            }
+            u64 i = a0 + lo, j = a1 + (diag - lo);
+            u64 ka = 0, kb = 0; u32 va = 0, vb = 0;
+            if (i < a1) { ka = sk[i]; va = sv[i]; }
+            if (j < b1) { kb = sk[j]; vb = sv[j]; }
+            for (; o < stop; ++o) {
+                const bool takeA = j >= b1 || (i < a1 && !pair_less(kb, vb, ka, va));
+                if (takeA) {
+                    dk[o] = ka; dv[o] = va; ++i;
+                    if (i < a1) { ka = sk[i]; va = sv[i]; }
+                } else {
+                    dk[o] = kb; dv[o] = vb; ++j;
+                    if (j < b1) { kb = sk[j]; vb = sv[j]; }
+                }
+            }
+        }
+        __syncthreads();
+        u64 *tk = sk; sk = dk; dk = tk;
+        u32 *tv = sv; sv = dv; dv = tv;
+        in_alt = !in_alt;
+    }
+    if (in_alt) {                                           // sk/sv now point into the alternate buffers
+        for (u64 i = tid; i < L; i += 256) { dk[i] = sk[i]; dv[i] = sv[i]; }
     }
 }
 
@@ -591,6 +838,8 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     u32 *partials = reinterpret_cast<u32 *>(scratch + L.partials);
     u32 *table = reinterpret_cast<u32 *>(scratch + L.table);
     u64 *offsets = reinterpret_cast<u64 *>(scratch + L.offsets);
+    u32 *order = reinterpret_cast<u32 *>(scratch + L.order);
+    u32 *chunk_start = reinterpret_cast<u32 *>(scratch + L.chunk_start);
     const u32 num_tiles = pp.tiles_x * pp.tiles_y;
     const SortPlan plan = sort_plan(num_tiles);
 
@@ -615,10 +864,12 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     }
 
     const u32 hist_blocks = (u32)(L.sort_tiles < kHistBlocks ? L.sort_tiles : kHistBlocks);
-    hipLaunchKernelGGL(sort_prehist_kernel, dim3(hist_blocks), dim3(kSortThreads), 0, stream,
-                       kin, header, out.capacity, plan, partials, digit_totals);
-    hipLaunchKernelGGL(sort_reduce_kernel, dim3(plan.passes * kReduceSlices), dim3(kMaxRadix), 0, stream,
-                       partials, hist_blocks, digit_totals);
+    if (plan.passes > 0) {
+        hipLaunchKernelGGL(sort_prehist_kernel, dim3(hist_blocks), dim3(kSortThreads), 0, stream,
+                           kin, header, out.capacity, plan, partials, digit_totals);
+        hipLaunchKernelGGL(sort_reduce_kernel, dim3(plan.passes * kReduceSlices), dim3(kMaxRadix), 0, stream,
+                           partials, hist_blocks, digit_totals);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // enough resident workgroups to fill 256 CUs several times over; each loops over sort tiles
@@ -637,14 +888,30 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
         u64 *tk = kin; kin = kout; kout = tk;
         u32 *tv = vin; vin = vout; vout = tv;
     }
-    // after the last swap `kin` is the sorted buffer == out.keys
+    // after the last swap `kin` is the partitioned buffer == out.keys
     const u32 rgrid = grid_for((out.capacity + 255) / 256, 256u * 16u);
     hipLaunchKernelGGL(tile_ranges_kernel, dim3(rgrid), dim3(256), 0, stream,
                        out.keys, header, out.capacity, num_tiles, out.tile_offsets,
                        n == 0 ? proj.offsets : nullptr);
-    if (out.tile_order)
-        hipLaunchKernelGGL(tile_order_kernel, dim3(1), dim3(1024), 0, stream,
-                           out.tile_offsets, num_tiles, out.tile_order);
+    hipLaunchKernelGGL(tile_order_kernel, dim3(1), dim3(1024), 0, stream,
+                       out.tile_offsets, num_tiles, order, out.tile_order, chunk_start);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // lists longer than 512 pairs: one workgroup per chunk; there are fewer than capacity / 512
+    // such tiles, each with at most one partial chunk, plus capacity / kChunk full chunks
+    const u64 max_chunks = out.capacity / 512 + out.capacity / kChunk + 1;
+    if (max_chunks > 0x7fffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tile_sort_kernel, dim3((u32)(max_chunks < (u64)num_tiles + out.capacity / kChunk + 1
+                                                         ? max_chunks : (u64)num_tiles + out.capacity / kChunk + 1)),
+                       dim3(kBigThreads), 0, stream,
+                       out.keys, out.vals, out.tile_offsets, chunk_start, num_tiles);
+    hipLaunchKernelGGL(tile_sort_small_kernel, dim3(num_tiles), dim3(kSmallThreads), 0, stream,
+                       out.keys, out.vals, out.tile_offsets, order, num_tiles);
+    // tiles longer than a chunk come first in `order`; there are at most capacity / kChunk of them
+    const u64 max_long = out.capacity / kChunk < (u64)num_tiles ? out.capacity / kChunk : (u64)num_tiles;
+    if (max_long > 0)
+        hipLaunchKernelGGL(tile_merge_kernel, dim3((u32)max_long), dim3(256), 0, stream,
+                           out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, num_tiles);
     return hipGetLastError();
 }
 

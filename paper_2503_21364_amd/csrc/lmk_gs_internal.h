@@ -17,7 +17,7 @@ constexpr u32 kPreBlock = 256;          // primitives per preprocess / emit work
 constexpr u32 kSortThreads = 256;       // radix sort workgroup
 constexpr u32 kSortItems = 16;          // keys per thread
 constexpr u32 kSortTile = kSortThreads * kSortItems;   // 4096 pairs per workgroup pass
-constexpr u32 kMaxRadixBits = 9;         // digits are at most 9 bits wide, chosen per frame
+constexpr u32 kMaxRadixBits = 8;         // digits are at most 8 bits wide, chosen per frame
 constexpr u32 kMaxRadix = 1u << kMaxRadixBits;
 constexpr u32 kMaxPasses = 8;
 constexpr u32 kHistBlocks = 512;         // workgroups of the up-front digit histogram
@@ -38,6 +38,8 @@ struct ScratchLayout {
     size_t partials;      // u32 [kHistBlocks][kMaxPasses][512] per-workgroup digit counts
     size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
     size_t offsets;       // u64 [512][sort_tiles] their output offsets
+    size_t order;         // u32 [tiles]     tile ids by descending list length
+    size_t chunk_start;   // u32 [tiles + 1] first sort chunk of every tile (chunks of kChunk pairs)
     size_t total;
     u32 pre_blocks;
     u64 sort_tiles;       // ceil(capacity / kSortTile)
@@ -45,7 +47,7 @@ struct ScratchLayout {
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
-inline ScratchLayout scratch_layout(u32 n, u64 capacity)
+inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
 {
     ScratchLayout L;
     L.pre_blocks = (n + kPreBlock - 1) / kPreBlock;
@@ -59,13 +61,17 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity)
     L.partials = o;      o += align256(sizeof(u32) * (size_t)kHistBlocks * kMaxPasses * kMaxRadix);
     L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
     L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
+    L.order = o;         o += align256(sizeof(u32) * (size_t)(tiles + 1));
+    L.chunk_start = o;   o += align256(sizeof(u32) * ((size_t)tiles + 2));
     L.total = o;
     return L;
 }
 
-// Digit plan of the LSD radix sort: keys carry 32 depth bits + ceil(log2(tiles)) tile bits;
-// they are cut into the fewest digits of at most 9 bits, as evenly as possible
-// (1080p: 45 bits -> 5 x 9; 2160p: 47 bits -> 5 x 8 + 7; 256 x 256: 40 bits -> 5 x 8).
+// The pairs are first partitioned by tile id with a stable LSD radix sort over the tile bits
+// only (digits of at most 8 bits: 7 + 6 at 1080p, 8 + 7 at 2160p, one pass at 256 x 256),
+// then every tile's list is sorted by (depth, index) on its own.
+constexpr u32 kChunk = 4096;             // pairs sorted in LDS by one workgroup
+
 struct SortPlan {
     u32 passes;
     u32 shift[kMaxPasses];
@@ -76,11 +82,10 @@ inline SortPlan sort_plan(u32 tiles)
 {
     u32 tile_bits = 0;
     while ((1ull << tile_bits) < (u64)tiles) ++tile_bits;
-    const u32 total = 32 + tile_bits;
     SortPlan P;
-    P.passes = (total + kMaxRadixBits - 1) / kMaxRadixBits;
-    const u32 base = total / P.passes, extra = total % P.passes;
-    u32 at = 0;
+    P.passes = (tile_bits + kMaxRadixBits - 1) / kMaxRadixBits;
+    const u32 base = P.passes ? tile_bits / P.passes : 0, extra = P.passes ? tile_bits % P.passes : 0;
+    u32 at = 32;
     for (u32 p = 0; p < kMaxPasses; ++p) {
         P.shift[p] = at;
         P.bits[p] = p < P.passes ? base + (p < extra ? 1u : 0u) : 0u;
