@@ -552,65 +552,54 @@ __global__ __launch_bounds__(256) void tile_ranges_kernel(
     }
 }
 
-// ---------------------------------------------------------------- order + chunk table
-// Tile ids by descending list length, bucketed by the position of the length's top bit
-// (within a bucket the order is whatever the atomics give -- it only decides which
-// workgroup starts first, never a result), and the exclusive prefix of chunks per tile.
+// ---------------------------------------------------------------- order + size classes
+// Tile ids by descending list length, bucketed by the bit length of (length - 1), so that
+// the three size classes of the per-tile sort are whole buckets: more than kMid pairs
+// (front of `order`), kSmallCap + 1 .. kMid, and the rest.  Within a bucket the order is
+// whatever the atomics give -- it only decides which workgroup starts first, never a
+// result.  classes[0] / classes[1] = number of tiles in the first / second class.
 // One workgroup.
+constexpr u32 kSmallThreads = 64, kSmallItems = 8, kSmallCap = kSmallThreads * kSmallItems;   // 512
+constexpr u32 kMidThreads = 256, kMidItems = 16, kMid = kMidThreads * kMidItems;              // 4096
+constexpr u32 kHugeThreads = 1024, kHugeItems = 16, kHuge = kHugeThreads * kHugeItems;        // 16384
+static_assert(kMid == kChunk, "the launch bounds on the host use kChunk");
+
+__device__ __forceinline__ u32 length_bucket(u64 len)
+{
+    return len > 1 ? 64u - (u32)__builtin_clzll(len - 1) : 0u;   // len in (2^(b-1), 2^b]
+}
+constexpr u32 kSmallBucket = 9, kMidBucket = 12;                 // 2^9 = kSmallCap, 2^12 = kMid
+
 __global__ __launch_bounds__(1024) void tile_order_kernel(
     const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order,
-    u32 *__restrict__ order_copy, u32 *__restrict__ chunk_start)
+    u32 *__restrict__ order_copy, u32 *__restrict__ classes)
 {
     __shared__ u32 s_cnt[65];
-    __shared__ u32 s_wave[1024 / kWave];
-    __shared__ u32 s_carry;
-    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 tid = threadIdx.x;
     if (tid < 65) s_cnt[tid] = 0;
-    if (tid == 0) s_carry = 0;
     __syncthreads();
     for (u32 t = tid; t < num_tiles; t += 1024) {
-        const u64 len = tile_offsets[t + 1] - tile_offsets[t];
-        const u32 b = len ? 64u - (u32)__builtin_clzll(len) : 0u;     // 0..64
+        const u32 b = length_bucket(tile_offsets[t + 1] - tile_offsets[t]);
         atomicAdd(&s_cnt[64 - b], 1u);                                 // long lists first
     }
     __syncthreads();
     if (tid == 0) {
-        u32 run = 0;
-        for (u32 k = 0; k < 65; ++k) { const u32 c = s_cnt[k]; s_cnt[k] = run; run += c; }
+        u32 run = 0, huge = 0, mid = 0;
+        for (u32 k = 0; k < 65; ++k) {
+            const u32 c = s_cnt[k];
+            const u32 b = 64 - k;
+            if (b > kMidBucket) huge += c; else if (b > kSmallBucket) mid += c;
+            s_cnt[k] = run; run += c;
+        }
+        classes[0] = huge; classes[1] = mid;
     }
     __syncthreads();
     for (u32 t = tid; t < num_tiles; t += 1024) {
-        const u64 len = tile_offsets[t + 1] - tile_offsets[t];
-        const u32 b = len ? 64u - (u32)__builtin_clzll(len) : 0u;
+        const u32 b = length_bucket(tile_offsets[t + 1] - tile_offsets[t]);
         const u32 slot = atomicAdd(&s_cnt[64 - b], 1u);
         order[slot] = t;
         if (order_copy) order_copy[slot] = t;
     }
-    // chunk_start[t] = number of chunks of the tiles before t
-    for (u32 base = 0; base < num_tiles; base += 1024) {
-        const u32 t = base + tid;
-        u32 c = 0;
-        if (t < num_tiles) {
-            const u64 len = tile_offsets[t + 1] - tile_offsets[t];
-            c = len > 512 ? (u32)((len + kChunk - 1) / kChunk) : 0u;   // short lists go to the one-wavefront sort
-        }
-        u32 incl = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const u32 v = __shfl_up(incl, o, 64);
-            if ((int)lane >= o) incl += v;
-        }
-        __syncthreads();
-        if (lane == kWave - 1) s_wave[wv] = incl;
-        __syncthreads();
-        u32 run = s_carry + incl - c;
-        for (u32 k = 0; k < wv; ++k) run += s_wave[k];
-        if (t < num_tiles) chunk_start[t] = run;
-        __syncthreads();
-        if (tid == 1023) s_carry = run + c;
-        __syncthreads();
-    }
-    if (tid == 0) chunk_start[num_tiles] = s_carry;
 }
 
 // ---------------------------------------------------------------- per-tile sort
@@ -620,14 +609,43 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
 // where its ITEMS outputs start in the two runs (merge-path binary search) and merges them
 // sequentially.  About 25 LDS accesses per element, against ~150 for a bitonic network over
 // the whole chunk.  Runs are stored with one padding slot per 16 elements so that the
-// strided accesses of neighbouring threads spread over the LDS banks.  Two instances:
-// 64 threads x 8 (one wavefront per short list, which is most tiles) and 256 x 16.
+// strided accesses of neighbouring threads spread over the LDS banks.  Three instances:
+// 64 threads x 8 (one wavefront per short list, which is most tiles), 256 x 16, and
+// 1024 x 16 (a whole compute unit's LDS) for the long lists.
 __device__ __forceinline__ u32 ts_slot(u32 p) { return p + (p >> 4); }
 
 __device__ __forceinline__ void ts_cswap(u64 &a, u64 &b)
 {
     const u64 lo = a < b ? a : b, hi = a < b ? b : a;
     a = lo; b = hi;
+}
+
+// ITEMS outputs, starting at output `diag`, of the merge of the sorted runs s[a0, a1) and s[a1, b1)
+template <u32 ITEMS>
+__device__ __forceinline__ void merge_from_lds(const u64 *s, u32 a0, u32 a1, u32 b1, u32 diag, u64 (&e)[ITEMS])
+{
+    const u32 lenA = a1 - a0, lenB = b1 - a1;
+    u32 l0 = diag > lenB ? diag - lenB : 0, h0 = diag < lenA ? diag : lenA;
+    while (l0 < h0) {
+        const u32 mid = (l0 + h0) >> 1;
+        if (s[ts_slot(a0 + mid)] < s[ts_slot(a1 + diag - 1 - mid)]) l0 = mid + 1; else h0 = mid;
+    }
+    u32 i = a0 + l0, j = a1 + (diag - l0);
+    u64 ka = i < a1 ? s[ts_slot(i)] : ~0ull;
+    u64 kb = j < b1 ? s[ts_slot(j)] : ~0ull;
+#pragma unroll
+    for (u32 k = 0; k < ITEMS; ++k) {
+        // ties only occur between padding values, where the side does not matter,
+        // as long as an exhausted run is never read
+        const bool takeA = j >= b1 || (i < a1 && ka <= kb);
+        if (takeA) {
+            e[k] = ka; ++i;
+            ka = i < a1 ? s[ts_slot(i)] : ~0ull;
+        } else {
+            e[k] = kb; ++j;
+            kb = j < b1 ? s[ts_slot(j)] : ~0ull;
+        }
+    }
 }
 
 template <u32 THREADS, u32 ITEMS>
@@ -672,29 +690,7 @@ __device__ __forceinline__ void sort_pairs_in_lds(u64 *__restrict__ keys, u32 *_
             const u32 a0 = (o0 / (2 * run)) * (2 * run);
             const u32 a1 = a0 + run < m ? a0 + run : m;
             const u32 b1 = a0 + 2 * run < m ? a0 + 2 * run : m;
-            const u32 lenA = a1 - a0, lenB = b1 - a1;
-            const u32 diag = o0 - a0;
-            u32 l0 = diag > lenB ? diag - lenB : 0, h0 = diag < lenA ? diag : lenA;
-            while (l0 < h0) {
-                const u32 mid = (l0 + h0) >> 1;
-                if (s[ts_slot(a0 + mid)] < s[ts_slot(a1 + diag - 1 - mid)]) l0 = mid + 1; else h0 = mid;
-            }
-            u32 i = a0 + l0, j = a1 + (diag - l0);
-            u64 ka = i < a1 ? s[ts_slot(i)] : ~0ull;
-            u64 kb = j < b1 ? s[ts_slot(j)] : ~0ull;
-#pragma unroll
-            for (u32 k = 0; k < ITEMS; ++k) {
-                // ties only occur between padding values, where the side does not matter,
-                // as long as an exhausted run is never read
-                const bool takeA = j >= b1 || (i < a1 && ka <= kb);
-                if (takeA) {
-                    e[k] = ka; ++i;
-                    ka = i < a1 ? s[ts_slot(i)] : ~0ull;
-                } else {
-                    e[k] = kb; ++j;
-                    kb = j < b1 ? s[ts_slot(j)] : ~0ull;
-                }
-            }
+            merge_from_lds<ITEMS>(s, a0, a1, b1, o0 - a0, e);
         }
         __syncthreads();
         if (active) {
@@ -709,10 +705,8 @@ __device__ __forceinline__ void sort_pairs_in_lds(u64 *__restrict__ keys, u32 *_
         keys[beg + p] = hi_bits | (c >> 32);
         vals[beg + p] = (u32)c;
     }
+    __syncthreads();                                        // s may be refilled by the caller
 }
-
-constexpr u32 kSmallThreads = 64, kSmallItems = 8, kSmallCap = kSmallThreads * kSmallItems;   // 512
-constexpr u32 kBigThreads = 256, kBigItems = kChunk / kBigThreads;                            // 16
 
 // short lists (2 .. 512 pairs): one wavefront each, walking `order` from its short end
 __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
@@ -729,96 +723,147 @@ __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
     sort_pairs_in_lds<kSmallThreads, kSmallItems>(keys, vals, beg, (u32)len, tile, s);
 }
 
-// longer lists: one workgroup per chunk of up to kChunk pairs (chunk table from tile_order_kernel)
-__global__ __launch_bounds__(kBigThreads) void tile_sort_kernel(
+// lists of 513 .. 4096 pairs: one workgroup each; they follow the long lists in `order`
+__global__ __launch_bounds__(kMidThreads) void tile_sort_mid_kernel(
     u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ tile_offsets,
-    const u32 *__restrict__ chunk_start, u32 num_tiles)
+    const u32 *__restrict__ order, const u32 *__restrict__ classes, u32 num_tiles)
 {
-    __shared__ u64 s[kChunk + kChunk / 16];
-    const u32 total = chunk_start[num_tiles];
-    const u32 b = blockIdx.x;
-    if (b >= total) return;
-    // the tile owning chunk b: last t with chunk_start[t] <= b (tiles without chunks share a
-    // start with their successor and are skipped by "last")
-    u32 lo = 0, hi = num_tiles - 1;
-    while (lo < hi) {
-        const u32 mid = (lo + hi + 1) >> 1;
-        if (chunk_start[mid] <= b) lo = mid; else hi = mid - 1;
-    }
-    const u32 tile = lo;
-    const u64 beg = tile_offsets[tile] + (u64)(b - chunk_start[tile]) * kChunk;
-    const u64 tile_end = tile_offsets[tile + 1];
-    if (beg >= tile_end) return;                               // cannot happen with a consistent table
-    const u32 n = (u32)((tile_end - beg) < (u64)kChunk ? (tile_end - beg) : (u64)kChunk);
-    if (n < 2) return;
-    sort_pairs_in_lds<kBigThreads, kBigItems>(keys, vals, beg, n, tile, s);
+    __shared__ u64 s[kMid + kMid / 16];
+    const u32 first = classes[0], count = classes[1];
+    if (blockIdx.x >= count || first + blockIdx.x >= num_tiles) return;
+    const u32 tile = order[first + blockIdx.x];
+    if (tile >= num_tiles) return;
+    const u64 beg = tile_offsets[tile];
+    const u64 len = tile_offsets[tile + 1] - beg;
+    if (len < 2 || len > (u64)kMid) return;                 // cannot happen with a consistent table
+    sort_pairs_in_lds<kMidThreads, kMidItems>(keys, vals, beg, (u32)len, tile, s);
 }
 
-// ---------------------------------------------------------------- merge of long lists
-// One workgroup per tile whose list is longer than a chunk: its sorted chunks are merged
-// pairwise (run length doubling) between the two pair buffers; the result ends in keys/vals.
+// ---------------------------------------------------------------- long lists
 __device__ __forceinline__ bool pair_less(u64 ka, u32 va, u64 kb, u32 vb)
 {
     return ka < kb || (ka == kb && va < vb);
 }
 
-__global__ __launch_bounds__(256) void tile_merge_kernel(
-    u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ keys_alt, u32 *__restrict__ vals_alt,
-    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, u32 num_tiles)
+// Merge-path split by one wavefront: the number of elements of A = [a0, a1) among the first
+// `diag` outputs of the merge of A and B = [a1, b1) (sorted runs in global memory).  Every
+// round the 64 lanes probe 64 evenly spaced candidates, which narrows the range 64-fold.
+__device__ __forceinline__ u64 wave_merge_split(const u64 *__restrict__ sk, const u32 *__restrict__ sv,
+                                                u64 a0, u64 a1, u64 b1, u64 diag, u32 lane)
 {
-    if (blockIdx.x >= num_tiles) return;
+    const u64 lenA = a1 - a0, lenB = b1 - a1;
+    u64 lo = diag > lenB ? diag - lenB : 0, hi = diag < lenA ? diag : lenA;
+    while (lo < hi) {                                       // wave-uniform
+        const u64 step = (hi - lo + 63) / 64;
+        const u64 m = lo + (u64)(lane + 1) * step - 1;
+        bool p = false;
+        if (m < hi) {
+            const u64 jb = a1 + (diag - 1 - m);
+            p = pair_less(sk[a0 + m], sv[a0 + m], sk[jb], sv[jb]);
+        }
+        const u64 c = (u64)__builtin_popcountll(__builtin_amdgcn_ballot_w64(p));   // leading run of "true"
+        const u64 nlo = lo + c * step;
+        const u64 nhi = lo + (c + 1) * step - 1;
+        hi = nhi < hi ? nhi : hi;
+        lo = nlo;
+    }
+    return lo;
+}
+
+// One workgroup of 1024 threads per tile whose list is longer than kMid pairs (the front of
+// `order`): chunks of up to kHuge pairs are sorted in LDS; a list longer than that is then
+// merged pairwise (run length doubling) between the two pair buffers, kHuge outputs at a
+// time: sixteen wavefronts find the splits of sixteen output segments, then each segment's
+// two input windows are staged in LDS, merged there and written out coalesced.  The result
+// ends in keys/vals.
+__global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
+    u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ keys_alt, u32 *__restrict__ vals_alt,
+    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, const u32 *__restrict__ classes,
+    u32 num_tiles)
+{
+    __shared__ u64 s[kHuge + kHuge / 16];
+    __shared__ u64 s_split[kHugeThreads / kWave][2];
+    if (blockIdx.x >= classes[0] || blockIdx.x >= num_tiles) return;
     const u32 tile = order[blockIdx.x];
     if (tile >= num_tiles) return;
     const u64 beg = tile_offsets[tile];
     const u64 L = tile_offsets[tile + 1] - beg;
-    if (L <= (u64)kChunk) return;
-    const u32 tid = threadIdx.x;
-    const u64 ipt = (L + 255) / 256;                       // outputs per thread and round
-    const u64 o_beg = (u64)tid * ipt < L ? (u64)tid * ipt : L;
-    const u64 o_end = o_beg + ipt < L ? o_beg + ipt : L;
+    if (L <= (u64)kMid) return;                             // cannot happen with a consistent table
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    constexpr u32 kWaves = kHugeThreads / kWave;
+
+    for (u64 c0 = 0; c0 < L; c0 += kHuge) {
+        const u32 n = (u32)(L - c0 < (u64)kHuge ? L - c0 : (u64)kHuge);
+        if (n >= 2) sort_pairs_in_lds<kHugeThreads, kHugeItems>(keys, vals, beg + c0, n, tile, s);
+    }
+    if (L <= (u64)kHuge) return;
+    // the chunk sorts of this workgroup wrote the runs the merges read
+    __threadfence_block();
+    __syncthreads();
 
     u64 *sk = keys + beg, *dk = keys_alt + beg;
     u32 *sv = vals + beg, *dv = vals_alt + beg;
+    const u64 hi_bits = (u64)tile << 32;
+    const u64 nseg = (L + kHuge - 1) / kHuge;
     bool in_alt = false;
-    for (u64 run = kChunk; run < L; run <<= 1) {
-        u64 o = o_beg;
-        while (o < o_end) {
-            // the pair of runs holding output o: A = [a0, a1), B = [a1, b1)
-            const u64 a0 = (o / (2 * run)) * (2 * run);
-            const u64 a1 = a0 + run < L ? a0 + run : L;
-            const u64 b1 = a0 + 2 * run < L ? a0 + 2 * run : L;
-            const u64 stop = o_end < b1 ? o_end : b1;       // this thread's outputs inside the pair
-            const u64 lenA = a1 - a0, lenB = b1 - a1;
-            const u64 diag = o - a0;                        // outputs of the pair before o
-            // merge-path split: i elements of A and diag - i of B precede output o
-            u64 lo = diag > lenB ? diag - lenB : 0, hi = diag < lenA ? diag : lenA;
-            while (lo < hi) {
-                const u64 mid = (lo + hi) >> 1;
-                const u64 jb = a1 + (diag - 1 - mid);
-                if (pair_less(sk[a0 + mid], sv[a0 + mid], sk[jb], sv[jb])) lo = mid + 1; else hi = mid;
-            }
-            u64 i = a0 + lo, j = a1 + (diag - lo);
-            u64 ka = 0, kb = 0; u32 va = 0, vb = 0;
-            if (i < a1) { ka = sk[i]; va = sv[i]; }
-            if (j < b1) { kb = sk[j]; vb = sv[j]; }
-            for (; o < stop; ++o) {
-                const bool takeA = j >= b1 || (i < a1 && !pair_less(kb, vb, ka, va));
-                if (takeA) {
-                    dk[o] = ka; dv[o] = va; ++i;
-                    if (i < a1) { ka = sk[i]; va = sv[i]; }
-                } else {
-                    dk[o] = kb; dv[o] = vb; ++j;
-                    if (j < b1) { kb = sk[j]; vb = sv[j]; }
+    for (u64 run = kHuge; run < L; run <<= 1) {
+        for (u64 seg0 = 0; seg0 < nseg; seg0 += kWaves) {
+            {   // wavefront wv: the splits at both ends of output segment seg0 + wv
+                const u64 seg = seg0 + wv;
+                if (seg < nseg) {
+                    const u64 o = seg * kHuge;
+                    const u64 a0 = (o / (2 * run)) * (2 * run);
+                    const u64 a1 = a0 + run < L ? a0 + run : L;
+                    const u64 b1 = a0 + 2 * run < L ? a0 + 2 * run : L;
+                    const u64 oe = o + kHuge < b1 ? o + kHuge : b1;
+                    const u64 i0 = wave_merge_split(sk, sv, a0, a1, b1, o - a0, lane);
+                    const u64 i1 = wave_merge_split(sk, sv, a0, a1, b1, oe - a0, lane);
+                    if (lane == 0) { s_split[wv][0] = i0; s_split[wv][1] = i1; }
                 }
             }
+            __syncthreads();
+            for (u32 w = 0; w < kWaves && seg0 + w < nseg; ++w) {
+                const u64 o = (seg0 + w) * kHuge;
+                const u64 a0 = (o / (2 * run)) * (2 * run);
+                const u64 a1 = a0 + run < L ? a0 + run : L;
+                const u64 b1 = a0 + 2 * run < L ? a0 + 2 * run : L;
+                const u64 oe = o + kHuge < b1 ? o + kHuge : b1;
+                const u64 i0 = s_split[w][0], i1 = s_split[w][1];
+                const u64 j0 = (o - a0) - i0;                // elements of B before the segment
+                const u32 la = (u32)(i1 - i0), total = (u32)(oe - o);
+                // stage A[i0, i1) then B[j0, j0 + total - la) as composites
+                for (u32 p = tid; p < total; p += kHugeThreads) {
+                    const u64 src = p < la ? a0 + i0 + p : a1 + j0 + (p - la);
+                    s[ts_slot(p)] = (sk[src] << 32) | (u64)sv[src];
+                }
+                __syncthreads();
+                const u32 o0 = tid * kHugeItems;
+                u64 e[kHugeItems];
+                if (o0 < total) merge_from_lds<kHugeItems>(s, 0u, la, total, o0, e);
+                __syncthreads();
+                if (o0 < total) {
+#pragma unroll
+                    for (u32 k = 0; k < kHugeItems; ++k)
+                        if (o0 + k < total) s[ts_slot(o0 + k)] = e[k];
+                }
+                __syncthreads();
+                for (u32 p = tid; p < total; p += kHugeThreads) {
+                    const u64 c = s[ts_slot(p)];
+                    dk[o + p] = hi_bits | (c >> 32);
+                    dv[o + p] = (u32)c;
+                }
+                __syncthreads();
+            }
         }
+        // this workgroup's writes of the round are read by all its threads in the next one
+        __threadfence_block();
         __syncthreads();
         u64 *tk = sk; sk = dk; dk = tk;
         u32 *tv = sv; sv = dv; dv = tv;
         in_alt = !in_alt;
     }
     if (in_alt) {                                           // sk/sv now point into the alternate buffers
-        for (u64 i = tid; i < L; i += 256) { dk[i] = sk[i]; dv[i] = sv[i]; }
+        for (u64 i = tid; i < L; i += kHugeThreads) { dk[i] = sk[i]; dv[i] = sv[i]; }
     }
 }
 
@@ -839,7 +884,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     u32 *table = reinterpret_cast<u32 *>(scratch + L.table);
     u64 *offsets = reinterpret_cast<u64 *>(scratch + L.offsets);
     u32 *order = reinterpret_cast<u32 *>(scratch + L.order);
-    u32 *chunk_start = reinterpret_cast<u32 *>(scratch + L.chunk_start);
+    u32 *classes = reinterpret_cast<u32 *>(scratch + L.classes);
     const u32 num_tiles = pp.tiles_x * pp.tiles_y;
     const SortPlan plan = sort_plan(num_tiles);
 
@@ -894,24 +939,19 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
                        out.keys, header, out.capacity, num_tiles, out.tile_offsets,
                        n == 0 ? proj.offsets : nullptr);
     hipLaunchKernelGGL(tile_order_kernel, dim3(1), dim3(1024), 0, stream,
-                       out.tile_offsets, num_tiles, order, out.tile_order, chunk_start);
+                       out.tile_offsets, num_tiles, order, out.tile_order, classes);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // lists longer than 512 pairs: one workgroup per chunk; there are fewer than capacity / 512
-    // such tiles, each with at most one partial chunk, plus capacity / kChunk full chunks
-    const u64 max_chunks = out.capacity / 512 + out.capacity / kChunk + 1;
-    if (max_chunks > 0x7fffffffull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(tile_sort_kernel, dim3((u32)(max_chunks < (u64)num_tiles + out.capacity / kChunk + 1
-                                                         ? max_chunks : (u64)num_tiles + out.capacity / kChunk + 1)),
-                       dim3(kBigThreads), 0, stream,
-                       out.keys, out.vals, out.tile_offsets, chunk_start, num_tiles);
+    // the long lists first (few workgroups that run long), then the mid-sized, then the rest;
+    // the grids are upper bounds from the capacity, surplus workgroups leave at once
+    const u64 max_huge = out.capacity / (kChunk + 1) + 1 < (u64)num_tiles ? out.capacity / (kChunk + 1) + 1 : (u64)num_tiles;
+    const u64 max_mid = out.capacity / 513 + 1 < (u64)num_tiles ? out.capacity / 513 + 1 : (u64)num_tiles;
+    hipLaunchKernelGGL(tile_sort_huge_kernel, dim3((u32)max_huge), dim3(1024), 0, stream,
+                       out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes, num_tiles);
+    hipLaunchKernelGGL(tile_sort_mid_kernel, dim3((u32)max_mid), dim3(256), 0, stream,
+                       out.keys, out.vals, out.tile_offsets, order, classes, num_tiles);
     hipLaunchKernelGGL(tile_sort_small_kernel, dim3(num_tiles), dim3(kSmallThreads), 0, stream,
                        out.keys, out.vals, out.tile_offsets, order, num_tiles);
-    // tiles longer than a chunk come first in `order`; there are at most capacity / kChunk of them
-    const u64 max_long = out.capacity / kChunk < (u64)num_tiles ? out.capacity / kChunk : (u64)num_tiles;
-    if (max_long > 0)
-        hipLaunchKernelGGL(tile_merge_kernel, dim3((u32)max_long), dim3(256), 0, stream,
-                           out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, num_tiles);
     return hipGetLastError();
 }
 

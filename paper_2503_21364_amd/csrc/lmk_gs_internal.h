@@ -39,7 +39,7 @@ struct ScratchLayout {
     size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
     size_t offsets;       // u64 [512][sort_tiles] their output offsets
     size_t order;         // u32 [tiles]     tile ids by descending list length
-    size_t chunk_start;   // u32 [tiles + 1] first sort chunk of every tile (chunks of kChunk pairs)
+    size_t classes;       // u32 [4]         tiles with lists longer than kHugeMin / kMidMin pairs (front of `order`)
     size_t total;
     u32 pre_blocks;
     u64 sort_tiles;       // ceil(capacity / kSortTile)
@@ -62,7 +62,7 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
     L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
     L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
     L.order = o;         o += align256(sizeof(u32) * (size_t)(tiles + 1));
-    L.chunk_start = o;   o += align256(sizeof(u32) * ((size_t)tiles + 2));
+    L.classes = o;       o += align256(sizeof(u32) * 4);
     L.total = o;
     return L;
 }

@@ -83,6 +83,21 @@ def test_cfg4_distributions_reduced_count():
     assert r.stats["D"] / r.stats["visible"] > 300   # hundreds of tiles per primitive
 
 
+@pytest.mark.parametrize("w,h,n,seed,binning", [
+    (64, 64, 100_000, 41, 0),       # 16 tiles, lists of several thousand pairs: one long chunk each
+    (48, 40, 150_000, 42, 0),       # 9 tiles (ragged), lists beyond one long chunk: merges between the buffers
+    (48, 40, 150_000, 43, 1),
+    (16, 16, 70_001, 44, 0),        # everything in one tile: several merge rounds, ragged last run
+])
+def test_long_lists_in_few_tiles(w, h, n, seed, binning):
+    sc = scenes.make_scene(0, n=n, seed=seed)
+    cam = dict(scenes.make_cameras(0, w, h)[0], binning=binning)
+    r = P.full_compare(sc, cam)
+    _report(f"long lists {w}x{h} n={n} binning {binning}", r.stats)
+    lens = np.diff(r.oracle.binned.tile_offsets.astype(np.int64))
+    assert lens.max() > (16384 if n > 100_000 or w == 16 else 4096)
+
+
 # ------------------------------------------------------------------ binning rule 1
 def _tight(cam):
     return dict(cam, binning=1)
@@ -241,7 +256,8 @@ def test_tile_order_is_a_permutation_by_descending_length_class():
     T = fr.tiles_x * fr.tiles_y
     assert np.array_equal(np.sort(order), np.arange(T))
     lens = np.diff(P.to_np(fr.tile_offsets).view(np.uint64).astype(np.int64))[order]
-    cls = np.where(lens > 0, np.floor(np.log2(np.maximum(lens, 1))).astype(np.int64) + 1, 0)
+    # classes: bit length of (length - 1), so that 2^k pairs still belong to the class below
+    cls = np.where(lens > 1, np.floor(np.log2(np.maximum(lens - 1, 1))).astype(np.int64) + 1, 0)
     assert np.all(np.diff(cls) <= 0)
     # and the image does not depend on the hint
     fr2 = B.Frame(sc["n"], 400, 240, 2_000_000, tile_order=False)
