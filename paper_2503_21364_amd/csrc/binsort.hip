@@ -560,7 +560,8 @@ __global__ __launch_bounds__(256) void tile_ranges_kernel(
 // result.  classes[0] / classes[1] = number of tiles in the first / second class.
 // One workgroup.
 constexpr u32 kSmallThreads = 64, kSmallItems = 8, kSmallCap = kSmallThreads * kSmallItems;   // 512
-constexpr u32 kMidThreads = 256, kMidItems = 16, kMid = kMidThreads * kMidItems;              // 4096
+constexpr u32 kLowThreads = 256, kLowItems = 8;                                               // 2048
+constexpr u32 kMidThreads = 512, kMidItems = 8, kMid = kMidThreads * kMidItems;               // 4096
 constexpr u32 kHugeThreads = 1024, kHugeItems = 16, kHuge = kHugeThreads * kHugeItems;        // 16384
 static_assert(kMid == kChunk, "the launch bounds on the host use kChunk");
 
@@ -568,7 +569,7 @@ __device__ __forceinline__ u32 length_bucket(u64 len)
 {
     return len > 1 ? 64u - (u32)__builtin_clzll(len - 1) : 0u;   // len in (2^(b-1), 2^b]
 }
-constexpr u32 kSmallBucket = 9, kMidBucket = 12;                 // 2^9 = kSmallCap, 2^12 = kMid
+constexpr u32 kSmallBucket = 9, kLowBucket = 11, kMidBucket = 12;   // 2^9 = kSmallCap, 2^11 = kLow, 2^12 = kMid
 
 __global__ __launch_bounds__(1024) void tile_order_kernel(
     const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order,
@@ -584,14 +585,14 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
     }
     __syncthreads();
     if (tid == 0) {
-        u32 run = 0, huge = 0, mid = 0;
+        u32 run = 0, huge = 0, mid = 0, low = 0;
         for (u32 k = 0; k < 65; ++k) {
             const u32 c = s_cnt[k];
             const u32 b = 64 - k;
-            if (b > kMidBucket) huge += c; else if (b > kSmallBucket) mid += c;
+            if (b > kMidBucket) huge += c; else if (b > kLowBucket) mid += c; else if (b > kSmallBucket) low += c;
             s_cnt[k] = run; run += c;
         }
-        classes[0] = huge; classes[1] = mid;
+        classes[0] = huge; classes[1] = mid; classes[2] = low;
     }
     __syncthreads();
     for (u32 t = tid; t < num_tiles; t += 1024) {
@@ -723,20 +724,25 @@ __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
     sort_pairs_in_lds<kSmallThreads, kSmallItems>(keys, vals, beg, (u32)len, tile, s);
 }
 
-// lists of 513 .. 4096 pairs: one workgroup each; they follow the long lists in `order`
-__global__ __launch_bounds__(kMidThreads) void tile_sort_mid_kernel(
+// lists of 513 .. 2048 and 2049 .. 4096 pairs: one workgroup each; in `order` they follow the
+// long lists, the longer class first (CLASS = 1: 2049 .. 4096, CLASS = 2: 513 .. 2048)
+template <u32 THREADS, u32 ITEMS, u32 CLASS>
+__global__ __launch_bounds__(THREADS) void tile_sort_class_kernel(
     u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ tile_offsets,
     const u32 *__restrict__ order, const u32 *__restrict__ classes, u32 num_tiles)
 {
-    __shared__ u64 s[kMid + kMid / 16];
-    const u32 first = classes[0], count = classes[1];
+    constexpr u32 CAP = THREADS * ITEMS;
+    __shared__ u64 s[CAP + CAP / 16];
+    u32 first = classes[0];
+    if (CLASS == 2) first += classes[1];
+    const u32 count = classes[CLASS];
     if (blockIdx.x >= count || first + blockIdx.x >= num_tiles) return;
     const u32 tile = order[first + blockIdx.x];
     if (tile >= num_tiles) return;
     const u64 beg = tile_offsets[tile];
     const u64 len = tile_offsets[tile + 1] - beg;
-    if (len < 2 || len > (u64)kMid) return;                 // cannot happen with a consistent table
-    sort_pairs_in_lds<kMidThreads, kMidItems>(keys, vals, beg, (u32)len, tile, s);
+    if (len < 2 || len > (u64)CAP) return;                  // cannot happen with a consistent table
+    sort_pairs_in_lds<THREADS, ITEMS>(keys, vals, beg, (u32)len, tile, s);
 }
 
 // ---------------------------------------------------------------- long lists
@@ -945,10 +951,13 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     // the long lists first (few workgroups that run long), then the mid-sized, then the rest;
     // the grids are upper bounds from the capacity, surplus workgroups leave at once
     const u64 max_huge = out.capacity / (kChunk + 1) + 1 < (u64)num_tiles ? out.capacity / (kChunk + 1) + 1 : (u64)num_tiles;
-    const u64 max_mid = out.capacity / 513 + 1 < (u64)num_tiles ? out.capacity / 513 + 1 : (u64)num_tiles;
+    const u64 max_mid = out.capacity / 2049 + 1 < (u64)num_tiles ? out.capacity / 2049 + 1 : (u64)num_tiles;
+    const u64 max_low = out.capacity / 513 + 1 < (u64)num_tiles ? out.capacity / 513 + 1 : (u64)num_tiles;
     hipLaunchKernelGGL(tile_sort_huge_kernel, dim3((u32)max_huge), dim3(1024), 0, stream,
                        out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes, num_tiles);
-    hipLaunchKernelGGL(tile_sort_mid_kernel, dim3((u32)max_mid), dim3(256), 0, stream,
+    hipLaunchKernelGGL((tile_sort_class_kernel<kMidThreads, kMidItems, 1>), dim3((u32)max_mid), dim3(kMidThreads), 0, stream,
+                       out.keys, out.vals, out.tile_offsets, order, classes, num_tiles);
+    hipLaunchKernelGGL((tile_sort_class_kernel<kLowThreads, kLowItems, 2>), dim3((u32)max_low), dim3(kLowThreads), 0, stream,
                        out.keys, out.vals, out.tile_offsets, order, classes, num_tiles);
     hipLaunchKernelGGL(tile_sort_small_kernel, dim3(num_tiles), dim3(kSmallThreads), 0, stream,
                        out.keys, out.vals, out.tile_offsets, order, num_tiles);

@@ -2,12 +2,13 @@
 // blend kernel whose share of render time Sec. 4.2.1 reports).
 //
 // One workgroup (4 wavefronts) per 16x16 tile; each wavefront owns a compact
-// 8x8 pixel block, one pixel per lane.  The tile's sorted list is consumed in
-// batches of 256 entries staged in LDS (each thread fetches one 48-byte feature
-// record; the next batch's records are already in flight while the current
-// batch is composited -- the software pipelining of Sec. 4.2.1).
+// 8x8 pixel block, each group of 16 lanes a 4x4 sub-block of it, one pixel per
+// lane.  The tile's sorted list is consumed in batches of 256 entries staged in
+// LDS (each thread fetches one 48-byte feature record; the next batch's records
+// are already in flight while the current batch is composited -- the software
+// pipelining of Sec. 4.2.1).
 //
-// Per batch a wavefront works in two phases:
+// Per batch a wavefront works in three phases:
 //  1. lane = entry.  64 entries at a time are tested against the wavefront's
 //     pixel block: the maximum of the splat's exponent over the (continuous)
 //     block is found in closed form -- the exponent is a concave quadratic, so
@@ -19,10 +20,16 @@
 //     per entry; LDS is read lane-distinct, not broadcast.  Survivors append
 //     their LDS offsets, in list order, to a per-wavefront survivor list
 //     (ballot + mbcnt ranks).
-//  2. lane = pixel.  The survivor list is walked four entries at a time: one
+//  2. lane = survivor.  The same test against each of the four 4x4 sub-blocks,
+//     64 survivors at a time, gives every 16-lane group its own survivor
+//     list: a splat that reaches the 8x8 block touches on average only
+//     about half of its sub-blocks, and the vector units -- the bound of this
+//     kernel -- are spent on (pixel, splat) pairs that can contribute.
+//  3. lane = pixel.  Each group walks its own list, four entries at a time: one
 //     16-byte LDS read yields four record offsets, the four exponentials are
 //     independent, the compositing updates follow in order under per-lane
-//     select masks.  The loop body has no data-dependent scalar control flow
+//     select masks.  The loop runs to the longest of the four lists (shorter
+//     ones read a null record) and has no data-dependent scalar control flow
 //     (the scalar unit, shared by the CU's four SIMDs, was as loaded as the
 //     vector units when survivors were walked with scalar bit scans).
 // A wavefront whose 64 pixels have all stopped skips the rest (per-wavefront
@@ -61,6 +68,28 @@ __device__ __forceinline__ Rec fetch_record(const u32 *__restrict__ vals, const 
 
 __device__ __forceinline__ float clamp_pm(float v, float h) { return __builtin_amdgcn_fmed3f(v, -h, h); }
 
+// Upper bound, with the rounding margin folded in, of A' dx^2 + B' dx dy + C' dy^2 over the
+// square [-half, half]^2 about a centre from which the splat centre lies at (xs, ys).
+// t.x = -B'/(2A'), t.y = -B'/(2C').
+__device__ __forceinline__ float square_reach(float xs, float ys, float Aq, float Bq, float Cq,
+                                              float tx, float ty, float half)
+{
+    const float kRelMargin = -2e-6f;    // times (A' ex^2 + C' ey^2) <= 0: covers fp32 rounding of the test
+    // candidate 1: x clamped into the square, best y on that vertical line
+    const float ex1 = clamp_pm(xs, half) - xs;
+    const float ey1 = clamp_pm(fmaf(ty, ex1, ys), half) - ys;
+    const float m1 = fmaf(Aq * ex1, ex1, Cq * ey1 * ey1);
+    const float p1 = fmaf(Bq * ex1, ey1, m1);
+    // candidate 2: y clamped, best x on that horizontal line
+    const float ey2 = clamp_pm(ys, half) - ys;
+    const float ex2 = clamp_pm(fmaf(tx, ey2, xs), half) - xs;
+    const float m2 = fmaf(Aq * ex2, ex2, Cq * ey2 * ey2);
+    const float p2 = fmaf(Bq * ex2, ey2, m2);
+    return fmaxf(fmaf(m1, kRelMargin, p1), fmaf(m2, kRelMargin, p2));
+}
+
+constexpr u32 kListLen = kBatch + 8;    // survivors of a batch plus null padding
+
 __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const u64 *__restrict__ tile_offsets, const u32 *__restrict__ tile_order,
     const u32 *__restrict__ vals, const float4 *__restrict__ feat, BlendParams bp,
@@ -72,7 +101,9 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     __shared__ float4 s_geo[kBatch + 1];    // du, dv, A', B'
     __shared__ float4 s_cop[kBatch + 1];    // C', lo, r, g
     __shared__ float4 s_tst[kBatch + 1];    // -B'/(2A'), -B'/(2C'), b, -
-    __shared__ __attribute__((aligned(16))) u32 s_list[kBlendThreads / kWave][kBatch + kSurv];
+    // survivor lists hold the records' byte offsets inside s_geo / s_cop / s_tst (at most 4096)
+    __shared__ __attribute__((aligned(16))) unsigned short s_list8[kBlendThreads / kWave][kListLen];
+    __shared__ __attribute__((aligned(16))) unsigned short s_list4[kBlendThreads / kWave][4][kListLen];
 
     u32 tile;
     if (tile_order) {
@@ -89,15 +120,17 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     }
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 grp = lane >> 4, gl = lane & 15u;                // 4x4 sub-block of the lane, pixel inside it
     const u32 tx = tile % bp.tiles_x, ty = tile / bp.tiles_x;
-    const u32 li = (wv & 1u) * 8u + (lane & 7u), lj = (wv >> 1) * 8u + (lane >> 3);
-    const u32 pxi = tx * LMK_GS_TILE + li, pyi = ty * LMK_GS_TILE + lj;
+    const u32 bi = (grp & 1u) * 4u + (gl & 3u), bj = (grp >> 1) * 4u + (gl >> 2);   // pixel inside the 8x8 block
+    const u32 pxi = tx * LMK_GS_TILE + (wv & 1u) * 8u + bi, pyi = ty * LMK_GS_TILE + (wv >> 1) * 8u + bj;
     const bool inside = pxi < bp.width && pyi < bp.height;
     // this wavefront's block centre relative to block 0's, and this lane's pixel centre
     const float bx = (float)((wv & 1u) * 8u), by = (float)((wv >> 1) * 8u);
-    const float ox = bx + ((float)(lane & 7u) - 3.5f), oy = by + ((float)(lane >> 3) - 3.5f);
+    const float ox = bx + ((float)bi - 3.5f), oy = by + ((float)bj - 3.5f);
     const float X0 = (float)(tx * LMK_GS_TILE) + 4.0f, Y0 = (float)(ty * LMK_GS_TILE) + 4.0f;
-    const float kHalf = 3.5f;           // pixel centres of a block span [-3.5, 3.5]^2 about its centre
+    const float kHalf8 = 3.5f;          // pixel centres of a block span [-3.5, 3.5]^2 about its centre
+    const float kHalf4 = 1.5f;          // and those of a sub-block [-1.5, 1.5]^2
 
     const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
     float T = 1.0f, cr = 0.0f, cg = 0.0f, cb = 0.0f;
@@ -105,7 +138,6 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const float kL2E = 1.4426950408889634f;
     // block test: log2(alpha_max) >= log2(1/255) - margin, i.e. alpha down to 0.99990/255 passes
     const float kPass = -7.994353436858858f - 1.5e-4f;
-    const float kRelMargin = -2e-6f;    // times (A' ex^2 + C' ey^2) <= 0: covers fp32 rounding of the test
     constexpr u32 kNullOfs = kBatch * 16u;
 
     if (tid == 0) {
@@ -132,38 +164,58 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
             const u64 npos = base + kBatch + tid;
             next = fetch_record(vals, feat, npos, npos < end);    // in flight during the loops below
         }
-        if (__builtin_amdgcn_ballot_w64(!done) == 0ull) continue;  // this wavefront is finished
+        const u64 alive = __builtin_amdgcn_ballot_w64(!done);
+        if (alive == 0ull) continue;                               // this wavefront is finished
 
         // ---- phase 1: lane = entry; which splats reach this wavefront's block at all?
-        u32 nsurv = 0;
+        u32 n8 = 0;
         for (u32 c0 = 0; c0 < cnt; c0 += kWave) {
             const float4 g = s_geo[c0 + lane];
             const float4 t = s_tst[c0 + lane];
             const float4 co = s_cop[c0 + lane];
-            const float xs = g.x - bx, ys = g.y - by;          // splat centre in block coordinates
-            // candidate 1: x clamped into the block, best y on that vertical line
-            const float ex1 = clamp_pm(xs, kHalf) - xs;
-            const float ey1 = clamp_pm(fmaf(t.y, ex1, ys), kHalf) - ys;
-            const float m1 = fmaf(g.z * ex1, ex1, co.x * ey1 * ey1);
-            const float p1 = fmaf(g.w * ex1, ey1, m1);
-            // candidate 2: y clamped, best x on that horizontal line
-            const float ey2 = clamp_pm(ys, kHalf) - ys;
-            const float ex2 = clamp_pm(fmaf(t.x, ey2, xs), kHalf) - xs;
-            const float m2 = fmaf(g.z * ex2, ex2, co.x * ey2 * ey2);
-            const float p2 = fmaf(g.w * ex2, ey2, m2);
-            const float best = fmaxf(fmaf(m1, kRelMargin, p1), fmaf(m2, kRelMargin, p2));
+            const float xs = g.x - bx, ys = g.y - by;
+            const float best = square_reach(xs, ys, g.z, g.w, co.x, t.x, t.y, kHalf8);
             const bool pass = best + co.y >= kPass;
             const u64 mask = __builtin_amdgcn_ballot_w64(pass);
             const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
-            if (pass) s_list[wv][nsurv + rank] = (c0 + lane) * 16u;
-            nsurv += (u32)__builtin_popcountll(mask);
+            if (pass) s_list8[wv][n8 + rank] = (unsigned short)((c0 + lane) * 16u);
+            n8 += (u32)__builtin_popcountll(mask);
         }
-        if (lane < kSurv) s_list[wv][nsurv + lane] = kNullOfs;   // pad the last group with the null record
 
-        // ---- phase 2: lane = pixel; composite the survivors in list order, kSurv at a time
-        for (u32 k = 0; k < nsurv; k += kSurv) {
-            const uint4 ofs4 = *reinterpret_cast<const uint4 *>(&s_list[wv][k]);
-            const u32 ofs[kSurv] = { ofs4.x, ofs4.y, ofs4.z, ofs4.w };
+        // ---- phase 2: lane = survivor; 64 survivors at a time against the four 4x4 sub-blocks,
+        // one list per sub-block; a sub-block whose pixels have all stopped takes nothing more.
+        u32 n4[4] = { 0u, 0u, 0u, 0u };
+        for (u32 k0 = 0; k0 < n8; k0 += kWave) {
+            const u32 k = k0 + lane;
+            const u32 ofs = k < n8 ? (u32)s_list8[wv][k] : kNullOfs;   // the null record never passes
+            const float4 g = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_geo) + ofs);
+            const float4 t = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_tst) + ofs);
+            const float4 co = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_cop) + ofs);
+            const float xs = g.x - bx, ys = g.y - by;
+#pragma unroll
+            for (u32 q = 0; q < 4; ++q) {
+                const float qx = (q & 1u) ? 2.0f : -2.0f, qy = (q >> 1) ? 2.0f : -2.0f;
+                const float best = square_reach(xs - qx, ys - qy, g.z, g.w, co.x, t.x, t.y, kHalf4);
+                const bool sub_alive = ((alive >> (16u * q)) & 0xffffull) != 0ull;
+                const bool pass = sub_alive && best + co.y >= kPass;
+                const u64 mask = __builtin_amdgcn_ballot_w64(pass);
+                const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+                if (pass) s_list4[wv][q][n4[q] + rank] = (unsigned short)ofs;
+                n4[q] += (u32)__builtin_popcountll(mask);
+            }
+        }
+        const u32 n_mine = grp == 0u ? n4[0] : (grp == 1u ? n4[1] : (grp == 2u ? n4[2] : n4[3]));
+        const u32 l01 = n4[0] > n4[1] ? n4[0] : n4[1], l23 = n4[2] > n4[3] ? n4[2] : n4[3];
+        const u32 longest = l01 > l23 ? l01 : l23;
+        unsigned short *my_list = s_list4[wv][grp];
+        // null records behind every list: a group past its own end keeps reading these
+        if (gl < 8u) my_list[n_mine + gl] = (unsigned short)kNullOfs;
+        const u32 n4_pad = (n_mine + kSurv - 1u) & ~(kSurv - 1u);
+
+        // ---- phase 3: lane = pixel; composite the group's survivors in list order, kSurv at a time
+        for (u32 k = 0; k < longest; k += kSurv) {
+            const uint2 ofs4 = *reinterpret_cast<const uint2 *>(my_list + (k < n4_pad ? k : n4_pad));
+            const u32 ofs[kSurv] = { ofs4.x & 0xffffu, ofs4.x >> 16, ofs4.y & 0xffffu, ofs4.y >> 16 };
             float alpha[kSurv];
             float4 co[kSurv];
 #pragma unroll
