@@ -27,23 +27,55 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP32_PEAK_TFLOPS = 157.3     # 256 CU x 128 lanes x 2 flop x 2.4 GHz (vector FP32, packed-FMA rate)
 
 
-def algorithmic_bytes(n, n_near, n_bin, D, tiles, passes, binning=0):
-    """HBM bytes the method itself must move in preprocess + bin_sort (per frame).
+def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0):
+    """HBM bytes the method itself must move in preprocess + bin_sort (per frame), for the
+    scheme this library runs.
 
     preprocess: mean 12 B + tiles_touched 4 B for every primitive; scale, rotation,
     opacity 32 B for those past the near plane; SH 192 B + outputs 64 B (depth 4,
     rect 8, feature record 48, reread count 4) for binned ones.
     scan: block sums only (negligible).  emit: 16 B per binned primitive (+ 32 B of its
     feature record under binning rule 1) + 12 B per pair.
-    sort: one up-front histogram read of 8 B per pair, then per pass histogram read 8 B +
-    scatter read 12 B + write 12 B per pair.  ranges: 8 B per pair + 8 B per tile.
+    partition by tile: one up-front histogram read of 8 B per pair, then per pass over the
+    tile bits (digits of at most 8 bits: 2 passes at 1080p and 2160p, 1 at 256 x 256)
+    histogram read 8 B + scatter read 12 B + write 12 B per pair.
+    ranges: 8 B per pair + 8 B per tile.  order: 12 B per tile.
+    per-tile sort: 12 B read + 12 B write per pair; a list longer than 16384 pairs is
+    also merged, 24 B per pair and doubling round (plus one copy when the rounds are odd).
     """
+    tile_bits = max(1, (tiles - 1).bit_length())
+    passes = (tile_bits + 7) // 8
     b_pre = 16 * n + 32 * n_near + 256 * n_bin
     b_emit = 4 * n + (48 if binning else 16) * n_bin + 12 * D
-    b_sort = D * (8 + 32 * passes)
-    b_ranges = 8 * D + 8 * (tiles + 1)
-    return dict(preprocess=b_pre, emit=b_emit, sort=b_sort, ranges=b_ranges,
-                total=b_pre + b_emit + b_sort + b_ranges)
+    b_part = D * (8 + 32 * passes)
+    b_ranges = 8 * D + 8 * (tiles + 1) + 12 * tiles
+    b_tsort = 24 * D
+    for L in long_lists:
+        rounds = 0
+        run = 16384
+        while run < L:
+            run *= 2
+            rounds += 1
+        b_tsort += 24 * L * (rounds + (rounds & 1))
+    return dict(preprocess=b_pre, emit=b_emit, partition=b_part, ranges=b_ranges, tile_sort=b_tsort,
+                total=b_pre + b_emit + b_part + b_ranges + b_tsort)
+
+
+def committed_traffic(cfg, binning):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (already scaled
+    by the copy-kernel calibration), from the summary committed under profiles/.  None when
+    there is no measurement for this workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) == 5 and t[0] == f"cfg{cfg}" and t[1] == f"binning{binning}":
+                    out[t[2]] = float(t[3]) + float(t[4])
+    except OSError:
+        return {}
+    return out
 
 
 def main():
@@ -85,7 +117,6 @@ def main():
     ccams = [B.make_camera(c) for c in cams]
     dev = B.Scene(scene)
     tiles = ((W + 15) // 16) * ((H + 15) // 16)
-    passes = (32 + (tiles - 1).bit_length() + 8) // 9      # digits of up to 9 bits
 
     # size the pair buffers from a dry run of every viewpoint (not timed)
     probe_cap = 64_000_000 if args.cfg != 4 else 7_000_000_000
@@ -93,11 +124,14 @@ def main():
     Ds, stats = [], []
     for cc in ccams:
         B.preprocess(dev, cc, fr)
+        B.bin_sort(cc, fr)
         D, status = B.read_status(fr)
+        assert status == B.OK, f"status {status} in the sizing run"
         tt = fr.tiles_touched[:n]
         n_bin = int((tt > 0).sum().item())
+        lens = (fr.tile_offsets[1:] - fr.tile_offsets[:-1])
         Ds.append(D)
-        stats.append(dict(D=D, n_bin=n_bin))
+        stats.append(dict(D=D, n_bin=n_bin, long_lists=[int(x) for x in lens[lens > 16384].tolist()]))
     del fr
     torch.cuda.empty_cache()
     capacity = int(max(Ds) * 1.25) + 4096
@@ -144,6 +178,7 @@ def main():
     t_pre = np.array([m[0].elapsed_time(m[1]) for m in marks])
     t_sort = np.array([m[1].elapsed_time(m[2]) for m in marks])
     t_blend = np.array([m[2].elapsed_time(m[3]) for m in marks])
+    t_frame = np.array([m[0].elapsed_time(m[3]) for m in marks])
     view_of = np.arange(args.steps) % nviews
 
     # ---- CPU oracle: counts E, C (algorithmic pairs) and the baseline time
@@ -155,19 +190,23 @@ def main():
         E, C, n_near, cpu_t = [], [], [], []
         sample_views = list(range(nviews))
         for v in sample_views:
+            # the timed baseline and the pair counts E, C of the metric use the plain binning
+            # rule (a pair for every tile of the support rectangle), whatever rule the GPU ran
             c0 = time.perf_counter()
-            ofr = ref.render_frame(scene, cams[v])
+            ofr = ref.render_frame(scene, dict(cams[v], binning=0))
             cpu_t.append(time.perf_counter() - c0)
-            assert ofr.binned.D == stats[v]["D"], "GPU and oracle disagree on the pair count"
             E.append(int(ofr.img.E.sum())); C.append(int(ofr.img.C.sum()))
             n_near.append(int((ofr.pre.stage != ref.CULL_NEAR).sum()))
+            D_ref = ofr.binned.D if args.binning == 0 else \
+                int(ref.preprocess(scene, cams[v]).tiles_touched.astype(np.uint64).sum())
+            assert D_ref == stats[v]["D"], "GPU and oracle disagree on the pair count"
             del ofr
         cores = len(os.sched_getaffinity(0))
         omp = os.environ.get("OMP_NUM_THREADS")
         threads = min(cores, int(omp)) if omp and omp.isdigit() else cores
         cpu = dict(value=len(sample_views) / sum(cpu_t), unit="frames/s", cores=threads, kind="oracle",
-                   sample=f"cfg {args.cfg}: one whole frame (preprocess, bin+sort, blend) for each of its "
-                          f"{len(sample_views)} viewpoints, {sum(cpu_t):.1f} s of oracle time",
+                   sample=f"cfg {args.cfg}: one whole frame (preprocess, bin+sort, blend; binning rule 0) for each "
+                          f"of its {len(sample_views)} viewpoints, {sum(cpu_t):.1f} s of oracle time",
                    blends_per_s=sum(E) / sum(cpu_t))
 
     out = {
@@ -181,6 +220,7 @@ def main():
                    "binning": args.binning, "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity},
         "stage_ms": {"preprocess": float(t_pre.mean()), "bin_sort": float(t_sort.mean()),
                      "render": float(t_blend.mean())},
+        "frame_ms": {"mean": float(t_frame.mean()), "median": float(np.median(t_frame)), "min": float(t_frame.min())},
         "per_view": [{"pairs": int(Ds[v]), "binned": stats[v]["n_bin"],
                       "preprocess_ms": float(t_pre[view_of == v].mean()),
                       "bin_sort_ms": float(t_sort[view_of == v].mean()),
@@ -194,19 +234,25 @@ def main():
         flops = (14.0 * Ev + 10.0 * Cv)[view_of].sum()
         tf = flops / (t_blend.sum() * 1e-3) / 1e12
         out["blends_per_s"] = blends
+        traffic = committed_traffic(args.cfg, args.binning) if args.n is None and args.views is None else {}
         out["roofline"] = {"kernel": "blend_kernel", "bound": "alu", "achieved": tf, "peak": FP32_PEAK_TFLOPS,
-                           "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": None,
+                           "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": traffic.get("blend_kernel"),
                            "avg_launch_ms": float(t_blend.mean()),
                            "flops_per_launch": float(flops / args.steps)}
-        byts = []
+        byts, byts_pre = [], []
         for v in range(nviews):
-            byts.append(algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles, passes,
-                                          args.binning)["total"])
-        byts = np.array(byts, dtype=np.float64)
+            ab = algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles,
+                                   stats[v]["long_lists"], args.binning)
+            byts.append(ab["total"]); byts_pre.append(ab["preprocess"])
+        byts = np.array(byts, dtype=np.float64); byts_pre = np.array(byts_pre, dtype=np.float64)
         gbs = byts[view_of].sum() / ((t_pre.sum() + t_sort.sum()) * 1e-3) / 1e9
-        out["roofline_hbm_stages"] = {"kernels": "preprocess + scan + emit + radix passes + ranges",
+        gbs_pre = byts_pre[view_of].sum() / (t_pre.sum() * 1e-3) / 1e9
+        gbs_sort = (byts - byts_pre)[view_of].sum() / (t_sort.sum() * 1e-3) / 1e9
+        out["roofline_hbm_stages"] = {"kernels": "preprocess + scan + emit + partition passes + ranges + order + "
+                                                 "per-tile sorts",
                                       "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                      "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                                      "frac": gbs / HBM_PEAK_GBS, "traffic": traffic.get("preprocess+bin_sort"),
+                                      "preprocess_GBs": gbs_pre, "bin_sort_GBs": gbs_sort,
                                       "bytes_per_frame": float(byts.mean())}
         out["cpu_baseline"] = cpu
     print(json.dumps(out), flush=True)

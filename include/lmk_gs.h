@@ -39,6 +39,8 @@ extern "C" {
 
 #define LMK_GS_TILE 16u             /* pixels per tile edge; the only supported value */
 #define LMK_GS_FEAT_STRIDE 12u      /* floats per primitive in lmk_gs_projected.feat */
+/* floats per primitive in lmk_gs_gaussians.sh: 3 (deg+1)^2 rounded up to whole 16-byte vectors (4, 12, 28, 48) */
+#define LMK_GS_SH_STRIDE(deg) ((3u * ((deg) + 1u) * ((deg) + 1u) + 3u) & ~3u)
 
 /* The scene (Sec. 2.2 Eq. 7-8 and the text after Eq. 8). */
 typedef struct lmk_gs_gaussians {
@@ -46,7 +48,9 @@ typedef struct lmk_gs_gaussians {
     const float *scale;    /* [3][n]  diagonal of S, linear and > 0                 */
     const float *rot;      /* [4][n]  quaternion (w,x,y,z) of R, any non-zero norm  */
     const float *opacity;  /* [n]     alpha in [0,1]                                */
-    const float *sh;       /* [(sh_degree+1)^2][3][n] real SH colour coefficients   */
+    const float *sh;       /* [n][LMK_GS_SH_STRIDE(sh_degree)] real SH colour coefficients, one 16-byte
+                              aligned record per primitive: coefficient k of channel c at [3k + c],
+                              the tail of the record unused                          */
     uint32_t n;            /* number of primitives (0 is allowed)                   */
     uint32_t sh_degree;    /* 0..3                                                  */
 } lmk_gs_gaussians;

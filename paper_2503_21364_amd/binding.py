@@ -121,8 +121,13 @@ def _stream_handle(stream) -> int | None:
     return stream.cuda_stream or None
 
 
+def sh_stride(sh_degree: int) -> int:
+    """LMK_GS_SH_STRIDE of include/lmk_gs.h."""
+    return (3 * (sh_degree + 1) ** 2 + 3) & ~3
+
+
 class Scene:
-    """Device-resident primitives (structure of arrays, see include/lmk_gs.h)."""
+    """Device-resident primitives (layouts of include/lmk_gs.h)."""
 
     def __init__(self, scene: dict, device="cuda:0"):
         self.n = int(scene["n"])
@@ -130,8 +135,11 @@ class Scene:
         f = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
         self.mean, self.scale, self.rot = f(scene["mean"]), f(scene["scale"]), f(scene["rot"])
         self.opacity = f(scene["opacity"])
+        # the generator's [coefficient][channel][n] planes become one record per primitive
         ncoef = (self.sh_degree + 1) ** 2
-        self.sh = f(scene["sh"][:ncoef])
+        rec = np.zeros((self.n, sh_stride(self.sh_degree)), np.float32)
+        rec[:, :3 * ncoef] = np.asarray(scene["sh"][:ncoef], np.float32).reshape(3 * ncoef, self.n).T
+        self.sh = f(rec)
         self.c = Gaussians(_ptr(self.mean), _ptr(self.scale), _ptr(self.rot), _ptr(self.opacity),
                            _ptr(self.sh), self.n, self.sh_degree)
 

@@ -84,7 +84,7 @@ int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
     if (g->n > 0) {
         if (!g->mean || !g->scale || !g->rot || !g->opacity || !g->sh) return LMK_GS_ERR_INVALID;
         if (!out->depth || !out->tiles_touched || !out->rect || !out->feat) return LMK_GS_ERR_INVALID;
-        if (!aligned(out->feat, 16) || !aligned(out->rect, 8)) return LMK_GS_ERR_INVALID;
+        if (!aligned(out->feat, 16) || !aligned(out->rect, 8) || !aligned(g->sh, 16)) return LMK_GS_ERR_INVALID;
     }
     if (!aligned(scratch, 256)) return LMK_GS_ERR_INVALID;
     // the part of the scratch this call touches does not depend on the pair capacity

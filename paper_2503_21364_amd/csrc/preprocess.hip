@@ -95,9 +95,12 @@ __device__ __forceinline__ u32 wave_sum(u32 v)
     return v;   // valid in lane 0
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <u32 DEG>
 __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     const float *__restrict__ mean, const float *__restrict__ scale, const float *__restrict__ rot,
-    const float *__restrict__ opacity, const float *__restrict__ sh, u32 n, u32 sh_degree,
+    const float *__restrict__ opacity, const float *__restrict__ sh, u32 n,
     ProjParams pp, ShConsts kc,
     float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
     float4 *__restrict__ feat, u32 *__restrict__ block_sums)
@@ -112,20 +115,24 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
 
     if (i < n) {
         const float *V = pp.cam.view;
-        // inputs are read exactly once per frame: stream them past the caches
+        // inputs are read exactly once per frame: stream them past the caches.  All eleven
+        // geometry planes are requested before the first use: primitives are culled in no
+        // particular index order, so the cache lines of a plane are needed whatever this lane
+        // decides, and one round trip to memory replaces three dependent ones.
         mx = __builtin_nontemporal_load(mean + i); my = __builtin_nontemporal_load(mean + N + i);
         mz = __builtin_nontemporal_load(mean + 2 * N + i);
+        const float qw0 = __builtin_nontemporal_load(rot + i), qx0 = __builtin_nontemporal_load(rot + N + i);
+        const float qy0 = __builtin_nontemporal_load(rot + 2 * N + i), qz0 = __builtin_nontemporal_load(rot + 3 * N + i);
+        const float s0 = __builtin_nontemporal_load(scale + i), s1 = __builtin_nontemporal_load(scale + N + i);
+        const float s2 = __builtin_nontemporal_load(scale + 2 * N + i);
+        const float o_in = __builtin_nontemporal_load(opacity + i);
         const float px = V[0] * mx + V[1] * my + V[2] * mz + V[3];
         const float py = V[4] * mx + V[5] * my + V[6] * mz + V[7];
         pz = V[8] * mx + V[9] * my + V[10] * mz + V[11];
         if (pz > pp.cam.near_z) {
             // Sigma = (R S)(R S)^T from the normalised quaternion
-            const float qw0 = __builtin_nontemporal_load(rot + i), qx0 = __builtin_nontemporal_load(rot + N + i);
-            const float qy0 = __builtin_nontemporal_load(rot + 2 * N + i), qz0 = __builtin_nontemporal_load(rot + 3 * N + i);
             const float qn = sqrtf(qw0 * qw0 + qx0 * qx0 + qy0 * qy0 + qz0 * qz0);
             const float w = qw0 / qn, x = qx0 / qn, y = qy0 / qn, z = qz0 / qn;
-            const float s0 = __builtin_nontemporal_load(scale + i), s1 = __builtin_nontemporal_load(scale + N + i);
-            const float s2 = __builtin_nontemporal_load(scale + 2 * N + i);
             const float M00 = (1.0f - 2.0f * (y * y + z * z)) * s0;
             const float M01 = (2.0f * (x * y - w * z)) * s1;
             const float M02 = (2.0f * (x * z + w * y)) * s2;
@@ -166,7 +173,7 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
             const float c = (U10 * T10 + U11 * T11 + U12 * T12) + pp.cam.lowpass;
 
             const float det = a * c - b * b;
-            o = __builtin_nontemporal_load(opacity + i);
+            o = o_in;
             if (det > 0.0f && !(o < 1.0f / 255.0f)) {
                 cA = c / det; cB = -b / det; cC = a / det;
                 u = (pp.cam.fx * px) / pz + pp.cam.cx;
@@ -219,60 +226,113 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
         cnt = kept;
     }
 
-    if (i < n) {
-        {
-            {
-                if (cnt) {
-                    // view-dependent colour: 0.5 + sum_k Y_k(dir) sh_k, clamped at 0
-                    float dx = mx - pp.cam.cam_pos[0], dy = my - pp.cam.cam_pos[1], dz = mz - pp.cam.cam_pos[2];
-                    const float inv = 1.0f / sqrtf(dx * dx + dy * dy + dz * dz);
-                    dx *= inv; dy *= inv; dz *= inv;
-                    const float *c0 = sh + i;      // plane (k*3 + ch) starts at c0 + (k*3+ch)*N
-                    float Y[16];
-                    Y[0] = kc.k0;
-                    u32 ncoef = 1;
-                    if (sh_degree > 0) {
-                        Y[1] = -kc.k1 * dy; Y[2] = kc.k1 * dz; Y[3] = -kc.k1 * dx;
-                        ncoef = 4;
-                    }
-                    const float xx = dx * dx, yy = dy * dy, zz = dz * dz;
-                    if (sh_degree > 1) {
-                        Y[4] = kc.k2 * dx * dy; Y[5] = -kc.k2 * dy * dz;
-                        Y[6] = kc.k20 * (2.0f * zz - xx - yy);
-                        Y[7] = -kc.k2 * dx * dz; Y[8] = 0.5f * kc.k2 * (xx - yy);
-                        ncoef = 9;
-                    }
-                    if (sh_degree > 2) {
-                        Y[9] = -kc.k33 * dy * (3.0f * xx - yy);
-                        Y[10] = kc.k32 * dx * dy * dz;
-                        Y[11] = -kc.k31 * dy * (4.0f * zz - xx - yy);
-                        Y[12] = kc.k30 * dz * (2.0f * zz - 3.0f * xx - 3.0f * yy);
-                        Y[13] = -kc.k31 * dx * (4.0f * zz - xx - yy);
-                        Y[14] = kc.k32b * dz * (xx - yy);
-                        Y[15] = -kc.k33 * dx * (xx - 3.0f * yy);
-                        ncoef = 16;
-                    }
-                    float r = 0.5f, g = 0.5f, bl = 0.5f;
-#pragma unroll
-                    for (u32 k = 0; k < 16; ++k) {
-                        if (k < ncoef) {
-                            r += Y[k] * __builtin_nontemporal_load(c0 + (size_t)(3 * k + 0) * N);
-                            g += Y[k] * __builtin_nontemporal_load(c0 + (size_t)(3 * k + 1) * N);
-                            bl += Y[k] * __builtin_nontemporal_load(c0 + (size_t)(3 * k + 2) * N);
-                        }
-                    }
-                    r = fmaxf(r, 0.0f); g = fmaxf(g, 0.0f); bl = fmaxf(bl, 0.0f);
+    // view-dependent colour: 0.5 + sum_k Y_k(dir) sh_k, clamped at 0.  The SH records are the bulk of
+    // the input bytes and only primitives that survived need theirs.  Where most of a wavefront's 64
+    // records are needed, the whole contiguous block of records is streamed in fully coalesced loads
+    // through LDS (a lane reading its own 192-byte record directly would touch 64 different cache
+    // lines per load instruction); where few are (close-up views cull most primitives), each survivor
+    // fetches only its own record and the rest of the block is never read.
+    {
+        constexpr u32 kVec = LMK_GS_SH_STRIDE(DEG) / 4;         // 16-byte vectors per record
+        constexpr u32 kCoef = (DEG + 1) * (DEG + 1);
+        constexpr u32 kPart = kVec > 7 ? kVec / 2 : kVec;       // vectors of a record staged at a time
+        constexpr u32 kParts = kVec / kPart;
+        constexpr u32 kSlot = kPart + 1;                        // padded record stride in LDS (bank spread)
+        constexpr u32 kDirectMax = 40;                          // survivors per wavefront served by direct loads
+        static_assert(kPart * kParts == kVec, "records are staged in equal parts");
+        __shared__ f32x4 s_sh[kPreBlock / kWave][kWave * kSlot];
+        const u32 lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+        const u32 survivors = (u32)__builtin_popcountll(__builtin_amdgcn_ballot_w64(cnt > 0));
+        const bool staged = survivors > kDirectMax;             // wave-uniform
+        const u32 first = blockIdx.x * kPreBlock + wv * kWave;  // first primitive of this wavefront
+        const u32 recs = first < n ? (n - first < kWave ? n - first : kWave) : 0u;
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(sh) + (size_t)first * kVec;
+        const f32x4 *rec = reinterpret_cast<const f32x4 *>(sh) + (size_t)i * kVec;   // this primitive's record
+        const f32x4 *lrec = &s_sh[wv][lane * kSlot];
 
-                    depth[i] = pz;
-                    rect[i] = make_ushort4((unsigned short)x0, (unsigned short)y0,
-                                           (unsigned short)x1, (unsigned short)y1);
-                    float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
-                    f[0] = make_float4(u, v, cA, cB);
-                    f[1] = make_float4(cC, o, r, g);
-                    f[2] = make_float4(bl, 0.0f, 0.0f, 0.0f);
-                }
+        float Y[16];
+        if (cnt) {
+            float dx = mx - pp.cam.cam_pos[0], dy = my - pp.cam.cam_pos[1], dz = mz - pp.cam.cam_pos[2];
+            const float inv = 1.0f / sqrtf(dx * dx + dy * dy + dz * dz);
+            dx *= inv; dy *= inv; dz *= inv;
+            Y[0] = kc.k0;
+            if (DEG > 0) { Y[1] = -kc.k1 * dy; Y[2] = kc.k1 * dz; Y[3] = -kc.k1 * dx; }
+            const float xx = dx * dx, yy = dy * dy, zz = dz * dz;
+            if (DEG > 1) {
+                Y[4] = kc.k2 * dx * dy; Y[5] = -kc.k2 * dy * dz;
+                Y[6] = kc.k20 * (2.0f * zz - xx - yy);
+                Y[7] = -kc.k2 * dx * dz; Y[8] = 0.5f * kc.k2 * (xx - yy);
+            }
+            if (DEG > 2) {
+                Y[9] = -kc.k33 * dy * (3.0f * xx - yy);
+                Y[10] = kc.k32 * dx * dy * dz;
+                Y[11] = -kc.k31 * dy * (4.0f * zz - xx - yy);
+                Y[12] = kc.k30 * dz * (2.0f * zz - 3.0f * xx - 3.0f * yy);
+                Y[13] = -kc.k31 * dx * (4.0f * zz - xx - yy);
+                Y[14] = kc.k32b * dz * (xx - yy);
+                Y[15] = -kc.k33 * dx * (xx - 3.0f * yy);
             }
         }
+        // coefficient k of channel ch sits at float [3k + ch] of the record
+        float acc[3] = { 0.5f, 0.5f, 0.5f };
+        f32x4 buf[kVec];
+        if (staged) {
+            // the wavefront's block of records, whole: every load instruction covers 1 KiB of
+            // consecutive addresses, all of them in flight together
+#pragma unroll
+            for (u32 j = 0; j < kVec; ++j) {
+                const u32 idx = j * kWave + lane;
+                buf[j] = idx < recs * kVec ? src[idx] : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+#pragma unroll
+        for (u32 part = 0; part < kParts; ++part) {
+            if (staged) {
+                // transpose through LDS, one part of every record at a time: vector idx of the block
+                // is vector idx % kVec of record idx / kVec
+#pragma unroll
+                for (u32 j = 0; j < kVec; ++j) {
+                    const u32 idx = j * kWave + lane;
+                    const u32 r = idx / kVec, v = idx % kVec;
+                    if (r < recs && v / kPart == part) s_sh[wv][r * kSlot + (v - part * kPart)] = buf[j];
+                }
+                // the loads below read what other lanes of this wavefront stored: LDS accesses of
+                // one wavefront complete in program order
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+            if (cnt) {
+#pragma unroll
+                for (u32 j = 0; j < kPart; ++j) {
+                    const u32 jj = part * kPart + j;
+                    const f32x4 q = staged ? lrec[j] : __builtin_nontemporal_load(rec + jj);
+#pragma unroll
+                    for (u32 m = 0; m < 4; ++m) {
+                        const u32 e = 4 * jj + m;               // compile-time: coefficient e / 3, channel e % 3
+                        if (e / 3 < kCoef) acc[e % 3] += Y[e / 3] * q[m];
+                    }
+                }
+            }
+            if (staged && part + 1 < kParts) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+        if (cnt) {
+            const float r = fmaxf(acc[0], 0.0f), g = fmaxf(acc[1], 0.0f), bl = fmaxf(acc[2], 0.0f);
+
+            depth[i] = pz;
+            rect[i] = make_ushort4((unsigned short)x0, (unsigned short)y0,
+                                   (unsigned short)x1, (unsigned short)y1);
+            float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
+            f[0] = make_float4(u, v, cA, cB);
+            f[1] = make_float4(cC, o, r, g);
+            f[2] = make_float4(bl, 0.0f, 0.0f, 0.0f);
+        }
+    }
+    if (i < n) {
         tiles_touched[i] = cnt;
     }
 
@@ -345,10 +405,18 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const ProjParams &pp, co
     u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
     if (L.pre_blocks > 0) {
-        hipLaunchKernelGGL(preprocess_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
-                           g.mean, g.scale, g.rot, g.opacity, g.sh, g.n, g.sh_degree, pp, kc,
-                           out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
-                           reinterpret_cast<float4 *>(out.feat), block_sums);
+        auto launch = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                               g.mean, g.scale, g.rot, g.opacity, g.sh, g.n, pp, kc,
+                               out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
+                               reinterpret_cast<float4 *>(out.feat), block_sums);
+        };
+        switch (g.sh_degree) {
+            case 0: launch(preprocess_kernel<0>); break;
+            case 1: launch(preprocess_kernel<1>); break;
+            case 2: launch(preprocess_kernel<2>); break;
+            default: launch(preprocess_kernel<3>); break;
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
