@@ -18,8 +18,10 @@
  *  - Arguments are validated on the host before the first HIP call; a
  *    validation failure enqueues nothing.
  *  - Return value: LMK_GS_OK or a negative LMK_GS_ERR_* code.
- *  - Structure-of-arrays inputs: an attribute with k components is k
- *    consecutive planes of n floats (component-major, plane stride n).
+ *  - Geometry inputs are structure-of-arrays: an attribute with k components
+ *    is k consecutive planes of n floats (component-major, plane stride n).
+ *    The SH coefficients are one record per primitive (only primitives that
+ *    survive culling need theirs, and a record is then two cache lines).
  */
 #ifndef LMK_GS_H
 #define LMK_GS_H
@@ -124,11 +126,14 @@ int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
 
 /* Stage 2 (duplication into keys, depth sort at tile granularity, Sec. 2.2 and
  * Sec. 4.2.1).  Prefix-sums tiles_touched, emits one (key, value) per
- * (primitive, tile of its rectangle) -- primitives in index order, rectangle
- * row-major -- sorts all pairs ascending by (tile, depth bits, primitive
- * index) with a stable LSD radix sort, and extracts the per-tile ranges.
- * If the pair count exceeds `capacity`, only the first `capacity` emitted
- * pairs are processed and the status word becomes LMK_GS_ERR_CAPACITY. */
+ * (primitive, tile that lmk_gs_camera.binning keeps) -- primitives in index
+ * order, rectangle row-major -- and leaves all pairs in keys/vals in ascending
+ * (tile, depth bits, primitive index) order, which is unique, together with
+ * the per-tile ranges.  How: the pairs are partitioned by tile id (radix passes
+ * over the tile bits only), then every tile's list is sorted on its own.
+ * keys_alt/vals_alt are working space.  If the pair count exceeds `capacity`,
+ * only the first `capacity` emitted pairs are processed and the status word
+ * becomes LMK_GS_ERR_CAPACITY. */
 int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,
                         const lmk_gs_binned *out,
                         void *scratch, size_t scratch_bytes, void *stream);
