@@ -656,3 +656,71 @@ uint32_t lmk_ref_trace_pixel(uint32_t n, const float *mean2d, const float *conic
                     opacity, rgb, 1.0, bg, &r, trace, cap);
     return r.E;
 }
+
+
+/* ------------------------------------------------------------------------
+ * View-frustum filtering of a voxel grid (Sec. 4.2.2, frustum-based dynamic loading:
+ * primitives are reordered offline into voxels, and per frame the voxels are
+ * filtered against the view frustum instead of the primitives).  [reading: the
+ * report gives no formula.]  A voxel is described by the bounding box of the
+ * means of its primitives and by smax, the largest scale component among them.
+ * It may be skipped only if every primitive in it is certain to be culled by
+ * steps 1 and 8 of lmk_ref_preprocess:
+ *  - near: every point of the box has camera z <= near;
+ *  - sides: for a primitive at camera-space (x, y, z), z > 0, the half-width of
+ *    its support in pixels is at most fx R / z + r0, with
+ *    R = sqrt(tau) sqrt(1 + lim_x^2) smax  (row norm of the clamped Jacobian
+ *    times the largest eigenvalue of Sigma) and r0 = sqrt(tau h); so it is off
+ *    the left edge if fx x + (cx + r0) z < -fx R, a linear inequality, and a
+ *    linear function over a box takes its extremes at the corners.  Likewise
+ *    for the other three edges (the right and bottom edges are those of the
+ *    tile grid, 16 TX and 16 TY).
+ * All of it in fp32 like the other key-path steps, with a relative slack so
+ * that rounding can only keep a voxel too many.  Assumes the 3x3 part of the
+ * view matrix is a rotation.
+ */
+int lmk_ref_voxel_visible(const ref_camera *cam, const float lo[3], const float hi[3], float smax)
+{
+    const float *V = cam->view;
+    const uint32_t TX = (cam->width + cam->tile - 1) / cam->tile;
+    const uint32_t TY = (cam->height + cam->tile - 1) / cam->tile;
+    const float XW = (float)(TX * cam->tile), YH = (float)(TY * cam->tile);
+    const float lim_x = 1.3f * ((0.5f * (float)cam->width) / cam->fx);
+    const float lim_y = 1.3f * ((0.5f * (float)cam->height) / cam->fy);
+    const float st = sqrtf(REF_TAU);
+    const float Rx = (st * sqrtf(1.0f + lim_x * lim_x)) * smax;
+    const float Ry = (st * sqrtf(1.0f + lim_y * lim_y)) * smax;
+    const float r0 = sqrtf(REF_TAU * cam->lowpass);
+    const float cl = cam->cx + r0, cr = (cam->cx - r0) - XW;
+    const float ct = cam->cy + r0, cb = (cam->cy - r0) - YH;
+    float zmax = 0.0f, maxL = 0.0f, minR = 0.0f, maxT = 0.0f, minB = 0.0f, mag = 0.0f;
+    for (int k = 0; k < 8; ++k) {
+        const float wx = (k & 1) ? hi[0] : lo[0], wy = (k & 2) ? hi[1] : lo[1], wz = (k & 4) ? hi[2] : lo[2];
+        const float x = V[0] * wx + V[1] * wy + V[2] * wz + V[3];
+        const float y = V[4] * wx + V[5] * wy + V[6] * wz + V[7];
+        const float z = V[8] * wx + V[9] * wy + V[10] * wz + V[11];
+        const float L = cam->fx * x + cl * z, R = cam->fx * x + cr * z;
+        const float T = cam->fy * y + ct * z, B = cam->fy * y + cb * z;
+        const float m = (cam->fx * fabsf(x) + cam->fy * fabsf(y)) + ((XW + YH) + (fabsf(cam->cx) + fabsf(cam->cy))) * fabsf(z);
+        if (k == 0) { zmax = z; maxL = L; minR = R; maxT = T; minB = B; mag = m; }
+        else {
+            zmax = z > zmax ? z : zmax; maxL = L > maxL ? L : maxL; minR = R < minR ? R : minR;
+            maxT = T > maxT ? T : maxT; minB = B < minB ? B : minB; mag = m > mag ? m : mag;
+        }
+    }
+    const float slack = 1e-5f * mag;
+    const float bx = (cam->fx * Rx) * 1.004f, by = (cam->fy * Ry) * 1.004f;
+    if (zmax + 1e-5f * fabsf(zmax) < cam->near_z) return 0;         /* behind the near plane */
+    if (maxL + slack < -bx) return 0;                               /* off the left edge */
+    if (minR - slack > bx) return 0;                                /* off the right edge */
+    if (maxT + slack < -by) return 0;                               /* above the top edge */
+    if (minB - slack > by) return 0;                                /* below the bottom edge */
+    return 1;
+}
+
+void lmk_ref_voxels_visible(const ref_camera *cam, uint32_t num_voxels, const float *box_lo,
+                            const float *box_hi, const float *smax, uint8_t *visible)
+{
+    for (uint32_t v = 0; v < num_voxels; ++v)
+        visible[v] = (uint8_t)lmk_ref_voxel_visible(cam, box_lo + 3 * (size_t)v, box_hi + 3 * (size_t)v, smax[v]);
+}

@@ -239,6 +239,64 @@ def trace_pixel(pre: SimpleNamespace, lst: np.ndarray, x: int, y: int) -> np.nda
     return trace[:m].copy()
 
 
+def build_voxel_index(scene: dict, voxel_size: float) -> SimpleNamespace:
+    """Offline reordering of the primitives into a voxel grid (Sec. 4.2.2, frustum-based dynamic loading): cell of a primitive =
+    floor(mean / voxel_size) per axis (fp32), cells in Morton order, primitives of a cell in their
+    original order.  Returns the permutation, the first primitive of every occupied voxel, the
+    bounding box of the means and the largest scale component of every voxel."""
+    n = int(scene["n"])
+    mean = _f32(scene["mean"]); scale = _f32(scene["scale"])
+    cell = np.floor(mean / np.float32(voxel_size)).astype(np.int64)            # (3, n)
+    cell -= cell.min(axis=1, keepdims=True) if n else 0
+    assert n == 0 or cell.max() < (1 << 21)
+    key = np.zeros(n, np.uint64)
+    for bit in range(21):
+        for ax in range(3):
+            key |= ((cell[ax].astype(np.uint64) >> np.uint64(bit)) & np.uint64(1)) << np.uint64(3 * bit + ax)
+    perm = np.lexsort((np.arange(n), key)).astype(np.uint32)
+    skey = key[perm]
+    starts = np.flatnonzero(np.concatenate([[True], skey[1:] != skey[:-1]])) if n else np.zeros(0, np.int64)
+    first = np.concatenate([starts, [n]]).astype(np.uint32)
+    V = len(starts)
+    m = mean[:, perm]; s = scale[:, perm].max(axis=0) if n else np.zeros(0, np.float32)
+    lo = np.stack([np.minimum.reduceat(m[a], starts) for a in range(3)], axis=1) if V else np.zeros((0, 3), np.float32)
+    hi = np.stack([np.maximum.reduceat(m[a], starts) for a in range(3)], axis=1) if V else np.zeros((0, 3), np.float32)
+    smax = np.maximum.reduceat(s, starts) if V else np.zeros(0, np.float32)
+    return SimpleNamespace(n=n, perm=perm, first=first, num_voxels=V,
+                           box_lo=np.ascontiguousarray(lo, np.float32), box_hi=np.ascontiguousarray(hi, np.float32),
+                           smax=np.ascontiguousarray(smax, np.float32))
+
+
+def reorder_scene(scene: dict, perm: np.ndarray) -> dict:
+    """The same primitives in the order perm (new index k holds old primitive perm[k])."""
+    out = dict(scene)
+    for k in ("mean", "scale", "rot", "sh"):
+        out[k] = np.ascontiguousarray(np.asarray(scene[k])[..., perm])
+    out["opacity"] = np.ascontiguousarray(np.asarray(scene["opacity"])[perm])
+    return out
+
+
+def voxels_visible(index: SimpleNamespace, cam: dict) -> np.ndarray:
+    """Per voxel: 0 only if every primitive in it is certain to be culled for this camera."""
+    vis = np.empty(index.num_voxels, np.uint8)
+    cc = _camera(cam)
+    lib().lmk_ref_voxels_visible(C.byref(cc), C.c_uint32(index.num_voxels), _p(index.box_lo), _p(index.box_hi),
+                                 _p(index.smax), _p(vis))
+    return vis
+
+
+def voxel_visible(cam: dict, lo, hi, smax: float) -> bool:
+    lo = np.ascontiguousarray(lo, np.float32); hi = np.ascontiguousarray(hi, np.float32)
+    lib().lmk_ref_voxel_visible.restype = C.c_int
+    return bool(lib().lmk_ref_voxel_visible(C.byref(_camera(cam)), _p(lo), _p(hi), C.c_float(float(np.float32(smax)))))
+
+
+def primitives_in_visible_voxels(index: SimpleNamespace, vis: np.ndarray) -> np.ndarray:
+    """Boolean mask over the (reordered) primitives: the voxel holding it passed the filter."""
+    counts = np.diff(index.first.astype(np.int64))
+    return np.repeat(vis.astype(bool), counts)
+
+
 def render_frame(scene: dict, cam: dict) -> SimpleNamespace:
     """Whole path, one frame."""
     pre = preprocess(scene, cam)
