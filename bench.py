@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--binning", type=int, default=1, choices=(0, 1),
                     help="0: a pair for every tile of a support rectangle; 1 (default): only for tiles the "
                          "splat can reach (same image, fewer pairs)")
+    ap.add_argument("--voxel", type=float, default=0.0,
+                    help="edge of the voxels for the offline spatial reordering + per-frame view-frustum filtering "
+                         "of voxels (0 = primitives in the order drawn, no filtering)")
     ap.add_argument("--views", type=int, default=None, help="use only the first K viewpoints of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (no blends/s either)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -115,6 +118,12 @@ def main():
         cams = cams[:max(1, args.views)]
     cams = [dict(c, binning=args.binning) for c in cams]
     ccams = [B.make_camera(c) for c in cams]
+    index = None
+    if args.voxel > 0.0:
+        # offline step, not timed: from here on "the scene" is the reordered scene, for the oracle too
+        index = B.VoxelIndex(scene, args.voxel)
+        scene = index.reorder(scene)
+        index.upload()
     dev = B.Scene(scene)
     tiles = ((W + 15) // 16) * ((H + 15) // 16)
 
@@ -123,7 +132,7 @@ def main():
     fr = B.Frame(n, W, H, probe_cap)
     Ds, stats = [], []
     for cc in ccams:
-        B.preprocess(dev, cc, fr)
+        B.preprocess(dev, cc, fr, index=index)
         B.bin_sort(cc, fr)
         D, status = B.read_status(fr)
         assert status == B.OK, f"status {status} in the sizing run"
@@ -149,7 +158,7 @@ def main():
     nviews = len(ccams)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     for i in range(args.warmup):
-        B.render_frame(dev, ccams[i % nviews], fr)
+        B.render_frame(dev, ccams[i % nviews], fr, index=index)
     torch.cuda.synchronize()
     D_chk, status = B.read_status(fr)
     assert status == B.OK, f"status {status}"
@@ -161,7 +170,7 @@ def main():
         cc = ccams[i % nviews]
         m = marks[i]
         m[0].record()
-        B.preprocess(dev, cc, fr)
+        B.preprocess(dev, cc, fr, index=index)
         m[1].record()
         B.bin_sort(cc, fr)
         m[2].record()
@@ -217,7 +226,10 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg{args.cfg}: {n} Gaussians, {W}x{H}, 16x16 tiles, SH degree 3, "
                                f"{nviews} seeded viewpoints rendered back-to-back",
-                   "binning": args.binning, "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity},
+                   "binning": args.binning, "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity,
+                   "voxel_filter": None if index is None else
+                   {"voxel_size": args.voxel, "voxels": index.num_voxels,
+                    "note": "primitives reordered offline into voxels; voxels filtered against the frustum per frame"}},
         "stage_ms": {"preprocess": float(t_pre.mean()), "bin_sort": float(t_sort.mean()),
                      "render": float(t_blend.mean())},
         "frame_ms": {"mean": float(t_frame.mean()), "median": float(np.median(t_frame)), "min": float(t_frame.min())},
@@ -234,7 +246,8 @@ def main():
         flops = (14.0 * Ev + 10.0 * Cv)[view_of].sum()
         tf = flops / (t_blend.sum() * 1e-3) / 1e12
         out["blends_per_s"] = blends
-        traffic = committed_traffic(args.cfg, args.binning) if args.n is None and args.views is None else {}
+        traffic = committed_traffic(args.cfg, args.binning) \
+            if args.n is None and args.views is None and index is None else {}
         out["roofline"] = {"kernel": "blend_kernel", "bound": "alu", "achieved": tf, "peak": FP32_PEAK_TFLOPS,
                            "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": traffic.get("blend_kernel"),
                            "avg_launch_ms": float(t_blend.mean()),

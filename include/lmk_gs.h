@@ -79,6 +79,21 @@ typedef struct lmk_gs_camera {
                                   under both rules; only pairs that can never contribute are dropped. */
 } lmk_gs_camera;
 
+/* Voxel index of a scene whose primitives were reordered offline into a voxel grid, for the
+ * view-frustum filtering of voxels of Sec. 4.2.2 (frustum-based dynamic loading): per frame the
+ * voxels, not the primitives, are tested against the view frustum, and primitives of voxels
+ * that cannot reach the image are neither read nor projected.  Built by lmk_gs_index_build;
+ * the pointers below are DEVICE copies of its outputs. */
+#define LMK_GS_PRE_BLOCK 256u       /* primitives per group in lmk_gs_voxel_index.block_range */
+typedef struct lmk_gs_voxel_index {
+    const float *box;             /* [num_voxels][8] per voxel: bounding box of its primitives' means
+                                     (lo x,y,z, hi x,y,z), largest scale component among them, 0;
+                                     16-byte aligned                                               */
+    const uint32_t *block_range;  /* [ceil(n / LMK_GS_PRE_BLOCK)][2] first and last voxel holding a
+                                     primitive of each group of LMK_GS_PRE_BLOCK consecutive primitives */
+    uint32_t num_voxels;
+} lmk_gs_voxel_index;
+
 /* Per-primitive results of lmk_gs_preprocess.  For a primitive with
  * tiles_touched == 0 (culled) the other arrays hold unspecified values. */
 typedef struct lmk_gs_projected {
@@ -123,6 +138,35 @@ int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height,
 int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
                           const lmk_gs_projected *out,
                           void *scratch, size_t scratch_bytes, void *stream);
+
+/* Offline step of Sec. 4.2.2, on the HOST (all pointers are host pointers, nothing touches the
+ * GPU): assigns every primitive to the voxel floor(mean / voxel_size) (per axis, in fp32), orders
+ * the occupied voxels along a Morton curve and the primitives of a voxel by their original index.
+ *   perm[k]        original index of the primitive that comes k-th in the new order   [n]
+ *   first[v]       new index of the first primitive of voxel v; first[num_voxels] = n [up to n + 1]
+ *   box            as lmk_gs_voxel_index.box                                           [up to n][8]
+ *   block_range    as lmk_gs_voxel_index.block_range         [ceil(n / LMK_GS_PRE_BLOCK)][2]
+ * The caller permutes its scene arrays with perm, uploads them and the index arrays, and from
+ * then on uses the new primitive indices everywhere.  scale may be linear scales of any sign
+ * (absolute values are used).  LMK_GS_ERR_INVALID for NULL pointers, voxel_size <= 0 or
+ * non-finite means; LMK_GS_ERR_UNSUPPORTED if the grid needs more than 2^21 cells along an axis. */
+int32_t lmk_gs_index_build(const float *mean, const float *scale, uint32_t n, float voxel_size,
+                           uint32_t *perm, uint32_t *first, float *box, uint32_t *block_range,
+                           uint32_t *num_voxels);
+
+/* lmk_gs_preprocess with the view-frustum filtering of voxels in front (Sec. 4.2.2): a group of
+ * LMK_GS_PRE_BLOCK consecutive primitives is skipped -- tiles_touched = 0, nothing else read or
+ * written -- when none of its voxels can reach the image.  A voxel is skipped only if, by a bound
+ * on the support of its largest splat, every primitive in it is certain to be culled by the
+ * near plane or to have an empty support rectangle, so every output is identical to
+ * lmk_gs_preprocess on the same (reordered) scene.  `g` must be the scene in the order of the
+ * index.  The 3x3 part of cam->view must be a rotation (LMK_GS_ERR_UNSUPPORTED otherwise).
+ * block_visible: optional device array [ceil(n / LMK_GS_PRE_BLOCK)] receiving 1 for every group
+ * that was processed, 0 for every group skipped (NULL: kept in scratch). */
+int32_t lmk_gs_preprocess_culled(const lmk_gs_gaussians *g, const lmk_gs_voxel_index *index,
+                                 const lmk_gs_camera *cam, const lmk_gs_projected *out,
+                                 uint8_t *block_visible,
+                                 void *scratch, size_t scratch_bytes, void *stream);
 
 /* Stage 2 (duplication into keys, depth sort at tile granularity, Sec. 2.2 and
  * Sec. 4.2.1).  Prefix-sums tiles_touched, emits one (key, value) per

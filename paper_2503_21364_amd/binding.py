@@ -19,8 +19,11 @@ OK, ERR_INVALID, ERR_CAPACITY, ERR_HIP, ERR_UNSUPPORTED = 0, -1, -2, -3, -4
 TILE = 16
 FEAT_STRIDE = 12
 
+PRE_BLOCK = 256
+
 EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
-           "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version")
+           "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version",
+           "lmk_gs_index_build", "lmk_gs_preprocess_culled")
 
 
 class Gaussians(C.Structure):
@@ -34,6 +37,10 @@ class Camera(C.Structure):
                 ("width", C.c_uint32), ("height", C.c_uint32), ("tile", C.c_uint32),
                 ("near_z", C.c_float), ("lowpass", C.c_float), ("bg", C.c_float * 3),
                 ("binning", C.c_uint32)]
+
+
+class VoxelIndexC(C.Structure):
+    _fields_ = [("box", C.c_void_p), ("block_range", C.c_void_p), ("num_voxels", C.c_uint32)]
 
 
 class Projected(C.Structure):
@@ -72,11 +79,16 @@ def lib() -> C.CDLL:
                                       C.c_void_p, C.c_size_t, C.c_void_p]
         l.lmk_gs_render.argtypes = [C.POINTER(Projected), C.POINTER(Binned), C.POINTER(Camera),
                                     C.c_void_p, C.c_void_p, C.c_void_p]
+        l.lmk_gs_index_build.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_float, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32)]
+        l.lmk_gs_preprocess_culled.argtypes = [C.POINTER(Gaussians), C.POINTER(VoxelIndexC), C.POINTER(Camera),
+                                               C.POINTER(Projected), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.lmk_gs_read_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_void_p]
         l.lmk_gs_strerror.argtypes = [C.c_int32]
         l.lmk_gs_strerror.restype = C.c_char_p
         for name in ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
-                     "lmk_gs_read_status", "lmk_gs_last_hip_error"):
+                     "lmk_gs_read_status", "lmk_gs_last_hip_error", "lmk_gs_index_build",
+                     "lmk_gs_preprocess_culled"):
             getattr(l, name).restype = C.c_int32
         l.lmk_gs_version.restype = C.c_uint32
         _lib = l
@@ -144,6 +156,47 @@ class Scene:
                            _ptr(self.sh), self.n, self.sh_degree)
 
 
+class VoxelIndex:
+    """Offline voxel reordering of a scene (lmk_gs_index_build, host side).  `perm`, `first`, `box`
+    and `block_range` are the host arrays the library returned; `reorder` applies the permutation
+    to a scene dict; `upload` puts the two arrays the kernels read on the device."""
+
+    def __init__(self, scene: dict, voxel_size: float):
+        n = int(scene["n"])
+        mean = np.ascontiguousarray(scene["mean"], dtype=np.float32)
+        scale = np.ascontiguousarray(scene["scale"], dtype=np.float32)
+        nb = (n + PRE_BLOCK - 1) // PRE_BLOCK
+        perm = np.empty(max(n, 1), np.uint32)
+        first = np.empty(n + 1, np.uint32)
+        box = np.empty((max(n, 1), 8), np.float32)
+        block_range = np.empty((max(nb, 1), 2), np.uint32)
+        nv = C.c_uint32(0)
+        rc = lib().lmk_gs_index_build(mean.ctypes.data, scale.ctypes.data, n, float(voxel_size), perm.ctypes.data,
+                                      first.ctypes.data, box.ctypes.data, block_range.ctypes.data, C.byref(nv))
+        if rc != OK:
+            raise LmkGsError(rc, "lmk_gs_index_build")
+        self.n, self.num_voxels, self.voxel_size = n, int(nv.value), float(voxel_size)
+        self.perm = perm[:n]
+        self.first = first[:self.num_voxels + 1].copy()
+        self.box = box[:self.num_voxels].copy()
+        self.block_range = block_range[:nb]
+        self.c = None
+
+    def reorder(self, scene: dict) -> dict:
+        out = dict(scene)
+        for k in ("mean", "scale", "rot", "sh"):
+            out[k] = np.ascontiguousarray(np.asarray(scene[k])[..., self.perm])
+        out["opacity"] = np.ascontiguousarray(np.asarray(scene["opacity"])[self.perm])
+        return out
+
+    def upload(self, device="cuda:0") -> "VoxelIndex":
+        self.box_dev = torch.from_numpy(np.ascontiguousarray(self.box if self.num_voxels else np.zeros((1, 8), np.float32))).to(device)
+        self.block_range_dev = torch.from_numpy(np.ascontiguousarray(
+            self.block_range if len(self.block_range) else np.zeros((1, 2), np.uint32)).view(np.int32)).to(device)
+        self.c = VoxelIndexC(_ptr(self.box_dev), _ptr(self.block_range_dev), self.num_voxels)
+        return self
+
+
 class Frame:
     """All device buffers of one frame in flight: per-primitive outputs, pair
     buffers for `capacity` pairs, scratch, and the image."""
@@ -175,11 +228,21 @@ class Frame:
                              self.capacity, _ptr(self.tile_offsets), _ptr(self.tile_order))
 
 
-def preprocess(scene: Scene, cam: Camera, frame: Frame, stream=None) -> None:
-    rc = lib().lmk_gs_preprocess(C.byref(scene.c), C.byref(cam), C.byref(frame.proj),
-                                 _ptr(frame.scratch), frame.scratch_bytes, _stream_handle(stream))
+def preprocess(scene: Scene, cam: Camera, frame: Frame, stream=None, index: VoxelIndex | None = None,
+               block_visible=None) -> None:
+    """lmk_gs_preprocess, or lmk_gs_preprocess_culled when a (uploaded) voxel index is given;
+    block_visible: optional uint8 device tensor receiving the per-group flags of the filter."""
+    if index is None:
+        rc = lib().lmk_gs_preprocess(C.byref(scene.c), C.byref(cam), C.byref(frame.proj),
+                                     _ptr(frame.scratch), frame.scratch_bytes, _stream_handle(stream))
+        where = "lmk_gs_preprocess"
+    else:
+        rc = lib().lmk_gs_preprocess_culled(C.byref(scene.c), C.byref(index.c), C.byref(cam), C.byref(frame.proj),
+                                            _ptr(block_visible), _ptr(frame.scratch), frame.scratch_bytes,
+                                            _stream_handle(stream))
+        where = "lmk_gs_preprocess_culled"
     if rc != OK:
-        raise LmkGsError(rc, "lmk_gs_preprocess")
+        raise LmkGsError(rc, where)
 
 
 def bin_sort(cam: Camera, frame: Frame, stream=None) -> None:
@@ -205,8 +268,8 @@ def read_status(frame: Frame, stream=None) -> tuple[int, int]:
     return int(d.value), int(s.value)
 
 
-def render_frame(scene: Scene, cam: Camera, frame: Frame, stream=None) -> None:
+def render_frame(scene: Scene, cam: Camera, frame: Frame, stream=None, index: VoxelIndex | None = None) -> None:
     """The whole hot path for one view: three asynchronous calls on one stream."""
-    preprocess(scene, cam, frame, stream)
+    preprocess(scene, cam, frame, stream, index)
     bin_sort(cam, frame, stream)
     render(cam, frame, stream)

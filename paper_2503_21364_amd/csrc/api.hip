@@ -72,9 +72,9 @@ int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height, uint
     return LMK_GS_OK;
 }
 
-int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
-                          const lmk_gs_projected *out, void *scratch, size_t scratch_bytes,
-                          void *stream)
+static int32_t preprocess_common(const lmk_gs_gaussians *g, const lmk_gs_voxel_index *index, uint8_t *block_visible,
+                                 const lmk_gs_camera *cam, const lmk_gs_projected *out,
+                                 void *scratch, size_t scratch_bytes, void *stream)
 {
     ProjParams pp;
     const int32_t rc = check_camera(cam, &pp);
@@ -85,14 +85,43 @@ int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
         if (!g->mean || !g->scale || !g->rot || !g->opacity || !g->sh) return LMK_GS_ERR_INVALID;
         if (!out->depth || !out->tiles_touched || !out->rect || !out->feat) return LMK_GS_ERR_INVALID;
         if (!aligned(out->feat, 16) || !aligned(out->rect, 8) || !aligned(g->sh, 16)) return LMK_GS_ERR_INVALID;
+        if (index) {
+            if (!index->box || !index->block_range || index->num_voxels == 0 || index->num_voxels > g->n)
+                return LMK_GS_ERR_INVALID;
+            if (!aligned(index->box, 16) || !aligned(index->block_range, 8)) return LMK_GS_ERR_INVALID;
+            // the bound on a splat's support assumes a rigid camera: rows of the 3x3 part orthonormal
+            const float *V = cam->view;
+            for (int r = 0; r < 3; ++r)
+                for (int c = r; c < 3; ++c) {
+                    const double d = (double)V[4 * r] * V[4 * c] + (double)V[4 * r + 1] * V[4 * c + 1] +
+                                     (double)V[4 * r + 2] * V[4 * c + 2];
+                    if (std::fabs(d - (r == c ? 1.0 : 0.0)) > 1e-3) return LMK_GS_ERR_UNSUPPORTED;
+                }
+        }
     }
     if (!aligned(scratch, 256)) return LMK_GS_ERR_INVALID;
     // the part of the scratch this call touches does not depend on the pair capacity
     const ScratchLayout L = scratch_layout(g->n, 0, 0);
     if (scratch_bytes < L.digit_totals) return LMK_GS_ERR_CAPACITY;
-    const hipError_t e = launch_preprocess(*g, pp, *out, static_cast<char *>(scratch), L,
-                                           static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_preprocess(*g, g->n > 0 ? index : nullptr, block_visible, pp, *out,
+                                           static_cast<char *>(scratch), L, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
+int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
+                          const lmk_gs_projected *out, void *scratch, size_t scratch_bytes,
+                          void *stream)
+{
+    return preprocess_common(g, nullptr, nullptr, cam, out, scratch, scratch_bytes, stream);
+}
+
+int32_t lmk_gs_preprocess_culled(const lmk_gs_gaussians *g, const lmk_gs_voxel_index *index,
+                                 const lmk_gs_camera *cam, const lmk_gs_projected *out,
+                                 uint8_t *block_visible,
+                                 void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (!index) return LMK_GS_ERR_INVALID;
+    return preprocess_common(g, index, block_visible, cam, out, scratch, scratch_bytes, stream);
 }
 
 int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,

@@ -40,52 +40,93 @@ __device__ __forceinline__ u64 load_D(const ScratchHeader *h, u64 capacity)
 }
 
 // ---------------------------------------------------------------- emit
+// Primitives whose rectangle has more than kBigArea tiles are not expanded by their own
+// workgroup: with a spatially ordered scene the close-up primitives, hundreds of tiles each,
+// sit in a few workgroups, which would then run many times longer than the rest.  Their index
+// and output offset go to a list (one atomic per wavefront) that emit_deferred_kernel expands, one
+// wavefront per primitive (one workgroup per primitive beyond kGiantArea tiles, from the back of
+// the same list), with the same output positions.
+constexpr u32 kBigArea = 128;
+constexpr u32 kGiantArea = 2048;
+
+__device__ __forceinline__ void append_deferred(bool want, u32 *counter, bool from_back, u32 i, u64 offset,
+                                                u32 *__restrict__ big_idx, u64 *__restrict__ big_off, u32 lane, u32 n)
+{
+    const u64 m = __builtin_amdgcn_ballot_w64(want);
+    if (m == 0ull) return;
+    u32 base = 0;
+    const int leader = (int)__builtin_ctzll(m);
+    if ((int)lane == leader) base = atomicAdd(counter, (u32)__builtin_popcountll(m));
+    base = (u32)__builtin_amdgcn_readlane((int)base, leader);
+    if (want) {
+        const u32 k = base + __builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, 0u));
+        if (k < n) {                                  // the list holds one entry per primitive at most
+            const u32 slot = from_back ? n - 1 - k : k;
+            big_idx[slot] = i;
+            big_off[slot] = offset;
+        }
+    }
+}
+
+__device__ __forceinline__ void append_big(u32 area, u32 i, u64 offset, ScratchHeader *header,
+                                           u32 *__restrict__ big_idx, u64 *__restrict__ big_off, u32 lane, u32 n)
+{
+    append_deferred(area > kBigArea && area <= kGiantArea, &header->big_count, false, i, offset, big_idx, big_off, lane, n);
+    append_deferred(area > kGiantArea, &header->giant_count, true, i, offset, big_idx, big_off, lane, n);
+}
+
 __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
     const float *__restrict__ depth, const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
-    ScratchHeader *__restrict__ header)
+    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off)
 {
-    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of tiles_touched inside the workgroup
+    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of the (small) rectangles expanded here
+    __shared__ u32 s_off[kPreBlock];      // exclusive prefix of tiles_touched: where a primitive's pairs start
     __shared__ ushort4 s_rect[kPreBlock];
     __shared__ u32 s_depth[kPreBlock];
     __shared__ u32 s_wave[kPreBlock / kWave];
+    __shared__ u32 s_wave2[kPreBlock / kWave];
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 i = blockIdx.x * kPreBlock + tid;
     const u32 cnt = i < n ? tiles_touched[i] : 0u;
+    const bool big = cnt > kBigArea;
+    const u32 small = big ? 0u : cnt;
     if (cnt) {
         s_rect[tid] = rect[i];
         s_depth[tid] = __float_as_uint(depth[i]);
     }
-    u32 incl = cnt;
+    u32 incl = small, incl2 = cnt;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-        const u32 t = __shfl_up(incl, o, 64);
-        if ((int)lane >= o) incl += t;
+        const u32 t = __shfl_up(incl, o, 64), t2 = __shfl_up(incl2, o, 64);
+        if ((int)lane >= o) { incl += t; incl2 += t2; }
     }
-    if (lane == kWave - 1) s_wave[wv] = incl;
+    if (lane == kWave - 1) { s_wave[wv] = incl; s_wave2[wv] = incl2; }
     __syncthreads();
-    u32 wave_base = 0, total = 0;
+    u32 wave_base = 0, total = 0, wave_base2 = 0, total2 = 0;
 #pragma unroll
     for (u32 k = 0; k < kPreBlock / kWave; ++k) {
-        const u32 w = s_wave[k];
-        if (k < wv) wave_base += w;
-        total += w;
+        const u32 w = s_wave[k], w2 = s_wave2[k];
+        if (k < wv) { wave_base += w; wave_base2 += w2; }
+        total += w; total2 += w2;
     }
-    const u32 excl = wave_base + incl - cnt;
-    s_excl[tid] = excl;
+    s_excl[tid] = wave_base + incl - small;
+    const u32 off = wave_base2 + incl2 - cnt;
+    s_off[tid] = off;
     const u64 base = block_offsets[blockIdx.x];
     if (offsets) {
-        if (i < n) offsets[i] = base + excl;
-        if (i == n - 1) offsets[n] = base + total;
+        if (i < n) offsets[i] = base + off;
+        if (i == n - 1) offsets[n] = base + total2;
     }
     if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
+    append_big(cnt, i, base + off, header, big_idx, big_off, lane, n);
     __syncthreads();
 
     for (u32 j = tid; j < total; j += kPreBlock) {
         // owner = last primitive whose exclusive prefix is <= j (primitives with
-        // zero tiles share a prefix with their successor and are skipped by "last")
+        // nothing to expand share a prefix with their successor and are skipped by "last")
         u32 lo = 0, hi = kPreBlock - 1;
         while (lo < hi) {
             const u32 mid = (lo + hi + 1) >> 1;
@@ -97,7 +138,7 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
         const u32 row = local / w;
         const u32 tx = (u32)r.x + (local - row * w);
         const u32 ty = (u32)r.y + row;
-        const u64 pos = base + j;
+        const u64 pos = base + s_off[lo] + local;
         if (pos < capacity) {
             keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)s_depth[lo];
             vals[pos] = blockIdx.x * kPreBlock + lo;
@@ -105,6 +146,10 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     }
 }
 
+// One wavefront per deferred primitive (persistent grid striding over the list): its rectangle
+// is walked 64 tiles at a time in row-major order; under binning rule 1 (TIGHT) each tile is put
+// through the splat/tile intersection test and the kept ones are compacted with ballot ranks,
+// so the pairs land exactly where the prefix sums say.
 // ---------------------------------------------------------------- emit, binning rule 1
 // Same expansion over the slots of every support rectangle, but each slot is first put
 // through the splat/tile intersection test of lmk_gs_camera.binning == 1 (identical
@@ -128,24 +173,30 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     const float *__restrict__ depth, const float4 *__restrict__ feat, ProjParams pp,
     const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
-    ScratchHeader *__restrict__ header)
+    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off)
 {
-    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of rectangle areas inside the workgroup
+    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of (small) rectangle areas inside the workgroup
+    __shared__ u32 s_bigpre[kPreBlock];   // pairs of deferred (big) primitives that precede each primitive
     __shared__ ushort4 s_rect[kPreBlock];
     __shared__ u32 s_depth[kPreBlock];
     __shared__ float4 s_t0[kPreBlock];    // u, v, A, B
     __shared__ float4 s_t1[kPreBlock];    // C, rx, ry, tau
     __shared__ u32 s_wave[kPreBlock / kWave];
     __shared__ u32 s_wave2[kPreBlock / kWave];
+    __shared__ u32 s_wave3[kPreBlock / kWave];
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 i = blockIdx.x * kPreBlock + tid;
     const u32 kept_cnt = i < n ? tiles_touched[i] : 0u;
-    u32 area = 0;
+    u32 area = 0, full_area = 0;
+    bool big = false;
     if (kept_cnt) {
         const ushort4 r = rect[i];
         s_rect[tid] = r;
         area = ((u32)r.z - (u32)r.x) * ((u32)r.w - (u32)r.y);
+        big = area > kBigArea;
+        full_area = area;
+        if (big) area = 0;                        // its slots are expanded by emit_deferred_kernel
         s_depth[tid] = __float_as_uint(depth[i]);
         const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
         const float4 f0 = f[0], f1 = f[1];
@@ -156,28 +207,32 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
         s_t1[tid] = make_float4(f1.x, -f0.w / f0.z, -f0.w / f1.x, tau);
     }
     // prefix sums over the workgroup: rectangle areas (slot ownership) and kept counts (offsets[])
-    u32 incl = area, incl2 = kept_cnt;
+    const u32 big_cnt = big ? kept_cnt : 0u;
+    u32 incl = area, incl2 = kept_cnt, incl3 = big_cnt;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-        const u32 t = __shfl_up(incl, o, 64), t2 = __shfl_up(incl2, o, 64);
-        if ((int)lane >= o) { incl += t; incl2 += t2; }
+        const u32 t = __shfl_up(incl, o, 64), t2 = __shfl_up(incl2, o, 64), t3 = __shfl_up(incl3, o, 64);
+        if ((int)lane >= o) { incl += t; incl2 += t2; incl3 += t3; }
     }
-    if (lane == kWave - 1) { s_wave[wv] = incl; s_wave2[wv] = incl2; }
+    if (lane == kWave - 1) { s_wave[wv] = incl; s_wave2[wv] = incl2; s_wave3[wv] = incl3; }
     __syncthreads();
-    u32 wave_base = 0, total = 0, wave_base2 = 0, total2 = 0;
+    u32 wave_base = 0, total = 0, wave_base2 = 0, total2 = 0, wave_base3 = 0;
 #pragma unroll
     for (u32 k = 0; k < kPreBlock / kWave; ++k) {
-        const u32 w = s_wave[k], w2 = s_wave2[k];
-        if (k < wv) { wave_base += w; wave_base2 += w2; }
+        const u32 w = s_wave[k], w2 = s_wave2[k], w3 = s_wave3[k];
+        if (k < wv) { wave_base += w; wave_base2 += w2; wave_base3 += w3; }
         total += w; total2 += w2;
     }
     s_excl[tid] = wave_base + incl - area;
+    const u32 kept_excl = wave_base2 + incl2 - kept_cnt;
+    s_bigpre[tid] = wave_base3 + incl3 - big_cnt;
     const u64 base = block_offsets[blockIdx.x];
     if (offsets) {
-        if (i < n) offsets[i] = base + (wave_base2 + incl2 - kept_cnt);
+        if (i < n) offsets[i] = base + kept_excl;
         if (i == n - 1) offsets[n] = base + total2;
     }
     if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
+    append_big(full_area, i, base + kept_excl, header, big_idx, big_off, lane, n);
     __syncthreads();
 
     const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
@@ -224,7 +279,7 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
             round_total += c;
         }
         if (keep) {
-            const u64 pos = base + running + before + rank;
+            const u64 pos = base + running + before + rank + s_bigpre[lo];
             if (pos < capacity) {
                 keys[pos] = ((u64)tile << 32) | (u64)s_depth[lo];
                 vals[pos] = blockIdx.x * kPreBlock + lo;
@@ -232,6 +287,159 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
         }
         running += round_total;
     }
+}
+
+template <bool TIGHT>
+__device__ __forceinline__ void emit_big_part(
+    u32 block, u32 blocks,
+    const ushort4 *__restrict__ rect, const float *__restrict__ depth, const float4 *__restrict__ feat,
+    const ProjParams &pp, u32 tiles_x, u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals,
+    const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx, const u64 *__restrict__ big_off,
+    u32 list_capacity)
+{
+    const u32 lane = threadIdx.x & (kWave - 1);
+    const u32 wave = (block * kPreBlock + threadIdx.x) / kWave, waves = blocks * (kPreBlock / kWave);
+    u32 count = header->big_count;
+    if (count > list_capacity) count = list_capacity;       // cannot happen: one entry per primitive at most
+    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
+    for (u32 k = wave; k < count; k += waves) {
+        const u32 i = big_idx[k];
+        if (i >= list_capacity) continue;                    // an index is a primitive: below n
+        const u64 off = big_off[k];
+        const ushort4 r = rect[i];
+        const u32 dbits = __float_as_uint(depth[i]);
+        const u32 w = (u32)r.z - (u32)r.x, area = w * ((u32)r.w - (u32)r.y);
+        float u = 0.f, v = 0.f, A = 0.f, B = 0.f, Cc = 0.f, rx = 0.f, ry = 0.f, tau = 0.f;
+        if (TIGHT) {
+            const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
+            const float4 f0 = f[0], f1 = f[1];
+            const u32 bits = __float_as_uint(f1.y);
+            const int E = (int)((bits >> 23) & 0xffu) - 127;
+            tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
+            u = f0.x; v = f0.y; A = f0.z; B = f0.w; Cc = f1.x;
+            rx = -f0.w / f0.z; ry = -f0.w / f1.x;
+        }
+        u32 running = 0;
+        for (u32 t0 = 0; t0 < area; t0 += kWave) {           // area > 0 implies w > 0
+            const u32 t = t0 + lane;
+            bool keep = t < area;
+            const u32 row = t / w;
+            const u32 tx = (u32)r.x + (t - row * w), ty = (u32)r.y + row;
+            if (TIGHT && keep) {
+                const float xs = u - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+                const float ys = v - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+                const float ex1 = emit_clampf(xs, -h, h) - xs;
+                const float ey1 = emit_clampf(ys + ry * ex1, -h, h) - ys;
+                const float ey2 = emit_clampf(ys, -h, h) - ys;
+                const float ex2 = emit_clampf(xs + rx * ey2, -h, h) - xs;
+                const float q1 = emit_quad_adj(A, B, Cc, ex1, ey1);
+                const float q2 = emit_quad_adj(A, B, Cc, ex2, ey2);
+                keep = (q1 < q2 ? q1 : q2) <= tau;
+            }
+            const u64 mask = __builtin_amdgcn_ballot_w64(keep);
+            if (keep) {
+                const u64 pos = off + running +
+                                __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+                if (pos < capacity) {
+                    keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
+                    vals[pos] = i;
+                }
+            }
+            running += (u32)__builtin_popcountll(mask);
+        }
+    }
+}
+
+// The same for the few primitives that cover thousands of tiles: one workgroup each, 256 tiles
+// per round, kept tiles ranked across the workgroup.
+template <bool TIGHT>
+__device__ __forceinline__ void emit_giant_part(
+    u32 block, u32 blocks,
+    const ushort4 *__restrict__ rect, const float *__restrict__ depth, const float4 *__restrict__ feat,
+    const ProjParams &pp, u32 tiles_x, u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals,
+    const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx, const u64 *__restrict__ big_off,
+    u32 list_capacity)
+{
+    __shared__ u32 s_wave[kPreBlock / kWave];
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    u32 count = header->giant_count;
+    if (count > list_capacity) count = list_capacity;
+    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
+    for (u32 k = block; k < count; k += blocks) {             // block-uniform
+        const u32 slot = list_capacity - 1 - k;
+        const u32 i = big_idx[slot];
+        if (i >= list_capacity) continue;
+        const u64 off = big_off[slot];
+        const ushort4 r = rect[i];
+        const u32 dbits = __float_as_uint(depth[i]);
+        const u32 w = (u32)r.z - (u32)r.x, area = w * ((u32)r.w - (u32)r.y);
+        float u = 0.f, v = 0.f, A = 0.f, B = 0.f, Cc = 0.f, rx = 0.f, ry = 0.f, tau = 0.f;
+        if (TIGHT) {
+            const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
+            const float4 f0 = f[0], f1 = f[1];
+            const u32 bits = __float_as_uint(f1.y);
+            const int E = (int)((bits >> 23) & 0xffu) - 127;
+            tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
+            u = f0.x; v = f0.y; A = f0.z; B = f0.w; Cc = f1.x;
+            rx = -f0.w / f0.z; ry = -f0.w / f1.x;
+        }
+        u32 running = 0;
+        for (u32 t0 = 0; t0 < area; t0 += kPreBlock) {
+            const u32 t = t0 + tid;
+            bool keep = t < area;
+            const u32 row = t / w;
+            const u32 tx = (u32)r.x + (t - row * w), ty = (u32)r.y + row;
+            if (TIGHT && keep) {
+                const float xs = u - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+                const float ys = v - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
+                const float ex1 = emit_clampf(xs, -h, h) - xs;
+                const float ey1 = emit_clampf(ys + ry * ex1, -h, h) - ys;
+                const float ey2 = emit_clampf(ys, -h, h) - ys;
+                const float ex2 = emit_clampf(xs + rx * ey2, -h, h) - xs;
+                const float q1 = emit_quad_adj(A, B, Cc, ex1, ey1);
+                const float q2 = emit_quad_adj(A, B, Cc, ex2, ey2);
+                keep = (q1 < q2 ? q1 : q2) <= tau;
+            }
+            const u64 mask = __builtin_amdgcn_ballot_w64(keep);
+            const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+            __syncthreads();                               // s_wave free again
+            if (lane == 0) s_wave[wv] = (u32)__builtin_popcountll(mask);
+            __syncthreads();
+            u32 before = 0, round_total = 0;
+#pragma unroll
+            for (u32 q = 0; q < kPreBlock / kWave; ++q) {
+                const u32 c = s_wave[q];
+                if (q < wv) before += c;
+                round_total += c;
+            }
+            if (keep) {
+                const u64 pos = off + running + before + rank;
+                if (pos < capacity) {
+                    keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
+                    vals[pos] = i;
+                }
+            }
+            running += round_total;
+        }
+    }
+}
+
+// One launch for both: the first kGiantBlocks workgroups take the giants, the rest the big ones.
+constexpr u32 kGiantBlocks = 256;
+
+template <bool TIGHT>
+__global__ __launch_bounds__(kPreBlock) void emit_deferred_kernel(
+    const ushort4 *__restrict__ rect, const float *__restrict__ depth, const float4 *__restrict__ feat,
+    ProjParams pp, u32 tiles_x, u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals,
+    const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx, const u64 *__restrict__ big_off,
+    u32 list_capacity)
+{
+    if (blockIdx.x < kGiantBlocks)
+        emit_giant_part<TIGHT>(blockIdx.x, kGiantBlocks, rect, depth, feat, pp, tiles_x, capacity, keys, vals,
+                               header, big_idx, big_off, list_capacity);
+    else
+        emit_big_part<TIGHT>(blockIdx.x - kGiantBlocks, gridDim.x - kGiantBlocks, rect, depth, feat, pp, tiles_x,
+                             capacity, keys, vals, header, big_idx, big_off, list_capacity);
 }
 
 // ---------------------------------------------------------------- radix sort
@@ -314,7 +522,18 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kSortThreads + tid;
-            if (idx < D) atomicAdd(&s_hist[(u32)(k[j] >> shift) & dmask], 1u);
+            const bool valid = idx < D;
+            const u32 d = (u32)(k[j] >> shift) & dmask;
+            // pairs of a spatially ordered scene arrive in runs of one tile: a wavefront whose 64
+            // keys share a digit adds once instead of queueing 64 atomics on one LDS word
+            const u64 live = __builtin_amdgcn_ballot_w64(valid);
+            const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
+            const u64 same = __builtin_amdgcn_ballot_w64(valid && d == d0);
+            if (live != 0ull && same == live && (live & 1ull)) {
+                if ((tid & (kWave - 1)) == 0) atomicAdd(&s_hist[d0], (u32)__builtin_popcountll(live));
+            } else if (valid) {
+                atomicAdd(&s_hist[d], 1u);
+            }
         }
         __syncthreads();
         for (u32 d = tid; d < kMaxRadix; d += kSortThreads) table[(u64)d * table_stride + tile] = s_hist[d];
@@ -524,9 +743,11 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 
 // ---------------------------------------------------------------- ranges
 __global__ __launch_bounds__(256) void tile_ranges_kernel(
-    const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
+    const u64 *__restrict__ keys, ScratchHeader *__restrict__ header, u64 capacity,
     u32 num_tiles, u64 *__restrict__ tile_offsets, u64 *__restrict__ offsets_if_empty)
 {
+    // the emit stage's list of deferred primitives has been consumed: empty it for the next call
+    if (blockIdx.x == 0 && threadIdx.x == 0) { header->big_count = 0; header->giant_count = 0; }
     // with no primitives the emit kernel never runs: the one-entry prefix sum is written here
     if (offsets_if_empty && blockIdx.x == 0 && threadIdx.x == 0) offsets_if_empty[0] = 0;
     const u64 D = load_D(header, capacity);
@@ -891,6 +1112,8 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     u64 *offsets = reinterpret_cast<u64 *>(scratch + L.offsets);
     u32 *order = reinterpret_cast<u32 *>(scratch + L.order);
     u32 *classes = reinterpret_cast<u32 *>(scratch + L.classes);
+    u32 *big_idx = reinterpret_cast<u32 *>(scratch + L.big_idx);
+    u64 *big_off = reinterpret_cast<u64 *>(scratch + L.big_off);
     const u32 num_tiles = pp.tiles_x * pp.tiles_y;
     const SortPlan plan = sort_plan(num_tiles);
 
@@ -901,15 +1124,28 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     u32 *vout = (plan.passes & 1u) ? out.vals : out.vals_alt;
 
     if (L.pre_blocks > 0) {
-        if (pp.cam.binning == 1u)
+        // the deferred primitives are expanded by a fixed grid of wavefronts striding over the list
+        const u32 big_grid = kGiantBlocks + (L.pre_blocks < 2048u ? L.pre_blocks : 2048u);
+        if (pp.cam.binning == 1u) {
             hipLaunchKernelGGL(emit_tight_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                reinterpret_cast<const float4 *>(proj.feat), pp,
-                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header);
-        else
+                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
+                               big_idx, big_off);
+            hipLaunchKernelGGL(emit_deferred_kernel<true>, dim3(big_grid), dim3(kPreBlock), 0, stream,
+                               reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
+                               reinterpret_cast<const float4 *>(proj.feat), pp, pp.tiles_x, out.capacity,
+                               kin, vin, header, big_idx, big_off, n);
+        } else {
             hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header);
+                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
+                               big_idx, big_off);
+            hipLaunchKernelGGL(emit_deferred_kernel<false>, dim3(big_grid), dim3(kPreBlock), 0, stream,
+                               reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
+                               reinterpret_cast<const float4 *>(proj.feat), pp, pp.tiles_x, out.capacity,
+                               kin, vin, header, big_idx, big_off, n);
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -13,7 +13,7 @@ typedef uint64_t u64;
 typedef uint32_t u32;
 
 constexpr u32 kWave = 64;               // CDNA wavefront width
-constexpr u32 kPreBlock = 256;          // primitives per preprocess / emit workgroup
+constexpr u32 kPreBlock = LMK_GS_PRE_BLOCK;   // primitives per preprocess / emit workgroup
 constexpr u32 kSortThreads = 256;       // radix sort workgroup
 constexpr u32 kSortItems = 16;          // keys per thread
 constexpr u32 kSortTile = kSortThreads * kSortItems;   // 4096 pairs per workgroup pass
@@ -27,6 +27,8 @@ struct ScratchHeader {
     u64 dup_count;      // D = sum of tiles_touched
     int32_t status;     // sticky LMK_GS_* code set by kernels
     int32_t pad;
+    u32 big_count;      // emit stage: deferred primitives expanded one wavefront each (front of the list)
+    u32 giant_count;    // ... and one workgroup each (back of the list)
 };
 
 // Carving of the caller's scratch buffer (all offsets multiples of 256 bytes).
@@ -34,12 +36,15 @@ struct ScratchLayout {
     size_t header;        // ScratchHeader
     size_t block_sums;    // u32 [pre_blocks]      tile counts per preprocess workgroup
     size_t block_offsets; // u64 [pre_blocks + 1]  their exclusive prefix sum
+    size_t voxel_flags;   // u8  [n]               voxel filter: 1 = the voxel may reach the image (at most n voxels)
     size_t digit_totals;  // u64 [kMaxPasses][512] global digit histogram of each pass
     size_t partials;      // u32 [kHistBlocks][kMaxPasses][512] per-workgroup digit counts
     size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
     size_t offsets;       // u64 [512][sort_tiles] their output offsets
     size_t order;         // u32 [tiles]     tile ids by descending list length
     size_t classes;       // u32 [4]         tiles with lists longer than kHugeMin / kMidMin pairs (front of `order`)
+    size_t big_idx;       // u32 [n]         primitives whose rectangles are expanded one wavefront each
+    size_t big_off;       // u64 [n]         and where their pairs start
     size_t total;
     u32 pre_blocks;
     u64 sort_tiles;       // ceil(capacity / kSortTile)
@@ -57,12 +62,15 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
     L.header = o;        o += align256(sizeof(ScratchHeader));
     L.block_sums = o;    o += align256(sizeof(u32) * (size_t)(L.pre_blocks + 1));
     L.block_offsets = o; o += align256(sizeof(u64) * ((size_t)L.pre_blocks + 1));
+    L.voxel_flags = o;   o += align256((size_t)n + 1);
     L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kMaxRadix);
     L.partials = o;      o += align256(sizeof(u32) * (size_t)kHistBlocks * kMaxPasses * kMaxRadix);
     L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
     L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
     L.order = o;         o += align256(sizeof(u32) * (size_t)(tiles + 1));
     L.classes = o;       o += align256(sizeof(u32) * 4);
+    L.big_idx = o;       o += align256(sizeof(u32) * ((size_t)n + 1));
+    L.big_off = o;       o += align256(sizeof(u64) * ((size_t)n + 1));
     L.total = o;
     return L;
 }
@@ -103,7 +111,10 @@ struct ProjParams {
 };
 
 // Launchers (each returns the hipError_t of its launches).
-hipError_t launch_preprocess(const lmk_gs_gaussians &g, const ProjParams &pp, const lmk_gs_projected &out,
+// index == nullptr: every primitive is processed; else the voxel filter runs first and the
+// per-workgroup decisions are also written to block_visible when that is not nullptr
+hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index *index, uint8_t *block_visible,
+                             const ProjParams &pp, const lmk_gs_projected &out,
                              char *scratch, const ScratchLayout &L, hipStream_t stream);
 hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams &pp, const lmk_gs_binned &out,
                            char *scratch, const ScratchLayout &L, hipStream_t stream);

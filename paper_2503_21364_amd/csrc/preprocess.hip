@@ -97,16 +97,92 @@ __device__ __forceinline__ u32 wave_sum(u32 v)
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// ---------------------------------------------------------------- voxel filter (Sec. 4.2.2)
+// Can any primitive of a voxel (bounding box of the means, largest scale component smax) be
+// binned?  Not if the whole box is behind the near plane, or beyond one image edge by more
+// than the largest support a primitive of the voxel can have there: for a primitive at
+// camera-space (x, y, z), z > 0, the half-width of its support is at most fx R / z + r0 pixels,
+// R = sqrt(11.09) sqrt(1 + lim_x^2) smax (row norm of the clamped EWA Jacobian times the largest
+// eigenvalue of Sigma), r0 = sqrt(11.09 lowpass); "off the left edge" then reads
+// fx x + (cx + r0) z < -fx R, linear in the position, so the box corners decide.  Evaluated in
+// fp32 without contraction like every step that decides an integer; the slack terms make
+// rounding keep a voxel rather than drop it.
+__device__ __forceinline__ bool voxel_visible(const ProjParams &pp, const float4 b0, const float4 b1)
+{
+    const float *V = pp.cam.view;
+    const float lo[3] = { b0.x, b0.y, b0.z }, hi[3] = { b0.w, b1.x, b1.y };
+    const float smax = b1.z;
+    const float XW = (float)(pp.tiles_x * LMK_GS_TILE), YH = (float)(pp.tiles_y * LMK_GS_TILE);
+    const float st = sqrtf(11.09f);
+    const float Rx = (st * sqrtf(1.0f + pp.lim_x * pp.lim_x)) * smax;
+    const float Ry = (st * sqrtf(1.0f + pp.lim_y * pp.lim_y)) * smax;
+    const float r0 = sqrtf(11.09f * pp.cam.lowpass);
+    const float cl = pp.cam.cx + r0, cr = (pp.cam.cx - r0) - XW;
+    const float ct = pp.cam.cy + r0, cb = (pp.cam.cy - r0) - YH;
+    const float cm = (XW + YH) + (fabsf(pp.cam.cx) + fabsf(pp.cam.cy));
+    float zmax = 0.f, maxL = 0.f, minR = 0.f, maxT = 0.f, minB = 0.f, mag = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float wx = (k & 1) ? hi[0] : lo[0], wy = (k & 2) ? hi[1] : lo[1], wz = (k & 4) ? hi[2] : lo[2];
+        const float x = V[0] * wx + V[1] * wy + V[2] * wz + V[3];
+        const float y = V[4] * wx + V[5] * wy + V[6] * wz + V[7];
+        const float z = V[8] * wx + V[9] * wy + V[10] * wz + V[11];
+        const float L = pp.cam.fx * x + cl * z, R = pp.cam.fx * x + cr * z;
+        const float T = pp.cam.fy * y + ct * z, B = pp.cam.fy * y + cb * z;
+        const float m = (pp.cam.fx * fabsf(x) + pp.cam.fy * fabsf(y)) + cm * fabsf(z);
+        if (k == 0) { zmax = z; maxL = L; minR = R; maxT = T; minB = B; mag = m; }
+        else {
+            zmax = z > zmax ? z : zmax; maxL = L > maxL ? L : maxL; minR = R < minR ? R : minR;
+            maxT = T > maxT ? T : maxT; minB = B < minB ? B : minB; mag = m > mag ? m : mag;
+        }
+    }
+    const float slack = 1e-5f * mag;
+    const float bx = (pp.cam.fx * Rx) * 1.004f, by = (pp.cam.fy * Ry) * 1.004f;
+    if (zmax + 1e-5f * fabsf(zmax) < pp.cam.near_z) return false;
+    if (maxL + slack < -bx) return false;
+    if (minR - slack > bx) return false;
+    if (maxT + slack < -by) return false;
+    if (minB - slack > by) return false;
+    return true;
+}
+
+// One thread per voxel.
+__global__ __launch_bounds__(256) void voxel_flags_kernel(
+    const float4 *__restrict__ box, u32 num_voxels, ProjParams pp, unsigned char *__restrict__ voxel_flags)
+{
+    const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= num_voxels) return;
+    voxel_flags[v] = voxel_visible(pp, box[2 * (size_t)v], box[2 * (size_t)v + 1]) ? 1 : 0;
+}
+
 template <u32 DEG>
 __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     const float *__restrict__ mean, const float *__restrict__ scale, const float *__restrict__ rot,
     const float *__restrict__ opacity, const float *__restrict__ sh, u32 n,
     ProjParams pp, ShConsts kc,
     float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
-    float4 *__restrict__ feat, u32 *__restrict__ block_sums)
+    float4 *__restrict__ feat, u32 *__restrict__ block_sums,
+    const unsigned char *__restrict__ voxel_flags, const uint2 *__restrict__ block_range, u32 num_voxels,
+    unsigned char *__restrict__ block_visible)
 {
     __shared__ u32 s_part[kPreBlock / kWave];
     const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
+    if (voxel_flags) {
+        // voxel filter: does any voxel holding one of this workgroup's primitives pass?
+        const uint2 r = block_range[blockIdx.x];
+        // a corrupt range can only cost time, never an out-of-bounds read
+        const u32 last = r.y < num_voxels ? r.y : num_voxels - 1;
+        int mine = 0;
+        for (u32 v = r.x + threadIdx.x; v <= last; v += kPreBlock) mine |= voxel_flags[v];
+        const int any = __syncthreads_or(mine);
+        if (block_visible && threadIdx.x == 0) block_visible[blockIdx.x] = any ? 1 : 0;
+        if (!any) {
+            // nothing of this workgroup can be binned: no input is read
+            if (i < n) tiles_touched[i] = 0;
+            if (threadIdx.x == 0) block_sums[blockIdx.x] = 0;
+            return;
+        }
+    }
     const size_t N = n;
     u32 cnt = 0;            // tiles of the support rectangle (then: tiles kept)
     float mx = 0.f, my = 0.f, mz = 0.f, pz = 0.f, o = 0.f;
@@ -394,10 +470,13 @@ __global__ __launch_bounds__(kScanThreads) void scan_block_sums_kernel(
         header->dup_count = s_carry;
         header->status = LMK_GS_OK;
         header->pad = 0;
+        header->big_count = 0;
+        header->giant_count = 0;
     }
 }
 
-hipError_t launch_preprocess(const lmk_gs_gaussians &g, const ProjParams &pp, const lmk_gs_projected &out,
+hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index *index, uint8_t *block_visible,
+                             const ProjParams &pp, const lmk_gs_projected &out,
                              char *scratch, const ScratchLayout &L, hipStream_t stream)
 {
     static const ShConsts kc = make_sh_consts();
@@ -405,11 +484,25 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const ProjParams &pp, co
     u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
     if (L.pre_blocks > 0) {
+        const unsigned char *vflags = nullptr;
+        const uint2 *ranges = nullptr;
+        u32 num_voxels = 0;
+        if (index) {
+            unsigned char *f = reinterpret_cast<unsigned char *>(scratch + L.voxel_flags);
+            num_voxels = index->num_voxels;
+            ranges = reinterpret_cast<const uint2 *>(index->block_range);
+            hipLaunchKernelGGL(voxel_flags_kernel, dim3((num_voxels + 255) / 256), dim3(256), 0, stream,
+                               reinterpret_cast<const float4 *>(index->box), num_voxels, pp, f);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            vflags = f;
+        }
         auto launch = [&](auto kernel) {
             hipLaunchKernelGGL(kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                g.mean, g.scale, g.rot, g.opacity, g.sh, g.n, pp, kc,
                                out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
-                               reinterpret_cast<float4 *>(out.feat), block_sums);
+                               reinterpret_cast<float4 *>(out.feat), block_sums,
+                               vflags, ranges, num_voxels, index ? block_visible : nullptr);
         };
         switch (g.sh_degree) {
             case 0: launch(preprocess_kernel<0>); break;

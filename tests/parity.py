@@ -33,9 +33,9 @@ def to_np(t):
     return t.detach().cpu().numpy()
 
 
-def gpu_frame(scene_dev: B.Scene, cam: dict, capacity: int, want_offsets=True) -> B.Frame:
+def gpu_frame(scene_dev: B.Scene, cam: dict, capacity: int, want_offsets=True, index=None) -> B.Frame:
     fr = B.Frame(scene_dev.n, int(cam["width"]), int(cam["height"]), capacity, want_offsets=want_offsets)
-    B.render_frame(scene_dev, B.make_camera(cam), fr)
+    B.render_frame(scene_dev, B.make_camera(cam), fr, index=index)
     torch.cuda.synchronize()
     return fr
 
@@ -100,14 +100,15 @@ def compare_image(fr: B.Frame, img, cam: dict, max_ambiguous_share=0.02) -> dict
 
 
 def full_compare(scene: dict, cam: dict, capacity: int | None = None, scene_dev: B.Scene | None = None,
-                 oracle_frame=None) -> SimpleNamespace:
-    """GPU frame vs oracle frame, every stage, element by element."""
+                 oracle_frame=None, index=None) -> SimpleNamespace:
+    """GPU frame vs oracle frame, every stage, element by element.  With a voxel index the GPU
+    runs the voxel filter first; the oracle frame is always the unfiltered definition."""
     ofr = ref.render_frame(scene, cam) if oracle_frame is None else oracle_frame
     if capacity is None:
         capacity = ofr.binned.D + 1000
     if scene_dev is None:
         scene_dev = B.Scene(scene)
-    fr = gpu_frame(scene_dev, cam, capacity)
+    fr = gpu_frame(scene_dev, cam, capacity, index=index)
     stats = {}
     stats.update(compare_projected(fr, ofr.pre))
     stats.update(compare_binned(fr, ofr.binned))

@@ -143,6 +143,60 @@ def test_bin_sort_and_render_reject_bad_arguments():
     assert lib.lmk_gs_read_status(None, None, None, None) == B.ERR_INVALID
 
 
+def test_index_build_matches_the_oracle_and_rejects_bad_input():
+    from oracle import ref
+    for cfg, n, vs in [(2, 50_000, 2.0), (3, 80_000, 40.0), (0, 1000, 0.3), (1, 777, 1.0), (0, 1, 1.0)]:
+        sc = scenes.make_scene(cfg, n=n, seed=11 + cfg)
+        vi = B.VoxelIndex(sc, vs)
+        oi = ref.build_voxel_index(sc, vs)
+        assert vi.num_voxels == oi.num_voxels
+        np.testing.assert_array_equal(vi.perm, oi.perm)
+        np.testing.assert_array_equal(vi.first, oi.first)
+        np.testing.assert_array_equal(vi.box[:, 0:3], oi.box_lo)
+        np.testing.assert_array_equal(vi.box[:, 3:6], oi.box_hi)
+        np.testing.assert_array_equal(vi.box[:, 6], oi.smax)
+        # voxel range of every group of PRE_BLOCK primitives, by definition
+        vox_of = np.repeat(np.arange(oi.num_voxels), np.diff(oi.first.astype(np.int64)))
+        for b in range(len(vi.block_range)):
+            a, e = b * B.PRE_BLOCK, min((b + 1) * B.PRE_BLOCK, n) - 1
+            assert tuple(vi.block_range[b]) == (vox_of[a], vox_of[e])
+    lib = B.lib()
+    nv = C.c_uint32(5)
+    m = np.zeros((3, 4), np.float32); sc_ = np.ones((3, 4), np.float32)
+    perm = np.zeros(4, np.uint32); first = np.zeros(5, np.uint32); box = np.zeros((4, 8), np.float32)
+    br = np.zeros((1, 2), np.uint32)
+    call = lambda mean=m, vs=1.0, p=perm: lib.lmk_gs_index_build(
+        None if mean is None else mean.ctypes.data, sc_.ctypes.data, 4, vs,
+        None if p is None else p.ctypes.data, first.ctypes.data, box.ctypes.data, br.ctypes.data, C.byref(nv))
+    assert call() == B.OK and nv.value == 1
+    assert call(vs=0.0) == B.ERR_INVALID and call(vs=float("nan")) == B.ERR_INVALID
+    assert call(mean=None) == B.ERR_INVALID and call(p=None) == B.ERR_INVALID
+    bad = m.copy(); bad[1, 2] = np.inf
+    assert call(mean=bad) == B.ERR_INVALID
+    wide = m.copy(); wide[0, 0] = 1e9
+    assert call(mean=wide, vs=1.0) == B.ERR_UNSUPPORTED
+    assert lib.lmk_gs_index_build(None, None, 0, 1.0, None, None, None, None, C.byref(nv)) == B.OK and nv.value == 0
+
+
+def test_preprocess_culled_rejects_bad_arguments():
+    lib = B.lib()
+    g, proj, _ = _args()
+    cam = _good_camera()
+    scratch = C.c_void_p(0x10000)
+    idx = B.VoxelIndexC(0x1000, 0x1000, 3)
+    call = lambda i_, c_=cam: lib.lmk_gs_preprocess_culled(
+        C.byref(g), None if i_ is None else C.byref(i_), C.byref(c_), C.byref(proj), None, scratch, 1 << 20, None)
+    assert C.sizeof(B.VoxelIndexC) == 24
+    assert call(None) == B.ERR_INVALID
+    assert call(B.VoxelIndexC(None, 0x1000, 3)) == B.ERR_INVALID
+    assert call(B.VoxelIndexC(0x1000, None, 3)) == B.ERR_INVALID
+    assert call(B.VoxelIndexC(0x1000, 0x1000, 0)) == B.ERR_INVALID
+    assert call(B.VoxelIndexC(0x1000, 0x1000, 11)) == B.ERR_INVALID          # more voxels than primitives
+    assert call(B.VoxelIndexC(0x1008, 0x1000, 3)) == B.ERR_INVALID          # box records not 16-byte aligned
+    skew = _good_camera(); skew.view[0] *= 1.1
+    assert call(idx, skew) == B.ERR_UNSUPPORTED
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "absent.so"))
