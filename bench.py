@@ -3,9 +3,10 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 2] [--no-cpu-baseline]
 
-A step is one frame: lmk_gs_preprocess + lmk_gs_bin_sort + lmk_gs_render for one
-viewpoint, all enqueued on one stream with no host synchronisation; steps cycle
-through the configuration's seeded viewpoints.  Inputs are resident in HBM
+A step is one frame: lmk_gs_preprocess_culled (or lmk_gs_preprocess with --voxel 0) +
+lmk_gs_bin_sort + lmk_gs_render for one viewpoint, all enqueued on one stream with no
+host synchronisation; steps cycle through the configuration's seeded viewpoints.  The
+scene is reordered into voxels once, before anything is timed.  Inputs are resident in HBM
 before the timed region.  Prints ONE JSON line (metric = frames/s) that also
 carries Gaussian-pixel blends/s, per-stage times, the roofline of the dominant
 kernel and of the HBM-bound stages, and the CPU oracle timed on the same
@@ -23,17 +24,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# voxel edge per configuration for the offline reordering (a few hundred primitives per voxel);
+# 0 = off where every viewpoint sees the whole scene and the filter can only cost
+VOXEL_SIZE = {0: 0.0, 1: 0.0, 2: 2.0, 3: 40.0, 4: 0.0}
+
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP32_PEAK_TFLOPS = 157.3     # 256 CU x 128 lanes x 2 flop x 2.4 GHz (vector FP32, packed-FMA rate)
 
 
-def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0):
+def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=None, voxels=0):
     """HBM bytes the method itself must move in preprocess + bin_sort (per frame), for the
     scheme this library runs.
 
-    preprocess: mean 12 B + tiles_touched 4 B for every primitive; scale, rotation,
-    opacity 32 B for those past the near plane; SH 192 B + outputs 64 B (depth 4,
-    rect 8, feature record 48, reread count 4) for binned ones.
+    preprocess: tiles_touched 4 B for every primitive; mean 12 B for every primitive of a
+    group the voxel filter lets through (all of them without the filter; n_near and n_bin count
+    only those); scale, rotation, opacity 32 B for those past the near plane; SH 192 B +
+    outputs 64 B (depth 4, rect 8, feature record 48, reread count 4) for binned ones; the
+    voxel table, 32 B per voxel + 8 B per group.
     scan: block sums only (negligible).  emit: 16 B per binned primitive (+ 32 B of its
     feature record under binning rule 1) + 12 B per pair.
     partition by tile: one up-front histogram read of 8 B per pair, then per pass over the
@@ -45,7 +52,8 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0):
     """
     tile_bits = max(1, (tiles - 1).bit_length())
     passes = (tile_bits + 7) // 8
-    b_pre = 16 * n + 32 * n_near + 256 * n_bin
+    n_proc = n if n_proc is None else n_proc
+    b_pre = 4 * n + 12 * n_proc + 32 * n_near + 256 * n_bin + 32 * voxels + (8 * ((n + 255) // 256) if voxels else 0)
     b_emit = 4 * n + (48 if binning else 16) * n_bin + 12 * D
     b_part = D * (8 + 32 * passes)
     b_ranges = 8 * D + 8 * (tiles + 1) + 12 * tiles
@@ -88,9 +96,14 @@ def main():
     ap.add_argument("--binning", type=int, default=1, choices=(0, 1),
                     help="0: a pair for every tile of a support rectangle; 1 (default): only for tiles the "
                          "splat can reach (same image, fewer pairs)")
-    ap.add_argument("--voxel", type=float, default=0.0,
+    ap.add_argument("--voxel", type=float, default=None,
                     help="edge of the voxels for the offline spatial reordering + per-frame view-frustum filtering "
-                         "of voxels (0 = primitives in the order drawn, no filtering)")
+                         "of voxels (default: a size per configuration; 0 = primitives in the order drawn, "
+                         "no filtering)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="frames in flight: with S > 1, frame i runs on stream i mod S with its own buffers, so the "
+                         "latency-bound kernels of one frame overlap the bandwidth- and ALU-bound ones of another "
+                         "(throughput mode; per-stage times then include the overlap)")
     ap.add_argument("--views", type=int, default=None, help="use only the first K viewpoints of the configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (no blends/s either)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -118,6 +131,8 @@ def main():
         cams = cams[:max(1, args.views)]
     cams = [dict(c, binning=args.binning) for c in cams]
     ccams = [B.make_camera(c) for c in cams]
+    if args.voxel is None:
+        args.voxel = VOXEL_SIZE[args.cfg]
     index = None
     if args.voxel > 0.0:
         # offline step, not timed: from here on "the scene" is the reordered scene, for the oracle too
@@ -131,8 +146,10 @@ def main():
     probe_cap = 64_000_000 if args.cfg != 4 else 7_000_000_000
     fr = B.Frame(n, W, H, probe_cap)
     Ds, stats = [], []
+    nb = (n + B.PRE_BLOCK - 1) // B.PRE_BLOCK
+    flags = torch.ones(max(nb, 1), dtype=torch.uint8, device="cuda")
     for cc in ccams:
-        B.preprocess(dev, cc, fr, index=index)
+        B.preprocess(dev, cc, fr, index=index, block_visible=flags if index is not None else None)
         B.bin_sort(cc, fr)
         D, status = B.read_status(fr)
         assert status == B.OK, f"status {status} in the sizing run"
@@ -140,11 +157,15 @@ def main():
         n_bin = int((tt > 0).sum().item())
         lens = (fr.tile_offsets[1:] - fr.tile_offsets[:-1])
         Ds.append(D)
-        stats.append(dict(D=D, n_bin=n_bin, long_lists=[int(x) for x in lens[lens > 16384].tolist()]))
+        stats.append(dict(D=D, n_bin=n_bin, long_lists=[int(x) for x in lens[lens > 16384].tolist()],
+                          processed=flags[:nb].bool().cpu().numpy().copy()))
     del fr
     torch.cuda.empty_cache()
     capacity = int(max(Ds) * 1.25) + 4096
-    fr = B.Frame(n, W, H, capacity)
+    S = max(1, args.streams)
+    frames = [B.Frame(n, W, H, capacity) for _ in range(S)]
+    streams = [None] if S == 1 else [torch.cuda.Stream() for _ in range(S)]
+    fr = frames[0]
 
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
@@ -158,10 +179,11 @@ def main():
     nviews = len(ccams)
     ev = lambda: torch.cuda.Event(enable_timing=True)
     for i in range(args.warmup):
-        B.render_frame(dev, ccams[i % nviews], fr, index=index)
+        B.render_frame(dev, ccams[i % nviews], frames[i % S], stream=streams[i % S], index=index)
     torch.cuda.synchronize()
-    D_chk, status = B.read_status(fr)
-    assert status == B.OK, f"status {status}"
+    for f in frames[:min(S, max(args.warmup, 1))]:
+        _, status = B.read_status(f)
+        assert status == B.OK, f"status {status}"
 
     marks = [[ev(), ev(), ev(), ev()] for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -169,20 +191,22 @@ def main():
     for i in range(args.steps):
         cc = ccams[i % nviews]
         m = marks[i]
-        m[0].record()
-        B.preprocess(dev, cc, fr, index=index)
-        m[1].record()
-        B.bin_sort(cc, fr)
-        m[2].record()
-        B.render(cc, fr)
-        m[3].record()
+        f, st = frames[i % S], streams[i % S]
+        m[0].record(st)
+        B.preprocess(dev, cc, f, stream=st, index=index)
+        m[1].record(st)
+        B.bin_sort(cc, f, stream=st)
+        m[2].record(st)
+        B.render(cc, f, stream=st)
+        m[3].record(st)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     total_s = t1 - t0
     ms_per_step = 1e3 * total_s / args.steps
     fps = args.steps / total_s
-    _, status = B.read_status(fr)
-    assert status == B.OK, f"status {status}"
+    for f in frames:
+        _, status = B.read_status(f)
+        assert status == B.OK, f"status {status}"
 
     t_pre = np.array([m[0].elapsed_time(m[1]) for m in marks])
     t_sort = np.array([m[1].elapsed_time(m[2]) for m in marks])
@@ -205,7 +229,9 @@ def main():
             ofr = ref.render_frame(scene, dict(cams[v], binning=0))
             cpu_t.append(time.perf_counter() - c0)
             E.append(int(ofr.img.E.sum())); C.append(int(ofr.img.C.sum()))
-            n_near.append(int((ofr.pre.stage != ref.CULL_NEAR).sum()))
+            proc = np.repeat(stats[v]["processed"], B.PRE_BLOCK)[:n]
+            stats[v]["n_proc"] = int(proc.sum())
+            n_near.append(int(((ofr.pre.stage != ref.CULL_NEAR) & proc).sum()))
             D_ref = ofr.binned.D if args.binning == 0 else \
                 int(ref.preprocess(scene, cams[v]).tiles_touched.astype(np.uint64).sum())
             assert D_ref == stats[v]["D"], "GPU and oracle disagree on the pair count"
@@ -227,6 +253,7 @@ def main():
         "config": {"workload": f"cfg{args.cfg}: {n} Gaussians, {W}x{H}, 16x16 tiles, SH degree 3, "
                                f"{nviews} seeded viewpoints rendered back-to-back",
                    "binning": args.binning, "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity,
+                   "frames_in_flight": S,
                    "voxel_filter": None if index is None else
                    {"voxel_size": args.voxel, "voxels": index.num_voxels,
                     "note": "primitives reordered offline into voxels; voxels filtered against the frustum per frame"}},
@@ -246,8 +273,9 @@ def main():
         flops = (14.0 * Ev + 10.0 * Cv)[view_of].sum()
         tf = flops / (t_blend.sum() * 1e-3) / 1e12
         out["blends_per_s"] = blends
+        # the committed measurement is of the default command of each configuration
         traffic = committed_traffic(args.cfg, args.binning) \
-            if args.n is None and args.views is None and index is None else {}
+            if args.n is None and args.views is None and args.voxel == VOXEL_SIZE[args.cfg] else {}
         out["roofline"] = {"kernel": "blend_kernel", "bound": "alu", "achieved": tf, "peak": FP32_PEAK_TFLOPS,
                            "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": traffic.get("blend_kernel"),
                            "avg_launch_ms": float(t_blend.mean()),
@@ -255,7 +283,8 @@ def main():
         byts, byts_pre = [], []
         for v in range(nviews):
             ab = algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles,
-                                   stats[v]["long_lists"], args.binning)
+                                   stats[v]["long_lists"], args.binning, stats[v]["n_proc"],
+                                   0 if index is None else index.num_voxels)
             byts.append(ab["total"]); byts_pre.append(ab["preprocess"])
         byts = np.array(byts, dtype=np.float64); byts_pre = np.array(byts_pre, dtype=np.float64)
         gbs = byts[view_of].sum() / ((t_pre.sum() + t_sort.sum()) * 1e-3) / 1e9

@@ -267,6 +267,31 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
         }
     }
 
+    // SH records (see below): a wavefront most of whose primitives are still alive requests its
+    // whole block of records now, so that the loads are in flight during the tile counting
+    constexpr u32 kVec = LMK_GS_SH_STRIDE(DEG) / 4;         // 16-byte vectors per record
+    constexpr u32 kCoef = (DEG + 1) * (DEG + 1);
+    constexpr u32 kPart = kVec > 7 ? kVec / 2 : kVec;       // vectors of a record staged at a time
+    constexpr u32 kParts = kVec / kPart;
+    constexpr u32 kSlot = kPart + 1;                        // padded record stride in LDS (bank spread)
+    constexpr u32 kDirectMax = 40;                          // survivors per wavefront served by direct loads
+    static_assert(kPart * kParts == kVec, "records are staged in equal parts");
+    __shared__ f32x4 s_sh[kPreBlock / kWave][kWave * kSlot];
+    const u32 sh_lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const bool staged = (u32)__builtin_popcountll(__builtin_amdgcn_ballot_w64(cnt > 0)) > kDirectMax;   // wave-uniform
+    const u32 first = blockIdx.x * kPreBlock + wv * kWave;  // first primitive of this wavefront
+    const u32 recs = first < n ? (n - first < kWave ? n - first : kWave) : 0u;
+    f32x4 buf[kVec];
+    if (staged) {
+        // every load instruction covers 1 KiB of consecutive addresses, all of them in flight together
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(sh) + (size_t)first * kVec;
+#pragma unroll
+        for (u32 j = 0; j < kVec; ++j) {
+            const u32 idx = j * kWave + sh_lane;
+            buf[j] = idx < recs * kVec ? src[idx] : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
     // binning rule 1: count only the tiles of the rectangle that the splat can reach.
     // Small rectangles are walked by their own lane; large ones one at a time by the whole
     // wavefront (64 tiles per step), so that one huge splat does not stall 63 idle lanes.
@@ -309,22 +334,8 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     // lines per load instruction); where few are (close-up views cull most primitives), each survivor
     // fetches only its own record and the rest of the block is never read.
     {
-        constexpr u32 kVec = LMK_GS_SH_STRIDE(DEG) / 4;         // 16-byte vectors per record
-        constexpr u32 kCoef = (DEG + 1) * (DEG + 1);
-        constexpr u32 kPart = kVec > 7 ? kVec / 2 : kVec;       // vectors of a record staged at a time
-        constexpr u32 kParts = kVec / kPart;
-        constexpr u32 kSlot = kPart + 1;                        // padded record stride in LDS (bank spread)
-        constexpr u32 kDirectMax = 40;                          // survivors per wavefront served by direct loads
-        static_assert(kPart * kParts == kVec, "records are staged in equal parts");
-        __shared__ f32x4 s_sh[kPreBlock / kWave][kWave * kSlot];
-        const u32 lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-        const u32 survivors = (u32)__builtin_popcountll(__builtin_amdgcn_ballot_w64(cnt > 0));
-        const bool staged = survivors > kDirectMax;             // wave-uniform
-        const u32 first = blockIdx.x * kPreBlock + wv * kWave;  // first primitive of this wavefront
-        const u32 recs = first < n ? (n - first < kWave ? n - first : kWave) : 0u;
-        const f32x4 *src = reinterpret_cast<const f32x4 *>(sh) + (size_t)first * kVec;
         const f32x4 *rec = reinterpret_cast<const f32x4 *>(sh) + (size_t)i * kVec;   // this primitive's record
-        const f32x4 *lrec = &s_sh[wv][lane * kSlot];
+        const f32x4 *lrec = &s_sh[wv][sh_lane * kSlot];
 
         float Y[16];
         if (cnt) {
@@ -351,16 +362,6 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
         }
         // coefficient k of channel ch sits at float [3k + ch] of the record
         float acc[3] = { 0.5f, 0.5f, 0.5f };
-        f32x4 buf[kVec];
-        if (staged) {
-            // the wavefront's block of records, whole: every load instruction covers 1 KiB of
-            // consecutive addresses, all of them in flight together
-#pragma unroll
-            for (u32 j = 0; j < kVec; ++j) {
-                const u32 idx = j * kWave + lane;
-                buf[j] = idx < recs * kVec ? src[idx] : f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-        }
 #pragma unroll
         for (u32 part = 0; part < kParts; ++part) {
             if (staged) {
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
                 // is vector idx % kVec of record idx / kVec
 #pragma unroll
                 for (u32 j = 0; j < kVec; ++j) {
-                    const u32 idx = j * kWave + lane;
+                    const u32 idx = j * kWave + sh_lane;
                     const u32 r = idx / kVec, v = idx % kVec;
                     if (r < recs && v / kPart == part) s_sh[wv][r * kSlot + (v - part * kPart)] = buf[j];
                 }
