@@ -1,34 +1,36 @@
-// Stage 2: duplication of primitives into (tile | depth) keys, stable LSD radix
-// sort of the pairs, per-tile range extraction (the "depth sorting ... at the
-// granularity of tiles" of Sec. 2.2; duplication with keys is the second
-// kernel named in Sec. 4.2.1).
+// Stage 2: duplication of primitives into (tile | depth) keys, sort of the pairs into
+// (tile, depth bits, index) order, per-tile range extraction (the "depth sorting ... at the
+// granularity of tiles" of Sec. 2.2; duplication with keys is the second kernel named in
+// Sec. 4.2.1).
 //
-// All of it is integer work bound by HBM traffic.  The kernels read the pair
-// count D from device memory, so the host never waits for it: grids are sized
+// Integer work bound by HBM traffic and, in the per-tile sorts, by LDS bandwidth.  The kernels
+// read the pair count D from device memory, so the host never waits for it: grids are sized
 // from the caller's capacity and surplus workgroups leave at once.
 //
-//   emit     one workgroup per 256 primitives; a load-balanced expansion: the
-//            workgroup's output slots are dealt round-robin to its threads and
-//            each slot finds its primitive by binary search in an LDS prefix
-//            array, so stores are contiguous whatever the rectangle sizes are.
-//   partition  stable LSD radix sort over the TILE bits of the keys only (two passes
-//            of 7 + 6 bits at 1080p).  One up-front kernel builds the global digit
-//            histogram of both passes; per pass: (1) digit counts of every 4096-pair
-//            sort tile, (2) one workgroup per digit turns its row of counts into
-//            output offsets, (3) scatter: wavefront match-any ranking (ballots over
-//            the digit bits) keeps equal digits in order, the tile is sorted by
-//            digit in LDS and written out in contiguous runs (128 or fewer bins, so
-//            runs are long and writes fill whole cache lines).
+//   emit     one workgroup per 256 primitives; a load-balanced expansion: the workgroup's
+//            output slots are dealt round-robin to its threads and each slot finds its
+//            primitive by binary search in an LDS prefix array, so stores are contiguous
+//            whatever the rectangle sizes are.  Under binning rule 1 every slot is first put
+//            through the splat/tile intersection test and the kept ones are compacted.
+//            Rectangles of more than 128 tiles are deferred to a list and expanded by
+//            emit_deferred_kernel, one wavefront (or, beyond 2048 tiles, one workgroup) each.
+//   partition  stable LSD radix sort over the TILE bits of the keys only (two passes of
+//            7 + 6 bits at 1080p).  Per pass: (1) digit counts of every 4096-pair sort tile
+//            (the first pass also accumulates the global digit totals of all passes),
+//            (2) one workgroup per digit turns its row of counts into output offsets,
+//            (3) scatter: wavefront match-any ranking (ballots over the digit bits) keeps
+//            equal digits in order, the tile is sorted by digit in LDS and written out in
+//            contiguous runs (128 or fewer bins, so runs are long and fill cache lines).
 //   ranges   tile_offsets[t] = first position whose tile id is >= t.
-//   order    tile ids by descending list length; chunk table (4096-pair chunks).
-//   tile sort  every chunk of every tile's list is sorted by (depth bits, index)
-//            in LDS by one workgroup (bitonic network on 64-bit composites; the
-//            order is total, so no stability is needed).  Lists of up to 4096
-//            pairs -- all but a few hundred tiles at 1080p -- are finished here.
-//   merge    a tile whose list is longer merges its sorted chunks pairwise,
-//            ping-ponging between the two pair buffers, one workgroup per tile.
-//            Sorting 32 depth bits this way costs one read and one write of the
-//            pairs instead of four radix passes over all of them.
+//   order    tile ids by descending list length, bucketed by the bit length of the length,
+//            which also gives the size classes of the per-tile sort.
+//   tile sort  every tile's list is sorted by (depth bits, index) as 64-bit composites with a
+//            merge sort in LDS (the order is total, so no stability is needed): one wavefront
+//            for lists of up to 512 pairs, 256 threads up to 2048, 512 threads up to 4096,
+//            1024 threads and most of a compute unit's LDS up to 16384; longer lists are
+//            sorted in 16384-pair chunks and merged pairwise between the two pair buffers
+//            through LDS-staged windows.  Sorting the 32 depth bits this way costs one read
+//            and one write of the pairs instead of four radix passes over all of them.
 #include "lmk_gs_internal.h"
 
 namespace lmk {
@@ -79,7 +81,8 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
     const float *__restrict__ depth, const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
-    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off)
+    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
+    u64 *__restrict__ digit_totals)
 {
     __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of the (small) rectangles expanded here
     __shared__ u32 s_off[kPreBlock];      // exclusive prefix of tiles_touched: where a primitive's pairs start
@@ -121,6 +124,8 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
         if (i == n - 1) offsets[n] = base + total2;
     }
     if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
+    if (blockIdx.x == 0)      // the partition's digit totals are accumulated with atomics: start from zero
+        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kPreBlock) digit_totals[k] = 0;
     append_big(cnt, i, base + off, header, big_idx, big_off, lane, n);
     __syncthreads();
 
@@ -173,7 +178,8 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     const float *__restrict__ depth, const float4 *__restrict__ feat, ProjParams pp,
     const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
-    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off)
+    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
+    u64 *__restrict__ digit_totals)
 {
     __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of (small) rectangle areas inside the workgroup
     __shared__ u32 s_bigpre[kPreBlock];   // pairs of deferred (big) primitives that precede each primitive
@@ -232,6 +238,8 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
         if (i == n - 1) offsets[n] = base + total2;
     }
     if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
+    if (blockIdx.x == 0)      // the partition's digit totals are accumulated with atomics: start from zero
+        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kPreBlock) digit_totals[k] = 0;
     append_big(full_area, i, base + kept_excl, header, big_idx, big_off, lane, n);
     __syncthreads();
 
@@ -443,72 +451,41 @@ __global__ __launch_bounds__(kPreBlock) void emit_deferred_kernel(
 }
 
 // ---------------------------------------------------------------- radix sort
-// (0a) one read of the keys: digit histograms of every pass, one partial per workgroup
-constexpr u32 kPrehistUnroll = 8;
-
-__global__ __launch_bounds__(kSortThreads) void sort_prehist_kernel(
-    const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
-    SortPlan plan, u32 *__restrict__ partials, u64 *__restrict__ digit_totals)
-{
-    __shared__ u32 s_hist[kMaxPasses][kMaxRadix];
-    const u64 D = load_D(header, capacity);
-    const u32 tid = threadIdx.x;
-    for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kSortThreads) (&s_hist[0][0])[k] = 0;
-    if (blockIdx.x == 0)
-        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kSortThreads) digit_totals[k] = 0;
-    __syncthreads();
-    const u64 chunk = (u64)kSortThreads * kPrehistUnroll;
-    for (u64 base = (u64)blockIdx.x * chunk; base < D; base += (u64)gridDim.x * chunk) {
-        u64 k[kPrehistUnroll];
-#pragma unroll
-        for (u32 j = 0; j < kPrehistUnroll; ++j) {
-            const u64 i = base + (u64)j * kSortThreads + tid;
-            k[j] = i < D ? keys[i] : 0ull;
-        }
-#pragma unroll
-        for (u32 j = 0; j < kPrehistUnroll; ++j) {
-            const u64 i = base + (u64)j * kSortThreads + tid;
-            if (i < D) {
-#pragma unroll
-                for (u32 p = 0; p < kMaxPasses; ++p)
-                    if (p < plan.passes)
-                        atomicAdd(&s_hist[p][(u32)(k[j] >> plan.shift[p]) & ((1u << plan.bits[p]) - 1u)], 1u);
-            }
-        }
-    }
-    __syncthreads();
-    u32 *out = partials + (size_t)blockIdx.x * kMaxPasses * kMaxRadix;
-    for (u32 k = tid; k < plan.passes * kMaxRadix; k += kSortThreads) out[k] = (&s_hist[0][0])[k];
-}
-
-// (0b) sums the partial histograms: workgroup (pass, slice) adds its slice of partials and
-// contributes one atomic per digit.
-constexpr u32 kReduceSlices = 32;
-
-__global__ __launch_bounds__(kMaxRadix) void sort_reduce_kernel(
-    const u32 *__restrict__ partials, u32 nblocks, u64 *__restrict__ digit_totals)
-{
-    const u32 d = threadIdx.x, pass = blockIdx.x / kReduceSlices, slice = blockIdx.x % kReduceSlices;
-    const u32 per = (nblocks + kReduceSlices - 1) / kReduceSlices;
-    const u32 b0 = slice * per, b1 = (b0 + per) < nblocks ? (b0 + per) : nblocks;
-    u64 total = 0;
-#pragma unroll 16
-    for (u32 b = b0; b < b1; ++b)
-        total += partials[((size_t)b * kMaxPasses + pass) * kMaxRadix + d];
-    if (total) atomicAdd(reinterpret_cast<unsigned long long *>(&digit_totals[(size_t)pass * kMaxRadix + d]),
-                         (unsigned long long)total);
-}
-
 // (1) digit counts of every sort tile of this pass -> table[digit][tile]
+// Pairs of a spatially ordered scene arrive in runs of one tile: a wavefront whose 64 keys share a
+// digit adds once instead of queueing 64 atomics on one LDS word.  Called by whole wavefronts.
+__device__ __forceinline__ void wave_hist_add(u32 *hist, u32 d, bool valid, u32 tid)
+{
+    const u64 live = __builtin_amdgcn_ballot_w64(valid);
+    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
+    const u64 same = __builtin_amdgcn_ballot_w64(valid && d == d0);
+    if (live != 0ull && same == live && (live & 1ull)) {
+        if ((tid & (kWave - 1)) == 0) atomicAdd(&hist[d0], (u32)__builtin_popcountll(live));
+    } else if (valid) {
+        atomicAdd(&hist[d], 1u);
+    }
+}
+
+// The first pass also builds the global digit totals of the later passes (they do not depend on
+// the order of the pairs): one more LDS histogram per later pass, flushed with one global atomic
+// per non-empty digit when the workgroup is done.  Its own totals are the row sums of `table`
+// and come out of the same flush.
+template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
-    u32 shift, u32 bits, u32 *__restrict__ table, u64 table_stride)
+    u32 shift, u32 bits, u32 *__restrict__ table, u64 table_stride, SortPlan plan,
+    u64 *__restrict__ digit_totals)
 {
     __shared__ u32 s_hist[kMaxRadix];
+    __shared__ u32 s_tot[FIRST ? kMaxPasses : 1][kMaxRadix];
     const u64 D = load_D(header, capacity);
     const u64 ntiles = (D + kSortTile - 1) / kSortTile;
     const u32 tid = threadIdx.x;
     const u32 dmask = (1u << bits) - 1u;
+    if (FIRST) {
+        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kSortThreads) (&s_tot[0][0])[k] = 0;
+        __syncthreads();
+    }
     for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_hist[d] = 0;
         __syncthreads();
@@ -524,20 +501,27 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
             const u64 idx = t0 + (u64)j * kSortThreads + tid;
             const bool valid = idx < D;
             const u32 d = (u32)(k[j] >> shift) & dmask;
-            // pairs of a spatially ordered scene arrive in runs of one tile: a wavefront whose 64
-            // keys share a digit adds once instead of queueing 64 atomics on one LDS word
-            const u64 live = __builtin_amdgcn_ballot_w64(valid);
-            const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
-            const u64 same = __builtin_amdgcn_ballot_w64(valid && d == d0);
-            if (live != 0ull && same == live && (live & 1ull)) {
-                if ((tid & (kWave - 1)) == 0) atomicAdd(&s_hist[d0], (u32)__builtin_popcountll(live));
-            } else if (valid) {
-                atomicAdd(&s_hist[d], 1u);
+            wave_hist_add(s_hist, d, valid, tid);
+            if (FIRST) {
+#pragma unroll
+                for (u32 p = 1; p < kMaxPasses; ++p)
+                    if (p < plan.passes && valid)
+                        atomicAdd(&s_tot[p][(u32)(k[j] >> plan.shift[p]) & ((1u << plan.bits[p]) - 1u)], 1u);
             }
         }
         __syncthreads();
-        for (u32 d = tid; d < kMaxRadix; d += kSortThreads) table[(u64)d * table_stride + tile] = s_hist[d];
+        for (u32 d = tid; d < kMaxRadix; d += kSortThreads) {
+            const u32 c = s_hist[d];
+            table[(u64)d * table_stride + tile] = c;
+            if (FIRST) s_tot[0][d] += c;                  // thread d owns s_tot[0][d] here
+        }
         __syncthreads();
+    }
+    if (FIRST) {
+        for (u32 k = tid; k < plan.passes * kMaxRadix; k += kSortThreads) {
+            const u32 c = (&s_tot[0][0])[k];
+            if (c) atomicAdd(reinterpret_cast<unsigned long long *>(&digit_totals[k]), (unsigned long long)c);
+        }
     }
 }
 
@@ -1107,7 +1091,6 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
     u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
     u64 *digit_totals = reinterpret_cast<u64 *>(scratch + L.digit_totals);
-    u32 *partials = reinterpret_cast<u32 *>(scratch + L.partials);
     u32 *table = reinterpret_cast<u32 *>(scratch + L.table);
     u64 *offsets = reinterpret_cast<u64 *>(scratch + L.offsets);
     u32 *order = reinterpret_cast<u32 *>(scratch + L.order);
@@ -1131,7 +1114,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                reinterpret_cast<const float4 *>(proj.feat), pp,
                                block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
-                               big_idx, big_off);
+                               big_idx, big_off, digit_totals);
             hipLaunchKernelGGL(emit_deferred_kernel<true>, dim3(big_grid), dim3(kPreBlock), 0, stream,
                                reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                reinterpret_cast<const float4 *>(proj.feat), pp, pp.tiles_x, out.capacity,
@@ -1140,7 +1123,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
             hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
-                               big_idx, big_off);
+                               big_idx, big_off, digit_totals);
             hipLaunchKernelGGL(emit_deferred_kernel<false>, dim3(big_grid), dim3(kPreBlock), 0, stream,
                                reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                reinterpret_cast<const float4 *>(proj.feat), pp, pp.tiles_x, out.capacity,
@@ -1150,21 +1133,20 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
         if (e != hipSuccess) return e;
     }
 
-    const u32 hist_blocks = (u32)(L.sort_tiles < kHistBlocks ? L.sort_tiles : kHistBlocks);
-    if (plan.passes > 0) {
-        hipLaunchKernelGGL(sort_prehist_kernel, dim3(hist_blocks), dim3(kSortThreads), 0, stream,
-                           kin, header, out.capacity, plan, partials, digit_totals);
-        hipLaunchKernelGGL(sort_reduce_kernel, dim3(plan.passes * kReduceSlices), dim3(kMaxRadix), 0, stream,
-                           partials, hist_blocks, digit_totals);
-    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // enough resident workgroups to fill 256 CUs several times over; each loops over sort tiles
     const u32 grid = grid_for(L.sort_tiles, 256u * 16u);
     for (u32 p = 0; p < plan.passes; ++p) {
         const u64 *totals = digit_totals + (size_t)p * kMaxRadix;
-        hipLaunchKernelGGL(radix_hist_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
-                           kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles);
+        if (p == 0)
+            hipLaunchKernelGGL(radix_hist_kernel<true>, dim3(grid), dim3(kSortThreads), 0, stream,
+                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles,
+                               plan, digit_totals);
+        else
+            hipLaunchKernelGGL(radix_hist_kernel<false>, dim3(grid), dim3(kSortThreads), 0, stream,
+                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles,
+                               plan, digit_totals);
         hipLaunchKernelGGL(radix_scan_kernel, dim3(1u << plan.bits[p]), dim3(kSortThreads), 0, stream,
                            header, out.capacity, table, offsets, L.sort_tiles, totals);
         hipLaunchKernelGGL(radix_scatter_kernel, dim3(grid), dim3(kSortThreads), 0, stream,

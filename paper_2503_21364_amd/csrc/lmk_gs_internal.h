@@ -20,7 +20,6 @@ constexpr u32 kSortTile = kSortThreads * kSortItems;   // 4096 pairs per workgro
 constexpr u32 kMaxRadixBits = 8;         // digits are at most 8 bits wide, chosen per frame
 constexpr u32 kMaxRadix = 1u << kMaxRadixBits;
 constexpr u32 kMaxPasses = 8;
-constexpr u32 kHistBlocks = 512;         // workgroups of the up-front digit histogram
 
 // Header at the start of the scratch buffer.
 struct ScratchHeader {
@@ -38,7 +37,6 @@ struct ScratchLayout {
     size_t block_offsets; // u64 [pre_blocks + 1]  their exclusive prefix sum
     size_t voxel_flags;   // u8  [n]               voxel filter: 1 = the voxel may reach the image (at most n voxels)
     size_t digit_totals;  // u64 [kMaxPasses][512] global digit histogram of each pass
-    size_t partials;      // u32 [kHistBlocks][kMaxPasses][512] per-workgroup digit counts
     size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
     size_t offsets;       // u64 [512][sort_tiles] their output offsets
     size_t order;         // u32 [tiles]     tile ids by descending list length
@@ -64,7 +62,6 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
     L.block_offsets = o; o += align256(sizeof(u64) * ((size_t)L.pre_blocks + 1));
     L.voxel_flags = o;   o += align256((size_t)n + 1);
     L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kMaxRadix);
-    L.partials = o;      o += align256(sizeof(u32) * (size_t)kHistBlocks * kMaxPasses * kMaxRadix);
     L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
     L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
     L.order = o;         o += align256(sizeof(u32) * (size_t)(tiles + 1));
