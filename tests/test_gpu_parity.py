@@ -184,10 +184,19 @@ def test_equal_depths_are_ordered_by_index():
     assert (keys[1:] == keys[:-1]).sum() > 1000
 
 
-def test_capacity_overflow_sets_status_and_stays_in_bounds():
-    sc = scenes.make_scene(0, n=5000, seed=17)
-    cam = scenes.make_cameras(0, 128, 128)[0]
+@pytest.mark.parametrize("n,scale_mul,wh,binning", [
+    (5000, 1.0, (128, 128), 0),
+    (3000, 6.0, (1920, 1080), 0),   # rectangles of hundreds and thousands of tiles: the deferred expansion paths
+    (3000, 6.0, (1920, 1080), 1),
+])
+def test_capacity_overflow_sets_status_and_stays_in_bounds(n, scale_mul, wh, binning):
+    sc = scenes.make_scene(0, n=n, seed=17)
+    sc["scale"] = sc["scale"] * np.float32(scale_mul)
+    cam = dict(scenes.make_cameras(0, *wh)[0], binning=binning)
     ofr = ref.render_frame(sc, cam)
+    if scale_mul > 1.0:
+        area = (ofr.pre.rect[:, 2].astype(int) - ofr.pre.rect[:, 0]) * (ofr.pre.rect[:, 3].astype(int) - ofr.pre.rect[:, 1])
+        assert (area > 2048).sum() > 10 and ((area > 128) & (area <= 2048)).sum() > 100 and (area <= 128).sum() > 10
     cap = ofr.binned.D // 2
     fr = P.gpu_frame(B.Scene(sc), cam, cap)
     D, status = B.read_status(fr)
