@@ -32,13 +32,14 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP32_PEAK_TFLOPS = 157.3     # 256 CU x 128 lanes x 2 flop x 2.4 GHz (vector FP32, packed-FMA rate)
 
 
-def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=None, voxels=0):
+def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=None, voxels=0, cov_cache=False):
     """HBM bytes the method itself must move in preprocess + bin_sort (per frame), for the
     scheme this library runs.
 
     preprocess: tiles_touched 4 B for every primitive; mean 12 B for every primitive of a
     group the voxel filter lets through (all of them without the filter; n_near and n_bin count
-    only those); scale, rotation, opacity 32 B for those past the near plane; SH 192 B +
+    only those); scale, rotation, opacity 32 B for those past the near plane (28 B with the
+    parameter cache: six covariance entries instead of seven rotation and scale values); SH 192 B +
     outputs 64 B (depth 4, rect 8, feature record 48, reread count 4) for binned ones; the
     voxel table, 32 B per voxel + 8 B per group.
     scan: block sums only (negligible).  emit: 16 B per binned primitive (+ 32 B of its
@@ -53,7 +54,7 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
     tile_bits = max(1, (tiles - 1).bit_length())
     passes = (tile_bits + 7) // 8
     n_proc = n if n_proc is None else n_proc
-    b_pre = 4 * n + 12 * n_proc + 32 * n_near + 256 * n_bin + 32 * voxels + (8 * ((n + 255) // 256) if voxels else 0)
+    b_pre = 4 * n + 12 * n_proc + (28 if cov_cache else 32) * n_near + 256 * n_bin + 32 * voxels + (8 * ((n + 255) // 256) if voxels else 0)
     b_emit = 4 * n + (48 if binning else 16) * n_bin + 12 * D
     b_part = D * (8 + 32 * passes)
     b_ranges = 8 * D + 8 * (tiles + 1) + 12 * tiles
@@ -100,6 +101,9 @@ def main():
                     help="edge of the voxels for the offline spatial reordering + per-frame view-frustum filtering "
                          "of voxels (default: a size per configuration; 0 = primitives in the order drawn, "
                          "no filtering)")
+    ap.add_argument("--no-cov-cache", action="store_true",
+                    help="compute every primitive's 3D covariance from rotation and scale in every frame instead "
+                         "of reading the parameter cache built once per scene")
     ap.add_argument("--streams", type=int, default=1,
                     help="frames in flight: with S > 1, frame i runs on stream i mod S with its own buffers, so the "
                          "latency-bound kernels of one frame overlap the bandwidth- and ALU-bound ones of another "
@@ -140,6 +144,8 @@ def main():
         scene = index.reorder(scene)
         index.upload()
     dev = B.Scene(scene)
+    if not args.no_cov_cache:
+        dev.build_cov3d()          # once per scene, not timed
     tiles = ((W + 15) // 16) * ((H + 15) // 16)
 
     # size the pair buffers from a dry run of every viewpoint (not timed)
@@ -253,7 +259,7 @@ def main():
         "config": {"workload": f"cfg{args.cfg}: {n} Gaussians, {W}x{H}, 16x16 tiles, SH degree 3, "
                                f"{nviews} seeded viewpoints rendered back-to-back",
                    "binning": args.binning, "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity,
-                   "frames_in_flight": S,
+                   "frames_in_flight": S, "parameter_cache": not args.no_cov_cache,
                    "voxel_filter": None if index is None else
                    {"voxel_size": args.voxel, "voxels": index.num_voxels,
                     "note": "primitives reordered offline into voxels; voxels filtered against the frustum per frame"}},
@@ -284,7 +290,7 @@ def main():
         for v in range(nviews):
             ab = algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles,
                                    stats[v]["long_lists"], args.binning, stats[v]["n_proc"],
-                                   0 if index is None else index.num_voxels)
+                                   0 if index is None else index.num_voxels, not args.no_cov_cache)
             byts.append(ab["total"]); byts_pre.append(ab["preprocess"])
         byts = np.array(byts, dtype=np.float64); byts_pre = np.array(byts_pre, dtype=np.float64)
         gbs = byts[view_of].sum() / ((t_pre.sum() + t_sort.sum()) * 1e-3) / 1e9

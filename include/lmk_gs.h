@@ -55,6 +55,11 @@ typedef struct lmk_gs_gaussians {
                               the tail of the record unused                          */
     uint32_t n;            /* number of primitives (0 is allowed)                   */
     uint32_t sh_degree;    /* 0..3                                                  */
+    const float *cov3d;    /* optional [6][n]: Sigma = R S S^T R^T of every primitive (xx, xy, xz,
+                              yy, yz, zz) as written by lmk_gs_build_cov3d -- the view-independent
+                              "inference parameter cache" of Sec. 5.2.2.  When not NULL,
+                              lmk_gs_preprocess reads it instead of rot and scale (which may then
+                              be NULL); the results are the same bit for bit             */
 } lmk_gs_gaussians;
 
 /* Pinhole camera.  Passed by value to the kernels (kernel arguments live in
@@ -138,6 +143,11 @@ int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height,
 int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
                           const lmk_gs_projected *out,
                           void *scratch, size_t scratch_bytes, void *stream);
+
+/* Fills the parameter cache lmk_gs_gaussians.cov3d (device array [6][n]) from g->rot and
+ * g->scale with the arithmetic lmk_gs_preprocess uses (Sec. 2.2 Eq. 8), once per scene.
+ * g->cov3d is ignored.  Asynchronous on `stream`. */
+int32_t lmk_gs_build_cov3d(const lmk_gs_gaussians *g, float *cov3d, void *stream);
 
 /* Offline step of Sec. 4.2.2, on the HOST (all pointers are host pointers, nothing touches the
  * GPU): assigns every primitive to the voxel floor(mean / voxel_size) (per axis, in fp32), orders

@@ -23,12 +23,13 @@ PRE_BLOCK = 256
 
 EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
            "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version",
-           "lmk_gs_index_build", "lmk_gs_preprocess_culled")
+           "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d")
 
 
 class Gaussians(C.Structure):
     _fields_ = [("mean", C.c_void_p), ("scale", C.c_void_p), ("rot", C.c_void_p),
-                ("opacity", C.c_void_p), ("sh", C.c_void_p), ("n", C.c_uint32), ("sh_degree", C.c_uint32)]
+                ("opacity", C.c_void_p), ("sh", C.c_void_p), ("n", C.c_uint32), ("sh_degree", C.c_uint32),
+                ("cov3d", C.c_void_p)]
 
 
 class Camera(C.Structure):
@@ -83,12 +84,13 @@ def lib() -> C.CDLL:
                                          C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32)]
         l.lmk_gs_preprocess_culled.argtypes = [C.POINTER(Gaussians), C.POINTER(VoxelIndexC), C.POINTER(Camera),
                                                C.POINTER(Projected), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.lmk_gs_build_cov3d.argtypes = [C.POINTER(Gaussians), C.c_void_p, C.c_void_p]
         l.lmk_gs_read_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_void_p]
         l.lmk_gs_strerror.argtypes = [C.c_int32]
         l.lmk_gs_strerror.restype = C.c_char_p
         for name in ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
                      "lmk_gs_read_status", "lmk_gs_last_hip_error", "lmk_gs_index_build",
-                     "lmk_gs_preprocess_culled"):
+                     "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d"):
             getattr(l, name).restype = C.c_int32
         l.lmk_gs_version.restype = C.c_uint32
         _lib = l
@@ -152,8 +154,18 @@ class Scene:
         rec = np.zeros((self.n, sh_stride(self.sh_degree)), np.float32)
         rec[:, :3 * ncoef] = np.asarray(scene["sh"][:ncoef], np.float32).reshape(3 * ncoef, self.n).T
         self.sh = f(rec)
+        self.cov3d = None
         self.c = Gaussians(_ptr(self.mean), _ptr(self.scale), _ptr(self.rot), _ptr(self.opacity),
-                           _ptr(self.sh), self.n, self.sh_degree)
+                           _ptr(self.sh), self.n, self.sh_degree, None)
+
+    def build_cov3d(self, stream=None) -> "Scene":
+        """Fills the parameter cache (lmk_gs_build_cov3d); later preprocess calls read it."""
+        self.cov3d = torch.empty((6, max(self.n, 1)), dtype=torch.float32, device=self.mean.device)
+        rc = lib().lmk_gs_build_cov3d(C.byref(self.c), _ptr(self.cov3d), _stream_handle(stream))
+        if rc != OK:
+            raise LmkGsError(rc, "lmk_gs_build_cov3d")
+        self.c.cov3d = _ptr(self.cov3d)
+        return self
 
 
 class VoxelIndex:

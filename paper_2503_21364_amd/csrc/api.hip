@@ -82,7 +82,8 @@ static int32_t preprocess_common(const lmk_gs_gaussians *g, const lmk_gs_voxel_i
     if (!g || !out || !scratch) return LMK_GS_ERR_INVALID;
     if (g->sh_degree > 3) return LMK_GS_ERR_INVALID;
     if (g->n > 0) {
-        if (!g->mean || !g->scale || !g->rot || !g->opacity || !g->sh) return LMK_GS_ERR_INVALID;
+        if (!g->mean || !g->opacity || !g->sh) return LMK_GS_ERR_INVALID;
+        if (!g->cov3d && (!g->scale || !g->rot)) return LMK_GS_ERR_INVALID;
         if (!out->depth || !out->tiles_touched || !out->rect || !out->feat) return LMK_GS_ERR_INVALID;
         if (!aligned(out->feat, 16) || !aligned(out->rect, 8) || !aligned(g->sh, 16)) return LMK_GS_ERR_INVALID;
         if (index) {
@@ -113,6 +114,14 @@ int32_t lmk_gs_preprocess(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
                           void *stream)
 {
     return preprocess_common(g, nullptr, nullptr, cam, out, scratch, scratch_bytes, stream);
+}
+
+int32_t lmk_gs_build_cov3d(const lmk_gs_gaussians *g, float *cov3d, void *stream)
+{
+    if (!g) return LMK_GS_ERR_INVALID;
+    if (g->n > 0 && (!g->scale || !g->rot || !cov3d)) return LMK_GS_ERR_INVALID;
+    const hipError_t e = launch_build_cov3d(*g, cov3d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
 }
 
 int32_t lmk_gs_preprocess_culled(const lmk_gs_gaussians *g, const lmk_gs_voxel_index *index,

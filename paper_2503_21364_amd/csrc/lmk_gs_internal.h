@@ -113,6 +113,7 @@ struct ProjParams {
 hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index *index, uint8_t *block_visible,
                              const ProjParams &pp, const lmk_gs_projected &out,
                              char *scratch, const ScratchLayout &L, hipStream_t stream);
+hipError_t launch_build_cov3d(const lmk_gs_gaussians &g, float *cov3d, hipStream_t stream);
 hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams &pp, const lmk_gs_binned &out,
                            char *scratch, const ScratchLayout &L, hipStream_t stream);
 hipError_t launch_render(const lmk_gs_projected &proj, const lmk_gs_binned &binned, const ProjParams &pp,

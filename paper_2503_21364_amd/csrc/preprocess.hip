@@ -155,10 +155,54 @@ __global__ __launch_bounds__(256) void voxel_flags_kernel(
     voxel_flags[v] = voxel_visible(pp, box[2 * (size_t)v], box[2 * (size_t)v + 1]) ? 1 : 0;
 }
 
+// Sigma = (R S)(R S)^T from an unnormalised quaternion (w, x, y, z) and the scales (Sec. 2.2 Eq. 8)
+__device__ __forceinline__ void covariance3d(float qw0, float qx0, float qy0, float qz0, float s0, float s1, float s2,
+                                             float &S00, float &S01, float &S02, float &S11, float &S12, float &S22)
+{
+    const float qn = sqrtf(qw0 * qw0 + qx0 * qx0 + qy0 * qy0 + qz0 * qz0);
+    const float w = qw0 / qn, x = qx0 / qn, y = qy0 / qn, z = qz0 / qn;
+    const float M00 = (1.0f - 2.0f * (y * y + z * z)) * s0;
+    const float M01 = (2.0f * (x * y - w * z)) * s1;
+    const float M02 = (2.0f * (x * z + w * y)) * s2;
+    const float M10 = (2.0f * (x * y + w * z)) * s0;
+    const float M11 = (1.0f - 2.0f * (x * x + z * z)) * s1;
+    const float M12 = (2.0f * (y * z - w * x)) * s2;
+    const float M20 = (2.0f * (x * z - w * y)) * s0;
+    const float M21 = (2.0f * (y * z + w * x)) * s1;
+    const float M22 = (1.0f - 2.0f * (x * x + y * y)) * s2;
+    S00 = M00 * M00 + M01 * M01 + M02 * M02;
+    S01 = M00 * M10 + M01 * M11 + M02 * M12;
+    S02 = M00 * M20 + M01 * M21 + M02 * M22;
+    S11 = M10 * M10 + M11 * M11 + M12 * M12;
+    S12 = M10 * M20 + M11 * M21 + M12 * M22;
+    S22 = M20 * M20 + M21 * M21 + M22 * M22;
+}
+
+// The view-independent part of the projection, once per scene (parameter cache, Sec. 5.2.2).
+__global__ __launch_bounds__(256) void build_cov3d_kernel(
+    const float *__restrict__ scale, const float *__restrict__ rot, u32 n, float *__restrict__ cov3d)
+{
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const size_t N = n;
+    float S00, S01, S02, S11, S12, S22;
+    covariance3d(rot[i], rot[N + i], rot[2 * N + i], rot[3 * N + i], scale[i], scale[N + i], scale[2 * N + i],
+                 S00, S01, S02, S11, S12, S22);
+    cov3d[i] = S00; cov3d[N + i] = S01; cov3d[2 * N + i] = S02;
+    cov3d[3 * N + i] = S11; cov3d[4 * N + i] = S12; cov3d[5 * N + i] = S22;
+}
+
+hipError_t launch_build_cov3d(const lmk_gs_gaussians &g, float *cov3d, hipStream_t stream)
+{
+    if (g.n == 0) return hipSuccess;
+    hipLaunchKernelGGL(build_cov3d_kernel, dim3((g.n + 255) / 256), dim3(256), 0, stream, g.scale, g.rot, g.n, cov3d);
+    return hipGetLastError();
+}
+
 template <u32 DEG>
 __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     const float *__restrict__ mean, const float *__restrict__ scale, const float *__restrict__ rot,
-    const float *__restrict__ opacity, const float *__restrict__ sh, u32 n,
+    const float *__restrict__ opacity, const float *__restrict__ sh, const float *__restrict__ cov3d, u32 n,
     ProjParams pp, ShConsts kc,
     float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
     float4 *__restrict__ feat, u32 *__restrict__ block_sums,
@@ -197,33 +241,25 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
         // decides, and one round trip to memory replaces three dependent ones.
         mx = __builtin_nontemporal_load(mean + i); my = __builtin_nontemporal_load(mean + N + i);
         mz = __builtin_nontemporal_load(mean + 2 * N + i);
-        const float qw0 = __builtin_nontemporal_load(rot + i), qx0 = __builtin_nontemporal_load(rot + N + i);
-        const float qy0 = __builtin_nontemporal_load(rot + 2 * N + i), qz0 = __builtin_nontemporal_load(rot + 3 * N + i);
-        const float s0 = __builtin_nontemporal_load(scale + i), s1 = __builtin_nontemporal_load(scale + N + i);
-        const float s2 = __builtin_nontemporal_load(scale + 2 * N + i);
+        // Sigma: from the parameter cache when the caller built one, else from rotation and scale
+        float S00, S01, S02, S11, S12, S22;
+        float qw0 = 1.f, qx0 = 0.f, qy0 = 0.f, qz0 = 0.f, s0 = 0.f, s1 = 0.f, s2 = 0.f;
+        if (cov3d) {
+            S00 = __builtin_nontemporal_load(cov3d + i); S01 = __builtin_nontemporal_load(cov3d + N + i);
+            S02 = __builtin_nontemporal_load(cov3d + 2 * N + i); S11 = __builtin_nontemporal_load(cov3d + 3 * N + i);
+            S12 = __builtin_nontemporal_load(cov3d + 4 * N + i); S22 = __builtin_nontemporal_load(cov3d + 5 * N + i);
+        } else {
+            qw0 = __builtin_nontemporal_load(rot + i); qx0 = __builtin_nontemporal_load(rot + N + i);
+            qy0 = __builtin_nontemporal_load(rot + 2 * N + i); qz0 = __builtin_nontemporal_load(rot + 3 * N + i);
+            s0 = __builtin_nontemporal_load(scale + i); s1 = __builtin_nontemporal_load(scale + N + i);
+            s2 = __builtin_nontemporal_load(scale + 2 * N + i);
+        }
         const float o_in = __builtin_nontemporal_load(opacity + i);
         const float px = V[0] * mx + V[1] * my + V[2] * mz + V[3];
         const float py = V[4] * mx + V[5] * my + V[6] * mz + V[7];
         pz = V[8] * mx + V[9] * my + V[10] * mz + V[11];
         if (pz > pp.cam.near_z) {
-            // Sigma = (R S)(R S)^T from the normalised quaternion
-            const float qn = sqrtf(qw0 * qw0 + qx0 * qx0 + qy0 * qy0 + qz0 * qz0);
-            const float w = qw0 / qn, x = qx0 / qn, y = qy0 / qn, z = qz0 / qn;
-            const float M00 = (1.0f - 2.0f * (y * y + z * z)) * s0;
-            const float M01 = (2.0f * (x * y - w * z)) * s1;
-            const float M02 = (2.0f * (x * z + w * y)) * s2;
-            const float M10 = (2.0f * (x * y + w * z)) * s0;
-            const float M11 = (1.0f - 2.0f * (x * x + z * z)) * s1;
-            const float M12 = (2.0f * (y * z - w * x)) * s2;
-            const float M20 = (2.0f * (x * z - w * y)) * s0;
-            const float M21 = (2.0f * (y * z + w * x)) * s1;
-            const float M22 = (1.0f - 2.0f * (x * x + y * y)) * s2;
-            const float S00 = M00 * M00 + M01 * M01 + M02 * M02;
-            const float S01 = M00 * M10 + M01 * M11 + M02 * M12;
-            const float S02 = M00 * M20 + M01 * M21 + M02 * M22;
-            const float S11 = M10 * M10 + M11 * M11 + M12 * M12;
-            const float S12 = M10 * M20 + M11 * M21 + M12 * M22;
-            const float S22 = M20 * M20 + M21 * M21 + M22 * M22;
+            if (!cov3d) covariance3d(qw0, qx0, qy0, qz0, s0, s1, s2, S00, S01, S02, S11, S12, S22);
 
             // EWA: Jacobian of the pinhole map at the guard-band clamped mean, times W
             const float txz = clamp_nan_lo(px / pz, -pp.lim_x, pp.lim_x) * pz;
@@ -500,7 +536,7 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
         }
         auto launch = [&](auto kernel) {
             hipLaunchKernelGGL(kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
-                               g.mean, g.scale, g.rot, g.opacity, g.sh, g.n, pp, kc,
+                               g.mean, g.scale, g.rot, g.opacity, g.sh, g.cov3d, g.n, pp, kc,
                                out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
                                reinterpret_cast<float4 *>(out.feat), block_sums,
                                vflags, ranges, num_voxels, index ? block_visible : nullptr);

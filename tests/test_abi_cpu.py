@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     # plain 4- and 8-byte fields in declaration order, no padding surprises
     assert C.sizeof(B.Camera) == 4 * (12 + 3 + 4 + 3 + 2 + 3 + 1)
-    assert C.sizeof(B.Gaussians) == 5 * 8 + 2 * 4
+    assert C.sizeof(B.Gaussians) == 5 * 8 + 2 * 4 + 8 and B.Gaussians.cov3d.offset == 48
     assert C.sizeof(B.Projected) == 5 * 8
     assert C.sizeof(B.Binned) == 7 * 8
     assert B.Binned.capacity.offset == 32 and B.Binned.tile_offsets.offset == 40
@@ -176,6 +176,22 @@ def test_index_build_matches_the_oracle_and_rejects_bad_input():
     wide = m.copy(); wide[0, 0] = 1e9
     assert call(mean=wide, vs=1.0) == B.ERR_UNSUPPORTED
     assert lib.lmk_gs_index_build(None, None, 0, 1.0, None, None, None, None, C.byref(nv)) == B.OK and nv.value == 0
+
+
+def test_parameter_cache_arguments():
+    lib = B.lib()
+    g, proj, _ = _args()
+    assert lib.lmk_gs_build_cov3d(None, C.c_void_p(0x1000), None) == B.ERR_INVALID
+    assert lib.lmk_gs_build_cov3d(C.byref(g), None, None) == B.ERR_INVALID
+    g2, _, _ = _args(); g2.rot = None
+    assert lib.lmk_gs_build_cov3d(C.byref(g2), C.c_void_p(0x1000), None) == B.ERR_INVALID
+    # with a cache, preprocess no longer needs rotation and scale; without one it does
+    cam = _good_camera()
+    call = lambda g_: lib.lmk_gs_preprocess(C.byref(g_), C.byref(cam), C.byref(proj), C.c_void_p(0x10000), 16, None)
+    g3, _, _ = _args(); g3.rot = None; g3.scale = None
+    assert call(g3) == B.ERR_INVALID
+    g3.cov3d = 0x1000
+    assert call(g3) == B.ERR_CAPACITY          # passes the pointer checks, stops at the scratch size
 
 
 def test_preprocess_culled_rejects_bad_arguments():
