@@ -433,7 +433,7 @@ __device__ __forceinline__ void emit_giant_part(
 }
 
 // One launch for both: the first kGiantBlocks workgroups take the giants, the rest the big ones.
-constexpr u32 kGiantBlocks = 256;
+constexpr u32 kGiantBlocks = 2048;
 
 template <bool TIGHT>
 __global__ __launch_bounds__(kPreBlock) void emit_deferred_kernel(
