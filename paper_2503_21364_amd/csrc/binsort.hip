@@ -49,6 +49,7 @@ __device__ __forceinline__ u64 load_D(const ScratchHeader *h, u64 capacity)
 // wavefront per primitive (one workgroup per primitive beyond kGiantArea tiles, from the back of
 // the same list), with the same output positions.
 constexpr u32 kBigArea = 128;
+constexpr u32 kMaskArea = 32;       // rectangles whose kept tiles the preprocess kernel recorded as a bit mask
 constexpr u32 kGiantArea = 2048;
 
 __device__ __forceinline__ void append_deferred(bool want, u32 *counter, bool from_back, u32 i, u64 offset,
@@ -179,10 +180,10 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
     ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
-    u64 *__restrict__ digit_totals)
+    u64 *__restrict__ digit_totals, const u32 *__restrict__ tile_masks)
 {
-    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of (small) rectangle areas inside the workgroup
-    __shared__ u32 s_bigpre[kPreBlock];   // pairs of deferred (big) primitives that precede each primitive
+    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of the rectangle areas expanded slot by slot
+    __shared__ u32 s_bigpre[kPreBlock];   // pairs of primitives expanded elsewhere (masked, deferred) that precede each primitive
     __shared__ ushort4 s_rect[kPreBlock];
     __shared__ u32 s_depth[kPreBlock];
     __shared__ float4 s_t0[kPreBlock];    // u, v, A, B
@@ -194,26 +195,40 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 i = blockIdx.x * kPreBlock + tid;
     const u32 kept_cnt = i < n ? tiles_touched[i] : 0u;
-    u32 area = 0, full_area = 0;
-    bool big = false;
+    // Three ways to expand a primitive's kept tiles, by the size of its rectangle:
+    //   up to kMaskArea tiles  its own thread walks the bit mask the preprocess kernel left
+    //                          (most primitives; no test, no feature record, no LDS search)
+    //   up to kBigArea         slot by slot across the workgroup, test repeated per slot
+    //   beyond                 deferred to emit_deferred_kernel
+    u32 area = 0, full_area = 0, mask = 0, dbits = 0;
+    ushort4 r = make_ushort4(0, 0, 0, 0);
+    bool big = false, masked = false;
     if (kept_cnt) {
-        const ushort4 r = rect[i];
+        r = rect[i];
         s_rect[tid] = r;
         area = ((u32)r.z - (u32)r.x) * ((u32)r.w - (u32)r.y);
         big = area > kBigArea;
+        masked = area <= kMaskArea;
         full_area = area;
-        if (big) area = 0;                        // its slots are expanded by emit_deferred_kernel
-        s_depth[tid] = __float_as_uint(depth[i]);
-        const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
-        const float4 f0 = f[0], f1 = f[1];
-        const u32 bits = __float_as_uint(f1.y);
-        const int E = (int)((bits >> 23) & 0xffu) - 127;
-        const float tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
-        s_t0[tid] = f0;
-        s_t1[tid] = make_float4(f1.x, -f0.w / f0.z, -f0.w / f1.x, tau);
+        dbits = __float_as_uint(depth[i]);
+        s_depth[tid] = dbits;
+        if (masked) {
+            mask = tile_masks[i];
+            area = 0;
+        } else if (big) {
+            area = 0;
+        } else {
+            const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
+            const float4 f0 = f[0], f1 = f[1];
+            const u32 bits = __float_as_uint(f1.y);
+            const int E = (int)((bits >> 23) & 0xffu) - 127;
+            const float tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
+            s_t0[tid] = f0;
+            s_t1[tid] = make_float4(f1.x, -f0.w / f0.z, -f0.w / f1.x, tau);
+        }
     }
     // prefix sums over the workgroup: rectangle areas (slot ownership) and kept counts (offsets[])
-    const u32 big_cnt = big ? kept_cnt : 0u;
+    const u32 big_cnt = (big || masked) ? kept_cnt : 0u;
     u32 incl = area, incl2 = kept_cnt, incl3 = big_cnt;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -241,6 +256,23 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     if (blockIdx.x == 0)      // the partition's digit totals are accumulated with atomics: start from zero
         for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kPreBlock) digit_totals[k] = 0;
     append_big(full_area, i, base + kept_excl, header, big_idx, big_off, lane, n);
+    if (masked) {
+        // kept tiles in row-major order = set bits in ascending order
+        const u32 w = (u32)r.z - (u32)r.x;
+        const u32 inv_w = (65536u + w - 1u) / w;           // slot / w == (slot * inv_w) >> 16 for slot < 32, w <= 32
+        u64 pos = base + kept_excl;
+        while (mask) {
+            const u32 slot = (u32)__builtin_ctz(mask);
+            mask &= mask - 1u;
+            const u32 row = (slot * inv_w) >> 16;
+            const u32 tx = (u32)r.x + (slot - row * w), ty = (u32)r.y + row;
+            if (pos < capacity) {
+                keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
+                vals[pos] = i;
+            }
+            ++pos;
+        }
+    }
     __syncthreads();
 
     const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
@@ -1114,7 +1146,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                reinterpret_cast<const float4 *>(proj.feat), pp,
                                block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
-                               big_idx, big_off, digit_totals);
+                               big_idx, big_off, digit_totals, reinterpret_cast<const u32 *>(scratch + L.tile_masks));
             hipLaunchKernelGGL(emit_deferred_kernel<true>, dim3(big_grid), dim3(kPreBlock), 0, stream,
                                reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                reinterpret_cast<const float4 *>(proj.feat), pp, pp.tiles_x, out.capacity,

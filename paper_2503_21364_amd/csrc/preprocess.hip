@@ -205,7 +205,7 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     const float *__restrict__ opacity, const float *__restrict__ sh, const float *__restrict__ cov3d, u32 n,
     ProjParams pp, ShConsts kc,
     float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
-    float4 *__restrict__ feat, u32 *__restrict__ block_sums,
+    float4 *__restrict__ feat, u32 *__restrict__ block_sums, u32 *__restrict__ tile_masks,
     const unsigned char *__restrict__ voxel_flags, const uint2 *__restrict__ block_range, u32 num_voxels,
     unsigned char *__restrict__ block_visible)
 {
@@ -229,6 +229,7 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     }
     const size_t N = n;
     u32 cnt = 0;            // tiles of the support rectangle (then: tiles kept)
+    u32 kept_mask = 0;      // binning rule 1: bit s = slot s (row-major) of the rectangle is kept, for the first 32 slots
     float mx = 0.f, my = 0.f, mz = 0.f, pz = 0.f, o = 0.f;
     float u = 0.f, v = 0.f, cA = 1.f, cB = 0.f, cC = 1.f;
     u32 x0 = 0, y0 = 0, x1 = 0, y1 = 0;
@@ -337,8 +338,10 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
         constexpr u32 kOwn = 16;
         u32 kept = 0;
         if (area > 0 && area <= kOwn) {
+            u32 slot = 0;
             for (u32 ty = y0; ty < y1; ++ty)
-                for (u32 tx = x0; tx < x1; ++tx) kept += tile_kept(tt, tx, ty) ? 1u : 0u;
+                for (u32 tx = x0; tx < x1; ++tx, ++slot)
+                    if (tile_kept(tt, tx, ty)) { ++kept; kept_mask |= 1u << slot; }
         }
         u64 big = __builtin_amdgcn_ballot_w64(area > kOwn);
         const u32 lane = threadIdx.x & (kWave - 1);
@@ -352,13 +355,18 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
             const u32 bx0 = __shfl(x0, src, 64), by0 = __shfl(y0, src, 64);
             const u32 bw = __shfl(w, src, 64), barea = __shfl(area, src, 64);
             u32 c = 0;
+            bool k0 = false;                                  // this lane's slot of the first 64
             for (u32 t = lane; t < barea; t += kWave) {
                 const u32 row = t / bw;
-                c += tile_kept(bt, bx0 + (t - row * bw), by0 + row) ? 1u : 0u;
+                const bool k = tile_kept(bt, bx0 + (t - row * bw), by0 + row);
+                if (t == lane) k0 = k;
+                c += k ? 1u : 0u;
             }
 #pragma unroll
             for (int o2 = 32; o2 > 0; o2 >>= 1) c += __shfl_xor(c, o2, 64);
-            if ((int)lane == src) kept = c;
+            // slots 0..31: the whole mask of a rectangle of up to 32 tiles
+            const u32 first_round = (u32)__builtin_amdgcn_ballot_w64(k0);
+            if ((int)lane == src) { kept = c; kept_mask = first_round; }
         }
         cnt = kept;
     }
@@ -447,6 +455,8 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     }
     if (i < n) {
         tiles_touched[i] = cnt;
+        // rectangles of up to 32 tiles: the emit stage expands the kept tiles from this mask
+        if (pp.cam.binning == 1u && cnt) tile_masks[i] = kept_mask;
     }
 
     // tile count of this workgroup (input of the prefix sum that places its pairs)
@@ -539,6 +549,7 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
                                g.mean, g.scale, g.rot, g.opacity, g.sh, g.cov3d, g.n, pp, kc,
                                out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
                                reinterpret_cast<float4 *>(out.feat), block_sums,
+                               reinterpret_cast<u32 *>(scratch + L.tile_masks),
                                vflags, ranges, num_voxels, index ? block_visible : nullptr);
         };
         switch (g.sh_degree) {
