@@ -40,13 +40,13 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
     group the voxel filter lets through (all of them without the filter; n_near and n_bin count
     only those); scale, rotation, opacity 32 B for those past the near plane (28 B with the
     parameter cache: six covariance entries instead of seven rotation and scale values); SH 192 B +
-    outputs 64 B (depth 4, rect 8, feature record 48, reread count 4) for binned ones; the
-    voxel table, 32 B per voxel + 8 B per group.
-    scan: block sums only (negligible).  emit: 16 B per binned primitive (+ 32 B of its
-    feature record under binning rule 1) + 12 B per pair.
-    partition by tile: one up-front histogram read of 8 B per pair, then per pass over the
-    tile bits (digits of at most 8 bits: 2 passes at 1080p and 2160p, 1 at 256 x 256)
-    histogram read 8 B + scatter read 12 B + write 12 B per pair.
+    outputs 64 B (depth 4, rect 8, feature record 48, reread count 4) for binned ones, plus the
+    4 B mask of kept tiles under binning rule 1; the voxel table, 32 B per voxel + 8 B per group.
+    scan: block sums only (negligible).  emit: 16 B per binned primitive (+ 4 B of its
+    mask under binning rule 1; the feature records of the few rectangles above 32 tiles are not
+    charged) + 12 B per pair.
+    partition by tile: per pass over the tile bits (digits of at most 8 bits: 2 passes at
+    1080p and 2160p, 1 at 256 x 256) histogram read 8 B + scatter read 12 B + write 12 B per pair.
     ranges: 8 B per pair + 8 B per tile.  order: 12 B per tile.
     per-tile sort: 12 B read + 12 B write per pair; a list longer than 16384 pairs is
     also merged, 24 B per pair and doubling round (plus one copy when the rounds are odd).
@@ -54,9 +54,9 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
     tile_bits = max(1, (tiles - 1).bit_length())
     passes = (tile_bits + 7) // 8
     n_proc = n if n_proc is None else n_proc
-    b_pre = 4 * n + 12 * n_proc + (28 if cov_cache else 32) * n_near + 256 * n_bin + 32 * voxels + (8 * ((n + 255) // 256) if voxels else 0)
-    b_emit = 4 * n + (48 if binning else 16) * n_bin + 12 * D
-    b_part = D * (8 + 32 * passes)
+    b_pre = 4 * n + 12 * n_proc + (28 if cov_cache else 32) * n_near + (260 if binning else 256) * n_bin + 32 * voxels + (8 * ((n + 255) // 256) if voxels else 0)
+    b_emit = 4 * n + (20 if binning else 16) * n_bin + 12 * D
+    b_part = D * 32 * passes
     b_ranges = 8 * D + 8 * (tiles + 1) + 12 * tiles
     b_tsort = 24 * D
     for L in long_lists:
