@@ -98,6 +98,24 @@ def test_long_lists_in_few_tiles(w, h, n, seed, binning):
     assert lens.max() > (16384 if n > 100_000 or w == 16 else 4096)
 
 
+@pytest.mark.parametrize("binning", [0, 1])
+def test_rectangles_of_every_size_class(binning):
+    """Rectangle areas from 1 tile to the whole 120 x 68 grid, dense around the sizes at which the
+    emit stage switches method (32, 128 and 2048 tiles)."""
+    rng = np.random.default_rng(5)
+    n = 4000
+    sc = scenes.make_scene(0, n=n, seed=55)
+    sc["scale"] = sc["scale"] * np.exp(rng.uniform(np.log(0.5), np.log(60.0), n)).astype(np.float32)[None, :]
+    cam = dict(scenes.make_cameras(0, 1920, 1080)[0], binning=binning)
+    r = P.full_compare(sc, cam)
+    rc = r.oracle.pre.rect.astype(int)
+    area = ((rc[:, 2] - rc[:, 0]) * (rc[:, 3] - rc[:, 1]))[r.oracle.pre.tiles_touched > 0]
+    for lo, hi in ((0, 16), (16, 32), (32, 48), (100, 128), (128, 160), (1800, 2048), (2048, 2400), (8159, 8160)):
+        assert ((area > lo) & (area <= hi)).sum() > 20, (lo, hi)
+    assert (area == 32).sum() > 0 and (area == 128).sum() > 0
+    _report(f"size classes binning {binning}", r.stats)
+
+
 # ------------------------------------------------------------------ binning rule 1
 def _tight(cam):
     return dict(cam, binning=1)
