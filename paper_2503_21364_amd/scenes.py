@@ -199,3 +199,35 @@ def hand_placed_scene(mean, scale, rot=(1, 0, 0, 0), opacity=1.0, sh_dc=(0.0, 0.
     return dict(mean=np.ascontiguousarray(mean.T), scale=np.ascontiguousarray(scale.T),
                 rot=np.ascontiguousarray(rot.T), opacity=np.ascontiguousarray(opacity),
                 sh=sh, sh_degree=3, n=n)
+
+
+HOSTILE_GROUPS = ("mean_nan", "mean_pinf", "mean_ninf", "quat_zero", "scale_nan", "scale_zero", "scale_negative",
+                  "scale_huge", "scale_denormal", "opacity_threshold", "opacity_below", "opacity_zero", "opacity_one",
+                  "on_near_plane", "quat_tiny", "quat_large")
+
+
+def hostile_scene(n: int = 3000, seed: int = 91, group_size: int = 40):
+    """Config-0 primitives with groups of degenerate attribute values (non-finite centres, zero or
+    non-finite rotations and scales, opacities at and around the 1/255 threshold, centres exactly
+    on the near plane of config 0's camera).  Returns (scene, {group name: primitive indices})."""
+    sc = make_scene(0, n=n, seed=seed)
+    idx = np.random.default_rng(seed).permutation(n)
+    groups = {name: idx[j * group_size:(j + 1) * group_size] for j, name in enumerate(HOSTILE_GROUPS)}
+    g = groups
+    sc["mean"][0, g["mean_nan"]] = np.nan
+    sc["mean"][2, g["mean_pinf"]] = np.inf
+    sc["mean"][1, g["mean_ninf"]] = -np.inf
+    sc["rot"][:, g["quat_zero"]] = 0.0
+    sc["scale"][1, g["scale_nan"]] = np.nan
+    sc["scale"][:, g["scale_zero"]] = 0.0                 # a point: only the low-pass remains
+    sc["scale"][0, g["scale_negative"]] *= -1.0           # the sign of a scale does not matter
+    sc["scale"][:, g["scale_huge"]] = 1e20                # the covariance overflows
+    sc["scale"][2, g["scale_denormal"]] = 1e-30
+    sc["opacity"][g["opacity_threshold"]] = np.float32(1.0 / 255.0)
+    sc["opacity"][g["opacity_below"]] = np.nextafter(np.float32(1.0 / 255.0), np.float32(0))
+    sc["opacity"][g["opacity_zero"]] = 0.0
+    sc["opacity"][g["opacity_one"]] = 1.0
+    sc["mean"][:, g["on_near_plane"]] = np.array([[0.0], [0.0], [4.0 - NEAR]], np.float32)
+    sc["rot"][:, g["quat_tiny"]] *= np.float32(1e-20)
+    sc["rot"][:, g["quat_large"]] *= np.float32(1e18)
+    return sc, groups

@@ -172,6 +172,16 @@ def test_everything_culled():
     np.testing.assert_array_equal(P.to_np(r.gpu.out_rgb[1]), np.float32(0.4))
 
 
+@pytest.mark.parametrize("binning", [0, 1])
+def test_degenerate_attribute_values(binning):
+    # non-finite centres, zero / non-finite / overflowing rotations and scales, opacities at the threshold
+    sc, groups = scenes.hostile_scene()
+    cam = dict(scenes.make_cameras(0, 300, 200)[0], binning=binning)
+    r = P.full_compare(sc, cam)
+    assert torch.isfinite(r.gpu.out_rgb).all() and torch.isfinite(r.gpu.out_T).all()
+    _report(f"degenerate values binning {binning}", r.stats)
+
+
 def test_single_primitive_covering_many_tiles():
     sc = scenes.hand_placed_scene([(0.1, -0.2, 0.0)], [(0.8, 0.3, 0.5)], rot=(0.9, 0.1, 0.3, -0.2),
                                   opacity=0.7, sh_dc=(1.0, 0.2, -0.4))

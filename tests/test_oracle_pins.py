@@ -521,3 +521,25 @@ def test_empty_scene():
     cam = scenes.make_cameras(0, 32, 32)[0]
     fr = ref.render_frame(sc, cam)
     assert fr.binned.D == 0 and np.all(fr.img.T == 1.0) and np.all(fr.img.rgb == 0.0)
+
+
+def test_degenerate_attribute_values_are_culled_where_the_readings_say_so():
+    sc, g = scenes.hostile_scene()
+    cam = scenes.make_cameras(0, 300, 200)[0]
+    fr = ref.render_frame(sc, cam)
+    st = fr.pre.stage
+    assert np.all(st[g["mean_nan"]] == ref.CULL_NEAR) and np.all(st[g["mean_pinf"]] == ref.CULL_NEAR)
+    for name in ("quat_zero", "scale_nan", "scale_huge"):
+        assert np.all(st[g[name]] == ref.CULL_DET), name
+    assert np.all(st[g["opacity_below"]] == ref.CULL_OPACITY) and np.all(st[g["opacity_zero"]] == ref.CULL_OPACITY)
+    assert not np.any(st[g["opacity_threshold"]] == ref.CULL_OPACITY)
+    # a zero-scale primitive is a point spread by the low-pass term only: Sigma' = h I
+    vis = [i for i in g["scale_zero"] if st[i] == ref.VISIBLE]
+    assert len(vis) > 0
+    np.testing.assert_allclose(fr.pre.cov2d[:, vis], np.array([[0.3], [0.0], [0.3]]) * np.ones((1, len(vis))), atol=1e-7)
+    # the sign of a scale and the norm of a quaternion do not matter
+    flip = dict(sc, scale=np.abs(sc["scale"]))
+    assert np.array_equal(ref.preprocess(flip, cam).rect[g["scale_negative"]], fr.pre.rect[g["scale_negative"]])
+    # nothing non-finite reaches the image
+    assert np.isfinite(fr.img.rgb).all() and np.isfinite(fr.img.T).all()
+    assert np.all(fr.pre.tiles_touched[st != ref.VISIBLE] == 0)
