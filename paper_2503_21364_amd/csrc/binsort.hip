@@ -958,7 +958,10 @@ __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
     const u64 beg = tile_offsets[tile];
     const u64 len = tile_offsets[tile + 1] - beg;
     if (len < 2 || len > (u64)kSmallCap) return;
-    sort_pairs_in_lds<kSmallThreads, kSmallItems>(keys, vals, beg, (u32)len, tile, s);
+    // fewer elements per lane for shorter lists: all 64 lanes work in every merge round
+    if (len <= 2u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 2u>(keys, vals, beg, (u32)len, tile, s);
+    else if (len <= 4u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 4u>(keys, vals, beg, (u32)len, tile, s);
+    else sort_pairs_in_lds<kSmallThreads, kSmallItems>(keys, vals, beg, (u32)len, tile, s);
 }
 
 // lists of 513 .. 2048 and 2049 .. 4096 pairs: one workgroup each; in `order` they follow the
