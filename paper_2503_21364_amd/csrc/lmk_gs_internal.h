@@ -35,6 +35,7 @@ struct ScratchLayout {
     size_t header;        // ScratchHeader
     size_t block_sums;    // u32 [pre_blocks]      tile counts per preprocess workgroup
     size_t block_offsets; // u64 [pre_blocks + 1]  their exclusive prefix sum
+    size_t voxel_flags;   // u8  [n]               voxel filter: 1 = the voxel may reach the image (at most n voxels)
     size_t tile_masks;    // u32 [n]               binning rule 1: kept tiles of rectangles of up to 32 tiles
     size_t digit_totals;  // u64 [kMaxPasses][512] global digit histogram of each pass
     size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
@@ -60,6 +61,7 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
     L.header = o;        o += align256(sizeof(ScratchHeader));
     L.block_sums = o;    o += align256(sizeof(u32) * (size_t)(L.pre_blocks + 1));
     L.block_offsets = o; o += align256(sizeof(u64) * ((size_t)L.pre_blocks + 1));
+    L.voxel_flags = o;   o += align256((size_t)n + 1);
     L.tile_masks = o;    o += align256(sizeof(u32) * ((size_t)n + 1));
     L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kMaxRadix);
     L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);

@@ -146,6 +146,15 @@ __device__ __forceinline__ bool voxel_visible(const ProjParams &pp, const float4
     return true;
 }
 
+// One thread per voxel.
+__global__ __launch_bounds__(256) void voxel_flags_kernel(
+    const float4 *__restrict__ box, u32 num_voxels, ProjParams pp, unsigned char *__restrict__ voxel_flags)
+{
+    const u32 v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= num_voxels) return;
+    voxel_flags[v] = voxel_visible(pp, box[2 * (size_t)v], box[2 * (size_t)v + 1]) ? 1 : 0;
+}
+
 // Sigma = (R S)(R S)^T from an unnormalised quaternion (w, x, y, z) and the scales (Sec. 2.2 Eq. 8)
 __device__ __forceinline__ void covariance3d(float qw0, float qx0, float qy0, float qz0, float s0, float s1, float s2,
                                              float &S00, float &S01, float &S02, float &S11, float &S12, float &S22)
@@ -197,20 +206,18 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     ProjParams pp, ShConsts kc,
     float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
     float4 *__restrict__ feat, u32 *__restrict__ block_sums, u32 *__restrict__ tile_masks,
-    const float4 *__restrict__ voxel_box, const uint2 *__restrict__ block_range, u32 num_voxels,
+    const unsigned char *__restrict__ voxel_flags, const uint2 *__restrict__ block_range, u32 num_voxels,
     unsigned char *__restrict__ block_visible)
 {
     __shared__ u32 s_part[kPreBlock / kWave];
     const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
-    if (voxel_box) {
-        // voxel filter: does any voxel holding one of this workgroup's primitives pass?  One
-        // voxel per thread (a workgroup's 256 primitives usually lie in one to three voxels).
+    if (voxel_flags) {
+        // voxel filter: does any voxel holding one of this workgroup's primitives pass?
         const uint2 r = block_range[blockIdx.x];
         // a corrupt range can only cost time, never an out-of-bounds read
         const u32 last = r.y < num_voxels ? r.y : num_voxels - 1;
         int mine = 0;
-        for (u32 v = r.x + threadIdx.x; v <= last && !mine; v += kPreBlock)
-            mine = voxel_visible(pp, voxel_box[2 * (size_t)v], voxel_box[2 * (size_t)v + 1]) ? 1 : 0;
+        for (u32 v = r.x + threadIdx.x; v <= last; v += kPreBlock) mine |= voxel_flags[v];
         const int any = __syncthreads_or(mine);
         if (block_visible && threadIdx.x == 0) block_visible[blockIdx.x] = any ? 1 : 0;
         if (!any) {
@@ -524,13 +531,18 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
     u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
     if (L.pre_blocks > 0) {
-        const float4 *boxes = nullptr;
+        const unsigned char *vflags = nullptr;
         const uint2 *ranges = nullptr;
         u32 num_voxels = 0;
         if (index) {
-            boxes = reinterpret_cast<const float4 *>(index->box);
-            ranges = reinterpret_cast<const uint2 *>(index->block_range);
+            unsigned char *f = reinterpret_cast<unsigned char *>(scratch + L.voxel_flags);
             num_voxels = index->num_voxels;
+            ranges = reinterpret_cast<const uint2 *>(index->block_range);
+            hipLaunchKernelGGL(voxel_flags_kernel, dim3((num_voxels + 255) / 256), dim3(256), 0, stream,
+                               reinterpret_cast<const float4 *>(index->box), num_voxels, pp, f);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            vflags = f;
         }
         auto launch = [&](auto kernel) {
             hipLaunchKernelGGL(kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
@@ -538,7 +550,7 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
                                out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
                                reinterpret_cast<float4 *>(out.feat), block_sums,
                                reinterpret_cast<u32 *>(scratch + L.tile_masks),
-                               boxes, ranges, num_voxels, index ? block_visible : nullptr);
+                               vflags, ranges, num_voxels, index ? block_visible : nullptr);
         };
         switch (g.sh_degree) {
             case 0: launch(preprocess_kernel<0>); break;
