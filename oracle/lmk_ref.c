@@ -13,7 +13,9 @@
  *                    Gaussian ("splatting"); depth sort; blending per screen tile
  *   Sec. 2.2 Eq. 9-10  front-to-back compositing with sigma_i = alpha_i G'_i(x')
  *   Sec. 4.2.1       the rasteriser stages named there: per-primitive projection,
- *                    duplication into (tile, depth) keys, sort, per-tile blend
+ *                    duplication into (tile, depth) keys, sort, per-tile blend;
+ *                    the per-tile intersection test (binning rule 1)
+ *   Sec. 4.2.2       view-frustum filtering of voxels of a reordered scene
  *
  * The report prints no constants (tile size, thresholds, SH basis, pixel
  * centres, key layout).  The readings taken here are listed at each step and
@@ -31,8 +33,11 @@
  * Pins (tests/test_oracle_*.py): closed-form isotropic footprint, single and
  * double splat closed forms, SH orthonormality and addition theorem against a
  * library routine, brute-force per-pixel compositing over all primitives,
- * tile-size independence, transmittance monotonicity, sort/CSR invariants.
- * No function here is "parity unpinned".
+ * tile-size independence, transmittance monotonicity, sort/CSR invariants;
+ * the tile intersection test of binning rule 1 against dense sampling and
+ * against the unchanged image; the voxel visibility test against brute-force
+ * conservativeness, closed cases and a planted mistake; the culls of
+ * degenerate attribute values.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
