@@ -127,7 +127,9 @@ typedef struct lmk_gs_binned {
 
 /* Bytes of device scratch the three calls need for n primitives, a
  * width x height image and `capacity` pairs.  The same scratch buffer
- * (256-byte aligned) must be passed to preprocess and bin_sort of one frame.
+ * (256-byte aligned) must be passed to preprocess and bin_sort of one frame:
+ * it carries the per-group tile counts and, under binning rule 1, the masks of
+ * kept tiles from the one to the other.  Its contents need no initialisation.
  * Its first 16 bytes are {uint64 pair count D, int32 status, int32 pad}. */
 int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height,
                                uint64_t capacity, size_t *scratch_bytes);
@@ -172,7 +174,7 @@ int32_t lmk_gs_index_build(const float *mean, const float *scale, uint32_t n, fl
  * lmk_gs_preprocess on the same (reordered) scene.  `g` must be the scene in the order of the
  * index.  The 3x3 part of cam->view must be a rotation (LMK_GS_ERR_UNSUPPORTED otherwise).
  * block_visible: optional device array [ceil(n / LMK_GS_PRE_BLOCK)] receiving 1 for every group
- * that was processed, 0 for every group skipped (NULL: kept in scratch). */
+ * that was processed, 0 for every group skipped (NULL: not reported). */
 int32_t lmk_gs_preprocess_culled(const lmk_gs_gaussians *g, const lmk_gs_voxel_index *index,
                                  const lmk_gs_camera *cam, const lmk_gs_projected *out,
                                  uint8_t *block_visible,
