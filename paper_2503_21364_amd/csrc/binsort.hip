@@ -78,13 +78,36 @@ __device__ __forceinline__ void append_big(u32 area, u32 i, u64 offset, ScratchH
     append_deferred(area > kGiantArea, &header->giant_count, true, i, offset, big_idx, big_off, lane, n);
 }
 
+// Where the pairs of workgroup `b` of the preprocess grid start: its offset inside its group
+// of kScanGroup workgroups plus the totals of the groups before.  Called by the whole workgroup
+// ahead of a __syncthreads(); `s_part` gets one partial sum per wavefront, summed by block_base_finish.
+__device__ __forceinline__ void block_base_start(const u64 *__restrict__ group_totals, u32 b, u64 *s_part,
+                                                 u32 tid, u32 lane, u32 wv)
+{
+    const u32 groups_before = b / kScanGroup;
+    u64 part = 0;
+    for (u32 g = tid; g < groups_before; g += kPreBlock) part += group_totals[g];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
+    if (lane == 0) s_part[wv] = part;
+}
+__device__ __forceinline__ u64 block_base_finish(const u64 *__restrict__ block_offsets, u32 b, const u64 *s_part)
+{
+    u64 base = block_offsets[b];
+#pragma unroll
+    for (u32 k = 0; k < kPreBlock / kWave; ++k) base += s_part[k];
+    return base;
+}
+
 __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
-    const float *__restrict__ depth, const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
+    const float *__restrict__ depth, const u64 *__restrict__ block_offsets,
+    const u64 *__restrict__ group_totals, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
     ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
     u64 *__restrict__ digit_totals)
 {
+    __shared__ u64 s_gpart[kPreBlock / kWave];
     __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of the (small) rectangles expanded here
     __shared__ u32 s_off[kPreBlock];      // exclusive prefix of tiles_touched: where a primitive's pairs start
     __shared__ ushort4 s_rect[kPreBlock];
@@ -94,6 +117,7 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 i = blockIdx.x * kPreBlock + tid;
+    block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);     // summed after the barrier below
     const u32 cnt = i < n ? tiles_touched[i] : 0u;
     const bool big = cnt > kBigArea;
     const u32 small = big ? 0u : cnt;
@@ -119,14 +143,15 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     s_excl[tid] = wave_base + incl - small;
     const u32 off = wave_base2 + incl2 - cnt;
     s_off[tid] = off;
-    const u64 base = block_offsets[blockIdx.x];
+    const u64 base = block_base_finish(block_offsets, blockIdx.x, s_gpart);
     if (offsets) {
         if (i < n) offsets[i] = base + off;
         if (i == n - 1) offsets[n] = base + total2;
     }
     if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
-    if (blockIdx.x == 0)      // the partition's digit totals are accumulated with atomics: start from zero
-        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kPreBlock) digit_totals[k] = 0;
+    // the partition's digit totals are accumulated with atomics: start from zero
+    for (u32 k = blockIdx.x * kPreBlock + tid; k < kMaxPasses * kTotalCopies * kMaxRadix; k += gridDim.x * kPreBlock)
+        digit_totals[k] = 0;
     append_big(cnt, i, base + off, header, big_idx, big_off, lane, n);
     __syncthreads();
 
@@ -177,11 +202,12 @@ __device__ __forceinline__ float emit_quad_adj(float A, float B, float C, float 
 __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
     const float *__restrict__ depth, const float4 *__restrict__ feat, ProjParams pp,
-    const u64 *__restrict__ block_offsets, u32 n, u32 tiles_x,
+    const u64 *__restrict__ block_offsets, const u64 *__restrict__ group_totals, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
     ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
     u64 *__restrict__ digit_totals, const u32 *__restrict__ tile_masks)
 {
+    __shared__ u64 s_gpart[kPreBlock / kWave];
     __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of the rectangle areas expanded slot by slot
     __shared__ u32 s_bigpre[kPreBlock];   // pairs of primitives expanded elsewhere (masked, deferred) that precede each primitive
     __shared__ ushort4 s_rect[kPreBlock];
@@ -194,6 +220,7 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 i = blockIdx.x * kPreBlock + tid;
+    block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);     // summed after the barrier below
     const u32 kept_cnt = i < n ? tiles_touched[i] : 0u;
     // Three ways to expand a primitive's kept tiles, by the size of its rectangle:
     //   up to kMaskArea tiles  its own thread walks the bit mask the preprocess kernel left
@@ -247,14 +274,15 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     s_excl[tid] = wave_base + incl - area;
     const u32 kept_excl = wave_base2 + incl2 - kept_cnt;
     s_bigpre[tid] = wave_base3 + incl3 - big_cnt;
-    const u64 base = block_offsets[blockIdx.x];
+    const u64 base = block_base_finish(block_offsets, blockIdx.x, s_gpart);
     if (offsets) {
         if (i < n) offsets[i] = base + kept_excl;
         if (i == n - 1) offsets[n] = base + total2;
     }
     if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
-    if (blockIdx.x == 0)      // the partition's digit totals are accumulated with atomics: start from zero
-        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kPreBlock) digit_totals[k] = 0;
+    // the partition's digit totals are accumulated with atomics: start from zero
+    for (u32 k = blockIdx.x * kPreBlock + tid; k < kMaxPasses * kTotalCopies * kMaxRadix; k += gridDim.x * kPreBlock)
+        digit_totals[k] = 0;
     append_big(full_area, i, base + kept_excl, header, big_idx, big_off, lane, n);
     if (masked) {
         // kept tiles in row-major order = set bits in ascending order
@@ -498,26 +526,22 @@ __device__ __forceinline__ void wave_hist_add(u32 *hist, u32 d, bool valid, u32 
     }
 }
 
-// The first pass also builds the global digit totals of the later passes (they do not depend on
-// the order of the pairs): one more LDS histogram per later pass, flushed with one global atomic
-// per non-empty digit when the workgroup is done.  Its own totals are the row sums of `table`
-// and come out of the same flush.
-template <bool FIRST>
+// Each pass also adds its digit totals (the row sums of `table`, which the scan needs as the
+// base of every digit) to `digit_totals`: kept per workgroup in LDS and flushed with one global
+// atomic per non-empty digit when the workgroup is done.  Atomics on one address are served one
+// after the other, and a pass over the high tile bits has only a few digits, so the totals are
+// kept in kTotalCopies copies (workgroup b adds to copy b % kTotalCopies; the scan adds them up).
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
-    u32 shift, u32 bits, u32 *__restrict__ table, u64 table_stride, SortPlan plan,
-    u64 *__restrict__ digit_totals)
+    u32 shift, u32 bits, u32 *__restrict__ table, u64 table_stride, u64 *__restrict__ digit_totals)
 {
     __shared__ u32 s_hist[kMaxRadix];
-    __shared__ u32 s_tot[FIRST ? kMaxPasses : 1][kMaxRadix];
+    __shared__ u32 s_tot[kMaxRadix];
     const u64 D = load_D(header, capacity);
     const u64 ntiles = (D + kSortTile - 1) / kSortTile;
     const u32 tid = threadIdx.x;
     const u32 dmask = (1u << bits) - 1u;
-    if (FIRST) {
-        for (u32 k = tid; k < kMaxPasses * kMaxRadix; k += kSortThreads) (&s_tot[0][0])[k] = 0;
-        __syncthreads();
-    }
+    for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_tot[d] = 0;    // thread d owns s_tot[d]
     for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_hist[d] = 0;
         __syncthreads();
@@ -531,29 +555,20 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kSortThreads + tid;
-            const bool valid = idx < D;
-            const u32 d = (u32)(k[j] >> shift) & dmask;
-            wave_hist_add(s_hist, d, valid, tid);
-            if (FIRST) {
-#pragma unroll
-                for (u32 p = 1; p < kMaxPasses; ++p)
-                    if (p < plan.passes && valid)
-                        atomicAdd(&s_tot[p][(u32)(k[j] >> plan.shift[p]) & ((1u << plan.bits[p]) - 1u)], 1u);
-            }
+            wave_hist_add(s_hist, (u32)(k[j] >> shift) & dmask, idx < D, tid);
         }
         __syncthreads();
         for (u32 d = tid; d < kMaxRadix; d += kSortThreads) {
             const u32 c = s_hist[d];
             table[(u64)d * table_stride + tile] = c;
-            if (FIRST) s_tot[0][d] += c;                  // thread d owns s_tot[0][d] here
+            s_tot[d] += c;
         }
         __syncthreads();
     }
-    if (FIRST) {
-        for (u32 k = tid; k < plan.passes * kMaxRadix; k += kSortThreads) {
-            const u32 c = (&s_tot[0][0])[k];
-            if (c) atomicAdd(reinterpret_cast<unsigned long long *>(&digit_totals[k]), (unsigned long long)c);
-        }
+    u64 *mine = digit_totals + (size_t)(blockIdx.x % kTotalCopies) * kMaxRadix;
+    for (u32 d = tid; d < kMaxRadix; d += kSortThreads) {
+        const u32 c = s_tot[d];
+        if (c) atomicAdd(reinterpret_cast<unsigned long long *>(&mine[d]), (unsigned long long)c);
     }
 }
 
@@ -572,7 +587,8 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
 
     // base = total of the digits below mine
     u64 part = 0;
-    for (u32 d = tid; d < digit; d += kSortThreads) part += digit_totals[d];
+    for (u32 k = tid; k < kTotalCopies * kMaxRadix; k += kSortThreads)
+        if ((k & (kMaxRadix - 1)) < digit) part += digit_totals[k];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
     if (lane == 0) s_wave[wv] = part;
@@ -586,33 +602,38 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
 
     const u32 *row = table + (u64)digit * table_stride;
     u64 *orow = offsets + (u64)digit * table_stride;
-    constexpr u32 kItems = 8;                  // consecutive sort tiles per thread, loaded together
-    for (u64 base = 0; base < ntiles; base += (u64)kSortThreads * kItems) {
-        const u64 first = base + (u64)tid * kItems;
-        u32 v[kItems];
-        u64 mine = 0;
+    // rows of 64 consecutive sort tiles per wavefront, so that loads and stores are whole lines;
+    // a count is at most kSortTile, so the sums inside one wavefront's rows fit 32 bits
+    constexpr u32 kRows = 8;
+    constexpr u32 kWaves = kSortThreads / kWave;
+    for (u64 base = 0; base < ntiles; base += (u64)kWaves * kRows * kWave) {
+        const u64 first = base + (u64)wv * kRows * kWave + lane;
+        u32 x[kRows], inc[kRows], before[kRows];
 #pragma unroll
-        for (u32 k = 0; k < kItems; ++k) v[k] = first + k < ntiles ? row[first + k] : 0u;
+        for (u32 k = 0; k < kRows; ++k) x[k] = first + k * kWave < ntiles ? row[first + k * kWave] : 0u;
+        u32 wave_total = 0;
 #pragma unroll
-        for (u32 k = 0; k < kItems; ++k) mine += v[k];
-        u64 incl = mine;
+        for (u32 k = 0; k < kRows; ++k) {
+            u32 v = x[k];
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const u64 t = __shfl_up(incl, o, 64);
-            if ((int)lane >= o) incl += t;
+            for (int o = 1; o < 64; o <<= 1) {
+                const u32 t = __shfl_up(v, o, 64);
+                if ((int)lane >= o) v += t;
+            }
+            inc[k] = v;
+            before[k] = wave_total;
+            wave_total += __shfl(v, kWave - 1, 64);
         }
         __syncthreads();                       // s_wave free again
-        if (lane == kWave - 1) s_wave[wv] = incl;
+        if (lane == 0) s_wave[wv] = wave_total;
         __syncthreads();
-        u64 run = s_carry + incl - mine;
+        u64 run = s_carry;
         for (u32 k = 0; k < wv; ++k) run += s_wave[k];
 #pragma unroll
-        for (u32 k = 0; k < kItems; ++k) {
-            if (first + k < ntiles) orow[first + k] = run;
-            run += v[k];
-        }
+        for (u32 k = 0; k < kRows; ++k)
+            if (first + k * kWave < ntiles) orow[first + k * kWave] = run + (before[k] + inc[k] - x[k]);
         __syncthreads();
-        if (tid == kSortThreads - 1) s_carry = run;
+        if (tid == kSortThreads - 1) s_carry = run + wave_total;
         __syncthreads();
     }
 }
@@ -808,35 +829,91 @@ __device__ __forceinline__ u32 length_bucket(u64 len)
 }
 constexpr u32 kSmallBucket = 9, kLowBucket = 11, kMidBucket = 12;   // 2^9 = kSmallCap, 2^11 = kLow, 2^12 = kMid
 
+// Most tiles fall into a handful of buckets, and LDS atomics on one word are served one after
+// the other: every bucket has kOrderCopies counters, picked by the low lane bits, so that the 64
+// atomics of a wavefront spread over that many words.  An exclusive scan over
+// [bucket][copy] turns the counts into the first slot of every (bucket, copy).
+constexpr u32 kOrderCopies = 16, kOrderCounters = 65 * kOrderCopies, kOrderBatch = 8, kOrderStage = 32768;
+
 __global__ __launch_bounds__(1024) void tile_order_kernel(
     const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order,
     u32 *__restrict__ order_copy, u32 *__restrict__ classes)
 {
-    __shared__ u32 s_cnt[65];
-    const u32 tid = threadIdx.x;
-    if (tid < 65) s_cnt[tid] = 0;
+    __shared__ u32 s_cnt[kOrderCounters];
+    __shared__ u32 s_wave[1024 / kWave];
+    // slots are scattered and one compute unit does all the address work: the order is put
+    // together in LDS and written out in whole lines (images of up to kOrderStage tiles)
+    __shared__ u32 s_order[kOrderStage];
+    const bool staged = num_tiles <= kOrderStage;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 copy = tid & (kOrderCopies - 1);
+    for (u32 k = tid; k < kOrderCounters; k += 1024) s_cnt[k] = 0;
     __syncthreads();
-    for (u32 t = tid; t < num_tiles; t += 1024) {
-        const u32 b = length_bucket(tile_offsets[t + 1] - tile_offsets[t]);
-        atomicAdd(&s_cnt[64 - b], 1u);                                 // long lists first
+    // kOrderBatch tiles per thread and round: all their loads are in flight together
+    for (u32 base = 0; base < num_tiles; base += kOrderBatch * 1024) {
+        u32 b[kOrderBatch];
+#pragma unroll
+        for (u32 j = 0; j < kOrderBatch; ++j) {
+            const u32 t = base + j * 1024 + tid;
+            b[j] = t < num_tiles ? length_bucket(tile_offsets[t + 1] - tile_offsets[t]) : 0xffu;
+        }
+#pragma unroll
+        for (u32 j = 0; j < kOrderBatch; ++j)
+            if (b[j] != 0xffu) atomicAdd(&s_cnt[(64 - b[j]) * kOrderCopies + copy], 1u);     // long lists first
     }
+    __syncthreads();
+    // exclusive scan of the counters, two per thread (kOrderCounters <= 2048)
+    const u32 k0 = 2 * tid, k1 = 2 * tid + 1;
+    const u32 c0 = k0 < kOrderCounters ? s_cnt[k0] : 0u, c1 = k1 < kOrderCounters ? s_cnt[k1] : 0u;
+    u32 incl = c0 + c1;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const u32 v = __shfl_up(incl, o, 64);
+        if ((int)lane >= o) incl += v;
+    }
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    u32 before = 0;
+    for (u32 k = 0; k < wv; ++k) before += s_wave[k];
+    const u32 excl = before + incl - (c0 + c1);
+    if (k0 < kOrderCounters) s_cnt[k0] = excl;
+    if (k1 < kOrderCounters) s_cnt[k1] = excl + c0;
     __syncthreads();
     if (tid == 0) {
-        u32 run = 0, huge = 0, mid = 0, low = 0;
-        for (u32 k = 0; k < 65; ++k) {
-            const u32 c = s_cnt[k];
-            const u32 b = 64 - k;
-            if (b > kMidBucket) huge += c; else if (b > kLowBucket) mid += c; else if (b > kSmallBucket) low += c;
-            s_cnt[k] = run; run += c;
-        }
-        classes[0] = huge; classes[1] = mid; classes[2] = low;
+        // tiles in buckets above a class limit = first slot of the first bucket at or below it
+        const u32 huge = s_cnt[(64 - kMidBucket) * kOrderCopies];
+        const u32 mid = s_cnt[(64 - kLowBucket) * kOrderCopies];
+        const u32 low = s_cnt[(64 - kSmallBucket) * kOrderCopies];
+        classes[0] = huge; classes[1] = mid - huge; classes[2] = low - mid;
     }
     __syncthreads();
-    for (u32 t = tid; t < num_tiles; t += 1024) {
-        const u32 b = length_bucket(tile_offsets[t + 1] - tile_offsets[t]);
-        const u32 slot = atomicAdd(&s_cnt[64 - b], 1u);
-        order[slot] = t;
-        if (order_copy) order_copy[slot] = t;
+    for (u32 base = 0; base < num_tiles; base += kOrderBatch * 1024) {
+        u32 b[kOrderBatch];
+#pragma unroll
+        for (u32 j = 0; j < kOrderBatch; ++j) {
+            const u32 t = base + j * 1024 + tid;
+            b[j] = t < num_tiles ? length_bucket(tile_offsets[t + 1] - tile_offsets[t]) : 0xffu;
+        }
+#pragma unroll
+        for (u32 j = 0; j < kOrderBatch; ++j) {
+            if (b[j] == 0xffu) continue;
+            const u32 t = base + j * 1024 + tid;
+            const u32 slot = atomicAdd(&s_cnt[(64 - b[j]) * kOrderCopies + copy], 1u);
+            if (staged) {
+                s_order[slot] = t;
+            } else {
+                order[slot] = t;
+                if (order_copy) order_copy[slot] = t;
+            }
+        }
+    }
+    if (staged) {
+        __syncthreads();
+        for (u32 k = tid; k < num_tiles; k += 1024) {
+            const u32 t = s_order[k];
+            order[k] = t;
+            if (order_copy) order_copy[k] = t;
+        }
     }
 }
 
@@ -1125,6 +1202,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
 {
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
     u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
+    const u64 *group_totals = reinterpret_cast<const u64 *>(scratch + L.group_totals);
     u64 *digit_totals = reinterpret_cast<u64 *>(scratch + L.digit_totals);
     u32 *table = reinterpret_cast<u32 *>(scratch + L.table);
     u64 *offsets = reinterpret_cast<u64 *>(scratch + L.offsets);
@@ -1148,7 +1226,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
             hipLaunchKernelGGL(emit_tight_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
                                reinterpret_cast<const float4 *>(proj.feat), pp,
-                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
+                               block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
                                big_idx, big_off, digit_totals, reinterpret_cast<const u32 *>(scratch + L.tile_masks));
             hipLaunchKernelGGL(emit_deferred_kernel<true>, dim3(big_grid), dim3(kPreBlock), 0, stream,
                                reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
@@ -1157,7 +1235,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
         } else {
             hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               block_offsets, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
+                               block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
                                big_idx, big_off, digit_totals);
             hipLaunchKernelGGL(emit_deferred_kernel<false>, dim3(big_grid), dim3(kPreBlock), 0, stream,
                                reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
@@ -1173,15 +1251,9 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     // enough resident workgroups to fill 256 CUs several times over; each loops over sort tiles
     const u32 grid = grid_for(L.sort_tiles, 256u * 16u);
     for (u32 p = 0; p < plan.passes; ++p) {
-        const u64 *totals = digit_totals + (size_t)p * kMaxRadix;
-        if (p == 0)
-            hipLaunchKernelGGL(radix_hist_kernel<true>, dim3(grid), dim3(kSortThreads), 0, stream,
-                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles,
-                               plan, digit_totals);
-        else
-            hipLaunchKernelGGL(radix_hist_kernel<false>, dim3(grid), dim3(kSortThreads), 0, stream,
-                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles,
-                               plan, digit_totals);
+        u64 *totals = digit_totals + (size_t)p * kTotalCopies * kMaxRadix;
+        hipLaunchKernelGGL(radix_hist_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
+                           kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles, totals);
         hipLaunchKernelGGL(radix_scan_kernel, dim3(1u << plan.bits[p]), dim3(kSortThreads), 0, stream,
                            header, out.capacity, table, offsets, L.sort_tiles, totals);
         hipLaunchKernelGGL(radix_scatter_kernel, dim3(grid), dim3(kSortThreads), 0, stream,

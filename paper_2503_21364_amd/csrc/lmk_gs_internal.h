@@ -15,11 +15,13 @@ typedef uint32_t u32;
 constexpr u32 kWave = 64;               // CDNA wavefront width
 constexpr u32 kPreBlock = LMK_GS_PRE_BLOCK;   // primitives per preprocess / emit workgroup
 constexpr u32 kSortThreads = 256;       // radix sort workgroup
-constexpr u32 kSortItems = 16;          // keys per thread
-constexpr u32 kSortTile = kSortThreads * kSortItems;   // 4096 pairs per workgroup pass
+constexpr u32 kSortItems = 8;           // keys per thread
+constexpr u32 kSortTile = kSortThreads * kSortItems;   // 2048 pairs per workgroup pass
 constexpr u32 kMaxRadixBits = 8;         // digits are at most 8 bits wide, chosen per frame
 constexpr u32 kMaxRadix = 1u << kMaxRadixBits;
 constexpr u32 kMaxPasses = 8;
+constexpr u32 kScanGroup = 256;         // preprocess workgroups per group of the two-level prefix sum
+constexpr u32 kTotalCopies = 4;         // copies of each pass's digit totals, to spread the atomics
 
 // Header at the start of the scratch buffer.
 struct ScratchHeader {
@@ -34,10 +36,11 @@ struct ScratchHeader {
 struct ScratchLayout {
     size_t header;        // ScratchHeader
     size_t block_sums;    // u32 [pre_blocks]      tile counts per preprocess workgroup
-    size_t block_offsets; // u64 [pre_blocks + 1]  their exclusive prefix sum
+    size_t block_offsets; // u64 [pre_blocks + 1]  their exclusive prefix sum within groups of kScanGroup
+    size_t group_totals;  // u64 [groups]          total of each group
     size_t voxel_flags;   // u8  [n]               voxel filter: 1 = the voxel may reach the image (at most n voxels)
     size_t tile_masks;    // u32 [n]               binning rule 1: kept tiles of rectangles of up to 32 tiles
-    size_t digit_totals;  // u64 [kMaxPasses][512] global digit histogram of each pass
+    size_t digit_totals;  // u64 [kMaxPasses][kTotalCopies][kMaxRadix] digit totals of each pass
     size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
     size_t offsets;       // u64 [512][sort_tiles] their output offsets
     size_t order;         // u32 [tiles]     tile ids by descending list length
@@ -61,9 +64,10 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
     L.header = o;        o += align256(sizeof(ScratchHeader));
     L.block_sums = o;    o += align256(sizeof(u32) * (size_t)(L.pre_blocks + 1));
     L.block_offsets = o; o += align256(sizeof(u64) * ((size_t)L.pre_blocks + 1));
+    L.group_totals = o;  o += align256(sizeof(u64) * ((size_t)L.pre_blocks / kScanGroup + 2));
     L.voxel_flags = o;   o += align256((size_t)n + 1);
     L.tile_masks = o;    o += align256(sizeof(u32) * ((size_t)n + 1));
-    L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kMaxRadix);
+    L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kTotalCopies * kMaxRadix);
     L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
     L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
     L.order = o;         o += align256(sizeof(u32) * (size_t)(tiles + 1));

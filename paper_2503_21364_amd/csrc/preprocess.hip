@@ -199,6 +199,15 @@ hipError_t launch_build_cov3d(const lmk_gs_gaussians &g, float *cov3d, hipStream
     return hipGetLastError();
 }
 
+__device__ __forceinline__ void reset_header(ScratchHeader *header)
+{
+    header->dup_count = 0;
+    header->status = LMK_GS_OK;
+    header->pad = 0;
+    header->big_count = 0;
+    header->giant_count = 0;
+}
+
 template <u32 DEG>
 __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     const float *__restrict__ mean, const float *__restrict__ scale, const float *__restrict__ rot,
@@ -207,10 +216,12 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
     float4 *__restrict__ feat, u32 *__restrict__ block_sums, u32 *__restrict__ tile_masks,
     const unsigned char *__restrict__ voxel_flags, const uint2 *__restrict__ block_range, u32 num_voxels,
-    unsigned char *__restrict__ block_visible)
+    unsigned char *__restrict__ block_visible, ScratchHeader *__restrict__ header)
 {
     __shared__ u32 s_part[kPreBlock / kWave];
     const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
+    // a new frame: D is accumulated by the scan that follows this kernel, the rest starts clean
+    if (blockIdx.x == 0 && threadIdx.x == 0) reset_header(header);
     if (voxel_flags) {
         // voxel filter: does any voxel holding one of this workgroup's primitives pass?
         const uint2 r = block_range[blockIdx.x];
@@ -471,54 +482,44 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     }
 }
 
-// Exclusive prefix sum (u64) over the workgroup tile counts; one workgroup.
-// Also publishes D and clears the status word.
-constexpr u32 kScanThreads = 1024;
-constexpr u32 kScanItems = 16;          // consecutive entries per thread, loaded together
-
-__global__ __launch_bounds__(kScanThreads) void scan_block_sums_kernel(
+// Exclusive prefix sum (u64) over the workgroup tile counts, in two levels: each workgroup of
+// this kernel scans kScanGroup consecutive counts (-> block_offsets, relative to the group) and
+// publishes the group's total; a consumer adds the totals of the groups before its own.  D is
+// the sum of the group totals, added to the header the preprocess kernel has just cleared.
+// (One workgroup scanning everything takes longer than the whole rest of this: its time is
+// the latency of one compute unit, not the data.)
+__global__ __launch_bounds__(kScanGroup) void scan_block_sums_kernel(
     const u32 *__restrict__ block_sums, u32 nb, u64 *__restrict__ block_offsets,
-    ScratchHeader *__restrict__ header)
+    u64 *__restrict__ group_totals, ScratchHeader *__restrict__ header)
 {
-    __shared__ u64 s_wave[kScanThreads / kWave];
-    __shared__ u64 s_carry;
+    constexpr u32 kWaves = kScanGroup / kWave;
+    __shared__ u64 s_wave[kWaves];
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    if (tid == 0) s_carry = 0;
-    __syncthreads();
-    for (u32 base = 0; base < nb; base += kScanThreads * kScanItems) {
-        const u32 first = base + tid * kScanItems;
-        u32 v[kScanItems];
-        u64 mine = 0;
-#pragma unroll
-        for (u32 k = 0; k < kScanItems; ++k) v[k] = first + k < nb ? block_sums[first + k] : 0u;
-#pragma unroll
-        for (u32 k = 0; k < kScanItems; ++k) mine += v[k];
-        u64 incl = mine;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const u64 t = __shfl_up(incl, o, 64);
-            if ((int)lane >= o) incl += t;
-        }
-        if (lane == kWave - 1) s_wave[wv] = incl;
-        __syncthreads();
-        u64 run = s_carry + incl - mine;
-        for (u32 k = 0; k < wv; ++k) run += s_wave[k];
-#pragma unroll
-        for (u32 k = 0; k < kScanItems; ++k) {
-            if (first + k < nb) block_offsets[first + k] = run;
-            run += v[k];
-        }
-        __syncthreads();
-        if (tid == kScanThreads - 1) s_carry = run;
-        __syncthreads();
+    if (nb == 0) {                             // no preprocess kernel ran: an empty frame
+        if (blockIdx.x == 0 && tid == 0) reset_header(header);
+        return;
     }
+    const u32 b = blockIdx.x * kScanGroup + tid;
+    const u32 x = b < nb ? block_sums[b] : 0u;
+    u64 incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const u64 t = __shfl_up(incl, o, 64);
+        if ((int)lane >= o) incl += t;
+    }
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    u64 before = 0, total = 0;
+#pragma unroll
+    for (u32 k = 0; k < kWaves; ++k) {
+        const u64 w = s_wave[k];
+        if (k < wv) before += w;
+        total += w;
+    }
+    if (b < nb) block_offsets[b] = before + incl - x;
     if (tid == 0) {
-        block_offsets[nb] = s_carry;
-        header->dup_count = s_carry;
-        header->status = LMK_GS_OK;
-        header->pad = 0;
-        header->big_count = 0;
-        header->giant_count = 0;
+        group_totals[blockIdx.x] = total;
+        if (total) atomicAdd(reinterpret_cast<unsigned long long *>(&header->dup_count), (unsigned long long)total);
     }
 }
 
@@ -550,7 +551,7 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
                                out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
                                reinterpret_cast<float4 *>(out.feat), block_sums,
                                reinterpret_cast<u32 *>(scratch + L.tile_masks),
-                               vflags, ranges, num_voxels, index ? block_visible : nullptr);
+                               vflags, ranges, num_voxels, index ? block_visible : nullptr, header);
         };
         switch (g.sh_degree) {
             case 0: launch(preprocess_kernel<0>); break;
@@ -561,8 +562,10 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(1), dim3(kScanThreads), 0, stream,
-                       block_sums, L.pre_blocks, block_offsets, header);
+    const u32 groups = L.pre_blocks ? (L.pre_blocks + kScanGroup - 1) / kScanGroup : 1u;
+    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(groups), dim3(kScanGroup), 0, stream,
+                       block_sums, L.pre_blocks, block_offsets,
+                       reinterpret_cast<u64 *>(scratch + L.group_totals), header);
     return hipGetLastError();
 }
 
