@@ -812,10 +812,16 @@ __global__ __launch_bounds__(256) void tile_ranges_kernel(
 
 // ---------------------------------------------------------------- order + size classes
 // Tile ids by descending list length, bucketed by the bit length of (length - 1), so that
-// the three size classes of the per-tile sort are whole buckets: more than kMid pairs
-// (front of `order`), kSmallCap + 1 .. kMid, and the rest.  Within a bucket the order is
-// whatever the atomics give -- it only decides which workgroup starts first, never a
-// result.  classes[0] / classes[1] = number of tiles in the first / second class.
+// the size classes of the per-tile sort are whole buckets.  From the front of `order`:
+//   classes[0]  lists longer than kHuge pairs          one workgroup each, merges between the pair buffers
+//   classes[3]  kMid + 1 .. kHuge ("long")             cut into chunks of kMid pairs, see below
+//   classes[1]  kLow + 1 .. kMid                       one workgroup of 512
+//   classes[2]  kSmallCap + 1 .. kLow                  one workgroup of 256
+//   the rest                                           one wavefront each
+// Within a bucket the order is whatever the atomics give -- it only decides which workgroup
+// starts first, never a result.  A long list is sorted as 2 .. 4 chunks by workgroups of the
+// 512-thread kernel and merged in two rounds by workgroups of the next two kernels, so that it
+// costs no kernel of its own: chunk_list = (tile, chunk) of every such chunk, classes[4] = how many.
 // One workgroup.
 constexpr u32 kSmallThreads = 64, kSmallItems = 8, kSmallCap = kSmallThreads * kSmallItems;   // 512
 constexpr u32 kLowThreads = 256, kLowItems = 8;                                               // 2048
@@ -827,7 +833,7 @@ __device__ __forceinline__ u32 length_bucket(u64 len)
 {
     return len > 1 ? 64u - (u32)__builtin_clzll(len - 1) : 0u;   // len in (2^(b-1), 2^b]
 }
-constexpr u32 kSmallBucket = 9, kLowBucket = 11, kMidBucket = 12;   // 2^9 = kSmallCap, 2^11 = kLow, 2^12 = kMid
+constexpr u32 kSmallBucket = 9, kLowBucket = 11, kMidBucket = 12, kHugeBucket = 14;   // 2^9 = kSmallCap, 2^11 = kLow, 2^12 = kMid, 2^14 = kHuge
 
 // Most tiles fall into a handful of buckets, and LDS atomics on one word are served one after
 // the other: every bucket has kOrderCopies counters, picked by the low lane bits, so that the 64
@@ -837,9 +843,10 @@ constexpr u32 kOrderCopies = 16, kOrderCounters = 65 * kOrderCopies, kOrderBatch
 
 __global__ __launch_bounds__(1024) void tile_order_kernel(
     const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order,
-    u32 *__restrict__ order_copy, u32 *__restrict__ classes)
+    u32 *__restrict__ order_copy, u32 *__restrict__ classes, uint2 *__restrict__ chunk_list, u64 chunk_capacity)
 {
     __shared__ u32 s_cnt[kOrderCounters];
+    __shared__ u32 s_long[2];                  // first long tile in `order`, number of long tiles
     __shared__ u32 s_wave[1024 / kWave];
     // slots are scattered and one compute unit does all the address work: the order is put
     // together in LDS and written out in whole lines (images of up to kOrderStage tiles)
@@ -881,10 +888,12 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
     __syncthreads();
     if (tid == 0) {
         // tiles in buckets above a class limit = first slot of the first bucket at or below it
-        const u32 huge = s_cnt[(64 - kMidBucket) * kOrderCopies];
+        const u32 huge = s_cnt[(64 - kHugeBucket) * kOrderCopies];
+        const u32 lng = s_cnt[(64 - kMidBucket) * kOrderCopies];
         const u32 mid = s_cnt[(64 - kLowBucket) * kOrderCopies];
         const u32 low = s_cnt[(64 - kSmallBucket) * kOrderCopies];
-        classes[0] = huge; classes[1] = mid - huge; classes[2] = low - mid;
+        classes[0] = huge; classes[3] = lng - huge; classes[1] = mid - lng; classes[2] = low - mid;
+        s_long[0] = huge; s_long[1] = lng - huge;
     }
     __syncthreads();
     for (u32 base = 0; base < num_tiles; base += kOrderBatch * 1024) {
@@ -914,7 +923,41 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
             order[k] = t;
             if (order_copy) order_copy[k] = t;
         }
+    } else {
+        __threadfence_block();                 // this workgroup reads its own writes of `order` below
+        __syncthreads();
     }
+    // the chunks of the long lists: an exclusive scan of their chunk counts places the entries
+    const u32 long_first = s_long[0], long_count = s_long[1];
+    u32 carry = 0;
+    for (u32 base = 0; base < long_count; base += 1024) {
+        const u32 k = base + tid;
+        u32 tile = 0, nch = 0;
+        if (k < long_count) {
+            tile = staged ? s_order[long_first + k] : order[long_first + k];
+            nch = (u32)((tile_offsets[tile + 1] - tile_offsets[tile] + kMid - 1) / kMid);
+        }
+        u32 incl = nch;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const u32 v = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += v;
+        }
+        __syncthreads();                       // s_wave free again
+        if (lane == kWave - 1) s_wave[wv] = incl;
+        __syncthreads();
+        u32 before = carry, total = carry;
+        for (u32 w = 0; w < 1024 / kWave; ++w) {
+            const u32 c = s_wave[w];
+            if (w < wv) before += c;
+            total += c;
+        }
+        const u32 at = before + incl - nch;
+        for (u32 c = 0; c < nch; ++c)
+            if ((u64)at + c < chunk_capacity) chunk_list[at + c] = make_uint2(tile, c);
+        carry = total;
+    }
+    if (tid == 0) classes[4] = (u64)carry < chunk_capacity ? carry : (u32)chunk_capacity;
 }
 
 // ---------------------------------------------------------------- per-tile sort
@@ -1023,46 +1066,7 @@ __device__ __forceinline__ void sort_pairs_in_lds(u64 *__restrict__ keys, u32 *_
     __syncthreads();                                        // s may be refilled by the caller
 }
 
-// short lists (2 .. 512 pairs): one wavefront each, walking `order` from its short end
-__global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
-    u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ tile_offsets,
-    const u32 *__restrict__ order, u32 num_tiles)
-{
-    __shared__ u64 s[kSmallCap + kSmallCap / 16];
-    if (blockIdx.x >= num_tiles) return;
-    const u32 tile = order[num_tiles - 1 - blockIdx.x];
-    if (tile >= num_tiles) return;
-    const u64 beg = tile_offsets[tile];
-    const u64 len = tile_offsets[tile + 1] - beg;
-    if (len < 2 || len > (u64)kSmallCap) return;
-    // fewer elements per lane for shorter lists: all 64 lanes work in every merge round
-    if (len <= 2u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 2u>(keys, vals, beg, (u32)len, tile, s);
-    else if (len <= 4u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 4u>(keys, vals, beg, (u32)len, tile, s);
-    else sort_pairs_in_lds<kSmallThreads, kSmallItems>(keys, vals, beg, (u32)len, tile, s);
-}
-
-// lists of 513 .. 2048 and 2049 .. 4096 pairs: one workgroup each; in `order` they follow the
-// long lists, the longer class first (CLASS = 1: 2049 .. 4096, CLASS = 2: 513 .. 2048)
-template <u32 THREADS, u32 ITEMS, u32 CLASS>
-__global__ __launch_bounds__(THREADS) void tile_sort_class_kernel(
-    u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ tile_offsets,
-    const u32 *__restrict__ order, const u32 *__restrict__ classes, u32 num_tiles)
-{
-    constexpr u32 CAP = THREADS * ITEMS;
-    __shared__ u64 s[CAP + CAP / 16];
-    u32 first = classes[0];
-    if (CLASS == 2) first += classes[1];
-    const u32 count = classes[CLASS];
-    if (blockIdx.x >= count || first + blockIdx.x >= num_tiles) return;
-    const u32 tile = order[first + blockIdx.x];
-    if (tile >= num_tiles) return;
-    const u64 beg = tile_offsets[tile];
-    const u64 len = tile_offsets[tile + 1] - beg;
-    if (len < 2 || len > (u64)CAP) return;                  // cannot happen with a consistent table
-    sort_pairs_in_lds<THREADS, ITEMS>(keys, vals, beg, (u32)len, tile, s);
-}
-
-// ---------------------------------------------------------------- long lists
+// ---------------------------------------------------------------- merges between the pair buffers
 __device__ __forceinline__ bool pair_less(u64 ka, u32 va, u64 kb, u32 vb)
 {
     return ka < kb || (ka == kb && va < vb);
@@ -1093,12 +1097,170 @@ __device__ __forceinline__ u64 wave_merge_split(const u64 *__restrict__ sk, cons
     return lo;
 }
 
-// One workgroup of 1024 threads per tile whose list is longer than kMid pairs (the front of
-// `order`): chunks of up to kHuge pairs are sorted in LDS; a list longer than that is then
-// merged pairwise (run length doubling) between the two pair buffers, kHuge outputs at a
-// time: sixteen wavefronts find the splits of sixteen output segments, then each segment's
-// two input windows are staged in LDS, merged there and written out coalesced.  The result
-// ends in keys/vals.
+// One output segment of THREADS * ITEMS pairs of a merge round over the sorted runs of length
+// `run` of one tile's list (L pairs at sk/sv, result to dk/dv): two wavefronts find where the
+// segment starts and ends in its pair of runs, the two input windows are staged in LDS as
+// composites, merged there and written out coalesced.  A run without a partner is copied.
+// Called by the whole workgroup; `s` holds THREADS * ITEMS composites (padded), s_split two words.
+template <u32 THREADS, u32 ITEMS>
+__device__ __forceinline__ void merge_segment(const u64 *__restrict__ sk, const u32 *__restrict__ sv,
+                                              u64 *__restrict__ dk, u32 *__restrict__ dv,
+                                              u64 L, u64 run, u64 seg, u32 tile, u64 *s, u64 *s_split)
+{
+    constexpr u32 CAP = THREADS * ITEMS;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u64 o = seg * CAP;
+    if (o >= L) return;                                     // the same for the whole workgroup
+    const u64 a0 = (o / (2 * run)) * (2 * run);
+    const u64 a1 = a0 + run < L ? a0 + run : L;
+    const u64 b1 = a0 + 2 * run < L ? a0 + 2 * run : L;
+    const u64 oe = o + CAP < b1 ? o + CAP : b1;
+    if (wv == 0) {
+        const u64 i0 = wave_merge_split(sk, sv, a0, a1, b1, o - a0, lane);
+        if (lane == 0) s_split[0] = i0;
+    }
+    if (wv == (THREADS > kWave ? 1u : 0u)) {
+        const u64 i1 = wave_merge_split(sk, sv, a0, a1, b1, oe - a0, lane);
+        if (lane == 0) s_split[1] = i1;
+    }
+    __syncthreads();
+    const u64 i0 = s_split[0], i1 = s_split[1];
+    const u64 j0 = (o - a0) - i0;                           // elements of B before the segment
+    const u32 la = (u32)(i1 - i0), total = (u32)(oe - o);
+    for (u32 p = tid; p < total; p += THREADS) {
+        const u64 src = p < la ? a0 + i0 + p : a1 + j0 + (p - la);
+        s[ts_slot(p)] = (sk[src] << 32) | (u64)sv[src];
+    }
+    __syncthreads();
+    const u32 o0 = tid * ITEMS;
+    u64 e[ITEMS];
+    if (o0 < total) merge_from_lds<ITEMS>(s, 0u, la, total, o0, e);
+    __syncthreads();
+    if (o0 < total) {
+#pragma unroll
+        for (u32 k = 0; k < ITEMS; ++k)
+            if (o0 + k < total) s[ts_slot(o0 + k)] = e[k];
+    }
+    __syncthreads();
+    const u64 hi_bits = (u64)tile << 32;
+    for (u32 p = tid; p < total; p += THREADS) {
+        const u64 c = s[ts_slot(p)];
+        dk[o + p] = hi_bits | (c >> 32);
+        dv[o + p] = (u32)c;
+    }
+    __syncthreads();                                        // s and s_split may be reused by the caller
+}
+
+// Lists of kLow + 1 .. kMid pairs, one workgroup each, and before them the chunks of the long
+// lists (kMid + 1 .. kHuge pairs), which are sorted in place like a list of their own.
+// Both count for more than kLow pairs each, which bounds the grid.
+__global__ __launch_bounds__(kMidThreads) void tile_sort_mid_kernel(
+    u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ tile_offsets,
+    const u32 *__restrict__ order, const u32 *__restrict__ classes, const uint2 *__restrict__ chunk_list,
+    u32 num_tiles)
+{
+    __shared__ u64 s[kMid + kMid / 16];
+    const u32 chunks = classes[4];
+    if (blockIdx.x < chunks) {
+        const uint2 c = chunk_list[blockIdx.x];
+        if (c.x >= num_tiles) return;
+        const u64 beg = tile_offsets[c.x];
+        const u64 len = tile_offsets[c.x + 1] - beg;
+        const u64 c0 = (u64)c.y * kMid;
+        if (c0 >= len) return;                              // cannot happen with a consistent table
+        const u32 n = (u32)(len - c0 < (u64)kMid ? len - c0 : (u64)kMid);
+        if (n >= 2) sort_pairs_in_lds<kMidThreads, kMidItems>(keys, vals, beg + c0, n, c.x, s);
+        return;
+    }
+    const u32 k = blockIdx.x - chunks;
+    const u32 first = classes[0] + classes[3];
+    if (k >= classes[1] || first + k >= num_tiles) return;
+    const u32 tile = order[first + k];
+    if (tile >= num_tiles) return;
+    const u64 beg = tile_offsets[tile];
+    const u64 len = tile_offsets[tile + 1] - beg;
+    if (len < 2 || len > (u64)kMid) return;                 // cannot happen with a consistent table
+    sort_pairs_in_lds<kMidThreads, kMidItems>(keys, vals, beg, (u32)len, tile, s);
+}
+
+// Lists of kSmallCap + 1 .. kLow pairs, one workgroup each, and before them the first merge round
+// of the long lists (runs of kMid pairs, pair buffers -> alternate buffers), kLow outputs per
+// workgroup: a fixed number of workgroups walks the segments.
+constexpr u32 kMergeBlocks1 = 1024, kMergeBlocks2 = 2048;
+__global__ __launch_bounds__(kLowThreads) void tile_sort_low_kernel(
+    u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ keys_alt, u32 *__restrict__ vals_alt,
+    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, const u32 *__restrict__ classes,
+    const uint2 *__restrict__ chunk_list, u32 num_tiles, u32 merge_blocks)
+{
+    constexpr u32 CAP = kLowThreads * kLowItems;
+    constexpr u32 kPerChunk = kMid / CAP;                   // output segments per chunk
+    __shared__ u64 s[CAP + CAP / 16];
+    __shared__ u64 s_split[2];
+    if (blockIdx.x < merge_blocks) {
+        const u64 segments = (u64)classes[4] * kPerChunk;
+        for (u64 g = blockIdx.x; g < segments; g += merge_blocks) {
+            const uint2 c = chunk_list[g / kPerChunk];
+            if (c.x >= num_tiles) continue;
+            const u64 beg = tile_offsets[c.x];
+            const u64 len = tile_offsets[c.x + 1] - beg;
+            merge_segment<kLowThreads, kLowItems>(keys + beg, vals + beg, keys_alt + beg, vals_alt + beg, len,
+                                                  (u64)kMid, (u64)c.y * kPerChunk + g % kPerChunk, c.x, s, s_split);
+        }
+        return;
+    }
+    const u32 k = blockIdx.x - merge_blocks;
+    const u32 first = classes[0] + classes[3] + classes[1];
+    if (k >= classes[2] || first + k >= num_tiles) return;
+    const u32 tile = order[first + k];
+    if (tile >= num_tiles) return;
+    const u64 beg = tile_offsets[tile];
+    const u64 len = tile_offsets[tile + 1] - beg;
+    if (len < 2 || len > (u64)CAP) return;                  // cannot happen with a consistent table
+    sort_pairs_in_lds<kLowThreads, kLowItems>(keys, vals, beg, (u32)len, tile, s);
+}
+
+// Short lists (2 .. 512 pairs): one wavefront each, walking `order` from its short end.  Before
+// them the second and last merge round of the long lists (runs of 2 * kMid pairs, alternate
+// buffers -> pair buffers; a list of one such run is copied), kSmallCap outputs per segment.
+__global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
+    u64 *__restrict__ keys, u32 *__restrict__ vals, const u64 *__restrict__ keys_alt, const u32 *__restrict__ vals_alt,
+    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, const u32 *__restrict__ classes,
+    const uint2 *__restrict__ chunk_list, u32 num_tiles, u32 merge_blocks)
+{
+    constexpr u32 kPerChunk = kMid / kSmallCap;
+    __shared__ u64 s[kSmallCap + kSmallCap / 16];
+    __shared__ u64 s_split[2];
+    if (blockIdx.x < merge_blocks) {
+        const u64 segments = (u64)classes[4] * kPerChunk;
+        for (u64 g = blockIdx.x; g < segments; g += merge_blocks) {
+            const uint2 c = chunk_list[g / kPerChunk];
+            if (c.x >= num_tiles) continue;
+            const u64 beg = tile_offsets[c.x];
+            const u64 len = tile_offsets[c.x + 1] - beg;
+            merge_segment<kSmallThreads, kSmallItems>(keys_alt + beg, vals_alt + beg, keys + beg, vals + beg, len,
+                                                      2 * (u64)kMid, (u64)c.y * kPerChunk + g % kPerChunk, c.x, s, s_split);
+        }
+        return;
+    }
+    const u32 k = blockIdx.x - merge_blocks;
+    if (k >= num_tiles) return;
+    const u32 tile = order[num_tiles - 1 - k];
+    if (tile >= num_tiles) return;
+    const u64 beg = tile_offsets[tile];
+    const u64 len = tile_offsets[tile + 1] - beg;
+    if (len < 2 || len > (u64)kSmallCap) return;
+    // fewer elements per lane for shorter lists: all 64 lanes work in every merge round
+    if (len <= 2u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 2u>(keys, vals, beg, (u32)len, tile, s);
+    else if (len <= 4u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 4u>(keys, vals, beg, (u32)len, tile, s);
+    else sort_pairs_in_lds<kSmallThreads, kSmallItems>(keys, vals, beg, (u32)len, tile, s);
+}
+
+// ---------------------------------------------------------------- lists beyond kHuge pairs
+// One workgroup of 1024 threads per tile whose list is longer than kHuge pairs (the front of
+// `order`): chunks of kHuge pairs are sorted in LDS, then merged pairwise (run length
+// doubling) between the two pair buffers, kHuge outputs at a time: sixteen wavefronts find the
+// splits of sixteen output segments, then each segment's two input windows are staged in
+// LDS, merged there and written out coalesced.  The result ends in keys/vals.
 __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
     u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ keys_alt, u32 *__restrict__ vals_alt,
     const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, const u32 *__restrict__ classes,
@@ -1111,7 +1273,7 @@ __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
     if (tile >= num_tiles) return;
     const u64 beg = tile_offsets[tile];
     const u64 L = tile_offsets[tile + 1] - beg;
-    if (L <= (u64)kMid) return;                             // cannot happen with a consistent table
+    if (L <= (u64)kHuge) return;                            // cannot happen with a consistent table
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     constexpr u32 kWaves = kHugeThreads / kWave;
 
@@ -1119,7 +1281,6 @@ __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
         const u32 n = (u32)(L - c0 < (u64)kHuge ? L - c0 : (u64)kHuge);
         if (n >= 2) sort_pairs_in_lds<kHugeThreads, kHugeItems>(keys, vals, beg + c0, n, tile, s);
     }
-    if (L <= (u64)kHuge) return;
     // the chunk sorts of this workgroup wrote the runs the merges read
     __threadfence_block();
     __syncthreads();
@@ -1269,23 +1430,31 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     hipLaunchKernelGGL(tile_ranges_kernel, dim3(rgrid), dim3(256), 0, stream,
                        out.keys, header, out.capacity, num_tiles, out.tile_offsets,
                        n == 0 ? proj.offsets : nullptr);
+    uint2 *chunk_list = reinterpret_cast<uint2 *>(scratch + L.chunk_list);
     hipLaunchKernelGGL(tile_order_kernel, dim3(1), dim3(1024), 0, stream,
-                       out.tile_offsets, num_tiles, order, out.tile_order, classes);
+                       out.tile_offsets, num_tiles, order, out.tile_order, classes, chunk_list,
+                       out.capacity / 2048 + 2);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // the long lists first (few workgroups that run long), then the mid-sized, then the rest;
-    // the grids are upper bounds from the capacity, surplus workgroups leave at once
-    const u64 max_huge = out.capacity / (kChunk + 1) + 1 < (u64)num_tiles ? out.capacity / (kChunk + 1) + 1 : (u64)num_tiles;
-    const u64 max_mid = out.capacity / 2049 + 1 < (u64)num_tiles ? out.capacity / 2049 + 1 : (u64)num_tiles;
-    const u64 max_low = out.capacity / 513 + 1 < (u64)num_tiles ? out.capacity / 513 + 1 : (u64)num_tiles;
-    hipLaunchKernelGGL(tile_sort_huge_kernel, dim3((u32)max_huge), dim3(1024), 0, stream,
+    // The lists beyond kHuge pairs first (few workgroups that run long), then by falling length.
+    // The grids are upper bounds from the capacity, surplus workgroups leave at once: a list of
+    // the class above kHuge / kLow / kSmallCap pairs, and likewise every chunk of a long list,
+    // counts for more than that many pairs.
+    auto at_most = [](u64 a, u64 b) { return (u32)(a < b ? a : b); };
+    const u32 max_huge = at_most(out.capacity / (kHuge + 1) + 1, num_tiles);
+    const u32 max_mid = at_most(out.capacity / (kLowThreads * kLowItems + 1) + 1, 4ull * num_tiles);
+    const u32 max_low = at_most(out.capacity / (kSmallCap + 1) + 1, num_tiles);
+    const u32 merge1 = at_most(2ull * max_mid, kMergeBlocks1), merge2 = at_most(8ull * max_mid, kMergeBlocks2);
+    hipLaunchKernelGGL(tile_sort_huge_kernel, dim3(max_huge), dim3(kHugeThreads), 0, stream,
                        out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes, num_tiles);
-    hipLaunchKernelGGL((tile_sort_class_kernel<kMidThreads, kMidItems, 1>), dim3((u32)max_mid), dim3(kMidThreads), 0, stream,
-                       out.keys, out.vals, out.tile_offsets, order, classes, num_tiles);
-    hipLaunchKernelGGL((tile_sort_class_kernel<kLowThreads, kLowItems, 2>), dim3((u32)max_low), dim3(kLowThreads), 0, stream,
-                       out.keys, out.vals, out.tile_offsets, order, classes, num_tiles);
-    hipLaunchKernelGGL(tile_sort_small_kernel, dim3(num_tiles), dim3(kSmallThreads), 0, stream,
-                       out.keys, out.vals, out.tile_offsets, order, num_tiles);
+    hipLaunchKernelGGL(tile_sort_mid_kernel, dim3(max_mid), dim3(kMidThreads), 0, stream,
+                       out.keys, out.vals, out.tile_offsets, order, classes, chunk_list, num_tiles);
+    hipLaunchKernelGGL(tile_sort_low_kernel, dim3(merge1 + max_low), dim3(kLowThreads), 0, stream,
+                       out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes,
+                       chunk_list, num_tiles, merge1);
+    hipLaunchKernelGGL(tile_sort_small_kernel, dim3(merge2 + num_tiles), dim3(kSmallThreads), 0, stream,
+                       out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes,
+                       chunk_list, num_tiles, merge2);
     return hipGetLastError();
 }
 

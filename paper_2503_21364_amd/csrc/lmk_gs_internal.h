@@ -44,7 +44,8 @@ struct ScratchLayout {
     size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
     size_t offsets;       // u64 [512][sort_tiles] their output offsets
     size_t order;         // u32 [tiles]     tile ids by descending list length
-    size_t classes;       // u32 [4]         tiles with lists longer than kHugeMin / kMidMin pairs (front of `order`)
+    size_t classes;       // u32 [8]         tiles per size class of the per-tile sort (see tile_order_kernel)
+    size_t chunk_list;    // uint2 [capacity / 2048 + 2]  (tile, chunk) of every chunk of the lists sorted in chunks
     size_t big_idx;       // u32 [n]         primitives whose rectangles are expanded one wavefront each
     size_t big_off;       // u64 [n]         and where their pairs start
     size_t total;
@@ -71,7 +72,8 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
     L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
     L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
     L.order = o;         o += align256(sizeof(u32) * (size_t)(tiles + 1));
-    L.classes = o;       o += align256(sizeof(u32) * 4);
+    L.classes = o;       o += align256(sizeof(u32) * 8);
+    L.chunk_list = o;    o += align256(sizeof(u32) * 2 * (size_t)(capacity / 2048 + 2));
     L.big_idx = o;       o += align256(sizeof(u32) * ((size_t)n + 1));
     L.big_off = o;       o += align256(sizeof(u64) * ((size_t)n + 1));
     L.total = o;

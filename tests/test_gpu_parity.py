@@ -83,19 +83,22 @@ def test_cfg4_distributions_reduced_count():
     assert r.stats["D"] / r.stats["visible"] > 300   # hundreds of tiles per primitive
 
 
-@pytest.mark.parametrize("w,h,n,seed,binning", [
-    (64, 64, 100_000, 41, 0),       # 16 tiles, lists of several thousand pairs: one long chunk each
-    (48, 40, 150_000, 42, 0),       # 9 tiles (ragged), lists beyond one long chunk: merges between the buffers
-    (48, 40, 150_000, 43, 1),
-    (16, 16, 70_001, 44, 0),        # everything in one tile: several merge rounds, ragged last run
+@pytest.mark.parametrize("w,h,n,seed,binning,lo,hi", [
+    (64, 64, 20_000, 41, 0, 4096, 8192),         # the four central tiles hold lists of two chunks: one merge round, then a copy
+    (64, 64, 30_000, 45, 1, 8192, 12288),        # three chunks: a run without a partner in the first round
+    (64, 64, 42_000, 46, 0, 12288, 16384),       # four chunks (ragged last one): both merge rounds
+    (64, 64, 100_000, 47, 0, 16384, 1 << 30),    # beyond kHuge next to mid-sized lists
+    (48, 40, 150_000, 42, 0, 16384, 1 << 30),    # 9 tiles (ragged), lists beyond kHuge: merges inside one workgroup
+    (48, 40, 150_000, 43, 1, 16384, 1 << 30),
+    (16, 16, 70_001, 44, 0, 16384, 1 << 30),     # everything in one tile: several merge rounds, ragged last run
 ])
-def test_long_lists_in_few_tiles(w, h, n, seed, binning):
+def test_long_lists_in_few_tiles(w, h, n, seed, binning, lo, hi):
     sc = scenes.make_scene(0, n=n, seed=seed)
     cam = dict(scenes.make_cameras(0, w, h)[0], binning=binning)
     r = P.full_compare(sc, cam)
     _report(f"long lists {w}x{h} n={n} binning {binning}", r.stats)
     lens = np.diff(r.oracle.binned.tile_offsets.astype(np.int64))
-    assert lens.max() > (16384 if n > 100_000 or w == 16 else 4096)
+    assert lo < lens.max() <= hi, lens.max()
 
 
 @pytest.mark.parametrize("binning", [0, 1])
