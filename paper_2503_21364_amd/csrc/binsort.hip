@@ -42,12 +42,12 @@ __device__ __forceinline__ u64 load_D(const ScratchHeader *h, u64 capacity)
 }
 
 // ---------------------------------------------------------------- emit
-// Primitives whose rectangle has more than kBigArea tiles are not expanded by their own
-// workgroup: with a spatially ordered scene the close-up primitives, hundreds of tiles each,
-// sit in a few workgroups, which would then run many times longer than the rest.  Their index
-// and output offset go to a list (one atomic per wavefront) that emit_deferred_kernel expands, one
-// wavefront per primitive (one workgroup per primitive beyond kGiantArea tiles, from the back of
-// the same list), with the same output positions.
+// Primitives whose rectangle has more than kBigArea tiles (binning rule 0; kMaskArea under
+// rule 1) are not expanded by their own workgroup: with a spatially ordered scene the close-up
+// primitives, tens to hundreds of tiles each, sit in a few workgroups, which would then run many
+// times longer than the rest.  Their index and output offset go to a list (one atomic per
+// wavefront) that emit_deferred_kernel expands, one wavefront per primitive (one workgroup per
+// primitive beyond kGiantArea tiles, from the back of the same list), with the same output positions.
 constexpr u32 kBigArea = 128;
 constexpr u32 kMaskArea = 32;       // rectangles whose kept tiles the preprocess kernel recorded as a bit mask
 constexpr u32 kGiantArea = 2048;
@@ -71,10 +71,10 @@ __device__ __forceinline__ void append_deferred(bool want, u32 *counter, bool fr
     }
 }
 
-__device__ __forceinline__ void append_big(u32 area, u32 i, u64 offset, ScratchHeader *header,
+__device__ __forceinline__ void append_big(u32 area, u32 own_limit, u32 i, u64 offset, ScratchHeader *header,
                                            u32 *__restrict__ big_idx, u64 *__restrict__ big_off, u32 lane, u32 n)
 {
-    append_deferred(area > kBigArea && area <= kGiantArea, &header->big_count, false, i, offset, big_idx, big_off, lane, n);
+    append_deferred(area > own_limit && area <= kGiantArea, &header->big_count, false, i, offset, big_idx, big_off, lane, n);
     append_deferred(area > kGiantArea, &header->giant_count, true, i, offset, big_idx, big_off, lane, n);
 }
 
@@ -99,9 +99,33 @@ __device__ __forceinline__ u64 block_base_finish(const u64 *__restrict__ block_o
     return base;
 }
 
+// What every workgroup of the emit grid does first.  Returns true when the preprocess kernel
+// counted no pair for this workgroup (culled, or a skipped voxel range): then it is done here,
+// without reading a primitive.
+__device__ __forceinline__ bool emit_prologue(const u32 *__restrict__ block_sums, const u64 *__restrict__ block_offsets,
+                                              const u64 *__restrict__ group_totals, u32 n, u64 capacity,
+                                              u64 *__restrict__ offsets, ScratchHeader *__restrict__ header,
+                                              u64 *__restrict__ digit_totals, u64 *s_gpart, u32 tid, u32 lane, u32 wv)
+{
+    if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
+    // the partition's digit totals are accumulated with atomics: start from zero
+    for (u32 k = blockIdx.x * kPreBlock + tid; k < kMaxPasses * kTotalCopies * kMaxRadix; k += gridDim.x * kPreBlock)
+        digit_totals[k] = 0;
+    if (block_sums[blockIdx.x] != 0) return false;
+    if (offsets) {
+        block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);
+        __syncthreads();
+        const u64 base = block_base_finish(block_offsets, blockIdx.x, s_gpart);
+        const u32 i = blockIdx.x * kPreBlock + tid;
+        if (i < n) offsets[i] = base;
+        if (i == n - 1) offsets[n] = base;
+    }
+    return true;
+}
+
 __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
-    const float *__restrict__ depth, const u64 *__restrict__ block_offsets,
+    const float *__restrict__ depth, const u32 *__restrict__ block_sums, const u64 *__restrict__ block_offsets,
     const u64 *__restrict__ group_totals, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
     ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
@@ -117,6 +141,9 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 i = blockIdx.x * kPreBlock + tid;
+    if (emit_prologue(block_sums, block_offsets, group_totals, n, capacity, offsets, header, digit_totals,
+                      s_gpart, tid, lane, wv))
+        return;
     block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);     // summed after the barrier below
     const u32 cnt = i < n ? tiles_touched[i] : 0u;
     const bool big = cnt > kBigArea;
@@ -148,11 +175,7 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
         if (i < n) offsets[i] = base + off;
         if (i == n - 1) offsets[n] = base + total2;
     }
-    if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
-    // the partition's digit totals are accumulated with atomics: start from zero
-    for (u32 k = blockIdx.x * kPreBlock + tid; k < kMaxPasses * kTotalCopies * kMaxRadix; k += gridDim.x * kPreBlock)
-        digit_totals[k] = 0;
-    append_big(cnt, i, base + off, header, big_idx, big_off, lane, n);
+    append_big(cnt, kBigArea, i, base + off, header, big_idx, big_off, lane, n);
     __syncthreads();
 
     for (u32 j = tid; j < total; j += kPreBlock) {
@@ -182,14 +205,15 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
 // through the splat/tile intersection test and the kept ones are compacted with ballot ranks,
 // so the pairs land exactly where the prefix sums say.
 // ---------------------------------------------------------------- emit, binning rule 1
-// Same expansion over the slots of every support rectangle, but each slot is first put
-// through the splat/tile intersection test of lmk_gs_camera.binning == 1 (identical
-// arithmetic to the count in the preprocess kernel; this translation unit is compiled
-// without floating-point contraction for that reason) and the kept slots are compacted:
-// the output position of a kept slot is the workgroup's base plus the number of kept
-// slots before it, so pairs still come out in (primitive, row-major tile) order.
-struct EmitTest { float u, v, A, B, C, rx, ry, tau; };
-
+// Only the tiles that pass the splat/tile intersection test of lmk_gs_camera.binning == 1 get a
+// pair, in (primitive, row-major tile) order: the output position of a kept tile is the
+// workgroup's base plus the number of kept tiles before it.  For a rectangle of up to
+// kMaskArea tiles (nearly all primitives) the preprocess kernel left the kept tiles as a bit
+// mask, which the primitive's own thread walks: no test, no feature record.  Larger rectangles
+// go to emit_deferred_kernel, which repeats the test per tile (identical arithmetic to the
+// count in the preprocess kernel; this translation unit is compiled without floating-point
+// contraction for that reason).  Expanding them here, slot by slot across the workgroup, made
+// the workgroups that hold the close-up primitives of a spatially ordered scene the long pole.
 __device__ __forceinline__ float emit_clampf(float v, float lo, float hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 __device__ __forceinline__ float emit_quad_adj(float A, float B, float C, float ex, float ey)
@@ -201,159 +225,68 @@ __device__ __forceinline__ float emit_quad_adj(float A, float B, float C, float 
 
 __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
-    const float *__restrict__ depth, const float4 *__restrict__ feat, ProjParams pp,
-    const u64 *__restrict__ block_offsets, const u64 *__restrict__ group_totals, u32 n, u32 tiles_x,
+    const float *__restrict__ depth,
+    const u32 *__restrict__ block_sums, const u64 *__restrict__ block_offsets,
+    const u64 *__restrict__ group_totals, u32 n, u32 tiles_x,
     u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
     ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
     u64 *__restrict__ digit_totals, const u32 *__restrict__ tile_masks)
 {
     __shared__ u64 s_gpart[kPreBlock / kWave];
-    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of the rectangle areas expanded slot by slot
-    __shared__ u32 s_bigpre[kPreBlock];   // pairs of primitives expanded elsewhere (masked, deferred) that precede each primitive
-    __shared__ ushort4 s_rect[kPreBlock];
-    __shared__ u32 s_depth[kPreBlock];
-    __shared__ float4 s_t0[kPreBlock];    // u, v, A, B
-    __shared__ float4 s_t1[kPreBlock];    // C, rx, ry, tau
     __shared__ u32 s_wave[kPreBlock / kWave];
-    __shared__ u32 s_wave2[kPreBlock / kWave];
-    __shared__ u32 s_wave3[kPreBlock / kWave];
 
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 i = blockIdx.x * kPreBlock + tid;
+    if (emit_prologue(block_sums, block_offsets, group_totals, n, capacity, offsets, header, digit_totals,
+                      s_gpart, tid, lane, wv))
+        return;
     block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);     // summed after the barrier below
     const u32 kept_cnt = i < n ? tiles_touched[i] : 0u;
-    // Three ways to expand a primitive's kept tiles, by the size of its rectangle:
-    //   up to kMaskArea tiles  its own thread walks the bit mask the preprocess kernel left
-    //                          (most primitives; no test, no feature record, no LDS search)
-    //   up to kBigArea         slot by slot across the workgroup, test repeated per slot
-    //   beyond                 deferred to emit_deferred_kernel
-    u32 area = 0, full_area = 0, mask = 0, dbits = 0;
+    u32 area = 0, mask = 0, dbits = 0;
     ushort4 r = make_ushort4(0, 0, 0, 0);
-    bool big = false, masked = false;
     if (kept_cnt) {
         r = rect[i];
-        s_rect[tid] = r;
         area = ((u32)r.z - (u32)r.x) * ((u32)r.w - (u32)r.y);
-        big = area > kBigArea;
-        masked = area <= kMaskArea;
-        full_area = area;
         dbits = __float_as_uint(depth[i]);
-        s_depth[tid] = dbits;
-        if (masked) {
-            mask = tile_masks[i];
-            area = 0;
-        } else if (big) {
-            area = 0;
-        } else {
-            const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
-            const float4 f0 = f[0], f1 = f[1];
-            const u32 bits = __float_as_uint(f1.y);
-            const int E = (int)((bits >> 23) & 0xffu) - 127;
-            const float tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
-            s_t0[tid] = f0;
-            s_t1[tid] = make_float4(f1.x, -f0.w / f0.z, -f0.w / f1.x, tau);
-        }
+        if (area <= kMaskArea) mask = tile_masks[i];
     }
-    // prefix sums over the workgroup: rectangle areas (slot ownership) and kept counts (offsets[])
-    const u32 big_cnt = (big || masked) ? kept_cnt : 0u;
-    u32 incl = area, incl2 = kept_cnt, incl3 = big_cnt;
+    // prefix sum of the kept counts over the workgroup: where every primitive's pairs start
+    u32 incl = kept_cnt;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-        const u32 t = __shfl_up(incl, o, 64), t2 = __shfl_up(incl2, o, 64), t3 = __shfl_up(incl3, o, 64);
-        if ((int)lane >= o) { incl += t; incl2 += t2; incl3 += t3; }
+        const u32 t = __shfl_up(incl, o, 64);
+        if ((int)lane >= o) incl += t;
     }
-    if (lane == kWave - 1) { s_wave[wv] = incl; s_wave2[wv] = incl2; s_wave3[wv] = incl3; }
+    if (lane == kWave - 1) s_wave[wv] = incl;
     __syncthreads();
-    u32 wave_base = 0, total = 0, wave_base2 = 0, total2 = 0, wave_base3 = 0;
+    u32 wave_base = 0, total = 0;
 #pragma unroll
     for (u32 k = 0; k < kPreBlock / kWave; ++k) {
-        const u32 w = s_wave[k], w2 = s_wave2[k], w3 = s_wave3[k];
-        if (k < wv) { wave_base += w; wave_base2 += w2; wave_base3 += w3; }
-        total += w; total2 += w2;
+        const u32 w = s_wave[k];
+        if (k < wv) wave_base += w;
+        total += w;
     }
-    s_excl[tid] = wave_base + incl - area;
-    const u32 kept_excl = wave_base2 + incl2 - kept_cnt;
-    s_bigpre[tid] = wave_base3 + incl3 - big_cnt;
+    const u32 kept_excl = wave_base + incl - kept_cnt;
     const u64 base = block_base_finish(block_offsets, blockIdx.x, s_gpart);
     if (offsets) {
         if (i < n) offsets[i] = base + kept_excl;
-        if (i == n - 1) offsets[n] = base + total2;
+        if (i == n - 1) offsets[n] = base + total;
     }
-    if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
-    // the partition's digit totals are accumulated with atomics: start from zero
-    for (u32 k = blockIdx.x * kPreBlock + tid; k < kMaxPasses * kTotalCopies * kMaxRadix; k += gridDim.x * kPreBlock)
-        digit_totals[k] = 0;
-    append_big(full_area, i, base + kept_excl, header, big_idx, big_off, lane, n);
-    if (masked) {
-        // kept tiles in row-major order = set bits in ascending order
-        const u32 w = (u32)r.z - (u32)r.x;
-        const u32 inv_w = (65536u + w - 1u) / w;           // slot / w == (slot * inv_w) >> 16 for slot < 32, w <= 32
-        u64 pos = base + kept_excl;
-        while (mask) {
-            const u32 slot = (u32)__builtin_ctz(mask);
-            mask &= mask - 1u;
-            const u32 row = (slot * inv_w) >> 16;
-            const u32 tx = (u32)r.x + (slot - row * w), ty = (u32)r.y + row;
-            if (pos < capacity) {
-                keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
-                vals[pos] = i;
-            }
-            ++pos;
+    append_big(area, kMaskArea, i, base + kept_excl, header, big_idx, big_off, lane, n);
+    // kept tiles in row-major order = set bits in ascending order
+    const u32 w = (u32)r.z - (u32)r.x;
+    const u32 inv_w = w ? (65536u + w - 1u) / w : 0u;      // slot / w == (slot * inv_w) >> 16 for slot < 32, w <= 32
+    u64 pos = base + kept_excl;
+    while (mask) {
+        const u32 slot = (u32)__builtin_ctz(mask);
+        mask &= mask - 1u;
+        const u32 row = (slot * inv_w) >> 16;
+        const u32 tx = (u32)r.x + (slot - row * w), ty = (u32)r.y + row;
+        if (pos < capacity) {
+            keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
+            vals[pos] = i;
         }
-    }
-    __syncthreads();
-
-    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
-    u32 running = 0;                                       // kept slots of earlier rounds (uniform)
-    for (u32 j0 = 0; j0 < total; j0 += kPreBlock) {
-        const u32 j = j0 + tid;
-        bool keep = false;
-        u32 lo = 0, tile = 0;
-        if (j < total) {
-            u32 hi = kPreBlock - 1;
-            while (lo < hi) {
-                const u32 mid = (lo + hi + 1) >> 1;
-                if (s_excl[mid] <= j) lo = mid; else hi = mid - 1;
-            }
-            const ushort4 r = s_rect[lo];
-            const u32 local = j - s_excl[lo];
-            const u32 w = (u32)r.z - (u32)r.x;
-            const u32 row = local / w;
-            const u32 tx = (u32)r.x + (local - row * w);
-            const u32 ty = (u32)r.y + row;
-            tile = ty * tiles_x + tx;
-            const float4 t0 = s_t0[lo], t1 = s_t1[lo];
-            const float xs = t0.x - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-            const float ys = t0.y - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-            const float ex1 = emit_clampf(xs, -h, h) - xs;
-            const float ey1 = emit_clampf(ys + t1.z * ex1, -h, h) - ys;
-            const float ey2 = emit_clampf(ys, -h, h) - ys;
-            const float ex2 = emit_clampf(xs + t1.y * ey2, -h, h) - xs;
-            const float q1 = emit_quad_adj(t0.z, t0.w, t1.x, ex1, ey1);
-            const float q2 = emit_quad_adj(t0.z, t0.w, t1.x, ex2, ey2);
-            const float qmin = q1 < q2 ? q1 : q2;
-            keep = qmin <= t1.w;
-        }
-        const u64 mask = __builtin_amdgcn_ballot_w64(keep);
-        const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
-        __syncthreads();                                   // s_wave free again
-        if (lane == 0) s_wave[wv] = (u32)__builtin_popcountll(mask);
-        __syncthreads();
-        u32 before = 0, round_total = 0;
-#pragma unroll
-        for (u32 k = 0; k < kPreBlock / kWave; ++k) {
-            const u32 c = s_wave[k];
-            if (k < wv) before += c;
-            round_total += c;
-        }
-        if (keep) {
-            const u64 pos = base + running + before + rank + s_bigpre[lo];
-            if (pos < capacity) {
-                keys[pos] = ((u64)tile << 32) | (u64)s_depth[lo];
-                vals[pos] = blockIdx.x * kPreBlock + lo;
-            }
-        }
-        running += round_total;
+        ++pos;
     }
 }
 
@@ -1362,6 +1295,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
                            char *scratch, const ScratchLayout &L, hipStream_t stream)
 {
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
+    const u32 *block_sums = reinterpret_cast<const u32 *>(scratch + L.block_sums);
     u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
     const u64 *group_totals = reinterpret_cast<const u64 *>(scratch + L.group_totals);
     u64 *digit_totals = reinterpret_cast<u64 *>(scratch + L.digit_totals);
@@ -1386,8 +1320,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
         if (pp.cam.binning == 1u) {
             hipLaunchKernelGGL(emit_tight_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               reinterpret_cast<const float4 *>(proj.feat), pp,
-                               block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
+                               block_sums, block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
                                big_idx, big_off, digit_totals, reinterpret_cast<const u32 *>(scratch + L.tile_masks));
             hipLaunchKernelGGL(emit_deferred_kernel<true>, dim3(big_grid), dim3(kPreBlock), 0, stream,
                                reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
@@ -1396,7 +1329,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
         } else {
             hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
                                proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
+                               block_sums, block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
                                big_idx, big_off, digit_totals);
             hipLaunchKernelGGL(emit_deferred_kernel<false>, dim3(big_grid), dim3(kPreBlock), 0, stream,
                                reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
