@@ -48,8 +48,11 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
     partition by tile: per pass over the tile bits (digits of at most 8 bits: 2 passes at
     1080p and 2160p, 1 at 256 x 256) histogram read 8 B + scatter read 12 B + write 12 B per pair.
     ranges: 8 B per pair + 8 B per tile.  order: 12 B per tile.
-    per-tile sort: 12 B read + 12 B write per pair; a list longer than 16384 pairs is
-    also merged, 24 B per pair and doubling round (plus one copy when the rounds are odd).
+    per-tile sort: 12 B read + 12 B write per pair; a list of 4097 .. 16384 pairs is sorted in
+    chunks and then goes through two merge rounds between the pair buffers (the second a copy for
+    a list of two chunks), 24 B per pair each; a list longer than 16384 pairs is merged, 24 B per
+    pair and doubling round (plus one copy when the rounds are odd).  `long_lists`: the lengths
+    above 4096.
     """
     tile_bits = max(1, (tiles - 1).bit_length())
     passes = (tile_bits + 7) // 8
@@ -60,6 +63,9 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
     b_ranges = 8 * D + 8 * (tiles + 1) + 12 * tiles
     b_tsort = 24 * D
     for L in long_lists:
+        if L <= 16384:
+            b_tsort += 48 * L
+            continue
         rounds = 0
         run = 16384
         while run < L:
@@ -163,7 +169,7 @@ def main():
         n_bin = int((tt > 0).sum().item())
         lens = (fr.tile_offsets[1:] - fr.tile_offsets[:-1])
         Ds.append(D)
-        stats.append(dict(D=D, n_bin=n_bin, long_lists=[int(x) for x in lens[lens > 16384].tolist()],
+        stats.append(dict(D=D, n_bin=n_bin, long_lists=[int(x) for x in lens[lens > 4096].tolist()],
                           processed=flags[:nb].bool().cpu().numpy().copy()))
     del fr
     torch.cuda.empty_cache()

@@ -7,30 +7,33 @@
 // read the pair count D from device memory, so the host never waits for it: grids are sized
 // from the caller's capacity and surplus workgroups leave at once.
 //
-//   emit     one workgroup per 256 primitives; a load-balanced expansion: the workgroup's
-//            output slots are dealt round-robin to its threads and each slot finds its
-//            primitive by binary search in an LDS prefix array, so stores are contiguous
-//            whatever the rectangle sizes are.  Under binning rule 1 every slot is first put
-//            through the splat/tile intersection test and the kept ones are compacted.
-//            Rectangles of more than 128 tiles are deferred to a list and expanded by
-//            emit_deferred_kernel, one wavefront (or, beyond 2048 tiles, one workgroup) each.
+//   emit     one workgroup per 256 primitives, placed by a two-level prefix sum over the
+//            workgroup tile counts of the preprocess kernel.  Binning rule 0: a load-balanced
+//            expansion, the workgroup's output slots are dealt round-robin to its threads and
+//            each slot finds its primitive by binary search in an LDS prefix array, so stores
+//            are contiguous whatever the rectangle sizes are.  Rule 1: every thread walks the
+//            bit mask of kept tiles the preprocess kernel left for its primitive.  Rectangles of
+//            more than 128 tiles (rule 1: more than 32, the width of the mask) are deferred to a
+//            list and expanded by emit_deferred_kernel, one wavefront (or, beyond 2048 tiles,
+//            one workgroup) each, which under rule 1 repeats the intersection test per tile.
 //   partition  stable LSD radix sort over the TILE bits of the keys only (two passes of
-//            7 + 6 bits at 1080p).  Per pass: (1) digit counts of every 4096-pair sort tile
-//            (the first pass also accumulates the global digit totals of all passes),
-//            (2) one workgroup per digit turns its row of counts into output offsets,
-//            (3) scatter: wavefront match-any ranking (ballots over the digit bits) keeps
-//            equal digits in order, the tile is sorted by digit in LDS and written out in
-//            contiguous runs (128 or fewer bins, so runs are long and fill cache lines).
+//            7 + 6 bits at 1080p).  Per pass: (1) digit counts of every 2048-pair sort tile
+//            and the pass's digit totals, (2) one workgroup per digit turns its row of counts
+//            into output offsets, (3) scatter: wavefront match-any ranking (ballots over the
+//            digit bits) keeps equal digits in order, the tile is sorted by digit in LDS and
+//            written out in contiguous runs (128 or fewer bins, so runs are long).
 //   ranges   tile_offsets[t] = first position whose tile id is >= t.
 //   order    tile ids by descending list length, bucketed by the bit length of the length,
-//            which also gives the size classes of the per-tile sort.
+//            which also gives the size classes of the per-tile sort and the chunk list.
 //   tile sort  every tile's list is sorted by (depth bits, index) as 64-bit composites with a
 //            merge sort in LDS (the order is total, so no stability is needed): one wavefront
-//            for lists of up to 512 pairs, 256 threads up to 2048, 512 threads up to 4096,
-//            1024 threads and most of a compute unit's LDS up to 16384; longer lists are
-//            sorted in 16384-pair chunks and merged pairwise between the two pair buffers
+//            for lists of up to 512 pairs, 256 threads up to 2048, 512 threads up to 4096.  A
+//            list of up to 16384 pairs is cut into 4096-pair chunks, sorted by workgroups of
+//            the 512-thread launch and merged in two rounds between the two pair buffers by
+//            workgroups of the 256-thread and the one-wavefront launch.  Lists beyond that get
+//            a workgroup of 1024 threads each: 16384-pair chunks in LDS, then pairwise merges
 //            through LDS-staged windows.  Sorting the 32 depth bits this way costs one read
-//            and one write of the pairs instead of four radix passes over all of them.
+//            and one write of most pairs instead of four radix passes over all of them.
 #include "lmk_gs_internal.h"
 
 namespace lmk {
@@ -200,10 +203,6 @@ __global__ __launch_bounds__(kPreBlock) void emit_kernel(
     }
 }
 
-// One wavefront per deferred primitive (persistent grid striding over the list): its rectangle
-// is walked 64 tiles at a time in row-major order; under binning rule 1 (TIGHT) each tile is put
-// through the splat/tile intersection test and the kept ones are compacted with ballot ranks,
-// so the pairs land exactly where the prefix sums say.
 // ---------------------------------------------------------------- emit, binning rule 1
 // Only the tiles that pass the splat/tile intersection test of lmk_gs_camera.binning == 1 get a
 // pair, in (primitive, row-major tile) order: the output position of a kept tile is the
@@ -290,6 +289,10 @@ __global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
     }
 }
 
+// One wavefront per deferred primitive (persistent grid striding over the list): its rectangle
+// is walked 64 tiles at a time in row-major order; under binning rule 1 (TIGHT) each tile is put
+// through the splat/tile intersection test and the kept ones are compacted with ballot ranks,
+// so the pairs land exactly where the prefix sums say.
 template <bool TIGHT>
 __device__ __forceinline__ void emit_big_part(
     u32 block, u32 blocks,
@@ -464,10 +467,12 @@ __device__ __forceinline__ void wave_hist_add(u32 *hist, u32 d, bool valid, u32 
 // atomic per non-empty digit when the workgroup is done.  Atomics on one address are served one
 // after the other, and a pass over the high tile bits has only a few digits, so the totals are
 // kept in kTotalCopies copies (workgroup b adds to copy b % kTotalCopies; the scan adds them up).
+template <u32 kSortItems>
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
     u32 shift, u32 bits, u32 *__restrict__ table, u64 table_stride, u64 *__restrict__ digit_totals)
 {
+    constexpr u32 kSortTile = kSortThreads * kSortItems;
     __shared__ u32 s_hist[kMaxRadix];
     __shared__ u32 s_tot[kMaxRadix];
     const u64 D = load_D(header, capacity);
@@ -509,12 +514,12 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
 // all smaller digits -> offsets[digit][tile] (u64)
 __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
     const ScratchHeader *__restrict__ header, u64 capacity, const u32 *__restrict__ table,
-    u64 *__restrict__ offsets, u64 table_stride, const u64 *__restrict__ digit_totals)
+    u64 *__restrict__ offsets, u64 table_stride, const u64 *__restrict__ digit_totals, u32 sort_tile)
 {
     __shared__ u64 s_wave[kSortThreads / kWave];
     __shared__ u64 s_carry;
     const u64 D = load_D(header, capacity);
-    const u64 ntiles = (D + kSortTile - 1) / kSortTile;
+    const u64 ntiles = (D + sort_tile - 1) / sort_tile;
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 digit = blockIdx.x;
 
@@ -536,7 +541,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
     const u32 *row = table + (u64)digit * table_stride;
     u64 *orow = offsets + (u64)digit * table_stride;
     // rows of 64 consecutive sort tiles per wavefront, so that loads and stores are whole lines;
-    // a count is at most kSortTile, so the sums inside one wavefront's rows fit 32 bits
+    // a count is at most 4096, so the sums inside one wavefront's rows fit 32 bits
     constexpr u32 kRows = 8;
     constexpr u32 kWaves = kSortThreads / kWave;
     for (u64 base = 0; base < ntiles; base += (u64)kWaves * kRows * kWave) {
@@ -572,14 +577,16 @@ __global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
 }
 
 // (3) stable scatter of one digit
+template <u32 kSortItems>
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
     const u64 *__restrict__ keys_in, const u32 *__restrict__ vals_in,
     u64 *__restrict__ keys_out, u32 *__restrict__ vals_out,
     const ScratchHeader *__restrict__ header, u64 capacity, u32 shift, u32 bits,
     const u64 *__restrict__ offsets, u64 table_stride)
 {
+    constexpr u32 kSortTile = kSortThreads * kSortItems;
     constexpr u32 kWaves = kSortThreads / kWave;
-    constexpr u32 kPerWave = kSortItems * kWave;       // 1024 consecutive pairs per wavefront
+    constexpr u32 kPerWave = kSortItems * kWave;       // consecutive pairs per wavefront
     __shared__ u32 s_wave_hist[kWaves][kMaxRadix];     // per-wavefront digit counters, then bases
     __shared__ u32 s_digit_start[kMaxRadix];           // first local position of each digit
     __shared__ u64 s_gofs[kMaxRadix];                  // global offset minus local start
@@ -1344,15 +1351,25 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     if (e != hipSuccess) return e;
     // enough resident workgroups to fill 256 CUs several times over; each loops over sort tiles
     const u32 grid = grid_for(L.sort_tiles, 256u * 16u);
+    const bool many = sort_items(out.capacity) == kSortItemsMany;
     for (u32 p = 0; p < plan.passes; ++p) {
         u64 *totals = digit_totals + (size_t)p * kTotalCopies * kMaxRadix;
-        hipLaunchKernelGGL(radix_hist_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
-                           kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles, totals);
+        if (many)
+            hipLaunchKernelGGL(radix_hist_kernel<kSortItemsMany>, dim3(grid), dim3(kSortThreads), 0, stream,
+                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles, totals);
+        else
+            hipLaunchKernelGGL(radix_hist_kernel<kSortItemsFew>, dim3(grid), dim3(kSortThreads), 0, stream,
+                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles, totals);
         hipLaunchKernelGGL(radix_scan_kernel, dim3(1u << plan.bits[p]), dim3(kSortThreads), 0, stream,
-                           header, out.capacity, table, offsets, L.sort_tiles, totals);
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3(grid), dim3(kSortThreads), 0, stream,
-                           kin, vin, kout, vout, header, out.capacity, plan.shift[p], plan.bits[p],
-                           offsets, L.sort_tiles);
+                           header, out.capacity, table, offsets, L.sort_tiles, totals, sort_tile_pairs(out.capacity));
+        if (many)
+            hipLaunchKernelGGL(radix_scatter_kernel<kSortItemsMany>, dim3(grid), dim3(kSortThreads), 0, stream,
+                               kin, vin, kout, vout, header, out.capacity, plan.shift[p], plan.bits[p],
+                               offsets, L.sort_tiles);
+        else
+            hipLaunchKernelGGL(radix_scatter_kernel<kSortItemsFew>, dim3(grid), dim3(kSortThreads), 0, stream,
+                               kin, vin, kout, vout, header, out.capacity, plan.shift[p], plan.bits[p],
+                               offsets, L.sort_tiles);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         u64 *tk = kin; kin = kout; kout = tk;

@@ -15,8 +15,14 @@ typedef uint32_t u32;
 constexpr u32 kWave = 64;               // CDNA wavefront width
 constexpr u32 kPreBlock = LMK_GS_PRE_BLOCK;   // primitives per preprocess / emit workgroup
 constexpr u32 kSortThreads = 256;       // radix sort workgroup
-constexpr u32 kSortItems = 8;           // keys per thread
-constexpr u32 kSortTile = kSortThreads * kSortItems;   // 2048 pairs per workgroup pass
+// Keys per thread of the partition kernels, so 2048 or 4096 pairs per sort tile.  With few sort
+// tiles a pass is bound by the latency of one workgroup and smaller tiles spread better over
+// the chip; with very many it is bound by HBM and the longer runs of a larger tile fill the
+// lines they write.  The host picks from the capacity, which it knows (D it does not).
+constexpr u32 kSortItemsFew = 8, kSortItemsMany = 16;
+constexpr u64 kManyPairs = 64ull << 20;
+inline u32 sort_items(u64 capacity) { return capacity > kManyPairs ? kSortItemsMany : kSortItemsFew; }
+inline u32 sort_tile_pairs(u64 capacity) { return kSortThreads * sort_items(capacity); }
 constexpr u32 kMaxRadixBits = 8;         // digits are at most 8 bits wide, chosen per frame
 constexpr u32 kMaxRadix = 1u << kMaxRadixBits;
 constexpr u32 kMaxPasses = 8;
@@ -50,7 +56,7 @@ struct ScratchLayout {
     size_t big_off;       // u64 [n]         and where their pairs start
     size_t total;
     u32 pre_blocks;
-    u64 sort_tiles;       // ceil(capacity / kSortTile)
+    u64 sort_tiles;       // ceil(capacity / sort_tile_pairs(capacity))
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -59,7 +65,7 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
 {
     ScratchLayout L;
     L.pre_blocks = (n + kPreBlock - 1) / kPreBlock;
-    L.sort_tiles = (capacity + kSortTile - 1) / kSortTile;
+    L.sort_tiles = (capacity + sort_tile_pairs(capacity) - 1) / sort_tile_pairs(capacity);
     if (L.sort_tiles == 0) L.sort_tiles = 1;
     size_t o = 0;
     L.header = o;        o += align256(sizeof(ScratchHeader));

@@ -101,6 +101,17 @@ def test_long_lists_in_few_tiles(w, h, n, seed, binning, lo, hi):
     assert lo < lens.max() <= hi, lens.max()
 
 
+def test_large_capacity_takes_the_wide_partition_tiles():
+    """Above 64 Mi pairs of capacity the partition works on 4096-pair tiles instead of 2048:
+    same result, here with several whole tiles and a ragged last one."""
+    sc = scenes.make_scene(0, n=30011, seed=48)
+    sc["scale"] *= np.float32(2.0)
+    cam = dict(scenes.make_cameras(0, 640, 360)[0], binning=1)
+    r = P.full_compare(sc, cam, capacity=(64 << 20) + 5)
+    _report("wide partition tiles", r.stats)
+    assert r.stats["D"] > 10 * 4096
+
+
 @pytest.mark.parametrize("binning", [0, 1])
 def test_rectangles_of_every_size_class(binning):
     """Rectangle areas from 1 tile to the whole 120 x 68 grid, dense around the sizes at which the
