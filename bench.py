@@ -51,7 +51,7 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
     per-tile sort: 12 B read + 12 B write per pair; a list of 4097 .. 16384 pairs is sorted in
     chunks and then goes through two merge rounds between the pair buffers (the second a copy for
     a list of two chunks), 24 B per pair each; a list longer than 16384 pairs is merged, 24 B per
-    pair and doubling round (plus one copy when the rounds are odd).  `long_lists`: the lengths
+    pair and doubling round.  `long_lists`: the lengths
     above 4096.
     """
     tile_bits = max(1, (tiles - 1).bit_length())
@@ -71,7 +71,7 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
         while run < L:
             run *= 2
             rounds += 1
-        b_tsort += 24 * L * (rounds + (rounds & 1))
+        b_tsort += 24 * L * rounds
     return dict(preprocess=b_pre, emit=b_emit, partition=b_part, ranges=b_ranges, tile_sort=b_tsort,
                 total=b_pre + b_emit + b_part + b_ranges + b_tsort)
 

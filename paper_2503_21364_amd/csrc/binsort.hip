@@ -947,9 +947,10 @@ __device__ __forceinline__ void merge_from_lds(const u64 *s, u32 a0, u32 a1, u32
 }
 
 template <u32 THREADS, u32 ITEMS>
-__device__ __forceinline__ void sort_pairs_in_lds(u64 *__restrict__ keys, u32 *__restrict__ vals,
-                                                  u64 beg, u32 n, u32 tile, u64 *s)
+__device__ __forceinline__ void sort_pairs_in_lds(u64 *keys, u32 *vals, u64 beg, u32 n, u32 tile, u64 *s,
+                                                  u64 *keys_out = nullptr, u32 *vals_out = nullptr)
 {
+    if (!keys_out) { keys_out = keys; vals_out = vals; }    // in place unless the caller wants the result elsewhere
     constexpr u32 CAP = THREADS * ITEMS;
     const u32 tid = threadIdx.x;
     const u32 m = (n + ITEMS - 1) / ITEMS * ITEMS;          // elements in play: n rounded up to whole runs
@@ -1000,8 +1001,8 @@ __device__ __forceinline__ void sort_pairs_in_lds(u64 *__restrict__ keys, u32 *_
     const u64 hi_bits = (u64)tile << 32;
     for (u32 p = tid; p < n; p += THREADS) {
         const u64 c = s[ts_slot(p)];
-        keys[beg + p] = hi_bits | (c >> 32);
-        vals[beg + p] = (u32)c;
+        keys_out[beg + p] = hi_bits | (c >> 32);
+        vals_out[beg + p] = (u32)c;
     }
     __syncthreads();                                        // s may be refilled by the caller
 }
@@ -1217,19 +1218,26 @@ __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     constexpr u32 kWaves = kHugeThreads / kWave;
 
+    // an odd number of merge rounds: the chunk sorts write to the alternate buffers, so that the
+    // last round ends in keys/vals either way
+    u32 rounds = 0;
+    for (u64 run = kHuge; run < L; run <<= 1) ++rounds;
+    const bool start_alt = (rounds & 1u) != 0u;
+    u64 *k0 = start_alt ? keys_alt : keys, *k1 = start_alt ? keys : keys_alt;
+    u32 *v0 = start_alt ? vals_alt : vals, *v1 = start_alt ? vals : vals_alt;
     for (u64 c0 = 0; c0 < L; c0 += kHuge) {
         const u32 n = (u32)(L - c0 < (u64)kHuge ? L - c0 : (u64)kHuge);
-        if (n >= 2) sort_pairs_in_lds<kHugeThreads, kHugeItems>(keys, vals, beg + c0, n, tile, s);
+        if (n >= 2) sort_pairs_in_lds<kHugeThreads, kHugeItems>(keys, vals, beg + c0, n, tile, s, k0, v0);
+        else if (start_alt && tid == 0) { k0[beg + c0] = keys[beg + c0]; v0[beg + c0] = vals[beg + c0]; }
     }
     // the chunk sorts of this workgroup wrote the runs the merges read
     __threadfence_block();
     __syncthreads();
 
-    u64 *sk = keys + beg, *dk = keys_alt + beg;
-    u32 *sv = vals + beg, *dv = vals_alt + beg;
+    u64 *sk = k0 + beg, *dk = k1 + beg;
+    u32 *sv = v0 + beg, *dv = v1 + beg;
     const u64 hi_bits = (u64)tile << 32;
     const u64 nseg = (L + kHuge - 1) / kHuge;
-    bool in_alt = false;
     for (u64 run = kHuge; run < L; run <<= 1) {
         for (u64 seg0 = 0; seg0 < nseg; seg0 += kWaves) {
             {   // wavefront wv: the splits at both ends of output segment seg0 + wv
@@ -1284,10 +1292,6 @@ __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
         __syncthreads();
         u64 *tk = sk; sk = dk; dk = tk;
         u32 *tv = sv; sv = dv; dv = tv;
-        in_alt = !in_alt;
-    }
-    if (in_alt) {                                           // sk/sv now point into the alternate buffers
-        for (u64 i = tid; i < L; i += kHugeThreads) { dk[i] = sk[i]; dv[i] = sv[i]; }
     }
 }
 
