@@ -931,18 +931,65 @@ __device__ __forceinline__ void merge_from_lds(const u64 *s, u32 a0, u32 a1, u32
     u32 i = a0 + l0, j = a1 + (diag - l0);
     u64 ka = i < a1 ? s[ts_slot(i)] : ~0ull;
     u64 kb = j < b1 ? s[ts_slot(j)] : ~0ull;
+    // Straight-line steps, selects only: an exhausted run shows the maximum value, which also is
+    // what the padding holds, so "A first unless B is smaller" needs no bounds in the comparison
+    // (a tie is between padding values, where the side does not matter).  The one LDS read per
+    // step is not branched around: when the run has just been used up it reads slot 0 and the
+    // value is dropped.
 #pragma unroll
     for (u32 k = 0; k < ITEMS; ++k) {
-        // ties only occur between padding values, where the side does not matter,
-        // as long as an exhausted run is never read
-        const bool takeA = j >= b1 || (i < a1 && ka <= kb);
-        if (takeA) {
-            e[k] = ka; ++i;
-            ka = i < a1 ? s[ts_slot(i)] : ~0ull;
-        } else {
-            e[k] = kb; ++j;
-            kb = j < b1 ? s[ts_slot(j)] : ~0ull;
-        }
+        const bool takeA = ka <= kb;
+        e[k] = takeA ? ka : kb;
+        const u32 next = (takeA ? i : j) + 1u;
+        const u32 lim = takeA ? a1 : b1;
+        const bool more = next < lim;
+        const u32 at = more ? next : 0u;
+        const u64 v = s[ts_slot(at)];
+        const u64 nv = more ? v : ~0ull;
+        i = takeA ? next : i;
+        j = takeA ? j : next;
+        ka = takeA ? nv : ka;
+        kb = takeA ? kb : nv;
+    }
+}
+
+// The first three merge rounds need no LDS: the runs of 2, 4 and 8 neighbouring lanes are merged
+// with a bitonic merge network whose lane exchanges are DPP moves (mirror within 2 / 4 / 8
+// lanes for the first, "flip" stage, lane xor 1 / 2 for the half-cleaners that follow).
+template <int CTRL>
+__device__ __forceinline__ u64 ts_dpp(u64 v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(u32)v, CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(u32)(v >> 32), CTRL, 0xf, 0xf, true);
+    return ((u64)(u32)hi << 32) | (u64)(u32)lo;
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;            // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kDppMirror4 = 0x1B, kDppMirror8 = 0x141;     // quad_perm [3,2,1,0], row_half_mirror
+
+// one stage across lanes: element k meets element k (FLIP: ITEMS - 1 - k) of the partner lane;
+// the lower lane of the pair keeps the smaller value
+template <int CTRL, bool FLIP, u32 ITEMS>
+__device__ __forceinline__ void ts_lane_stage(u64 (&e)[ITEMS], bool upper)
+{
+    u64 p[ITEMS];
+#pragma unroll
+    for (u32 k = 0; k < ITEMS; ++k) p[k] = ts_dpp<CTRL>(e[FLIP ? ITEMS - 1 - k : k]);
+#pragma unroll
+    for (u32 k = 0; k < ITEMS; ++k) {
+        const bool mine = (e[k] < p[k]) != upper;           // lower keeps the smaller, upper the larger
+        e[k] = mine ? e[k] : p[k];
+    }
+}
+
+// a bitonic sequence of ITEMS values in registers -> ascending
+template <u32 ITEMS>
+__device__ __forceinline__ void ts_clean(u64 (&e)[ITEMS])
+{
+#pragma unroll
+    for (u32 j = ITEMS >> 1; j > 0; j >>= 1) {
+#pragma unroll
+        for (u32 i = 0; i < ITEMS; ++i)
+            if ((i & j) == 0) ts_cswap(e[i], e[i | j]);
     }
 }
 
@@ -952,38 +999,47 @@ __device__ __forceinline__ void sort_pairs_in_lds(u64 *keys, u32 *vals, u64 beg,
 {
     if (!keys_out) { keys_out = keys; vals_out = vals; }    // in place unless the caller wants the result elsewhere
     constexpr u32 CAP = THREADS * ITEMS;
+    constexpr u32 kLaneRun = 8 * ITEMS;                     // sorted run length after the lane merges
     const u32 tid = threadIdx.x;
     const u32 m = (n + ITEMS - 1) / ITEMS * ITEMS;          // elements in play: n rounded up to whole runs
-    // coalesced load into LDS; composites beyond n are the maximum value and sort to the end
-    for (u32 i = tid; i < m; i += THREADS)
-        s[ts_slot(i)] = i < n ? ((keys[beg + i] << 32) | (u64)vals[beg + i]) : ~0ull;
-    __syncthreads();
     const u32 o0 = tid * ITEMS;
     const bool active = o0 < m;
+    // each thread's ITEMS consecutive pairs as composites; beyond n the maximum value, which sorts to the end
     u64 e[ITEMS];
-    if (active) {
 #pragma unroll
-        for (u32 k = 0; k < ITEMS; ++k) e[k] = s[ts_slot(o0 + k)];
-        // sort the run in registers (bitonic network)
+    for (u32 k = 0; k < ITEMS; ++k)
+        e[k] = o0 + k < n ? ((keys[beg + o0 + k] << 32) | (u64)vals[beg + o0 + k]) : ~0ull;
+    // sort the run in registers (bitonic network)
 #pragma unroll
-        for (u32 k = 2; k <= ITEMS; k <<= 1) {
+    for (u32 k = 2; k <= ITEMS; k <<= 1) {
 #pragma unroll
-            for (u32 j = k >> 1; j > 0; j >>= 1) {
+        for (u32 j = k >> 1; j > 0; j >>= 1) {
 #pragma unroll
-                for (u32 i = 0; i < ITEMS; ++i) {
-                    const u32 l = i ^ j;
-                    if (l > i) {
-                        if ((i & k) == 0) ts_cswap(e[i], e[l]); else ts_cswap(e[l], e[i]);
-                    }
+            for (u32 i = 0; i < ITEMS; ++i) {
+                const u32 l = i ^ j;
+                if (l > i) {
+                    if ((i & k) == 0) ts_cswap(e[i], e[l]); else ts_cswap(e[l], e[i]);
                 }
             }
         }
+    }
+    // runs of 2, 4, 8 lanes (every lane takes part; lanes beyond m hold the maximum value)
+    ts_lane_stage<kDppXor1, true, ITEMS>(e, (tid & 1u) != 0u);
+    ts_clean<ITEMS>(e);
+    ts_lane_stage<kDppMirror4, true, ITEMS>(e, (tid & 2u) != 0u);
+    ts_lane_stage<kDppXor1, false, ITEMS>(e, (tid & 1u) != 0u);
+    ts_clean<ITEMS>(e);
+    ts_lane_stage<kDppMirror8, true, ITEMS>(e, (tid & 4u) != 0u);
+    ts_lane_stage<kDppXor2, false, ITEMS>(e, (tid & 2u) != 0u);
+    ts_lane_stage<kDppXor1, false, ITEMS>(e, (tid & 1u) != 0u);
+    ts_clean<ITEMS>(e);
+    if (active) {
 #pragma unroll
         for (u32 k = 0; k < ITEMS; ++k) s[ts_slot(o0 + k)] = e[k];
     }
     __syncthreads();
 
-    for (u32 run = ITEMS; run < m && run < CAP; run <<= 1) {
+    for (u32 run = kLaneRun; run < m && run < CAP; run <<= 1) {
         if (active) {
             // outputs [o0, o0 + ITEMS) of the pair of runs holding them: A = [a0, a1), B = [a1, b1)
             const u32 a0 = (o0 / (2 * run)) * (2 * run);
