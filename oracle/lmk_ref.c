@@ -1,5 +1,6 @@
 /*
- * lmk_ref.c -- CPU oracle for tile-based 3D Gaussian splatting (forward).
+ * lmk_ref.c -- CPU oracle for tile-based 3D Gaussian splatting (forward, and the
+ * gradient through the compositing).
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
  * GPU renderer is checked against.  It shares no code, header, table or
@@ -12,6 +13,8 @@
  *   Sec. 2.2 (text)  SH colour + opacity per primitive; EWA projection to a 2D
  *                    Gaussian ("splatting"); depth sort; blending per screen tile
  *   Sec. 2.2 Eq. 9-10  front-to-back compositing with sigma_i = alpha_i G'_i(x')
+ *   Sec. 2.2 (text)  the rasteriser is differentiable: gradient of a loss through Eq. 9-10
+ *                    with respect to each primitive's 2D mean, conic, opacity and colour
  *   Sec. 4.2.1       the rasteriser stages named there: per-primitive projection,
  *                    duplication into (tile, depth) keys, sort, per-tile blend;
  *                    the per-tile intersection test (binning rule 1)
@@ -37,7 +40,9 @@
  * the tile intersection test of binning rule 1 against dense sampling and
  * against the unchanged image; the voxel visibility test against brute-force
  * conservativeness, closed cases and a planted mistake; the culls of
- * degenerate attribute values.  No function here is "parity unpinned".
+ * degenerate attribute values; the gradient through the compositing against
+ * central differences of the forward functions, one- and two-splat closed forms
+ * and the partition of unity of the weights.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -728,4 +733,149 @@ void lmk_ref_voxels_visible(const ref_camera *cam, uint32_t num_voxels, const fl
 {
     for (uint32_t v = 0; v < num_voxels; ++v)
         visible[v] = (uint8_t)lmk_ref_voxel_visible(cam, box_lo + 3 * (size_t)v, box_hi + 3 * (size_t)v, smax[v]);
+}
+
+
+/* ------------------------------------------------------------------------
+ * Gradient of a scalar loss through the compositing of Eq. 9-10 (Sec. 2.2: the
+ * rasteriser is differentiable, and all parameters of the primitives are optimised
+ * through the rendering process).  Given dL/dC_hat(x') (three channels) and
+ * dL/dT_end(x') for every pixel, the gradient with respect to what the compositing
+ * reads of every primitive: its 2D mean (u, v), its conic (A, B, C), its opacity o and
+ * its colour c.  The chain from there back to the 3D parameters is not part of this
+ * function.
+ *
+ * For one pixel with composited entries i = 1..m in front-to-back order,
+ *   T_1 = 1, T_{i+1} = T_i (1 - alpha_i), w_i = alpha_i T_i,
+ *   C_hat = sum_i c_i w_i + bg T_{m+1},   T_end = T_{m+1},
+ * so, with S_i = sum_{j>i} c_j w_j + bg T_end (what lies behind entry i),
+ *   dL/dc_i     = w_i dL/dC_hat
+ *   dL/dalpha_i = dL/dC_hat . (T_i c_i - S_i / (1 - alpha_i)) - dL/dT_end T_end / (1 - alpha_i)
+ * and alpha_i = o_i exp(-q_i / 2), q = A dx^2 + 2 B dx dy + C dy^2, dx = u - px, dy = v - py:
+ *   dalpha/do = exp(-q/2),  dalpha/dq = -alpha / 2,
+ *   dq/dA = dx^2, dq/dB = 2 dx dy, dq/dC = dy^2, dq/du = 2 (A dx + B dy), dq/dv = 2 (B dx + C dy).
+ * [reading] The thresholds of the forward walk are constants of the derivative: an entry
+ * that was skipped (alpha < 1/255), the entry that stopped the walk and everything after it
+ * get no gradient; where alpha was clamped to 0.99 it does not depend on o or q; where the
+ * exponent was clamped to 0 (q < 0) alpha does not depend on q.
+ * The forward walk here takes the same steps and the same decisions as composite_pixel
+ * (a test compares the two images bit for bit); it also reports the pixels that hold a
+ * decision within rounding of its threshold (amb), whose gradients an fp32 renderer may
+ * legitimately compute from the other decision.
+ * Outputs are accumulated over all pixels in fp64: g_mean2d [2][n], g_conic [3][n],
+ * g_opacity [n], g_rgb [3][n] (overwritten).  out_rgb/out_T (may be NULL): the forward image.
+ */
+typedef struct { uint32_t g; double alpha, gauss, dx, dy, T; int clamped_alpha, clamped_power; } ref_entry;
+
+void lmk_ref_render_backward(uint32_t n, const float *mean2d, const float *conic,
+                             const float *opacity, const double *rgb,
+                             const uint32_t *sorted_vals, const uint64_t *tile_offsets,
+                             const ref_camera *cam, const double *grad_rgb, const double *grad_T,
+                             double *g_mean2d, double *g_conic, double *g_opacity, double *g_rgb,
+                             double *out_rgb, double *out_T, uint32_t *out_amb)
+{
+    const uint32_t W = cam->width, H = cam->height, TS = cam->tile;
+    const uint32_t TX = (W + TS - 1) / TS;
+    const size_t N = n, HW = (size_t)H * W;
+    const double EPS = 1.0 / 16777216.0;
+    memset(g_mean2d, 0, sizeof(double) * 2 * N);
+    memset(g_conic, 0, sizeof(double) * 3 * N);
+    memset(g_opacity, 0, sizeof(double) * N);
+    memset(g_rgb, 0, sizeof(double) * 3 * N);
+#pragma omp parallel
+    {
+        ref_entry *rec = NULL;
+        size_t rec_cap = 0;
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t jj = 0; jj < (int64_t)H; ++jj) {
+            const uint32_t j = (uint32_t)jj;
+            for (uint32_t i = 0; i < W; ++i) {
+                const uint32_t t = (j / TS) * TX + (i / TS);
+                const uint32_t *list = sorted_vals + tile_offsets[t];
+                const uint64_t count = tile_offsets[t + 1] - tile_offsets[t];
+                if (count > rec_cap) {
+                    free(rec);
+                    rec_cap = (size_t)count + 64;
+                    rec = (ref_entry *)malloc(sizeof(ref_entry) * rec_cap);
+                }
+                const double pxc = (double)i + 0.5, pyc = (double)j + 0.5;
+                const size_t p = (size_t)j * W + i;
+                /* forward walk, recording the composited entries */
+                double T = 1.0, acc[3] = { 0.0, 0.0, 0.0 }, relT = 0.0;
+                uint32_t m = 0, amb = 0;
+                for (uint64_t k = 0; k < count; ++k) {
+                    const size_t g = list[k];
+                    const double dx = (double)mean2d[g] - pxc;
+                    const double dy = (double)mean2d[N + g] - pyc;
+                    const double A = conic[g], B = conic[N + g], Cc = conic[2 * N + g];
+                    const double q = A * dx * dx + 2.0 * B * dx * dy + Cc * dy * dy;
+                    double power = -0.5 * q;
+                    const int cp = power > 0.0;
+                    if (cp) power = 0.0;
+                    const double gauss = exp(power);
+                    const double raw = (double)opacity[g] * gauss;
+                    double alpha = raw;
+                    const int ca = alpha > (double)REF_ALPHA_MAX;
+                    if (ca) alpha = (double)REF_ALPHA_MAX;
+                    const double mag = fabs(A) * dx * dx + 2.0 * fabs(B * dx * dy) + fabs(Cc) * dy * dy;
+                    const double dalpha = 0.5 * 8.0 * EPS * mag + 8.0 * EPS;
+                    if (fabs(log(255.0 * raw)) <= dalpha + 1e-6) ++amb;
+                    if (fabs(raw / (double)REF_ALPHA_MAX - 1.0) <= dalpha + 1e-6) ++amb;   /* at the 0.99 clamp */
+                    if ((float)alpha < REF_ALPHA_MIN) continue;
+                    const double Tn = T * (1.0 - alpha);
+                    const double relTn = relT + alpha * dalpha / (1.0 - alpha) + 2.0 * EPS;
+                    if (fabs(Tn / (double)REF_T_MIN - 1.0) <= relTn + 1e-6) ++amb;
+                    if ((float)Tn < REF_T_MIN) break;
+                    const double w = alpha * T;
+                    acc[0] += rgb[g] * w; acc[1] += rgb[N + g] * w; acc[2] += rgb[2 * N + g] * w;
+                    rec[m].g = (uint32_t)g; rec[m].alpha = alpha; rec[m].gauss = gauss;
+                    rec[m].dx = dx; rec[m].dy = dy; rec[m].T = T;
+                    rec[m].clamped_alpha = ca; rec[m].clamped_power = cp;
+                    ++m;
+                    T = Tn; relT = relTn;
+                }
+                if (out_rgb)
+                    for (int ch = 0; ch < 3; ++ch) out_rgb[(size_t)ch * HW + p] = acc[ch] + T * (double)cam->bg[ch];
+                if (out_T) out_T[p] = T;
+                if (out_amb) out_amb[p] = amb;
+                /* back to front */
+                const double Gc[3] = { grad_rgb[p], grad_rgb[HW + p], grad_rgb[2 * HW + p] };
+                const double GT = grad_T ? grad_T[p] : 0.0;
+                const double Tend = T;
+                double S[3] = { (double)cam->bg[0] * Tend, (double)cam->bg[1] * Tend, (double)cam->bg[2] * Tend };
+                for (uint32_t e = m; e-- > 0;) {
+                    const ref_entry *r = &rec[e];
+                    const size_t g = r->g;
+                    const double c[3] = { rgb[g], rgb[N + g], rgb[2 * N + g] };
+                    const double w = r->alpha * r->T;
+                    const double inv = 1.0 / (1.0 - r->alpha);
+                    double dLda = -GT * Tend * inv;
+                    for (int ch = 0; ch < 3; ++ch) dLda += Gc[ch] * (r->T * c[ch] - S[ch] * inv);
+                    for (int ch = 0; ch < 3; ++ch) {
+#pragma omp atomic
+                        g_rgb[(size_t)ch * N + g] += w * Gc[ch];
+                        S[ch] += c[ch] * w;
+                    }
+                    if (r->clamped_alpha) continue;
+                    const double dLdo = dLda * r->gauss;
+#pragma omp atomic
+                    g_opacity[g] += dLdo;
+                    if (r->clamped_power) continue;
+                    const double dLdq = dLda * (-0.5 * r->alpha);
+                    const double A = conic[g], B = conic[N + g], Cc = conic[2 * N + g];
+#pragma omp atomic
+                    g_conic[g] += dLdq * r->dx * r->dx;
+#pragma omp atomic
+                    g_conic[N + g] += dLdq * 2.0 * r->dx * r->dy;
+#pragma omp atomic
+                    g_conic[2 * N + g] += dLdq * r->dy * r->dy;
+#pragma omp atomic
+                    g_mean2d[g] += dLdq * 2.0 * (A * r->dx + B * r->dy);
+#pragma omp atomic
+                    g_mean2d[N + g] += dLdq * 2.0 * (B * r->dx + Cc * r->dy);
+                }
+            }
+        }
+        free(rec);
+    }
 }
