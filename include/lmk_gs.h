@@ -203,6 +203,24 @@ int32_t lmk_gs_render(const lmk_gs_projected *proj, const lmk_gs_binned *binned,
                       const lmk_gs_camera *cam,
                       float *out_rgb, float *out_transmittance, void *stream);
 
+/* Gradient of a scalar loss L through stage 3 (Sec. 2.2: the rasteriser is differentiable and
+ * the parameters of the primitives are optimised through the rendering process).  Inputs:
+ * the frame as lmk_gs_render read it (proj->feat, the sorted lists and tile ranges, the
+ * camera), grad_rgb [3][height][width] = dL/d out_rgb and grad_transmittance [height][width]
+ * = dL/d out_transmittance (NULL: zero), all device pointers.  Output: grad_feat
+ * [n][LMK_GS_FEAT_STRIDE] (device, 16-byte aligned), laid out like the feature record:
+ * dL/d{u, v, A, B, C, opacity, r, g, b}, then three zeros; it is overwritten (cleared by the
+ * call, then accumulated with float atomics whose order is not fixed, so two runs agree to
+ * fp32 rounding, not bit for bit).  The thresholds of the forward walk are constants of the
+ * derivative: a skipped pair (alpha < 1/255), the pair that stopped a pixel's walk and every
+ * pair behind it get nothing, and where alpha was clamped to 0.99 it depends on neither the
+ * opacity nor the conic.  The chain from the feature record back to the 3D parameters is not
+ * part of this call.  Errors as lmk_gs_render. */
+int32_t lmk_gs_render_backward(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_binned *binned,
+                               const lmk_gs_camera *cam,
+                               const float *grad_rgb, const float *grad_transmittance,
+                               float *grad_feat, void *stream);
+
 /* Copies {pair count D, status} of the frame from scratch to the host.
  * Synchronises `stream`.  Either output pointer may be NULL. */
 int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream);

@@ -764,6 +764,10 @@ void lmk_ref_voxels_visible(const ref_camera *cam, uint32_t num_voxels, const fl
  * legitimately compute from the other decision.
  * Outputs are accumulated over all pixels in fp64: g_mean2d [2][n], g_conic [3][n],
  * g_opacity [n], g_rgb [3][n] (overwritten).  out_rgb/out_T (may be NULL): the forward image.
+ * g_abs (may be NULL) [9][n], rows u, v, A, B, C, o, r, g, b: the same sums with every term
+ * replaced by its magnitude (|dL/dC| . (T_i |c_i| + |S_i| / (1 - alpha_i)) + |dL/dT_end| T_end /
+ * (1 - alpha_i) in place of dL/dalpha_i), the scale against which an fp32 evaluation's rounding is
+ * measured.
  */
 typedef struct { uint32_t g; double alpha, gauss, dx, dy, T; int clamped_alpha, clamped_power; } ref_entry;
 
@@ -772,7 +776,7 @@ void lmk_ref_render_backward(uint32_t n, const float *mean2d, const float *conic
                              const uint32_t *sorted_vals, const uint64_t *tile_offsets,
                              const ref_camera *cam, const double *grad_rgb, const double *grad_T,
                              double *g_mean2d, double *g_conic, double *g_opacity, double *g_rgb,
-                             double *out_rgb, double *out_T, uint32_t *out_amb)
+                             double *out_rgb, double *out_T, uint32_t *out_amb, double *g_abs)
 {
     const uint32_t W = cam->width, H = cam->height, TS = cam->tile;
     const uint32_t TX = (W + TS - 1) / TS;
@@ -782,6 +786,7 @@ void lmk_ref_render_backward(uint32_t n, const float *mean2d, const float *conic
     memset(g_conic, 0, sizeof(double) * 3 * N);
     memset(g_opacity, 0, sizeof(double) * N);
     memset(g_rgb, 0, sizeof(double) * 3 * N);
+    if (g_abs) memset(g_abs, 0, sizeof(double) * 9 * N);
 #pragma omp parallel
     {
         ref_entry *rec = NULL;
@@ -843,6 +848,7 @@ void lmk_ref_render_backward(uint32_t n, const float *mean2d, const float *conic
                 const double GT = grad_T ? grad_T[p] : 0.0;
                 const double Tend = T;
                 double S[3] = { (double)cam->bg[0] * Tend, (double)cam->bg[1] * Tend, (double)cam->bg[2] * Tend };
+                double Sabs[3] = { fabs(S[0]), fabs(S[1]), fabs(S[2]) };
                 for (uint32_t e = m; e-- > 0;) {
                     const ref_entry *r = &rec[e];
                     const size_t g = r->g;
@@ -851,10 +857,34 @@ void lmk_ref_render_backward(uint32_t n, const float *mean2d, const float *conic
                     const double inv = 1.0 / (1.0 - r->alpha);
                     double dLda = -GT * Tend * inv;
                     for (int ch = 0; ch < 3; ++ch) dLda += Gc[ch] * (r->T * c[ch] - S[ch] * inv);
+                    double mag = fabs(GT) * Tend * inv;
+                    for (int ch = 0; ch < 3; ++ch) mag += fabs(Gc[ch]) * (r->T * fabs(c[ch]) + Sabs[ch] * inv);
                     for (int ch = 0; ch < 3; ++ch) {
 #pragma omp atomic
                         g_rgb[(size_t)ch * N + g] += w * Gc[ch];
+                        if (g_abs) {
+#pragma omp atomic
+                            g_abs[(size_t)(6 + ch) * N + g] += w * fabs(Gc[ch]);
+                        }
                         S[ch] += c[ch] * w;
+                        Sabs[ch] += fabs(c[ch]) * w;
+                    }
+                    if (g_abs && !r->clamped_alpha) {
+                        const double mq = r->clamped_power ? 0.0 : mag * 0.5 * r->alpha;
+                        const double Aa = fabs((double)conic[g]), Ba = fabs((double)conic[N + g]), Ca = fabs((double)conic[2 * N + g]);
+                        const double ax = fabs(r->dx), ay = fabs(r->dy);
+#pragma omp atomic
+                        g_abs[0 * N + g] += mq * 2.0 * (Aa * ax + Ba * ay);
+#pragma omp atomic
+                        g_abs[1 * N + g] += mq * 2.0 * (Ba * ax + Ca * ay);
+#pragma omp atomic
+                        g_abs[2 * N + g] += mq * ax * ax;
+#pragma omp atomic
+                        g_abs[3 * N + g] += mq * 2.0 * ax * ay;
+#pragma omp atomic
+                        g_abs[4 * N + g] += mq * ay * ay;
+#pragma omp atomic
+                        g_abs[5 * N + g] += mag * r->gauss;
                     }
                     if (r->clamped_alpha) continue;
                     const double dLdo = dLda * r->gauss;

@@ -162,7 +162,8 @@ def render(pre: SimpleNamespace, binned: SimpleNamespace, cam: dict) -> SimpleNa
 
 def render_backward(pre: SimpleNamespace, binned: SimpleNamespace, cam: dict, grad_rgb, grad_T=None) -> SimpleNamespace:
     """Gradient of a loss through the compositing, with respect to every primitive's 2D mean,
-    conic, opacity and colour; grad_rgb [3][H][W], grad_T [H][W] or None (fp64)."""
+    conic, opacity and colour; grad_rgb [3][H][W], grad_T [H][W] or None (fp64).  `abs` [9][n]
+    (rows u, v, A, B, C, o, r, g, b): the sums of the magnitudes of the terms."""
     H, W = int(cam["height"]), int(cam["width"])
     n = pre.n
     grad_rgb = np.ascontiguousarray(grad_rgb, dtype=np.float64)
@@ -171,14 +172,14 @@ def render_backward(pre: SimpleNamespace, binned: SimpleNamespace, cam: dict, gr
     out = SimpleNamespace(mean2d=np.empty((2, n), np.float64), conic=np.empty((3, n), np.float64),
                           opacity=np.empty(n, np.float64), rgb=np.empty((3, n), np.float64),
                           img_rgb=np.empty((3, H, W), np.float64), img_T=np.empty((H, W), np.float64),
-                          amb=np.empty((H, W), np.uint32))
+                          amb=np.empty((H, W), np.uint32), abs=np.empty((9, n), np.float64))
     cc = _camera(cam)
     vals = binned.vals if binned.D else np.zeros(1, np.uint32)
     lib().lmk_ref_render_backward(C.c_uint32(n), _p(pre.mean2d), _p(pre.conic), _p(pre.opacity), _p(pre.rgb),
                                   _p(vals), _p(binned.tile_offsets), C.byref(cc), _p(grad_rgb),
                                   _p(gT) if gT is not None else None,
                                   _p(out.mean2d), _p(out.conic), _p(out.opacity), _p(out.rgb),
-                                  _p(out.img_rgb), _p(out.img_T), _p(out.amb))
+                                  _p(out.img_rgb), _p(out.img_T), _p(out.amb), _p(out.abs))
     return out
 
 

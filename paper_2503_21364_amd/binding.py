@@ -23,7 +23,7 @@ PRE_BLOCK = 256
 
 EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
            "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version",
-           "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d")
+           "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward")
 
 
 class Gaussians(C.Structure):
@@ -85,12 +85,14 @@ def lib() -> C.CDLL:
         l.lmk_gs_preprocess_culled.argtypes = [C.POINTER(Gaussians), C.POINTER(VoxelIndexC), C.POINTER(Camera),
                                                C.POINTER(Projected), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.lmk_gs_build_cov3d.argtypes = [C.POINTER(Gaussians), C.c_void_p, C.c_void_p]
+        l.lmk_gs_render_backward.argtypes = [C.POINTER(Projected), C.c_uint32, C.POINTER(Binned), C.POINTER(Camera),
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.lmk_gs_read_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_void_p]
         l.lmk_gs_strerror.argtypes = [C.c_int32]
         l.lmk_gs_strerror.restype = C.c_char_p
         for name in ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
                      "lmk_gs_read_status", "lmk_gs_last_hip_error", "lmk_gs_index_build",
-                     "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d"):
+                     "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward"):
             getattr(l, name).restype = C.c_int32
         l.lmk_gs_version.restype = C.c_uint32
         _lib = l
@@ -269,6 +271,16 @@ def render(cam: Camera, frame: Frame, stream=None) -> None:
                              _ptr(frame.out_rgb), _ptr(frame.out_T), _stream_handle(stream))
     if rc != OK:
         raise LmkGsError(rc, "lmk_gs_render")
+
+
+def render_backward(cam: Camera, frame: Frame, grad_rgb, grad_T, grad_feat, stream=None) -> None:
+    """lmk_gs_render_backward on a frame that went through preprocess and bin_sort: grad_rgb
+    [3][H][W] and grad_T [H][W] (or None) float32 device tensors in, grad_feat [n][FEAT_STRIDE] out."""
+    rc = lib().lmk_gs_render_backward(C.byref(frame.proj), C.c_uint32(frame.n), C.byref(frame.binned),
+                                      C.byref(cam), _ptr(grad_rgb), _ptr(grad_T), _ptr(grad_feat),
+                                      _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_render_backward")
 
 
 def read_status(frame: Frame, stream=None) -> tuple[int, int]:

@@ -31,6 +31,7 @@ UNITS = {
     "preprocess.hip": EXACT,
     "binsort.hip": EXACT,       # the tile intersection test of binning rule 1 decides integers too
     "render.hip": [],
+    "render_bwd.hip": [],       # same options as render.hip: pass 1 repeats its arithmetic
     "index.hip": EXACT,         # host code: the voxel of a primitive is decided by one fp32 division
 }
 

@@ -169,6 +169,23 @@ int32_t lmk_gs_render(const lmk_gs_projected *proj, const lmk_gs_binned *binned,
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
 }
 
+int32_t lmk_gs_render_backward(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_binned *binned,
+                               const lmk_gs_camera *cam, const float *grad_rgb,
+                               const float *grad_transmittance, float *grad_feat, void *stream)
+{
+    ProjParams pp;
+    const int32_t rc = check_camera(cam, &pp);
+    if (rc != LMK_GS_OK) return rc;
+    if (!proj || !binned || !grad_rgb) return LMK_GS_ERR_INVALID;
+    if (n > 0 && (!grad_feat || !proj->feat)) return LMK_GS_ERR_INVALID;
+    if (!binned->tile_offsets) return LMK_GS_ERR_INVALID;
+    if (binned->capacity > 0 && !binned->vals) return LMK_GS_ERR_INVALID;
+    if (!aligned(proj->feat, 16) || !aligned(grad_feat, 16)) return LMK_GS_ERR_INVALID;
+    const hipError_t e = launch_render_backward(*proj, n, *binned, pp, grad_rgb, grad_transmittance,
+                                                grad_feat, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
 int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream)
 {
     if (!scratch) return LMK_GS_ERR_INVALID;

@@ -132,5 +132,8 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
                            char *scratch, const ScratchLayout &L, hipStream_t stream);
 hipError_t launch_render(const lmk_gs_projected &proj, const lmk_gs_binned &binned, const ProjParams &pp,
                          float *out_rgb, float *out_T, hipStream_t stream);
+hipError_t launch_render_backward(const lmk_gs_projected &proj, u32 n, const lmk_gs_binned &binned,
+                                  const ProjParams &pp, const float *grad_rgb, const float *grad_T,
+                                  float *grad_feat, hipStream_t stream);
 
 }  // namespace lmk

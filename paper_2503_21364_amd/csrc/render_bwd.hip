@@ -1,0 +1,247 @@
+// Gradient of a scalar loss through the compositing of stage 3 (Sec. 2.2 Eq. 9-10; the text
+// after them: the rasteriser is differentiable and every parameter of the primitives is
+// optimised through the rendering process).
+//
+// For a pixel whose walk composited the entries i = 1..m (T_1 = 1, T_{i+1} = T_i (1 - a_i),
+// w_i = a_i T_i, C = sum c_i w_i + bg T_{m+1}), with S_i = sum_{j>i} c_j w_j + bg T_{m+1}:
+//   dL/dc_i = w_i dL/dC
+//   dL/da_i = dL/dC . (T_i c_i - S_i / (1 - a_i)) - dL/dT_end T_end / (1 - a_i)
+//   a = o exp(-q/2), q = A dx^2 + 2 B dx dy + C dy^2:  da/do = a / o, da/dq = -a / 2
+// The thresholds of the walk are constants of the derivative: skipped entries, the entry that
+// stops the walk and everything behind it get nothing; where a was clamped to 0.99 it depends
+// on neither o nor q.
+//
+// One workgroup per 16x16 tile, one thread per pixel.  Pass 1 repeats the forward walk with the
+// arithmetic of blend_kernel (same expression for log2(alpha), same comparisons), which gives
+// every pixel its final transmittance and the position of its last composited entry.  Pass 2
+// walks the list back to front in batches of 256 entries staged in LDS: T_i is recovered as
+// T_{i+1} / (1 - a_i), S_i is a running sum.  The nine gradient components of an entry are summed
+// over the 64 pixels of a wavefront with DPP adds (only when some pixel of the wavefront has a
+// contribution), over the four wavefronts with LDS float atomics, and leave the workgroup as
+// one global float atomic per (entry, component): the order of these additions is not fixed, so
+// results differ from run to run by fp32 rounding.
+//
+// Bound by vector-instruction issue (the same exponent evaluation as the forward pass, twice,
+// plus the reductions); HBM traffic is the forward's gather plus 36 bytes of atomics per pair.
+#include "lmk_gs_internal.h"
+
+namespace lmk {
+
+namespace {
+
+constexpr u32 kBwdThreads = 256, kBwdBatch = 256;
+constexpr u32 kGradComps = 9;               // u, v, A, B, C, opacity, r, g, b
+
+struct BwdParams {
+    u32 width, height, tiles_x, num_tiles;
+    float bg0, bg1, bg2;
+};
+
+// sum over the 64 lanes of a wavefront, returned in every lane
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float wave_sum_f(float v)
+{
+    v += dpp_f<0xB1>(v);            // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E>(v);            // quad_perm [2,3,0,1]
+    v += dpp_f<0x141>(v);           // row_half_mirror: the other quad of the 8
+    v += dpp_f<0x140>(v);           // row_mirror: the other 8 of the 16
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+__global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
+    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ vals, const float4 *__restrict__ feat,
+    BwdParams bp, const float *__restrict__ grad_rgb, const float *__restrict__ grad_T,
+    float *__restrict__ grad_feat)
+{
+    // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C, lo = log2(opacity):
+    // log2(alpha) = A' dx^2 + B' dx dy + C' dy^2 + lo, exactly as blend_kernel evaluates it
+    __shared__ float4 s_geo[kBwdBatch];          // du, dv, A', B'
+    __shared__ float4 s_cop[kBwdBatch];          // C', lo, r, g
+    __shared__ float4 s_org[kBwdBatch];          // b, A, B, C
+    __shared__ float s_opa[kBwdBatch];           // opacity
+    __shared__ u32 s_id[kBwdBatch];              // primitive index
+    __shared__ float s_acc[kBwdBatch][kGradComps];
+    __shared__ u32 s_last[kBwdThreads / kWave];
+
+    const u32 tile = blockIdx.x;
+    if (tile >= bp.num_tiles) return;
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 tx = tile % bp.tiles_x, ty = tile / bp.tiles_x;
+    const u32 lx = tid & 15u, ly = tid >> 4;
+    const u32 pxi = tx * LMK_GS_TILE + lx, pyi = ty * LMK_GS_TILE + ly;
+    const bool inside = pxi < bp.width && pyi < bp.height;
+    // pixel centre relative to (X0, Y0) = tile origin + 4, the reference point of blend_kernel
+    const float ox = (float)lx - 3.5f, oy = (float)ly - 3.5f;
+    const float X0 = (float)(tx * LMK_GS_TILE) + 4.0f, Y0 = (float)(ty * LMK_GS_TILE) + 4.0f;
+    const float kL2E = 1.4426950408889634f;
+    const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
+    const u64 len64 = end - start;
+    const u32 len = len64 < 0xffffff00ull ? (u32)len64 : 0xffffff00u;     // a tile's list is far shorter
+
+    // ---- pass 1: the forward walk
+    float T = 1.0f;
+    u32 last = 0;                       // entries of the list up to and including the last composited one
+    bool done = !inside;
+    for (u32 base = 0; base < len; base += kBwdBatch) {
+        if (__syncthreads_and(done)) break;        // also: everyone is past the previous batch
+        const u32 cnt = len - base < kBwdBatch ? len - base : kBwdBatch;
+        if (tid < cnt) {
+            const u32 g = vals[start + base + tid];
+            const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
+            const float4 a = f[0], b = f[1];
+            const float A = -0.5f * kL2E * a.z, Bq = -kL2E * a.w, Cq = -0.5f * kL2E * b.x;
+            s_geo[tid] = make_float4(a.x - X0, a.y - Y0, A, Bq);
+            s_cop[tid] = make_float4(Cq, __log2f(b.y), b.z, b.w);
+        }
+        __syncthreads();
+        if (!done) {
+            for (u32 j = 0; j < cnt; ++j) {
+                const float4 g = s_geo[j];
+                const float4 co = s_cop[j];
+                const float dx = g.x - ox, dy = g.y - oy;
+                const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co.x * dy, dy, co.y));
+                const float alpha = fminf(0.99f, __builtin_amdgcn_exp2f(p));
+                const float Tn = fmaf(-T, alpha, T);
+                const bool hit = !(alpha < 1.0f / 255.0f);
+                if (hit && Tn < 1e-4f) { done = true; break; }
+                if (hit) { T = Tn; last = base + j + 1u; }
+            }
+        }
+    }
+    const float T_end = T;
+
+    // the longest walk of the tile bounds pass 2
+    u32 wl = last;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const u32 t = (u32)__shfl_xor((int)wl, o, 64);
+        wl = t > wl ? t : wl;
+    }
+    __syncthreads();                    // pass 1 is over in every wavefront: LDS is free
+    if (lane == 0) s_last[wv] = wl;
+    __syncthreads();
+    u32 max_last = 0;
+#pragma unroll
+    for (u32 k = 0; k < kBwdThreads / kWave; ++k) max_last = s_last[k] > max_last ? s_last[k] : max_last;
+    if (max_last == 0) return;
+
+    // ---- pass 2: back to front
+    const size_t plane = (size_t)bp.width * bp.height;
+    const size_t pix = (size_t)pyi * bp.width + pxi;
+    const float gr = inside ? grad_rgb[pix] : 0.0f;
+    const float gg = inside ? grad_rgb[plane + pix] : 0.0f;
+    const float gb = inside ? grad_rgb[2 * plane + pix] : 0.0f;
+    const float gT = (inside && grad_T) ? grad_T[pix] : 0.0f;
+    const float gT_end = gT * T_end;
+    float Sr = bp.bg0 * T_end, Sg = bp.bg1 * T_end, Sb = bp.bg2 * T_end;
+    T = T_end;
+    for (u32 b = (max_last + kBwdBatch - 1) / kBwdBatch; b-- > 0;) {
+        const u32 base = b * kBwdBatch;
+        const u32 cnt = max_last - base < kBwdBatch ? max_last - base : kBwdBatch;
+        __syncthreads();                // the previous batch has been flushed
+        if (tid < cnt) {
+            const u32 g = vals[start + base + tid];
+            const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
+            const float4 a = f[0], bq = f[1], c = f[2];
+            const float A = -0.5f * kL2E * a.z, Bq = -kL2E * a.w, Cq = -0.5f * kL2E * bq.x;
+            s_geo[tid] = make_float4(a.x - X0, a.y - Y0, A, Bq);
+            s_cop[tid] = make_float4(Cq, __log2f(bq.y), bq.z, bq.w);
+            s_org[tid] = make_float4(c.x, a.z, a.w, bq.x);
+            s_opa[tid] = bq.y;
+            s_id[tid] = g;
+        }
+#pragma unroll
+        for (u32 k = 0; k < kGradComps; ++k) s_acc[tid][k] = 0.0f;
+        __syncthreads();
+        for (u32 j = cnt; j-- > 0;) {
+            const float4 g = s_geo[j];
+            const float4 co = s_cop[j];
+            const float dx = g.x - ox, dy = g.y - oy;
+            const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co.x * dy, dy, co.y));
+            const float raw = __builtin_amdgcn_exp2f(p);
+            const float alpha = fminf(0.99f, raw);
+            const bool hit = base + j < last && !(alpha < 1.0f / 255.0f);
+            if (__builtin_amdgcn_ballot_w64(hit) == 0ull) continue;      // nothing from this wavefront
+            float v[kGradComps];
+#pragma unroll
+            for (u32 k = 0; k < kGradComps; ++k) v[k] = 0.0f;
+            if (hit) {
+                const float4 og = s_org[j];
+                const float inv = 1.0f / (1.0f - alpha);
+                const float Ti = T * inv;                   // transmittance in front of this entry
+                const float w = alpha * Ti;
+                const float dLda = gr * (Ti * co.z - Sr * inv) + gg * (Ti * co.w - Sg * inv)
+                                 + gb * (Ti * og.x - Sb * inv) - gT_end * inv;
+                Sr = fmaf(co.z, w, Sr); Sg = fmaf(co.w, w, Sg); Sb = fmaf(og.x, w, Sb);
+                T = Ti;
+                v[6] = w * gr; v[7] = w * gg; v[8] = w * gb;
+                if (!(raw > 0.99f)) {
+                    v[5] = dLda * (alpha / s_opa[j]);
+                    const float dLdq = -0.5f * alpha * dLda;
+                    v[2] = dLdq * dx * dx;
+                    v[3] = dLdq * 2.0f * dx * dy;
+                    v[4] = dLdq * dy * dy;
+                    v[0] = dLdq * 2.0f * (og.y * dx + og.z * dy);
+                    v[1] = dLdq * 2.0f * (og.z * dx + og.w * dy);
+                }
+            }
+#pragma unroll
+            for (u32 k = 0; k < kGradComps; ++k) {
+                const float s = wave_sum_f(v[k]);
+                if (lane == 0 && s != 0.0f) atomicAdd(&s_acc[j][k], s);
+            }
+        }
+        __syncthreads();
+        if (tid < cnt) {
+            float *out = grad_feat + (size_t)s_id[tid] * LMK_GS_FEAT_STRIDE;
+#pragma unroll
+            for (u32 k = 0; k < kGradComps; ++k) {
+                const float s = s_acc[tid][k];
+                if (s != 0.0f) atomicAdd(out + k, s);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(float4 *__restrict__ p, size_t count4)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count4; i += stride)
+        p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+}  // namespace
+
+hipError_t launch_render_backward(const lmk_gs_projected &proj, u32 n, const lmk_gs_binned &binned,
+                                  const ProjParams &pp, const float *grad_rgb, const float *grad_T,
+                                  float *grad_feat, hipStream_t stream)
+{
+    // a fill kernel, not a memset node: the call may be captured into a graph
+    const size_t count4 = (size_t)n * (LMK_GS_FEAT_STRIDE / 4);
+    if (count4 > 0) {
+        const size_t blocks = (count4 + 255) / 256;
+        hipLaunchKernelGGL(zero_kernel, dim3((u32)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, stream,
+                           reinterpret_cast<float4 *>(grad_feat), count4);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    BwdParams bp;
+    bp.width = pp.cam.width; bp.height = pp.cam.height;
+    bp.tiles_x = pp.tiles_x; bp.num_tiles = pp.tiles_x * pp.tiles_y;
+    bp.bg0 = pp.cam.bg[0]; bp.bg1 = pp.cam.bg[1]; bp.bg2 = pp.cam.bg[2];
+    if (n == 0 || binned.capacity == 0) return hipSuccess;
+    hipLaunchKernelGGL(blend_backward_kernel, dim3(bp.num_tiles), dim3(kBwdThreads), 0, stream,
+                       binned.tile_offsets, binned.vals, reinterpret_cast<const float4 *>(proj.feat), bp,
+                       grad_rgb, grad_T, grad_feat);
+    return hipGetLastError();
+}
+
+}  // namespace lmk

@@ -141,6 +141,17 @@ def test_bin_sort_and_render_reject_bad_arguments():
     bad = _good_camera(); bad.tile = 32
     assert rd(proj, binned, bad) == B.ERR_UNSUPPORTED
     assert lib.lmk_gs_read_status(None, None, None, None) == B.ERR_INVALID
+    # the gradient call checks its arguments the same way, before any HIP call
+    rb = lambda p_, b_, c_, g1=_fake(), g2=_fake(), out=_fake(): lib.lmk_gs_render_backward(
+        None if p_ is None else C.byref(p_), 100, None if b_ is None else C.byref(b_),
+        None if c_ is None else C.byref(c_), g1, g2, out, None)
+    assert rb(None, binned, cam) == B.ERR_INVALID
+    assert rb(proj, None, cam) == B.ERR_INVALID
+    assert rb(proj, binned, None) == B.ERR_INVALID
+    assert rb(proj, binned, cam, None) == B.ERR_INVALID          # dL/d rgb is required, dL/dT is not
+    assert rb(proj, binned, cam, _fake(), None, None) == B.ERR_INVALID
+    assert rb(proj, binned, cam, _fake(), None, 0x1004) == B.ERR_INVALID   # grad_feat must be 16-byte aligned
+    assert rb(proj, binned, bad) == B.ERR_UNSUPPORTED
 
 
 def test_index_build_matches_the_oracle_and_rejects_bad_input():

@@ -1,0 +1,140 @@
+"""Parity of lmk_gs_render_backward with the oracle's gradient through the compositing
+(Sec. 2.2 Eq. 9-10 and the text after them).  Tolerance, written here: the kernel evaluates the
+same sums in fp32, recovering T_i as T_{i+1} / (1 - alpha_i) and adding terms in an order that is
+not fixed; every term carries a relative rounding error of a few 2^-24 per composited entry in front
+of it (the error of T), so a component may differ from the fp64 value by up to
+RTOL x (sum of the magnitudes of its terms, which the oracle reports) with RTOL = 2e-5 -- a few
+2^-24 for each of a hundred composited entries; the largest ratio seen is 1.6e-6 -- plus 1e-7.  A pixel holding a decision within rounding of its
+threshold may legitimately take the other one: primitives that can contribute at such a pixel are
+left out of the comparison (their share is checked to be small)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2503_21364_amd import binding as B, scenes
+import parity as P
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 2e-5, 1e-7
+
+
+def _compare(sc, cam, seed, with_T=True, max_excluded=0.4):
+    H, W = int(cam["height"]), int(cam["width"])
+    ofr = ref.render_frame(sc, cam)
+    rng = np.random.default_rng(seed)
+    Gc = rng.normal(size=(3, H, W)).astype(np.float32)
+    GT = rng.normal(size=(H, W)).astype(np.float32) if with_T else None
+    g = ref.render_backward(ofr.pre, ofr.binned, cam, Gc.astype(np.float64),
+                            None if GT is None else GT.astype(np.float64))
+    dev = B.Scene(sc)
+    fr = P.gpu_frame(dev, cam, ofr.binned.D + 100)
+    P.compare_binned(fr, ofr.binned)                     # the lists the gradient walks are the oracle's
+    c = B.make_camera(cam)
+    d_rgb = torch.from_numpy(Gc).cuda()
+    d_T = None if GT is None else torch.from_numpy(GT).cuda()
+    out = torch.full((max(sc["n"], 1), B.FEAT_STRIDE), 7.0, dtype=torch.float32, device="cuda")   # must be overwritten
+    B.render_backward(c, fr, d_rgb, d_T, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)[: sc["n"]]
+    assert not got[:, 9:].any()
+    got = got[:, :9]
+    want = np.concatenate([g.mean2d, g.conic, g.opacity[None, :], g.rgb]).T      # [n][9]
+    scale = g.abs.T
+    # a primitive that can contribute (alpha near or above 1/255) at a pixel holding an ambiguous
+    # decision is not compared: that pixel's share of its gradient depends on the decision
+    TS = 16
+    tiles_x = (W + TS - 1) // TS
+    excluded = np.zeros(sc["n"], bool)
+    off = ofr.binned.tile_offsets.astype(np.int64)
+    pre = ofr.pre
+    ys, xs = np.nonzero(g.amb)
+    for y, x in zip(ys, xs):
+        t = (y // TS) * tiles_x + x // TS
+        ids = ofr.binned.vals[off[t]:off[t + 1]].astype(np.int64)
+        dx = pre.mean2d[0, ids].astype(np.float64) - (x + 0.5)
+        dy = pre.mean2d[1, ids].astype(np.float64) - (y + 0.5)
+        q = pre.conic[0, ids] * dx * dx + 2.0 * pre.conic[1, ids] * dx * dy + pre.conic[2, ids] * dy * dy
+        alpha = pre.opacity[ids] * np.exp(-0.5 * np.maximum(q, 0.0))
+        excluded[ids[alpha >= 0.9 / 255.0]] = True
+    touched = scale.sum(1) > 0
+    assert touched.sum() > 0
+    share = (excluded & touched).sum() / touched.sum()
+    assert share <= max_excluded, share
+    keep = ~excluded
+    err = np.abs(got - want)
+    tol = RTOL * scale + ATOL
+    bad = (err > tol) & keep[:, None]
+    if bad.any():
+        i, k = np.argwhere(bad)[0]
+        raise AssertionError(f"{bad.sum()} components beyond tolerance; first: primitive {i} component {k}: "
+                             f"got {got[i, k]:.6e} want {want[i, k]:.6e} scale {scale[i, k]:.3e}")
+    # primitives the oracle gives nothing get exactly nothing
+    assert not got[keep & ~touched].any()
+    rel = (err[keep] / (scale[keep] + 1e-30))[scale[keep] > 1e-6]
+    return dict(n=sc["n"], D=int(ofr.binned.D), compared=int(keep.sum()), excluded_share=float(share),
+                worst_rel=float(rel.max()) if rel.size else 0.0, median_rel=float(np.median(rel)) if rel.size else 0.0)
+
+
+@pytest.mark.parametrize("w,h,n,seed,scale_mul", [
+    (64, 48, 300, 3, 3.0),          # the frame of the finite-difference pin
+    (37, 23, 1000, 5, 2.0),         # ragged tiles, pixels outside the image in every edge tile
+    (200, 120, 4000, 7, 3.0),       # lists of several batches
+    (16, 16, 3000, 9, 1.0),         # one tile, a long list: many batches back to front
+])
+def test_small_frames(w, h, n, seed, scale_mul):
+    sc = scenes.make_scene(0, n=n, seed=seed)
+    sc["scale"] = sc["scale"] * np.float32(scale_mul)
+    cam = dict(scenes.make_cameras(0, w, h)[0])
+    cam["bg"] = np.array([0.3, 0.1, 0.2], np.float32)
+    st = _compare(sc, cam, seed)
+    print(f"[backward] {w}x{h} n={n}: {st}", flush=True)
+
+
+def test_cfg0_and_no_transmittance_gradient():
+    sc = scenes.make_scene(0)
+    cam = scenes.make_cameras(0)[0]
+    st = _compare(sc, cam, 21, with_T=False)
+    print(f"[backward] cfg0: {st}", flush=True)
+
+
+def test_opaque_and_saturating_splats():
+    """Opacity 1 in the centre (alpha clamped to 0.99) and walks that stop early."""
+    sc = scenes.make_scene(0, n=2000, seed=13)
+    sc["scale"] = sc["scale"] * np.float32(4.0)
+    sc["opacity"] = np.where(np.arange(sc["n"]) % 3 == 0, np.float32(1.0), sc["opacity"]).astype(np.float32)
+    cam = scenes.make_cameras(0, 96, 64)[0]
+    st = _compare(sc, cam, 13)
+    print(f"[backward] opaque: {st}", flush=True)
+
+
+def test_empty_frame_clears_the_output():
+    sc = scenes.make_scene(0, n=50, seed=2)
+    sc["mean"][2] += 100.0          # everything behind the camera
+    cam = scenes.make_cameras(0, 64, 64)[0]
+    dev = B.Scene(sc)
+    fr = P.gpu_frame(dev, cam, 1000)
+    out = torch.full((50, B.FEAT_STRIDE), 3.0, dtype=torch.float32, device="cuda")
+    B.render_backward(B.make_camera(cam), fr, torch.ones(3, 64, 64, device="cuda"), None, out)
+    torch.cuda.synchronize()
+    assert not out.any().item()
+
+
+def test_weights_sum_to_one_at_full_size_cfg1():
+    """At a size the oracle's gradient is not run: with dL/dC = 1 on one channel the colour gradients
+    of that channel add up to (pixels) - sum of the final transmittance of the forward image."""
+    sc = scenes.make_scene(1)
+    cam = scenes.make_cameras(1)[0]
+    dev = B.Scene(sc)
+    fr = B.Frame(sc["n"], int(cam["width"]), int(cam["height"]), 6_000_000)
+    c = B.make_camera(cam)
+    B.render_frame(dev, c, fr)
+    H, W = int(cam["height"]), int(cam["width"])
+    Gc = torch.zeros(3, H, W, device="cuda"); Gc[2] = 1.0
+    out = torch.empty(sc["n"], B.FEAT_STRIDE, dtype=torch.float32, device="cuda")
+    B.render_backward(c, fr, Gc, None, out)
+    torch.cuda.synchronize()
+    total = out[:, 8].double().sum().item() + fr.out_T.double().sum().item()
+    assert abs(total - H * W) < 2e-4 * H * W, total
+    assert not out[:, 6].any().item() and not out[:, 7].any().item()

@@ -169,3 +169,14 @@ def test_two_splats_order_matters_as_in_the_closed_form():
     np.testing.assert_allclose(g.opacity, [1.0 - bb, 1.0 - a], rtol=1e-12)
     np.testing.assert_allclose(g.rgb[:, 0], [a, a, a], rtol=1e-12)
     np.testing.assert_allclose(g.rgb[:, 1], [bb * (1 - a)] * 3, rtol=1e-12)
+
+
+def test_magnitude_sums_bound_the_gradients():
+    sc, cam, pre, b = _frame(n=500, seed=5)
+    H, W = cam["height"], cam["width"]
+    rng = np.random.default_rng(5)
+    g = ref.render_backward(pre, b, cam, rng.normal(size=(3, H, W)), rng.normal(size=(H, W)))
+    signed = np.concatenate([g.mean2d, g.conic, g.opacity[None, :], g.rgb])
+    assert signed.shape == g.abs.shape
+    assert (np.abs(signed) <= g.abs * (1 + 1e-12) + 1e-300).all()
+    assert (g.abs[:, np.abs(signed).sum(0) > 0] > 0).any()
