@@ -107,6 +107,9 @@ def main():
                     help="edge of the voxels for the offline spatial reordering + per-frame view-frustum filtering "
                          "of voxels (default: a size per configuration; 0 = primitives in the order drawn, "
                          "no filtering)")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time lmk_gs_render_backward (gradient through the compositing) on every viewpoint "
+                         "and add a \"backward\" object to the JSON line; the headline value is unchanged")
     ap.add_argument("--no-cov-cache", action="store_true",
                     help="compute every primitive's 3D covariance from rotation and scale in every frame instead "
                          "of reading the parameter cache built once per scene")
@@ -229,6 +232,29 @@ def main():
     # ---- CPU oracle: counts E, C (algorithmic pairs) and the baseline time
     cpu = None
     E = C = None
+    bwd_ms = None
+    if args.backward:
+        # per viewpoint: the forward frame once (not timed), then the gradient call a few times with
+        # HIP events around it; random dL/d rgb and dL/dT, resident before the timed region
+        gen = torch.Generator(device="cuda"); gen.manual_seed(1)
+        g_rgb = torch.randn(3, H, W, device="cuda", generator=gen)
+        g_T = torch.randn(H, W, device="cuda", generator=gen)
+        g_feat = torch.empty(max(n, 1), B.FEAT_STRIDE, dtype=torch.float32, device="cuda")
+        reps = 5
+        bwd_ms = []
+        for v in range(nviews):
+            B.render_frame(dev, ccams[v], fr, index=index)
+            B.render_backward(ccams[v], fr, g_rgb, g_T, g_feat)          # warm-up
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(reps):
+                B.render_backward(ccams[v], fr, g_rgb, g_T, g_feat)
+            e1.record()
+            torch.cuda.synchronize()
+            bwd_ms.append(e0.elapsed_time(e1) / reps)
+        del g_rgb, g_T, g_feat
+
     n_near = None
     if not args.no_cpu_baseline:
         from oracle import ref
@@ -308,7 +334,24 @@ def main():
                                       "frac": gbs / HBM_PEAK_GBS, "traffic": traffic.get("preprocess+bin_sort"),
                                       "preprocess_GBs": gbs_pre, "bin_sort_GBs": gbs_sort,
                                       "bytes_per_frame": float(byts.mean())}
+        if bwd_ms is not None:
+            # algorithmic flops of the gradient call: both passes evaluate alpha for every visited pair
+            # (14 E each, E as counted by the oracle), pass 1 also composites (10 C), pass 2 spends 45 per
+            # composited pair (1 / (1 - alpha), T_i, w: 4; dL/dalpha: 14; S and the colour gradient: 9;
+            # opacity, conic and mean gradients: 18)
+            bflops = 28.0 * Ev + 55.0 * Cv
+            btf = bflops.sum() / (sum(bwd_ms) * 1e-3) / 1e12
+            out["backward"] = {"entry": "lmk_gs_render_backward", "ms_per_call": float(np.mean(bwd_ms)),
+                               "per_view_ms": [float(x) for x in bwd_ms],
+                               "pairs_per_s": float(Ev.sum() / (sum(bwd_ms) * 1e-3)),
+                               "roofline": {"kernel": "blend_backward_kernel", "bound": "alu", "achieved": btf,
+                                            "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                            "frac": btf / FP32_PEAK_TFLOPS, "traffic": None,
+                                            "flops_per_launch": float(bflops.mean())}}
         out["cpu_baseline"] = cpu
+    elif bwd_ms is not None:
+        out["backward"] = {"entry": "lmk_gs_render_backward", "ms_per_call": float(np.mean(bwd_ms)),
+                           "per_view_ms": [float(x) for x in bwd_ms]}
     print(json.dumps(out), flush=True)
 
 

@@ -36,6 +36,7 @@
 // progress, Sec. 4.2.1); the tile leaves when all four have.  Bound by FP32
 // VALU issue; HBM traffic is the 52 bytes per list entry of the gather.
 #include "lmk_gs_internal.h"
+#include "blend_reach.h"
 
 namespace lmk {
 
@@ -64,28 +65,6 @@ __device__ __forceinline__ Rec fetch_record(const u32 *__restrict__ vals, const 
         r.a = r.b = r.c = make_float4(0.f, 0.f, 0.f, 0.f);
     }
     return r;
-}
-
-__device__ __forceinline__ float clamp_pm(float v, float h) { return __builtin_amdgcn_fmed3f(v, -h, h); }
-
-// Upper bound, with the rounding margin folded in, of A' dx^2 + B' dx dy + C' dy^2 over the
-// square [-half, half]^2 about a centre from which the splat centre lies at (xs, ys).
-// t.x = -B'/(2A'), t.y = -B'/(2C').
-__device__ __forceinline__ float square_reach(float xs, float ys, float Aq, float Bq, float Cq,
-                                              float tx, float ty, float half)
-{
-    const float kRelMargin = -2e-6f;    // times (A' ex^2 + C' ey^2) <= 0: covers fp32 rounding of the test
-    // candidate 1: x clamped into the square, best y on that vertical line
-    const float ex1 = clamp_pm(xs, half) - xs;
-    const float ey1 = clamp_pm(fmaf(ty, ex1, ys), half) - ys;
-    const float m1 = fmaf(Aq * ex1, ex1, Cq * ey1 * ey1);
-    const float p1 = fmaf(Bq * ex1, ey1, m1);
-    // candidate 2: y clamped, best x on that horizontal line
-    const float ey2 = clamp_pm(ys, half) - ys;
-    const float ex2 = clamp_pm(fmaf(tx, ey2, xs), half) - xs;
-    const float m2 = fmaf(Aq * ex2, ex2, Cq * ey2 * ey2);
-    const float p2 = fmaf(Bq * ex2, ey2, m2);
-    return fmaxf(fmaf(m1, kRelMargin, p1), fmaf(m2, kRelMargin, p2));
 }
 
 constexpr u32 kListLen = kBatch + 8;    // survivors of a batch plus null padding
@@ -136,8 +115,7 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     float T = 1.0f, cr = 0.0f, cg = 0.0f, cb = 0.0f;
     bool done = !inside;
     const float kL2E = 1.4426950408889634f;
-    // block test: log2(alpha_max) >= log2(1/255) - margin, i.e. alpha down to 0.99990/255 passes
-    const float kPass = -7.994353436858858f - 1.5e-4f;
+    const float kPass = kBlockPass;
     constexpr u32 kNullOfs = kBatch * 16u;
 
     if (tid == 0) {

@@ -11,19 +11,24 @@
 // stops the walk and everything behind it get nothing; where a was clamped to 0.99 it depends
 // on neither o nor q.
 //
-// One workgroup per 16x16 tile, one thread per pixel.  Pass 1 repeats the forward walk with the
-// arithmetic of blend_kernel (same expression for log2(alpha), same comparisons), which gives
-// every pixel its final transmittance and the position of its last composited entry.  Pass 2
-// walks the list back to front in batches of 256 entries staged in LDS: T_i is recovered as
+// One workgroup per 16x16 tile, one thread per pixel, each wavefront an 8x8 block.  Entries are
+// staged in LDS in batches of 256.  Per batch every wavefront first tests, one entry per lane,
+// which entries can reach alpha >= 1/255 anywhere in its block (the block test of blend_kernel)
+// and keeps their slots in a list; its pixels then only walk that list.  Pass 1 repeats the
+// forward walk with the arithmetic of blend_kernel (same expression for log2(alpha), same
+// comparisons), which gives every pixel its final transmittance and the position of its last
+// composited entry.  Pass 2 takes the batches, and each list, back to front: T_i is recovered as
 // T_{i+1} / (1 - a_i), S_i is a running sum.  The nine gradient components of an entry are summed
-// over the 64 pixels of a wavefront with DPP adds (only when some pixel of the wavefront has a
-// contribution), over the four wavefronts with LDS float atomics, and leave the workgroup as
-// one global float atomic per (entry, component): the order of these additions is not fixed, so
-// results differ from run to run by fp32 rounding.
+// over the 16 lanes of a row with DPP adds (only when some pixel of the wavefront has a
+// contribution), over the sixteen rows of the tile with LDS float atomics, and leave the
+// workgroup as one global float atomic per (entry, component): the order of these additions is
+// not fixed, so results differ from run to run by fp32 rounding.
 //
-// Bound by vector-instruction issue (the same exponent evaluation as the forward pass, twice,
-// plus the reductions); HBM traffic is the forward's gather plus 36 bytes of atomics per pair.
+// Bound by vector-instruction issue (the exponent evaluation of the forward pass, twice, the
+// gradient arithmetic and the reductions); HBM traffic is the forward's gather, twice, plus 36
+// bytes of atomics per pair.
 #include "lmk_gs_internal.h"
+#include "blend_reach.h"
 
 namespace lmk {
 
@@ -37,54 +42,110 @@ struct BwdParams {
     float bg0, bg1, bg2;
 };
 
-// sum over the 64 lanes of a wavefront, returned in every lane
+// sum over the 16 lanes of a row, returned in every lane of the row
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v)
 {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
-__device__ __forceinline__ float wave_sum_f(float v)
+__device__ __forceinline__ void row_sums(float (&v)[kGradComps])
 {
-    v += dpp_f<0xB1>(v);            // quad_perm [1,0,3,2]
-    v += dpp_f<0x4E>(v);            // quad_perm [2,3,0,1]
-    v += dpp_f<0x141>(v);           // row_half_mirror: the other quad of the 8
-    v += dpp_f<0x140>(v);           // row_mirror: the other 8 of the 16
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-    return (r0 + r1) + (r2 + r3);
+#pragma unroll
+    for (u32 c = 0; c < kGradComps; ++c) v[c] += dpp_f<0xB1>(v[c]);     // quad_perm [1,0,3,2]
+#pragma unroll
+    for (u32 c = 0; c < kGradComps; ++c) v[c] += dpp_f<0x4E>(v[c]);     // quad_perm [2,3,0,1]
+#pragma unroll
+    for (u32 c = 0; c < kGradComps; ++c) v[c] += dpp_f<0x141>(v[c]);    // row_half_mirror: the other quad of the 8
+#pragma unroll
+    for (u32 c = 0; c < kGradComps; ++c) v[c] += dpp_f<0x140>(v[c]);    // row_mirror: the other 8 of the 16
+}
+
+// the survivors of one batch for one wavefront: slots of the entries that pass the block test
+__device__ __forceinline__ u32 block_survivors(const float4 *s_geo, const float4 *s_cop, const float4 *s_tst,
+                                               u32 cnt, float bx, float by, u32 lane, unsigned short *list)
+{
+    u32 n8 = 0;
+    for (u32 c0 = 0; c0 < cnt; c0 += kWave) {
+        const u32 e = c0 + lane;
+        const float4 g = s_geo[e < cnt ? e : 0u];
+        const float4 t = s_tst[e < cnt ? e : 0u];
+        const float4 co = s_cop[e < cnt ? e : 0u];
+        const float best = square_reach(g.x - bx, g.y - by, g.z, g.w, co.x, t.x, t.y, 3.5f);
+        const bool pass = e < cnt && best + co.y >= kBlockPass;
+        const u64 mask = __builtin_amdgcn_ballot_w64(pass);
+        const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+        if (pass) list[n8 + rank] = (unsigned short)e;
+        n8 += (u32)__builtin_popcountll(mask);
+    }
+    return n8;
+}
+
+// ... and of those, per 4x4 sub-block (the 16 lanes of a row), the ones that can reach it: one
+// survivor per lane, tested against the four sub-blocks; list order is kept
+__device__ __forceinline__ void subblock_survivors(const float4 *s_geo, const float4 *s_cop, const float4 *s_tst,
+                                                   const unsigned short *list8, u32 n8, float bx, float by, u32 lane,
+                                                   unsigned short (*list4)[kBwdBatch], u32 (&n4)[4])
+{
+    n4[0] = n4[1] = n4[2] = n4[3] = 0u;
+    for (u32 k0 = 0; k0 < n8; k0 += kWave) {
+        const u32 k = k0 + lane;
+        const bool valid = k < n8;
+        const u32 e = valid ? (u32)list8[k] : 0u;
+        const float4 g = s_geo[e];
+        const float4 t = s_tst[e];
+        const float4 co = s_cop[e];
+        const float xs = g.x - bx, ys = g.y - by;
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q) {
+            const float qx = (q & 1u) ? 2.0f : -2.0f, qy = (q >> 1) ? 2.0f : -2.0f;
+            const float best = square_reach(xs - qx, ys - qy, g.z, g.w, co.x, t.x, t.y, 1.5f);
+            const bool pass = valid && best + co.y >= kBlockPass;
+            const u64 mask = __builtin_amdgcn_ballot_w64(pass);
+            const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+            if (pass) list4[q][n4[q] + rank] = (unsigned short)e;
+            n4[q] += (u32)__builtin_popcountll(mask);
+        }
+    }
 }
 
 __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
-    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ vals, const float4 *__restrict__ feat,
-    BwdParams bp, const float *__restrict__ grad_rgb, const float *__restrict__ grad_T,
-    float *__restrict__ grad_feat)
+    const u64 *__restrict__ tile_offsets, const u32 *__restrict__ tile_order, const u32 *__restrict__ vals,
+    const float4 *__restrict__ feat, BwdParams bp, const float *__restrict__ grad_rgb,
+    const float *__restrict__ grad_T, float *__restrict__ grad_feat)
 {
     // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C, lo = log2(opacity):
     // log2(alpha) = A' dx^2 + B' dx dy + C' dy^2 + lo, exactly as blend_kernel evaluates it
     __shared__ float4 s_geo[kBwdBatch];          // du, dv, A', B'
     __shared__ float4 s_cop[kBwdBatch];          // C', lo, r, g
-    __shared__ float4 s_org[kBwdBatch];          // b, A, B, C
-    __shared__ float s_opa[kBwdBatch];           // opacity
+    __shared__ float4 s_tst[kBwdBatch];          // -B'/(2A'), -B'/(2C'), b, 1 / opacity
+    __shared__ float4 s_org[kBwdBatch];          // A, B, C, -
     __shared__ u32 s_id[kBwdBatch];              // primitive index
     __shared__ float s_acc[kBwdBatch][kGradComps];
+    __shared__ unsigned short s_list[kBwdThreads / kWave][kBwdBatch];
+    __shared__ unsigned short s_list4[kBwdThreads / kWave][4][kBwdBatch];
     __shared__ u32 s_last[kBwdThreads / kWave];
 
-    const u32 tile = blockIdx.x;
+    if (blockIdx.x >= bp.num_tiles) return;
+    // the tiles with the longest lists first, when the caller has the hint
+    const u32 tile = tile_order ? tile_order[blockIdx.x] : blockIdx.x;
     if (tile >= bp.num_tiles) return;
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const u32 tx = tile % bp.tiles_x, ty = tile / bp.tiles_x;
-    const u32 lx = tid & 15u, ly = tid >> 4;
-    const u32 pxi = tx * LMK_GS_TILE + lx, pyi = ty * LMK_GS_TILE + ly;
+    const u32 grp = lane >> 4, gl = lane & 15u;                    // 4x4 sub-block of the lane, pixel inside it
+    const u32 bi = (grp & 1u) * 4u + (gl & 3u), bj = (grp >> 1) * 4u + (gl >> 2);   // pixel inside the 8x8 block
+    const u32 pxi = tx * LMK_GS_TILE + (wv & 1u) * 8u + bi, pyi = ty * LMK_GS_TILE + (wv >> 1) * 8u + bj;
     const bool inside = pxi < bp.width && pyi < bp.height;
-    // pixel centre relative to (X0, Y0) = tile origin + 4, the reference point of blend_kernel
-    const float ox = (float)lx - 3.5f, oy = (float)ly - 3.5f;
+    // (X0, Y0) = centre of block 0, the reference point of blend_kernel; this block's centre and this
+    // lane's pixel centre relative to it
+    const float bx = (float)((wv & 1u) * 8u), by = (float)((wv >> 1) * 8u);
+    const float ox = bx + ((float)bi - 3.5f), oy = by + ((float)bj - 3.5f);
     const float X0 = (float)(tx * LMK_GS_TILE) + 4.0f, Y0 = (float)(ty * LMK_GS_TILE) + 4.0f;
     const float kL2E = 1.4426950408889634f;
     const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
     const u64 len64 = end - start;
     const u32 len = len64 < 0xffffff00ull ? (u32)len64 : 0xffffff00u;     // a tile's list is far shorter
+    unsigned short *my_list = s_list[wv];
+    const unsigned short *my_list4 = s_list4[wv][grp];
 
     // ---- pass 1: the forward walk
     float T = 1.0f;
@@ -100,25 +161,35 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
             const float A = -0.5f * kL2E * a.z, Bq = -kL2E * a.w, Cq = -0.5f * kL2E * b.x;
             s_geo[tid] = make_float4(a.x - X0, a.y - Y0, A, Bq);
             s_cop[tid] = make_float4(Cq, __log2f(b.y), b.z, b.w);
+            s_tst[tid] = make_float4(-Bq / (2.0f * A), -Bq / (2.0f * Cq), 0.0f, 0.0f);
         }
         __syncthreads();
-        if (!done) {
-            for (u32 j = 0; j < cnt; ++j) {
-                const float4 g = s_geo[j];
-                const float4 co = s_cop[j];
-                const float dx = g.x - ox, dy = g.y - oy;
-                const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co.x * dy, dy, co.y));
-                const float alpha = fminf(0.99f, __builtin_amdgcn_exp2f(p));
-                const float Tn = fmaf(-T, alpha, T);
-                const bool hit = !(alpha < 1.0f / 255.0f);
-                if (hit && Tn < 1e-4f) { done = true; break; }
-                if (hit) { T = Tn; last = base + j + 1u; }
-            }
+        if (__builtin_amdgcn_ballot_w64(!done) == 0ull) continue;     // this wavefront is finished
+        const u32 n8 = block_survivors(s_geo, s_cop, s_tst, cnt, bx, by, lane, my_list);
+        u32 n4[4];
+        subblock_survivors(s_geo, s_cop, s_tst, my_list, n8, bx, by, lane, s_list4[wv], n4);
+        const u32 n_mine = grp == 0u ? n4[0] : (grp == 1u ? n4[1] : (grp == 2u ? n4[2] : n4[3]));
+        const u32 l01 = n4[0] > n4[1] ? n4[0] : n4[1], l23 = n4[2] > n4[3] ? n4[2] : n4[3];
+        const u32 longest = l01 > l23 ? l01 : l23;
+        for (u32 k = 0; k < longest; ++k) {
+            const bool in_list = k < n_mine;
+            const u32 j = (u32)my_list4[in_list ? k : 0u] & (kBwdBatch - 1u);
+            const float4 g = s_geo[j];
+            const float4 co = s_cop[j];
+            const float dx = g.x - ox, dy = g.y - oy;
+            const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co.x * dy, dy, co.y));
+            const float alpha = fminf(0.99f, __builtin_amdgcn_exp2f(p));
+            const float Tn = fmaf(-T, alpha, T);
+            const bool hit = in_list && !done && !(alpha < 1.0f / 255.0f);
+            const bool stop = hit && Tn < 1e-4f;
+            if (hit && !stop) { T = Tn; last = base + j + 1u; }
+            done = done || stop;
+            if (__builtin_amdgcn_ballot_w64(!done) == 0ull) break;     // all 64 pixels stopped
         }
     }
     const float T_end = T;
 
-    // the longest walk of the tile bounds pass 2
+    // the longest walk of each wavefront and of the tile bound pass 2
     u32 wl = last;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -143,6 +214,7 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     const float gT_end = gT * T_end;
     float Sr = bp.bg0 * T_end, Sg = bp.bg1 * T_end, Sb = bp.bg2 * T_end;
     T = T_end;
+    const bool row_leader = (lane & 15u) == 0u;
     for (u32 b = (max_last + kBwdBatch - 1) / kBwdBatch; b-- > 0;) {
         const u32 base = b * kBwdBatch;
         const u32 cnt = max_last - base < kBwdBatch ? max_last - base : kBwdBatch;
@@ -154,58 +226,73 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
             const float A = -0.5f * kL2E * a.z, Bq = -kL2E * a.w, Cq = -0.5f * kL2E * bq.x;
             s_geo[tid] = make_float4(a.x - X0, a.y - Y0, A, Bq);
             s_cop[tid] = make_float4(Cq, __log2f(bq.y), bq.z, bq.w);
-            s_org[tid] = make_float4(c.x, a.z, a.w, bq.x);
-            s_opa[tid] = bq.y;
+            s_tst[tid] = make_float4(-Bq / (2.0f * A), -Bq / (2.0f * Cq), c.x, 1.0f / bq.y);
+            s_org[tid] = make_float4(a.z, a.w, bq.x, 0.0f);
             s_id[tid] = g;
         }
 #pragma unroll
         for (u32 k = 0; k < kGradComps; ++k) s_acc[tid][k] = 0.0f;
         __syncthreads();
-        for (u32 j = cnt; j-- > 0;) {
+        // a wavefront none of whose pixels walked this far has nothing to add (it still takes part
+        // in the barriers and the flush below)
+        const u32 n8 = base < wl ? block_survivors(s_geo, s_cop, s_tst, cnt, bx, by, lane, my_list) : 0u;
+        u32 n4[4];
+        subblock_survivors(s_geo, s_cop, s_tst, my_list, n8, bx, by, lane, s_list4[wv], n4);
+        const u32 n_mine = grp == 0u ? n4[0] : (grp == 1u ? n4[1] : (grp == 2u ? n4[2] : n4[3]));
+        const u32 l01 = n4[0] > n4[1] ? n4[0] : n4[1], l23 = n4[2] > n4[3] ? n4[2] : n4[3];
+        const u32 longest = l01 > l23 ? l01 : l23;
+        for (u32 k = longest; k-- > 0;) {
+            const bool in_list = k < n_mine;
+            const u32 j = (u32)my_list4[in_list ? k : 0u] & (kBwdBatch - 1u);    // the same for the 16 lanes of a row
             const float4 g = s_geo[j];
             const float4 co = s_cop[j];
             const float dx = g.x - ox, dy = g.y - oy;
             const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co.x * dy, dy, co.y));
             const float raw = __builtin_amdgcn_exp2f(p);
             const float alpha = fminf(0.99f, raw);
-            const bool hit = base + j < last && !(alpha < 1.0f / 255.0f);
-            if (__builtin_amdgcn_ballot_w64(hit) == 0ull) continue;      // nothing from this wavefront
+            const bool hit = in_list && base + j < last && !(alpha < 1.0f / 255.0f);
+            const u64 hits = __builtin_amdgcn_ballot_w64(hit);
+            if (hits == 0ull) continue;                                  // nothing from this wavefront
             float v[kGradComps];
 #pragma unroll
-            for (u32 k = 0; k < kGradComps; ++k) v[k] = 0.0f;
+            for (u32 c = 0; c < kGradComps; ++c) v[c] = 0.0f;
             if (hit) {
                 const float4 og = s_org[j];
-                const float inv = 1.0f / (1.0f - alpha);
+                const float4 ts = s_tst[j];
+                const float inv = __builtin_amdgcn_rcpf(1.0f - alpha);     // 1 - alpha >= 0.01; one ulp is enough here
                 const float Ti = T * inv;                   // transmittance in front of this entry
                 const float w = alpha * Ti;
                 const float dLda = gr * (Ti * co.z - Sr * inv) + gg * (Ti * co.w - Sg * inv)
-                                 + gb * (Ti * og.x - Sb * inv) - gT_end * inv;
-                Sr = fmaf(co.z, w, Sr); Sg = fmaf(co.w, w, Sg); Sb = fmaf(og.x, w, Sb);
+                                 + gb * (Ti * ts.z - Sb * inv) - gT_end * inv;
+                Sr = fmaf(co.z, w, Sr); Sg = fmaf(co.w, w, Sg); Sb = fmaf(ts.z, w, Sb);
                 T = Ti;
                 v[6] = w * gr; v[7] = w * gg; v[8] = w * gb;
                 if (!(raw > 0.99f)) {
-                    v[5] = dLda * (alpha / s_opa[j]);
+                    v[5] = dLda * (alpha * ts.w);
                     const float dLdq = -0.5f * alpha * dLda;
                     v[2] = dLdq * dx * dx;
                     v[3] = dLdq * 2.0f * dx * dy;
                     v[4] = dLdq * dy * dy;
-                    v[0] = dLdq * 2.0f * (og.y * dx + og.z * dy);
-                    v[1] = dLdq * 2.0f * (og.z * dx + og.w * dy);
+                    v[0] = dLdq * 2.0f * (og.x * dx + og.y * dy);
+                    v[1] = dLdq * 2.0f * (og.y * dx + og.z * dy);
                 }
             }
+            // the nine row sums side by side (independent DPP chains), then one guarded group of
+            // LDS atomics from the first lane of every row that had a contribution
+            row_sums(v);
+            const bool row_hit = ((hits >> (lane & 48u)) & 0xffffull) != 0ull;
+            if (row_leader && row_hit) {
 #pragma unroll
-            for (u32 k = 0; k < kGradComps; ++k) {
-                const float s = wave_sum_f(v[k]);
-                if (lane == 0 && s != 0.0f) atomicAdd(&s_acc[j][k], s);
+                for (u32 c = 0; c < kGradComps; ++c) atomicAdd(&s_acc[j][c], v[c]);
             }
         }
         __syncthreads();
         if (tid < cnt) {
             float *out = grad_feat + (size_t)s_id[tid] * LMK_GS_FEAT_STRIDE;
 #pragma unroll
-            for (u32 k = 0; k < kGradComps; ++k) {
-                const float s = s_acc[tid][k];
-                if (s != 0.0f) atomicAdd(out + k, s);
+            for (u32 c = 0; c < kGradComps; ++c) {
+                const float s = s_acc[tid][c];
+                if (s != 0.0f) atomicAdd(out + c, s);
             }
         }
     }
@@ -239,8 +326,8 @@ hipError_t launch_render_backward(const lmk_gs_projected &proj, u32 n, const lmk
     bp.bg0 = pp.cam.bg[0]; bp.bg1 = pp.cam.bg[1]; bp.bg2 = pp.cam.bg[2];
     if (n == 0 || binned.capacity == 0) return hipSuccess;
     hipLaunchKernelGGL(blend_backward_kernel, dim3(bp.num_tiles), dim3(kBwdThreads), 0, stream,
-                       binned.tile_offsets, binned.vals, reinterpret_cast<const float4 *>(proj.feat), bp,
-                       grad_rgb, grad_T, grad_feat);
+                       binned.tile_offsets, binned.tile_order, binned.vals,
+                       reinterpret_cast<const float4 *>(proj.feat), bp, grad_rgb, grad_T, grad_feat);
     return hipGetLastError();
 }
 
