@@ -14,7 +14,8 @@
  *                    Gaussian ("splatting"); depth sort; blending per screen tile
  *   Sec. 2.2 Eq. 9-10  front-to-back compositing with sigma_i = alpha_i G'_i(x')
  *   Sec. 2.2 (text)  the rasteriser is differentiable: gradient of a loss through Eq. 9-10
- *                    with respect to each primitive's 2D mean, conic, opacity and colour
+ *                    with respect to each primitive's 2D mean, conic, opacity and colour, and
+ *                    from there through the projection to mean, scale, rotation, opacity, SH
  *   Sec. 4.2.1       the rasteriser stages named there: per-primitive projection,
  *                    duplication into (tile, depth) keys, sort, per-tile blend;
  *                    the per-tile intersection test (binning rule 1)
@@ -40,9 +41,10 @@
  * the tile intersection test of binning rule 1 against dense sampling and
  * against the unchanged image; the voxel visibility test against brute-force
  * conservativeness, closed cases and a planted mistake; the culls of
- * degenerate attribute values; the gradient through the compositing against
- * central differences of the forward functions, one- and two-splat closed forms
- * and the partition of unity of the weights.  No function here is "parity unpinned".
+ * degenerate attribute values; the gradients through the compositing and through
+ * the projection against central differences of the forward functions, one- and
+ * two-splat closed forms, the partition of unity of the weights, and the
+ * invariances of the projection.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -907,5 +909,202 @@ void lmk_ref_render_backward(uint32_t n, const float *mean2d, const float *conic
             }
         }
         free(rec);
+    }
+}
+
+
+/* ------------------------------------------------------------------------
+ * Gradient of a scalar loss through the per-primitive projection (the chain behind
+ * lmk_ref_render_backward: Sec. 2.2 says every parameter of the primitives is optimised through
+ * the rendering process).  Given, for each primitive, dL/d{u, v, A, B, C, o, r, g, b} -- the
+ * quantities lmk_ref_preprocess hands to the compositing -- the gradient with respect to its
+ * mean, scale, rotation quaternion (as stored, any norm), opacity and SH coefficients.
+ * Each step of lmk_ref_preprocess is differentiated in reverse order, in fp64, from the fp32
+ * inputs:
+ *   conic = inverse of [[a, b], [b, c]];  a, b, c = rows of T = J W applied to Sigma (+ h on the
+ *   diagonal);  J from the camera-space position p (with the guard-band clamp: where p_x / p_z is
+ *   clamped, J's third column depends on p_z only);  u, v from p;  p = W mean + t;
+ *   Sigma = M M^T, M = R(q / |q|) diag(s);  colour = max(0, 0.5 + sum_k Y_k(d) sh_k) with
+ *   d = (mean - camera centre) / |.|.
+ * [reading] Culls and clamps are constants of the derivative: a primitive that lmk_ref_preprocess
+ * did not bin (stage != visible) gets zero; a colour channel clamped at 0 passes nothing on.  B is
+ * the single off-diagonal value that q = A dx^2 + 2 B dx dy + C dy^2 uses.
+ * Outputs (overwritten), same layouts as the inputs: g_mean [3][n], g_scale [3][n], g_rot [4][n],
+ * g_opacity [n], g_sh [ncoef][3][n].  g_feat: [9][n] planes u, v, A, B, C, o, r, g, b.
+ */
+static void sh_basis_grad(const double d[3], double dY[16][3])
+{
+    const double x = d[0], y = d[1], z = d[2];
+    const double xx = x * x, yy = y * y, zz = z * z;
+    const double k1 = sqrt(3.0 / (4.0 * M_PI));
+    const double k2 = 0.5 * sqrt(15.0 / M_PI);
+    const double k20 = 0.25 * sqrt(5.0 / M_PI);
+    const double k33 = 0.25 * sqrt(35.0 / (2.0 * M_PI));
+    const double k32 = 0.5 * sqrt(105.0 / M_PI);
+    const double k31 = 0.25 * sqrt(21.0 / (2.0 * M_PI));
+    const double k30 = 0.25 * sqrt(7.0 / M_PI);
+    const double k32b = 0.25 * sqrt(105.0 / M_PI);
+    memset(dY, 0, sizeof(double) * 16 * 3);
+    dY[1][1] = -k1;
+    dY[2][2] = k1;
+    dY[3][0] = -k1;
+    dY[4][0] = k2 * y;            dY[4][1] = k2 * x;
+    dY[5][1] = -k2 * z;           dY[5][2] = -k2 * y;
+    dY[6][0] = -2.0 * k20 * x;    dY[6][1] = -2.0 * k20 * y;   dY[6][2] = 4.0 * k20 * z;
+    dY[7][0] = -k2 * z;           dY[7][2] = -k2 * x;
+    dY[8][0] = k2 * x;            dY[8][1] = -k2 * y;
+    dY[9][0] = -k33 * 6.0 * x * y;                 dY[9][1] = -k33 * (3.0 * xx - 3.0 * yy);
+    dY[10][0] = k32 * y * z;      dY[10][1] = k32 * x * z;     dY[10][2] = k32 * x * y;
+    dY[11][0] = k31 * 2.0 * x * y;
+    dY[11][1] = -k31 * (4.0 * zz - xx - 3.0 * yy);
+    dY[11][2] = -k31 * 8.0 * y * z;
+    dY[12][0] = -k30 * 6.0 * x * z;
+    dY[12][1] = -k30 * 6.0 * y * z;
+    dY[12][2] = k30 * (6.0 * zz - 3.0 * xx - 3.0 * yy);
+    dY[13][0] = -k31 * (4.0 * zz - 3.0 * xx - yy);
+    dY[13][1] = k31 * 2.0 * x * y;
+    dY[13][2] = -k31 * 8.0 * x * z;
+    dY[14][0] = k32b * 2.0 * x * z;
+    dY[14][1] = -k32b * 2.0 * y * z;
+    dY[14][2] = k32b * (xx - yy);
+    dY[15][0] = -k33 * (3.0 * xx - 3.0 * yy);
+    dY[15][1] = k33 * 6.0 * x * y;
+}
+
+void lmk_ref_preprocess_backward(uint32_t n, const float *mean, const float *scale, const float *rot,
+                                 const float *sh, uint32_t sh_degree,
+                                 const ref_camera *cam, const uint8_t *stage, const double *g_feat,
+                                 double *g_mean, double *g_scale, double *g_rot, double *g_opacity,
+                                 double *g_sh)
+{
+    const size_t N = n;
+    const uint32_t ncoef = (sh_degree + 1) * (sh_degree + 1);
+    const double lim_x = (double)(1.3f * ((0.5f * (float)cam->width) / cam->fx));
+    const double lim_y = (double)(1.3f * ((0.5f * (float)cam->height) / cam->fy));
+    const float *V = cam->view;
+    const double fx = cam->fx, fy = cam->fy;
+    memset(g_mean, 0, sizeof(double) * 3 * N);
+    memset(g_scale, 0, sizeof(double) * 3 * N);
+    memset(g_rot, 0, sizeof(double) * 4 * N);
+    memset(g_opacity, 0, sizeof(double) * N);
+    memset(g_sh, 0, sizeof(double) * (size_t)ncoef * 3 * N);
+#pragma omp parallel for schedule(static)
+    for (int64_t ii = 0; ii < (int64_t)n; ++ii) {
+        const size_t i = (size_t)ii;
+        if (stage[i] != REF_VISIBLE) continue;
+        const double gu = g_feat[i], gv = g_feat[N + i];
+        const double gA = g_feat[2 * N + i], gB = g_feat[3 * N + i], gC = g_feat[4 * N + i];
+        const double gcol[3] = { g_feat[6 * N + i], g_feat[7 * N + i], g_feat[8 * N + i] };
+        g_opacity[i] = g_feat[5 * N + i];
+
+        /* forward quantities, fp64 from the fp32 inputs */
+        const double m[3] = { mean[i], mean[N + i], mean[2 * N + i] };
+        double W[3][3], p[3];
+        for (int r = 0; r < 3; ++r) {
+            for (int c = 0; c < 3; ++c) W[r][c] = V[4 * r + c];
+            p[r] = W[r][0] * m[0] + W[r][1] * m[1] + W[r][2] * m[2] + (double)V[4 * r + 3];
+        }
+        const double qr[4] = { rot[i], rot[N + i], rot[2 * N + i], rot[3 * N + i] };
+        const double qn = sqrt(qr[0] * qr[0] + qr[1] * qr[1] + qr[2] * qr[2] + qr[3] * qr[3]);
+        const double w = qr[0] / qn, x = qr[1] / qn, y = qr[2] / qn, z = qr[3] / qn;
+        double R[3][3];
+        R[0][0] = 1.0 - 2.0 * (y * y + z * z); R[0][1] = 2.0 * (x * y - w * z); R[0][2] = 2.0 * (x * z + w * y);
+        R[1][0] = 2.0 * (x * y + w * z); R[1][1] = 1.0 - 2.0 * (x * x + z * z); R[1][2] = 2.0 * (y * z - w * x);
+        R[2][0] = 2.0 * (x * z - w * y); R[2][1] = 2.0 * (y * z + w * x); R[2][2] = 1.0 - 2.0 * (x * x + y * y);
+        const double s[3] = { scale[i], scale[N + i], scale[2 * N + i] };
+        double M[3][3], Sg[3][3];
+        for (int r = 0; r < 3; ++r) for (int c = 0; c < 3; ++c) M[r][c] = R[r][c] * s[c];
+        for (int r = 0; r < 3; ++r)
+            for (int c = 0; c < 3; ++c) Sg[r][c] = M[r][0] * M[c][0] + M[r][1] * M[c][1] + M[r][2] * M[c][2];
+        const double rx = p[0] / p[2], ry = p[1] / p[2];
+        const int clx = !(rx > -lim_x) || rx > lim_x, cly = !(ry > -lim_y) || ry > lim_y;
+        const double cxr = !(rx > -lim_x) ? -lim_x : (rx > lim_x ? lim_x : rx);
+        const double cyr = !(ry > -lim_y) ? -lim_y : (ry > lim_y ? lim_y : ry);
+        double J[2][3] = { { fx / p[2], 0.0, -fx * cxr / p[2] }, { 0.0, fy / p[2], -fy * cyr / p[2] } };
+        double T[2][3];
+        for (int r = 0; r < 2; ++r)
+            for (int c = 0; c < 3; ++c) T[r][c] = J[r][0] * W[0][c] + J[r][1] * W[1][c] + J[r][2] * W[2][c];
+        double ST[2][3];                       /* Sigma T_r^T */
+        for (int r = 0; r < 2; ++r)
+            for (int c = 0; c < 3; ++c) ST[r][c] = Sg[c][0] * T[r][0] + Sg[c][1] * T[r][1] + Sg[c][2] * T[r][2];
+        const double a = T[0][0] * ST[0][0] + T[0][1] * ST[0][1] + T[0][2] * ST[0][2] + (double)cam->lowpass;
+        const double b = T[0][0] * ST[1][0] + T[0][1] * ST[1][1] + T[0][2] * ST[1][2];
+        const double c = T[1][0] * ST[1][0] + T[1][1] * ST[1][1] + T[1][2] * ST[1][2] + (double)cam->lowpass;
+        const double det = a * c - b * b, id2 = 1.0 / (det * det);
+
+        /* conic (A, B, C) = (c, -b, a) / det  ->  a, b, c */
+        const double ga = gA * (-c * c * id2) + gB * (b * c * id2) + gC * (-b * b * id2);
+        const double gb = gA * (2.0 * b * c * id2) + gB * (-(a * c + b * b) * id2) + gC * (2.0 * a * b * id2);
+        const double gc = gA * (-b * b * id2) + gB * (a * b * id2) + gC * (-a * a * id2);
+
+        /* a = T0 Sigma T0^T + h, b = T0 Sigma T1^T, c = T1 Sigma T1^T + h  ->  Sigma (all nine entries), T */
+        double gS[3][3], gT[2][3];
+        for (int r = 0; r < 3; ++r)
+            for (int k = 0; k < 3; ++k)
+                gS[r][k] = ga * T[0][r] * T[0][k] + gb * T[0][r] * T[1][k] + gc * T[1][r] * T[1][k];
+        for (int k = 0; k < 3; ++k) {
+            gT[0][k] = 2.0 * ga * ST[0][k] + gb * ST[1][k];
+            gT[1][k] = 2.0 * gc * ST[1][k] + gb * ST[0][k];
+        }
+        /* T = J W  ->  J */
+        double gJ[2][3];
+        for (int r = 0; r < 2; ++r)
+            for (int k = 0; k < 3; ++k) gJ[r][k] = gT[r][0] * W[k][0] + gT[r][1] * W[k][1] + gT[r][2] * W[k][2];
+        /* J and (u, v)  ->  p */
+        double gp[3] = { 0.0, 0.0, 0.0 };
+        const double iz = 1.0 / p[2], iz2 = iz * iz;
+        gp[2] += gJ[0][0] * (-fx * iz2) + gJ[1][1] * (-fy * iz2);
+        if (clx) gp[2] += gJ[0][2] * (fx * cxr * iz2);
+        else { gp[0] += gJ[0][2] * (-fx * iz2); gp[2] += gJ[0][2] * (2.0 * fx * p[0] * iz2 * iz); }
+        if (cly) gp[2] += gJ[1][2] * (fy * cyr * iz2);
+        else { gp[1] += gJ[1][2] * (-fy * iz2); gp[2] += gJ[1][2] * (2.0 * fy * p[1] * iz2 * iz); }
+        gp[0] += gu * fx * iz;  gp[2] += gu * (-fx * p[0] * iz2);
+        gp[1] += gv * fy * iz;  gp[2] += gv * (-fy * p[1] * iz2);
+        double gm[3];
+        for (int k = 0; k < 3; ++k) gm[k] = W[0][k] * gp[0] + W[1][k] * gp[1] + W[2][k] * gp[2];
+
+        /* Sigma = M M^T  ->  M  ->  s, R */
+        double gM[3][3], gR[3][3];
+        for (int r = 0; r < 3; ++r)
+            for (int k = 0; k < 3; ++k)
+                gM[r][k] = (gS[r][0] + gS[0][r]) * M[0][k] + (gS[r][1] + gS[1][r]) * M[1][k] + (gS[r][2] + gS[2][r]) * M[2][k];
+        for (int k = 0; k < 3; ++k) {
+            g_scale[(size_t)k * N + i] = gM[0][k] * R[0][k] + gM[1][k] * R[1][k] + gM[2][k] * R[2][k];
+            for (int r = 0; r < 3; ++r) gR[r][k] = gM[r][k] * s[k];
+        }
+        /* R(w, x, y, z)  ->  unit quaternion  ->  stored quaternion */
+        double gq[4];
+        gq[0] = 2.0 * (-z * gR[0][1] + y * gR[0][2] + z * gR[1][0] - x * gR[1][2] - y * gR[2][0] + x * gR[2][1]);
+        gq[1] = 2.0 * (y * gR[0][1] + z * gR[0][2] + y * gR[1][0] - 2.0 * x * gR[1][1] - w * gR[1][2]
+                       + z * gR[2][0] + w * gR[2][1] - 2.0 * x * gR[2][2]);
+        gq[2] = 2.0 * (-2.0 * y * gR[0][0] + x * gR[0][1] + w * gR[0][2] + x * gR[1][0] + z * gR[1][2]
+                       - w * gR[2][0] + z * gR[2][1] - 2.0 * y * gR[2][2]);
+        gq[3] = 2.0 * (-2.0 * z * gR[0][0] - w * gR[0][1] + x * gR[0][2] + w * gR[1][0] - 2.0 * z * gR[1][1]
+                       + y * gR[1][2] + x * gR[2][0] + y * gR[2][1]);
+        const double qh[4] = { w, x, y, z };
+        const double dot = gq[0] * w + gq[1] * x + gq[2] * y + gq[3] * z;
+        for (int k = 0; k < 4; ++k) g_rot[(size_t)k * N + i] = (gq[k] - qh[k] * dot) / qn;
+
+        /* colour = max(0, 0.5 + sum_k Y_k(d) sh_k), d = (mean - camera centre) / |.| */
+        double dv[3] = { m[0] - (double)cam->cam_pos[0], m[1] - (double)cam->cam_pos[1], m[2] - (double)cam->cam_pos[2] };
+        const double len = sqrt(dv[0] * dv[0] + dv[1] * dv[1] + dv[2] * dv[2]);
+        const double d[3] = { dv[0] / len, dv[1] / len, dv[2] / len };
+        double Y[16], dY[16][3];
+        lmk_ref_sh_basis(d, Y);
+        sh_basis_grad(d, dY);
+        double gd[3] = { 0.0, 0.0, 0.0 };
+        for (int ch = 0; ch < 3; ++ch) {
+            double acc = 0.5;
+            for (uint32_t k = 0; k < ncoef; ++k) acc += Y[k] * (double)sh[((size_t)k * 3 + ch) * N + i];
+            if (!(acc > 0.0)) continue;                      /* clamped at 0 */
+            for (uint32_t k = 0; k < ncoef; ++k) {
+                const double c_k = (double)sh[((size_t)k * 3 + ch) * N + i];
+                g_sh[((size_t)k * 3 + ch) * N + i] = Y[k] * gcol[ch];
+                for (int t = 0; t < 3; ++t) gd[t] += gcol[ch] * c_k * dY[k][t];
+            }
+        }
+        const double dd = gd[0] * d[0] + gd[1] * d[1] + gd[2] * d[2];
+        for (int k = 0; k < 3; ++k) gm[k] += (gd[k] - d[k] * dd) / len;
+        for (int k = 0; k < 3; ++k) g_mean[(size_t)k * N + i] = gm[k];
     }
 }

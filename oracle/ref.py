@@ -183,6 +183,25 @@ def render_backward(pre: SimpleNamespace, binned: SimpleNamespace, cam: dict, gr
     return out
 
 
+def preprocess_backward(scene: dict, cam: dict, pre: SimpleNamespace, g_feat) -> SimpleNamespace:
+    """Gradient through the per-primitive projection: g_feat [9][n] (planes u, v, A, B, C, o, r, g, b)
+    -> gradients with respect to mean [3][n], scale [3][n], rot [4][n], opacity [n], sh [k][3][n]."""
+    n = scene["n"]
+    g_feat = np.ascontiguousarray(g_feat, dtype=np.float64)
+    assert g_feat.shape == (9, n)
+    sh = _f32(scene["sh"])
+    out = SimpleNamespace(mean=np.empty((3, n), np.float64), scale=np.empty((3, n), np.float64),
+                          rot=np.empty((4, n), np.float64), opacity=np.empty(n, np.float64),
+                          sh=np.empty(sh.shape, np.float64))
+    cc = _camera(cam)
+    mean, scale, rot = _f32(scene["mean"]), _f32(scene["scale"]), _f32(scene["rot"])
+    lib().lmk_ref_preprocess_backward(C.c_uint32(n), _p(mean), _p(scale), _p(rot), _p(sh),
+                                      C.c_uint32(int(scene.get("sh_degree", 3))), C.byref(cc), _p(pre.stage),
+                                      _p(g_feat), _p(out.mean), _p(out.scale), _p(out.rot), _p(out.opacity),
+                                      _p(out.sh))
+    return out
+
+
 def depth_order(pre: SimpleNamespace) -> np.ndarray:
     order = np.empty(max(pre.n, 1), np.uint32)
     m = lib().lmk_ref_depth_order(C.c_uint32(pre.n), _p(pre.stage), _p(pre.depth), _p(order))

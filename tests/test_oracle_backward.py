@@ -180,3 +180,106 @@ def test_magnitude_sums_bound_the_gradients():
     assert signed.shape == g.abs.shape
     assert (np.abs(signed) <= g.abs * (1 + 1e-12) + 1e-300).all()
     assert (g.abs[:, np.abs(signed).sum(0) > 0] > 0).any()
+
+
+# ---------------------------------------------------------------- the chain through the projection
+def _proj_loss(sc, cam, wts, i):
+    """sum of weights x (u, v, A, B, C, o, r, g, b) of primitive i, from the forward oracle; None
+    when the primitive is not binned."""
+    pre = ref.preprocess(sc, cam)
+    if pre.stage[i] != ref.VISIBLE:
+        return None
+    vals = np.array([pre.mean2d[0, i], pre.mean2d[1, i], pre.conic[0, i], pre.conic[1, i], pre.conic[2, i],
+                     pre.opacity[i], pre.rgb[0, i], pre.rgb[1, i], pre.rgb[2, i]], dtype=np.float64)
+    return float(wts @ vals)
+
+
+@pytest.mark.parametrize("seed,guard", [(31, False), (32, False), (33, True)])
+def test_projection_gradient_against_central_differences(seed, guard):
+    """The forward oracle evaluates u, v and the conic in fp32, so a central difference with a
+    relative step of 2^-9 carries a noise of about 1e-4 of the values; a wrong or missing term is of
+    order one."""
+    n = 24
+    sc = scenes.make_scene(0, n=n, seed=seed)
+    sc["scale"] = sc["scale"] * np.float32(3.0)
+    cam = dict(scenes.make_cameras(0, 256, 256)[0])
+    if guard:
+        # far off to the side, large enough to stay binned: the guard-band clamp of the Jacobian is active
+        sc["mean"][0] = np.float32(6.0) + sc["mean"][0]
+        sc["scale"] = sc["scale"] * np.float32(40.0)
+    pre = ref.preprocess(sc, cam)
+    vis = np.flatnonzero(pre.stage == ref.VISIBLE)
+    assert len(vis) >= 5
+    if guard:
+        lim = 1.3 * 0.5 * cam["width"] / cam["fx"]
+        V = np.asarray(cam["view"], np.float64).reshape(3, 4)
+        pc = V[:, :3] @ sc["mean"].astype(np.float64) + V[:, 3:4]
+        assert (np.abs(pc[0, vis] / pc[2, vis]) > lim).any()
+    rng = np.random.default_rng(seed)
+    W = rng.normal(size=(9, n))
+    W[2:5] *= 1e-2                              # conic entries are large for small splats: keep the terms comparable
+    g = ref.preprocess_backward(sc, cam, pre, W)
+    checked = 0
+    for i in vis[:5]:
+        for name, rows in (("mean", 3), ("scale", 3), ("rot", 4), ("opacity", 0)):
+            for r in range(max(rows, 1)):
+                idx = (i,) if rows == 0 else (r, i)
+                lo, hi = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in sc.items()}, \
+                         {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in sc.items()}
+                x = sc[name][idx]
+                step = np.float32(max(abs(float(x)), 0.05) * 2.0 ** -9)
+                lo[name][idx] = x - step; hi[name][idx] = x + step
+                den = float(hi[name][idx]) - float(lo[name][idx])
+                l_hi, l_lo = _proj_loss(hi, cam, W[:, i], i), _proj_loss(lo, cam, W[:, i], i)
+                assert l_hi is not None and l_lo is not None
+                fd = (l_hi - l_lo) / den
+                analytic = getattr(g, name)[idx]
+                scale_ = max(abs(fd), abs(analytic), 1e-6)
+                # noise floor of the fp32 forward values under this step
+                terms = np.abs(W[:, i] * np.array([pre.mean2d[0, i], pre.mean2d[1, i], pre.conic[0, i], pre.conic[1, i],
+                                                   pre.conic[2, i], pre.opacity[i], 0, 0, 0]))
+                noise = 4 * 2.0 ** -24 * terms.sum() / den
+                assert abs(fd - analytic) <= 2e-3 * scale_ + noise, (i, name, r, fd, analytic, noise)
+                checked += 1
+    assert checked == 5 * 11
+    # SH coefficients: the colour is linear in them (fp64 in the forward oracle)
+    i = int(vis[0])
+    for k in (0, 3, 8, 15):
+        for ch in range(3):
+            lo = dict(sc, sh=sc["sh"].copy()); hi = dict(sc, sh=sc["sh"].copy())
+            lo["sh"][k, ch, i] -= np.float32(2.0 ** -6); hi["sh"][k, ch, i] += np.float32(2.0 ** -6)
+            den = float(hi["sh"][k, ch, i]) - float(lo["sh"][k, ch, i])
+            fd = (_proj_loss(hi, cam, W[:, i], i) - _proj_loss(lo, cam, W[:, i], i)) / den
+            assert abs(fd - g.sh[k, ch, i]) <= 1e-6 * max(abs(fd), 1e-3), (k, ch, fd, g.sh[k, ch, i])
+
+
+def test_projection_gradient_special_cases():
+    sc = scenes.make_scene(0, n=40, seed=35)
+    cam = scenes.make_cameras(0, 128, 128)[0]
+    pre = ref.preprocess(sc, cam)
+    W = np.random.default_rng(1).normal(size=(9, 40))
+    g = ref.preprocess_backward(sc, cam, pre, W)
+    hidden = pre.stage != ref.VISIBLE
+    # a primitive that was not binned gets nothing
+    sc2 = dict(sc, mean=sc["mean"].copy()); sc2["mean"][2, :5] += 100.0
+    pre2 = ref.preprocess(sc2, cam)
+    g2 = ref.preprocess_backward(sc2, cam, pre2, W)
+    assert (pre2.stage[:5] != ref.VISIBLE).all()
+    for arr in (g2.mean, g2.scale, g2.rot):
+        assert not arr[:, :5].any()
+    assert not g2.opacity[:5].any() and not g2.sh[:, :, :5].any()
+    assert not g.mean[:, hidden].any()
+    # opacity passes straight through; the quaternion gradient is orthogonal to the quaternion
+    # (the covariance does not depend on its norm); scaling all three scales by t scales Sigma by t^2
+    vis = ~hidden
+    np.testing.assert_array_equal(g.opacity[vis], W[5, vis])
+    dots = (g.rot * sc["rot"].astype(np.float64)).sum(0)
+    assert np.abs(dots[vis]).max() <= 1e-9 * np.abs(g.rot[:, vis]).max()
+    # only the DC coefficient: the colour does not depend on the direction, so the mean gets
+    # nothing from the colour -- drop the colour weights and the mean gradient must not change
+    W0 = W.copy(); W0[6:] = 0.0
+    sc3 = dict(sc, sh=sc["sh"].copy()); sc3["sh"][1:] = 0.0
+    pre3 = ref.preprocess(sc3, cam)
+    g3a = ref.preprocess_backward(sc3, cam, pre3, W)
+    g3b = ref.preprocess_backward(sc3, cam, pre3, W0)
+    np.testing.assert_allclose(g3a.mean, g3b.mean, rtol=0, atol=1e-12 * np.abs(g3a.mean).max())
