@@ -221,6 +221,28 @@ int32_t lmk_gs_render_backward(const lmk_gs_projected *proj, uint32_t n, const l
                                const float *grad_rgb, const float *grad_transmittance,
                                float *grad_feat, void *stream);
 
+/* Where lmk_gs_preprocess_backward writes; device pointers, same layouts as lmk_gs_gaussians. */
+typedef struct lmk_gs_gaussian_grads {
+    float *mean;      /* [3][n] */
+    float *scale;     /* [3][n] */
+    float *rot;       /* [4][n] with respect to the quaternion as stored (any norm) */
+    float *opacity;   /* [n]    */
+    float *sh;        /* [n][LMK_GS_SH_STRIDE(sh_degree)], 16-byte aligned; padding entries get 0 */
+} lmk_gs_gaussian_grads;
+
+/* Gradient of a scalar loss through stage 1 (Sec. 2.2: every parameter of the primitives is
+ * optimised through the rendering process): from grad_feat [n][LMK_GS_FEAT_STRIDE], the
+ * output of lmk_gs_render_backward, to the gradient with respect to mean, scale, rotation,
+ * opacity and SH coefficients of every primitive.  g: the scene as lmk_gs_preprocess read it
+ * (scale and rot are required even when a covariance cache is present); proj->tiles_touched
+ * from that call tells which primitives were binned.  Culls and clamps are constants of the
+ * derivative: a primitive that was not binned gets zeros, a colour channel clamped at 0 passes
+ * nothing on.  Every output element is written.  Asynchronous on `stream`; errors as
+ * lmk_gs_preprocess. */
+int32_t lmk_gs_preprocess_backward(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
+                                   const lmk_gs_projected *proj, const float *grad_feat,
+                                   const lmk_gs_gaussian_grads *out, void *stream);
+
 /* Copies {pair count D, status} of the frame from scratch to the host.
  * Synchronises `stream`.  Either output pointer may be NULL. */
 int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream);

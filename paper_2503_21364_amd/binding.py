@@ -23,13 +23,19 @@ PRE_BLOCK = 256
 
 EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
            "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version",
-           "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward")
+           "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
+           "lmk_gs_preprocess_backward")
 
 
 class Gaussians(C.Structure):
     _fields_ = [("mean", C.c_void_p), ("scale", C.c_void_p), ("rot", C.c_void_p),
                 ("opacity", C.c_void_p), ("sh", C.c_void_p), ("n", C.c_uint32), ("sh_degree", C.c_uint32),
                 ("cov3d", C.c_void_p)]
+
+
+class GaussianGrads(C.Structure):
+    _fields_ = [("mean", C.c_void_p), ("scale", C.c_void_p), ("rot", C.c_void_p),
+                ("opacity", C.c_void_p), ("sh", C.c_void_p)]
 
 
 class Camera(C.Structure):
@@ -85,6 +91,8 @@ def lib() -> C.CDLL:
         l.lmk_gs_preprocess_culled.argtypes = [C.POINTER(Gaussians), C.POINTER(VoxelIndexC), C.POINTER(Camera),
                                                C.POINTER(Projected), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.lmk_gs_build_cov3d.argtypes = [C.POINTER(Gaussians), C.c_void_p, C.c_void_p]
+        l.lmk_gs_preprocess_backward.argtypes = [C.POINTER(Gaussians), C.POINTER(Camera), C.POINTER(Projected),
+                                                 C.c_void_p, C.POINTER(GaussianGrads), C.c_void_p]
         l.lmk_gs_render_backward.argtypes = [C.POINTER(Projected), C.c_uint32, C.POINTER(Binned), C.POINTER(Camera),
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.lmk_gs_read_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_void_p]
@@ -92,7 +100,8 @@ def lib() -> C.CDLL:
         l.lmk_gs_strerror.restype = C.c_char_p
         for name in ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
                      "lmk_gs_read_status", "lmk_gs_last_hip_error", "lmk_gs_index_build",
-                     "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward"):
+                     "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
+           "lmk_gs_preprocess_backward"):
             getattr(l, name).restype = C.c_int32
         l.lmk_gs_version.restype = C.c_uint32
         _lib = l
@@ -281,6 +290,24 @@ def render_backward(cam: Camera, frame: Frame, grad_rgb, grad_T, grad_feat, stre
                                       _stream_handle(stream))
     if rc != OK:
         raise LmkGsError(rc, "lmk_gs_render_backward")
+
+
+class SceneGrads:
+    """Device buffers for the output of lmk_gs_preprocess_backward, laid out like the scene."""
+
+    def __init__(self, scene: "Scene", device="cuda:0"):
+        n = max(scene.n, 1)
+        e = lambda shape: torch.empty(shape, dtype=torch.float32, device=device)
+        self.mean, self.scale, self.rot = e((3, n)), e((3, n)), e((4, n))
+        self.opacity, self.sh = e((n,)), e((n, sh_stride(scene.sh_degree)))
+        self.c = GaussianGrads(_ptr(self.mean), _ptr(self.scale), _ptr(self.rot), _ptr(self.opacity), _ptr(self.sh))
+
+
+def preprocess_backward(scene: "Scene", cam: Camera, frame: Frame, grad_feat, grads: SceneGrads, stream=None) -> None:
+    rc = lib().lmk_gs_preprocess_backward(C.byref(scene.c), C.byref(cam), C.byref(frame.proj), _ptr(grad_feat),
+                                          C.byref(grads.c), _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_preprocess_backward")
 
 
 def read_status(frame: Frame, stream=None) -> tuple[int, int]:

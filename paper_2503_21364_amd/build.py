@@ -32,6 +32,7 @@ UNITS = {
     "binsort.hip": EXACT,       # the tile intersection test of binning rule 1 decides integers too
     "render.hip": [],
     "render_bwd.hip": [],       # same options as render.hip: pass 1 repeats its arithmetic
+    "preprocess_bwd.hip": [],
     "index.hip": EXACT,         # host code: the voxel of a primitive is decided by one fp32 division
 }
 

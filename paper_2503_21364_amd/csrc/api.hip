@@ -186,6 +186,26 @@ int32_t lmk_gs_render_backward(const lmk_gs_projected *proj, uint32_t n, const l
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
 }
 
+int32_t lmk_gs_preprocess_backward(const lmk_gs_gaussians *g, const lmk_gs_camera *cam,
+                                   const lmk_gs_projected *proj, const float *grad_feat,
+                                   const lmk_gs_gaussian_grads *out, void *stream)
+{
+    ProjParams pp;
+    const int32_t rc = check_camera(cam, &pp);
+    if (rc != LMK_GS_OK) return rc;
+    if (!g || !proj || !out) return LMK_GS_ERR_INVALID;
+    if (g->sh_degree > 3) return LMK_GS_ERR_INVALID;
+    if (g->n > 0) {
+        if (!g->mean || !g->scale || !g->rot || !g->sh || !proj->tiles_touched || !grad_feat)
+            return LMK_GS_ERR_INVALID;
+        if (!out->mean || !out->scale || !out->rot || !out->opacity || !out->sh) return LMK_GS_ERR_INVALID;
+        if (!aligned(g->sh, 16) || !aligned(out->sh, 16) || !aligned(grad_feat, 16)) return LMK_GS_ERR_INVALID;
+    }
+    const hipError_t e = launch_preprocess_backward(*g, pp, *proj, grad_feat, *out,
+                                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
 int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream)
 {
     if (!scratch) return LMK_GS_ERR_INVALID;

@@ -135,5 +135,8 @@ hipError_t launch_render(const lmk_gs_projected &proj, const lmk_gs_binned &binn
 hipError_t launch_render_backward(const lmk_gs_projected &proj, u32 n, const lmk_gs_binned &binned,
                                   const ProjParams &pp, const float *grad_rgb, const float *grad_T,
                                   float *grad_feat, hipStream_t stream);
+hipError_t launch_preprocess_backward(const lmk_gs_gaussians &g, const ProjParams &pp,
+                                      const lmk_gs_projected &proj, const float *grad_feat,
+                                      const lmk_gs_gaussian_grads &out, hipStream_t stream);
 
 }  // namespace lmk

@@ -38,6 +38,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(B.Camera) == 4 * (12 + 3 + 4 + 3 + 2 + 3 + 1)
     assert C.sizeof(B.Gaussians) == 5 * 8 + 2 * 4 + 8 and B.Gaussians.cov3d.offset == 48
     assert C.sizeof(B.Projected) == 5 * 8
+    assert C.sizeof(B.GaussianGrads) == 5 * 8
     assert C.sizeof(B.Binned) == 7 * 8
     assert B.Binned.capacity.offset == 32 and B.Binned.tile_offsets.offset == 40
 
@@ -152,6 +153,27 @@ def test_bin_sort_and_render_reject_bad_arguments():
     assert rb(proj, binned, cam, _fake(), None, None) == B.ERR_INVALID
     assert rb(proj, binned, cam, _fake(), None, 0x1004) == B.ERR_INVALID   # grad_feat must be 16-byte aligned
     assert rb(proj, binned, bad) == B.ERR_UNSUPPORTED
+
+
+def test_preprocess_backward_rejects_bad_arguments():
+    lib = B.lib()
+    g, proj, _ = _args()
+    cam = _good_camera()
+    grads = B.GaussianGrads(0x1000, 0x2000, 0x3000, 0x4000, 0x5000)
+    call = lambda g_, c_, p_, gf=C.c_void_p(0x6000), o_=grads: lib.lmk_gs_preprocess_backward(
+        None if g_ is None else C.byref(g_), None if c_ is None else C.byref(c_),
+        None if p_ is None else C.byref(p_), gf, None if o_ is None else C.byref(o_), None)
+    assert call(None, cam, proj) == B.ERR_INVALID
+    assert call(g, None, proj) == B.ERR_INVALID
+    assert call(g, cam, None) == B.ERR_INVALID
+    assert call(g, cam, proj, None) == B.ERR_INVALID
+    assert call(g, cam, proj, C.c_void_p(0x6004)) == B.ERR_INVALID          # grad_feat must be 16-byte aligned
+    assert call(g, cam, proj, C.c_void_p(0x6000), None) == B.ERR_INVALID
+    assert call(g, cam, proj, C.c_void_p(0x6000), B.GaussianGrads(0x1000, 0x2000, None, 0x4000, 0x5000)) == B.ERR_INVALID
+    g2, _, _ = _args(); g2.rot = None                                        # the cache alone is not enough here
+    assert call(g2, cam, proj) == B.ERR_INVALID
+    bad = _good_camera(); bad.tile = 8
+    assert call(g, bad, proj) == B.ERR_UNSUPPORTED
 
 
 def test_index_build_matches_the_oracle_and_rejects_bad_input():
