@@ -76,6 +76,19 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
                 total=b_pre + b_emit + b_part + b_ranges + b_tsort)
 
 
+def _projection_backward_report(ms, n, stats, nviews):
+    """lmk_gs_preprocess_backward: HBM-bound.  Algorithmic bytes per call: 4 B (tile count) for every
+    primitive; a binned one reads its 36 B of feature-record gradient, 40 B of mean, scale and rotation
+    and 192 B of SH, and every primitive gets 44 B + 192 B of gradient written (zeros when not binned)."""
+    byts = [4.0 * n + 268.0 * stats[v]["n_bin"] + 236.0 * n for v in range(nviews)]
+    gbs = sum(byts) / (sum(ms) * 1e-3) / 1e9
+    return {"entry": "lmk_gs_preprocess_backward", "ms_per_call": sum(ms) / len(ms),
+            "per_view_ms": [float(x) for x in ms],
+            "roofline": {"kernel": "preprocess_backward_kernel", "bound": "hbm", "achieved": gbs,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                         "bytes_per_call": sum(byts) / len(byts)}}
+
+
 def committed_traffic(cfg, binning):
     """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (already scaled
     by the copy-kernel calibration), from the summary committed under profiles/.  None when
@@ -240,20 +253,26 @@ def main():
         g_rgb = torch.randn(3, H, W, device="cuda", generator=gen)
         g_T = torch.randn(H, W, device="cuda", generator=gen)
         g_feat = torch.empty(max(n, 1), B.FEAT_STRIDE, dtype=torch.float32, device="cuda")
+        grads = B.SceneGrads(dev)
         reps = 5
-        bwd_ms = []
+        bwd_ms, bwd_pre_ms = [], []
         for v in range(nviews):
             B.render_frame(dev, ccams[v], fr, index=index)
             B.render_backward(ccams[v], fr, g_rgb, g_T, g_feat)          # warm-up
+            B.preprocess_backward(dev, ccams[v], fr, g_feat, grads)
             torch.cuda.synchronize()
-            e0, e1 = ev(), ev()
+            e0, e1, e2 = ev(), ev(), ev()
             e0.record()
             for _ in range(reps):
                 B.render_backward(ccams[v], fr, g_rgb, g_T, g_feat)
             e1.record()
+            for _ in range(reps):
+                B.preprocess_backward(dev, ccams[v], fr, g_feat, grads)
+            e2.record()
             torch.cuda.synchronize()
             bwd_ms.append(e0.elapsed_time(e1) / reps)
-        del g_rgb, g_T, g_feat
+            bwd_pre_ms.append(e1.elapsed_time(e2) / reps)
+        del g_rgb, g_T, g_feat, grads
 
     n_near = None
     if not args.no_cpu_baseline:
@@ -344,6 +363,7 @@ def main():
             out["backward"] = {"entry": "lmk_gs_render_backward", "ms_per_call": float(np.mean(bwd_ms)),
                                "per_view_ms": [float(x) for x in bwd_ms],
                                "pairs_per_s": float(Ev.sum() / (sum(bwd_ms) * 1e-3)),
+                               "projection": _projection_backward_report(bwd_pre_ms, n, stats, nviews),
                                "roofline": {"kernel": "blend_backward_kernel", "bound": "alu", "achieved": btf,
                                             "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                                             "frac": btf / FP32_PEAK_TFLOPS, "traffic": None,
@@ -351,7 +371,8 @@ def main():
         out["cpu_baseline"] = cpu
     elif bwd_ms is not None:
         out["backward"] = {"entry": "lmk_gs_render_backward", "ms_per_call": float(np.mean(bwd_ms)),
-                           "per_view_ms": [float(x) for x in bwd_ms]}
+                           "per_view_ms": [float(x) for x in bwd_ms],
+                           "projection": _projection_backward_report(bwd_pre_ms, n, stats, nviews)}
     print(json.dumps(out), flush=True)
 
 

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void preprocess_backward_kernel(
         g_scale[i] = 0.f; g_scale[N + i] = 0.f; g_scale[2 * N + i] = 0.f;
         g_rot[i] = 0.f; g_rot[N + i] = 0.f; g_rot[2 * N + i] = 0.f; g_rot[3 * N + i] = 0.f;
         g_opacity[i] = 0.f;
-        for (u32 k = 0; k < STRIDE; ++k) gsh[k] = 0.f;
+        for (u32 k = 0; k < STRIDE / 4; ++k) reinterpret_cast<float4 *>(gsh)[k] = make_float4(0.f, 0.f, 0.f, 0.f);
         return;
     }
     const float *gf = grad_feat + (size_t)i * LMK_GS_FEAT_STRIDE;
@@ -225,7 +225,18 @@ __global__ __launch_bounds__(256) void preprocess_backward_kernel(
     const float dxn = vx / len, dyn = vy / len, dzn = vz / len;
     float Y[16], dYx[16], dYy[16], dYz[16];
     sh_basis_and_grad<DEG>(dxn, dyn, dzn, shk, Y, dYx, dYy, dYz);
-    const float *coef = sh + (size_t)i * STRIDE;
+    // the SH record and its gradient as whole 16-byte vectors (both are 16-byte aligned records)
+    float coef[STRIDE], gout[STRIDE];
+    {
+        const float4 *c4 = reinterpret_cast<const float4 *>(sh + (size_t)i * STRIDE);
+#pragma unroll
+        for (u32 k = 0; k < STRIDE / 4; ++k) {
+            const float4 t = c4[k];
+            coef[4 * k] = t.x; coef[4 * k + 1] = t.y; coef[4 * k + 2] = t.z; coef[4 * k + 3] = t.w;
+        }
+    }
+#pragma unroll
+    for (u32 k = 0; k < STRIDE; ++k) gout[k] = 0.f;
     float gdx = 0.f, gdy = 0.f, gdz = 0.f;
 #pragma unroll
     for (u32 ch = 0; ch < 3; ++ch) {
@@ -236,11 +247,16 @@ __global__ __launch_bounds__(256) void preprocess_backward_kernel(
 #pragma unroll
         for (u32 k = 0; k < NC; ++k) {
             const float ck = coef[3 * k + ch];
-            gsh[3 * k + ch] = Y[k] * gch;
+            gout[3 * k + ch] = Y[k] * gch;
             gdx += gch * ck * dYx[k]; gdy += gch * ck * dYy[k]; gdz += gch * ck * dYz[k];
         }
     }
-    for (u32 k = 3 * NC; k < STRIDE; ++k) gsh[k] = 0.f;
+    {
+        float4 *o4 = reinterpret_cast<float4 *>(gsh);
+#pragma unroll
+        for (u32 k = 0; k < STRIDE / 4; ++k)
+            o4[k] = make_float4(gout[4 * k], gout[4 * k + 1], gout[4 * k + 2], gout[4 * k + 3]);
+    }
     const float dd = gdx * dxn + gdy * dyn + gdz * dzn;
     gm[0] += (gdx - dxn * dd) / len;
     gm[1] += (gdy - dyn * dd) / len;
