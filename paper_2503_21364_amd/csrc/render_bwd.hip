@@ -35,6 +35,8 @@ namespace lmk {
 namespace {
 
 constexpr u32 kBwdThreads = 256, kBwdBatch = 256;
+typedef unsigned char slot_t;               // a slot of the staged batch (kBwdBatch <= 256)
+static_assert(kBwdBatch <= 256 && (kBwdBatch & (kBwdBatch - 1)) == 0, "slots are bytes and masked");
 constexpr u32 kGradComps = 9;               // u, v, A, B, C, opacity, r, g, b
 
 struct BwdParams {
@@ -62,7 +64,7 @@ __device__ __forceinline__ void row_sums(float (&v)[kGradComps])
 
 // the survivors of one batch for one wavefront: slots of the entries that pass the block test
 __device__ __forceinline__ u32 block_survivors(const float4 *s_geo, const float4 *s_cop, const float4 *s_tst,
-                                               u32 cnt, float bx, float by, u32 lane, unsigned short *list)
+                                               u32 cnt, float bx, float by, u32 lane, slot_t *list)
 {
     u32 n8 = 0;
     for (u32 c0 = 0; c0 < cnt; c0 += kWave) {
@@ -74,7 +76,7 @@ __device__ __forceinline__ u32 block_survivors(const float4 *s_geo, const float4
         const bool pass = e < cnt && best + co.y >= kBlockPass;
         const u64 mask = __builtin_amdgcn_ballot_w64(pass);
         const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
-        if (pass) list[n8 + rank] = (unsigned short)e;
+        if (pass) list[n8 + rank] = (slot_t)e;
         n8 += (u32)__builtin_popcountll(mask);
     }
     return n8;
@@ -83,8 +85,8 @@ __device__ __forceinline__ u32 block_survivors(const float4 *s_geo, const float4
 // ... and of those, per 4x4 sub-block (the 16 lanes of a row), the ones that can reach it: one
 // survivor per lane, tested against the four sub-blocks; list order is kept
 __device__ __forceinline__ void subblock_survivors(const float4 *s_geo, const float4 *s_cop, const float4 *s_tst,
-                                                   const unsigned short *list8, u32 n8, float bx, float by, u32 lane,
-                                                   unsigned short (*list4)[kBwdBatch], u32 (&n4)[4])
+                                                   const slot_t *list8, u32 n8, float bx, float by, u32 lane,
+                                                   slot_t (*list4)[kBwdBatch], u32 (&n4)[4])
 {
     n4[0] = n4[1] = n4[2] = n4[3] = 0u;
     for (u32 k0 = 0; k0 < n8; k0 += kWave) {
@@ -102,7 +104,7 @@ __device__ __forceinline__ void subblock_survivors(const float4 *s_geo, const fl
             const bool pass = valid && best + co.y >= kBlockPass;
             const u64 mask = __builtin_amdgcn_ballot_w64(pass);
             const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
-            if (pass) list4[q][n4[q] + rank] = (unsigned short)e;
+            if (pass) list4[q][n4[q] + rank] = (slot_t)e;
             n4[q] += (u32)__builtin_popcountll(mask);
         }
     }
@@ -118,11 +120,10 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     __shared__ float4 s_geo[kBwdBatch];          // du, dv, A', B'
     __shared__ float4 s_cop[kBwdBatch];          // C', lo, r, g
     __shared__ float4 s_tst[kBwdBatch];          // -B'/(2A'), -B'/(2C'), b, 1 / opacity
-    __shared__ float4 s_org[kBwdBatch];          // A, B, C, -
     __shared__ u32 s_id[kBwdBatch];              // primitive index
     __shared__ float s_acc[kBwdBatch][kGradComps];
-    __shared__ unsigned short s_list[kBwdThreads / kWave][kBwdBatch];
-    __shared__ unsigned short s_list4[kBwdThreads / kWave][4][kBwdBatch];
+    __shared__ slot_t s_list[kBwdThreads / kWave][kBwdBatch];
+    __shared__ slot_t s_list4[kBwdThreads / kWave][4][kBwdBatch];
     __shared__ u32 s_last[kBwdThreads / kWave];
 
     if (blockIdx.x >= bp.num_tiles) return;
@@ -144,8 +145,8 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
     const u64 len64 = end - start;
     const u32 len = len64 < 0xffffff00ull ? (u32)len64 : 0xffffff00u;     // a tile's list is far shorter
-    unsigned short *my_list = s_list[wv];
-    const unsigned short *my_list4 = s_list4[wv][grp];
+    slot_t *my_list = s_list[wv];
+    const slot_t *my_list4 = s_list4[wv][grp];
 
     // ---- pass 1: the forward walk
     float T = 1.0f;
@@ -227,11 +228,12 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
             s_geo[tid] = make_float4(a.x - X0, a.y - Y0, A, Bq);
             s_cop[tid] = make_float4(Cq, __log2f(bq.y), bq.z, bq.w);
             s_tst[tid] = make_float4(-Bq / (2.0f * A), -Bq / (2.0f * Cq), c.x, 1.0f / bq.y);
-            s_org[tid] = make_float4(a.z, a.w, bq.x, 0.0f);
             s_id[tid] = g;
         }
+        if (tid < kBwdBatch) {
 #pragma unroll
-        for (u32 k = 0; k < kGradComps; ++k) s_acc[tid][k] = 0.0f;
+            for (u32 k = 0; k < kGradComps; ++k) s_acc[tid][k] = 0.0f;
+        }
         __syncthreads();
         // a wavefront none of whose pixels walked this far has nothing to add (it still takes part
         // in the barriers and the flush below)
@@ -257,7 +259,6 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
 #pragma unroll
             for (u32 c = 0; c < kGradComps; ++c) v[c] = 0.0f;
             if (hit) {
-                const float4 og = s_org[j];
                 const float4 ts = s_tst[j];
                 const float inv = __builtin_amdgcn_rcpf(1.0f - alpha);     // 1 - alpha >= 0.01; one ulp is enough here
                 const float Ti = T * inv;                   // transmittance in front of this entry
@@ -273,8 +274,10 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
                     v[2] = dLdq * dx * dx;
                     v[3] = dLdq * 2.0f * dx * dy;
                     v[4] = dLdq * dy * dy;
-                    v[0] = dLdq * 2.0f * (og.x * dx + og.y * dy);
-                    v[1] = dLdq * 2.0f * (og.y * dx + og.z * dy);
+                    // 2 (A dx + B dy) and 2 (B dx + C dy) from A' = -0.5 log2(e) A, B' = -log2(e) B, C' likewise
+                    const float kInv = -2.0f / kL2E;
+                    v[0] = dLdq * kInv * (2.0f * g.z * dx + g.w * dy);
+                    v[1] = dLdq * kInv * (g.w * dx + 2.0f * co.x * dy);
                 }
             }
             // the nine row sums side by side (independent DPP chains), then one guarded group of
@@ -287,13 +290,12 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
             }
         }
         __syncthreads();
-        if (tid < cnt) {
-            float *out = grad_feat + (size_t)s_id[tid] * LMK_GS_FEAT_STRIDE;
-#pragma unroll
-            for (u32 c = 0; c < kGradComps; ++c) {
-                const float s = s_acc[tid][c];
-                if (s != 0.0f) atomicAdd(out + c, s);
-            }
+        // consecutive lanes take the consecutive components of an entry, so that the atomics of one
+        // instruction fall into few cache lines (nine lanes per 36-byte record)
+        for (u32 idx = tid; idx < cnt * kGradComps; idx += kBwdThreads) {
+            const u32 e = idx / kGradComps, c = idx - e * kGradComps;
+            const float v = s_acc[e][c];
+            if (v != 0.0f) atomicAdd(grad_feat + (size_t)s_id[e] * LMK_GS_FEAT_STRIDE + c, v);
         }
     }
 }
