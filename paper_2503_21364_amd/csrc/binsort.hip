@@ -902,14 +902,14 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
 
 // ---------------------------------------------------------------- per-tile sort
 // Sorts up to THREADS * ITEMS pairs of one tile by (depth bits, index) with a merge sort:
-// each thread sorts ITEMS composites in registers (a fixed network, no memory traffic),
-// then the sorted runs are merged pairwise through LDS, run length doubling: a thread finds
-// where its ITEMS outputs start in the two runs (merge-path binary search) and merges them
-// sequentially.  About 25 LDS accesses per element, against ~150 for a bitonic network over
-// the whole chunk.  Runs are stored with one padding slot per 16 elements so that the
-// strided accesses of neighbouring threads spread over the LDS banks.  Three instances:
-// 64 threads x 8 (one wavefront per short list, which is most tiles), 256 x 16, and
-// 1024 x 16 (a whole compute unit's LDS) for the long lists.
+// each thread sorts ITEMS composites in registers (a fixed network, no memory traffic), the
+// runs of 2, 4 and 8 neighbouring lanes are merged in registers too (bitonic merges with DPP
+// lane exchanges), and from there the sorted runs are merged pairwise through LDS, run length
+// doubling: a thread finds where its ITEMS outputs start in the two runs (merge-path binary
+// search) and merges them sequentially.  Runs are stored with one padding slot per 16 elements
+// so that the strided accesses of neighbouring threads spread over the LDS banks.  Instances:
+// 64 threads x 2 / 4 / 8 (one wavefront per short list, which is most tiles), 256 x 8,
+// 512 x 8, and 1024 x 16 (most of a compute unit's LDS) for the chunks of the longest lists.
 __device__ __forceinline__ u32 ts_slot(u32 p) { return p + (p >> 4); }
 
 __device__ __forceinline__ void ts_cswap(u64 &a, u64 &b)
