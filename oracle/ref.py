@@ -192,7 +192,7 @@ def preprocess_backward(scene: dict, cam: dict, pre: SimpleNamespace, g_feat) ->
     sh = _f32(scene["sh"])
     out = SimpleNamespace(mean=np.empty((3, n), np.float64), scale=np.empty((3, n), np.float64),
                           rot=np.empty((4, n), np.float64), opacity=np.empty(n, np.float64),
-                          sh=np.empty(sh.shape, np.float64))
+                          sh=np.zeros(sh.shape, np.float64))      # coefficients beyond the degree stay 0
     cc = _camera(cam)
     mean, scale, rot = _f32(scene["mean"]), _f32(scene["scale"]), _f32(scene["rot"])
     lib().lmk_ref_preprocess_backward(C.c_uint32(n), _p(mean), _p(scale), _p(rot), _p(sh),
