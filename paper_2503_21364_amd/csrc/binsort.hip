@@ -34,6 +34,8 @@
 //            a workgroup of 1024 threads each: 16384-pair chunks in LDS, then pairwise merges
 //            through LDS-staged windows.  Sorting the 32 depth bits this way costs one read
 //            and one write of most pairs instead of four radix passes over all of them.
+#include <type_traits>
+
 #include "lmk_gs_internal.h"
 
 namespace lmk {
@@ -480,7 +482,9 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
     const u32 tid = threadIdx.x;
     const u32 dmask = (1u << bits) - 1u;
     for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_tot[d] = 0;    // thread d owns s_tot[d]
-    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // a whole tile needs no bounds checks: the body is instantiated twice
+    auto run_tile = [&](u64 tile, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
         for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_hist[d] = 0;
         __syncthreads();
         const u64 t0 = tile * kSortTile;
@@ -488,12 +492,12 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kSortThreads + tid;
-            k[j] = idx < D ? keys[idx] : 0ull;
+            k[j] = (FULL || idx < D) ? keys[idx] : 0ull;
         }
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kSortThreads + tid;
-            wave_hist_add(s_hist, (u32)(k[j] >> shift) & dmask, idx < D, tid);
+            wave_hist_add(s_hist, (u32)(k[j] >> shift) & dmask, FULL || idx < D, tid);
         }
         __syncthreads();
         for (u32 d = tid; d < kMaxRadix; d += kSortThreads) {
@@ -502,6 +506,10 @@ __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
             s_tot[d] += c;
         }
         __syncthreads();
+    };
+    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if ((tile + 1) * kSortTile <= D) run_tile(tile, std::true_type());
+        else run_tile(tile, std::false_type());
     }
     u64 *mine = digit_totals + (size_t)(blockIdx.x % kTotalCopies) * kMaxRadix;
     for (u32 d = tid; d < kMaxRadix; d += kSortThreads) {
@@ -599,7 +607,9 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
     const u64 lane_lt = (1ull << lane) - 1ull;
     const u32 radix = 1u << bits, dmask = radix - 1u;
 
-    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // a whole tile needs none of the bounds checks: the body is instantiated twice
+    auto run_tile = [&](u64 tile, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
         for (u32 k = tid; k < kWaves * kMaxRadix; k += kSortThreads) (&s_wave_hist[0][0])[k] = 0;
         __syncthreads();
 
@@ -610,14 +620,14 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kWave + lane;
-            const bool valid = idx < D;
+            const bool valid = FULL || idx < D;
             key[j] = valid ? keys_in[idx] : ~0ull;
             val[j] = valid ? vals_in[idx] : 0u;
         }
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kWave + lane;
-            const bool valid = idx < D;
+            const bool valid = FULL || idx < D;
             const u32 digit = (u32)(key[j] >> shift) & dmask;
             // lanes of this wavefront holding the same digit (match-any by ballots)
             u64 peers = __builtin_amdgcn_ballot_w64(valid);
@@ -684,7 +694,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kWave + lane;
-            if (idx < D) {
+            if (FULL || idx < D) {
                 const u32 digit = (u32)(key[j] >> shift) & dmask;
                 rank[j] = s_digit_start[digit] + s_wave_hist[wv][digit] + rank[j];
                 s_stage[rank[j]] = key[j];
@@ -695,7 +705,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u32 p = j * kSortThreads + tid;
-            if (p < count) {
+            if (FULL || p < count) {
                 const u64 k = s_stage[p];
                 dg[j] = (u32)(k >> shift) & dmask;
                 keys_out[s_gofs[dg[j]] + p] = k;
@@ -706,15 +716,19 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u64 idx = t0 + (u64)j * kWave + lane;
-            if (idx < D) s_vals[rank[j]] = val[j];
+            if (FULL || idx < D) s_vals[rank[j]] = val[j];
         }
         __syncthreads();
 #pragma unroll
         for (u32 j = 0; j < kSortItems; ++j) {
             const u32 p = j * kSortThreads + tid;
-            if (p < count) vals_out[s_gofs[dg[j]] + p] = s_vals[p];
+            if (FULL || p < count) vals_out[s_gofs[dg[j]] + p] = s_vals[p];
         }
         __syncthreads();
+    };
+    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if ((tile + 1) * kSortTile <= D) run_tile(tile, std::true_type());
+        else run_tile(tile, std::false_type());
     }
 }
 
