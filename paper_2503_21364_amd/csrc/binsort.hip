@@ -629,16 +629,21 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
             const u64 idx = t0 + (u64)j * kWave + lane;
             const bool valid = FULL || idx < D;
             const u32 digit = (u32)(key[j] >> shift) & dmask;
-            // lanes of this wavefront holding the same digit (match-any by ballots)
-            u64 peers = __builtin_amdgcn_ballot_w64(valid);
+            // lanes of this wavefront holding the same digit (match-any by ballots): per digit bit,
+            // keep the lanes whose bit equals mine -- with m = 0 / ~0 for my bit 0 / 1 that is
+            // peers & ~(ballot ^ m), on the two 32-bit halves
+            const u64 live = __builtin_amdgcn_ballot_w64(valid);
+            u32 peers_lo = (u32)live, peers_hi = (u32)(live >> 32);
 #pragma unroll
             for (u32 b = 0; b < kMaxRadixBits; ++b) {
                 if (b < bits) {
-                    const bool bit = (digit >> b) & 1u;
-                    const u64 bal = __builtin_amdgcn_ballot_w64(bit);
-                    peers &= bit ? bal : ~bal;
+                    const u32 m = 0u - ((digit >> b) & 1u);
+                    const u64 bal = __builtin_amdgcn_ballot_w64(m != 0u);
+                    peers_lo &= ~((u32)bal ^ m);
+                    peers_hi &= ~((u32)(bal >> 32) ^ m);
                 }
             }
+            const u64 peers = ((u64)peers_hi << 32) | (u64)peers_lo;
             const u32 before = __popcll(peers & lane_lt);
             u32 old = 0;
             if (valid && before == 0)                  // lowest peer lane adds for the group
