@@ -255,3 +255,33 @@ def test_projection_backward_lower_sh_degrees(deg):
     cam = scenes.make_cameras(0, 128, 128)[0]
     st = _compare_projection(sc, cam, 61 + deg)
     print(f"[backward] projection, SH degree {deg}: {st}", flush=True)
+
+
+def test_gradient_calls_on_a_side_stream_and_twice():
+    """Both calls are asynchronous on the caller's stream; two runs agree to rounding (the additions
+    of the first call are atomic, their order is not fixed); the second call overwrites its output."""
+    sc = scenes.make_scene(0, n=4000, seed=71)
+    sc["scale"] = sc["scale"] * np.float32(2.5)
+    cam = scenes.make_cameras(0, 160, 96)[0]
+    dev = B.Scene(sc)
+    c = B.make_camera(cam)
+    H, W = 96, 160
+    gen = torch.Generator(device="cuda"); gen.manual_seed(3)
+    g_rgb = torch.randn(3, H, W, device="cuda", generator=gen)
+    g_T = torch.randn(H, W, device="cuda", generator=gen)
+    outs = []
+    for stream in (None, torch.cuda.Stream()):
+        fr = B.Frame(sc["n"], W, H, 400_000)
+        gfeat = torch.full((sc["n"], B.FEAT_STRIDE), 5.0, device="cuda")
+        grads = B.SceneGrads(dev)
+        torch.cuda.synchronize()
+        B.render_frame(dev, c, fr, stream=stream)
+        B.render_backward(c, fr, g_rgb, g_T, gfeat, stream=stream)
+        B.preprocess_backward(dev, c, fr, gfeat, grads, stream=stream)
+        B.render_backward(c, fr, g_rgb, g_T, gfeat, stream=stream)         # again: cleared, not added to
+        torch.cuda.synchronize()
+        outs.append((gfeat.clone(), grads.mean.clone(), grads.scale.clone(), grads.sh.clone()))
+    for a, b in zip(outs[0], outs[1]):
+        scale_ = a.abs().max().item()
+        assert (a - b).abs().max().item() <= 1e-4 * scale_ + 1e-6
+    assert outs[0][0].abs().max().item() > 0
