@@ -347,3 +347,31 @@ def test_runs_on_a_side_stream():
     s.synchronize()
     P.compare_binned(fr, ofr.binned)
     P.compare_image(fr, ofr.img, cam)
+
+
+@pytest.mark.parametrize("lengths", [
+    (4096, 4097, 8192, 8193), (16384, 16385, 512, 513), (2048, 2049, 1, 0), (12288, 12289, 64, 65),
+])
+def test_list_lengths_on_the_size_class_boundaries(lengths):
+    """Four tiles whose lists have exactly the given lengths (tiny splats at the tile centres, at
+    random depths): every boundary between the per-tile sort's size classes, from both sides."""
+    W, H = 64, 16
+    eye = (0.0, 0.0, -10.0)
+    cam = scenes.make_camera(scenes.look_at(eye, (0.0, 0.0, 0.0), (0.0, -1.0, 0.0)), eye, W, H, 50.0)
+    rng = np.random.default_rng(sum(lengths))
+    means = []
+    # the camera's axes from its own view matrix: world = eye + R^T (x, y, z)_camera
+    V = np.asarray(cam["view"], np.float64).reshape(3, 4)
+    R, t = V[:, :3], V[:, 3]
+    for tile, L in enumerate(lengths):
+        u, v = 16.0 * tile + 8.0, 8.0
+        z = 10.0 + rng.uniform(-1.0, 1.0, size=L)
+        pc = np.stack([(u - cam["cx"]) / cam["fx"] * z, (v - cam["cy"]) / cam["fy"] * z, z])
+        means.append((R.T @ (pc - t[:, None])).T)
+    means = np.concatenate(means) if sum(lengths) else np.zeros((0, 3))
+    order = rng.permutation(len(means))
+    sc = scenes.hand_placed_scene(means[order], (0.002, 0.002, 0.002), opacity=0.5, sh_dc=(0.4, 0.2, 0.1))
+    r = P.full_compare(sc, dict(cam, binning=1))
+    lens = np.diff(r.oracle.binned.tile_offsets.astype(np.int64))
+    assert tuple(lens) == tuple(lengths), lens
+    _report(f"class boundaries {lengths}", r.stats)
