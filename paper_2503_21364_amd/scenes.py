@@ -231,3 +231,60 @@ def hostile_scene(n: int = 3000, seed: int = 91, group_size: int = 40):
     sc["rot"][:, g["quat_tiny"]] *= np.float32(1e-20)
     sc["rot"][:, g["quat_large"]] *= np.float32(1e18)
     return sc, groups
+
+
+# ---------------------------------------------------------------------------------------------
+# Anchor scenes (the input of the AnchorDecoder, Sec. 4.2.1): anchors that carry a feature
+# vector, per-axis extents and K learnable offsets, plus the weights of the three two-layer
+# perceptrons that turn an anchor and a viewing direction into K Gaussian primitives.
+# Layout (float32):
+#     position (3, A)        anchor centres
+#     feature  (A, F)        F = ANCHOR_FEAT values per anchor, one record per anchor
+#     extent   (6, A)        linear, > 0: rows 0-2 scale the offsets, rows 3-5 bound the scales
+#     offsets  (A, K, 3)     offsets of the K primitives of an anchor, in units of extent 0-2
+#     mlp      {"opacity" | "colour" | "cov": dict(w1 (F, F+3), b1 (F,), w2t (F, outs), b2 (outs,))}
+#              first layer as (hidden unit, input), second layer as (hidden unit, output);
+#              outs = K, 3K, 7K
+ANCHOR_FEAT = 32
+ANCHOR_K = 10
+ANCHOR_OUTS = {"opacity": 1, "colour": 3, "cov": 7}      # outputs per primitive
+
+
+def make_decoder(seed: int = 7000, k: int = ANCHOR_K, scale: float = 1.0) -> dict:
+    """Random weights of the three perceptrons (fan-in scaled normal draws, small biases)."""
+    rng = np.random.default_rng(seed)
+    F, D = ANCHOR_FEAT, ANCHOR_FEAT + 3
+    mlp = {}
+    for name, per in ANCHOR_OUTS.items():
+        outs = per * k
+        mlp[name] = dict(
+            w1=_normal(rng, (F, D), 0.0, scale / math.sqrt(D)),
+            b1=_normal(rng, (F,), 0.0, 0.1),
+            w2t=_normal(rng, (F, outs), 0.0, scale / math.sqrt(F)),
+            b2=_normal(rng, (outs,), 0.0, 0.1))
+    return mlp
+
+
+def make_anchor_scene(a: int, seed: int = 6000, k: int = ANCHOR_K, layout: str = "cube") -> dict:
+    """Draw `a` anchors.  layout "cube": centres uniform in [-1,1]^3 (seen by config 0's camera);
+    "clusters": the 64 clusters of config 2 (seen by its cameras).  With k = 10, 300 k anchors
+    of the cluster layout decode to 3 M candidate primitives, the size of config 2."""
+    rng = np.random.default_rng(seed)
+    if layout == "cube":
+        position = rng.uniform(-1.0, 1.0, size=(3, a)).astype(np.float32)
+        reach_mu, bound_mu = -3.0, -3.0
+    elif layout == "clusters":
+        centres, stds, rots = cluster_layout(2000)
+        which = rng.integers(0, 64, size=a)
+        local = _normal(rng, (a, 3)) * stds[which].astype(np.float32)
+        position = np.ascontiguousarray((np.einsum("nij,nj->ni", rots[which].astype(np.float32), local)
+                                         + centres[which].astype(np.float32)).T.astype(np.float32))
+        reach_mu, bound_mu = -2.0, -3.3
+    else:
+        raise ValueError(f"unknown layout {layout}")
+    feature = _normal(rng, (a, ANCHOR_FEAT))
+    extent = np.empty((6, a), dtype=np.float32)
+    extent[:3] = np.exp(_normal(rng, (3, a), reach_mu, 0.4))
+    extent[3:] = np.exp(_normal(rng, (3, a), bound_mu, 0.8))
+    offsets = _normal(rng, (a, k, 3))
+    return dict(position=position, feature=feature, extent=extent, offsets=offsets, a=a, k=k)

@@ -1,0 +1,258 @@
+"""Pins of the AnchorDecoder oracle (oracle/anchor_ref.py) against closed forms, a library
+perceptron, invariants and the rasteriser oracle's colour convention.  CPU only."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import anchor_ref as AR
+from oracle import ref
+from paper_2503_21364_amd import scenes
+
+F = scenes.ANCHOR_FEAT
+
+
+def _zero_decoder(k):
+    mlp = scenes.make_decoder(seed=11, k=k)
+    for p in mlp.values():
+        for w in p.values():
+            w[...] = 0.0
+    return mlp
+
+
+def _logistic(y):
+    return 1.0 / (1.0 + math.exp(-y))
+
+
+def test_zero_second_layer_gives_the_bias_closed_form():
+    # W2 = 0: every raw output is its bias, whatever the anchor and the view.  Written out slot by
+    # slot: slot = v K + j, colour units 3j+c, covariance units 7j+m (3 scales, then 4 quaternion).
+    k = 4
+    sc = scenes.make_anchor_scene(7, seed=3, k=k)
+    mlp = scenes.make_decoder(seed=5, k=k)
+    for p in mlp.values():
+        p["w2t"][...] = 0.0
+    visible = np.array([5, 0, 6, 2])
+    d = AR.decode(sc, mlp, (0.3, -0.2, 4.0), visible)
+    assert d.n == len(visible) * k
+    for v, a in enumerate(visible):
+        for j in range(k):
+            s = v * k + j
+            b = float(mlp["opacity"]["b2"][j])
+            assert d.opacity[s] == pytest.approx(max(math.tanh(b), 0.0), abs=1e-15)
+            assert (d.opacity[s] > 0) == (b > 0)
+            for c in range(3):
+                col = _logistic(float(mlp["colour"]["b2"][3 * j + c]))
+                assert d.colour[c, s] == pytest.approx(col, abs=1e-15)
+                assert d.sh_dc[c, s] == pytest.approx((col - 0.5) / 0.28209479177387814, abs=1e-12)
+                bound = float(sc["extent"][3 + c, a])
+                assert d.scale[c, s] == pytest.approx(bound * _logistic(float(mlp["cov"]["b2"][7 * j + c])), rel=1e-14)
+                reach = float(sc["extent"][c, a])
+                assert d.mean[c, s] == pytest.approx(
+                    float(sc["position"][c, a]) + float(sc["offsets"][a, j, c]) * reach, abs=1e-14)
+            for m in range(4):
+                assert d.rot[m, s] == pytest.approx(float(mlp["cov"]["b2"][7 * j + 3 + m]), abs=1e-15)
+
+
+def test_pass_through_first_layer_shows_relu_and_index_order():
+    # hidden unit h = relu(feature[h+1 mod F]) (a non-symmetric W1, so a transposed W1 fails);
+    # output unit u = hidden unit (5u + 2) mod F (a non-symmetric W2).
+    k = 10
+    sc = scenes.make_anchor_scene(9, seed=8, k=k)
+    mlp = _zero_decoder(k)
+    for name, per in AR.GROUPS:
+        p = mlp[name]
+        for h in range(F):
+            p["w1"][h, (h + 1) % F] = 1.0
+        for u in range(per * k):
+            p["w2t"][(5 * u + 2) % F, u] = 1.0
+    d = AR.decode(sc, mlp, (0.0, 0.0, 4.0))
+    feat = sc["feature"].astype(np.float64)
+    hid = np.maximum(np.roll(feat, -1, axis=1), 0.0)          # hid[:, h] = relu(feat[:, h+1])
+    assert (feat < 0).any()
+    for a in range(sc["a"]):
+        for j in range(k):
+            s = a * k + j
+            assert d.pre_opacity[s] == hid[a, (5 * j + 2) % F]
+            for c in range(3):
+                assert d.colour[c, s] == pytest.approx(_logistic(hid[a, (5 * (3 * j + c) + 2) % F]), abs=1e-15)
+            for m in range(4):
+                assert d.rot[m, s] == hid[a, (5 * (7 * j + 3 + m) + 2) % F]
+
+
+def test_view_direction_points_from_camera_to_anchor_and_ignores_distance():
+    k = 2
+    sc = scenes.make_anchor_scene(3, seed=1, k=k)
+    sc["feature"][...] = 0.0
+    sc["position"][...] = np.array([[0.0, 1.0, 0.0], [0.0, 0.0, 0.0], [0.0, 0.0, -2.0]], np.float32)   # columns = anchors
+    mlp = _zero_decoder(k)
+    p = mlp["cov"]
+    # hidden 0/1/2 = relu(+dir.x / +dir.y / +dir.z), hidden 3/4/5 = relu(-dir.x / -dir.y / -dir.z)
+    for ax in range(3):
+        p["w1"][ax, F + ax] = 1.0
+        p["w1"][3 + ax, F + ax] = -1.0
+    # quaternion units of primitive 0 read hidden 0, 2, 3, 5
+    for m, h in enumerate((0, 2, 3, 5)):
+        p["w2t"][h, 3 + m] = 1.0
+    cam = (0.0, 0.0, -2.0)
+    d = AR.decode(sc, mlp, cam)
+    # anchor 0 at the origin: direction (0,0,1); anchor 1 at (1,0,0): (1,0,2)/sqrt 5; anchor 2 at the camera: 0
+    np.testing.assert_allclose(d.rot[:, 0 * k], [0.0, 1.0, 0.0, 0.0], atol=1e-15)
+    np.testing.assert_allclose(d.rot[:, 1 * k], [1 / math.sqrt(5), 2 / math.sqrt(5), 0.0, 0.0], atol=1e-15)
+    np.testing.assert_allclose(d.rot[:, 2 * k], [0.0, 0.0, 0.0, 0.0], atol=0)
+    # the camera twice as far along the same rays through anchor 0: same direction, same output
+    far = AR.decode(sc, mlp, (0.0, 0.0, -4.0), visible=[0])
+    np.testing.assert_allclose(far.rot[:, 0], d.rot[:, 0], atol=1e-15)
+    # from the other side the direction flips
+    back = AR.decode(sc, mlp, (0.0, 0.0, 3.0), visible=[0])
+    np.testing.assert_allclose(back.rot[:, 0], [0.0, 0.0, 0.0, 1.0], atol=1e-15)
+
+
+def test_perceptron_equals_library_modules():
+    k = 10
+    mlp = scenes.make_decoder(seed=21, k=k)
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((50, F + 3))
+    for name, per in AR.GROUPS:
+        p = mlp[name]
+        net = torch.nn.Sequential(torch.nn.Linear(F + 3, F), torch.nn.ReLU(), torch.nn.Linear(F, per * k)).double()
+        with torch.no_grad():
+            net[0].weight.copy_(torch.from_numpy(p["w1"].astype(np.float64)))
+            net[0].bias.copy_(torch.from_numpy(p["b1"].astype(np.float64)))
+            net[2].weight.copy_(torch.from_numpy(p["w2t"].astype(np.float64).T.copy()))
+            net[2].bias.copy_(torch.from_numpy(p["b2"].astype(np.float64)))
+            want = net(torch.from_numpy(x)).numpy()
+        np.testing.assert_allclose(AR.perceptron(p, x), want, rtol=0, atol=1e-13)
+
+
+def test_decode_equals_library_modules_end_to_end():
+    # the whole decode from torch modules and torch activations, assembled independently
+    k = 10
+    sc = scenes.make_anchor_scene(40, seed=12, k=k)
+    mlp = scenes.make_decoder(seed=13, k=k)
+    cam = np.array([0.4, 0.1, 3.5])
+    d = AR.decode(sc, mlp, cam)
+    pos = torch.from_numpy(sc["position"].astype(np.float64).T.copy())
+    delta = pos - torch.from_numpy(cam)
+    x = torch.cat([torch.from_numpy(sc["feature"].astype(np.float64)), torch.nn.functional.normalize(delta, dim=1)], 1)
+    out = {}
+    for name, per in AR.GROUPS:
+        p = mlp[name]
+        h = torch.relu(torch.nn.functional.linear(x, torch.from_numpy(p["w1"].astype(np.float64)),
+                                                  torch.from_numpy(p["b1"].astype(np.float64))))
+        out[name] = torch.nn.functional.linear(h, torch.from_numpy(p["w2t"].astype(np.float64).T.copy()),
+                                               torch.from_numpy(p["b2"].astype(np.float64))).reshape(sc["a"], k, per)
+    ext = torch.from_numpy(sc["extent"].astype(np.float64).T.copy())
+    op = torch.tanh(out["opacity"][..., 0]).clamp_min(0.0)
+    col = torch.sigmoid(out["colour"])
+    scl = ext[:, None, 3:] * torch.sigmoid(out["cov"][..., :3])
+    mean = pos[:, None, :] + torch.from_numpy(sc["offsets"].astype(np.float64)) * ext[:, None, :3]
+    n = d.n
+    np.testing.assert_allclose(d.opacity, op.reshape(n).numpy(), atol=1e-14)
+    np.testing.assert_allclose(d.colour, col.reshape(n, 3).numpy().T, atol=1e-14)
+    np.testing.assert_allclose(d.scale, scl.reshape(n, 3).numpy().T, rtol=1e-13)
+    np.testing.assert_allclose(d.rot, out["cov"][..., 3:].reshape(n, 4).numpy().T, atol=1e-13)
+    np.testing.assert_allclose(d.mean, mean.reshape(n, 3).numpy().T, atol=1e-14)
+
+
+def test_invariants_translation_reach_and_list_order():
+    k = 10
+    sc = scenes.make_anchor_scene(60, seed=30, k=k)
+    mlp = scenes.make_decoder(seed=31, k=k)
+    cam = np.array([0.5, -0.25, 4.0])
+    d = AR.decode(sc, mlp, cam)
+    # translating anchors and camera together (by amounts exact in float64) moves only the centres
+    t = np.array([2.0, -4.0, 8.0])
+    moved = dict(sc, position=sc["position"].astype(np.float64) + t[:, None])
+    dm = AR.decode(moved, mlp, cam + t)
+    np.testing.assert_allclose(dm.mean - t[:, None], d.mean, atol=1e-14)
+    for name in ("scale", "rot", "opacity", "colour"):
+        np.testing.assert_allclose(getattr(dm, name), getattr(d, name), atol=1e-14)
+    # doubling the reach doubles every centre's displacement from its anchor and nothing else
+    wide = dict(sc, extent=np.concatenate([2 * sc["extent"][:3], sc["extent"][3:]]))
+    dw = AR.decode(wide, mlp, cam)
+    anchor_of_slot = np.repeat(sc["position"].astype(np.float64), k, axis=1)
+    np.testing.assert_allclose(dw.mean - anchor_of_slot, 2 * (d.mean - anchor_of_slot), atol=1e-14)
+    np.testing.assert_array_equal(dw.scale, d.scale)
+    # doubling the scale bound doubles the scales
+    big = dict(sc, extent=np.concatenate([sc["extent"][:3], 2 * sc["extent"][3:]]))
+    np.testing.assert_allclose(AR.decode(big, mlp, cam).scale, 2 * d.scale, rtol=1e-15)
+    # a list of anchors (with a repeat) gives the listed anchors' blocks in list order
+    lst = np.array([17, 3, 59, 3, 0])
+    dl = AR.decode(sc, mlp, cam, lst)
+    assert dl.n == len(lst) * k
+    for v, a in enumerate(lst):
+        for name in ("mean", "scale", "rot", "colour"):
+            np.testing.assert_allclose(getattr(dl, name)[:, v * k:(v + 1) * k], getattr(d, name)[:, a * k:(a + 1) * k],
+                                       rtol=0, atol=1e-14)      # the library product rounds by batch shape
+        np.testing.assert_allclose(dl.opacity[v * k:(v + 1) * k], d.opacity[a * k:(a + 1) * k], rtol=0, atol=1e-14)
+    assert AR.decode(sc, mlp, cam, np.zeros(0, np.int64)).n == 0
+
+
+def test_mask_is_the_sign_of_the_opacity_output():
+    k = 10
+    sc = scenes.make_anchor_scene(200, seed=40, k=k)
+    mlp = scenes.make_decoder(seed=41, k=k)
+    cam = (0.0, 0.0, 4.0)
+    d = AR.decode(sc, mlp, cam)
+    kept = d.opacity > 0
+    assert 0.2 < kept.mean() < 0.8                      # the synthetic decoder keeps about half
+    assert ((d.opacity >= 0) & (d.opacity < 1)).all()
+    np.testing.assert_array_equal(kept, d.pre_opacity > 0)
+    # tanh is odd: the negated output layer keeps exactly the others, with mirrored raw outputs
+    neg = dict(mlp, opacity=dict(mlp["opacity"], w2t=-mlp["opacity"]["w2t"], b2=-mlp["opacity"]["b2"]))
+    dn = AR.decode(sc, neg, cam)
+    np.testing.assert_allclose(dn.pre_opacity, -d.pre_opacity, atol=1e-15)
+    np.testing.assert_array_equal(dn.opacity > 0, (~kept) & (d.pre_opacity != 0))
+    np.testing.assert_allclose(dn.opacity[~kept], np.tanh(-d.pre_opacity[~kept]), atol=1e-15)
+
+
+def test_colour_round_trip_through_the_rasteriser_oracle():
+    # the degree-0 coefficient written by the decoder gives back the decoder's colour when the
+    # rasteriser oracle evaluates its SH colour 0.5 + Y_00 dc
+    k = 10
+    sc = scenes.make_anchor_scene(300, seed=50, k=k)
+    mlp = scenes.make_decoder(seed=51, k=k)
+    cam = scenes.make_cameras(0)[0]
+    d = AR.decode(sc, mlp, cam["cam_pos"])
+    pre = ref.preprocess(AR.as_scene(d), cam)
+    seen = pre.tiles_touched > 0
+    assert seen.sum() > 500
+    np.testing.assert_allclose(pre.rgb[:, seen], d.colour[:, seen], atol=3e-7)
+    # and every slot the decoder did not keep is culled by the rasteriser
+    assert not (seen & (d.opacity == 0)).any()
+
+
+def test_float32_evaluation_stays_within_the_stated_bound():
+    # sequential float32 accumulation of both layers (the way a GPU thread evaluates them)
+    # differs from the float64 result by less than bound()
+    k = 10
+    sc = scenes.make_anchor_scene(6, seed=60, k=k)
+    mlp = scenes.make_decoder(seed=61, k=k, scale=2.0)
+    cam = np.array([0.2, 0.3, 3.0], np.float32)
+    idx = np.arange(sc["a"])
+    x64 = AR.view_input(sc, cam, idx)
+    bnd = AR.bound(sc, mlp, cam)
+    f32 = np.float32
+    for name, per in AR.GROUPS:
+        p = mlp[name]
+        want = AR.perceptron(p, x64)
+        got = np.empty_like(want)
+        for a in range(sc["a"]):
+            x = x64[a].astype(np.float32)
+            hid = []
+            for h in range(F):
+                acc = f32(p["b1"][h])
+                for i in range(F + 3):
+                    acc = f32(acc + f32(p["w1"][h, i] * x[i]))
+                hid.append(max(acc, f32(0)))
+            for u in range(per * k):
+                acc = f32(p["b2"][u])
+                for h in range(F):
+                    acc = f32(acc + f32(p["w2t"][h, u] * hid[h]))
+                got[a, u] = acc
+        err = np.abs(got - want).reshape(sc["a"] * k, per).T
+        lim = getattr(bnd, name)
+        assert (err <= lim).all(), (name, float((err / lim).max()))
+        assert (err > 0).any()
