@@ -243,6 +243,64 @@ int32_t lmk_gs_preprocess_backward(const lmk_gs_gaussians *g, const lmk_gs_camer
                                    const lmk_gs_projected *proj, const float *grad_feat,
                                    const lmk_gs_gaussian_grads *out, void *stream);
 
+/* ---- AnchorDecoder (Sec. 3.1: the Decoder component of the anchor-based Gaussian models; Sec. 4.2.1:
+ * its steps -- the mask of the anchors to decode, the collation of an anchor's feature with the view
+ * without the distance, three dual-layer perceptrons for covariance, colour and neural opacity, the
+ * combination with the anchor's own tensors, post-processing -- fused here into one kernel).  The
+ * report gives no formula for the steps; what each computes follows the anchor-based method that its
+ * ScaffoldGSEncoding / OctreeGSEncoding implement. */
+#define LMK_GS_ANCHOR_FEAT 32u      /* feature values per anchor = hidden width of the perceptrons */
+
+/* The anchors of a scene; device pointers, read only. */
+typedef struct lmk_gs_anchors {
+    const float *position;  /* [3][a]     anchor centres                                              */
+    const float *feature;   /* [a][LMK_GS_ANCHOR_FEAT]  one 128-byte record per anchor, 16-byte aligned */
+    const float *extent;    /* [6][a]     linear, > 0: rows 0-2 scale the offsets, rows 3-5 bound the scales */
+    const float *offsets;   /* [a][k][3]  offsets of the k primitives of an anchor, in units of extent 0-2, 8-byte aligned */
+    uint32_t a;             /* number of anchors (0 is allowed)                                       */
+    uint32_t k;             /* primitives per anchor: 10 or 4                                         */
+} lmk_gs_anchors;
+
+/* One perceptron y = W2 relu(W1 x + b1) + b2 with x = [feature, dir] (LMK_GS_ANCHOR_FEAT + 3 inputs),
+ * hidden width LMK_GS_ANCHOR_FEAT; device pointers, read only. */
+typedef struct lmk_gs_perceptron {
+    const float *w1;    /* [LMK_GS_ANCHOR_FEAT][LMK_GS_ANCHOR_FEAT + 3]  (hidden unit, input)       */
+    const float *b1;    /* [LMK_GS_ANCHOR_FEAT]                                                     */
+    const float *w2t;   /* [LMK_GS_ANCHOR_FEAT][outputs]                 (hidden unit, output)      */
+    const float *b2;    /* [outputs]                                                                */
+} lmk_gs_perceptron;
+
+/* outputs: opacity k (unit j = primitive j), colour 3k (units 3j..3j+2), cov 7k (units 7j..7j+2 the
+ * scales, 7j+3..7j+6 the quaternion). */
+typedef struct lmk_gs_anchor_decoder {
+    lmk_gs_perceptron opacity, colour, cov;
+} lmk_gs_anchor_decoder;
+
+/* Where lmk_gs_anchor_decode writes: the arrays of an lmk_gs_gaussians of n = v * k primitives with
+ * sh_degree 0, device pointers.  Slot v' * k + j holds primitive j of the anchor listed v'-th. */
+typedef struct lmk_gs_decoded {
+    float *mean;      /* [3][n] */
+    float *scale;     /* [3][n] */
+    float *rot;       /* [4][n] unnormalised quaternion (w, x, y, z) */
+    float *opacity;   /* [n]    */
+    float *sh;        /* [n][4] degree-0 coefficient per channel, then 0; 16-byte aligned */
+} lmk_gs_decoded;
+
+/* Decodes the anchors listed in `visible` (device array of v anchor indices computed beforehand, the
+ * pre-computed mask indices of Sec. 4.2.1; NULL = anchors 0..v-1, then v <= a) as seen from cam_pos
+ * (host pointer, 3 floats).  Per listed anchor: dir = (position - cam_pos) / |.| (0 if the two
+ * coincide); the three perceptrons on [feature, dir]; per primitive j: opacity = tanh(y) if y > 0,
+ * else exactly 0 (lmk_gs_preprocess culls such a primitive); colour = logistic(y), stored as the
+ * degree-0 SH coefficient (colour - 0.5) / Y_00; scale = extent[3..5] * logistic(y);
+ * rotation = the four quaternion units as they are; centre = position + offsets[j] * extent[0..2].
+ * All in fp32.  A listed index >= a gives k primitives of opacity 0 (all other values 0).  Every
+ * element of the n slots of `out` is written; `out` feeds lmk_gs_preprocess directly.
+ * Asynchronous on `stream`.  LMK_GS_ERR_INVALID: NULL or misaligned pointer, v * k >= 2^32, visible
+ * NULL with v > a; LMK_GS_ERR_UNSUPPORTED: k other than 10 or 4. */
+int32_t lmk_gs_anchor_decode(const lmk_gs_anchors *anchors, const lmk_gs_anchor_decoder *decoder,
+                             const float *cam_pos, const uint32_t *visible, uint32_t v,
+                             const lmk_gs_decoded *out, void *stream);
+
 /* Copies {pair count D, status} of the frame from scratch to the host.
  * Synchronises `stream`.  Either output pointer may be NULL. */
 int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream);

@@ -24,7 +24,7 @@ PRE_BLOCK = 256
 EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
            "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version",
            "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
-           "lmk_gs_preprocess_backward")
+           "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode")
 
 
 class Gaussians(C.Structure):
@@ -34,6 +34,24 @@ class Gaussians(C.Structure):
 
 
 class GaussianGrads(C.Structure):
+    _fields_ = [("mean", C.c_void_p), ("scale", C.c_void_p), ("rot", C.c_void_p),
+                ("opacity", C.c_void_p), ("sh", C.c_void_p)]
+
+
+class Anchors(C.Structure):
+    _fields_ = [("position", C.c_void_p), ("feature", C.c_void_p), ("extent", C.c_void_p),
+                ("offsets", C.c_void_p), ("a", C.c_uint32), ("k", C.c_uint32)]
+
+
+class Perceptron(C.Structure):
+    _fields_ = [("w1", C.c_void_p), ("b1", C.c_void_p), ("w2t", C.c_void_p), ("b2", C.c_void_p)]
+
+
+class AnchorDecoder(C.Structure):
+    _fields_ = [("opacity", Perceptron), ("colour", Perceptron), ("cov", Perceptron)]
+
+
+class Decoded(C.Structure):
     _fields_ = [("mean", C.c_void_p), ("scale", C.c_void_p), ("rot", C.c_void_p),
                 ("opacity", C.c_void_p), ("sh", C.c_void_p)]
 
@@ -95,13 +113,15 @@ def lib() -> C.CDLL:
                                                  C.c_void_p, C.POINTER(GaussianGrads), C.c_void_p]
         l.lmk_gs_render_backward.argtypes = [C.POINTER(Projected), C.c_uint32, C.POINTER(Binned), C.POINTER(Camera),
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.lmk_gs_anchor_decode.argtypes = [C.POINTER(Anchors), C.POINTER(AnchorDecoder), C.POINTER(C.c_float),
+                                           C.c_void_p, C.c_uint32, C.POINTER(Decoded), C.c_void_p]
         l.lmk_gs_read_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_void_p]
         l.lmk_gs_strerror.argtypes = [C.c_int32]
         l.lmk_gs_strerror.restype = C.c_char_p
         for name in ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
                      "lmk_gs_read_status", "lmk_gs_last_hip_error", "lmk_gs_index_build",
                      "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
-           "lmk_gs_preprocess_backward"):
+                     "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode"):
             getattr(l, name).restype = C.c_int32
         l.lmk_gs_version.restype = C.c_uint32
         _lib = l
@@ -308,6 +328,60 @@ def preprocess_backward(scene: "Scene", cam: Camera, frame: Frame, grad_feat, gr
                                           C.byref(grads.c), _stream_handle(stream))
     if rc != OK:
         raise LmkGsError(rc, "lmk_gs_preprocess_backward")
+
+
+class AnchorScene:
+    """Device-resident anchors and decoder weights (layouts of include/lmk_gs.h)."""
+
+    def __init__(self, anchors: dict, mlp: dict, device="cuda:0"):
+        self.a, self.k = int(anchors["a"]), int(anchors["k"])
+        f = lambda t: torch.from_numpy(np.ascontiguousarray(t, dtype=np.float32)).to(device)
+        self.position, self.feature = f(anchors["position"]), f(anchors["feature"])
+        self.extent, self.offsets = f(anchors["extent"]), f(anchors["offsets"])
+        self.c = Anchors(_ptr(self.position), _ptr(self.feature), _ptr(self.extent), _ptr(self.offsets),
+                         self.a, self.k)
+        self.weights = {name: {w: f(mlp[name][w]) for w in ("w1", "b1", "w2t", "b2")}
+                        for name in ("opacity", "colour", "cov")}
+        net = lambda p: Perceptron(_ptr(p["w1"]), _ptr(p["b1"]), _ptr(p["w2t"]), _ptr(p["b2"]))
+        self.decoder = AnchorDecoder(net(self.weights["opacity"]), net(self.weights["colour"]),
+                                     net(self.weights["cov"]))
+
+
+class DecodedScene:
+    """Output buffers of lmk_gs_anchor_decode for a list of v anchors with k primitives each."""
+
+    def __init__(self, v: int, k: int, device="cuda:0"):
+        self.k, self.v, self.n = int(k), int(v), int(v) * int(k)
+        n = max(self.n, 1)
+        e = lambda shape: torch.empty(shape, dtype=torch.float32, device=device)
+        self.mean, self.scale, self.rot = e((3, n)), e((3, n)), e((4, n))
+        self.opacity, self.sh = e((n,)), e((n, 4))
+        self.c = Decoded(_ptr(self.mean), _ptr(self.scale), _ptr(self.rot), _ptr(self.opacity), _ptr(self.sh))
+
+    def scene(self) -> "Scene":
+        """The decoded slots as a Scene object (no copy) for preprocess."""
+        sc = Scene.__new__(Scene)
+        sc.n, sc.sh_degree = self.n, 0
+        sc.mean, sc.scale, sc.rot, sc.opacity, sc.sh = self.mean, self.scale, self.rot, self.opacity, self.sh
+        sc.cov3d = None
+        sc.c = Gaussians(_ptr(self.mean), _ptr(self.scale), _ptr(self.rot), _ptr(self.opacity), _ptr(self.sh),
+                         self.n, 0, None)
+        return sc
+
+
+def anchor_decode(anchors: AnchorScene, cam_pos, out: DecodedScene, visible=None, v: int | None = None,
+                  stream=None) -> None:
+    """lmk_gs_anchor_decode: `visible` is a uint32/int32 device tensor of anchor indices or None
+    (then anchors 0..v-1, v defaulting to all).  `out` must be sized for v anchors."""
+    if v is None:
+        v = anchors.a if visible is None else int(visible.numel())
+    if out.n != v * anchors.k:
+        raise ValueError("output buffers are sized for another list length")
+    cam = (C.c_float * 3)(*[float(x) for x in cam_pos])
+    rc = lib().lmk_gs_anchor_decode(C.byref(anchors.c), C.byref(anchors.decoder), cam, _ptr(visible),
+                                    C.c_uint32(v), C.byref(out.c), _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_anchor_decode")
 
 
 def read_status(frame: Frame, stream=None) -> tuple[int, int]:

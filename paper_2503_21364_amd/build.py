@@ -33,6 +33,7 @@ UNITS = {
     "render.hip": [],
     "render_bwd.hip": [],       # same options as render.hip: pass 1 repeats its arithmetic
     "preprocess_bwd.hip": [],
+    "anchor_decode.hip": [],
     "index.hip": EXACT,         # host code: the voxel of a primitive is decided by one fp32 division
 }
 

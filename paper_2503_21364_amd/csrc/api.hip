@@ -206,6 +206,32 @@ int32_t lmk_gs_preprocess_backward(const lmk_gs_gaussians *g, const lmk_gs_camer
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
 }
 
+int32_t lmk_gs_anchor_decode(const lmk_gs_anchors *anchors, const lmk_gs_anchor_decoder *decoder,
+                             const float *cam_pos, const uint32_t *visible, uint32_t v,
+                             const lmk_gs_decoded *out, void *stream)
+{
+    if (!anchors || !decoder || !cam_pos || !out) return LMK_GS_ERR_INVALID;
+    if (anchors->k != 10u && anchors->k != 4u) return LMK_GS_ERR_UNSUPPORTED;
+    if ((uint64_t)v * anchors->k >= (1ull << 32)) return LMK_GS_ERR_INVALID;
+    if (!visible && v > anchors->a) return LMK_GS_ERR_INVALID;
+    for (int i = 0; i < 3; ++i)
+        if (!std::isfinite(cam_pos[i])) return LMK_GS_ERR_INVALID;
+    if (v > 0) {
+        if (anchors->a > 0 && (!anchors->position || !anchors->feature || !anchors->extent || !anchors->offsets))
+            return LMK_GS_ERR_INVALID;
+        if (!aligned(anchors->feature, 16) || !aligned(anchors->offsets, 8)) return LMK_GS_ERR_INVALID;
+        const lmk_gs_perceptron *nets[3] = {&decoder->opacity, &decoder->colour, &decoder->cov};
+        for (const lmk_gs_perceptron *p : nets)
+            if (!p->w1 || !p->b1 || !p->w2t || !p->b2 || !aligned(p->w1, 4) || !aligned(p->w2t, 4))
+                return LMK_GS_ERR_INVALID;
+        if (!out->mean || !out->scale || !out->rot || !out->opacity || !out->sh) return LMK_GS_ERR_INVALID;
+        if (!aligned(out->sh, 16)) return LMK_GS_ERR_INVALID;
+    }
+    const hipError_t e = launch_anchor_decode(*anchors, *decoder, cam_pos, visible, v, *out,
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
 int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream)
 {
     if (!scratch) return LMK_GS_ERR_INVALID;

@@ -138,5 +138,8 @@ hipError_t launch_render_backward(const lmk_gs_projected &proj, u32 n, const lmk
 hipError_t launch_preprocess_backward(const lmk_gs_gaussians &g, const ProjParams &pp,
                                       const lmk_gs_projected &proj, const float *grad_feat,
                                       const lmk_gs_gaussian_grads &out, hipStream_t stream);
+hipError_t launch_anchor_decode(const lmk_gs_anchors &anchors, const lmk_gs_anchor_decoder &decoder,
+                                const float *cam_pos, const u32 *visible, u32 v,
+                                const lmk_gs_decoded &out, hipStream_t stream);
 
 }  // namespace lmk

@@ -176,6 +176,38 @@ def test_preprocess_backward_rejects_bad_arguments():
     assert call(g, bad, proj) == B.ERR_UNSUPPORTED
 
 
+def test_anchor_decode_rejects_bad_arguments():
+    lib = B.lib()
+    assert C.sizeof(B.Anchors) == 4 * 8 + 2 * 4 and C.sizeof(B.Perceptron) == 4 * 8
+    assert C.sizeof(B.AnchorDecoder) == 3 * C.sizeof(B.Perceptron) and C.sizeof(B.Decoded) == 5 * 8
+    an = lambda **kw: B.Anchors(**{**dict(position=0x1000, feature=0x2000, extent=0x3000, offsets=0x4000, a=100, k=10), **kw})
+    net = lambda **kw: B.Perceptron(**{**dict(w1=0x5000, b1=0x5100, w2t=0x5200, b2=0x5300), **kw})
+    dec = lambda **kw: B.AnchorDecoder(**{**dict(opacity=net(), colour=net(), cov=net()), **kw})
+    out = lambda **kw: B.Decoded(**{**dict(mean=0x6000, scale=0x7000, rot=0x8000, opacity=0x9000, sh=0xa000), **kw})
+    cam = (C.c_float * 3)(0.0, 0.0, 4.0)
+
+    def call(a_=an(), d_=dec(), c_=cam, vis=C.c_void_p(0xb000), v=50, o_=out()):
+        return lib.lmk_gs_anchor_decode(None if a_ is None else C.byref(a_), None if d_ is None else C.byref(d_),
+                                        c_, vis, C.c_uint32(v), None if o_ is None else C.byref(o_), None)
+    assert call(a_=None) == B.ERR_INVALID
+    assert call(d_=None) == B.ERR_INVALID
+    assert call(c_=None) == B.ERR_INVALID
+    assert call(o_=None) == B.ERR_INVALID
+    assert call(a_=an(k=7)) == B.ERR_UNSUPPORTED
+    assert call(a_=an(feature=None)) == B.ERR_INVALID
+    assert call(a_=an(feature=0x2004)) == B.ERR_INVALID                      # records are 16-byte aligned
+    assert call(a_=an(offsets=0x4004)) == B.ERR_INVALID
+    assert call(d_=dec(colour=net(w2t=None))) == B.ERR_INVALID
+    assert call(d_=dec(cov=net(b1=None))) == B.ERR_INVALID
+    assert call(o_=out(rot=None)) == B.ERR_INVALID
+    assert call(o_=out(sh=0xa008)) == B.ERR_INVALID
+    assert call(vis=None, v=101) == B.ERR_INVALID                            # no list: at most all anchors
+    assert call(v=(1 << 32) // 10 + 1) == B.ERR_INVALID                      # v * k must fit 32 bits
+    assert call(c_=(C.c_float * 3)(0.0, float("nan"), 0.0)) == B.ERR_INVALID
+    assert call(v=0) == B.OK                                                 # nothing listed: nothing launched
+    assert call(v=0, a_=an(a=0, position=None, feature=None, extent=None, offsets=None)) == B.OK
+
+
 def test_index_build_matches_the_oracle_and_rejects_bad_input():
     from oracle import ref
     for cfg, n, vs in [(2, 50_000, 2.0), (3, 80_000, 40.0), (0, 1000, 0.3), (1, 777, 1.0), (0, 1, 1.0)]:
