@@ -106,6 +106,113 @@ def committed_traffic(cfg, binning):
     return out
 
 
+def anchor_bench(args):
+    """Anchor-model frames: lmk_gs_anchor_decode + preprocess + bin_sort + render per viewpoint.
+
+    Algorithmic work of the decode kernel per listed anchor (k primitives, F = 32 features):
+    flops = 2 (3 F (F + 3) + F 11 k) for the two layers of the three perceptrons (13 760 at k = 10;
+    the activations are not counted); bytes = 4 (3 + F + 6 + 3 k) read + 4 k (3 + 3 + 4 + 1 + 4) written
+    (884 at k = 10)."""
+    import numpy as np
+    import torch
+    from paper_2503_21364_amd import binding as B
+    from paper_2503_21364_amd import scenes
+
+    a, k, F = args.anchors, scenes.ANCHOR_K, scenes.ANCHOR_FEAT
+    anchors = scenes.make_anchor_scene(a, seed=6000, k=k, layout="clusters")
+    mlp = scenes.make_decoder(seed=7000, k=k)
+    spec = scenes.CONFIGS[2]
+    W, H = spec["width"], spec["height"]
+    cams = [dict(c, binning=args.binning) for c in scenes.make_cameras(2)]
+    if args.views is not None:
+        cams = cams[:max(1, args.views)]
+    ccams = [B.make_camera(c) for c in cams]
+    nviews = len(cams)
+    dev = B.AnchorScene(anchors, mlp)
+    dec = B.DecodedScene(a, k)
+    scene = dec.scene()
+    n = scene.n
+
+    fr = B.Frame(n, W, H, 64_000_000)
+    Ds = []
+    for c, cc in zip(cams, ccams):
+        B.anchor_decode(dev, c["cam_pos"], dec)
+        B.render_frame(scene, cc, fr)
+        D, status = B.read_status(fr)
+        assert status == B.OK, f"status {status} in the sizing run"
+        Ds.append(D)
+    kept = float((dec.opacity > 0).float().mean().item())
+    del fr
+    torch.cuda.empty_cache()
+    capacity = int(max(Ds) * 1.25) + 4096
+    fr = B.Frame(n, W, H, capacity)
+
+    def frame(i, marks=None):
+        c, cc = cams[i % nviews], ccams[i % nviews]
+        if marks: marks[0].record()
+        B.anchor_decode(dev, c["cam_pos"], dec)
+        if marks: marks[1].record()
+        B.preprocess(scene, cc, fr)
+        if marks: marks[2].record()
+        B.bin_sort(cc, fr)
+        if marks: marks[3].record()
+        B.render(cc, fr)
+        if marks: marks[4].record()
+
+    for i in range(args.warmup):
+        frame(i)
+    torch.cuda.synchronize()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = [[ev() for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        frame(i, marks[i])
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    _, status = B.read_status(fr)
+    assert status == B.OK, f"status {status}"
+    stage = lambda j: np.array([m[j].elapsed_time(m[j + 1]) for m in marks])
+    t_dec, t_pre, t_sort, t_blend = stage(0), stage(1), stage(2), stage(3)
+
+    flops = 2.0 * (3 * F * (F + 3) + F * 11 * k) * a
+    byts = (4.0 * (3 + F + 6 + 3 * k) + 4.0 * k * 15) * a
+    tf = flops / (t_dec.mean() * 1e-3) / 1e12
+    out = {
+        "metric": "frames/s, anchor model: decode + 1080p render",
+        "value": args.steps / total_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * total_s / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"anchors: {a} anchors (config 2's clusters) x {k} primitives = {n} candidate "
+                               f"Gaussians decoded per frame, {W}x{H}, {nviews} seeded viewpoints of config 2",
+                   "binning": args.binning, "kept_fraction": kept, "pairs_per_frame_mean": float(np.mean(Ds)),
+                   "capacity": capacity},
+        "stage_ms": {"anchor_decode": float(t_dec.mean()), "preprocess": float(t_pre.mean()),
+                     "bin_sort": float(t_sort.mean()), "render": float(t_blend.mean())},
+        "roofline": {"kernel": "anchor_decode_kernel", "bound": "alu", "achieved": tf, "peak": FP32_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": None,
+                     "avg_launch_ms": float(t_dec.mean()), "flops_per_launch": flops,
+                     "hbm_GBs": byts / (t_dec.mean() * 1e-3) / 1e9, "bytes_per_launch": byts},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import anchor_ref as AR
+        from oracle import ref
+        c0 = time.perf_counter()
+        d = AR.decode(anchors, mlp, cams[0]["cam_pos"])
+        c1 = time.perf_counter()
+        ofr = ref.render_frame(AR.as_scene(d), dict(cams[0], binning=0))
+        c2 = time.perf_counter()
+        cores = len(os.sched_getaffinity(0))
+        omp = os.environ.get("OMP_NUM_THREADS")
+        threads = min(cores, int(omp)) if omp and omp.isdigit() else cores
+        out["cpu_baseline"] = dict(value=1.0 / (c2 - c0), unit="frames/s", cores=threads, kind="oracle",
+                                   sample=f"viewpoint 0 only: decode of all {a} anchors ({c1 - c0:.1f} s, numpy float64) "
+                                          f"and one whole frame of the rasteriser oracle ({c2 - c1:.1f} s)",
+                                   decode_anchors_per_s=a / (c1 - c0))
+        del ofr
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +230,10 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="also time lmk_gs_render_backward (gradient through the compositing) on every viewpoint "
                          "and add a \"backward\" object to the JSON line; the headline value is unchanged")
+    ap.add_argument("--anchors", type=int, default=0, metavar="A",
+                    help="anchor-model mode: A anchors of the cluster layout (300000 gives 3 M candidate primitives) "
+                         "are decoded by lmk_gs_anchor_decode in every frame and rendered by the three calls; the "
+                         "JSON line then reports that pipeline and the roofline of the decode kernel")
     ap.add_argument("--no-cov-cache", action="store_true",
                     help="compute every primitive's 3D covariance from rotation and scale in every frame instead "
                          "of reading the parameter cache built once per scene")
@@ -148,6 +259,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.lib()   # fails loudly if the HIP library is not built
+    if args.anchors > 0:
+        return anchor_bench(args)
     spec = scenes.CONFIGS[args.cfg]
     n = spec["n"] if args.n is None else args.n
     W, H = spec["width"], spec["height"]

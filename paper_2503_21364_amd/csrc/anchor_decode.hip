@@ -24,7 +24,7 @@ namespace {
 
 constexpr u32 kFeat = LMK_GS_ANCHOR_FEAT;
 constexpr u32 kIn = kFeat + 3;
-constexpr u32 kDecBlock = 256;
+constexpr u32 kDecBlock = 64;           // one wavefront per workgroup: nothing is shared between wavefronts
 constexpr float kInvY00 = 3.5449077018110318f;      // 1 / (0.5 sqrt(1/pi))
 
 // y = W2 relu(W1 x + b1) + b2.  w1 [kFeat][kIn], w2t [kFeat][OUTS]; every index is wave-uniform.
