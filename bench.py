@@ -90,7 +90,7 @@ def _projection_backward_report(ms, n, stats, nviews):
                          "bytes_per_call": sum(byts) / len(byts)}}
 
 
-def committed_traffic(cfg, binning):
+def committed_traffic(cfg, binning, workload=None):
     """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (already scaled
     by the copy-kernel calibration), from the summary committed under profiles/.  None when
     there is no measurement for this workload."""
@@ -100,7 +100,7 @@ def committed_traffic(cfg, binning):
         with open(path) as f:
             for line in f:
                 t = line.split()
-                if len(t) == 5 and t[0] == f"cfg{cfg}" and t[1] == f"binning{binning}":
+                if len(t) == 5 and t[0] == (workload or f"cfg{cfg}") and t[1] == f"binning{binning}":
                     out[t[2]] = float(t[3]) + float(t[4])
     except OSError:
         return {}
@@ -161,6 +161,15 @@ def anchor_bench(args):
         B.render(cc, fr)
         if marks: marks[4].record()
 
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     for i in range(args.warmup):
         frame(i)
     torch.cuda.synchronize()
@@ -180,6 +189,8 @@ def anchor_bench(args):
     flops = 2.0 * (3 * F * (F + 3) + F * 11 * k) * a
     byts = (4.0 * (3 + F + 6 + 3 * k) + 4.0 * k * 15) * a
     tf = flops / (t_dec.mean() * 1e-3) / 1e12
+    # the committed counter measurement is of the default command of this mode
+    traffic = committed_traffic(2, args.binning, f"anchors{a}") if args.views is None else {}
     out = {
         "metric": "frames/s, anchor model: decode + 1080p render",
         "value": args.steps / total_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -192,7 +203,8 @@ def anchor_bench(args):
         "stage_ms": {"anchor_decode": float(t_dec.mean()), "preprocess": float(t_pre.mean()),
                      "bin_sort": float(t_sort.mean()), "render": float(t_blend.mean())},
         "roofline": {"kernel": "anchor_decode_kernel", "bound": "mfma", "achieved": tf, "peak": FP32_MFMA_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": tf / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": tf / FP32_MFMA_PEAK_TFLOPS,
+                     "traffic": traffic.get("anchor_decode_kernel"),
                      "avg_launch_ms": float(t_dec.mean()), "flops_per_launch": flops,
                      "hbm_GBs": byts / (t_dec.mean() * 1e-3) / 1e9, "bytes_per_launch": byts},
     }
