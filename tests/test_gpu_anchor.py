@@ -126,6 +126,48 @@ def test_an_anchor_at_the_camera_has_no_view_direction():
     _compare(out, anchors, mlp, cam)
 
 
+def test_saturated_activations_and_large_outputs():
+    # weights ten times larger: raw outputs of tens, tanh and the logistic function at their limits
+    anchors = scenes.make_anchor_scene(1000, seed=55)
+    mlp = scenes.make_decoder(seed=56, scale=10.0)
+    cam = (0.1, 0.2, 3.0)
+    out = _run(anchors, mlp, cam)
+    want = _compare(out, anchors, mlp, cam)
+    assert np.abs(want.pre_opacity).max() > 50 and (want.opacity > 0.999999).any()
+    assert (want.colour < 1e-6).any() and (want.colour > 1 - 1e-6).any()
+
+
+def test_non_finite_anchors_stay_confined_and_render():
+    """Anchors with NaN / infinite features, extents or centres: what they decode to is not defined,
+    but every other anchor's slots are unaffected and the rasteriser takes the result and returns a
+    finite image."""
+    a, k = 2000, 10
+    anchors = scenes.make_anchor_scene(a, seed=57)
+    mlp = scenes.make_decoder(seed=58)
+    bad = np.array([0, 31, 32, 500, 1023, 1999])
+    anchors["feature"][bad[0], 3] = np.nan
+    anchors["feature"][bad[1], :] = np.inf
+    anchors["feature"][bad[2], 17] = -np.inf
+    anchors["extent"][4, bad[3]] = np.nan
+    anchors["position"][1, bad[4]] = np.inf
+    anchors["offsets"][bad[5], 2, 0] = np.nan
+    cam = dict(scenes.make_cameras(0)[0], binning=1)
+    out = _run(anchors, mlp, cam["cam_pos"])
+    bad_slots = (bad[:, None] * k + np.arange(k)[None, :]).reshape(-1)
+    clean = {key: (np.nan_to_num(val, nan=0.0, posinf=0.0, neginf=0.0) if isinstance(val, np.ndarray) else val)
+             for key, val in anchors.items()}
+    with np.errstate(all="ignore"):
+        _compare(out, clean, mlp, cam["cam_pos"], skip_slots=bad_slots)
+    scene = out.scene()
+    fr = B.Frame(scene.n, cam["width"], cam["height"], 2_000_000)
+    B.render_frame(scene, B.make_camera(cam), fr)
+    torch.cuda.synchronize()
+    d, status = B.read_status(fr)
+    assert status == B.OK and d > 1000
+    img = fr.out_rgb.cpu().numpy()
+    assert np.isfinite(img).all() and np.isfinite(fr.out_T.cpu().numpy()).all()
+
+
 def test_nothing_listed_is_a_no_op():
     anchors = scenes.make_anchor_scene(10, seed=61)
     mlp = scenes.make_decoder(seed=62)

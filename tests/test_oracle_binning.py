@@ -120,7 +120,7 @@ def test_rule1_pipeline_still_equals_brute_force():
 
 
 def test_rule1_statistics_on_config_shapes():
-    # the reduction in pairs the rule buys on the benchmark distributions (documented in the design doc)
+    # the reduction in pairs the rule buys on the benchmark distributions
     sc = scenes.make_scene(1, n=50_000)
     cam0 = scenes.make_cameras(1)[0]
     pre0 = ref.preprocess(sc, cam0)
