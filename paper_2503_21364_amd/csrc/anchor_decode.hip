@@ -107,8 +107,83 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// ---- the pieces of a tile's work, as functions of compile-time (perceptron M, output tile T)
+
+// First layer of perceptron M: 18 accumulations from zero (the bias rides on the constant input), ReLU.
+template <u32 K, u32 M>
+__device__ __forceinline__ f32x16 first_layer(const float *s_w, const float (&xf)[kSteps1], u32 lane)
+{
+    f32x16 h = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (u32 t = 0; t < kSteps1; ++t)
+        h = __builtin_amdgcn_mfma_f32_32x32x2f32(s_w[(M * kSteps1 + t) * kWave + lane], xf[t], h, 0, 0, 0);
+    return h;
+}
+
+__device__ __forceinline__ void relu16(f32x16 &h)
+{
+#pragma unroll
+    for (u32 r = 0; r < 16; ++r) h[r] = fmaxf(h[r], 0.0f);
+}
+
+// Output tile T of the second layer of perceptron M, without its bias.
+template <u32 K, u32 M, u32 T>
+__device__ __forceinline__ f32x16 second_layer(const float *s_w, const f32x16 &h, u32 lane)
+{
+    using L = DecodeLayout<K>;
+    f32x16 y = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (u32 st = 0; st < kSteps2; ++st)
+        y = __builtin_amdgcn_mfma_f32_32x32x2f32(
+            s_w[(L::kFrag1 + (L::tiles_before(M) + T) * kSteps2 + st) * kWave + lane], h[st], y, 0, 0, 0);
+    return y;
+}
+
+// Reads out output tile T of perceptron M: bias, activation, and the value into its slot of the
+// wavefront's stage `s` (first half: opacity | centres x 3 | SH records; second half: the seven
+// covariance planes and an eighth, never read).  No control flow: a register that holds no output
+// (rows of a padded tile) writes to a slot that is overwritten later (opacity: the centres' planes;
+// colour: the padding word of a record) or never read.
+template <u32 K, u32 M, u32 T>
+__device__ __forceinline__ void read_out(const f32x16 &y, float *s, const float *s_w, u32 j, u32 hi, u32 lane,
+                                         bool live, float ex3, float ex4, float ex5)
+{
+    using L = DecodeLayout<K>;
+    constexpr u32 outs = L::outs(M);
+    float *s_sh = s + 4 * L::kPlane;
+#pragma unroll
+    for (u32 r = 0; r < 16; ++r) {
+        if (kTile * T + row_of_reg(r, 0) >= outs) continue;              // neither half-lane holds an output here
+        const u32 o = kTile * T + row_of_reg(r, 0) + 4 * hi;               // output unit of this register
+        const float yr = y[r] + s_w[L::kBias2 + (L::tiles_before(M) + T) * kTile + row_of_reg(r, 0) + 4 * hi];
+        const bool valid = o < outs;
+        if (M == 0) {
+            s[valid ? j * K + o : L::kPlane + lane] = (live && yr > 0.0f) ? tanh_pos(yr) : 0.0f;
+        } else if (M == 1) {
+            const u32 p = o / 3, c = o - 3 * p;
+            s_sh[valid ? 4 * (j * K + p) + c : 4 * (j * K) + 3] = live ? (logistic(yr) - 0.5f) * kInvY00 : 0.0f;
+        } else {
+            const u32 p = o / 7, c = o - 7 * p;
+            // a scale (c < 3) or a quaternion component; which, depends on the half-lane only
+            const u32 o0 = kTile * T + row_of_reg(r, 0), o1 = o0 + 4;     // folded: the loop is unrolled
+            const bool scale0 = o0 % 7 < 3, scale1 = o1 % 7 < 3;
+            float val = yr;
+            if (scale0 || scale1) {
+                float bound = ex5;
+                bound = c == 1 ? ex4 : bound;
+                bound = c == 0 ? ex3 : bound;
+                const float sc = bound * logistic(yr);
+                // bitwise select: both arms are computed, no branch around the exponential
+                const u32 pick = c < 3 ? ~0u : 0u;
+                val = __uint_as_float((__float_as_uint(sc) & pick) | (__float_as_uint(yr) & ~pick));
+            }
+            s[valid ? c * L::kPlane + j * K + p : 7 * L::kPlane + lane] = live ? val : 0.0f;
+        }
+    }
+}
+
 template <u32 K>
-__global__ __launch_bounds__(256) void anchor_decode_kernel(
+__global__ __launch_bounds__(256, 2) void anchor_decode_kernel(
     const float *__restrict__ position, const float *__restrict__ feature, const float *__restrict__ extent,
     const float *__restrict__ offsets, u32 a, const u32 *__restrict__ visible, u32 v,
     const float *__restrict__ op_w1, const float *__restrict__ op_b1, const float *__restrict__ op_w2t,
@@ -236,77 +311,56 @@ __global__ __launch_bounds__(256) void anchor_decode_kernel(
             xf[16] = in.p2x; xf[17] = in.p2y;
         }
 
-        // stage layout, first half of the tile's work: opacity | centres (3 planes) | SH records
+        // The tile's products in order; the read-out of an output tile follows the issue of the next product.
         float *s_op = s, *s_mean = s + L::kPlane, *s_sh = s + 4 * L::kPlane;
-#pragma unroll
-        for (u32 m = 0; m < 3; ++m) {
-            const u32 outs = L::outs(m);
-            // first layer: 18 accumulations from zero (the bias rides on the constant input), ReLU
-            f32x16 h = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (u32 t = 0; t < kSteps1; ++t)
-                h = __builtin_amdgcn_mfma_f32_32x32x2f32(s_w[(m * kSteps1 + t) * kWave + lane], xf[t], h, 0, 0, 0);
-#pragma unroll
-            for (u32 r = 0; r < 16; ++r) h[r] = fmaxf(h[r], 0.0f);
+        f32x16 h = first_layer<K, 0>(s_w, xf, lane);
+        relu16(h);
+        const f32x16 y_op = second_layer<K, 0, 0>(s_w, h, lane);
+        h = first_layer<K, 1>(s_w, xf, lane);
+        read_out<K, 0, 0>(y_op, s, s_w, j, hi, lane, live, ex[3], ex[4], ex[5]);
+        relu16(h);
+        const f32x16 y_col = second_layer<K, 1, 0>(s_w, h, lane);
+        h = first_layer<K, 2>(s_w, xf, lane);
+        read_out<K, 1, 0>(y_col, s, s_w, j, hi, lane, live, ex[3], ex[4], ex[5]);
+        relu16(h);
+        const f32x16 y_cov0 = second_layer<K, 2, 0>(s_w, h, lane);
 
-            if (m == 2) {
-                // the first half leaves the stage: opacity, centres, SH records
+        // the first half leaves the stage: opacity, centres, SH records
 #pragma unroll
-                for (u32 pp = 0; pp < K / 2; ++pp) {
-                    const u32 p = hi * (K / 2) + pp;
+        for (u32 pp = 0; pp < K / 2; ++pp) {
+            const u32 p = hi * (K / 2) + pp;
 #pragma unroll
-                    for (u32 c = 0; c < 3; ++c)
-                        s_mean[c * L::kPlane + j * K + p] = live ? fmaf(off[3 * pp + c], ex[c], pos[c]) : 0.0f;
-                }
-                for (u32 e = lane; e < L::kPlane; e += kWave) s_sh[4 * e + 3] = 0.0f;
-                wave_sync();
-                write_planes<L::kPlane, 1>(opacity + slot0, 0, s_op, count, lane);
-                write_planes<L::kPlane, 3>(mean + slot0, n, s_mean, count, lane);
-                {
-                    const float4 *s4 = reinterpret_cast<const float4 *>(s_sh);
-                    float4 *dst = reinterpret_cast<float4 *>(sh) + slot0;
-                    float4 recs[L::kPlane / kWave];
-#pragma unroll
-                    for (u32 q = 0; q < L::kPlane / kWave; ++q) recs[q] = s4[q * kWave + lane];
-#pragma unroll
-                    for (u32 q = 0; q < L::kPlane / kWave; ++q)
-                        if (q * kWave + lane < count) dst[q * kWave + lane] = recs[q];
-                }
-                wave_sync();
-            }
-
-#pragma unroll
-            for (u32 T = 0; T < L::tiles(m); ++T) {
-                f32x16 y = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                float bias[16];
-#pragma unroll
-                for (u32 r = 0; r < 16; ++r)
-                    bias[r] = s_w[L::kBias2 + (L::tiles_before(m) + T) * kTile + row_of_reg(r, 0) + 4 * hi];
-#pragma unroll
-                for (u32 st = 0; st < kSteps2; ++st)
-                    y = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                        s_w[(L::kFrag1 + (L::tiles_before(m) + T) * kSteps2 + st) * kWave + lane], h[st], y, 0, 0, 0);
-#pragma unroll
-                for (u32 r = 0; r < 16; ++r) {
-                    const u32 o = kTile * T + row_of_reg(r, 0) + 4 * hi;     // output unit of this register
-                    const float yr = y[r] + bias[r];
-                    if (o < outs) {
-                        if (m == 0) {
-                            s_op[j * K + o] = (live && yr > 0.0f) ? tanh_pos(yr) : 0.0f;
-                        } else if (m == 1) {
-                            const u32 p = o / 3, c = o - 3 * p;
-                            s_sh[4 * (j * K + p) + c] = live ? (logistic(yr) - 0.5f) * kInvY00 : 0.0f;
-                        } else {
-                            const u32 p = o / 7, c = o - 7 * p;
-                            const float bound = c == 0 ? ex[3] : (c == 1 ? ex[4] : ex[5]);
-                            const float val = c < 3 ? bound * logistic(yr) : yr;
-                            s[c * L::kPlane + j * K + p] = live ? val : 0.0f;
-                        }
-                    }
-                }
-            }
+            for (u32 c = 0; c < 3; ++c)
+                s_mean[c * L::kPlane + j * K + p] = live ? fmaf(off[3 * pp + c], ex[c], pos[c]) : 0.0f;
         }
+#pragma unroll
+        for (u32 q = 0; q < L::kPlane / kWave; ++q) s_sh[4 * (q * kWave + lane) + 3] = 0.0f;
+        wave_sync();
+        write_planes<L::kPlane, 1>(opacity + slot0, 0, s_op, count, lane);
+        write_planes<L::kPlane, 3>(mean + slot0, n, s_mean, count, lane);
+        {
+            const float4 *s4 = reinterpret_cast<const float4 *>(s_sh);
+            float4 *dst = reinterpret_cast<float4 *>(sh) + slot0;
+            float4 recs[L::kPlane / kWave];
+#pragma unroll
+            for (u32 q = 0; q < L::kPlane / kWave; ++q) recs[q] = s4[q * kWave + lane];
+#pragma unroll
+            for (u32 q = 0; q < L::kPlane / kWave; ++q)
+                if (q * kWave + lane < count) dst[q * kWave + lane] = recs[q];
+        }
+        wave_sync();
+
         // second half: the seven covariance planes
+        if constexpr (L::tiles(2) == 3) {
+            const f32x16 y_cov1 = second_layer<K, 2, 1>(s_w, h, lane);
+            read_out<K, 2, 0>(y_cov0, s, s_w, j, hi, lane, live, ex[3], ex[4], ex[5]);
+            const f32x16 y_cov2 = second_layer<K, 2, 2>(s_w, h, lane);
+            read_out<K, 2, 1>(y_cov1, s, s_w, j, hi, lane, live, ex[3], ex[4], ex[5]);
+            read_out<K, 2, 2>(y_cov2, s, s_w, j, hi, lane, live, ex[3], ex[4], ex[5]);
+        } else {
+            static_assert(L::tiles(2) == 1 || L::tiles(2) == 3, "7 k outputs in one or three tiles");
+            read_out<K, 2, 0>(y_cov0, s, s_w, j, hi, lane, live, ex[3], ex[4], ex[5]);
+        }
         wave_sync();
         write_planes<L::kPlane, 3>(scale + slot0, n, s, count, lane);
         write_planes<L::kPlane, 4>(rot + slot0, n, s + 3 * L::kPlane, count, lane);
