@@ -43,6 +43,15 @@ float64 output is within the float32 error bound of zero as undecided (either wa
 such a primitive has an opacity far below 1/255 and never reaches the image).  `bound`
 returns that error bound: for a dot product accumulated in float32, |error| <= n u |w|.|x|.
 
+View-frustum mask of the anchors [reading; Sec. 4.2.1 names a mask computation with pre-computed
+indices, Sec. 4.2.2 the frustum test of boxes]: offline, every anchor gets the box that holds every
+centre its primitives can take, position +- max_j |offset_j| * extent[0:3] per axis (float32, one
+rounding per operation), and the largest scale any of them can take, max(extent[3:6]) (the logistic
+factor is below 1).  Per frame an anchor is decoded only if that box passes the rasteriser oracle's
+conservative box-against-frustum test (lmk_ref_voxel_visible: a box that fails cannot hold a
+primitive that is binned); the primitives of an anchor that fails get opacity 0.  The decision is
+taken in float32 by the same written formulas on both sides, so it is unique.
+
 Pins (tests/test_oracle_anchor.py): closed forms with a zero second layer, with a
 pass-through first layer, with a view-only first layer; the perceptron against
 torch.nn.Linear/ReLU modules; translation, offset-scaling and list-permutation invariants;
@@ -127,6 +136,38 @@ def bound(anchors: dict, mlp: dict, cam_pos, visible=None) -> SimpleNamespace:
         terms = (x.shape[1] + 1) + (m1.shape[1] + 1) + 8
         out[name] = np.ascontiguousarray((terms * 2.0 ** -24 * m2).reshape(n, per).T)
     return SimpleNamespace(opacity=out["opacity"][0], colour=out["colour"], cov=out["cov"])
+
+
+def anchor_boxes(anchors: dict) -> SimpleNamespace:
+    """Offline: per anchor the box of its primitives' possible centres and the bound of their scales,
+    in float32 (box_lo, box_hi (a, 3); smax (a,))."""
+    f32 = np.float32
+    pos = np.asarray(anchors["position"], f32).T                                  # (a, 3)
+    ext = np.asarray(anchors["extent"], f32)
+    off = np.asarray(anchors["offsets"], f32)                                     # (a, k, 3)
+    a = int(anchors["a"])
+    if a == 0:
+        z = np.zeros((0, 3), f32)
+        return SimpleNamespace(num_voxels=0, box_lo=z, box_hi=z.copy(), smax=np.zeros(0, f32))
+    reach = (np.abs(off) * ext[0:3].T[:, None, :]).astype(f32).max(axis=1)        # (a, 3)
+    return SimpleNamespace(num_voxels=a, box_lo=np.ascontiguousarray(pos - reach, f32),
+                           box_hi=np.ascontiguousarray(pos + reach, f32),
+                           smax=np.ascontiguousarray(ext[3:6].max(axis=0), f32))
+
+
+def anchors_visible(anchors: dict, cam: dict) -> np.ndarray:
+    """Per anchor: False only if none of its primitives can be binned for this camera."""
+    from oracle import ref
+    return ref.voxels_visible(anchor_boxes(anchors), cam).astype(bool)
+
+
+def decode_culled(anchors: dict, mlp: dict, cam: dict) -> SimpleNamespace:
+    """decode() of every anchor, with the primitives of anchors that fail the frustum test at opacity 0.
+    `.visible` is the per-anchor mask."""
+    d = decode(anchors, mlp, cam["cam_pos"])
+    d.visible = anchors_visible(anchors, cam)
+    d.opacity = np.where(np.repeat(d.visible, d.k), d.opacity, 0.0)
+    return d
 
 
 def as_scene(dec: SimpleNamespace) -> dict:

@@ -256,3 +256,67 @@ def test_float32_evaluation_stays_within_the_stated_bound():
         lim = getattr(bnd, name)
         assert (err <= lim).all(), (name, float((err / lim).max()))
         assert (err > 0).any()
+
+
+def _interior_cameras():
+    return [scenes.make_cameras(2, 480, 270)[v] for v in (0, 4, 5, 7)]
+
+
+def test_anchor_boxes_hold_every_centre_and_scale():
+    anchors = scenes.make_anchor_scene(500, seed=70, layout="clusters")
+    mlp = scenes.make_decoder(seed=71)
+    d = AR.decode(anchors, mlp, (1.0, 2.0, 3.0))
+    b = AR.anchor_boxes(anchors)
+    k = d.k
+    lo, hi = np.repeat(b.box_lo.astype(np.float64), k, axis=0).T, np.repeat(b.box_hi.astype(np.float64), k, axis=0).T
+    slack = 4 * 2.0 ** -24 * (np.abs(d.mean) + 1e-30)
+    assert (d.mean >= lo - slack).all() and (d.mean <= hi + slack).all()
+    assert (d.scale <= np.repeat(b.smax.astype(np.float64), k)[None, :]).all()
+    # and the box is tight: on every axis some primitive of the anchor reaches a face
+    reach = np.abs(d.mean - np.repeat(anchors["position"].astype(np.float64), k, axis=1)).reshape(3, -1, k).max(axis=2)
+    np.testing.assert_allclose(reach, ((b.box_hi - b.box_lo) / 2).T, rtol=1e-5)
+
+
+def test_frustum_mask_never_drops_a_primitive_that_is_binned():
+    anchors = scenes.make_anchor_scene(20_000, seed=72, layout="clusters")
+    mlp = scenes.make_decoder(seed=73)
+    dropped = kept_binned = 0
+    for cam in _interior_cameras():
+        d = AR.decode(anchors, mlp, cam["cam_pos"])
+        vis = np.repeat(AR.anchors_visible(anchors, cam), d.k)
+        pre = ref.preprocess(AR.as_scene(d), cam)
+        binned = pre.tiles_touched > 0
+        assert not (binned & ~vis).any()
+        dropped += int((~vis).sum()); kept_binned += int((binned & vis).sum())
+    assert dropped > 100_000 and kept_binned > 20_000          # not vacuous either way
+
+
+def test_frustum_mask_leaves_keys_and_image_unchanged():
+    anchors = scenes.make_anchor_scene(6000, seed=74, layout="clusters")
+    mlp = scenes.make_decoder(seed=75)
+    cam = dict(scenes.make_cameras(2, 320, 180)[5], binning=1)
+    full = ref.render_frame(AR.as_scene(AR.decode(anchors, mlp, cam["cam_pos"])), cam)
+    dc = AR.decode_culled(anchors, mlp, cam)
+    assert 0.01 < dc.visible.mean() < 0.95
+    culled = ref.render_frame(AR.as_scene(dc), cam)
+    assert full.binned.D == culled.binned.D > 1000
+    np.testing.assert_array_equal(full.binned.keys, culled.binned.keys)
+    np.testing.assert_array_equal(full.binned.vals, culled.binned.vals)
+    np.testing.assert_array_equal(full.img.rgb, culled.img.rgb)
+    np.testing.assert_array_equal(full.img.T, culled.img.T)
+
+
+def test_a_box_without_the_offsets_reach_would_drop_binned_primitives():
+    # the planted mistake: anchor centres alone as boxes
+    anchors = scenes.make_anchor_scene(20_000, seed=72, layout="clusters")
+    mlp = scenes.make_decoder(seed=73)
+    b = AR.anchor_boxes(anchors)
+    pos = np.ascontiguousarray(anchors["position"].T, np.float32)
+    wrong = type(b)(num_voxels=b.num_voxels, box_lo=pos, box_hi=pos.copy(), smax=b.smax)
+    bad = 0
+    for cam in _interior_cameras():
+        d = AR.decode(anchors, mlp, cam["cam_pos"])
+        vis = np.repeat(ref.voxels_visible(wrong, cam).astype(bool), d.k)
+        pre = ref.preprocess(AR.as_scene(d), cam)
+        bad += int(((pre.tiles_touched > 0) & ~vis).sum())
+    assert bad > 0
