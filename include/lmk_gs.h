@@ -301,6 +301,31 @@ int32_t lmk_gs_anchor_decode(const lmk_gs_anchors *anchors, const lmk_gs_anchor_
                              const float *cam_pos, const uint32_t *visible, uint32_t v,
                              const lmk_gs_decoded *out, void *stream);
 
+/* Offline step of the anchors' view-frustum mask, on the HOST (host pointers, nothing touches the GPU;
+ * layouts as in lmk_gs_anchors).  Per anchor: the box that holds every centre its primitives can take,
+ * position -+ max_j |offsets[j]| * extent[0..2] per axis, and the largest scale they can take,
+ * max(extent[3..5]); and, for the decoded scene of a * k slots, the anchors spanned by every group of
+ * LMK_GS_PRE_BLOCK consecutive slots.
+ *   box          [a][8]  lo x,y,z, hi x,y,z, scale bound, 0      (as lmk_gs_voxel_index.box)
+ *   block_range  [ceil(a k / LMK_GS_PRE_BLOCK)][2]               (as lmk_gs_voxel_index.block_range)
+ * Uploaded, {box, block_range, num_voxels = a} is the lmk_gs_voxel_index with which
+ * lmk_gs_preprocess_culled skips the slots of anchors outside the view, and box is what
+ * lmk_gs_anchor_decode_culled reads.  LMK_GS_ERR_INVALID: NULL pointer, k = 0, a k >= 2^32. */
+int32_t lmk_gs_anchor_index_build(const float *position, const float *extent, const float *offsets,
+                                  uint32_t a, uint32_t k, float *box, uint32_t *block_range);
+
+/* lmk_gs_anchor_decode of all a anchors in their order (slot i k + j = primitive j of anchor i), with
+ * the mask computation of Sec. 4.2.1 in front: an anchor is decoded only if its box (device array
+ * [a][8] from lmk_gs_anchor_index_build, 16-byte aligned) passes the conservative box-against-frustum
+ * test of Sec. 4.2.2 that lmk_gs_preprocess_culled applies to voxels -- a box that fails holds no
+ * primitive that can be binned, so the image is unchanged.  anchor_visible (device, [a] bytes) receives
+ * the mask.  The k slots of an anchor that fails get opacity 0; their other elements are zero or left
+ * untouched (a tile of 32 consecutive anchors none of which passes is neither read nor decoded).
+ * Errors as lmk_gs_anchor_decode and lmk_gs_preprocess (camera). */
+int32_t lmk_gs_anchor_decode_culled(const lmk_gs_anchors *anchors, const lmk_gs_anchor_decoder *decoder,
+                                    const lmk_gs_camera *cam, const float *box, uint8_t *anchor_visible,
+                                    const lmk_gs_decoded *out, void *stream);
+
 /* Copies {pair count D, status} of the frame from scratch to the host.
  * Synchronises `stream`.  Either output pointer may be NULL. */
 int32_t lmk_gs_read_status(const void *scratch, uint64_t *dup_count, int32_t *status, void *stream);

@@ -24,7 +24,8 @@ PRE_BLOCK = 256
 EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
            "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version",
            "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
-           "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode")
+           "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode", "lmk_gs_anchor_index_build",
+           "lmk_gs_anchor_decode_culled")
 
 
 class Gaussians(C.Structure):
@@ -115,13 +116,18 @@ def lib() -> C.CDLL:
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.lmk_gs_anchor_decode.argtypes = [C.POINTER(Anchors), C.POINTER(AnchorDecoder), C.POINTER(C.c_float),
                                            C.c_void_p, C.c_uint32, C.POINTER(Decoded), C.c_void_p]
+        l.lmk_gs_anchor_index_build.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32,
+                                                C.c_void_p, C.c_void_p]
+        l.lmk_gs_anchor_decode_culled.argtypes = [C.POINTER(Anchors), C.POINTER(AnchorDecoder), C.POINTER(Camera),
+                                                  C.c_void_p, C.c_void_p, C.POINTER(Decoded), C.c_void_p]
         l.lmk_gs_read_status.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.c_void_p]
         l.lmk_gs_strerror.argtypes = [C.c_int32]
         l.lmk_gs_strerror.restype = C.c_char_p
         for name in ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lmk_gs_render",
                      "lmk_gs_read_status", "lmk_gs_last_hip_error", "lmk_gs_index_build",
                      "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
-                     "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode"):
+                     "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode", "lmk_gs_anchor_index_build",
+                     "lmk_gs_anchor_decode_culled"):
             getattr(l, name).restype = C.c_int32
         l.lmk_gs_version.restype = C.c_uint32
         _lib = l
@@ -347,6 +353,30 @@ class AnchorScene:
                                      net(self.weights["cov"]))
 
 
+class AnchorIndex:
+    """Offline part of the anchors' view-frustum mask (lmk_gs_anchor_index_build, host side): per-anchor
+    boxes and, for the decoded scene, the anchors spanned by every group of PRE_BLOCK slots.  `c` is the
+    lmk_gs_voxel_index over the decoded slots for lmk_gs_preprocess_culled (one "voxel" per anchor)."""
+
+    def __init__(self, anchors: dict, device="cuda:0"):
+        a, k = int(anchors["a"]), int(anchors["k"])
+        pos = np.ascontiguousarray(anchors["position"], dtype=np.float32)
+        ext = np.ascontiguousarray(anchors["extent"], dtype=np.float32)
+        off = np.ascontiguousarray(anchors["offsets"], dtype=np.float32)
+        nb = (a * k + PRE_BLOCK - 1) // PRE_BLOCK
+        self.box = np.zeros((max(a, 1), 8), np.float32)
+        self.block_range = np.zeros((max(nb, 1), 2), np.uint32)
+        rc = lib().lmk_gs_anchor_index_build(pos.ctypes.data, ext.ctypes.data, off.ctypes.data, a, k,
+                                             self.box.ctypes.data, self.block_range.ctypes.data)
+        if rc != OK:
+            raise LmkGsError(rc, "lmk_gs_anchor_index_build")
+        self.a, self.k, self.num_voxels = a, k, a
+        self.box_dev = torch.from_numpy(self.box).to(device)
+        self.block_range_dev = torch.from_numpy(self.block_range.view(np.int32)).to(device)
+        self.visible = torch.zeros(max(a, 1), dtype=torch.uint8, device=device)     # per-frame mask
+        self.c = VoxelIndexC(_ptr(self.box_dev), _ptr(self.block_range_dev), a)
+
+
 class DecodedScene:
     """Output buffers of lmk_gs_anchor_decode for a list of v anchors with k primitives each."""
 
@@ -382,6 +412,18 @@ def anchor_decode(anchors: AnchorScene, cam_pos, out: DecodedScene, visible=None
                                     C.c_uint32(v), C.byref(out.c), _stream_handle(stream))
     if rc != OK:
         raise LmkGsError(rc, "lmk_gs_anchor_decode")
+
+
+def anchor_decode_culled(anchors: AnchorScene, index: AnchorIndex, cam: Camera, out: DecodedScene, stream=None) -> None:
+    """lmk_gs_anchor_decode_culled: every anchor in order, those outside the view masked; the mask is
+    left in index.visible."""
+    if out.n != anchors.a * anchors.k:
+        raise ValueError("output buffers are sized for another number of anchors")
+    rc = lib().lmk_gs_anchor_decode_culled(C.byref(anchors.c), C.byref(anchors.decoder), C.byref(cam),
+                                           _ptr(index.box_dev), _ptr(index.visible), C.byref(out.c),
+                                           _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_anchor_decode_culled")
 
 
 def read_status(frame: Frame, stream=None) -> tuple[int, int]:

@@ -186,6 +186,7 @@ template <u32 K>
 __global__ __launch_bounds__(256, 2) void anchor_decode_kernel(
     const float *__restrict__ position, const float *__restrict__ feature, const float *__restrict__ extent,
     const float *__restrict__ offsets, u32 a, const u32 *__restrict__ visible, u32 v,
+    const unsigned char *__restrict__ anchor_visible,
     const float *__restrict__ op_w1, const float *__restrict__ op_b1, const float *__restrict__ op_w2t,
     const float *__restrict__ op_b2,
     const float *__restrict__ col_w1, const float *__restrict__ col_b1, const float *__restrict__ col_w2t,
@@ -242,13 +243,18 @@ __global__ __launch_bounds__(256, 2) void anchor_decode_kernel(
         if (tile >= num_tiles || item >= v) return ~0u;
         return visible ? visible[item] : item;
     };
-    // Only issues loads: nothing here waits for them.  A lane without an anchor reads anchor 0
-    // (its results are replaced by zeros when they are staged), so the loads are unconditional.
-    auto load_tile = [&](u32 idx_or_none) -> TileIn {
+    // Only issues loads: nothing here waits for them (but for the mask bit, requested a tile earlier).
+    // A lane without an anchor reads anchor 0 (its results are replaced by zeros when they are
+    // staged), so the loads of a tile are unconditional.
+    auto mask_entry = [&](u32 idx_or_none) -> u32 {      // the anchor's bit of the frustum mask (1 without a mask)
+        return (anchor_visible && idx_or_none < a) ? (u32)anchor_visible[idx_or_none] : 1u;
+    };
+    auto load_tile = [&](u32 idx_or_none, u32 mask_bit) -> TileIn {
         TileIn in;
-        in.live = idx_or_none < a;
+        in.live = idx_or_none < a && mask_bit != 0u;
         const u32 idx = in.live ? idx_or_none : 0u;
-        if (a > 0) {                                    // uniform
+        // a tile none of whose anchors is decoded reads nothing
+        if (a > 0 && __builtin_amdgcn_ballot_w64(in.live) != 0ull) {          // uniform
             const float *rec = feature + (size_t)idx * kFeat;
             const float4 *r4 = reinterpret_cast<const float4 *>(rec + (hi ? 20 : 0));
             in.q0 = r4[0]; in.q1 = r4[1]; in.q2 = r4[2];
@@ -274,20 +280,28 @@ __global__ __launch_bounds__(256, 2) void anchor_decode_kernel(
     };
 
     // Every wavefront takes tiles in a strided loop (no workgroup barrier inside: trip counts
-    // differ).  The loads run two tiles ahead for the list entry and one tile ahead for the
-    // anchor's data, so a tile's arithmetic covers the next tile's memory latency.
+    // differ).  The loads run two tiles ahead for the list entry and the mask bit and one tile
+    // ahead for the anchor's data, so a tile's arithmetic covers the next tile's memory latency.
     const u32 first = blockIdx.x * kWaves + wv;
-    TileIn next_in = load_tile(list_entry(first));
+    const u32 first_idx = list_entry(first);
+    TileIn next_in = load_tile(first_idx, mask_entry(first_idx));
     u32 next_idx = list_entry(first + stride);
+    u32 next_bit = mask_entry(next_idx);
     for (u32 tile = first; tile < num_tiles; tile += stride) {
         const TileIn in = next_in;
-        next_in = load_tile(next_idx);
+        next_in = load_tile(next_idx, next_bit);
         next_idx = list_entry(tile + 2 * stride);
+        next_bit = mask_entry(next_idx);
 
         const u32 tile_items = v - tile * kTile < kTile ? v - tile * kTile : kTile;
         const u32 count = tile_items * K;
         const size_t slot0 = (size_t)tile * L::kPlane;
         const bool live = in.live;
+        if (anchor_visible && __builtin_amdgcn_ballot_w64(live) == 0ull) {
+            // nothing of this tile is in view: its slots get opacity 0 and nothing else
+            for (u32 t = lane; t < count; t += kWave) opacity[slot0 + t] = 0.0f;
+            continue;
+        }
         float xf[kSteps1];
         float pos[3], ex[6], off[3 * K / 2];
 #pragma unroll
@@ -370,13 +384,14 @@ __global__ __launch_bounds__(256, 2) void anchor_decode_kernel(
 
 template <u32 K>
 hipError_t launch_k(const lmk_gs_anchors &an, const lmk_gs_anchor_decoder &d, const float *cam,
-                    const u32 *visible, u32 v, const lmk_gs_decoded &out, hipStream_t stream)
+                    const u32 *visible, u32 v, const uint8_t *anchor_visible, const lmk_gs_decoded &out,
+                    hipStream_t stream)
 {
     const u32 num_tiles = (v + kTile - 1) / kTile;
     const u32 want = (num_tiles + 3) / 4;
     const u32 blocks = want < kMaxDecodeBlocks ? want : kMaxDecodeBlocks;
     hipLaunchKernelGGL(anchor_decode_kernel<K>, dim3(blocks), dim3(256), 0, stream,
-                       an.position, an.feature, an.extent, an.offsets, an.a, visible, v,
+                       an.position, an.feature, an.extent, an.offsets, an.a, visible, v, anchor_visible,
                        d.opacity.w1, d.opacity.b1, d.opacity.w2t, d.opacity.b2,
                        d.colour.w1, d.colour.b1, d.colour.w2t, d.colour.b2,
                        d.cov.w1, d.cov.b1, d.cov.w2t, d.cov.b2,
@@ -387,12 +402,12 @@ hipError_t launch_k(const lmk_gs_anchors &an, const lmk_gs_anchor_decoder &d, co
 }  // namespace
 
 hipError_t launch_anchor_decode(const lmk_gs_anchors &anchors, const lmk_gs_anchor_decoder &decoder,
-                                const float *cam_pos, const u32 *visible, u32 v,
+                                const float *cam_pos, const u32 *visible, u32 v, const uint8_t *anchor_visible,
                                 const lmk_gs_decoded &out, hipStream_t stream)
 {
     if (v == 0) return hipSuccess;
-    if (anchors.k == 10) return launch_k<10>(anchors, decoder, cam_pos, visible, v, out, stream);
-    return launch_k<4>(anchors, decoder, cam_pos, visible, v, out, stream);
+    if (anchors.k == 10) return launch_k<10>(anchors, decoder, cam_pos, visible, v, anchor_visible, out, stream);
+    return launch_k<4>(anchors, decoder, cam_pos, visible, v, anchor_visible, out, stream);
 }
 
 }  // namespace lmk

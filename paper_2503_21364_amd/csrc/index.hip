@@ -88,3 +88,42 @@ extern "C" int32_t lmk_gs_index_build(const float *mean, const float *scale, uin
     *num_voxels = nv;
     return LMK_GS_OK;
 }
+
+extern "C" int32_t lmk_gs_anchor_index_build(const float *position, const float *extent, const float *offsets,
+                                             uint32_t a, uint32_t k, float *box, uint32_t *block_range)
+{
+    if (k == 0) return LMK_GS_ERR_INVALID;
+    if ((uint64_t)a * k >= (1ull << 32)) return LMK_GS_ERR_INVALID;
+    if (a == 0) return LMK_GS_OK;
+    if (!position || !extent || !offsets || !box || !block_range) return LMK_GS_ERR_INVALID;
+    const size_t A = a;
+    for (size_t i = 0; i < A; ++i) {
+        float reach[3] = {0.0f, 0.0f, 0.0f};
+        for (uint32_t j = 0; j < k; ++j)
+            for (int c = 0; c < 3; ++c) {
+                const float r = std::fabs(offsets[(i * k + j) * 3 + c]) * extent[c * A + i];
+                // a NaN reach must not be lost in the comparison
+                if (!(r <= reach[c])) reach[c] = r;
+            }
+        float *b = box + 8 * i;
+        for (int c = 0; c < 3; ++c) {
+            const float centre = position[c * A + i];
+            b[c] = centre - reach[c];
+            b[3 + c] = centre + reach[c];
+        }
+        float smax = extent[3 * A + i];
+        for (int c = 4; c < 6; ++c)
+            if (!(extent[c * A + i] <= smax)) smax = extent[c * A + i];
+        b[6] = smax;
+        b[7] = 0.0f;
+    }
+    const uint64_t n = (uint64_t)a * k;
+    const uint64_t groups = (n + LMK_GS_PRE_BLOCK - 1) / LMK_GS_PRE_BLOCK;
+    for (uint64_t g = 0; g < groups; ++g) {
+        const uint64_t s0 = g * LMK_GS_PRE_BLOCK;
+        const uint64_t s1 = s0 + LMK_GS_PRE_BLOCK - 1 < n - 1 ? s0 + LMK_GS_PRE_BLOCK - 1 : n - 1;
+        block_range[2 * g] = (uint32_t)(s0 / k);
+        block_range[2 * g + 1] = (uint32_t)(s1 / k);
+    }
+    return LMK_GS_OK;
+}

@@ -139,7 +139,9 @@ hipError_t launch_preprocess_backward(const lmk_gs_gaussians &g, const ProjParam
                                       const lmk_gs_projected &proj, const float *grad_feat,
                                       const lmk_gs_gaussian_grads &out, hipStream_t stream);
 hipError_t launch_anchor_decode(const lmk_gs_anchors &anchors, const lmk_gs_anchor_decoder &decoder,
-                                const float *cam_pos, const u32 *visible, u32 v,
+                                const float *cam_pos, const u32 *visible, u32 v, const uint8_t *anchor_visible,
                                 const lmk_gs_decoded &out, hipStream_t stream);
+// visible[i] = the box (lo, hi, reach of the scales) passes the frustum test of the voxel filter
+hipError_t launch_box_flags(const float *box, u32 count, const ProjParams &pp, uint8_t *visible, hipStream_t stream);
 
 }  // namespace lmk

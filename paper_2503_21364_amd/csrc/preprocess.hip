@@ -569,4 +569,12 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
     return hipGetLastError();
 }
 
+hipError_t launch_box_flags(const float *box, u32 count, const ProjParams &pp, uint8_t *visible, hipStream_t stream)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(voxel_flags_kernel, dim3((count + 255) / 256), dim3(256), 0, stream,
+                       reinterpret_cast<const float4 *>(box), count, pp, visible);
+    return hipGetLastError();
+}
+
 }  // namespace lmk

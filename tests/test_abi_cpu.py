@@ -208,6 +208,66 @@ def test_anchor_decode_rejects_bad_arguments():
     assert call(v=0, a_=an(a=0, position=None, feature=None, extent=None, offsets=None)) == B.OK
 
 
+def test_anchor_index_build_matches_the_oracle_and_rejects_bad_input():
+    from oracle import anchor_ref as AR
+    lib = B.lib()
+    for a, k, layout in ((1000, 10, "clusters"), (77, 4, "cube"), (1, 10, "cube")):
+        an = scenes.make_anchor_scene(a, seed=5 + a, k=k, layout=layout)
+        nb = (a * k + B.PRE_BLOCK - 1) // B.PRE_BLOCK
+        box = np.full((a, 8), np.nan, np.float32)
+        rng = np.full((nb, 2), 0xFFFFFFFF, np.uint32)
+        rc = lib.lmk_gs_anchor_index_build(an["position"].ctypes.data, an["extent"].ctypes.data,
+                                           an["offsets"].ctypes.data, a, k, box.ctypes.data, rng.ctypes.data)
+        assert rc == B.OK
+        want = AR.anchor_boxes(an)
+        assert np.array_equal(box[:, 0:3].view(np.uint32), want.box_lo.view(np.uint32))
+        assert np.array_equal(box[:, 3:6].view(np.uint32), want.box_hi.view(np.uint32))
+        assert np.array_equal(box[:, 6].view(np.uint32), want.smax.view(np.uint32)) and (box[:, 7] == 0).all()
+        slots = np.arange(a * k)
+        first = (slots // k)[::B.PRE_BLOCK]
+        last = np.minimum(slots[::B.PRE_BLOCK] + B.PRE_BLOCK - 1, a * k - 1) // k
+        assert np.array_equal(rng[:, 0], first) and np.array_equal(rng[:, 1], last)
+    an = scenes.make_anchor_scene(10, seed=1)
+    box = np.zeros((10, 8), np.float32); rng = np.zeros((1, 2), np.uint32)
+    args = lambda **kw: [kw.get("p", an["position"].ctypes.data), kw.get("e", an["extent"].ctypes.data),
+                         kw.get("o", an["offsets"].ctypes.data), kw.get("a", 10), kw.get("k", 10),
+                         kw.get("b", box.ctypes.data), kw.get("r", rng.ctypes.data)]
+    assert lib.lmk_gs_anchor_index_build(*args()) == B.OK
+    assert lib.lmk_gs_anchor_index_build(*args(p=None)) == B.ERR_INVALID
+    assert lib.lmk_gs_anchor_index_build(*args(b=None)) == B.ERR_INVALID
+    assert lib.lmk_gs_anchor_index_build(*args(r=None)) == B.ERR_INVALID
+    assert lib.lmk_gs_anchor_index_build(*args(k=0)) == B.ERR_INVALID
+    assert lib.lmk_gs_anchor_index_build(*args(a=1 << 30, k=10)) == B.ERR_INVALID
+    assert lib.lmk_gs_anchor_index_build(*args(a=0, p=None, e=None, o=None, b=None, r=None)) == B.OK
+
+
+def test_anchor_decode_culled_rejects_bad_arguments():
+    lib = B.lib()
+    an = B.Anchors(position=0x1000, feature=0x2000, extent=0x3000, offsets=0x4000, a=100, k=10)
+    net = B.Perceptron(w1=0x5000, b1=0x5100, w2t=0x5200, b2=0x5300)
+    dec = B.AnchorDecoder(opacity=net, colour=net, cov=net)
+    out = B.Decoded(mean=0x6000, scale=0x7000, rot=0x8000, opacity=0x9000, sh=0xa000)
+    cam = _good_camera()
+
+    def call(a_=an, d_=dec, c_=cam, box=C.c_void_p(0xb000), vis=C.c_void_p(0xc000), o_=out):
+        return lib.lmk_gs_anchor_decode_culled(None if a_ is None else C.byref(a_), None if d_ is None else C.byref(d_),
+                                               None if c_ is None else C.byref(c_), box, vis,
+                                               None if o_ is None else C.byref(o_), None)
+    assert call(a_=None) == B.ERR_INVALID
+    assert call(d_=None) == B.ERR_INVALID
+    assert call(c_=None) == B.ERR_INVALID
+    assert call(o_=None) == B.ERR_INVALID
+    assert call(box=None) == B.ERR_INVALID
+    assert call(box=C.c_void_p(0xb008)) == B.ERR_INVALID                     # boxes are read as 16-byte vectors
+    assert call(vis=None) == B.ERR_INVALID
+    assert call(a_=B.Anchors(position=0x1000, feature=0x2000, extent=0x3000, offsets=0x4000, a=100, k=7)) == B.ERR_UNSUPPORTED
+    assert call(a_=B.Anchors(position=0x1000, feature=None, extent=0x3000, offsets=0x4000, a=100, k=10)) == B.ERR_INVALID
+    assert call(o_=B.Decoded(mean=0x6000, scale=0x7000, rot=None, opacity=0x9000, sh=0xa000)) == B.ERR_INVALID
+    bad = _good_camera(); bad.tile = 8
+    assert call(c_=bad) == B.ERR_UNSUPPORTED
+    assert call(a_=B.Anchors(position=None, feature=None, extent=None, offsets=None, a=0, k=10), box=None, vis=None) == B.OK
+
+
 def test_index_build_matches_the_oracle_and_rejects_bad_input():
     from oracle import ref
     for cfg, n, vs in [(2, 50_000, 2.0), (3, 80_000, 40.0), (0, 1000, 0.3), (1, 777, 1.0), (0, 1, 1.0)]:
