@@ -130,19 +130,37 @@ def anchor_bench(args):
         cams = cams[:max(1, args.views)]
     ccams = [B.make_camera(c) for c in cams]
     nviews = len(cams)
+    masked = not args.no_anchor_mask
+    if masked:
+        # offline, not timed: anchors in voxel order, per-anchor boxes; the oracle leg uses the same order
+        anchors = B.reorder_anchors(anchors, 2.0)
+        aindex = B.AnchorIndex(anchors)
     dev = B.AnchorScene(anchors, mlp)
     dec = B.DecodedScene(a, k)
     scene = dec.scene()
     n = scene.n
 
+    def decode(c, cc):
+        if masked:
+            B.anchor_decode_culled(dev, aindex, cc, dec)
+        else:
+            B.anchor_decode(dev, c["cam_pos"], dec)
+
+    def project(cc, frame_):
+        B.preprocess(scene, cc, frame_, index=aindex if masked else None)
+
     fr = B.Frame(n, W, H, 64_000_000)
     Ds = []
+    in_view = []
     for c, cc in zip(cams, ccams):
-        B.anchor_decode(dev, c["cam_pos"], dec)
-        B.render_frame(scene, cc, fr)
+        decode(c, cc)
+        project(cc, fr)
+        B.bin_sort(cc, fr)
+        B.render(cc, fr)
         D, status = B.read_status(fr)
         assert status == B.OK, f"status {status} in the sizing run"
         Ds.append(D)
+        in_view.append(float(aindex.visible[:a].float().mean().item()) if masked else 1.0)
     kept = float((dec.opacity > 0).float().mean().item())
     del fr
     torch.cuda.empty_cache()
@@ -152,9 +170,9 @@ def anchor_bench(args):
     def frame(i, marks=None):
         c, cc = cams[i % nviews], ccams[i % nviews]
         if marks: marks[0].record()
-        B.anchor_decode(dev, c["cam_pos"], dec)
+        decode(c, cc)
         if marks: marks[1].record()
-        B.preprocess(scene, cc, fr)
+        project(cc, fr)
         if marks: marks[2].record()
         B.bin_sort(cc, fr)
         if marks: marks[3].record()
@@ -186,11 +204,16 @@ def anchor_bench(args):
     stage = lambda j: np.array([m[j].elapsed_time(m[j + 1]) for m in marks])
     t_dec, t_pre, t_sort, t_blend = stage(0), stage(1), stage(2), stage(3)
 
-    flops = 2.0 * (3 * F * (F + 3) + F * 11 * k) * a
-    byts = (4.0 * (3 + F + 6 + 3 * k) + 4.0 * k * 15) * a
+    # algorithmic work of a launch: anchors in view are decoded (flops, all their bytes); an anchor out of
+    # view costs its 32-byte box, its mask byte (written, then read) and the k opacities written
+    view_of = np.arange(args.steps) % nviews
+    seen = np.array(in_view)[view_of] * a
+    flops = float((2.0 * (3 * F * (F + 3) + F * 11 * k) * seen).mean())
+    per_seen = 4.0 * (3 + F + 6 + 3 * k) + 4.0 * k * 15
+    byts = float((per_seen * seen + ((34.0 * a + (a - seen) * 4.0 * k) if masked else 0.0)).mean())
     tf = flops / (t_dec.mean() * 1e-3) / 1e12
     # the committed counter measurement is of the default command of this mode
-    traffic = committed_traffic(2, args.binning, f"anchors{a}") if args.views is None else {}
+    traffic = committed_traffic(2, args.binning, f"anchors{a}" + ("" if masked else "-nomask")) if args.views is None else {}
     out = {
         "metric": "frames/s, anchor model: decode + 1080p render",
         "value": args.steps / total_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -199,9 +222,12 @@ def anchor_bench(args):
         "config": {"workload": f"anchors: {a} anchors (config 2's clusters) x {k} primitives = {n} candidate "
                                f"Gaussians decoded per frame, {W}x{H}, {nviews} seeded viewpoints of config 2",
                    "binning": args.binning, "kept_fraction": kept, "pairs_per_frame_mean": float(np.mean(Ds)),
-                   "capacity": capacity},
+                   "capacity": capacity, "frustum_mask": masked,
+                   "anchors_in_view": [round(x, 4) for x in in_view]},
         "stage_ms": {"anchor_decode": float(t_dec.mean()), "preprocess": float(t_pre.mean()),
                      "bin_sort": float(t_sort.mean()), "render": float(t_blend.mean())},
+        "decode_ms_per_view": [float(t_dec[view_of == v].mean()) for v in range(nviews) if (view_of == v).any()],
+        "preprocess_ms_per_view": [float(t_pre[view_of == v].mean()) for v in range(nviews) if (view_of == v).any()],
         "roofline": {"kernel": "anchor_decode_kernel", "bound": "mfma", "achieved": tf, "peak": FP32_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": tf / FP32_MFMA_PEAK_TFLOPS,
                      "traffic": traffic.get("anchor_decode_kernel"),
@@ -212,7 +238,7 @@ def anchor_bench(args):
         from oracle import anchor_ref as AR
         from oracle import ref
         c0 = time.perf_counter()
-        d = AR.decode(anchors, mlp, cams[0]["cam_pos"])
+        d = AR.decode_culled(anchors, mlp, cams[0]) if masked else AR.decode(anchors, mlp, cams[0]["cam_pos"])
         c1 = time.perf_counter()
         ofr = ref.render_frame(AR.as_scene(d), dict(cams[0], binning=0))
         c2 = time.perf_counter()
@@ -248,6 +274,9 @@ def main():
                     help="anchor-model mode: A anchors of the cluster layout (300000 gives 3 M candidate primitives) "
                          "are decoded by lmk_gs_anchor_decode in every frame and rendered by the three calls; the "
                          "JSON line then reports that pipeline and the roofline of the decode kernel")
+    ap.add_argument("--no-anchor-mask", action="store_true",
+                    help="anchor-model mode without the view-frustum mask: every anchor is decoded and every slot "
+                         "projected in every frame")
     ap.add_argument("--no-cov-cache", action="store_true",
                     help="compute every primitive's 3D covariance from rotation and scale in every frame instead "
                          "of reading the parameter cache built once per scene")

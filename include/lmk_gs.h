@@ -97,6 +97,10 @@ typedef struct lmk_gs_voxel_index {
     const uint32_t *block_range;  /* [ceil(n / LMK_GS_PRE_BLOCK)][2] first and last voxel holding a
                                      primitive of each group of LMK_GS_PRE_BLOCK consecutive primitives */
     uint32_t num_voxels;
+    const uint8_t *visible;       /* optional [num_voxels]: this frame's result of the box test for every voxel,
+                                     already on the device (lmk_gs_anchor_decode_culled leaves it in
+                                     anchor_visible, for the same camera); NULL = lmk_gs_preprocess_culled
+                                     computes it                                                    */
 } lmk_gs_voxel_index;
 
 /* Per-primitive results of lmk_gs_preprocess.  For a primitive with

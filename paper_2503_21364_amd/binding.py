@@ -66,7 +66,8 @@ class Camera(C.Structure):
 
 
 class VoxelIndexC(C.Structure):
-    _fields_ = [("box", C.c_void_p), ("block_range", C.c_void_p), ("num_voxels", C.c_uint32)]
+    _fields_ = [("box", C.c_void_p), ("block_range", C.c_void_p), ("num_voxels", C.c_uint32),
+                ("visible", C.c_void_p)]
 
 
 class Projected(C.Structure):
@@ -242,7 +243,7 @@ class VoxelIndex:
         self.box_dev = torch.from_numpy(np.ascontiguousarray(self.box if self.num_voxels else np.zeros((1, 8), np.float32))).to(device)
         self.block_range_dev = torch.from_numpy(np.ascontiguousarray(
             self.block_range if len(self.block_range) else np.zeros((1, 2), np.uint32)).view(np.int32)).to(device)
-        self.c = VoxelIndexC(_ptr(self.box_dev), _ptr(self.block_range_dev), self.num_voxels)
+        self.c = VoxelIndexC(_ptr(self.box_dev), _ptr(self.block_range_dev), self.num_voxels, None)
         return self
 
 
@@ -353,6 +354,18 @@ class AnchorScene:
                                      net(self.weights["cov"]))
 
 
+def reorder_anchors(anchors: dict, voxel_size: float) -> dict:
+    """Offline: the anchors in the voxel order of lmk_gs_index_build applied to their centres, so that
+    consecutive anchors are close in space (a tile of the decoder and a group of the rasteriser then
+    fall inside or outside a view together)."""
+    idx = VoxelIndex(dict(mean=anchors["position"], scale=anchors["extent"][3:6], n=anchors["a"]), voxel_size)
+    perm = idx.perm
+    return dict(anchors, position=np.ascontiguousarray(anchors["position"][:, perm]),
+                feature=np.ascontiguousarray(anchors["feature"][perm]),
+                extent=np.ascontiguousarray(anchors["extent"][:, perm]),
+                offsets=np.ascontiguousarray(anchors["offsets"][perm]))
+
+
 class AnchorIndex:
     """Offline part of the anchors' view-frustum mask (lmk_gs_anchor_index_build, host side): per-anchor
     boxes and, for the decoded scene, the anchors spanned by every group of PRE_BLOCK slots.  `c` is the
@@ -374,7 +387,9 @@ class AnchorIndex:
         self.box_dev = torch.from_numpy(self.box).to(device)
         self.block_range_dev = torch.from_numpy(self.block_range.view(np.int32)).to(device)
         self.visible = torch.zeros(max(a, 1), dtype=torch.uint8, device=device)     # per-frame mask
-        self.c = VoxelIndexC(_ptr(self.box_dev), _ptr(self.block_range_dev), a)
+        # after lmk_gs_anchor_decode_culled of a frame, `visible` holds that frame's mask: preprocess reuses it
+        self.c = VoxelIndexC(_ptr(self.box_dev), _ptr(self.block_range_dev), a, _ptr(self.visible))
+        self.c_recompute = VoxelIndexC(_ptr(self.box_dev), _ptr(self.block_range_dev), a, None)
 
 
 class DecodedScene:

@@ -536,14 +536,18 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
         const uint2 *ranges = nullptr;
         u32 num_voxels = 0;
         if (index) {
-            unsigned char *f = reinterpret_cast<unsigned char *>(scratch + L.voxel_flags);
             num_voxels = index->num_voxels;
             ranges = reinterpret_cast<const uint2 *>(index->block_range);
-            hipLaunchKernelGGL(voxel_flags_kernel, dim3((num_voxels + 255) / 256), dim3(256), 0, stream,
-                               reinterpret_cast<const float4 *>(index->box), num_voxels, pp, f);
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            vflags = f;
+            if (index->visible) {
+                vflags = index->visible;                // this frame's flags, computed by the caller's earlier call
+            } else {
+                unsigned char *f = reinterpret_cast<unsigned char *>(scratch + L.voxel_flags);
+                hipLaunchKernelGGL(voxel_flags_kernel, dim3((num_voxels + 255) / 256), dim3(256), 0, stream,
+                                   reinterpret_cast<const float4 *>(index->box), num_voxels, pp, f);
+                hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return e;
+                vflags = f;
+            }
         }
         auto launch = [&](auto kernel) {
             hipLaunchKernelGGL(kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,

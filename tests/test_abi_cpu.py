@@ -324,16 +324,16 @@ def test_preprocess_culled_rejects_bad_arguments():
     g, proj, _ = _args()
     cam = _good_camera()
     scratch = C.c_void_p(0x10000)
-    idx = B.VoxelIndexC(0x1000, 0x1000, 3)
+    idx = B.VoxelIndexC(0x1000, 0x1000, 3, None)
     call = lambda i_, c_=cam: lib.lmk_gs_preprocess_culled(
         C.byref(g), None if i_ is None else C.byref(i_), C.byref(c_), C.byref(proj), None, scratch, 1 << 20, None)
-    assert C.sizeof(B.VoxelIndexC) == 24
+    assert C.sizeof(B.VoxelIndexC) == 32 and B.VoxelIndexC.visible.offset == 24
     assert call(None) == B.ERR_INVALID
-    assert call(B.VoxelIndexC(None, 0x1000, 3)) == B.ERR_INVALID
-    assert call(B.VoxelIndexC(0x1000, None, 3)) == B.ERR_INVALID
-    assert call(B.VoxelIndexC(0x1000, 0x1000, 0)) == B.ERR_INVALID
-    assert call(B.VoxelIndexC(0x1000, 0x1000, 11)) == B.ERR_INVALID          # more voxels than primitives
-    assert call(B.VoxelIndexC(0x1008, 0x1000, 3)) == B.ERR_INVALID          # box records not 16-byte aligned
+    assert call(B.VoxelIndexC(None, 0x1000, 3, None)) == B.ERR_INVALID
+    assert call(B.VoxelIndexC(0x1000, None, 3, None)) == B.ERR_INVALID
+    assert call(B.VoxelIndexC(0x1000, 0x1000, 0, None)) == B.ERR_INVALID
+    assert call(B.VoxelIndexC(0x1000, 0x1000, 11, None)) == B.ERR_INVALID          # more voxels than primitives
+    assert call(B.VoxelIndexC(0x1008, 0x1000, 3, None)) == B.ERR_INVALID          # box records not 16-byte aligned
     skew = _good_camera(); skew.view[0] *= 1.1
     assert call(idx, skew) == B.ERR_UNSUPPORTED
 
