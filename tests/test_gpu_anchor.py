@@ -304,3 +304,36 @@ def test_culled_pipeline_renders_like_the_oracles(view):
     err = np.abs(fr.out_rgb.cpu().numpy().astype(np.float64) - want.img.rgb)
     print(f"[anchor culled chain] view {view}: D={d} mean |err| {err.mean():.2e} max {err.max():.2e}", flush=True)
     assert err.mean() < 1e-6 and (err.max(axis=0) > 1e-4).mean() < 1e-3 and err.max() < 5e-3
+
+
+def test_full_size_masked_decode_on_every_benchmark_view():
+    """The configuration bench.py --anchors 300000 times: 300 k cluster anchors in voxel order (the order
+    comes from the oracle's index builder here), the eight views of config 2 at 1080p.  Per view: the mask
+    bit for bit, opacity 0 for every slot out of view, and the slots in view against the oracle on the
+    two views with the fewest anchors in view (the others decode what the unmasked full-size test covers)."""
+    a, k = 300_000, 10
+    anchors = scenes.make_anchor_scene(a, seed=6000, layout="clusters")
+    perm = ref.build_voxel_index(dict(mean=anchors["position"], scale=anchors["extent"][3:6], n=a), 2.0).perm
+    anchors = dict(anchors, position=np.ascontiguousarray(anchors["position"][:, perm]),
+                   feature=np.ascontiguousarray(anchors["feature"][perm]),
+                   extent=np.ascontiguousarray(anchors["extent"][:, perm]),
+                   offsets=np.ascontiguousarray(anchors["offsets"][perm]))
+    mlp = scenes.make_decoder(seed=7000)
+    dev = B.AnchorScene(anchors, mlp)
+    index = B.AnchorIndex(anchors)
+    out = B.DecodedScene(a, k)
+    fractions = []
+    for view, cam in enumerate(scenes.make_cameras(2)):
+        out.opacity.fill_(float("nan"))
+        B.anchor_decode_culled(dev, index, B.make_camera(cam), out)
+        torch.cuda.synchronize()
+        vis = AR.anchors_visible(anchors, cam)
+        assert np.array_equal(index.visible.cpu().numpy()[:a].astype(bool), vis), view
+        hidden = np.flatnonzero(np.repeat(~vis, k))
+        op = out.opacity.cpu().numpy()
+        assert (op[hidden] == 0).all() and np.isfinite(op).all(), view
+        fractions.append(vis.mean())
+        if view in (5, 6):
+            _compare(out, anchors, mlp, cam["cam_pos"], skip_slots=hidden)
+    print("[anchor masks] in view:", " ".join(f"{x:.3f}" for x in fractions), flush=True)
+    assert min(fractions) < 0.1 and max(fractions) > 0.9
