@@ -232,7 +232,9 @@ def anchor_bench(args):
                      "unit": "TFLOP/s", "frac": tf / FP32_MFMA_PEAK_TFLOPS,
                      "traffic": traffic.get("anchor_decode_kernel"),
                      "avg_launch_ms": float(t_dec.mean()), "flops_per_launch": flops,
-                     "hbm_GBs": byts / (t_dec.mean() * 1e-3) / 1e9, "bytes_per_launch": byts},
+                     "hbm_GBs": byts / (t_dec.mean() * 1e-3) / 1e9, "bytes_per_launch": byts,
+                     "note": "time of the whole decode call (with the mask: box test kernel + decode kernel), "
+                             "work of the anchors in view, both as means over the views"},
     }
     if not args.no_cpu_baseline:
         from oracle import anchor_ref as AR

@@ -206,9 +206,10 @@ int32_t lmk_gs_preprocess_backward(const lmk_gs_gaussians *g, const lmk_gs_camer
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
 }
 
-int32_t lmk_gs_anchor_decode(const lmk_gs_anchors *anchors, const lmk_gs_anchor_decoder *decoder,
-                             const float *cam_pos, const uint32_t *visible, uint32_t v,
-                             const lmk_gs_decoded *out, void *stream)
+// Host-side checks shared by the two decode calls: v anchors are going to be decoded.
+static int32_t check_decode_args(const lmk_gs_anchors *anchors, const lmk_gs_anchor_decoder *decoder,
+                                 const float *cam_pos, const uint32_t *visible, uint32_t v,
+                                 const lmk_gs_decoded *out)
 {
     if (!anchors || !decoder || !cam_pos || !out) return LMK_GS_ERR_INVALID;
     if (anchors->k != 10u && anchors->k != 4u) return LMK_GS_ERR_UNSUPPORTED;
@@ -216,17 +217,25 @@ int32_t lmk_gs_anchor_decode(const lmk_gs_anchors *anchors, const lmk_gs_anchor_
     if (!visible && v > anchors->a) return LMK_GS_ERR_INVALID;
     for (int i = 0; i < 3; ++i)
         if (!std::isfinite(cam_pos[i])) return LMK_GS_ERR_INVALID;
-    if (v > 0) {
-        if (anchors->a > 0 && (!anchors->position || !anchors->feature || !anchors->extent || !anchors->offsets))
+    if (v == 0) return LMK_GS_OK;
+    if (anchors->a > 0 && (!anchors->position || !anchors->feature || !anchors->extent || !anchors->offsets))
+        return LMK_GS_ERR_INVALID;
+    if (!aligned(anchors->feature, 16) || !aligned(anchors->offsets, 8)) return LMK_GS_ERR_INVALID;
+    const lmk_gs_perceptron *nets[3] = {&decoder->opacity, &decoder->colour, &decoder->cov};
+    for (const lmk_gs_perceptron *p : nets)
+        if (!p->w1 || !p->b1 || !p->w2t || !p->b2 || !aligned(p->w1, 4) || !aligned(p->w2t, 4))
             return LMK_GS_ERR_INVALID;
-        if (!aligned(anchors->feature, 16) || !aligned(anchors->offsets, 8)) return LMK_GS_ERR_INVALID;
-        const lmk_gs_perceptron *nets[3] = {&decoder->opacity, &decoder->colour, &decoder->cov};
-        for (const lmk_gs_perceptron *p : nets)
-            if (!p->w1 || !p->b1 || !p->w2t || !p->b2 || !aligned(p->w1, 4) || !aligned(p->w2t, 4))
-                return LMK_GS_ERR_INVALID;
-        if (!out->mean || !out->scale || !out->rot || !out->opacity || !out->sh) return LMK_GS_ERR_INVALID;
-        if (!aligned(out->sh, 16)) return LMK_GS_ERR_INVALID;
-    }
+    if (!out->mean || !out->scale || !out->rot || !out->opacity || !out->sh) return LMK_GS_ERR_INVALID;
+    if (!aligned(out->sh, 16)) return LMK_GS_ERR_INVALID;
+    return LMK_GS_OK;
+}
+
+int32_t lmk_gs_anchor_decode(const lmk_gs_anchors *anchors, const lmk_gs_anchor_decoder *decoder,
+                             const float *cam_pos, const uint32_t *visible, uint32_t v,
+                             const lmk_gs_decoded *out, void *stream)
+{
+    const int32_t rc = check_decode_args(anchors, decoder, cam_pos, visible, v, out);
+    if (rc != LMK_GS_OK) return rc;
     const hipError_t e = launch_anchor_decode(*anchors, *decoder, cam_pos, visible, v, nullptr, *out,
                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
@@ -240,19 +249,10 @@ int32_t lmk_gs_anchor_decode_culled(const lmk_gs_anchors *anchors, const lmk_gs_
     const int32_t rc = check_camera(cam, &pp);
     if (rc != LMK_GS_OK) return rc;
     if (!anchors) return LMK_GS_ERR_INVALID;
-    if (anchors->a > 0 && (!box || !anchor_visible || !aligned(box, 16))) return LMK_GS_ERR_INVALID;
-    if ((uint64_t)anchors->a * anchors->k >= (1ull << 32)) return LMK_GS_ERR_INVALID;
-    // the argument checks of the plain call, before anything is launched
-    const int32_t rc2 = lmk_gs_anchor_decode(anchors, decoder, cam->cam_pos, nullptr, 0, out, stream);
+    const int32_t rc2 = check_decode_args(anchors, decoder, cam->cam_pos, nullptr, anchors->a, out);
     if (rc2 != LMK_GS_OK) return rc2;
     if (anchors->a == 0) return LMK_GS_OK;
-    if (!anchors->position || !anchors->feature || !anchors->extent || !anchors->offsets) return LMK_GS_ERR_INVALID;
-    if (!aligned(anchors->feature, 16) || !aligned(anchors->offsets, 8)) return LMK_GS_ERR_INVALID;
-    const lmk_gs_perceptron *nets[3] = {&decoder->opacity, &decoder->colour, &decoder->cov};
-    for (const lmk_gs_perceptron *p : nets)
-        if (!p->w1 || !p->b1 || !p->w2t || !p->b2) return LMK_GS_ERR_INVALID;
-    if (!out->mean || !out->scale || !out->rot || !out->opacity || !out->sh || !aligned(out->sh, 16))
-        return LMK_GS_ERR_INVALID;
+    if (!box || !anchor_visible || !aligned(box, 16)) return LMK_GS_ERR_INVALID;
     hipError_t e = launch_box_flags(box, anchors->a, pp, anchor_visible, static_cast<hipStream_t>(stream));
     if (e == hipSuccess)
         e = launch_anchor_decode(*anchors, *decoder, cam->cam_pos, nullptr, anchors->a, anchor_visible, *out,
