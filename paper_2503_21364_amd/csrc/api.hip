@@ -287,6 +287,7 @@ const char *lmk_gs_strerror(int32_t code)
 
 int32_t lmk_gs_last_hip_error(void) { return g_last_hip_error.load(); }
 
-uint32_t lmk_gs_version(void) { return 200;   // 0.2.0: the gradient calls and the anchor decoder joined the three forward calls }
+// 0.2.0: the gradient calls and the anchor decoder joined the three forward calls
+uint32_t lmk_gs_version(void) { return 200; }
 
 }  // extern "C"
