@@ -198,6 +198,28 @@ int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_c
                         const lmk_gs_binned *out,
                         void *scratch, size_t scratch_bytes, void *stream);
 
+/* lmk_gs_bin_sort for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with
+ * the scratch in a fixed array that is part of the library's code object (96 MiB on every GPU the
+ * library runs on, held until the process ends).  The call allocates and frees nothing.  What
+ * lmk_gs_preprocess would have left in a caller's scratch is recomputed from `proj` (tiles_touched,
+ * rect, and under binning rule 1 the feature records), so `proj` may come from lmk_gs_preprocess on
+ * any scratch buffer; keys, vals, tile_offsets and tile_order are the same as lmk_gs_bin_sort's,
+ * bit for bit (proj->offsets, when present, too).
+ * count_status: optional device array of two 64-bit words receiving {pair count D, status (0 or
+ * LMK_GS_ERR_CAPACITY, sign-extended)} when the work completes -- this call has no scratch to hand
+ * to lmk_gs_read_status.
+ * Limits: n <= LMK_GS_STATIC_MAX_N, out->capacity <= LMK_GS_STATIC_MAX_CAPACITY, at most
+ * LMK_GS_STATIC_MAX_TILES tiles; beyond them LMK_GS_ERR_CAPACITY is returned and nothing is
+ * enqueued.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams, or different host threads) race and give undefined results; calls on one
+ * stream, or otherwise ordered, are safe, and nothing needs clearing between them. */
+#define LMK_GS_STATIC_MAX_N (4u << 20)
+#define LMK_GS_STATIC_MAX_CAPACITY (16ull << 20)
+#define LMK_GS_STATIC_MAX_TILES 16384u
+int32_t lmk_gs_bin_sort_static(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,
+                               const lmk_gs_binned *out, uint64_t *count_status, void *stream);
+
 /* Stage 3 (Sec. 2.2 Eq. 9-10).  Each pixel walks its tile's list front to back:
  * alpha = min(0.99, o * exp(-q/2)), pairs with alpha < 1/255 are skipped, the
  * walk stops before the pair that would take T below 1e-4.

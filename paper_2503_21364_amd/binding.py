@@ -25,7 +25,7 @@ EXPORTS = ("lmk_gs_workspace_bytes", "lmk_gs_preprocess", "lmk_gs_bin_sort", "lm
            "lmk_gs_read_status", "lmk_gs_strerror", "lmk_gs_last_hip_error", "lmk_gs_version",
            "lmk_gs_index_build", "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
            "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode", "lmk_gs_anchor_index_build",
-           "lmk_gs_anchor_decode_culled")
+           "lmk_gs_anchor_decode_culled", "lmk_gs_bin_sort_static")
 
 
 class Gaussians(C.Structure):
@@ -104,6 +104,8 @@ def lib() -> C.CDLL:
                                         C.c_void_p, C.c_size_t, C.c_void_p]
         l.lmk_gs_bin_sort.argtypes = [C.POINTER(Projected), C.c_uint32, C.POINTER(Camera), C.POINTER(Binned),
                                       C.c_void_p, C.c_size_t, C.c_void_p]
+        l.lmk_gs_bin_sort_static.argtypes = [C.POINTER(Projected), C.c_uint32, C.POINTER(Camera), C.POINTER(Binned),
+                                             C.c_void_p, C.c_void_p]
         l.lmk_gs_render.argtypes = [C.POINTER(Projected), C.POINTER(Binned), C.POINTER(Camera),
                                     C.c_void_p, C.c_void_p, C.c_void_p]
         l.lmk_gs_index_build.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_float, C.c_void_p, C.c_void_p,
@@ -128,7 +130,7 @@ def lib() -> C.CDLL:
                      "lmk_gs_read_status", "lmk_gs_last_hip_error", "lmk_gs_index_build",
                      "lmk_gs_preprocess_culled", "lmk_gs_build_cov3d", "lmk_gs_render_backward",
                      "lmk_gs_preprocess_backward", "lmk_gs_anchor_decode", "lmk_gs_anchor_index_build",
-                     "lmk_gs_anchor_decode_culled"):
+                     "lmk_gs_anchor_decode_culled", "lmk_gs_bin_sort_static"):
             getattr(l, name).restype = C.c_int32
         l.lmk_gs_version.restype = C.c_uint32
         _lib = l
@@ -300,6 +302,18 @@ def bin_sort(cam: Camera, frame: Frame, stream=None) -> None:
                                _ptr(frame.scratch), frame.scratch_bytes, _stream_handle(stream))
     if rc != OK:
         raise LmkGsError(rc, "lmk_gs_bin_sort")
+
+
+STATIC_MAX_N, STATIC_MAX_CAPACITY, STATIC_MAX_TILES = 4 << 20, 16 << 20, 16384
+
+
+def bin_sort_static(cam: Camera, frame: Frame, count_status=None, stream=None) -> None:
+    """lmk_gs_bin_sort_static: stage 2 on the library's own fixed scratch array (no workspace, no
+    allocation); count_status: optional int64 device tensor of two elements receiving {D, status}."""
+    rc = lib().lmk_gs_bin_sort_static(C.byref(frame.proj), frame.n, C.byref(cam), C.byref(frame.binned),
+                                      _ptr(count_status), _stream_handle(stream))
+    if rc != OK:
+        raise LmkGsError(rc, "lmk_gs_bin_sort_static")
 
 
 def render(cam: Camera, frame: Frame, stream=None) -> None:

@@ -5,6 +5,7 @@
 
 #include <atomic>
 #include <cmath>
+#include <mutex>
 
 using namespace lmk;
 
@@ -55,6 +56,36 @@ int32_t check_camera(const lmk_gs_camera *cam, ProjParams *pp)
 }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// ---- the scratch of lmk_gs_bin_sort_static: one array per GPU, part of the loaded code object.
+// `static_scratch` is only a host-side handle of the symbol; the device address comes from
+// hipGetSymbolAddress, once per device, and only that address is ever handed to a kernel.
+constexpr uint32_t kStaticMaxN = LMK_GS_STATIC_MAX_N;
+constexpr uint64_t kStaticMaxCapacity = LMK_GS_STATIC_MAX_CAPACITY;
+constexpr uint32_t kStaticMaxTiles = LMK_GS_STATIC_MAX_TILES;
+constexpr size_t kStaticBytes = 96u << 20;
+static __device__ __align__(256) unsigned char static_scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+char *g_static_ptr[kMaxDevices] = {};
+
+// device address of this GPU's copy of the array (the current device's), or nullptr with *err set
+char *static_scratch_ptr(hipError_t *err)
+{
+    int dev = 0;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_static_ptr[dev] = static_cast<char *>(p);
+    }
+    return g_static_ptr[dev];
+}
 
 }  // namespace
 
@@ -150,6 +181,34 @@ int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_c
     if (scratch_bytes < L.total) return LMK_GS_ERR_CAPACITY;
     const hipError_t e = launch_bin_sort(*proj, n, pp, *out, static_cast<char *>(scratch), L,
                                          static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
+}
+
+int32_t lmk_gs_bin_sort_static(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,
+                               const lmk_gs_binned *out, uint64_t *count_status, void *stream)
+{
+    ProjParams pp;
+    const int32_t rc = check_camera(cam, &pp);
+    if (rc != LMK_GS_OK) return rc;
+    if (!proj || !out) return LMK_GS_ERR_INVALID;
+    if (n > 0 && (!proj->depth || !proj->tiles_touched || !proj->rect)) return LMK_GS_ERR_INVALID;
+    if (n > 0 && cam->binning == 1u && (!proj->feat || !aligned(proj->feat, 16))) return LMK_GS_ERR_INVALID;
+    if (!out->tile_offsets) return LMK_GS_ERR_INVALID;
+    if (out->capacity > 0 && (!out->keys || !out->vals || !out->keys_alt || !out->vals_alt))
+        return LMK_GS_ERR_INVALID;
+    if (!aligned(proj->rect, 8) || !aligned(count_status, 8)) return LMK_GS_ERR_INVALID;
+    // the fixed array bounds what fits: sizes beyond it are refused before anything is enqueued
+    if (n > kStaticMaxN || out->capacity > kStaticMaxCapacity || pp.tiles_x * pp.tiles_y > kStaticMaxTiles)
+        return LMK_GS_ERR_CAPACITY;
+    const ScratchLayout L = scratch_layout(n, out->capacity, pp.tiles_x * pp.tiles_y);
+    if (L.total > kStaticBytes) return LMK_GS_ERR_CAPACITY;
+    hipError_t e = hipSuccess;
+    char *scratch = static_scratch_ptr(&e);
+    if (!scratch) return hip_fail(e);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    e = launch_rebuild_handover(*proj, n, pp, scratch, L, s);
+    if (e == hipSuccess) e = launch_bin_sort(*proj, n, pp, *out, scratch, L, s);
+    if (e == hipSuccess && count_status) e = launch_copy_status(scratch, L, count_status, s);
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);
 }
 

@@ -127,6 +127,11 @@ struct ProjParams {
 hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index *index, uint8_t *block_visible,
                              const ProjParams &pp, const lmk_gs_projected &out,
                              char *scratch, const ScratchLayout &L, hipStream_t stream);
+// the scratch contents lmk_gs_bin_sort expects from lmk_gs_preprocess, recomputed from proj alone
+hipError_t launch_rebuild_handover(const lmk_gs_projected &proj, u32 n, const ProjParams &pp,
+                                   char *scratch, const ScratchLayout &L, hipStream_t stream);
+// out[0] = D, out[1] = status (sign-extended) from the scratch header
+hipError_t launch_copy_status(const char *scratch, const ScratchLayout &L, u64 *out, hipStream_t stream);
 hipError_t launch_build_cov3d(const lmk_gs_gaussians &g, float *cov3d, hipStream_t stream);
 hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams &pp, const lmk_gs_binned &out,
                            char *scratch, const ScratchLayout &L, hipStream_t stream);

@@ -573,6 +573,82 @@ hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- hand-over rebuilt from the outputs
+// What lmk_gs_preprocess leaves in the scratch for lmk_gs_bin_sort -- the tile count of every
+// workgroup of 256 primitives and, under binning rule 1, the mask of kept tiles of every rectangle
+// of up to 32 tiles -- recomputed from the per-primitive outputs alone (tiles_touched, rect and the
+// feature record), with the arithmetic of preprocess_kernel, so that a caller holding only those
+// outputs can run stage 2 on a scratch buffer of its own.
+__global__ __launch_bounds__(kPreBlock) void rebuild_handover_kernel(
+    const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect, const float4 *__restrict__ feat,
+    u32 n, ProjParams pp, u32 *__restrict__ block_sums, u32 *__restrict__ tile_masks,
+    ScratchHeader *__restrict__ header)
+{
+    __shared__ u32 s_part[kPreBlock / kWave];
+    const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x == 0) reset_header(header);
+    const u32 cnt = i < n ? tiles_touched[i] : 0u;
+    if (pp.cam.binning == 1u && cnt) {
+        const ushort4 r = rect[i];
+        const u32 w = (u32)r.z - (u32)r.x, area = w * ((u32)r.w - (u32)r.y);
+        if (area <= 32u) {
+            const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
+            const float4 f0 = f[0], f1 = f[1];
+            const TileTest tt = make_tile_test(f0.x, f0.y, f0.z, f0.w, f1.x, opacity_tau(pp, f1.y));
+            u32 mask = 0, slot = 0;
+            for (u32 ty = r.y; ty < r.w; ++ty)
+                for (u32 tx = r.x; tx < r.z; ++tx, ++slot)
+                    if (tile_kept(tt, tx, ty)) mask |= 1u << slot;
+            tile_masks[i] = mask;
+        }
+    }
+    const u32 ws = wave_sum(cnt);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = ws;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 t = 0;
+#pragma unroll
+        for (u32 k = 0; k < kPreBlock / kWave; ++k) t += s_part[k];
+        block_sums[blockIdx.x] = t;
+    }
+}
+
+hipError_t launch_rebuild_handover(const lmk_gs_projected &proj, u32 n, const ProjParams &pp,
+                                   char *scratch, const ScratchLayout &L, hipStream_t stream)
+{
+    u32 *block_sums = reinterpret_cast<u32 *>(scratch + L.block_sums);
+    ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
+    if (L.pre_blocks > 0) {
+        hipLaunchKernelGGL(rebuild_handover_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                           proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect),
+                           reinterpret_cast<const float4 *>(proj.feat), n, pp, block_sums,
+                           reinterpret_cast<u32 *>(scratch + L.tile_masks), header);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const u32 groups = L.pre_blocks ? (L.pre_blocks + kScanGroup - 1) / kScanGroup : 1u;
+    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(groups), dim3(kScanGroup), 0, stream,
+                       block_sums, L.pre_blocks, reinterpret_cast<u64 *>(scratch + L.block_offsets),
+                       reinterpret_cast<u64 *>(scratch + L.group_totals), header);
+    return hipGetLastError();
+}
+
+// {D, status} of the frame from the scratch header to a caller's device array of two 64-bit words
+__global__ void copy_status_kernel(const ScratchHeader *__restrict__ header, u64 *__restrict__ out)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        out[0] = header->dup_count;
+        out[1] = (u64)(long long)header->status;
+    }
+}
+
+hipError_t launch_copy_status(const char *scratch, const ScratchLayout &L, u64 *out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(copy_status_kernel, dim3(1), dim3(64), 0, stream,
+                       reinterpret_cast<const ScratchHeader *>(scratch + L.header), out);
+    return hipGetLastError();
+}
+
 hipError_t launch_box_flags(const float *box, u32 count, const ProjParams &pp, uint8_t *visible, hipStream_t stream)
 {
     if (count == 0) return hipSuccess;

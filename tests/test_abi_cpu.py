@@ -155,6 +155,29 @@ def test_bin_sort_and_render_reject_bad_arguments():
     assert rb(proj, binned, bad) == B.ERR_UNSUPPORTED
 
 
+def test_bin_sort_static_rejects_bad_arguments_and_sizes_beyond_its_array():
+    lib = B.lib()
+    _, proj, binned = _args()
+    cam = _good_camera()
+    bs = lambda p_, n_, c_, b_, cs=None: lib.lmk_gs_bin_sort_static(
+        None if p_ is None else C.byref(p_), n_, None if c_ is None else C.byref(c_),
+        None if b_ is None else C.byref(b_), cs, None)
+    assert bs(None, 10, cam, binned) == B.ERR_INVALID
+    assert bs(proj, 10, None, binned) == B.ERR_INVALID
+    assert bs(proj, 10, cam, None) == B.ERR_INVALID
+    assert bs(proj, 10, cam, binned, 0x1004) == B.ERR_INVALID          # count_status must be 8-byte aligned
+    b2 = B.Binned(0x1000, 0x1000, None, 0x1000, 100, 0x1000, None)
+    assert bs(proj, 10, cam, b2) == B.ERR_INVALID
+    # beyond the fixed array: refused before anything touches the GPU
+    assert bs(proj, B.STATIC_MAX_N + 1, cam, binned) == B.ERR_CAPACITY
+    b3 = B.Binned(0x1000, 0x1000, 0x1000, 0x1000, B.STATIC_MAX_CAPACITY + 1, 0x1000, None)
+    assert bs(proj, 10, cam, b3) == B.ERR_CAPACITY
+    big = _good_camera(); big.width, big.height = 16 * 200, 16 * 100       # 20000 tiles
+    assert bs(proj, 10, big, binned) == B.ERR_CAPACITY
+    # the limits fit the array: the workspace of the largest accepted call is below 96 MiB
+    assert B.workspace_bytes(B.STATIC_MAX_N, 2048, 2048, B.STATIC_MAX_CAPACITY) <= 96 << 20
+
+
 def test_preprocess_backward_rejects_bad_arguments():
     lib = B.lib()
     g, proj, _ = _args()
