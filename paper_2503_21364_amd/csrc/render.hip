@@ -74,12 +74,12 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const u32 *__restrict__ vals, const float4 *__restrict__ feat, BlendParams bp,
     float *__restrict__ out_rgb, float *__restrict__ out_T)
 {
-    // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C, lo = log2(opacity):
-    // log2(alpha) = A' dx^2 + B' dx dy + C' dy^2 + lo.  (du, dv) = splat centre relative to
-    // the centre of block 0.  Slot kBatch is a null record that can never contribute.
-    __shared__ float4 s_geo[kBatch + 1];    // du, dv, A', B'
-    __shared__ float4 s_cop[kBatch + 1];    // C', lo, r, g
-    __shared__ float4 s_tst[kBatch + 1];    // -B'/(2A'), -B'/(2C'), b, -
+    // The staged form of an entry (stage_entry): (du, dv) = splat centre relative to the centre of
+    // block 0, the coefficients of log2(alpha) with the square completed, and what the block tests
+    // read.  Slot kBatch is a null record that can never contribute.
+    __shared__ float4 s_geo[kBatch + 1];    // du, dv, A', -B/A
+    __shared__ float4 s_cop[kBatch + 1];    // -0.5 log2(e) (C - B^2/A), lo, r, g
+    __shared__ float4 s_tst[kBatch + 1];    // B', C', b, -B/C
     // survivor lists hold the records' byte offsets inside s_geo / s_cop / s_tst (at most 4096)
     __shared__ __attribute__((aligned(16))) unsigned short s_list8[kBlendThreads / kWave][kListLen];
     __shared__ __attribute__((aligned(16))) unsigned short s_list4[kBlendThreads / kWave][4][kListLen];
@@ -114,7 +114,6 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
     const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
     float T = 1.0f, cr = 0.0f, cg = 0.0f, cb = 0.0f;
     bool done = !inside;
-    const float kL2E = 1.4426950408889634f;
     const float kPass = kBlockPass;
     constexpr u32 kNullOfs = kBatch * 16u;
 
@@ -131,11 +130,10 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
         {
             // every thread stages one slot; slots past the end of the list can never pass a test
             const bool valid = tid < cnt;
-            const float A = -0.5f * kL2E * next.a.z, Bq = -kL2E * next.a.w, Cq = -0.5f * kL2E * next.b.x;
-            s_geo[tid] = make_float4(next.a.x - X0, next.a.y - Y0, A, Bq);
-            s_cop[tid] = make_float4(Cq, valid ? __log2f(next.b.y) : -1000.0f, next.b.z, next.b.w);
-            s_tst[tid] = make_float4(valid ? -Bq / (2.0f * A) : 0.0f, valid ? -Bq / (2.0f * Cq) : 0.0f,
-                                     next.c.x, 0.0f);
+            const StagedEntry se = stage_entry(next.a, next.b, next.c.x, X0, Y0);
+            s_geo[tid] = valid ? se.geo : make_float4(0.f, 0.f, 0.f, 0.f);
+            s_cop[tid] = valid ? se.cop : make_float4(0.f, -1000.0f, 0.f, 0.f);
+            s_tst[tid] = valid ? se.tst : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         __syncthreads();
         {
@@ -152,7 +150,7 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
             const float4 t = s_tst[c0 + lane];
             const float4 co = s_cop[c0 + lane];
             const float xs = g.x - bx, ys = g.y - by;
-            const float best = square_reach(xs, ys, g.z, g.w, co.x, t.x, t.y, kHalf8);
+            const float best = square_reach(xs, ys, g.z, t.x, t.y, g.w, t.w, kHalf8);
             const bool pass = best + co.y >= kPass;
             const u64 mask = __builtin_amdgcn_ballot_w64(pass);
             const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
@@ -173,7 +171,7 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
 #pragma unroll
             for (u32 q = 0; q < 4; ++q) {
                 const float qx = (q & 1u) ? 2.0f : -2.0f, qy = (q >> 1) ? 2.0f : -2.0f;
-                const float best = square_reach(xs - qx, ys - qy, g.z, g.w, co.x, t.x, t.y, kHalf4);
+                const float best = square_reach(xs - qx, ys - qy, g.z, t.x, t.y, g.w, t.w, kHalf4);
                 const bool sub_alive = ((alive >> (16u * q)) & 0xffffull) != 0ull;
                 const bool pass = sub_alive && best + co.y >= kPass;
                 const u64 mask = __builtin_amdgcn_ballot_w64(pass);
@@ -201,8 +199,7 @@ __global__ __launch_bounds__(kBlendThreads) void blend_kernel(
                 const float4 g = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_geo) + ofs[q]);
                 co[q] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(s_cop) + ofs[q]);
                 const float dx = g.x - ox, dy = g.y - oy;
-                const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co[q].x * dy, dy, co[q].y));
-                alpha[q] = fminf(0.99f, __builtin_amdgcn_exp2f(p));
+                alpha[q] = fminf(0.99f, __builtin_amdgcn_exp2f(log2_alpha(g, co[q], dx, dy)));
             }
 #pragma unroll
             for (u32 q = 0; q < kSurv; ++q) {

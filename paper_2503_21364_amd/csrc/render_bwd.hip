@@ -72,7 +72,7 @@ __device__ __forceinline__ u32 block_survivors(const float4 *s_geo, const float4
         const float4 g = s_geo[e < cnt ? e : 0u];
         const float4 t = s_tst[e < cnt ? e : 0u];
         const float4 co = s_cop[e < cnt ? e : 0u];
-        const float best = square_reach(g.x - bx, g.y - by, g.z, g.w, co.x, t.x, t.y, 3.5f);
+        const float best = square_reach(g.x - bx, g.y - by, g.z, t.x, t.y, g.w, t.w, 3.5f);
         const bool pass = e < cnt && best + co.y >= kBlockPass;
         const u64 mask = __builtin_amdgcn_ballot_w64(pass);
         const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
@@ -100,7 +100,7 @@ __device__ __forceinline__ void subblock_survivors(const float4 *s_geo, const fl
 #pragma unroll
         for (u32 q = 0; q < 4; ++q) {
             const float qx = (q & 1u) ? 2.0f : -2.0f, qy = (q >> 1) ? 2.0f : -2.0f;
-            const float best = square_reach(xs - qx, ys - qy, g.z, g.w, co.x, t.x, t.y, 1.5f);
+            const float best = square_reach(xs - qx, ys - qy, g.z, t.x, t.y, g.w, t.w, 1.5f);
             const bool pass = valid && best + co.y >= kBlockPass;
             const u64 mask = __builtin_amdgcn_ballot_w64(pass);
             const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
@@ -115,11 +115,10 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     const float4 *__restrict__ feat, BwdParams bp, const float *__restrict__ grad_rgb,
     const float *__restrict__ grad_T, float *__restrict__ grad_feat)
 {
-    // A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C, lo = log2(opacity):
-    // log2(alpha) = A' dx^2 + B' dx dy + C' dy^2 + lo, exactly as blend_kernel evaluates it
-    __shared__ float4 s_geo[kBwdBatch];          // du, dv, A', B'
-    __shared__ float4 s_cop[kBwdBatch];          // C', lo, r, g
-    __shared__ float4 s_tst[kBwdBatch];          // -B'/(2A'), -B'/(2C'), b, 1 / opacity
+    // the staged form of blend_kernel (stage_entry), so that log2(alpha) is evaluated exactly as there
+    __shared__ float4 s_geo[kBwdBatch];          // du, dv, A', -B/A
+    __shared__ float4 s_cop[kBwdBatch];          // -0.5 log2(e) (C - B^2/A), lo, r, g
+    __shared__ float4 s_tst[kBwdBatch];          // B', C', b, -B/C
     __shared__ u32 s_id[kBwdBatch];              // primitive index
     __shared__ float s_acc[kBwdBatch][kGradComps];
     __shared__ slot_t s_list[kBwdThreads / kWave][kBwdBatch];
@@ -158,11 +157,8 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
         if (tid < cnt) {
             const u32 g = vals[start + base + tid];
             const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
-            const float4 a = f[0], b = f[1];
-            const float A = -0.5f * kL2E * a.z, Bq = -kL2E * a.w, Cq = -0.5f * kL2E * b.x;
-            s_geo[tid] = make_float4(a.x - X0, a.y - Y0, A, Bq);
-            s_cop[tid] = make_float4(Cq, __log2f(b.y), b.z, b.w);
-            s_tst[tid] = make_float4(-Bq / (2.0f * A), -Bq / (2.0f * Cq), 0.0f, 0.0f);
+            const StagedEntry se = stage_entry(f[0], f[1], 0.0f, X0, Y0);
+            s_geo[tid] = se.geo; s_cop[tid] = se.cop; s_tst[tid] = se.tst;
         }
         __syncthreads();
         if (__builtin_amdgcn_ballot_w64(!done) == 0ull) continue;     // this wavefront is finished
@@ -178,8 +174,7 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
             const float4 g = s_geo[j];
             const float4 co = s_cop[j];
             const float dx = g.x - ox, dy = g.y - oy;
-            const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co.x * dy, dy, co.y));
-            const float alpha = fminf(0.99f, __builtin_amdgcn_exp2f(p));
+            const float alpha = fminf(0.99f, __builtin_amdgcn_exp2f(log2_alpha(g, co, dx, dy)));
             const float Tn = fmaf(-T, alpha, T);
             const bool hit = in_list && !done && !(alpha < 1.0f / 255.0f);
             const bool stop = hit && Tn < 1e-4f;
@@ -223,11 +218,8 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
         if (tid < cnt) {
             const u32 g = vals[start + base + tid];
             const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
-            const float4 a = f[0], bq = f[1], c = f[2];
-            const float A = -0.5f * kL2E * a.z, Bq = -kL2E * a.w, Cq = -0.5f * kL2E * bq.x;
-            s_geo[tid] = make_float4(a.x - X0, a.y - Y0, A, Bq);
-            s_cop[tid] = make_float4(Cq, __log2f(bq.y), bq.z, bq.w);
-            s_tst[tid] = make_float4(-Bq / (2.0f * A), -Bq / (2.0f * Cq), c.x, 1.0f / bq.y);
+            const StagedEntry se = stage_entry(f[0], f[1], f[2].x, X0, Y0);
+            s_geo[tid] = se.geo; s_cop[tid] = se.cop; s_tst[tid] = se.tst;
             s_id[tid] = g;
         }
         if (tid < kBwdBatch) {
@@ -249,8 +241,7 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
             const float4 g = s_geo[j];
             const float4 co = s_cop[j];
             const float dx = g.x - ox, dy = g.y - oy;
-            const float p = fmaf(dx, fmaf(g.z, dx, g.w * dy), fmaf(co.x * dy, dy, co.y));
-            const float raw = __builtin_amdgcn_exp2f(p);
+            const float raw = __builtin_amdgcn_exp2f(log2_alpha(g, co, dx, dy));
             const float alpha = fminf(0.99f, raw);
             const bool hit = in_list && base + j < last && !(alpha < 1.0f / 255.0f);
             const u64 hits = __builtin_amdgcn_ballot_w64(hit);
@@ -269,15 +260,15 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
                 T = Ti;
                 v[6] = w * gr; v[7] = w * gg; v[8] = w * gb;
                 if (!(raw > 0.99f)) {
-                    v[5] = dLda * (alpha * ts.w);
+                    v[5] = dLda * (alpha * __builtin_amdgcn_exp2f(-co.y));      // alpha / opacity
                     const float dLdq = -0.5f * alpha * dLda;
                     v[2] = dLdq * dx * dx;
                     v[3] = dLdq * 2.0f * dx * dy;
                     v[4] = dLdq * dy * dy;
                     // 2 (A dx + B dy) and 2 (B dx + C dy) from A' = -0.5 log2(e) A, B' = -log2(e) B, C' likewise
                     const float kInv = -2.0f / kL2E;
-                    v[0] = dLdq * kInv * (2.0f * g.z * dx + g.w * dy);
-                    v[1] = dLdq * kInv * (g.w * dx + 2.0f * co.x * dy);
+                    v[0] = dLdq * kInv * (2.0f * g.z * dx + ts.x * dy);
+                    v[1] = dLdq * kInv * (ts.x * dx + 2.0f * ts.y * dy);
                 }
             }
             // the nine row sums side by side (independent DPP chains), then one guarded group of

@@ -7,14 +7,13 @@ Bars (written out here, used by every parity test):
   * key-path floats (u, v, conic, opacity): produced by the same fp32 operation
     sequence on both sides, compared exactly;
   * SH colour (fp32 on the GPU, fp64 in the oracle): 2e-5 absolute + 1e-5 relative;
-  * image and transmittance: |gpu - oracle| <= 1e-4 + beta(pixel).  beta is the
-    oracle's per-pixel error budget for an fp32 renderer: a first-order bound of
-    the fp32 rounding of the quadratic form (tiny unless a long thin splat is
-    evaluated far from its centre), plus, for a pixel in which some pair sits
-    within that rounding of a decision threshold (alpha = 1/255, T = 1e-4), the
-    whole contribution that flipping the decision would move.  The share of
-    pixels with such an ambiguous decision is returned and bounded by the caller,
-    and so is the largest budget among the unambiguous ones.
+  * image and transmittance: |gpu - oracle| <= 1e-4 per channel on every pixel in which the
+    oracle found no decision (alpha against 1/255, T' against 1e-4) within fp32 rounding of its
+    threshold.  A pixel that holds such a decision may take it either way in any fp32 renderer,
+    which moves it by that pair's whole contribution (up to 4e-3); there the bar is
+    1e-4 + beta(pixel), beta being the oracle's bound on what the flips can move plus the
+    first-order fp32 rounding of the walk.  The share of such pixels is bounded (0.5 %), and so
+    is the share of the other pixels whose rounding budget alone exceeds a quarter of the bar.
 """
 from __future__ import annotations
 
@@ -73,25 +72,34 @@ def compare_binned(fr: B.Frame, b) -> dict:
     return dict(D=D)
 
 
-def compare_image(fr: B.Frame, img, cam: dict, max_ambiguous_share=0.02) -> dict:
+def image_errors(rgb, T, img):
+    """Per-pixel errors, tolerances and the mask of pixels without an ambiguous decision."""
+    plain = img.amb == 0
+    tol_rgb = np.where(plain, IMG_TOL, IMG_TOL + img.beta)
+    tol_T = np.where(plain, IMG_TOL, IMG_TOL + img.beta_T)
+    err_rgb = np.abs(rgb - img.rgb).max(axis=0)
+    err_T = np.abs(T - img.T)
+    return err_rgb, err_T, tol_rgb, tol_T, plain
+
+
+def compare_image(fr: B.Frame, img, cam: dict, max_ambiguous_share=0.005, max_loose_share=0.25) -> dict:
     rgb = to_np(fr.out_rgb).astype(np.float64)
     T = to_np(fr.out_T).astype(np.float64)
     assert float(np.max(np.abs(cam["bg"]))) <= 1.0
-    tol_rgb = IMG_TOL + img.beta
-    tol_T = IMG_TOL + img.beta_T
-    err_rgb = np.abs(rgb - img.rgb).max(axis=0)
-    err_T = np.abs(T - img.T)
-    plain = img.amb == 0
+    err_rgb, err_T, tol_rgb, tol_T, plain = image_errors(rgb, T, img)
     share = 1.0 - plain.mean()
     bad = (err_rgb > tol_rgb) | (err_T > tol_T)
     if bad.any():
         ys, xs = np.nonzero(bad)
-        raise AssertionError(f"{bad.sum()} pixels beyond tolerance; first (x={xs[0]}, y={ys[0]}): "
+        raise AssertionError(f"{bad.sum()} pixels beyond tolerance ({(bad & plain).sum()} of them without an "
+                             f"ambiguous decision: bar {IMG_TOL}); first (x={xs[0]}, y={ys[0]}): "
                              f"rgb err {err_rgb[ys[0], xs[0]]:.3e}, T err {err_T[ys[0], xs[0]]:.3e}, "
-                             f"beta {img.beta[ys[0], xs[0]]:.3e}, amb {img.amb[ys[0], xs[0]]}")
+                             f"beta {img.beta[ys[0], xs[0]]:.3e}, amb {img.amb[ys[0], xs[0]]}; "
+                             f"worst unambiguous rgb err {err_rgb[plain].max():.3e}")
     assert share <= max_ambiguous_share, f"{share:.4f} of the pixels hold an ambiguous decision"
-    # the rounding part of the budget must stay a small fraction of the tolerance for most pixels
+    # the rounding part of the budget must stay a small fraction of the bar for most pixels
     loose = (img.beta[plain] > 0.25 * IMG_TOL).mean() if plain.any() else 0.0
+    assert loose <= max_loose_share, f"rounding budget above a quarter of the bar on {loose:.3f} of the pixels"
     assert np.median(img.beta) <= 0.1 * IMG_TOL, f"median rounding budget {np.median(img.beta):.2e}"
     return dict(max_err_plain=float(err_rgb[plain].max()) if plain.any() else 0.0,
                 max_err_T_plain=float(err_T[plain].max()) if plain.any() else 0.0,
