@@ -133,8 +133,8 @@ static int32_t preprocess_common(const lmk_gs_gaussians *g, const lmk_gs_voxel_i
     }
     if (!aligned(scratch, 256)) return LMK_GS_ERR_INVALID;
     // the part of the scratch this call touches does not depend on the pair capacity
-    const ScratchLayout L = scratch_layout(g->n, 0, 0);
-    if (scratch_bytes < L.digit_totals) return LMK_GS_ERR_CAPACITY;
+    const ScratchLayout L = scratch_layout(g->n, 0, pp.tiles_x * pp.tiles_y);
+    if (scratch_bytes < L.bin_count) return LMK_GS_ERR_CAPACITY;
     const hipError_t e = launch_preprocess(*g, g->n > 0 ? index : nullptr, block_visible, pp, *out,
                                            static_cast<char *>(scratch), L, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LMK_GS_OK : hip_fail(e);

@@ -1,776 +1,366 @@
 // Stage 2: duplication of primitives into (tile | depth) keys, sort of the pairs into
-// (tile, depth bits, index) order, per-tile range extraction (the "depth sorting ... at the
-// granularity of tiles" of Sec. 2.2; duplication with keys is the second kernel named in
-// Sec. 4.2.1).
+// (tile, depth bits, index) order, per-tile ranges (the "depth sorting ... at the granularity of
+// tiles" of Sec. 2.2; duplication with keys is the second kernel named in Sec. 4.2.1).
 //
-// Integer work bound by HBM traffic and, in the per-tile sorts, by LDS bandwidth.  The kernels
-// read the pair count D from device memory, so the host never waits for it: grids are sized
-// from the caller's capacity and surplus workgroups leave at once.
+// The sorted order is total -- (tile, depth bits, primitive index) has no ties -- so it does not
+// matter in which order a tile's pairs arrive in the tile's slice of the buffers: the per-tile
+// sort fixes it.  The pairs are therefore written straight into their tile's slice, never
+// partitioned by a sort over the tile bits: count per tile, scan, then write on a second walk.
 //
-//   emit     one workgroup per 256 primitives, placed by a two-level prefix sum over the
-//            workgroup tile counts of the preprocess kernel.  Binning rule 0: a load-balanced
-//            expansion, the workgroup's output slots are dealt round-robin to its threads and
-//            each slot finds its primitive by binary search in an LDS prefix array, so stores
-//            are contiguous whatever the rectangle sizes are.  Rule 1: every thread walks the
-//            bit mask of kept tiles the preprocess kernel left for its primitive.  Rectangles of
-//            more than 128 tiles (rule 1: more than 32, the width of the mask) are deferred to a
-//            list and expanded by emit_deferred_kernel, one wavefront (or, beyond 2048 tiles,
-//            one workgroup) each, which under rule 1 repeats the intersection test per tile.
-//   partition  stable LSD radix sort over the TILE bits of the keys only (two passes of
-//            7 + 6 bits at 1080p).  Per pass: (1) digit counts of every 2048-pair sort tile
-//            and the pass's digit totals, (2) one workgroup per digit turns its row of counts
-//            into output offsets, (3) scatter: wavefront match-any ranking (ballots over the
-//            digit bits) keeps equal digits in order, the tile is sorted by digit in LDS and
-//            written out in contiguous runs (128 or fewer bins, so runs are long).
-//   ranges   tile_offsets[t] = first position whose tile id is >= t.
-//   order    tile ids by descending list length, bucketed by the bit length of the length,
-//            which also gives the size classes of the per-tile sort and the chunk list.
-//   tile sort  every tile's list is sorted by (depth bits, index) as 64-bit composites with a
-//            merge sort in LDS (the order is total, so no stability is needed): one wavefront
-//            for lists of up to 512 pairs, 256 threads up to 2048, 512 threads up to 4096.  A
-//            list of up to 16384 pairs is cut into 4096-pair chunks, sorted by workgroups of
-//            the 512-thread launch and merged in two rounds between the two pair buffers by
-//            workgroups of the 256-thread and the one-wavefront launch.  Lists beyond that get
-//            a workgroup of 1024 threads each: 16384-pair chunks in LDS, then pairwise merges
-//            through LDS-staged windows.  Sorting the 32 depth bits this way costs one read
-//            and one write of most pairs instead of four radix passes over all of them.
+//   count    one workgroup per 1024 consecutive primitives.  A rectangle of up to 32 tiles (nearly
+//            all of them) is walked by its own lane -- binning rule 0: every tile; rule 1: the kept
+//            tiles, from the bit mask the projection kernel left -- and counted per tile in LDS.  A
+//            scene in spatial order puts a workgroup's pairs into few tiles, and the workgroup then
+//            adds to the global per-tile counts with ONE returning atomic per tile it touched, not
+//            per pair: the value returned is where its run starts inside that tile's slice.  The
+//            (tile, start) list goes to memory for the emit kernel, at a place that follows from
+//            the prefix sum over the workgroup pair counts which the projection stage left (a list
+//            has at most one entry per pair).  Larger rectangles go to a list of their own.
+//   count (large rectangles)  one wavefront per listed primitive (one workgroup beyond 2048 tiles)
+//            walks its rectangle 64 tiles per step in row-major order (rule 1: with the
+//            intersection test), one atomic per pair.  Lanes hold consecutive tiles, so the
+//            atomics of one instruction fall into one or two cache lines and the memory side takes
+//            them together (ten times the rate of scattered ones).  The close-up primitives of a
+//            frame sit in a few workgroups; the list spreads them over the whole chip.
+//   scan     one workgroup: the capacity check, exclusive prefix sum of the per-tile counts = the
+//            per-tile ranges, a running position per tile for the listed primitives, the tiles by
+//            descending list length with the size classes and the chunk list of the per-tile
+//            sort; it leaves the counters zero.
+//   emit     the same walks again.  A workgroup sets its LDS counters to range start + run start
+//            for the tiles of its list and hands out positions from them.  A listed primitive
+//            advances the tile's running position pair by pair, again with lane-consecutive
+//            atomics, eight steps in flight.  What is written is the composite the list is
+//            ordered by, depth bits << 32 | index.
+//   tile sort  every tile's slice is sorted by that composite with a merge sort in LDS and
+//            rewritten in its final form (key = tile << 32 | depth bits, value = index): one
+//            wavefront for lists of up to 512 pairs, 256 threads up to 2048, 512 threads up to
+//            4096.  A list of up to 16384 pairs is cut into 4096-pair chunks, sorted by
+//            workgroups of the 512-thread launch and merged in two rounds between the two pair
+//            buffers by workgroups of the 256-thread and the one-wavefront launch.  Lists beyond
+//            that get a workgroup of 1024 threads each: 16384-pair chunks in LDS, then pairwise
+//            merges through LDS-staged windows.
+//
+// Integer work, bound by HBM traffic, global atomic throughput and, in the per-tile sorts, by
+// LDS bandwidth and vector issue.  Atomics on one address are served one after the other (about
+// 12 ns each), so nothing here funnels every workgroup through one counter.  The kernels read the
+// pair count from device memory, so the host never waits for it: grids are sized from the
+// caller's capacity and surplus workgroups leave at once.  If D exceeds the capacity nothing is
+// emitted: every range is empty, the status word says so and D tells the caller how much room a
+// retry needs.
 #include <type_traits>
 
 #include "lmk_gs_internal.h"
+#include "tile_test.h"
 
 namespace lmk {
 
-__device__ __forceinline__ u64 load_D(const ScratchHeader *h, u64 capacity)
+constexpr u32 kMaskArea = 32;       // rectangles whose kept tiles the projection kernel recorded as a bit mask
+
+// ---------------------------------------------------------------- walking a primitive's tiles
+// t / w and t % w for t < 2^22 (a tile grid has at most 2^22 tiles), 1 <= w <= 4096; inv_w = 1 / w
+__device__ __forceinline__ void div_tiles(u32 t, u32 w, float inv_w, u32 &row, u32 &col)
 {
-    const u64 d = h->dup_count;
-    return d < capacity ? d : capacity;
+    u32 q = (u32)((float)t * inv_w);            // within one of the quotient
+    int r = (int)(t - q * w);
+    if (r < 0) { q -= 1u; r += (int)w; }
+    else if (r >= (int)w) { q += 1u; r -= (int)w; }
+    row = q; col = (u32)r;
 }
 
-// ---------------------------------------------------------------- emit
-// Primitives whose rectangle has more than kBigArea tiles (binning rule 0; kMaskArea under
-// rule 1) are not expanded by their own workgroup: with a spatially ordered scene the close-up
-// primitives, tens to hundreds of tiles each, sit in a few workgroups, which would then run many
-// times longer than the rest.  Their index and output offset go to a list (one atomic per
-// wavefront) that emit_deferred_kernel expands, one wavefront per primitive (one workgroup per
-// primitive beyond kGiantArea tiles, from the back of the same list), with the same output positions.
-constexpr u32 kBigArea = 128;
-constexpr u32 kMaskArea = 32;       // rectangles whose kept tiles the preprocess kernel recorded as a bit mask
-constexpr u32 kGiantArea = 2048;
-
-__device__ __forceinline__ void append_deferred(bool want, u32 *counter, bool from_back, u32 i, u64 offset,
-                                                u32 *__restrict__ big_idx, u64 *__restrict__ big_off, u32 lane, u32 n)
+// A rectangle of up to kMaskArea tiles, walked by its own lane: f(tile id) for every tile that
+// gets a pair, in row-major order.  Under binning rule 1 (TIGHT) those are the set bits of `mask`.
+template <bool TIGHT, class F>
+__device__ __forceinline__ void walk_small(ushort4 r, u32 area, u32 mask, u32 tiles_x, F &&f)
 {
-    const u64 m = __builtin_amdgcn_ballot_w64(want);
-    if (m == 0ull) return;
-    u32 base = 0;
-    const int leader = (int)__builtin_ctzll(m);
-    if ((int)lane == leader) base = atomicAdd(counter, (u32)__builtin_popcountll(m));
-    base = (u32)__builtin_amdgcn_readlane((int)base, leader);
-    if (want) {
-        const u32 k = base + __builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, 0u));
-        if (k < n) {                                  // the list holds one entry per primitive at most
-            const u32 slot = from_back ? n - 1 - k : k;
-            big_idx[slot] = i;
-            big_off[slot] = offset;
+    const u32 w = (u32)r.z - (u32)r.x;
+    const u32 inv_w = w ? (65536u + w - 1u) / w : 0u;       // slot / w == (slot * inv_w) >> 16 for slot < 32, w <= 32
+    if (TIGHT) {
+        while (mask) {
+            const u32 slot = (u32)__builtin_ctz(mask);
+            mask &= mask - 1u;
+            const u32 row = (slot * inv_w) >> 16;
+            f(((u32)r.y + row) * tiles_x + (u32)r.x + (slot - row * w));
+        }
+    } else {
+        for (u32 slot = 0; slot < area; ++slot) {
+            const u32 row = (slot * inv_w) >> 16;
+            f(((u32)r.y + row) * tiles_x + (u32)r.x + (slot - row * w));
         }
     }
 }
 
-__device__ __forceinline__ void append_big(u32 area, u32 own_limit, u32 i, u64 offset, ScratchHeader *header,
-                                           u32 *__restrict__ big_idx, u64 *__restrict__ big_off, u32 lane, u32 n)
+// One listed primitive, walked by a whole wavefront, 64 tiles of its rectangle per step in
+// row-major order.  For every tile that gets a pair (under binning rule 1, TIGHT, every tile goes
+// through the intersection test), first value = issue(tile, rank), then commit(tile, rank, value)
+// -- kLargeBatch steps at a time, all their `issue` calls ahead of the first `commit`: `issue`
+// starts a memory operation (a returning atomic) whose latency would otherwise be paid once per
+// step, one after the other.  rank = the pair's number among those this wavefront found.
+constexpr u32 kLargeBatch = 8;
+
+// A rectangle shared by several wavefronts: wavefront `part` of `parts` takes batches part, part + parts, ...
+template <bool TIGHT, class Issue, class Commit>
+__device__ __forceinline__ void walk_large(ushort4 r, const float4 *__restrict__ feat_i, const ProjParams &pp,
+                                           u32 lane, u32 part, u32 parts, Issue &&issue, Commit &&commit)
 {
-    append_deferred(area > own_limit && area <= kGiantArea, &header->big_count, false, i, offset, big_idx, big_off, lane, n);
-    append_deferred(area > kGiantArea, &header->giant_count, true, i, offset, big_idx, big_off, lane, n);
+    const u32 w = (u32)r.z - (u32)r.x, area = w * ((u32)r.w - (u32)r.y);
+    TileTest tt = make_tile_test(0.f, 0.f, 1.f, 0.f, 1.f, 0.f);
+    if (TIGHT) {
+        const float4 f0 = feat_i[0], f1 = feat_i[1];
+        tt = make_tile_test(f0.x, f0.y, f0.z, f0.w, f1.x, opacity_tau(pp, f1.y));
+    }
+    const float inv_w = 1.0f / (float)w;
+    u32 running = 0;
+    for (u32 t0 = part * kWave * kLargeBatch; t0 < area; t0 += parts * kWave * kLargeBatch) {   // area > 0 implies w > 0; wave-uniform
+        bool keep[kLargeBatch];
+        u32 tile[kLargeBatch], rank[kLargeBatch];
+        u64 value[kLargeBatch];
+#pragma unroll
+        for (u32 b = 0; b < kLargeBatch; ++b) {
+            keep[b] = false; tile[b] = 0; rank[b] = 0;
+            if (t0 + b * kWave < area) {                        // wave-uniform
+                const u32 t = t0 + b * kWave + lane;
+                bool k = t < area;
+                u32 row = 0, col = 0;
+                if (k) div_tiles(t, w, inv_w, row, col);
+                const u32 tx = (u32)r.x + col, ty = (u32)r.y + row;
+                if (TIGHT && k) k = tile_kept(tt, tx, ty);
+                const u64 m = __builtin_amdgcn_ballot_w64(k);
+                keep[b] = k;
+                tile[b] = ty * pp.tiles_x + tx;
+                rank[b] = running + __builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, 0u));
+                running += (u32)__builtin_popcountll(m);
+            }
+        }
+#pragma unroll
+        for (u32 b = 0; b < kLargeBatch; ++b) value[b] = keep[b] ? issue(tile[b], rank[b]) : 0ull;
+#pragma unroll
+        for (u32 b = 0; b < kLargeBatch; ++b)
+            if (keep[b]) commit(tile[b], rank[b], value[b]);
+    }
 }
 
-// Where the pairs of workgroup `b` of the preprocess grid start: its offset inside its group
-// of kScanGroup workgroups plus the totals of the groups before.  Called by the whole workgroup
-// ahead of a __syncthreads(); `s_part` gets one partial sum per wavefront, summed by block_base_finish.
-__device__ __forceinline__ void block_base_start(const u64 *__restrict__ group_totals, u32 b, u64 *s_part,
+// ---------------------------------------------------------------- count
+// LDS_TILES > 0: the image has at most LDS_TILES tiles, rectangles of up to kMaskArea tiles are
+// counted in LDS, larger ones listed.  LDS_TILES == 0 (images of more tiles): every primitive is
+// listed.
+// A workgroup takes kBinBlock consecutive primitives, kBinBlock / THREADS per thread (primitive
+// tid + j THREADS in round j): with 32 KB of counters, workgroups of 256 threads fit four to a
+// compute unit, and what bounds these kernels is the chain of memory round trips of a workgroup.
+template <u32 LDS_TILES> struct BinShape {
+    static constexpr u32 kThreads = LDS_TILES == kLdsTilesSmall ? 256u : kBinBlock;
+    static constexpr u32 kPer = kBinBlock / kThreads;
+    static constexpr u32 kWaves = kThreads / kWave;
+    static constexpr u32 kRounds = LDS_TILES / kThreads;    // counters per thread
+};
+constexpr u32 kGiantArea = 2048;    // listed rectangles beyond this many tiles get a workgroup, not a wavefront
+
+// Where the list of counting workgroup b starts: the pairs of all primitives before its own, from
+// the two-level prefix sum the projection stage left (block_offsets inside a group of kScanGroup
+// preprocess workgroups, plus the totals of the groups before).  Called by the whole workgroup
+// ahead of a barrier; one partial sum per wavefront goes to s_part, list_first_finish adds them.
+template <u32 THREADS>
+__device__ __forceinline__ void list_first_start(const u64 *__restrict__ group_totals, u32 b, u64 *s_part,
                                                  u32 tid, u32 lane, u32 wv)
 {
-    const u32 groups_before = b / kScanGroup;
+    const u32 groups_before = (b * (kBinBlock / kPreBlock)) / kScanGroup;
     u64 part = 0;
-    for (u32 g = tid; g < groups_before; g += kPreBlock) part += group_totals[g];
+    for (u32 g = tid; g < groups_before; g += THREADS) part += group_totals[g];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
     if (lane == 0) s_part[wv] = part;
 }
-__device__ __forceinline__ u64 block_base_finish(const u64 *__restrict__ block_offsets, u32 b, const u64 *s_part)
+template <u32 WAVES>
+__device__ __forceinline__ u64 list_first_finish(const u64 *__restrict__ block_offsets, u32 b, const u64 *s_part)
 {
-    u64 base = block_offsets[b];
+    u64 first = block_offsets[b * (kBinBlock / kPreBlock)];
 #pragma unroll
-    for (u32 k = 0; k < kPreBlock / kWave; ++k) base += s_part[k];
-    return base;
+    for (u32 k = 0; k < WAVES; ++k) first += s_part[k];
+    return first;
 }
 
-// What every workgroup of the emit grid does first.  Returns true when the preprocess kernel
-// counted no pair for this workgroup (culled, or a skipped voxel range): then it is done here,
-// without reading a primitive.
-__device__ __forceinline__ bool emit_prologue(const u32 *__restrict__ block_sums, const u64 *__restrict__ block_offsets,
-                                              const u64 *__restrict__ group_totals, u32 n, u64 capacity,
-                                              u64 *__restrict__ offsets, ScratchHeader *__restrict__ header,
-                                              u64 *__restrict__ digit_totals, u64 *s_gpart, u32 tid, u32 lane, u32 wv)
+template <u32 LDS_TILES, bool TIGHT>
+__global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void count_kernel(
+    const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect, const u32 *__restrict__ tile_masks,
+    u32 n, u32 tiles_x, u32 num_tiles, u32 *__restrict__ tile_count,
+    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx,
+    const u64 *__restrict__ block_offsets, const u64 *__restrict__ group_totals,
+    u32 *__restrict__ bin_count, uint2 *__restrict__ list, u64 list_capacity)
 {
-    if (blockIdx.x == 0 && tid == 0 && header->dup_count > capacity) header->status = LMK_GS_ERR_CAPACITY;
-    // the partition's digit totals are accumulated with atomics: start from zero
-    for (u32 k = blockIdx.x * kPreBlock + tid; k < kMaxPasses * kTotalCopies * kMaxRadix; k += gridDim.x * kPreBlock)
-        digit_totals[k] = 0;
-    if (block_sums[blockIdx.x] != 0) return false;
-    if (offsets) {
-        block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);
+    constexpr bool LDS = LDS_TILES > 0;
+    constexpr u32 kThreads = BinShape<LDS_TILES>::kThreads, kPer = BinShape<LDS_TILES>::kPer;
+    constexpr u32 kWaves = BinShape<LDS_TILES>::kWaves;
+    constexpr u32 kRounds = LDS ? BinShape<LDS_TILES>::kRounds : 1;
+    constexpr u32 kSmallMax = LDS ? kMaskArea : 0u;
+    __shared__ u32 s_hist[LDS ? LDS_TILES : 1];
+    __shared__ u32 s_next;
+    __shared__ u32 s_wave[kWaves][2];
+    __shared__ u32 s_base[2];
+    __shared__ u64 s_part[kWaves];
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    // everything this thread will need is requested at once: one round trip to memory
+    u32 cnt[kPer], mask[kPer];
+    ushort4 r[kPer];
+    bool any = false;
+#pragma unroll
+    for (u32 j = 0; j < kPer; ++j) {
+        const u32 i = blockIdx.x * kBinBlock + j * kThreads + tid;
+        cnt[j] = i < n ? tiles_touched[i] : 0u;
+        r[j] = i < n ? rect[i] : make_ushort4(0, 0, 0, 0);
+        mask[j] = (TIGHT && LDS && i < n) ? tile_masks[i] : 0u;
+    }
+    if (LDS) {
+        list_first_start<kThreads>(group_totals, blockIdx.x, s_part, tid, lane, wv);
+        for (u32 t = tid; t < num_tiles; t += kThreads) s_hist[t] = 0;
+        if (tid == 0) s_next = 0;
+    }
+#pragma unroll
+    for (u32 j = 0; j < kPer; ++j) any = any || cnt[j] != 0u;
+    if (!__syncthreads_or(any)) {                           // nothing of this workgroup was binned
+        if (LDS && tid == 0) bin_count[blockIdx.x] = 0;
+        return;
+    }
+    u32 large_bits = 0, giant_bits = 0;                     // bit j: primitive j of this thread goes to the list
+#pragma unroll
+    for (u32 j = 0; j < kPer; ++j) {
+        const u32 area = cnt[j] ? ((u32)r[j].z - (u32)r[j].x) * ((u32)r[j].w - (u32)r[j].y) : 0u;
+        if (LDS && area > 0u && area <= kSmallMax) {
+            walk_small<TIGHT>(r[j], area, mask[j], tiles_x, [&](u32 tile) {
+                if (tile < num_tiles) atomicAdd(&s_hist[tile], 1u);     // a rectangle never leaves the grid; a corrupt one must not either
+            });
+        }
+        if (area > kGiantArea) giant_bits |= 1u << j;
+        else if (area > kSmallMax) large_bits |= 1u << j;
+    }
+    // the lists of the other primitives (wavefront-sized rectangles from the front of big_idx,
+    // workgroup-sized ones from the back): one global atomic each per workgroup that has any
+    const u32 my_large = (u32)__builtin_popcount(large_bits), my_giant = (u32)__builtin_popcount(giant_bits);
+    if (__syncthreads_or((my_large | my_giant) != 0u)) {    // also: every LDS count above is done
+        u32 incl = my_large, incl2 = my_giant;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const u32 v = __shfl_up(incl, o, 64), v2 = __shfl_up(incl2, o, 64);
+            if ((int)lane >= o) { incl += v; incl2 += v2; }
+        }
+        if (lane == kWave - 1) { s_wave[wv][0] = incl; s_wave[wv][1] = incl2; }
         __syncthreads();
-        const u64 base = block_base_finish(block_offsets, blockIdx.x, s_gpart);
-        const u32 i = blockIdx.x * kPreBlock + tid;
-        if (i < n) offsets[i] = base;
-        if (i == n - 1) offsets[n] = base;
-    }
-    return true;
-}
-
-__global__ __launch_bounds__(kPreBlock) void emit_kernel(
-    const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
-    const float *__restrict__ depth, const u32 *__restrict__ block_sums, const u64 *__restrict__ block_offsets,
-    const u64 *__restrict__ group_totals, u32 n, u32 tiles_x,
-    u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
-    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
-    u64 *__restrict__ digit_totals)
-{
-    __shared__ u64 s_gpart[kPreBlock / kWave];
-    __shared__ u32 s_excl[kPreBlock];     // exclusive prefix of the (small) rectangles expanded here
-    __shared__ u32 s_off[kPreBlock];      // exclusive prefix of tiles_touched: where a primitive's pairs start
-    __shared__ ushort4 s_rect[kPreBlock];
-    __shared__ u32 s_depth[kPreBlock];
-    __shared__ u32 s_wave[kPreBlock / kWave];
-    __shared__ u32 s_wave2[kPreBlock / kWave];
-
-    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const u32 i = blockIdx.x * kPreBlock + tid;
-    if (emit_prologue(block_sums, block_offsets, group_totals, n, capacity, offsets, header, digit_totals,
-                      s_gpart, tid, lane, wv))
-        return;
-    block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);     // summed after the barrier below
-    const u32 cnt = i < n ? tiles_touched[i] : 0u;
-    const bool big = cnt > kBigArea;
-    const u32 small = big ? 0u : cnt;
-    if (cnt) {
-        s_rect[tid] = rect[i];
-        s_depth[tid] = __float_as_uint(depth[i]);
-    }
-    u32 incl = small, incl2 = cnt;
+        u32 before = 0, total = 0, before2 = 0, total2 = 0;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const u32 t = __shfl_up(incl, o, 64), t2 = __shfl_up(incl2, o, 64);
-        if ((int)lane >= o) { incl += t; incl2 += t2; }
-    }
-    if (lane == kWave - 1) { s_wave[wv] = incl; s_wave2[wv] = incl2; }
-    __syncthreads();
-    u32 wave_base = 0, total = 0, wave_base2 = 0, total2 = 0;
-#pragma unroll
-    for (u32 k = 0; k < kPreBlock / kWave; ++k) {
-        const u32 w = s_wave[k], w2 = s_wave2[k];
-        if (k < wv) { wave_base += w; wave_base2 += w2; }
-        total += w; total2 += w2;
-    }
-    s_excl[tid] = wave_base + incl - small;
-    const u32 off = wave_base2 + incl2 - cnt;
-    s_off[tid] = off;
-    const u64 base = block_base_finish(block_offsets, blockIdx.x, s_gpart);
-    if (offsets) {
-        if (i < n) offsets[i] = base + off;
-        if (i == n - 1) offsets[n] = base + total2;
-    }
-    append_big(cnt, kBigArea, i, base + off, header, big_idx, big_off, lane, n);
-    __syncthreads();
-
-    for (u32 j = tid; j < total; j += kPreBlock) {
-        // owner = last primitive whose exclusive prefix is <= j (primitives with
-        // nothing to expand share a prefix with their successor and are skipped by "last")
-        u32 lo = 0, hi = kPreBlock - 1;
-        while (lo < hi) {
-            const u32 mid = (lo + hi + 1) >> 1;
-            if (s_excl[mid] <= j) lo = mid; else hi = mid - 1;
+        for (u32 k = 0; k < kWaves; ++k) {
+            const u32 w = s_wave[k][0], w2 = s_wave[k][1];
+            if (k < wv) { before += w; before2 += w2; }
+            total += w; total2 += w2;
         }
-        const ushort4 r = s_rect[lo];
-        const u32 local = j - s_excl[lo];
-        const u32 w = (u32)r.z - (u32)r.x;
-        const u32 row = local / w;
-        const u32 tx = (u32)r.x + (local - row * w);
-        const u32 ty = (u32)r.y + row;
-        const u64 pos = base + s_off[lo] + local;
-        if (pos < capacity) {
-            keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)s_depth[lo];
-            vals[pos] = blockIdx.x * kPreBlock + lo;
+        if (tid == 0) {
+            s_base[0] = total ? atomicAdd(&header->big_count, total) : 0u;
+            s_base[1] = total2 ? atomicAdd(&header->giant_count, total2) : 0u;
+        }
+        __syncthreads();
+        u32 slot = s_base[0] + before + incl - my_large;
+        u32 slot2 = s_base[1] + before2 + incl2 - my_giant;
+#pragma unroll
+        for (u32 j = 0; j < kPer; ++j) {
+            const u32 i = blockIdx.x * kBinBlock + j * kThreads + tid;
+            // the two lists hold one entry per primitive at most, n in all, and never meet
+            if (large_bits & (1u << j)) { if (slot < n) big_idx[slot] = i; ++slot; }
+            if (giant_bits & (1u << j)) { if (slot2 < n) big_idx[n - 1u - slot2] = i; ++slot2; }
+        }
+    }
+    if (!LDS) return;
+    // The tiles this workgroup touched, compacted to the front of s_hist as tile << 11 | (count - 1)
+    // (a workgroup holds 1024 primitives and a primitive has one pair per tile at most): every
+    // thread first reads its counters, then, all reads done, the entries are written.
+    u32 c[kRounds];
+#pragma unroll
+    for (u32 k = 0; k < kRounds; ++k) {
+        const u32 t = k * kThreads + tid;
+        c[k] = t < num_tiles ? s_hist[t] : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (u32 k = 0; k < kRounds; ++k) {
+        const u64 nz = __builtin_amdgcn_ballot_w64(c[k] != 0u);
+        if (nz == 0ull) continue;                           // wave-uniform
+        u32 at = 0;
+        const int leader = (int)__builtin_ctzll(nz);
+        if ((int)lane == leader) at = atomicAdd(&s_next, (u32)__builtin_popcountll(nz));
+        at = __shfl(at, leader, 64);
+        if (c[k] != 0u)
+            s_hist[at + __builtin_amdgcn_mbcnt_hi((u32)(nz >> 32), __builtin_amdgcn_mbcnt_lo((u32)nz, 0u))] =
+                ((k * kThreads + tid) << 11) | ((c[k] - 1u) & 2047u);
+    }
+    __syncthreads();
+    const u32 touched = s_next;
+    const u64 first = list_first_finish<kWaves>(block_offsets, blockIdx.x, s_part);
+    if (tid == 0) bin_count[blockIdx.x] = touched;
+    // one reservation per touched tile: the run of this workgroup starts where the tile's counter
+    // stood; up to kFlush entries per thread with their atomics in flight together
+    constexpr u32 kFlush = 4;
+    for (u32 k0 = 0; k0 < touched; k0 += kFlush * kThreads) {
+        u32 ent[kFlush], start[kFlush];
+#pragma unroll
+        for (u32 q = 0; q < kFlush; ++q) {
+            const u32 k = k0 + q * kThreads + tid;
+            ent[q] = k < touched ? s_hist[k] : 0u;
+            start[q] = k < touched ? atomicAdd(&tile_count[ent[q] >> 11], (ent[q] & 2047u) + 1u) : 0u;
+        }
+#pragma unroll
+        for (u32 q = 0; q < kFlush; ++q) {
+            const u32 k = k0 + q * kThreads + tid;
+            if (k < touched && first + k < list_capacity) list[first + k] = make_uint2(ent[q] >> 11, start[q]);
         }
     }
 }
 
-// ---------------------------------------------------------------- emit, binning rule 1
-// Only the tiles that pass the splat/tile intersection test of lmk_gs_camera.binning == 1 get a
-// pair, in (primitive, row-major tile) order: the output position of a kept tile is the
-// workgroup's base plus the number of kept tiles before it.  For a rectangle of up to
-// kMaskArea tiles (nearly all primitives) the preprocess kernel left the kept tiles as a bit
-// mask, which the primitive's own thread walks: no test, no feature record.  Larger rectangles
-// go to emit_deferred_kernel, which repeats the test per tile (identical arithmetic to the
-// count in the preprocess kernel; this translation unit is compiled without floating-point
-// contraction for that reason).  Expanding them here, slot by slot across the workgroup, made
-// the workgroups that hold the close-up primitives of a spatially ordered scene the long pole.
-__device__ __forceinline__ float emit_clampf(float v, float lo, float hi) { return v < lo ? lo : (v > hi ? hi : v); }
+// Fixed grids stride over the deferred lists: the first kGiantBlocks workgroups take the
+// workgroup-sized rectangles (their wavefronts share a rectangle batch by batch), the wavefronts of
+// the others the wavefront-sized ones.
+constexpr u32 kLargeThreads = 256, kLargeBlocks = 2048, kGiantBlocks = 1024;
 
-__device__ __forceinline__ float emit_quad_adj(float A, float B, float C, float ex, float ey)
+// f(rectangle index, primitive index, part, parts) for every listed primitive this wavefront
+// has a share of: workgroup `block` of `blocks`, THREADS threads each; the first `giant_blocks` of
+// them take the list of workgroup-sized rectangles.
+template <u32 THREADS, class F>
+__device__ __forceinline__ void for_each_listed(const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx,
+                                                u32 n, u32 block, u32 blocks, u32 giant_blocks, u32 tid, F &&f)
 {
-    const float m = A * ex * ex + C * ey * ey;
-    const float q = m + 2.0f * B * ex * ey;
-    return q - 4e-6f * m;
-}
-
-__global__ __launch_bounds__(kPreBlock) void emit_tight_kernel(
-    const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect,
-    const float *__restrict__ depth,
-    const u32 *__restrict__ block_sums, const u64 *__restrict__ block_offsets,
-    const u64 *__restrict__ group_totals, u32 n, u32 tiles_x,
-    u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ offsets,
-    ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx, u64 *__restrict__ big_off,
-    u64 *__restrict__ digit_totals, const u32 *__restrict__ tile_masks)
-{
-    __shared__ u64 s_gpart[kPreBlock / kWave];
-    __shared__ u32 s_wave[kPreBlock / kWave];
-
-    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const u32 i = blockIdx.x * kPreBlock + tid;
-    if (emit_prologue(block_sums, block_offsets, group_totals, n, capacity, offsets, header, digit_totals,
-                      s_gpart, tid, lane, wv))
-        return;
-    block_base_start(group_totals, blockIdx.x, s_gpart, tid, lane, wv);     // summed after the barrier below
-    const u32 kept_cnt = i < n ? tiles_touched[i] : 0u;
-    u32 area = 0, mask = 0, dbits = 0;
-    ushort4 r = make_ushort4(0, 0, 0, 0);
-    if (kept_cnt) {
-        r = rect[i];
-        area = ((u32)r.z - (u32)r.x) * ((u32)r.w - (u32)r.y);
-        dbits = __float_as_uint(depth[i]);
-        if (area <= kMaskArea) mask = tile_masks[i];
-    }
-    // prefix sum of the kept counts over the workgroup: where every primitive's pairs start
-    u32 incl = kept_cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const u32 t = __shfl_up(incl, o, 64);
-        if ((int)lane >= o) incl += t;
-    }
-    if (lane == kWave - 1) s_wave[wv] = incl;
-    __syncthreads();
-    u32 wave_base = 0, total = 0;
-#pragma unroll
-    for (u32 k = 0; k < kPreBlock / kWave; ++k) {
-        const u32 w = s_wave[k];
-        if (k < wv) wave_base += w;
-        total += w;
-    }
-    const u32 kept_excl = wave_base + incl - kept_cnt;
-    const u64 base = block_base_finish(block_offsets, blockIdx.x, s_gpart);
-    if (offsets) {
-        if (i < n) offsets[i] = base + kept_excl;
-        if (i == n - 1) offsets[n] = base + total;
-    }
-    append_big(area, kMaskArea, i, base + kept_excl, header, big_idx, big_off, lane, n);
-    // kept tiles in row-major order = set bits in ascending order
-    const u32 w = (u32)r.z - (u32)r.x;
-    const u32 inv_w = w ? (65536u + w - 1u) / w : 0u;      // slot / w == (slot * inv_w) >> 16 for slot < 32, w <= 32
-    u64 pos = base + kept_excl;
-    while (mask) {
-        const u32 slot = (u32)__builtin_ctz(mask);
-        mask &= mask - 1u;
-        const u32 row = (slot * inv_w) >> 16;
-        const u32 tx = (u32)r.x + (slot - row * w), ty = (u32)r.y + row;
-        if (pos < capacity) {
-            keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
-            vals[pos] = i;
+    constexpr u32 kWaves = THREADS / kWave;
+    if (block < giant_blocks) {
+        u32 count = header->giant_count;
+        if (count > n) count = n;                           // cannot happen: one entry per primitive at most
+        for (u32 k = block; k < count; k += giant_blocks) { // uniform
+            const u32 i = big_idx[n - 1u - k];
+            if (i < n) f(i, tid / kWave, kWaves);
         }
-        ++pos;
+    } else {
+        const u32 wave = ((block - giant_blocks) * THREADS + tid) / kWave, waves = (blocks - giant_blocks) * kWaves;
+        u32 count = header->big_count;
+        if (count > n) count = n;
+        for (u32 k = wave; k < count; k += waves) {         // wave-uniform
+            const u32 i = big_idx[k];
+            if (i < n) f(i, 0u, 1u);
+        }
     }
 }
 
-// One wavefront per deferred primitive (persistent grid striding over the list): its rectangle
-// is walked 64 tiles at a time in row-major order; under binning rule 1 (TIGHT) each tile is put
-// through the splat/tile intersection test and the kept ones are compacted with ballot ranks,
-// so the pairs land exactly where the prefix sums say.
 template <bool TIGHT>
-__device__ __forceinline__ void emit_big_part(
-    u32 block, u32 blocks,
-    const ushort4 *__restrict__ rect, const float *__restrict__ depth, const float4 *__restrict__ feat,
-    const ProjParams &pp, u32 tiles_x, u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals,
-    const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx, const u64 *__restrict__ big_off,
-    u32 list_capacity)
+__global__ __launch_bounds__(kLargeThreads) void count_large_kernel(
+    const ushort4 *__restrict__ rect, const float4 *__restrict__ feat, ProjParams pp, u32 n, u32 num_tiles,
+    u32 *__restrict__ large_count, const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx,
+    u32 giant_blocks)
 {
     const u32 lane = threadIdx.x & (kWave - 1);
-    const u32 wave = (block * kPreBlock + threadIdx.x) / kWave, waves = blocks * (kPreBlock / kWave);
-    u32 count = header->big_count;
-    if (count > list_capacity) count = list_capacity;       // cannot happen: one entry per primitive at most
-    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
-    for (u32 k = wave; k < count; k += waves) {
-        const u32 i = big_idx[k];
-        if (i >= list_capacity) continue;                    // an index is a primitive: below n
-        const u64 off = big_off[k];
-        const ushort4 r = rect[i];
-        const u32 dbits = __float_as_uint(depth[i]);
-        const u32 w = (u32)r.z - (u32)r.x, area = w * ((u32)r.w - (u32)r.y);
-        float u = 0.f, v = 0.f, A = 0.f, B = 0.f, Cc = 0.f, rx = 0.f, ry = 0.f, tau = 0.f;
-        if (TIGHT) {
-            const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
-            const float4 f0 = f[0], f1 = f[1];
-            const u32 bits = __float_as_uint(f1.y);
-            const int E = (int)((bits >> 23) & 0xffu) - 127;
-            tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
-            u = f0.x; v = f0.y; A = f0.z; B = f0.w; Cc = f1.x;
-            rx = -f0.w / f0.z; ry = -f0.w / f1.x;
-        }
-        u32 running = 0;
-        for (u32 t0 = 0; t0 < area; t0 += kWave) {           // area > 0 implies w > 0
-            const u32 t = t0 + lane;
-            bool keep = t < area;
-            const u32 row = t / w;
-            const u32 tx = (u32)r.x + (t - row * w), ty = (u32)r.y + row;
-            if (TIGHT && keep) {
-                const float xs = u - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-                const float ys = v - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-                const float ex1 = emit_clampf(xs, -h, h) - xs;
-                const float ey1 = emit_clampf(ys + ry * ex1, -h, h) - ys;
-                const float ey2 = emit_clampf(ys, -h, h) - ys;
-                const float ex2 = emit_clampf(xs + rx * ey2, -h, h) - xs;
-                const float q1 = emit_quad_adj(A, B, Cc, ex1, ey1);
-                const float q2 = emit_quad_adj(A, B, Cc, ex2, ey2);
-                keep = (q1 < q2 ? q1 : q2) <= tau;
-            }
-            const u64 mask = __builtin_amdgcn_ballot_w64(keep);
-            if (keep) {
-                const u64 pos = off + running +
-                                __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
-                if (pos < capacity) {
-                    keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
-                    vals[pos] = i;
-                }
-            }
-            running += (u32)__builtin_popcountll(mask);
-        }
-    }
+    for_each_listed<kLargeThreads>(header, big_idx, n, blockIdx.x, gridDim.x, giant_blocks, threadIdx.x,
+        [&](u32 i, u32 part, u32 parts) {
+            walk_large<TIGHT>(rect[i], feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4), pp, lane, part, parts,
+                [&](u32 tile, u32) -> u64 { if (tile < num_tiles) atomicAdd(&large_count[tile], 1u); return 0ull; },
+                [&](u32, u32, u64) {});
+        });
 }
 
-// The same for the few primitives that cover thousands of tiles: one workgroup each, 256 tiles
-// per round, kept tiles ranked across the workgroup.
-template <bool TIGHT>
-__device__ __forceinline__ void emit_giant_part(
-    u32 block, u32 blocks,
-    const ushort4 *__restrict__ rect, const float *__restrict__ depth, const float4 *__restrict__ feat,
-    const ProjParams &pp, u32 tiles_x, u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals,
-    const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx, const u64 *__restrict__ big_off,
-    u32 list_capacity)
-{
-    __shared__ u32 s_wave[kPreBlock / kWave];
-    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    u32 count = header->giant_count;
-    if (count > list_capacity) count = list_capacity;
-    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
-    for (u32 k = block; k < count; k += blocks) {             // block-uniform
-        const u32 slot = list_capacity - 1 - k;
-        const u32 i = big_idx[slot];
-        if (i >= list_capacity) continue;
-        const u64 off = big_off[slot];
-        const ushort4 r = rect[i];
-        const u32 dbits = __float_as_uint(depth[i]);
-        const u32 w = (u32)r.z - (u32)r.x, area = w * ((u32)r.w - (u32)r.y);
-        float u = 0.f, v = 0.f, A = 0.f, B = 0.f, Cc = 0.f, rx = 0.f, ry = 0.f, tau = 0.f;
-        if (TIGHT) {
-            const float4 *f = feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4);
-            const float4 f0 = f[0], f1 = f[1];
-            const u32 bits = __float_as_uint(f1.y);
-            const int E = (int)((bits >> 23) & 0xffu) - 127;
-            tau = pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
-            u = f0.x; v = f0.y; A = f0.z; B = f0.w; Cc = f1.x;
-            rx = -f0.w / f0.z; ry = -f0.w / f1.x;
-        }
-        u32 running = 0;
-        for (u32 t0 = 0; t0 < area; t0 += kPreBlock) {
-            const u32 t = t0 + tid;
-            bool keep = t < area;
-            const u32 row = t / w;
-            const u32 tx = (u32)r.x + (t - row * w), ty = (u32)r.y + row;
-            if (TIGHT && keep) {
-                const float xs = u - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-                const float ys = v - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-                const float ex1 = emit_clampf(xs, -h, h) - xs;
-                const float ey1 = emit_clampf(ys + ry * ex1, -h, h) - ys;
-                const float ey2 = emit_clampf(ys, -h, h) - ys;
-                const float ex2 = emit_clampf(xs + rx * ey2, -h, h) - xs;
-                const float q1 = emit_quad_adj(A, B, Cc, ex1, ey1);
-                const float q2 = emit_quad_adj(A, B, Cc, ex2, ey2);
-                keep = (q1 < q2 ? q1 : q2) <= tau;
-            }
-            const u64 mask = __builtin_amdgcn_ballot_w64(keep);
-            const u32 rank = __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
-            __syncthreads();                               // s_wave free again
-            if (lane == 0) s_wave[wv] = (u32)__builtin_popcountll(mask);
-            __syncthreads();
-            u32 before = 0, round_total = 0;
-#pragma unroll
-            for (u32 q = 0; q < kPreBlock / kWave; ++q) {
-                const u32 c = s_wave[q];
-                if (q < wv) before += c;
-                round_total += c;
-            }
-            if (keep) {
-                const u64 pos = off + running + before + rank;
-                if (pos < capacity) {
-                    keys[pos] = ((u64)(ty * tiles_x + tx) << 32) | (u64)dbits;
-                    vals[pos] = i;
-                }
-            }
-            running += round_total;
-        }
-    }
-}
-
-// One launch for both: the first kGiantBlocks workgroups take the giants, the rest the big ones.
-constexpr u32 kGiantBlocks = 2048;
-
-template <bool TIGHT>
-__global__ __launch_bounds__(kPreBlock) void emit_deferred_kernel(
-    const ushort4 *__restrict__ rect, const float *__restrict__ depth, const float4 *__restrict__ feat,
-    ProjParams pp, u32 tiles_x, u64 capacity, u64 *__restrict__ keys, u32 *__restrict__ vals,
-    const ScratchHeader *__restrict__ header, const u32 *__restrict__ big_idx, const u64 *__restrict__ big_off,
-    u32 list_capacity)
-{
-    if (blockIdx.x < kGiantBlocks)
-        emit_giant_part<TIGHT>(blockIdx.x, kGiantBlocks, rect, depth, feat, pp, tiles_x, capacity, keys, vals,
-                               header, big_idx, big_off, list_capacity);
-    else
-        emit_big_part<TIGHT>(blockIdx.x - kGiantBlocks, gridDim.x - kGiantBlocks, rect, depth, feat, pp, tiles_x,
-                             capacity, keys, vals, header, big_idx, big_off, list_capacity);
-}
-
-// ---------------------------------------------------------------- radix sort
-// (1) digit counts of every sort tile of this pass -> table[digit][tile]
-// Pairs of a spatially ordered scene arrive in runs of one tile: a wavefront whose 64 keys share a
-// digit adds once instead of queueing 64 atomics on one LDS word.  Called by whole wavefronts.
-__device__ __forceinline__ void wave_hist_add(u32 *hist, u32 d, bool valid, u32 tid)
-{
-    const u64 live = __builtin_amdgcn_ballot_w64(valid);
-    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
-    const u64 same = __builtin_amdgcn_ballot_w64(valid && d == d0);
-    if (live != 0ull && same == live && (live & 1ull)) {
-        if ((tid & (kWave - 1)) == 0) atomicAdd(&hist[d0], (u32)__builtin_popcountll(live));
-    } else if (valid) {
-        atomicAdd(&hist[d], 1u);
-    }
-}
-
-// Each pass also adds its digit totals (the row sums of `table`, which the scan needs as the
-// base of every digit) to `digit_totals`: kept per workgroup in LDS and flushed with one global
-// atomic per non-empty digit when the workgroup is done.  Atomics on one address are served one
-// after the other, and a pass over the high tile bits has only a few digits, so the totals are
-// kept in kTotalCopies copies (workgroup b adds to copy b % kTotalCopies; the scan adds them up).
-template <u32 kSortItems>
-__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(
-    const u64 *__restrict__ keys, const ScratchHeader *__restrict__ header, u64 capacity,
-    u32 shift, u32 bits, u32 *__restrict__ table, u64 table_stride, u64 *__restrict__ digit_totals)
-{
-    constexpr u32 kSortTile = kSortThreads * kSortItems;
-    __shared__ u32 s_hist[kMaxRadix];
-    __shared__ u32 s_tot[kMaxRadix];
-    const u64 D = load_D(header, capacity);
-    const u64 ntiles = (D + kSortTile - 1) / kSortTile;
-    const u32 tid = threadIdx.x;
-    const u32 dmask = (1u << bits) - 1u;
-    for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_tot[d] = 0;    // thread d owns s_tot[d]
-    // a whole tile needs no bounds checks: the body is instantiated twice
-    auto run_tile = [&](u64 tile, auto full_tag) {
-        constexpr bool FULL = decltype(full_tag)::value;
-        for (u32 d = tid; d < kMaxRadix; d += kSortThreads) s_hist[d] = 0;
-        __syncthreads();
-        const u64 t0 = tile * kSortTile;
-        u64 k[kSortItems];
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u64 idx = t0 + (u64)j * kSortThreads + tid;
-            k[j] = (FULL || idx < D) ? keys[idx] : 0ull;
-        }
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u64 idx = t0 + (u64)j * kSortThreads + tid;
-            wave_hist_add(s_hist, (u32)(k[j] >> shift) & dmask, FULL || idx < D, tid);
-        }
-        __syncthreads();
-        for (u32 d = tid; d < kMaxRadix; d += kSortThreads) {
-            const u32 c = s_hist[d];
-            table[(u64)d * table_stride + tile] = c;
-            s_tot[d] += c;
-        }
-        __syncthreads();
-    };
-    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        if ((tile + 1) * kSortTile <= D) run_tile(tile, std::true_type());
-        else run_tile(tile, std::false_type());
-    }
-    u64 *mine = digit_totals + (size_t)(blockIdx.x % kTotalCopies) * kMaxRadix;
-    for (u32 d = tid; d < kMaxRadix; d += kSortThreads) {
-        const u32 c = s_tot[d];
-        if (c) atomicAdd(reinterpret_cast<unsigned long long *>(&mine[d]), (unsigned long long)c);
-    }
-}
-
-// (2) one workgroup per digit: exclusive scan of its row of counts, offset by the total of
-// all smaller digits -> offsets[digit][tile] (u64)
-__global__ __launch_bounds__(kSortThreads) void radix_scan_kernel(
-    const ScratchHeader *__restrict__ header, u64 capacity, const u32 *__restrict__ table,
-    u64 *__restrict__ offsets, u64 table_stride, const u64 *__restrict__ digit_totals, u32 sort_tile)
-{
-    __shared__ u64 s_wave[kSortThreads / kWave];
-    __shared__ u64 s_carry;
-    const u64 D = load_D(header, capacity);
-    const u64 ntiles = (D + sort_tile - 1) / sort_tile;
-    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const u32 digit = blockIdx.x;
-
-    // base = total of the digits below mine
-    u64 part = 0;
-    for (u32 k = tid; k < kTotalCopies * kMaxRadix; k += kSortThreads)
-        if ((k & (kMaxRadix - 1)) < digit) part += digit_totals[k];
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
-    if (lane == 0) s_wave[wv] = part;
-    __syncthreads();
-    if (tid == 0) {
-        u64 b = 0;
-        for (u32 k = 0; k < kSortThreads / kWave; ++k) b += s_wave[k];
-        s_carry = b;
-    }
-    __syncthreads();
-
-    const u32 *row = table + (u64)digit * table_stride;
-    u64 *orow = offsets + (u64)digit * table_stride;
-    // rows of 64 consecutive sort tiles per wavefront, so that loads and stores are whole lines;
-    // a count is at most 4096, so the sums inside one wavefront's rows fit 32 bits
-    constexpr u32 kRows = 8;
-    constexpr u32 kWaves = kSortThreads / kWave;
-    for (u64 base = 0; base < ntiles; base += (u64)kWaves * kRows * kWave) {
-        const u64 first = base + (u64)wv * kRows * kWave + lane;
-        u32 x[kRows], inc[kRows], before[kRows];
-#pragma unroll
-        for (u32 k = 0; k < kRows; ++k) x[k] = first + k * kWave < ntiles ? row[first + k * kWave] : 0u;
-        u32 wave_total = 0;
-#pragma unroll
-        for (u32 k = 0; k < kRows; ++k) {
-            u32 v = x[k];
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const u32 t = __shfl_up(v, o, 64);
-                if ((int)lane >= o) v += t;
-            }
-            inc[k] = v;
-            before[k] = wave_total;
-            wave_total += __shfl(v, kWave - 1, 64);
-        }
-        __syncthreads();                       // s_wave free again
-        if (lane == 0) s_wave[wv] = wave_total;
-        __syncthreads();
-        u64 run = s_carry;
-        for (u32 k = 0; k < wv; ++k) run += s_wave[k];
-#pragma unroll
-        for (u32 k = 0; k < kRows; ++k)
-            if (first + k * kWave < ntiles) orow[first + k * kWave] = run + (before[k] + inc[k] - x[k]);
-        __syncthreads();
-        if (tid == kSortThreads - 1) s_carry = run + wave_total;
-        __syncthreads();
-    }
-}
-
-// (3) stable scatter of one digit
-template <u32 kSortItems>
-__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(
-    const u64 *__restrict__ keys_in, const u32 *__restrict__ vals_in,
-    u64 *__restrict__ keys_out, u32 *__restrict__ vals_out,
-    const ScratchHeader *__restrict__ header, u64 capacity, u32 shift, u32 bits,
-    const u64 *__restrict__ offsets, u64 table_stride)
-{
-    constexpr u32 kSortTile = kSortThreads * kSortItems;
-    constexpr u32 kWaves = kSortThreads / kWave;
-    constexpr u32 kPerWave = kSortItems * kWave;       // consecutive pairs per wavefront
-    __shared__ u32 s_wave_hist[kWaves][kMaxRadix];     // per-wavefront digit counters, then bases
-    __shared__ u32 s_digit_start[kMaxRadix];           // first local position of each digit
-    __shared__ u64 s_gofs[kMaxRadix];                  // global offset minus local start
-    __shared__ u32 s_scan[kWaves];
-    __shared__ u64 s_stage[kSortTile];                 // keys, then (reused) values
-
-    const u64 D = load_D(header, capacity);
-    const u64 ntiles = (D + kSortTile - 1) / kSortTile;
-    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const u64 lane_lt = (1ull << lane) - 1ull;
-    const u32 radix = 1u << bits, dmask = radix - 1u;
-
-    // a whole tile needs none of the bounds checks: the body is instantiated twice
-    auto run_tile = [&](u64 tile, auto full_tag) {
-        constexpr bool FULL = decltype(full_tag)::value;
-        for (u32 k = tid; k < kWaves * kMaxRadix; k += kSortThreads) (&s_wave_hist[0][0])[k] = 0;
-        __syncthreads();
-
-        const u64 t0 = tile * kSortTile + (u64)wv * kPerWave;
-        u64 key[kSortItems];
-        u32 val[kSortItems];
-        u32 rank[kSortItems];
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u64 idx = t0 + (u64)j * kWave + lane;
-            const bool valid = FULL || idx < D;
-            key[j] = valid ? keys_in[idx] : ~0ull;
-            val[j] = valid ? vals_in[idx] : 0u;
-        }
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u64 idx = t0 + (u64)j * kWave + lane;
-            const bool valid = FULL || idx < D;
-            const u32 digit = (u32)(key[j] >> shift) & dmask;
-            // lanes of this wavefront holding the same digit (match-any by ballots): per digit bit,
-            // keep the lanes whose bit equals mine -- with m = 0 / ~0 for my bit 0 / 1 that is
-            // peers & ~(ballot ^ m), on the two 32-bit halves
-            const u64 live = __builtin_amdgcn_ballot_w64(valid);
-            u32 peers_lo = (u32)live, peers_hi = (u32)(live >> 32);
-#pragma unroll
-            for (u32 b = 0; b < kMaxRadixBits; ++b) {
-                if (b < bits) {
-                    const u32 m = 0u - ((digit >> b) & 1u);
-                    const u64 bal = __builtin_amdgcn_ballot_w64(m != 0u);
-                    peers_lo &= ~((u32)bal ^ m);
-                    peers_hi &= ~((u32)(bal >> 32) ^ m);
-                }
-            }
-            const u64 peers = ((u64)peers_hi << 32) | (u64)peers_lo;
-            const u32 before = __popcll(peers & lane_lt);
-            u32 old = 0;
-            if (valid && before == 0)                  // lowest peer lane adds for the group
-                old = atomicAdd(&s_wave_hist[wv][digit], (u32)__popcll(peers));
-            const int leader = valid ? (__ffsll((long long)peers) - 1) : (int)lane;
-            old = __shfl(old, leader, 64);
-            rank[j] = old + before;                    // position among this wavefront's equal digits
-        }
-        __syncthreads();
-
-        // thread t owns kDPT consecutive digits: tile totals, per-wavefront bases, local starts
-        {
-            constexpr u32 kDPT = kMaxRadix / kSortThreads;
-            u32 cnt[kDPT];
-            u32 mine = 0;
-#pragma unroll
-            for (u32 h = 0; h < kDPT; ++h) {
-                const u32 d = kDPT * tid + h;
-                u32 run = 0;
-#pragma unroll
-                for (u32 k = 0; k < kWaves; ++k) {
-                    const u32 c = s_wave_hist[k][d];
-                    s_wave_hist[k][d] = run;
-                    run += c;
-                }
-                cnt[h] = run;
-                mine += run;
-            }
-            u32 incl = mine;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const u32 t = __shfl_up(incl, o, 64);
-                if ((int)lane >= o) incl += t;
-            }
-            if (lane == kWave - 1) s_scan[wv] = incl;
-            __syncthreads();
-            u32 start = incl - mine;
-#pragma unroll
-            for (u32 k = 0; k < kWaves; ++k) if (k < wv) start += s_scan[k];
-#pragma unroll
-            for (u32 h = 0; h < kDPT; ++h) {
-                const u32 d = kDPT * tid + h;
-                s_digit_start[d] = start;
-                if (d < radix) s_gofs[d] = offsets[(u64)d * table_stride + tile] - (u64)start;
-                start += cnt[h];
-            }
-        }
-        __syncthreads();
-
-        // sort the tile by digit in LDS: keys first, then the values through the same slots
-        const u64 tile_base = tile * kSortTile;
-        const u32 count = (u32)((D - tile_base) < (u64)kSortTile ? (D - tile_base) : (u64)kSortTile);
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u64 idx = t0 + (u64)j * kWave + lane;
-            if (FULL || idx < D) {
-                const u32 digit = (u32)(key[j] >> shift) & dmask;
-                rank[j] = s_digit_start[digit] + s_wave_hist[wv][digit] + rank[j];
-                s_stage[rank[j]] = key[j];
-            }
-        }
-        __syncthreads();
-        u32 dg[kSortItems];                            // digit of the key that ended up in slot p
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u32 p = j * kSortThreads + tid;
-            if (FULL || p < count) {
-                const u64 k = s_stage[p];
-                dg[j] = (u32)(k >> shift) & dmask;
-                keys_out[s_gofs[dg[j]] + p] = k;
-            }
-        }
-        __syncthreads();
-        u32 *s_vals = reinterpret_cast<u32 *>(s_stage);
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u64 idx = t0 + (u64)j * kWave + lane;
-            if (FULL || idx < D) s_vals[rank[j]] = val[j];
-        }
-        __syncthreads();
-#pragma unroll
-        for (u32 j = 0; j < kSortItems; ++j) {
-            const u32 p = j * kSortThreads + tid;
-            if (FULL || p < count) vals_out[s_gofs[dg[j]] + p] = s_vals[p];
-        }
-        __syncthreads();
-    };
-    for (u64 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        if ((tile + 1) * kSortTile <= D) run_tile(tile, std::true_type());
-        else run_tile(tile, std::false_type());
-    }
-}
-
-// ---------------------------------------------------------------- ranges
-__global__ __launch_bounds__(256) void tile_ranges_kernel(
-    const u64 *__restrict__ keys, ScratchHeader *__restrict__ header, u64 capacity,
-    u32 num_tiles, u64 *__restrict__ tile_offsets, u64 *__restrict__ offsets_if_empty)
-{
-    // the emit stage's list of deferred primitives has been consumed: empty it for the next call
-    if (blockIdx.x == 0 && threadIdx.x == 0) { header->big_count = 0; header->giant_count = 0; }
-    // with no primitives the emit kernel never runs: the one-entry prefix sum is written here
-    if (offsets_if_empty && blockIdx.x == 0 && threadIdx.x == 0) offsets_if_empty[0] = 0;
-    const u64 D = load_D(header, capacity);
-    const u64 stride = (u64)gridDim.x * blockDim.x;
-    const u64 first = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-    if (D == 0) {
-        for (u64 t = first; t <= num_tiles; t += stride) tile_offsets[t] = 0;
-        return;
-    }
-    for (u64 i = first; i < D; i += stride) {
-        u64 t = keys[i] >> 32;
-        if (t > num_tiles) t = num_tiles;
-        u64 tp;     // tiles in (tp, t] start at i
-        if (i == 0) {
-            for (u64 k = 0; k <= t; ++k) tile_offsets[k] = 0;
-        } else {
-            tp = keys[i - 1] >> 32;
-            if (tp > num_tiles) tp = num_tiles;
-            for (u64 k = tp + 1; k <= t; ++k) tile_offsets[k] = i;
-        }
-        if (i == D - 1)
-            for (u64 k = t + 1; k <= num_tiles; ++k) tile_offsets[k] = D;
-    }
-}
-
-// ---------------------------------------------------------------- order + size classes
-// Tile ids by descending list length, bucketed by the bit length of (length - 1), so that
+// ---------------------------------------------------------------- scan + order + size classes
+// One workgroup.  (1) D = sum of the per-tile counts; more than the buffers hold: status, and every
+// list is treated as empty from here on.  (2) tile_offsets = exclusive prefix sum of the counts.
+// (3) Tile ids by descending list length, bucketed by the bit length of (length - 1), so that
 // the size classes of the per-tile sort are whole buckets.  From the front of `order`:
 //   classes[0]  lists longer than kHuge pairs          one workgroup each, merges between the pair buffers
 //   classes[3]  kMid + 1 .. kHuge ("long")             cut into chunks of kMid pairs, see below
@@ -781,16 +371,18 @@ __global__ __launch_bounds__(256) void tile_ranges_kernel(
 // starts first, never a result.  A long list is sorted as 2 .. 4 chunks by workgroups of the
 // 512-thread kernel and merged in two rounds by workgroups of the next two kernels, so that it
 // costs no kernel of its own: chunk_list = (tile, chunk) of every such chunk, classes[4] = how many.
-// One workgroup.
+// (4) The counters are left zero for the next call.
+// A single workgroup's time is memory round trips, not data: with SMALL (up to 8192 tiles) every
+// thread reads its eight counters once and everything else works from registers and LDS.
 constexpr u32 kSmallThreads = 64, kSmallItems = 8, kSmallCap = kSmallThreads * kSmallItems;   // 512
 constexpr u32 kLowThreads = 256, kLowItems = 8;                                               // 2048
 constexpr u32 kMidThreads = 512, kMidItems = 8, kMid = kMidThreads * kMidItems;               // 4096
 constexpr u32 kHugeThreads = 1024, kHugeItems = 16, kHuge = kHugeThreads * kHugeItems;        // 16384
 static_assert(kMid == kChunk, "the launch bounds on the host use kChunk");
 
-__device__ __forceinline__ u32 length_bucket(u64 len)
+__device__ __forceinline__ u32 length_bucket(u32 len)
 {
-    return len > 1 ? 64u - (u32)__builtin_clzll(len - 1) : 0u;   // len in (2^(b-1), 2^b]
+    return len > 1u ? 32u - (u32)__builtin_clz(len - 1u) : 0u;   // len in (2^(b-1), 2^b]
 }
 constexpr u32 kSmallBucket = 9, kLowBucket = 11, kMidBucket = 12, kHugeBucket = 14;   // 2^9 = kSmallCap, 2^11 = kLow, 2^12 = kMid, 2^14 = kHuge
 
@@ -798,37 +390,137 @@ constexpr u32 kSmallBucket = 9, kLowBucket = 11, kMidBucket = 12, kHugeBucket = 
 // the other: every bucket has kOrderCopies counters, picked by the low lane bits, so that the 64
 // atomics of a wavefront spread over that many words.  An exclusive scan over
 // [bucket][copy] turns the counts into the first slot of every (bucket, copy).
-constexpr u32 kOrderCopies = 16, kOrderCounters = 65 * kOrderCopies, kOrderBatch = 8, kOrderStage = 32768;
+constexpr u32 kScanThreads = 1024, kScanItems = 8;
+constexpr u32 kOrderCopies = 16, kOrderBuckets = 33, kOrderCounters = kOrderBuckets * kOrderCopies;
+constexpr u32 kOrderStage = 32768;
+static_assert(kOrderCounters <= 2 * kScanThreads, "the counters are scanned two per thread");
+static_assert(kLdsTilesSmall == kScanThreads * kScanItems, "SMALL: one round of kScanItems tiles per thread");
 
-__global__ __launch_bounds__(1024) void tile_order_kernel(
-    const u64 *__restrict__ tile_offsets, u32 num_tiles, u32 *__restrict__ order,
-    u32 *__restrict__ order_copy, u32 *__restrict__ classes, uint2 *__restrict__ chunk_list, u64 chunk_capacity)
+template <bool SMALL>
+__global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(
+    u32 *__restrict__ tile_count, u32 *__restrict__ large_count, u32 num_tiles, u64 capacity, ScratchHeader *__restrict__ header,
+    u64 *__restrict__ tile_offsets, u32 *__restrict__ tile_cursor, u64 *__restrict__ prim_offsets_if_empty,
+    u32 *__restrict__ order, u32 *__restrict__ order_copy, u32 *__restrict__ classes,
+    uint2 *__restrict__ chunk_list, u64 chunk_capacity)
 {
+    constexpr u32 kWaves = kScanThreads / kWave;
+    // the running positions of the emit kernel are 32 bits wide: absolute where every position
+    // fits (they start at the tile's range start), else relative to the range start
+    const bool wide = capacity > 0xffffffffull;
+    __shared__ u64 s_sum[kWaves];
     __shared__ u32 s_cnt[kOrderCounters];
     __shared__ u32 s_long[2];                  // first long tile in `order`, number of long tiles
-    __shared__ u32 s_wave[1024 / kWave];
+    __shared__ u32 s_wave[kWaves];
     // slots are scattered and one compute unit does all the address work: the order is put
     // together in LDS and written out in whole lines (images of up to kOrderStage tiles)
-    __shared__ u32 s_order[kOrderStage];
-    const bool staged = num_tiles <= kOrderStage;
+    __shared__ u32 s_order[SMALL ? kLdsTilesSmall : kOrderStage];
+    __shared__ u32 s_len[SMALL ? kLdsTilesSmall : 1];      // SMALL: the list lengths, for the chunk list
+    const bool staged = SMALL || num_tiles <= kOrderStage;
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const u32 copy = tid & (kOrderCopies - 1);
-    for (u32 k = tid; k < kOrderCounters; k += 1024) s_cnt[k] = 0;
-    __syncthreads();
-    // kOrderBatch tiles per thread and round: all their loads are in flight together
-    for (u32 base = 0; base < num_tiles; base += kOrderBatch * 1024) {
-        u32 b[kOrderBatch];
+
+    // ---- (1) D
+    // a tile's list = the runs of the counting workgroups (tile_count) followed by the pairs of
+    // the listed primitives (large_count)
+    u32 mine8[kScanItems], runs8[kScanItems];  // SMALL: list length and length of the runs of tiles tid * kScanItems + j
+    u64 part = 0;
+    if (SMALL) {
 #pragma unroll
-        for (u32 j = 0; j < kOrderBatch; ++j) {
-            const u32 t = base + j * 1024 + tid;
-            b[j] = t < num_tiles ? length_bucket(tile_offsets[t + 1] - tile_offsets[t]) : 0xffu;
+        for (u32 j = 0; j < kScanItems; ++j) {
+            const u32 t = tid * kScanItems + j;
+            runs8[j] = t < num_tiles ? tile_count[t] : 0u;
+            mine8[j] = runs8[j] + (t < num_tiles ? large_count[t] : 0u);
+            part += mine8[j];
         }
+    } else {
+        for (u32 t = tid; t < num_tiles; t += kScanThreads) part += (u64)tile_count[t] + large_count[t];
+    }
 #pragma unroll
-        for (u32 j = 0; j < kOrderBatch; ++j)
-            if (b[j] != 0xffu) atomicAdd(&s_cnt[(64 - b[j]) * kOrderCopies + copy], 1u);     // long lists first
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
+    if (lane == 0) s_sum[wv] = part;
+    __syncthreads();
+    u64 D = 0;
+#pragma unroll
+    for (u32 k = 0; k < kWaves; ++k) D += s_sum[k];
+    const bool overflow = D > capacity;
+    if (tid == 0) {
+        header->dup_count = D;
+        if (overflow) header->status = LMK_GS_ERR_CAPACITY;
+        // with no primitives nothing else writes the one-entry prefix sum over the primitives
+        if (prim_offsets_if_empty) prim_offsets_if_empty[0] = 0;
+    }
+    if (SMALL) {
+#pragma unroll
+        for (u32 j = 0; j < kScanItems; ++j) {
+            if (overflow) { mine8[j] = 0u; runs8[j] = 0u; }
+            s_len[tid * kScanItems + j] = mine8[j];
+        }
+    }
+    __syncthreads();                           // s_sum is reused below
+
+    // ---- (2) per-tile ranges: kScanItems consecutive tiles per thread, entry num_tiles = the end
+    u64 carry = 0;
+    for (u32 base = 0; base <= num_tiles; base += kScanThreads * kScanItems) {
+        const u32 t0 = base + tid * kScanItems;
+        u32 c[kScanItems], runs[kScanItems];
+        u64 mine = 0;
+#pragma unroll
+        for (u32 j = 0; j < kScanItems; ++j) {
+            if (SMALL) {
+                c[j] = base == 0u ? mine8[j] : 0u;
+                runs[j] = base == 0u ? runs8[j] : 0u;
+            } else {
+                const bool in = !overflow && t0 + j < num_tiles;
+                runs[j] = in ? tile_count[t0 + j] : 0u;
+                c[j] = runs[j] + (in ? large_count[t0 + j] : 0u);
+            }
+            mine += c[j];
+        }
+        u64 incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const u64 v = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += v;
+        }
+        if (lane == kWave - 1) s_sum[wv] = incl;
+        __syncthreads();
+        u64 before = carry, total = carry;
+#pragma unroll
+        for (u32 k = 0; k < kWaves; ++k) {
+            const u64 v = s_sum[k];
+            if (k < wv) before += v;
+            total += v;
+        }
+        u64 run = before + incl - mine;
+#pragma unroll
+        for (u32 j = 0; j < kScanItems; ++j) {
+            if (t0 + j <= num_tiles) {
+                tile_offsets[t0 + j] = run;
+                tile_cursor[t0 + j] = (wide ? 0u : (u32)run) + runs[j];   // the listed primitives' pairs follow the runs
+            }
+            run += c[j];
+        }
+        carry = total;
+        __syncthreads();                       // s_sum free again
+    }
+
+    // ---- (3) order and size classes.  Tile of (thread, round j): SMALL tid * kScanItems + j, else
+    // base + j * kScanThreads + tid.
+    const u32 copy = tid & (kOrderCopies - 1);
+    for (u32 k = tid; k < kOrderCounters; k += kScanThreads) s_cnt[k] = 0;
+    __syncthreads();
+    const u32 sweep = SMALL ? 1u : kScanThreads * kScanItems;
+    for (u32 base = 0; base < (SMALL ? 1u : num_tiles); base += sweep) {
+#pragma unroll
+        for (u32 j = 0; j < kScanItems; ++j) {
+            const u32 t = SMALL ? tid * kScanItems + j : base + j * kScanThreads + tid;
+            if (t < num_tiles) {
+                const u32 b = length_bucket(SMALL ? mine8[j] : (overflow ? 0u : tile_count[t] + large_count[t]));
+                atomicAdd(&s_cnt[(32 - b) * kOrderCopies + copy], 1u);      // long lists first
+            }
+        }
     }
     __syncthreads();
-    // exclusive scan of the counters, two per thread (kOrderCounters <= 2048)
+    // exclusive scan of the counters, two per thread
     const u32 k0 = 2 * tid, k1 = 2 * tid + 1;
     const u32 c0 = k0 < kOrderCounters ? s_cnt[k0] : 0u, c1 = k1 < kOrderCounters ? s_cnt[k1] : 0u;
     u32 incl = c0 + c1;
@@ -847,26 +539,21 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
     __syncthreads();
     if (tid == 0) {
         // tiles in buckets above a class limit = first slot of the first bucket at or below it
-        const u32 huge = s_cnt[(64 - kHugeBucket) * kOrderCopies];
-        const u32 lng = s_cnt[(64 - kMidBucket) * kOrderCopies];
-        const u32 mid = s_cnt[(64 - kLowBucket) * kOrderCopies];
-        const u32 low = s_cnt[(64 - kSmallBucket) * kOrderCopies];
+        const u32 huge = s_cnt[(32 - kHugeBucket) * kOrderCopies];
+        const u32 lng = s_cnt[(32 - kMidBucket) * kOrderCopies];
+        const u32 mid = s_cnt[(32 - kLowBucket) * kOrderCopies];
+        const u32 low = s_cnt[(32 - kSmallBucket) * kOrderCopies];
         classes[0] = huge; classes[3] = lng - huge; classes[1] = mid - lng; classes[2] = low - mid;
         s_long[0] = huge; s_long[1] = lng - huge;
     }
     __syncthreads();
-    for (u32 base = 0; base < num_tiles; base += kOrderBatch * 1024) {
-        u32 b[kOrderBatch];
+    for (u32 base = 0; base < (SMALL ? 1u : num_tiles); base += sweep) {
 #pragma unroll
-        for (u32 j = 0; j < kOrderBatch; ++j) {
-            const u32 t = base + j * 1024 + tid;
-            b[j] = t < num_tiles ? length_bucket(tile_offsets[t + 1] - tile_offsets[t]) : 0xffu;
-        }
-#pragma unroll
-        for (u32 j = 0; j < kOrderBatch; ++j) {
-            if (b[j] == 0xffu) continue;
-            const u32 t = base + j * 1024 + tid;
-            const u32 slot = atomicAdd(&s_cnt[(64 - b[j]) * kOrderCopies + copy], 1u);
+        for (u32 j = 0; j < kScanItems; ++j) {
+            const u32 t = SMALL ? tid * kScanItems + j : base + j * kScanThreads + tid;
+            if (t >= num_tiles) continue;
+            const u32 b = length_bucket(SMALL ? mine8[j] : (overflow ? 0u : tile_count[t] + large_count[t]));
+            const u32 slot = atomicAdd(&s_cnt[(32 - b) * kOrderCopies + copy], 1u);
             if (staged) {
                 s_order[slot] = t;
             } else {
@@ -877,7 +564,7 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
     }
     if (staged) {
         __syncthreads();
-        for (u32 k = tid; k < num_tiles; k += 1024) {
+        for (u32 k = tid; k < num_tiles; k += kScanThreads) {
             const u32 t = s_order[k];
             order[k] = t;
             if (order_copy) order_copy[k] = t;
@@ -888,35 +575,154 @@ __global__ __launch_bounds__(1024) void tile_order_kernel(
     }
     // the chunks of the long lists: an exclusive scan of their chunk counts places the entries
     const u32 long_first = s_long[0], long_count = s_long[1];
-    u32 carry = 0;
-    for (u32 base = 0; base < long_count; base += 1024) {
+    u32 chunk_carry = 0;
+    for (u32 base = 0; base < long_count; base += kScanThreads) {
         const u32 k = base + tid;
         u32 tile = 0, nch = 0;
         if (k < long_count) {
             tile = staged ? s_order[long_first + k] : order[long_first + k];
-            nch = (u32)((tile_offsets[tile + 1] - tile_offsets[tile] + kMid - 1) / kMid);
+            if (tile < num_tiles) nch = ((SMALL ? s_len[tile] : tile_count[tile] + large_count[tile]) + kMid - 1) / kMid;
         }
-        u32 incl = nch;
+        u32 inc = nch;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
-            const u32 v = __shfl_up(incl, o, 64);
-            if ((int)lane >= o) incl += v;
+            const u32 v = __shfl_up(inc, o, 64);
+            if ((int)lane >= o) inc += v;
         }
         __syncthreads();                       // s_wave free again
-        if (lane == kWave - 1) s_wave[wv] = incl;
+        if (lane == kWave - 1) s_wave[wv] = inc;
         __syncthreads();
-        u32 before = carry, total = carry;
-        for (u32 w = 0; w < 1024 / kWave; ++w) {
+        u32 bef = chunk_carry, total = chunk_carry;
+        for (u32 w = 0; w < kWaves; ++w) {
             const u32 c = s_wave[w];
-            if (w < wv) before += c;
+            if (w < wv) bef += c;
             total += c;
         }
-        const u32 at = before + incl - nch;
+        const u32 at = bef + inc - nch;
         for (u32 c = 0; c < nch; ++c)
             if ((u64)at + c < chunk_capacity) chunk_list[at + c] = make_uint2(tile, c);
-        carry = total;
+        chunk_carry = total;
     }
-    if (tid == 0) classes[4] = (u64)carry < chunk_capacity ? carry : (u32)chunk_capacity;
+    if (tid == 0) classes[4] = (u64)chunk_carry < chunk_capacity ? chunk_carry : (u32)chunk_capacity;
+
+    // ---- (4) every read of the counters is done: leave them zero
+    __syncthreads();
+    for (u32 t = tid; t <= num_tiles; t += kScanThreads) { tile_count[t] = 0; large_count[t] = 0; }
+}
+
+// ---------------------------------------------------------------- emit
+// Workgroups [0, bin_blocks) repeat the walk of the small rectangles of their 1024 primitives; the
+// LDS counters now start at the tile's range start + the workgroup's run start and hand out
+// positions.  The workgroups behind them walk the listed primitives and advance the tiles'
+// running positions pair by pair.
+// WIDE: positions need 64 bits (capacity of 2^32 pairs or more): LDS counters and running
+// positions are then relative to the tile's range start, which is read from memory for every pair.
+template <u32 LDS_TILES, bool TIGHT, bool WIDE>
+__global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void emit_kernel(
+    const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect, const float *__restrict__ depth,
+    const float4 *__restrict__ feat, const u32 *__restrict__ tile_masks, u32 n, ProjParams pp, u32 num_tiles,
+    const u64 *__restrict__ tile_offsets, u32 *__restrict__ tile_cursor, const ScratchHeader *__restrict__ header,
+    const u32 *__restrict__ big_idx, const u64 *__restrict__ block_offsets, const u64 *__restrict__ group_totals,
+    const u32 *__restrict__ bin_count, const uint2 *__restrict__ list, u64 list_capacity,
+    u32 bin_blocks, u32 giant_blocks, u64 capacity, u64 *__restrict__ keys)
+{
+    constexpr bool LDS = LDS_TILES > 0;
+    constexpr u32 kThreads = BinShape<LDS_TILES>::kThreads, kPer = BinShape<LDS_TILES>::kPer;
+    constexpr u32 kWaves = BinShape<LDS_TILES>::kWaves;
+    __shared__ u32 s_cur[LDS ? LDS_TILES : 1];
+    __shared__ u64 s_part[kWaves];
+    if (header->status != LMK_GS_OK) return;                // more pairs than the buffers hold: nothing is emitted
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    if (blockIdx.x >= bin_blocks) {
+        for_each_listed<kThreads>(header, big_idx, n, blockIdx.x - bin_blocks, gridDim.x - bin_blocks, giant_blocks, tid,
+            [&](u32 i, u32 part, u32 parts) {
+                const u64 comp = ((u64)__float_as_uint(depth[i]) << 32) | (u64)i;
+                walk_large<TIGHT>(rect[i], feat + (size_t)i * (LMK_GS_FEAT_STRIDE / 4), pp, lane, part, parts,
+                    [&](u32 tile, u32) -> u64 {
+                        if (tile >= num_tiles) return ~0ull;
+                        const u32 at = atomicAdd(&tile_cursor[tile], 1u);
+                        return WIDE ? tile_offsets[tile] + at : (u64)at;
+                    },
+                    [&](u32, u32, u64 pos) { if (pos < capacity) keys[pos] = comp; });
+            });
+        return;
+    }
+    if (!LDS) return;                                       // every primitive is on a list
+    const u32 entries = bin_count[blockIdx.x];
+    if (entries == 0u) return;                              // the same for the whole workgroup
+    list_first_start<kThreads>(group_totals, blockIdx.x, s_part, tid, lane, wv);
+    // this thread's primitives: requested now, used after the counters are set up
+    u32 cnt[kPer], mask[kPer], dbits[kPer];
+    ushort4 r[kPer];
+#pragma unroll
+    for (u32 j = 0; j < kPer; ++j) {
+        const u32 i = blockIdx.x * kBinBlock + j * kThreads + tid;
+        cnt[j] = i < n ? tiles_touched[i] : 0u;
+        r[j] = i < n ? rect[i] : make_ushort4(0, 0, 0, 0);
+        mask[j] = (TIGHT && i < n) ? tile_masks[i] : 0u;
+        dbits[j] = i < n ? __float_as_uint(depth[i]) : 0u;
+    }
+    __syncthreads();
+    const u64 first = list_first_finish<kWaves>(block_offsets, blockIdx.x, s_part);
+    for (u32 k = tid; k < entries; k += kThreads) {
+        if (first + k >= list_capacity) break;
+        const uint2 e = list[first + k];
+        if (e.x < num_tiles) s_cur[e.x] = WIDE ? e.y : (u32)tile_offsets[e.x] + e.y;
+    }
+    __syncthreads();
+#pragma unroll
+    for (u32 j = 0; j < kPer; ++j) {
+        const u32 area = cnt[j] ? ((u32)r[j].z - (u32)r[j].x) * ((u32)r[j].w - (u32)r[j].y) : 0u;
+        if (area == 0u || area > kMaskArea) continue;
+        const u64 comp = ((u64)dbits[j] << 32) | (u64)(blockIdx.x * kBinBlock + j * kThreads + tid);
+        walk_small<TIGHT>(r[j], area, mask[j], pp.tiles_x, [&](u32 tile) {
+            if (tile >= num_tiles) return;
+            const u32 at = atomicAdd(&s_cur[tile], 1u);
+            const u64 pos = WIDE ? tile_offsets[tile] + at : (u64)at;
+            if (pos < capacity) keys[pos] = comp;
+        });
+    }
+}
+
+// ---------------------------------------------------------------- prefix sum over the primitives
+// lmk_gs_projected.offsets (optional output): exclusive prefix sum of tiles_touched -- the scan
+// inside every group of 256 primitives on top of the two-level prefix sum over the groups that the
+// projection stage left.  Nothing else in this stage depends on it.
+__global__ __launch_bounds__(kPreBlock) void prim_offsets_kernel(
+    const u32 *__restrict__ tiles_touched, u32 n, const u64 *__restrict__ block_offsets,
+    const u64 *__restrict__ group_totals, u64 *__restrict__ offsets)
+{
+    __shared__ u64 s_gpart[kPreBlock / kWave];
+    __shared__ u32 s_wave[kPreBlock / kWave];
+    const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const u32 i = blockIdx.x * kPreBlock + tid;
+    // totals of the groups before this workgroup's own
+    const u32 groups_before = blockIdx.x / kScanGroup;
+    u64 part = 0;
+    for (u32 g = tid; g < groups_before; g += kPreBlock) part += group_totals[g];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_down(part, o, 64);
+    if (lane == 0) s_gpart[wv] = part;
+    const u32 cnt = i < n ? tiles_touched[i] : 0u;
+    u32 incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const u32 t = __shfl_up(incl, o, 64);
+        if ((int)lane >= o) incl += t;
+    }
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    u64 base = block_offsets[blockIdx.x];
+    u32 wave_base = 0, total = 0;
+#pragma unroll
+    for (u32 k = 0; k < kPreBlock / kWave; ++k) {
+        base += s_gpart[k];
+        const u32 w = s_wave[k];
+        if (k < wv) wave_base += w;
+        total += w;
+    }
+    if (i < n) offsets[i] = base + wave_base + incl - cnt;
+    if (i == n - 1) offsets[n] = base + total;
 }
 
 // ---------------------------------------------------------------- per-tile sort
@@ -1012,6 +818,9 @@ __device__ __forceinline__ void ts_clean(u64 (&e)[ITEMS])
     }
 }
 
+// On entry keys[beg .. beg + n) holds what the emit kernel wrote: depth bits << 32 | primitive index,
+// the composite the list is ordered by.  On return keys/vals (or keys_out/vals_out) hold the
+// sorted pairs in their final form, key = tile << 32 | depth bits, value = primitive index.
 template <u32 THREADS, u32 ITEMS>
 __device__ __forceinline__ void sort_pairs_in_lds(u64 *keys, u32 *vals, u64 beg, u32 n, u32 tile, u64 *s,
                                                   u64 *keys_out = nullptr, u32 *vals_out = nullptr)
@@ -1023,11 +832,11 @@ __device__ __forceinline__ void sort_pairs_in_lds(u64 *keys, u32 *vals, u64 beg,
     const u32 m = (n + ITEMS - 1) / ITEMS * ITEMS;          // elements in play: n rounded up to whole runs
     const u32 o0 = tid * ITEMS;
     const bool active = o0 < m;
-    // each thread's ITEMS consecutive pairs as composites; beyond n the maximum value, which sorts to the end
+    // each thread's ITEMS consecutive composites; beyond n the maximum value, which sorts to the end
     u64 e[ITEMS];
 #pragma unroll
     for (u32 k = 0; k < ITEMS; ++k)
-        e[k] = o0 + k < n ? ((keys[beg + o0 + k] << 32) | (u64)vals[beg + o0 + k]) : ~0ull;
+        e[k] = o0 + k < n ? keys[beg + o0 + k] : ~0ull;
     // sort the run in registers (bitonic network)
 #pragma unroll
     for (u32 k = 2; k <= ITEMS; k <<= 1) {
@@ -1185,7 +994,7 @@ __global__ __launch_bounds__(kMidThreads) void tile_sort_mid_kernel(
         const u64 c0 = (u64)c.y * kMid;
         if (c0 >= len) return;                              // cannot happen with a consistent table
         const u32 n = (u32)(len - c0 < (u64)kMid ? len - c0 : (u64)kMid);
-        if (n >= 2) sort_pairs_in_lds<kMidThreads, kMidItems>(keys, vals, beg + c0, n, c.x, s);
+        sort_pairs_in_lds<kMidThreads, kMidItems>(keys, vals, beg + c0, n, c.x, s);     // n >= 1
         return;
     }
     const u32 k = blockIdx.x - chunks;
@@ -1235,7 +1044,7 @@ __global__ __launch_bounds__(kLowThreads) void tile_sort_low_kernel(
     sort_pairs_in_lds<kLowThreads, kLowItems>(keys, vals, beg, (u32)len, tile, s);
 }
 
-// Short lists (2 .. 512 pairs): one wavefront each, walking `order` from its short end.  Before
+// Short lists (1 .. 512 pairs): one wavefront each, walking `order` from its short end.  Before
 // them the second and last merge round of the long lists (runs of 2 * kMid pairs, alternate
 // buffers -> pair buffers; a list of one such run is copied), kSmallCap outputs per segment.
 __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
@@ -1264,7 +1073,14 @@ __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
     if (tile >= num_tiles) return;
     const u64 beg = tile_offsets[tile];
     const u64 len = tile_offsets[tile + 1] - beg;
-    if (len < 2 || len > (u64)kSmallCap) return;
+    if (len < 1 || len > (u64)kSmallCap) return;
+    if (len == 1) {                                         // nothing to sort: only the pair's form changes
+        if (threadIdx.x == 0) {
+            const u64 c = keys[beg];
+            keys[beg] = ((u64)tile << 32) | (c >> 32); vals[beg] = (u32)c;
+        }
+        return;
+    }
     // fewer elements per lane for shorter lists: all 64 lanes work in every merge round
     if (len <= 2u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 2u>(keys, vals, beg, (u32)len, tile, s);
     else if (len <= 4u * kSmallThreads) sort_pairs_in_lds<kSmallThreads, 4u>(keys, vals, beg, (u32)len, tile, s);
@@ -1280,10 +1096,12 @@ __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
 __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
     u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ keys_alt, u32 *__restrict__ vals_alt,
     const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, const u32 *__restrict__ classes,
-    u32 num_tiles)
+    u32 num_tiles, ScratchHeader *__restrict__ header)
 {
     __shared__ u64 s[kHuge + kHuge / 16];
     __shared__ u64 s_split[kHugeThreads / kWave][2];
+    // the emit kernel has consumed the deferred list: empty it for the next call
+    if (blockIdx.x == 0 && threadIdx.x == 0) { header->big_count = 0; header->giant_count = 0; }
     if (blockIdx.x >= classes[0] || blockIdx.x >= num_tiles) return;
     const u32 tile = order[blockIdx.x];
     if (tile >= num_tiles) return;
@@ -1303,7 +1121,10 @@ __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
     for (u64 c0 = 0; c0 < L; c0 += kHuge) {
         const u32 n = (u32)(L - c0 < (u64)kHuge ? L - c0 : (u64)kHuge);
         if (n >= 2) sort_pairs_in_lds<kHugeThreads, kHugeItems>(keys, vals, beg + c0, n, tile, s, k0, v0);
-        else if (start_alt && tid == 0) { k0[beg + c0] = keys[beg + c0]; v0[beg + c0] = vals[beg + c0]; }
+        else if (tid == 0) {                                 // a chunk of one pair: only its form changes
+            const u64 c = keys[beg + c0];
+            k0[beg + c0] = ((u64)tile << 32) | (c >> 32); v0[beg + c0] = (u32)c;
+        }
     }
     // the chunk sorts of this workgroup wrote the runs the merges read
     __threadfence_block();
@@ -1371,100 +1192,93 @@ __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
 }
 
 // ---------------------------------------------------------------- launcher
-static inline u32 grid_for(u64 work_items, u32 cap)
-{
-    if (work_items < 1) work_items = 1;
-    return (u32)(work_items < (u64)cap ? work_items : (u64)cap);
-}
-
 hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams &pp, const lmk_gs_binned &out,
                            char *scratch, const ScratchLayout &L, hipStream_t stream)
 {
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
-    const u32 *block_sums = reinterpret_cast<const u32 *>(scratch + L.block_sums);
-    u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
+    const u32 num_tiles = pp.tiles_x * pp.tiles_y;
+    u32 *tile_count = reinterpret_cast<u32 *>(scratch + L.tile_count);
+    u32 *large_count = tile_count + (num_tiles + 1);
+    const u64 *block_offsets = reinterpret_cast<const u64 *>(scratch + L.block_offsets);
     const u64 *group_totals = reinterpret_cast<const u64 *>(scratch + L.group_totals);
-    u64 *digit_totals = reinterpret_cast<u64 *>(scratch + L.digit_totals);
-    u32 *table = reinterpret_cast<u32 *>(scratch + L.table);
-    u64 *offsets = reinterpret_cast<u64 *>(scratch + L.offsets);
+    const u32 *tile_masks = reinterpret_cast<const u32 *>(scratch + L.tile_masks);
+    u32 *bin_count = reinterpret_cast<u32 *>(scratch + L.bin_count);
+    u32 *tile_cursor = reinterpret_cast<u32 *>(scratch + L.tile_cursor);
+    u32 *big_idx = reinterpret_cast<u32 *>(scratch + L.big_idx);
     u32 *order = reinterpret_cast<u32 *>(scratch + L.order);
     u32 *classes = reinterpret_cast<u32 *>(scratch + L.classes);
-    u32 *big_idx = reinterpret_cast<u32 *>(scratch + L.big_idx);
-    u64 *big_off = reinterpret_cast<u64 *>(scratch + L.big_off);
-    const u32 num_tiles = pp.tiles_x * pp.tiles_y;
-    const SortPlan plan = sort_plan(num_tiles);
+    uint2 *chunk_list = reinterpret_cast<uint2 *>(scratch + L.chunk_list);
+    const ushort4 *rect = reinterpret_cast<const ushort4 *>(proj.rect);
+    const float4 *feat = reinterpret_cast<const float4 *>(proj.feat);
+    // the (tile, start) lists of the counting workgroups live in the alternate key buffer, which
+    // nothing else uses before the merge rounds of the per-tile sort; a list has at most one entry
+    // per pair of its workgroup and starts at the number of pairs before the workgroup
+    uint2 *list = reinterpret_cast<uint2 *>(out.keys_alt);
+    const bool tight = pp.cam.binning == 1u;
+    const bool wide = out.capacity > 0xffffffffull;
+    const u32 lds_tiles = num_tiles <= kLdsTilesSmall ? kLdsTilesSmall : (num_tiles <= kLdsTilesLarge ? kLdsTilesLarge : 0u);
+    const u32 bin_threads = lds_tiles == kLdsTilesSmall ? BinShape<kLdsTilesSmall>::kThreads : kBinBlock;
+    // the listed primitives are walked by fixed grids striding over the two lists: as workgroups of
+    // kLargeThreads threads in the counting pass, as workgroups of the emit kernel behind its own
+    const u32 large_blocks = 4u * L.bin_blocks < kLargeBlocks ? 4u * L.bin_blocks : kLargeBlocks;
+    const u32 giant_blocks = L.bin_blocks < kGiantBlocks ? L.bin_blocks : kGiantBlocks;
+    const u32 large_blocks_emit = (large_blocks * kLargeThreads + bin_threads - 1) / bin_threads;
+    hipError_t e;
 
-    // ping-pong so that the last pass lands in keys/vals
-    u64 *kin = (plan.passes & 1u) ? out.keys_alt : out.keys;
-    u32 *vin = (plan.passes & 1u) ? out.vals_alt : out.vals;
-    u64 *kout = (plan.passes & 1u) ? out.keys : out.keys_alt;
-    u32 *vout = (plan.passes & 1u) ? out.vals : out.vals_alt;
-
-    if (L.pre_blocks > 0) {
-        // the deferred primitives are expanded by a fixed grid of wavefronts striding over the list
-        const u32 big_grid = kGiantBlocks + (L.pre_blocks < 2048u ? L.pre_blocks : 2048u);
-        if (pp.cam.binning == 1u) {
-            hipLaunchKernelGGL(emit_tight_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
-                               proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               block_sums, block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
-                               big_idx, big_off, digit_totals, reinterpret_cast<const u32 *>(scratch + L.tile_masks));
-            hipLaunchKernelGGL(emit_deferred_kernel<true>, dim3(big_grid), dim3(kPreBlock), 0, stream,
-                               reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               reinterpret_cast<const float4 *>(proj.feat), pp, pp.tiles_x, out.capacity,
-                               kin, vin, header, big_idx, big_off, n);
-        } else {
-            hipLaunchKernelGGL(emit_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
-                               proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               block_sums, block_offsets, group_totals, n, pp.tiles_x, out.capacity, kin, vin, proj.offsets, header,
-                               big_idx, big_off, digit_totals);
-            hipLaunchKernelGGL(emit_deferred_kernel<false>, dim3(big_grid), dim3(kPreBlock), 0, stream,
-                               reinterpret_cast<const ushort4 *>(proj.rect), proj.depth,
-                               reinterpret_cast<const float4 *>(proj.feat), pp, pp.tiles_x, out.capacity,
-                               kin, vin, header, big_idx, big_off, n);
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    // enough resident workgroups to fill 256 CUs several times over; each loops over sort tiles
-    const u32 grid = grid_for(L.sort_tiles, 256u * 16u);
-    const bool many = sort_items(out.capacity) == kSortItemsMany;
-    for (u32 p = 0; p < plan.passes; ++p) {
-        u64 *totals = digit_totals + (size_t)p * kTotalCopies * kMaxRadix;
-        if (many)
-            hipLaunchKernelGGL(radix_hist_kernel<kSortItemsMany>, dim3(grid), dim3(kSortThreads), 0, stream,
-                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles, totals);
+    if (L.bin_blocks > 0) {
+        auto count = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, dim3(L.bin_blocks), dim3(bin_threads), 0, stream,
+                               proj.tiles_touched, rect, tile_masks, n, pp.tiles_x, num_tiles, tile_count, header, big_idx,
+                               block_offsets, group_totals, bin_count, list, out.capacity);
+        };
+        if (lds_tiles == kLdsTilesSmall) { if (tight) count(count_kernel<kLdsTilesSmall, true>); else count(count_kernel<kLdsTilesSmall, false>); }
+        else if (lds_tiles == kLdsTilesLarge) { if (tight) count(count_kernel<kLdsTilesLarge, true>); else count(count_kernel<kLdsTilesLarge, false>); }
+        else { if (tight) count(count_kernel<0u, true>); else count(count_kernel<0u, false>); }
+        if (tight)
+            hipLaunchKernelGGL(count_large_kernel<true>, dim3(giant_blocks + large_blocks), dim3(kLargeThreads), 0, stream,
+                               rect, feat, pp, n, num_tiles, large_count, header, big_idx, giant_blocks);
         else
-            hipLaunchKernelGGL(radix_hist_kernel<kSortItemsFew>, dim3(grid), dim3(kSortThreads), 0, stream,
-                               kin, header, out.capacity, plan.shift[p], plan.bits[p], table, L.sort_tiles, totals);
-        hipLaunchKernelGGL(radix_scan_kernel, dim3(1u << plan.bits[p]), dim3(kSortThreads), 0, stream,
-                           header, out.capacity, table, offsets, L.sort_tiles, totals, sort_tile_pairs(out.capacity));
-        if (many)
-            hipLaunchKernelGGL(radix_scatter_kernel<kSortItemsMany>, dim3(grid), dim3(kSortThreads), 0, stream,
-                               kin, vin, kout, vout, header, out.capacity, plan.shift[p], plan.bits[p],
-                               offsets, L.sort_tiles);
-        else
-            hipLaunchKernelGGL(radix_scatter_kernel<kSortItemsFew>, dim3(grid), dim3(kSortThreads), 0, stream,
-                               kin, vin, kout, vout, header, out.capacity, plan.shift[p], plan.bits[p],
-                               offsets, L.sort_tiles);
+            hipLaunchKernelGGL(count_large_kernel<false>, dim3(giant_blocks + large_blocks), dim3(kLargeThreads), 0, stream,
+                               rect, feat, pp, n, num_tiles, large_count, header, big_idx, giant_blocks);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        u64 *tk = kin; kin = kout; kout = tk;
-        u32 *tv = vin; vin = vout; vout = tv;
     }
-    // after the last swap `kin` is the partitioned buffer == out.keys
-    const u32 rgrid = grid_for((out.capacity + 255) / 256, 256u * 16u);
-    hipLaunchKernelGGL(tile_ranges_kernel, dim3(rgrid), dim3(256), 0, stream,
-                       out.keys, header, out.capacity, num_tiles, out.tile_offsets,
-                       n == 0 ? proj.offsets : nullptr);
-    uint2 *chunk_list = reinterpret_cast<uint2 *>(scratch + L.chunk_list);
-    hipLaunchKernelGGL(tile_order_kernel, dim3(1), dim3(1024), 0, stream,
-                       out.tile_offsets, num_tiles, order, out.tile_order, classes, chunk_list,
-                       out.capacity / 2048 + 2);
+    if (num_tiles <= kLdsTilesSmall)
+        hipLaunchKernelGGL(tile_scan_kernel<true>, dim3(1), dim3(kScanThreads), 0, stream,
+                           tile_count, large_count, num_tiles, out.capacity, header, out.tile_offsets, tile_cursor,
+                           n == 0 ? proj.offsets : nullptr, order, out.tile_order, classes, chunk_list,
+                           out.capacity / 2048 + 2);
+    else
+        hipLaunchKernelGGL(tile_scan_kernel<false>, dim3(1), dim3(kScanThreads), 0, stream,
+                           tile_count, large_count, num_tiles, out.capacity, header, out.tile_offsets, tile_cursor,
+                           n == 0 ? proj.offsets : nullptr, order, out.tile_order, classes, chunk_list,
+                           out.capacity / 2048 + 2);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (L.bin_blocks > 0) {
+        auto emit = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, dim3(L.bin_blocks + giant_blocks + large_blocks_emit), dim3(bin_threads), 0, stream,
+                               proj.tiles_touched, rect, proj.depth, feat, tile_masks, n, pp, num_tiles,
+                               out.tile_offsets, tile_cursor, header, big_idx, block_offsets, group_totals,
+                               bin_count, list, out.capacity, L.bin_blocks, giant_blocks, out.capacity, out.keys);
+        };
+        auto emit_for = [&](auto lds_tag) {
+            constexpr u32 LT = decltype(lds_tag)::value;
+            if (tight) { if (wide) emit(emit_kernel<LT, true, true>); else emit(emit_kernel<LT, true, false>); }
+            else { if (wide) emit(emit_kernel<LT, false, true>); else emit(emit_kernel<LT, false, false>); }
+        };
+        if (lds_tiles == kLdsTilesSmall) emit_for(std::integral_constant<u32, kLdsTilesSmall>());
+        else if (lds_tiles == kLdsTilesLarge) emit_for(std::integral_constant<u32, kLdsTilesLarge>());
+        else emit_for(std::integral_constant<u32, 0u>());
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (proj.offsets) {
+            hipLaunchKernelGGL(prim_offsets_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                               proj.tiles_touched, n, block_offsets, group_totals, proj.offsets);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
     // The lists beyond kHuge pairs first (few workgroups that run long), then by falling length.
     // The grids are upper bounds from the capacity, surplus workgroups leave at once: a list of
     // the class above kHuge / kLow / kSmallCap pairs, and likewise every chunk of a long list,
@@ -1475,7 +1289,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     const u32 max_low = at_most(out.capacity / (kSmallCap + 1) + 1, num_tiles);
     const u32 merge1 = at_most(2ull * max_mid, kMergeBlocks1), merge2 = at_most(8ull * max_mid, kMergeBlocks2);
     hipLaunchKernelGGL(tile_sort_huge_kernel, dim3(max_huge), dim3(kHugeThreads), 0, stream,
-                       out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes, num_tiles);
+                       out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes, num_tiles, header);
     hipLaunchKernelGGL(tile_sort_mid_kernel, dim3(max_mid), dim3(kMidThreads), 0, stream,
                        out.keys, out.vals, out.tile_offsets, order, classes, chunk_list, num_tiles);
     hipLaunchKernelGGL(tile_sort_low_kernel, dim3(merge1 + max_low), dim3(kLowThreads), 0, stream,

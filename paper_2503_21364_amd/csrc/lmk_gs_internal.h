@@ -13,50 +13,46 @@ typedef uint64_t u64;
 typedef uint32_t u32;
 
 constexpr u32 kWave = 64;               // CDNA wavefront width
-constexpr u32 kPreBlock = LMK_GS_PRE_BLOCK;   // primitives per preprocess / emit workgroup
-constexpr u32 kSortThreads = 256;       // radix sort workgroup
-// Keys per thread of the partition kernels, so 2048 or 4096 pairs per sort tile.  With few sort
-// tiles a pass is bound by the latency of one workgroup and smaller tiles spread better over
-// the chip; with very many it is bound by HBM and the longer runs of a larger tile fill the
-// lines they write.  The host picks from the capacity, which it knows (D it does not).
-constexpr u32 kSortItemsFew = 8, kSortItemsMany = 16;
-constexpr u64 kManyPairs = 64ull << 20;
-inline u32 sort_items(u64 capacity) { return capacity > kManyPairs ? kSortItemsMany : kSortItemsFew; }
-inline u32 sort_tile_pairs(u64 capacity) { return kSortThreads * sort_items(capacity); }
-constexpr u32 kMaxRadixBits = 8;         // digits are at most 8 bits wide, chosen per frame
-constexpr u32 kMaxRadix = 1u << kMaxRadixBits;
-constexpr u32 kMaxPasses = 8;
+constexpr u32 kPreBlock = LMK_GS_PRE_BLOCK;   // primitives per preprocess workgroup
+constexpr u32 kBinBlock = 1024;         // primitives per workgroup of the counting and emit kernels of stage 2
 constexpr u32 kScanGroup = 256;         // preprocess workgroups per group of the two-level prefix sum
-constexpr u32 kTotalCopies = 4;         // copies of each pass's digit totals, to spread the atomics
+static_assert(kScanGroup % (kBinBlock / kPreBlock) == 0, "the blocks of one counting workgroup lie in one group");
+// The counting and emit kernels keep one counter per tile in LDS: up to 8192 tiles (1080p has
+// 8160) in 32 KB, up to 32768 (2160p has 32400) in 128 KB.  Larger images take the route of the
+// large rectangles for every primitive: one global atomic per pair.
+constexpr u32 kLdsTilesSmall = 8192, kLdsTilesLarge = 32768;
+constexpr u32 kChunk = 4096;            // pairs sorted in LDS by one workgroup of the per-tile sort
 
 // Header at the start of the scratch buffer.
 struct ScratchHeader {
-    u64 dup_count;      // D = sum of tiles_touched
+    u64 dup_count;      // D = pairs of the frame = sum of tiles_touched (known when lmk_gs_preprocess is done)
     int32_t status;     // sticky LMK_GS_* code set by kernels
     int32_t pad;
-    u32 big_count;      // emit stage: deferred primitives expanded one wavefront each (front of the list)
-    u32 giant_count;    // ... and one workgroup each (back of the list)
+    u32 big_count;      // stage 2: primitives on the deferred list, from the front (one wavefront each)
+    u32 giant_count;    // ... and from the back (one workgroup each)
+    u32 pad2[2];
 };
 
-// Carving of the caller's scratch buffer (all offsets multiples of 256 bytes).
+// Carving of the caller's scratch buffer (all offsets multiples of 256 bytes).  The part up to
+// `bin_count` is what lmk_gs_preprocess touches; it depends on n and the image size only.
 struct ScratchLayout {
     size_t header;        // ScratchHeader
-    size_t block_sums;    // u32 [pre_blocks]      tile counts per preprocess workgroup
+    size_t tile_count;    // u32 [2][tiles + 1]  pairs per tile in the counting workgroups' runs / of the listed primitives:
+                          //                     zero between frames, accumulated by the counting kernels
+    size_t block_sums;    // u32 [pre_blocks]      tile counts per preprocess workgroup (256 primitives)
     size_t block_offsets; // u64 [pre_blocks + 1]  their exclusive prefix sum within groups of kScanGroup
     size_t group_totals;  // u64 [groups]          total of each group
-    size_t voxel_flags;   // u8  [n]               voxel filter: 1 = the voxel may reach the image (at most n voxels)
-    size_t tile_masks;    // u32 [n]               binning rule 1: kept tiles of rectangles of up to 32 tiles
-    size_t digit_totals;  // u64 [kMaxPasses][kTotalCopies][kMaxRadix] digit totals of each pass
-    size_t table;         // u32 [512][sort_tiles] per-(digit, sort tile) counts of the running pass
-    size_t offsets;       // u64 [512][sort_tiles] their output offsets
+    size_t voxel_flags;   // u8  [n]           voxel filter: 1 = the voxel may reach the image (at most n voxels)
+    size_t tile_masks;    // u32 [n]           binning rule 1: kept tiles of rectangles of up to 32 tiles
+    size_t bin_count;     // u32 [bin_blocks]  entries in each counting workgroup's list of (tile, start of its run)
+    size_t tile_cursor;   // u32 [tiles + 1] running position of the listed primitives' pairs inside every tile's slice
+    size_t big_idx;       // u32 [n]         deferred list: primitives whose rectangles are walked by wavefronts of their own
     size_t order;         // u32 [tiles]     tile ids by descending list length
-    size_t classes;       // u32 [8]         tiles per size class of the per-tile sort (see tile_order_kernel)
+    size_t classes;       // u32 [8]         tiles per size class of the per-tile sort (see tile_scan_kernel)
     size_t chunk_list;    // uint2 [capacity / 2048 + 2]  (tile, chunk) of every chunk of the lists sorted in chunks
-    size_t big_idx;       // u32 [n]         primitives whose rectangles are expanded one wavefront each
-    size_t big_off;       // u64 [n]         and where their pairs start
     size_t total;
-    u32 pre_blocks;
-    u64 sort_tiles;       // ceil(capacity / sort_tile_pairs(capacity))
+    u32 pre_blocks;       // ceil(n / kPreBlock)
+    u32 bin_blocks;       // ceil(n / kBinBlock)
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -65,52 +61,23 @@ inline ScratchLayout scratch_layout(u32 n, u64 capacity, u32 tiles)
 {
     ScratchLayout L;
     L.pre_blocks = (n + kPreBlock - 1) / kPreBlock;
-    L.sort_tiles = (capacity + sort_tile_pairs(capacity) - 1) / sort_tile_pairs(capacity);
-    if (L.sort_tiles == 0) L.sort_tiles = 1;
+    L.bin_blocks = (n + kBinBlock - 1) / kBinBlock;
     size_t o = 0;
     L.header = o;        o += align256(sizeof(ScratchHeader));
+    L.tile_count = o;    o += align256(sizeof(u32) * 2 * ((size_t)tiles + 1));
     L.block_sums = o;    o += align256(sizeof(u32) * (size_t)(L.pre_blocks + 1));
     L.block_offsets = o; o += align256(sizeof(u64) * ((size_t)L.pre_blocks + 1));
     L.group_totals = o;  o += align256(sizeof(u64) * ((size_t)L.pre_blocks / kScanGroup + 2));
     L.voxel_flags = o;   o += align256((size_t)n + 1);
     L.tile_masks = o;    o += align256(sizeof(u32) * ((size_t)n + 1));
-    L.digit_totals = o;  o += align256(sizeof(u64) * kMaxPasses * kTotalCopies * kMaxRadix);
-    L.table = o;         o += align256(sizeof(u32) * kMaxRadix * (size_t)L.sort_tiles);
-    L.offsets = o;       o += align256(sizeof(u64) * kMaxRadix * (size_t)L.sort_tiles);
+    L.bin_count = o;     o += align256(sizeof(u32) * ((size_t)L.bin_blocks + 1));
+    L.tile_cursor = o;   o += align256(sizeof(u32) * ((size_t)tiles + 1));
+    L.big_idx = o;       o += align256(sizeof(u32) * ((size_t)n + 1));
     L.order = o;         o += align256(sizeof(u32) * (size_t)(tiles + 1));
     L.classes = o;       o += align256(sizeof(u32) * 8);
     L.chunk_list = o;    o += align256(sizeof(u32) * 2 * (size_t)(capacity / 2048 + 2));
-    L.big_idx = o;       o += align256(sizeof(u32) * ((size_t)n + 1));
-    L.big_off = o;       o += align256(sizeof(u64) * ((size_t)n + 1));
     L.total = o;
     return L;
-}
-
-// The pairs are first partitioned by tile id with a stable LSD radix sort over the tile bits
-// only (digits of at most 8 bits: 7 + 6 at 1080p, 8 + 7 at 2160p, one pass at 256 x 256),
-// then every tile's list is sorted by (depth, index) on its own.
-constexpr u32 kChunk = 4096;             // pairs sorted in LDS by one workgroup
-
-struct SortPlan {
-    u32 passes;
-    u32 shift[kMaxPasses];
-    u32 bits[kMaxPasses];
-};
-
-inline SortPlan sort_plan(u32 tiles)
-{
-    u32 tile_bits = 0;
-    while ((1ull << tile_bits) < (u64)tiles) ++tile_bits;
-    SortPlan P;
-    P.passes = (tile_bits + kMaxRadixBits - 1) / kMaxRadixBits;
-    const u32 base = P.passes ? tile_bits / P.passes : 0, extra = P.passes ? tile_bits % P.passes : 0;
-    u32 at = 32;
-    for (u32 p = 0; p < kMaxPasses; ++p) {
-        P.shift[p] = at;
-        P.bits[p] = p < P.passes ? base + (p < extra ? 1u : 0u) : 0u;
-        at += P.bits[p];
-    }
-    return P;
 }
 
 // Camera-derived kernel arguments (host-computed, passed by value).

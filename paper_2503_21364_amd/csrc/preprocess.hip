@@ -1,7 +1,6 @@
 // Stage 1: per-primitive projection, culling, support rectangle and SH colour
 // (Sec. 2.2 Eq. 8, the EWA projection and SH colour of Sec. 2.2; the
-// per-primitive kernel named in Sec. 4.2.1), plus the prefix sum over
-// workgroup tile counts that fixes the pair count D.
+// per-primitive kernel named in Sec. 4.2.1).
 //
 // This translation unit is compiled with -ffp-contract=off and correctly
 // rounded fp32 divide/sqrt: everything that decides an integer (depth bits,
@@ -13,6 +12,7 @@
 // bytes a visible primitive needs) are read only by lanes that survive the
 // culls.
 #include "lmk_gs_internal.h"
+#include "tile_test.h"
 
 #include <cmath>
 
@@ -39,60 +39,6 @@ static ShConsts make_sh_consts()
 __device__ __forceinline__ float clamp_nan_lo(float v, float lo, float hi)
 {
     return !(v > lo) ? lo : (v > hi ? hi : v);
-}
-
-// ---- binning rule 1: can the splat reach alpha >= 1/255 on the square spanned by a tile's
-// pixel centres?  q(d) = d^T conic d is convex: its minimum over the square is at the splat
-// centre if inside, else on an edge facing it (clamp one coordinate, minimise along that line).
-// Contributing needs q <= 2 ln(255 o); tau bounds that from above from the exponent and the top
-// three mantissa bits of o (table from the host), so no run-time logarithm decides an integer.
-// Same fp32 operation sequence as the CPU definition of the rule; see include/lmk_gs.h.
-struct TileTest { float u, v, A, B, C, rx, ry, tau; };
-
-__device__ __forceinline__ float opacity_tau(const ProjParams &pp, float o)
-{
-    const u32 bits = __float_as_uint(o);
-    const int E = (int)((bits >> 23) & 0xffu) - 127;
-    return pp.tau_tab[(bits >> 20) & 7u] + (float)E * 1.3862944f;
-}
-
-__device__ __forceinline__ TileTest make_tile_test(float u, float v, float A, float B, float C, float tau)
-{
-    TileTest t;
-    t.u = u; t.v = v; t.A = A; t.B = B; t.C = C; t.tau = tau;
-    t.rx = -B / A; t.ry = -B / C;
-    return t;
-}
-
-__device__ __forceinline__ float clampf3(float v, float lo, float hi) { return v < lo ? lo : (v > hi ? hi : v); }
-
-__device__ __forceinline__ float quad_adj(const TileTest &t, float ex, float ey)
-{
-    const float m = t.A * ex * ex + t.C * ey * ey;
-    const float q = m + 2.0f * t.B * ex * ey;
-    return q - 4e-6f * m;
-}
-
-__device__ __forceinline__ bool tile_kept(const TileTest &t, u32 tx, u32 ty)
-{
-    const float h = 0.5f * (float)LMK_GS_TILE - 0.5f;
-    const float xs = t.u - ((float)(tx * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-    const float ys = t.v - ((float)(ty * LMK_GS_TILE) + 0.5f * (float)LMK_GS_TILE);
-    const float ex1 = clampf3(xs, -h, h) - xs;
-    const float ey1 = clampf3(ys + t.ry * ex1, -h, h) - ys;
-    const float ey2 = clampf3(ys, -h, h) - ys;
-    const float ex2 = clampf3(xs + t.rx * ey2, -h, h) - xs;
-    const float q1 = quad_adj(t, ex1, ey1);
-    const float q2 = quad_adj(t, ex2, ey2);
-    const float qmin = q1 < q2 ? q1 : q2;
-    return qmin <= t.tau;
-}
-
-__device__ __forceinline__ u32 wave_sum(u32 v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-    return v;   // valid in lane 0
 }
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -199,13 +145,44 @@ hipError_t launch_build_cov3d(const lmk_gs_gaussians &g, float *cov3d, hipStream
     return hipGetLastError();
 }
 
-__device__ __forceinline__ void reset_header(ScratchHeader *header)
+// A new frame starts from a clean header and zeroed per-tile pair counters (stage 2 accumulates
+// into them with atomics, and leaves them zero again).  Called by every thread of a grid of
+// `threads` threads, `g` = global thread id.
+__device__ __forceinline__ void reset_frame_state(ScratchHeader *header, u32 *__restrict__ tile_count,
+                                                  u32 num_tiles, u32 g, u32 threads)
 {
-    header->dup_count = 0;
-    header->status = LMK_GS_OK;
-    header->pad = 0;
-    header->big_count = 0;
-    header->giant_count = 0;
+    if (g == 0) {
+        header->dup_count = 0;
+        header->status = LMK_GS_OK;
+        header->pad = 0;
+        header->big_count = 0;
+        header->giant_count = 0;
+        header->pad2[0] = header->pad2[1] = 0;
+    }
+    for (u32 t = g; t < 2u * (num_tiles + 1u); t += threads) tile_count[t] = 0;    // both halves: runs, listed primitives
+}
+
+// an empty scene: no projection kernel runs, the frame state is reset by this one
+__global__ __launch_bounds__(256) void reset_frame_kernel(ScratchHeader *header, u32 *tile_count, u32 num_tiles)
+{
+    reset_frame_state(header, tile_count, num_tiles, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
+}
+
+// tile count of a workgroup of kPreBlock primitives (input of the prefix sum that fixes D and
+// gives stage 2 a place for each workgroup's list); called by the whole workgroup
+__device__ __forceinline__ void block_total(u32 cnt, u32 *s_part, u32 *__restrict__ block_sums)
+{
+    u32 v = cnt;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 t = 0;
+#pragma unroll
+        for (u32 k = 0; k < kPreBlock / kWave; ++k) t += s_part[k];
+        block_sums[blockIdx.x] = t;
+    }
 }
 
 template <u32 DEG>
@@ -214,14 +191,14 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
     const float *__restrict__ opacity, const float *__restrict__ sh, const float *__restrict__ cov3d, u32 n,
     ProjParams pp, ShConsts kc,
     float *__restrict__ depth, u32 *__restrict__ tiles_touched, ushort4 *__restrict__ rect,
-    float4 *__restrict__ feat, u32 *__restrict__ block_sums, u32 *__restrict__ tile_masks,
+    float4 *__restrict__ feat, u32 *__restrict__ tile_masks,
     const unsigned char *__restrict__ voxel_flags, const uint2 *__restrict__ block_range, u32 num_voxels,
-    unsigned char *__restrict__ block_visible, ScratchHeader *__restrict__ header)
+    unsigned char *__restrict__ block_visible, ScratchHeader *__restrict__ header,
+    u32 *__restrict__ tile_count, u32 num_tiles, u32 *__restrict__ block_sums)
 {
     __shared__ u32 s_part[kPreBlock / kWave];
     const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
-    // a new frame: D is accumulated by the scan that follows this kernel, the rest starts clean
-    if (blockIdx.x == 0 && threadIdx.x == 0) reset_header(header);
+    reset_frame_state(header, tile_count, num_tiles, i, gridDim.x * kPreBlock);
     if (voxel_flags) {
         // voxel filter: does any voxel holding one of this workgroup's primitives pass?
         const uint2 r = block_range[blockIdx.x];
@@ -469,17 +446,7 @@ __global__ __launch_bounds__(kPreBlock) void preprocess_kernel(
         // rectangles of up to 32 tiles: the emit stage expands the kept tiles from this mask
         if (pp.cam.binning == 1u && cnt) tile_masks[i] = kept_mask;
     }
-
-    // tile count of this workgroup (input of the prefix sum that places its pairs)
-    const u32 ws = wave_sum(cnt);
-    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = ws;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        u32 t = 0;
-#pragma unroll
-        for (u32 k = 0; k < kPreBlock / kWave; ++k) t += s_part[k];
-        block_sums[blockIdx.x] = t;
-    }
+    block_total(cnt, s_part, block_sums);
 }
 
 // Exclusive prefix sum (u64) over the workgroup tile counts, in two levels: each workgroup of
@@ -495,10 +462,6 @@ __global__ __launch_bounds__(kScanGroup) void scan_block_sums_kernel(
     constexpr u32 kWaves = kScanGroup / kWave;
     __shared__ u64 s_wave[kWaves];
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    if (nb == 0) {                             // no preprocess kernel ran: an empty frame
-        if (blockIdx.x == 0 && tid == 0) reset_header(header);
-        return;
-    }
     const u32 b = blockIdx.x * kScanGroup + tid;
     const u32 x = b < nb ? block_sums[b] : 0u;
     u64 incl = x;
@@ -523,70 +486,80 @@ __global__ __launch_bounds__(kScanGroup) void scan_block_sums_kernel(
     }
 }
 
+static hipError_t launch_scan_block_sums(char *scratch, const ScratchLayout &L, hipStream_t stream)
+{
+    hipLaunchKernelGGL(scan_block_sums_kernel, dim3((L.pre_blocks + kScanGroup - 1) / kScanGroup), dim3(kScanGroup), 0, stream,
+                       reinterpret_cast<const u32 *>(scratch + L.block_sums), L.pre_blocks,
+                       reinterpret_cast<u64 *>(scratch + L.block_offsets),
+                       reinterpret_cast<u64 *>(scratch + L.group_totals),
+                       reinterpret_cast<ScratchHeader *>(scratch + L.header));
+    return hipGetLastError();
+}
+
 hipError_t launch_preprocess(const lmk_gs_gaussians &g, const lmk_gs_voxel_index *index, uint8_t *block_visible,
                              const ProjParams &pp, const lmk_gs_projected &out,
                              char *scratch, const ScratchLayout &L, hipStream_t stream)
 {
     static const ShConsts kc = make_sh_consts();
-    u32 *block_sums = reinterpret_cast<u32 *>(scratch + L.block_sums);
-    u64 *block_offsets = reinterpret_cast<u64 *>(scratch + L.block_offsets);
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
-    if (L.pre_blocks > 0) {
-        const unsigned char *vflags = nullptr;
-        const uint2 *ranges = nullptr;
-        u32 num_voxels = 0;
-        if (index) {
-            num_voxels = index->num_voxels;
-            ranges = reinterpret_cast<const uint2 *>(index->block_range);
-            if (index->visible) {
-                vflags = index->visible;                // this frame's flags, computed by the caller's earlier call
-            } else {
-                unsigned char *f = reinterpret_cast<unsigned char *>(scratch + L.voxel_flags);
-                hipLaunchKernelGGL(voxel_flags_kernel, dim3((num_voxels + 255) / 256), dim3(256), 0, stream,
-                                   reinterpret_cast<const float4 *>(index->box), num_voxels, pp, f);
-                hipError_t e = hipGetLastError();
-                if (e != hipSuccess) return e;
-                vflags = f;
-            }
-        }
-        auto launch = [&](auto kernel) {
-            hipLaunchKernelGGL(kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
-                               g.mean, g.scale, g.rot, g.opacity, g.sh, g.cov3d, g.n, pp, kc,
-                               out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
-                               reinterpret_cast<float4 *>(out.feat), block_sums,
-                               reinterpret_cast<u32 *>(scratch + L.tile_masks),
-                               vflags, ranges, num_voxels, index ? block_visible : nullptr, header);
-        };
-        switch (g.sh_degree) {
-            case 0: launch(preprocess_kernel<0>); break;
-            case 1: launch(preprocess_kernel<1>); break;
-            case 2: launch(preprocess_kernel<2>); break;
-            default: launch(preprocess_kernel<3>); break;
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+    u32 *tile_count = reinterpret_cast<u32 *>(scratch + L.tile_count);
+    u32 *block_sums = reinterpret_cast<u32 *>(scratch + L.block_sums);
+    const u32 num_tiles = pp.tiles_x * pp.tiles_y;
+    if (L.pre_blocks == 0) {
+        hipLaunchKernelGGL(reset_frame_kernel, dim3(16), dim3(256), 0, stream, header, tile_count, num_tiles);
+        return hipGetLastError();
     }
-    const u32 groups = L.pre_blocks ? (L.pre_blocks + kScanGroup - 1) / kScanGroup : 1u;
-    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(groups), dim3(kScanGroup), 0, stream,
-                       block_sums, L.pre_blocks, block_offsets,
-                       reinterpret_cast<u64 *>(scratch + L.group_totals), header);
-    return hipGetLastError();
+    const unsigned char *vflags = nullptr;
+    const uint2 *ranges = nullptr;
+    u32 num_voxels = 0;
+    if (index) {
+        num_voxels = index->num_voxels;
+        ranges = reinterpret_cast<const uint2 *>(index->block_range);
+        if (index->visible) {
+            vflags = index->visible;                // this frame's flags, computed by the caller's earlier call
+        } else {
+            unsigned char *f = reinterpret_cast<unsigned char *>(scratch + L.voxel_flags);
+            hipLaunchKernelGGL(voxel_flags_kernel, dim3((num_voxels + 255) / 256), dim3(256), 0, stream,
+                               reinterpret_cast<const float4 *>(index->box), num_voxels, pp, f);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            vflags = f;
+        }
+    }
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                           g.mean, g.scale, g.rot, g.opacity, g.sh, g.cov3d, g.n, pp, kc,
+                           out.depth, out.tiles_touched, reinterpret_cast<ushort4 *>(out.rect),
+                           reinterpret_cast<float4 *>(out.feat),
+                           reinterpret_cast<u32 *>(scratch + L.tile_masks),
+                           vflags, ranges, num_voxels, index ? block_visible : nullptr, header,
+                           tile_count, num_tiles, block_sums);
+    };
+    switch (g.sh_degree) {
+        case 0: launch(preprocess_kernel<0>); break;
+        case 1: launch(preprocess_kernel<1>); break;
+        case 2: launch(preprocess_kernel<2>); break;
+        default: launch(preprocess_kernel<3>); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_scan_block_sums(scratch, L, stream);
 }
 
 // ---------------------------------------------------------------- hand-over rebuilt from the outputs
-// What lmk_gs_preprocess leaves in the scratch for lmk_gs_bin_sort -- the tile count of every
-// workgroup of 256 primitives and, under binning rule 1, the mask of kept tiles of every rectangle
-// of up to 32 tiles -- recomputed from the per-primitive outputs alone (tiles_touched, rect and the
+// What lmk_gs_preprocess leaves in the scratch for lmk_gs_bin_sort -- the pair count, zeroed
+// per-tile counters, the prefix sum over the workgroup tile counts and, under binning rule 1, the
+// mask of kept tiles of every rectangle of up to 32 tiles -- recomputed from the per-primitive outputs alone (tiles_touched, rect and the
 // feature record), with the arithmetic of preprocess_kernel, so that a caller holding only those
 // outputs can run stage 2 on a scratch buffer of its own.
 __global__ __launch_bounds__(kPreBlock) void rebuild_handover_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect, const float4 *__restrict__ feat,
-    u32 n, ProjParams pp, u32 *__restrict__ block_sums, u32 *__restrict__ tile_masks,
-    ScratchHeader *__restrict__ header)
+    u32 n, ProjParams pp, u32 *__restrict__ tile_masks, ScratchHeader *__restrict__ header,
+    u32 *__restrict__ tile_count, u32 num_tiles, u32 *__restrict__ block_sums)
 {
     __shared__ u32 s_part[kPreBlock / kWave];
     const u32 i = blockIdx.x * kPreBlock + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x == 0) reset_header(header);
+    reset_frame_state(header, tile_count, num_tiles, i, gridDim.x * kPreBlock);
     const u32 cnt = i < n ? tiles_touched[i] : 0u;
     if (pp.cam.binning == 1u && cnt) {
         const ushort4 r = rect[i];
@@ -602,35 +575,27 @@ __global__ __launch_bounds__(kPreBlock) void rebuild_handover_kernel(
             tile_masks[i] = mask;
         }
     }
-    const u32 ws = wave_sum(cnt);
-    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = ws;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        u32 t = 0;
-#pragma unroll
-        for (u32 k = 0; k < kPreBlock / kWave; ++k) t += s_part[k];
-        block_sums[blockIdx.x] = t;
-    }
+    block_total(cnt, s_part, block_sums);
 }
 
 hipError_t launch_rebuild_handover(const lmk_gs_projected &proj, u32 n, const ProjParams &pp,
                                    char *scratch, const ScratchLayout &L, hipStream_t stream)
 {
-    u32 *block_sums = reinterpret_cast<u32 *>(scratch + L.block_sums);
     ScratchHeader *header = reinterpret_cast<ScratchHeader *>(scratch + L.header);
-    if (L.pre_blocks > 0) {
-        hipLaunchKernelGGL(rebuild_handover_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
-                           proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect),
-                           reinterpret_cast<const float4 *>(proj.feat), n, pp, block_sums,
-                           reinterpret_cast<u32 *>(scratch + L.tile_masks), header);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+    u32 *tile_count = reinterpret_cast<u32 *>(scratch + L.tile_count);
+    const u32 num_tiles = pp.tiles_x * pp.tiles_y;
+    if (L.pre_blocks == 0) {
+        hipLaunchKernelGGL(reset_frame_kernel, dim3(16), dim3(256), 0, stream, header, tile_count, num_tiles);
+        return hipGetLastError();
     }
-    const u32 groups = L.pre_blocks ? (L.pre_blocks + kScanGroup - 1) / kScanGroup : 1u;
-    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(groups), dim3(kScanGroup), 0, stream,
-                       block_sums, L.pre_blocks, reinterpret_cast<u64 *>(scratch + L.block_offsets),
-                       reinterpret_cast<u64 *>(scratch + L.group_totals), header);
-    return hipGetLastError();
+    hipLaunchKernelGGL(rebuild_handover_kernel, dim3(L.pre_blocks), dim3(kPreBlock), 0, stream,
+                       proj.tiles_touched, reinterpret_cast<const ushort4 *>(proj.rect),
+                       reinterpret_cast<const float4 *>(proj.feat), n, pp,
+                       reinterpret_cast<u32 *>(scratch + L.tile_masks), header, tile_count, num_tiles,
+                       reinterpret_cast<u32 *>(scratch + L.block_sums));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_scan_block_sums(scratch, L, stream);
 }
 
 // {D, status} of the frame from the scratch header to a caller's device array of two 64-bit words

@@ -240,16 +240,26 @@ def test_capacity_overflow_sets_status_and_stays_in_bounds(n, scale_mul, wh, bin
         area = (ofr.pre.rect[:, 2].astype(int) - ofr.pre.rect[:, 0]) * (ofr.pre.rect[:, 3].astype(int) - ofr.pre.rect[:, 1])
         assert (area > 2048).sum() > 10 and ((area > 128) & (area <= 2048)).sum() > 100 and (area <= 128).sum() > 10
     cap = ofr.binned.D // 2
-    fr = P.gpu_frame(B.Scene(sc), cam, cap)
+    dev = B.Scene(sc)
+    fr = B.Frame(dev.n, wh[0], wh[1], cap)
+    for t in (fr.keys, fr.vals, fr.keys_alt, fr.vals_alt):
+        t.fill_(-3)
+    B.render_frame(dev, B.make_camera(cam), fr)
+    torch.cuda.synchronize()
     D, status = B.read_status(fr)
+    # the true pair count comes back, so that the caller can size a retry
     assert D == ofr.binned.D and status == B.ERR_CAPACITY
-    # the truncated run sorted exactly the first `cap` emitted pairs
-    b = ref.bin_sort(ofr.pre, cam, keep_unsorted=True)
-    perm = np.argsort(b.keys_unsorted[:cap], kind="stable")
-    np.testing.assert_array_equal(P.to_np(fr.keys[:cap]).view(np.uint64), b.keys_unsorted[:cap][perm])
-    np.testing.assert_array_equal(P.to_np(fr.vals[:cap]).view(np.uint32), b.vals_unsorted[:cap][perm])
-    to = P.to_np(fr.tile_offsets).view(np.uint64)
-    assert to[-1] == cap and np.all(np.diff(to.astype(np.int64)) >= 0)
+    # nothing was emitted: every range is empty, the pair buffers are as they were, the image is the background
+    assert not P.to_np(fr.tile_offsets).any()
+    assert bool((fr.keys == -3).all()) and bool((fr.vals == -3).all())
+    assert bool((fr.out_T == 1.0).all())
+    bg = torch.tensor(np.asarray(cam["bg"], np.float32), device="cuda")[:, None, None]
+    assert bool((fr.out_rgb == bg).all())
+    # and the retry with the capacity the call reported fits exactly
+    fr2 = B.Frame(dev.n, wh[0], wh[1], D, want_offsets=True)
+    B.render_frame(dev, B.make_camera(cam), fr2)
+    torch.cuda.synchronize()
+    P.compare_binned(fr2, ofr.binned)
 
 
 # ------------------------------------------------------------------ stage isolation
