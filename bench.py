@@ -3,13 +3,13 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 2] [--no-cpu-baseline]
 
-A step is one frame: lmk_gs_preprocess_culled (or lmk_gs_preprocess with --voxel 0) +
-lmk_gs_bin_sort + lmk_gs_render for one viewpoint, all enqueued on one stream with no
-host synchronisation; steps cycle through the configuration's seeded viewpoints.  The
-scene is reordered into voxels once, before anything is timed.  Inputs are resident in HBM
-before the timed region.  Prints ONE JSON line (metric = frames/s) that also
-carries Gaussian-pixel blends/s, per-stage times, the roofline of the dominant
-kernel and of the HBM-bound stages, and the CPU oracle timed on the same
+A step is one pass over the configuration's seeded viewpoints (8 for configs 1-3, 1 for configs 0
+and 4), each frame being lmk_gs_preprocess_culled (or lmk_gs_preprocess with --voxel 0) +
+lmk_gs_bin_sort + lmk_gs_render, all enqueued on one stream with no host synchronisation, so that
+every viewpoint weighs the same whatever --steps is.  The scene is reordered into voxels once,
+before anything is timed.  Inputs are resident in HBM before the timed region.  Prints ONE JSON
+line (metric = frames/s) that also carries Gaussian-pixel blends/s, per-stage times, the roofline
+of the dominant kernel and of the HBM-bound stages, and the CPU oracle timed on the same
 workload as a baseline.
 """
 from __future__ import annotations
@@ -43,26 +43,22 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
     parameter cache: six covariance entries instead of seven rotation and scale values); SH 192 B +
     outputs 64 B (depth 4, rect 8, feature record 48, reread count 4) for binned ones, plus the
     4 B mask of kept tiles under binning rule 1; the voxel table, 32 B per voxel + 8 B per group.
-    scan: block sums only (negligible).  emit: 16 B per binned primitive (+ 4 B of its
-    mask under binning rule 1; the feature records of the few rectangles above 32 tiles are not
-    charged) + 12 B per pair.
-    partition by tile: per pass over the tile bits (digits of at most 8 bits: 2 passes at
-    1080p and 2160p, 1 at 256 x 256) histogram read 8 B + scatter read 12 B + write 12 B per pair.
-    ranges: 8 B per pair + 8 B per tile.  order: 12 B per tile.
-    per-tile sort: 12 B read + 12 B write per pair; a list of 4097 .. 16384 pairs is sorted in
-    chunks and then goes through two merge rounds between the pair buffers (the second a copy for
-    a list of two chunks), 24 B per pair each; a list longer than 16384 pairs is merged, 24 B per
-    pair and doubling round.  `long_lists`: the lengths
-    above 4096.
+    bin_sort (pairs are written straight into their tile's slice, no partition passes):
+    count: tiles_touched 4 + rect 8 (+ mask 4 under rule 1) for every primitive of a group that
+    was projected; scan: 16 B per tile; emit: the same again + depth 4, and the 8-byte composite
+    (depth bits, index) of every pair written; per-tile sort: 8 B read + 12 B written per pair;
+    a list of 4097 .. 16384 pairs is sorted in chunks and then goes through two merge rounds
+    between the pair buffers (the second a copy for a list of two chunks), 24 B per pair each; a
+    list longer than 16384 pairs is merged, 24 B per pair and doubling round.  The (tile, run
+    start) lists of the counting workgroups and the second reads of the few rectangles above 32
+    tiles are not charged.  `long_lists`: the lengths above 4096.
     """
-    tile_bits = max(1, (tiles - 1).bit_length())
-    passes = (tile_bits + 7) // 8
     n_proc = n if n_proc is None else n_proc
     b_pre = 4 * n + 12 * n_proc + (28 if cov_cache else 32) * n_near + (260 if binning else 256) * n_bin + 32 * voxels + (8 * ((n + 255) // 256) if voxels else 0)
-    b_emit = 4 * n + (20 if binning else 16) * n_bin + 12 * D
-    b_part = D * 32 * passes
-    b_ranges = 8 * D + 8 * (tiles + 1) + 12 * tiles
-    b_tsort = 24 * D
+    per_prim = 16 if binning else 12
+    b_count = per_prim * n_proc + 16 * tiles
+    b_emit = (per_prim + 4) * n_proc + 8 * D
+    b_tsort = 20 * D
     for L in long_lists:
         if L <= 16384:
             b_tsort += 48 * L
@@ -73,8 +69,29 @@ def algorithmic_bytes(n, n_near, n_bin, D, tiles, long_lists, binning=0, n_proc=
             run *= 2
             rounds += 1
         b_tsort += 24 * L * rounds
-    return dict(preprocess=b_pre, emit=b_emit, partition=b_part, ranges=b_ranges, tile_sort=b_tsort,
-                total=b_pre + b_emit + b_part + b_ranges + b_tsort)
+    # context only: what a single-level LSD radix sort of the 64-bit keys (8-bit digits over the
+    # 32 depth bits + the tile bits) with duplication in index order and a range pass would move
+    tile_bits = max(1, (tiles - 1).bit_length())
+    passes = (32 + tile_bits + 7) // 8
+    b_radix = 20 * n_bin + 12 * D + D * (8 + 24 * passes) + 8 * D
+    return dict(preprocess=b_pre, count=b_count, emit=b_emit, tile_sort=b_tsort,
+                total=b_pre + b_count + b_emit + b_tsort, radix_scheme_bin_sort=b_radix)
+
+
+def committed_counters(cfg, binning):
+    """VALU counters of the blend kernel from the rocprofv3 --pmc summary committed under profiles/
+    (lines `cfgN binningB blend_kernel <name> <value>`); {} when there is none for this workload."""
+    path = os.path.join(ROOT, "profiles", "blend_counters.txt")
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) == 5 and t[0] == f"cfg{cfg}" and t[1] == f"binning{binning}" and t[2] == "blend_kernel":
+                    out[t[3]] = float(t[4])
+    except OSError:
+        return {}
+    return out
 
 
 def _projection_backward_report(ms, n, stats, nviews):
@@ -188,14 +205,15 @@ def anchor_bench(args):
         del src, dst
         torch.cuda.empty_cache()
 
-    for i in range(args.warmup):
+    nframes = args.steps * nviews                   # a step = one pass over the viewpoints
+    for i in range(args.warmup * nviews):
         frame(i)
     torch.cuda.synchronize()
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    marks = [[ev() for _ in range(5)] for _ in range(args.steps)]
+    marks = [[ev() for _ in range(5)] for _ in range(nframes)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(nframes):
         frame(i, marks[i])
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
@@ -206,7 +224,7 @@ def anchor_bench(args):
 
     # algorithmic work of a launch: anchors in view are decoded (flops, all their bytes); an anchor out of
     # view costs its 32-byte box, its mask byte (written, then read) and the k opacities written
-    view_of = np.arange(args.steps) % nviews
+    view_of = np.arange(nframes) % nviews
     seen = np.array(in_view)[view_of] * a
     flops = float((2.0 * (3 * F * (F + 3) + F * 11 * k) * seen).mean())
     per_seen = 4.0 * (3 + F + 6 + 3 * k) + 4.0 * k * 15
@@ -216,10 +234,10 @@ def anchor_bench(args):
     traffic = committed_traffic(2, args.binning, f"anchors{a}" + ("" if masked else "-nomask")) if args.views is None else {}
     out = {
         "metric": "frames/s, anchor model: decode + 1080p render",
-        "value": args.steps / total_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": nframes / total_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * total_s / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"anchors: {a} anchors (config 2's clusters) x {k} primitives = {n} candidate "
+        "config": {"frames_per_step": nviews, "workload": f"anchors: {a} anchors (config 2's clusters) x {k} primitives = {n} candidate "
                                f"Gaussians decoded per frame, {W}x{H}, {nviews} seeded viewpoints of config 2",
                    "binning": args.binning, "kept_fraction": kept, "pairs_per_frame_mean": float(np.mean(Ds)),
                    "capacity": capacity, "frustum_mask": masked,
@@ -258,8 +276,9 @@ def anchor_bench(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=160)
-    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--steps", type=int, default=20,
+                    help="timed steps; a step is one pass over the configuration's viewpoints (8 frames for configs 1-3)")
+    ap.add_argument("--warmup", type=int, default=2, help="untimed steps before them")
     ap.add_argument("--cfg", type=int, default=2, help="configuration 0-4 (2 is the headline: 3M Gaussians, 1080p)")
     ap.add_argument("--n", type=int, default=None, help="override the primitive count (reported in config)")
     ap.add_argument("--binning", type=int, default=1, choices=(0, 1),
@@ -363,18 +382,19 @@ def main():
         torch.cuda.empty_cache()
 
     nviews = len(ccams)
+    nframes = args.steps * nviews                   # a step = one pass over the viewpoints
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    for i in range(args.warmup):
+    for i in range(args.warmup * nviews):
         B.render_frame(dev, ccams[i % nviews], frames[i % S], stream=streams[i % S], index=index)
     torch.cuda.synchronize()
-    for f in frames[:min(S, max(args.warmup, 1))]:
+    for f in frames[:min(S, max(args.warmup * nviews, 1))]:
         _, status = B.read_status(f)
         assert status == B.OK, f"status {status}"
 
-    marks = [[ev(), ev(), ev(), ev()] for _ in range(args.steps)]
+    marks = [[ev(), ev(), ev(), ev()] for _ in range(nframes)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(nframes):
         cc = ccams[i % nviews]
         m = marks[i]
         f, st = frames[i % S], streams[i % S]
@@ -389,7 +409,7 @@ def main():
     t1 = time.perf_counter()
     total_s = t1 - t0
     ms_per_step = 1e3 * total_s / args.steps
-    fps = args.steps / total_s
+    fps = nframes / total_s
     for f in frames:
         _, status = B.read_status(f)
         assert status == B.OK, f"status {status}"
@@ -398,7 +418,7 @@ def main():
     t_sort = np.array([m[1].elapsed_time(m[2]) for m in marks])
     t_blend = np.array([m[2].elapsed_time(m[3]) for m in marks])
     t_frame = np.array([m[0].elapsed_time(m[3]) for m in marks])
-    view_of = np.arange(args.steps) % nviews
+    view_of = np.arange(nframes) % nviews
 
     # ---- CPU oracle: counts E, C (algorithmic pairs) and the baseline time
     cpu = None
@@ -433,7 +453,49 @@ def main():
         del g_rgb, g_T, g_feat, grads
 
     n_near = None
-    if not args.no_cpu_baseline:
+    estimated = False
+    if not args.no_cpu_baseline and args.cfg == 4 and args.n is None:
+        # The frame is too large for the oracle to bin whole (6e9 pairs): it is timed on a sample -- all
+        # primitives projected, then three bands of three tile rows each (top, middle, bottom of the
+        # image) binned and blended -- and the frame time and the pair counts E, C are scaled up from
+        # the sampled pixel rows.
+        from oracle import ref
+        estimated = True
+        cam0 = dict(cams[0], binning=0)
+        c0 = time.perf_counter()
+        pre = ref.preprocess(scene, cam0)
+        order = ref.depth_order(pre)
+        t_head = time.perf_counter() - c0
+        ty = (H + 15) // 16
+        rows, t_bands, e_sum, c_sum, px = 0, 0.0, 0, 0, 0
+        for frac in (0.1, 0.5, 0.9):
+            a = min(max(int(frac * ty) - 1, 0), max(ty - 3, 0))
+            c1 = time.perf_counter()
+            band = ref.band_lists(pre, cam0, a, min(a + 3, ty), order)
+            img = ref.render_band(pre, cam0, band)
+            t_bands += time.perf_counter() - c1
+            rows += min(a + 3, ty) - a
+            e_sum += int(img.E.sum()); c_sum += int(img.C.sum()); px += img.E.size
+            del band, img
+        scale = (W * H) / px
+        E, C = [e_sum * scale], [c_sum * scale]
+        t_frame_cpu = t_head + t_bands * ty / rows
+        proc = np.repeat(stats[0]["processed"], B.PRE_BLOCK)[:n]
+        stats[0]["n_proc"] = int(proc.sum())
+        n_near = [int(((pre.stage != ref.CULL_NEAR) & proc).sum())]
+        D_ref = int(pre.tiles_touched.astype(np.uint64).sum()) if args.binning == 0 else \
+            int(ref.preprocess(scene, cams[0]).tiles_touched.astype(np.uint64).sum())
+        assert D_ref == stats[0]["D"], "GPU and oracle disagree on the pair count"
+        cores = len(os.sched_getaffinity(0))
+        omp = os.environ.get("OMP_NUM_THREADS")
+        threads = min(cores, int(omp)) if omp and omp.isdigit() else cores
+        cpu = dict(value=1.0 / t_frame_cpu, unit="frames/s", cores=threads, kind="oracle",
+                   sample=f"cfg 4: every primitive projected and depth-ordered ({t_head:.1f} s), then {rows} of the "
+                          f"{ty} tile rows binned and blended in three bands ({t_bands:.1f} s; binning rule 0); frame "
+                          f"time and pair counts scaled up from the sampled rows",
+                   blends_per_s=e_sum / t_bands)
+        del pre, order
+    elif not args.no_cpu_baseline:
         from oracle import ref
         E, C, n_near, cpu_t = [], [], [], []
         sample_views = list(range(nviews))
@@ -465,7 +527,8 @@ def main():
         "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"cfg{args.cfg}: {n} Gaussians, {W}x{H}, 16x16 tiles, SH degree 3, "
+        "config": {"frames_per_step": nviews,
+                   "workload": f"cfg{args.cfg}: {n} Gaussians, {W}x{H}, 16x16 tiles, SH degree 3, "
                                f"{nviews} seeded viewpoints rendered back-to-back",
                    "binning": args.binning, "pairs_per_frame_mean": float(np.mean(Ds)), "capacity": capacity,
                    "frames_in_flight": S, "parameter_cache": not args.no_cov_cache,
@@ -488,29 +551,43 @@ def main():
         flops = (14.0 * Ev + 10.0 * Cv)[view_of].sum()
         tf = flops / (t_blend.sum() * 1e-3) / 1e12
         out["blends_per_s"] = blends
+        if estimated:
+            out["blends_note"] = "E and C are scaled up from the sampled tile rows of the CPU baseline"
         # the committed measurement is of the default command of each configuration
         traffic = committed_traffic(args.cfg, args.binning) \
             if args.n is None and args.views is None and args.voxel == VOXEL_SIZE[args.cfg] else {}
         out["roofline"] = {"kernel": "blend_kernel", "bound": "alu", "achieved": tf, "peak": FP32_PEAK_TFLOPS,
                            "unit": "TFLOP/s", "frac": tf / FP32_PEAK_TFLOPS, "traffic": traffic.get("blend_kernel"),
                            "avg_launch_ms": float(t_blend.mean()),
-                           "flops_per_launch": float(flops / args.steps)}
-        byts, byts_pre = [], []
+                           "flops_per_launch": float(flops / nframes),
+                           "note": "algorithmic flops 14 E + 10 C (E, C counted by the oracle under binning rule 0) "
+                                   "over the blend kernel's time; the instruction-issue view is in valu_counters"}
+        counters = committed_counters(args.cfg, args.binning) \
+            if args.n is None and args.views is None and args.voxel == VOXEL_SIZE[args.cfg] else {}
+        if counters:
+            out["roofline"]["valu_counters"] = counters
+        byts, byts_pre, byts_radix = [], [], []
         for v in range(nviews):
             ab = algorithmic_bytes(n, n_near[v], stats[v]["n_bin"], stats[v]["D"], tiles,
                                    stats[v]["long_lists"], args.binning, stats[v]["n_proc"],
                                    0 if index is None else index.num_voxels, not args.no_cov_cache)
-            byts.append(ab["total"]); byts_pre.append(ab["preprocess"])
+            byts.append(ab["total"]); byts_pre.append(ab["preprocess"]); byts_radix.append(ab["radix_scheme_bin_sort"])
         byts = np.array(byts, dtype=np.float64); byts_pre = np.array(byts_pre, dtype=np.float64)
+        byts_radix = np.array(byts_radix, dtype=np.float64)
         gbs = byts[view_of].sum() / ((t_pre.sum() + t_sort.sum()) * 1e-3) / 1e9
         gbs_pre = byts_pre[view_of].sum() / (t_pre.sum() * 1e-3) / 1e9
         gbs_sort = (byts - byts_pre)[view_of].sum() / (t_sort.sum() * 1e-3) / 1e9
-        out["roofline_hbm_stages"] = {"kernels": "preprocess + scan + emit + partition passes + ranges + order + "
-                                                 "per-tile sorts",
+        gbs_radix = (byts_pre + byts_radix)[view_of].sum() / ((t_pre.sum() + t_sort.sum()) * 1e-3) / 1e9
+        out["roofline_hbm_stages"] = {"kernels": "preprocess + block scan + count + tile scan + emit + per-tile sorts",
                                       "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                       "frac": gbs / HBM_PEAK_GBS, "traffic": traffic.get("preprocess+bin_sort"),
                                       "preprocess_GBs": gbs_pre, "bin_sort_GBs": gbs_sort,
-                                      "bytes_per_frame": float(byts.mean())}
+                                      "bytes_per_frame": float(byts.mean()),
+                                      "radix_scheme_equivalent_GBs": gbs_radix,
+                                      "note": "achieved = bytes of the scheme this library runs (no partition passes) over "
+                                              "the two stages' time; radix_scheme_equivalent_GBs charges the same time with "
+                                              "what a single-level 64-bit LSD radix sort of the same pairs would have to "
+                                              "move -- context for comparisons across schemes, not a roofline claim"}
         if bwd_ms is not None:
             # algorithmic flops of the gradient call: both passes evaluate alpha for every visited pair
             # (14 E each, E as counted by the oracle), pass 1 also composites (10 C), pass 2 spends 45 per

@@ -132,9 +132,10 @@ typedef struct lmk_gs_binned {
 /* Bytes of device scratch the three calls need for n primitives, a
  * width x height image and `capacity` pairs.  The same scratch buffer
  * (256-byte aligned) must be passed to preprocess and bin_sort of one frame:
- * it carries the per-group tile counts and, under binning rule 1, the masks of
- * kept tiles from the one to the other.  Its contents need no initialisation.
- * Its first 16 bytes are {uint64 pair count D, int32 status, int32 pad}. */
+ * it carries the pair count, the per-group tile counts with their prefix sum and,
+ * under binning rule 1, the masks of kept tiles from the one to the other.  Its
+ * contents need no initialisation.  Its first 16 bytes are {uint64 pair count D,
+ * int32 status, int32 pad}; D is final when lmk_gs_preprocess has completed. */
 int32_t lmk_gs_workspace_bytes(uint32_t n, uint32_t width, uint32_t height,
                                uint64_t capacity, size_t *scratch_bytes);
 
@@ -185,15 +186,18 @@ int32_t lmk_gs_preprocess_culled(const lmk_gs_gaussians *g, const lmk_gs_voxel_i
                                  void *scratch, size_t scratch_bytes, void *stream);
 
 /* Stage 2 (duplication into keys, depth sort at tile granularity, Sec. 2.2 and
- * Sec. 4.2.1).  Prefix-sums tiles_touched, emits one (key, value) per
- * (primitive, tile that lmk_gs_camera.binning keeps) -- primitives in index
- * order, rectangle row-major -- and leaves all pairs in keys/vals in ascending
- * (tile, depth bits, primitive index) order, which is unique, together with
- * the per-tile ranges.  How: the pairs are partitioned by tile id (radix passes
- * over the tile bits only), then every tile's list is sorted on its own.
- * keys_alt/vals_alt are working space.  If the pair count exceeds `capacity`,
- * only the first `capacity` emitted pairs are processed and the status word
- * becomes LMK_GS_ERR_CAPACITY. */
+ * Sec. 4.2.1).  One (key, value) pair per (primitive, tile that lmk_gs_camera.binning
+ * keeps); on return all pairs are in keys/vals in ascending (tile, depth bits,
+ * primitive index) order, which is unique, together with the per-tile ranges.
+ * How: that order has no ties, so the order in which a tile's pairs arrive in the
+ * tile's slice is free -- the pairs are counted per tile, the counts are scanned into
+ * the ranges, every pair is written straight into its tile's slice, and each slice
+ * is sorted on its own.  proj->offsets, when present, receives the exclusive prefix
+ * sum of tiles_touched.  keys_alt/vals_alt are working space.
+ * If the pair count D exceeds `capacity`, nothing is emitted: the status word
+ * becomes LMK_GS_ERR_CAPACITY, every tile range is empty (lmk_gs_render then gives
+ * the background), keys/vals are left as they were, and D (lmk_gs_read_status) tells
+ * how much room a retry needs. */
 int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,
                         const lmk_gs_binned *out,
                         void *scratch, size_t scratch_bytes, void *stream);

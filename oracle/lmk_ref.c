@@ -635,6 +635,91 @@ uint64_t lmk_ref_tile_list(uint32_t n, const uint32_t *tiles_touched, const uint
     return m;
 }
 
+/* The sorted lists of every tile of a band of tile rows [ty0, ty1), for frames too large to bin
+ * whole on the host.  The primitives are visited in front-to-back order (`order`, from
+ * lmk_ref_depth_order), and a primitive is appended to the list of every tile of the band that its
+ * rectangle contains (binning rule 1: and on which tile_kept holds): the lists are born in
+ * (depth bits, index) order, which is the sorted order of step 12 restricted to one tile.
+ * out_offsets[k], k = 0 .. (ty1 - ty0) * tiles_x: start of the list of tile (ty0 * tiles_x + k) inside
+ * out_vals; out_vals has capacity cap.  Returns the number of pairs of the band; if that exceeds
+ * cap only out_offsets is complete and nothing is written to out_vals. */
+uint64_t lmk_ref_band_lists(uint32_t n, const uint32_t *tiles_touched, const uint16_t *rect,
+                            const uint32_t *order, uint32_t order_len,
+                            uint32_t binning, uint32_t ts, uint32_t tiles_x, uint32_t ty0, uint32_t ty1,
+                            const float *mean2d, const float *conic, const float *opacity,
+                            uint64_t *out_offsets, uint32_t *out_vals, uint64_t cap)
+{
+    const size_t N = n;
+    const uint32_t rows = ty1 - ty0;
+    const size_t nt = (size_t)rows * tiles_x;
+    init_tau_table();
+    uint64_t *count = (uint64_t *)calloc(nt + 1, sizeof(uint64_t));
+    for (int pass = 0; pass < 2; ++pass) {
+        /* one tile row at a time; rows are independent */
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t rr = 0; rr < (int64_t)rows; ++rr) {
+            const uint32_t ty = ty0 + (uint32_t)rr;
+            uint64_t *cur = (uint64_t *)malloc((size_t)tiles_x * sizeof(uint64_t));
+            for (uint32_t tx = 0; tx < tiles_x; ++tx)
+                cur[tx] = pass ? out_offsets[(size_t)rr * tiles_x + tx] : 0;
+            for (uint32_t k = 0; k < order_len; ++k) {
+                const uint32_t i = order[k];
+                if (!tiles_touched[i] || !(rect[4 * i + 1] <= ty && ty < rect[4 * i + 3])) continue;
+                for (uint32_t tx = rect[4 * i]; tx < rect[4 * i + 2] && tx < tiles_x; ++tx) {
+                    if (binning == 1 && !tile_kept(mean2d[i], mean2d[N + i], conic[i], conic[N + i],
+                                                   conic[2 * N + i], opacity_tau(opacity[i]), tx, ty, ts))
+                        continue;
+                    if (pass) out_vals[cur[tx]] = i;
+                    ++cur[tx];
+                }
+            }
+            if (!pass)
+                for (uint32_t tx = 0; tx < tiles_x; ++tx) count[(size_t)rr * tiles_x + tx] = cur[tx];
+            free(cur);
+        }
+        if (!pass) {
+            uint64_t run = 0;
+            for (size_t t = 0; t < nt; ++t) { out_offsets[t] = run; run += count[t]; }
+            out_offsets[nt] = run;
+            if (run > cap) { free(count); return run; }
+        }
+    }
+    free(count);
+    return out_offsets[nt];
+}
+
+/* Step 14 for the pixel rows of a band of tile rows [ty0, ty1) through the lists of
+ * lmk_ref_band_lists: outputs are [rows_px][W] (rgb: [3][rows_px][W]), rows_px = the band's
+ * pixel rows inside the image. */
+void lmk_ref_render_band(uint32_t n, const uint8_t *stage, const float *mean2d, const float *conic,
+                         const float *opacity, const double *rgb,
+                         const uint32_t *band_vals, const uint64_t *band_offsets,
+                         const ref_camera *cam, uint32_t ty0, uint32_t ty1,
+                         double *out_rgb, double *out_T, uint32_t *out_E, uint32_t *out_C,
+                         double *out_beta, double *out_beta_T, uint32_t *out_amb)
+{
+    const uint32_t W = cam->width, H = cam->height, TS = cam->tile;
+    const uint32_t TX = (W + TS - 1) / TS;
+    const uint32_t y0 = ty0 * TS, y1 = ty1 * TS < H ? ty1 * TS : H;
+    const size_t rows = y1 > y0 ? y1 - y0 : 0;
+    const double cmax = max_rgb(n, stage, rgb);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t jj = 0; jj < (int64_t)rows; ++jj) {
+        const uint32_t j = y0 + (uint32_t)jj;
+        for (uint32_t i = 0; i < W; ++i) {
+            const size_t t = (size_t)(j / TS - ty0) * TX + (i / TS);
+            ref_pixel r;
+            composite_pixel((double)i + 0.5, (double)j + 0.5,
+                            band_vals + band_offsets[t], band_offsets[t + 1] - band_offsets[t],
+                            n, mean2d, conic, opacity, rgb, cmax, cam->bg, &r, NULL, 0);
+            const size_t p = (size_t)jj * W + i;
+            for (int ch = 0; ch < 3; ++ch) out_rgb[(size_t)ch * rows * W + p] = r.rgb[ch];
+            out_T[p] = r.T; out_E[p] = r.E; out_C[p] = r.C;
+            out_beta[p] = r.beta; out_beta_T[p] = r.beta_T; out_amb[p] = r.amb;
+        }
+    }
+}
+
 /* Walk an explicit list at chosen pixels (used with lmk_ref_tile_list to check
  * tiles of a frame too large to bin whole on the host). */
 void lmk_ref_render_pixels_list(uint32_t n, const uint8_t *stage, const float *mean2d,

@@ -253,6 +253,46 @@ def tile_list(pre: SimpleNamespace, tile_x: int, tile_y: int, cam: dict | None =
         cap = m
 
 
+def band_lists(pre: SimpleNamespace, cam: dict, ty0: int, ty1: int, order=None) -> SimpleNamespace:
+    """Sorted lists of every tile of the tile rows [ty0, ty1) (frames too large to bin whole):
+    offsets [(ty1 - ty0) * tiles_x + 1] into vals, lists in tile order."""
+    if order is None:
+        order = depth_order(pre)
+    tx, _ = tiles_xy(cam)
+    nt = (ty1 - ty0) * tx
+    offsets = np.empty(nt + 1, np.uint64)
+    o = order if order.size else np.zeros(1, np.uint32)
+    args = lambda vals, cap: (C.c_uint32(pre.n), _p(pre.tiles_touched), _p(pre.rect), _p(o), C.c_uint32(order.size),
+                              C.c_uint32(int(cam.get("binning", 0))), C.c_uint32(int(cam["tile"])), C.c_uint32(tx),
+                              C.c_uint32(ty0), C.c_uint32(ty1), _p(pre.mean2d), _p(pre.conic), _p(pre.opacity),
+                              _p(offsets), _p(vals), C.c_uint64(cap))
+    lib().lmk_ref_band_lists.restype = C.c_uint64
+    dummy = np.zeros(1, np.uint32)
+    m = int(lib().lmk_ref_band_lists(*args(dummy, 0)))          # sizes only
+    vals = np.empty(max(m, 1), np.uint32)
+    if m:
+        lib().lmk_ref_band_lists(*args(vals, m))
+    return SimpleNamespace(offsets=offsets, vals=vals[:m], ty0=ty0, ty1=ty1, tiles_x=tx)
+
+
+def render_band(pre: SimpleNamespace, cam: dict, band: SimpleNamespace) -> SimpleNamespace:
+    """Step 14 for the pixel rows of a band through its lists (outputs cover only those rows)."""
+    H, W, ts = int(cam["height"]), int(cam["width"]), int(cam["tile"])
+    y0, y1 = band.ty0 * ts, min(band.ty1 * ts, H)
+    rows = max(y1 - y0, 0)
+    out = SimpleNamespace(rgb=np.empty((3, rows, W), np.float64), T=np.empty((rows, W), np.float64),
+                          E=np.empty((rows, W), np.uint32), C=np.empty((rows, W), np.uint32),
+                          beta=np.empty((rows, W), np.float64), beta_T=np.empty((rows, W), np.float64),
+                          amb=np.empty((rows, W), np.uint32), y0=y0, y1=y1)
+    cc = _camera(cam)
+    vals = band.vals if band.vals.size else np.zeros(1, np.uint32)
+    lib().lmk_ref_render_band(C.c_uint32(pre.n), _p(pre.stage), _p(pre.mean2d), _p(pre.conic), _p(pre.opacity),
+                              _p(pre.rgb), _p(vals), _p(band.offsets), C.byref(cc), C.c_uint32(band.ty0),
+                              C.c_uint32(band.ty1), _p(out.rgb), _p(out.T), _p(out.E), _p(out.C),
+                              _p(out.beta), _p(out.beta_T), _p(out.amb))
+    return out
+
+
 def render_pixels_list(pre: SimpleNamespace, cam: dict, lst: np.ndarray, xs, ys) -> SimpleNamespace:
     xs = np.ascontiguousarray(xs, dtype=np.uint32)
     ys = np.ascontiguousarray(ys, dtype=np.uint32)

@@ -183,6 +183,7 @@ __global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void count_kernel(
     const u32 *__restrict__ tiles_touched, const ushort4 *__restrict__ rect, const u32 *__restrict__ tile_masks,
     u32 n, u32 tiles_x, u32 num_tiles, u32 *__restrict__ tile_count,
     ScratchHeader *__restrict__ header, u32 *__restrict__ big_idx,
+    const u32 *__restrict__ block_sums, u32 pre_blocks,
     const u64 *__restrict__ block_offsets, const u64 *__restrict__ group_totals,
     u32 *__restrict__ bin_count, uint2 *__restrict__ list, u64 list_capacity)
 {
@@ -197,6 +198,19 @@ __global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void count_kernel(
     __shared__ u32 s_base[2];
     __shared__ u64 s_part[kWaves];
     const u32 tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    {   // the projection stage counted the pairs of every 256 primitives: a workgroup none of whose
+        // primitives was binned (culled, or a skipped voxel range) leaves without reading one
+        u32 pairs = 0;
+#pragma unroll
+        for (u32 q = 0; q < kBinBlock / kPreBlock; ++q) {
+            const u32 pb = blockIdx.x * (kBinBlock / kPreBlock) + q;
+            pairs |= pb < pre_blocks ? block_sums[pb] : 0u;
+        }
+        if (pairs == 0u) {                                  // the same for the whole workgroup
+            if (LDS && tid == 0) bin_count[blockIdx.x] = 0;
+            return;
+        }
+    }
     // everything this thread will need is requested at once: one round trip to memory
     u32 cnt[kPer], mask[kPer];
     ushort4 r[kPer];
@@ -1229,6 +1243,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
         auto count = [&](auto kernel) {
             hipLaunchKernelGGL(kernel, dim3(L.bin_blocks), dim3(bin_threads), 0, stream,
                                proj.tiles_touched, rect, tile_masks, n, pp.tiles_x, num_tiles, tile_count, header, big_idx,
+                               reinterpret_cast<const u32 *>(scratch + L.block_sums), L.pre_blocks,
                                block_offsets, group_totals, bin_count, list, out.capacity);
         };
         if (lds_tiles == kLdsTilesSmall) { if (tight) count(count_kernel<kLdsTilesSmall, true>); else count(count_kernel<kLdsTilesSmall, false>); }

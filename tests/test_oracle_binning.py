@@ -127,3 +127,37 @@ def test_rule1_statistics_on_config_shapes():
     pre1 = ref.preprocess(sc, dict(cam0, binning=1))
     r = pre1.tiles_touched.sum() / pre0.tiles_touched.sum()
     assert 0.6 < r < 0.9
+
+
+@pytest.mark.parametrize("binning", [0, 1])
+def test_band_lists_and_band_render_are_the_frame_cut_into_tile_rows(binning):
+    """The band-streaming functions (for frames too large to bin whole) against three other
+    routes to the same thing: the whole-frame sort, the per-tile list from the definition, and
+    the brute-force image."""
+    sc = scenes.make_scene(0, n=4000, seed=61)
+    sc["scale"] *= np.float32(2.5)
+    W, H = 150, 101                                    # ragged in both directions: 10 x 7 tiles
+    cam = dict(scenes.make_cameras(0, W, H)[0], binning=binning)
+    fr = ref.render_frame(sc, cam)
+    tx, ty = ref.tiles_xy(cam)
+    order = ref.depth_order(fr.pre)
+    total = 0
+    for a, b in [(0, 2), (2, 3), (3, ty)]:
+        band = ref.band_lists(fr.pre, cam, a, b, order)
+        lo, hi = int(fr.binned.tile_offsets[a * tx]), int(fr.binned.tile_offsets[b * tx])
+        np.testing.assert_array_equal(band.vals, fr.binned.vals[lo:hi])
+        np.testing.assert_array_equal(band.offsets, fr.binned.tile_offsets[a * tx:b * tx + 1] - np.uint64(lo))
+        total += band.vals.size
+        # one tile of the band straight from the definition
+        t = a * tx + 3
+        np.testing.assert_array_equal(band.vals[int(band.offsets[3]):int(band.offsets[4])],
+                                      ref.tile_list(fr.pre, 3, a, cam))
+        img = ref.render_band(fr.pre, cam, band)
+        assert (img.y0, img.y1) == (a * 16, min(b * 16, H))
+        ys, xs = np.mgrid[img.y0:img.y1, 0:W]
+        br = ref.render_pixels_brute(fr.pre, cam, xs.ravel(), ys.ravel(), order)
+        assert np.array_equal(br.rgb.T.reshape(3, img.y1 - img.y0, W), img.rgb)
+        assert np.array_equal(br.T.reshape(img.y1 - img.y0, W), img.T)
+        assert np.array_equal(img.E, fr.img.E[img.y0:img.y1]) and np.array_equal(img.C, fr.img.C[img.y0:img.y1])
+        assert np.array_equal(img.amb, fr.img.amb[img.y0:img.y1])
+    assert total == fr.binned.D
