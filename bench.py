@@ -25,8 +25,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # voxel edge per configuration for the offline reordering (a few hundred primitives per voxel);
-# 0 = off where every viewpoint sees the whole scene and the filter can only cost
-VOXEL_SIZE = {0: 0.0, 1: 0.0, 2: 2.0, 3: 40.0, 4: 0.0}
+# 0 = off (configs 0 and 4: one viewpoint that sees everything); the spatial order also lets the
+# counting workgroups of stage 2 combine the pairs of neighbouring primitives per tile
+VOXEL_SIZE = {0: 0.0, 1: 1.0, 2: 2.0, 3: 40.0, 4: 0.0}
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP32_PEAK_TFLOPS = 157.3     # 256 CU x 128 lanes x 2 flop x 2.4 GHz (vector FP32, packed-FMA rate)

@@ -5,8 +5,9 @@ not fixed; every term carries a relative rounding error of a few 2^-24 per compo
 of it (the error of T), so a component may differ from the fp64 value by up to
 RTOL x (sum of the magnitudes of its terms, which the oracle reports) with RTOL = 2e-5 -- a few
 2^-24 for each of a hundred composited entries; the largest ratio seen is 1.6e-6 -- plus 1e-7.  A pixel holding a decision within rounding of its
-threshold may legitimately take the other one: primitives that can contribute at such a pixel are
-left out of the comparison (their share is checked to be small)."""
+threshold may legitimately take the other one: such pixels (the oracle marks them, at most 0.5 % of
+a frame) get a zero upstream gradient on both sides, and then every component of every primitive is
+compared."""
 import numpy as np
 import pytest
 import torch
@@ -20,12 +21,24 @@ pytestmark = pytest.mark.gpu
 RTOL, ATOL = 2e-5, 1e-7
 
 
-def _compare(sc, cam, seed, with_T=True, max_excluded=0.4):
+def _compare(sc, cam, seed, with_T=True, max_masked=0.005):
     H, W = int(cam["height"]), int(cam["width"])
     ofr = ref.render_frame(sc, cam)
     rng = np.random.default_rng(seed)
     Gc = rng.normal(size=(3, H, W)).astype(np.float32)
     GT = rng.normal(size=(H, W)).astype(np.float32) if with_T else None
+    # A pixel holding a decision within rounding of its threshold (alpha against 1/255 or the 0.99
+    # clamp, T' against 1e-4) may take the other one on the GPU, and its whole share of the gradients
+    # of the primitives it sees then differs.  Such pixels (the oracle marks them; the marks depend on
+    # the forward walk only) get a zero upstream gradient on both sides, so that every component of
+    # every primitive is compared, with nothing left out.
+    amb = ref.render_backward(ofr.pre, ofr.binned, cam, Gc.astype(np.float64),
+                              None if GT is None else GT.astype(np.float64)).amb > 0
+    masked = float(amb.mean())
+    assert masked <= max_masked, masked
+    Gc[:, amb] = 0.0
+    if GT is not None:
+        GT[amb] = 0.0
     g = ref.render_backward(ofr.pre, ofr.binned, cam, Gc.astype(np.float64),
                             None if GT is None else GT.astype(np.float64))
     dev = B.Scene(sc)
@@ -42,39 +55,21 @@ def _compare(sc, cam, seed, with_T=True, max_excluded=0.4):
     got = got[:, :9]
     want = np.concatenate([g.mean2d, g.conic, g.opacity[None, :], g.rgb]).T      # [n][9]
     scale = g.abs.T
-    # a primitive that can contribute (alpha near or above 1/255) at a pixel holding an ambiguous
-    # decision is not compared: that pixel's share of its gradient depends on the decision
-    TS = 16
-    tiles_x = (W + TS - 1) // TS
-    excluded = np.zeros(sc["n"], bool)
-    off = ofr.binned.tile_offsets.astype(np.int64)
-    pre = ofr.pre
-    ys, xs = np.nonzero(g.amb)
-    for y, x in zip(ys, xs):
-        t = (y // TS) * tiles_x + x // TS
-        ids = ofr.binned.vals[off[t]:off[t + 1]].astype(np.int64)
-        dx = pre.mean2d[0, ids].astype(np.float64) - (x + 0.5)
-        dy = pre.mean2d[1, ids].astype(np.float64) - (y + 0.5)
-        q = pre.conic[0, ids] * dx * dx + 2.0 * pre.conic[1, ids] * dx * dy + pre.conic[2, ids] * dy * dy
-        alpha = pre.opacity[ids] * np.exp(-0.5 * np.maximum(q, 0.0))
-        excluded[ids[alpha >= 0.9 / 255.0]] = True
     touched = scale.sum(1) > 0
     assert touched.sum() > 0
-    share = (excluded & touched).sum() / touched.sum()
-    assert share <= max_excluded, share
-    keep = ~excluded
     err = np.abs(got - want)
     tol = RTOL * scale + ATOL
-    bad = (err > tol) & keep[:, None]
+    bad = err > tol
     if bad.any():
         i, k = np.argwhere(bad)[0]
         raise AssertionError(f"{bad.sum()} components beyond tolerance; first: primitive {i} component {k}: "
                              f"got {got[i, k]:.6e} want {want[i, k]:.6e} scale {scale[i, k]:.3e}")
     # primitives the oracle gives nothing get exactly nothing
-    assert not got[keep & ~touched].any()
-    rel = (err[keep] / (scale[keep] + 1e-30))[scale[keep] > 1e-6]
-    return dict(n=sc["n"], D=int(ofr.binned.D), compared=int(keep.sum()), excluded_share=float(share),
-                worst_rel=float(rel.max()) if rel.size else 0.0, median_rel=float(np.median(rel)) if rel.size else 0.0)
+    assert not got[~touched].any()
+    rel = (err / (scale + 1e-30))[scale > 1e-6]
+    return dict(n=sc["n"], D=int(ofr.binned.D), compared=int(sc["n"]), with_gradient=int(touched.sum()),
+                masked_pixel_share=masked, worst_rel=float(rel.max()) if rel.size else 0.0,
+                median_rel=float(np.median(rel)) if rel.size else 0.0)
 
 
 @pytest.mark.parametrize("w,h,n,seed,scale_mul", [
@@ -119,6 +114,18 @@ def test_empty_frame_clears_the_output():
     B.render_backward(B.make_camera(cam), fr, torch.ones(3, 64, 64, device="cuda"), None, out)
     torch.cuda.synchronize()
     assert not out.any().item()
+
+
+@pytest.mark.parametrize("cfg,view", [(1, 0), (2, 0), (2, 5)])
+def test_full_size_frames_element_by_element(cfg, view):
+    """Configurations 1 and 2 at their full size (500 k / 3 M primitives, 1920x1080): every component
+    of every primitive's gradient against the oracle, to the tolerance of the small frames."""
+    sc = scenes.make_scene(cfg)
+    cam = scenes.make_cameras(cfg)[view]
+    st = _compare(sc, cam, 100 + 10 * cfg + view)
+    print(f"[backward] cfg{cfg} view {view} full size: {st}", flush=True)
+    assert st["with_gradient"] > 50_000
+    torch.cuda.empty_cache()
 
 
 def test_weights_sum_to_one_at_full_size_cfg1():
