@@ -347,6 +347,6 @@ const char *lmk_gs_strerror(int32_t code)
 int32_t lmk_gs_last_hip_error(void) { return g_last_hip_error.load(); }
 
 // 0.2.0: the gradient calls and the anchor decoder joined the three forward calls
-uint32_t lmk_gs_version(void) { return 200; }
+uint32_t lmk_gs_version(void) { return 300; }
 
 }  // extern "C"

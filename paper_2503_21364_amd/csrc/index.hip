@@ -1,7 +1,7 @@
 // Offline voxel reordering of a scene (host code only; Sec. 4.2.2, frustum-based dynamic
-// loading: the primitives "must be reordered based on their spatial arrangement, a process
-// performed offline", into voxels that can be indexed quickly and filtered against the view
-// frustum instead of the primitives).
+// loading).  Once, before any frame, the primitives are sorted by the cell of a regular grid that
+// holds their centre, so that a voxel is a run of consecutive primitives; per frame the voxels,
+// not the primitives, are then tested against the view frustum.
 #include "lmk_gs_internal.h"
 
 #include <algorithm>

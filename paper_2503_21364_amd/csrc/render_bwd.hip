@@ -18,11 +18,15 @@
 // forward walk with the arithmetic of blend_kernel (same expression for log2(alpha), same
 // comparisons), which gives every pixel its final transmittance and the position of its last
 // composited entry.  Pass 2 takes the batches, and each list, back to front: T_i is recovered as
-// T_{i+1} / (1 - a_i), S_i is a running sum.  The nine gradient components of an entry are summed
-// over the 16 lanes of a row with DPP adds (only when some pixel of the wavefront has a
-// contribution), over the sixteen rows of the tile with LDS float atomics, and leave the
-// workgroup as one global float atomic per (entry, component): the order of these additions is
-// not fixed, so results differ from run to run by fp32 rounding.
+// T_{i+1} / (1 - a_i), S_i is a running sum.  What is summed over the pixels of an entry are not the
+// nine gradient components themselves but nine moments from which they follow linearly, with
+// m = a dL/da (0 where a was clamped): sum m dx, sum m dy, sum m dx^2, sum m dx dy, sum m dy^2,
+// sum m, and sum w dL/dC per channel; the per-entry factors (A, B, C, 1 / opacity) are applied once
+// per (tile, entry) when the sums leave the workgroup.  A pixel without a contribution adds zeros,
+// so the arithmetic has no branches.  The sums go over the 4 lanes of a quad with DPP adds, over
+// the quads and rows of the tile with LDS float atomics, and leave the workgroup as one global
+// float atomic per (entry, component): the order of these additions is not fixed, so results
+// differ from run to run by fp32 rounding.
 //
 // Bound by vector-instruction issue (the exponent evaluation of the forward pass, twice, the
 // gradient arithmetic and the reductions); HBM traffic is the forward's gather, twice, plus 36
@@ -35,8 +39,10 @@ namespace lmk {
 namespace {
 
 constexpr u32 kBwdThreads = 256, kBwdBatch = 256;
+constexpr u32 kBwdWaves = kBwdThreads / kWave;
 typedef unsigned char slot_t;               // a slot of the staged batch (kBwdBatch <= 256)
 static_assert(kBwdBatch <= 256 && (kBwdBatch & (kBwdBatch - 1)) == 0, "slots are bytes and masked");
+static_assert(kBwdBatch <= kBwdThreads, "one thread stages one entry");
 constexpr u32 kGradComps = 9;               // u, v, A, B, C, opacity, r, g, b
 
 struct BwdParams {
@@ -50,7 +56,8 @@ __device__ __forceinline__ float dpp_f(float v)
 {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
-__device__ __forceinline__ void row_sums(float (&v)[kGradComps])
+// sum over the 16 lanes of a row, left in every lane of the row
+__device__ __forceinline__ void group_sums(float (&v)[kGradComps])
 {
 #pragma unroll
     for (u32 c = 0; c < kGradComps; ++c) v[c] += dpp_f<0xB1>(v[c]);     // quad_perm [1,0,3,2]
@@ -60,6 +67,22 @@ __device__ __forceinline__ void row_sums(float (&v)[kGradComps])
     for (u32 c = 0; c < kGradComps; ++c) v[c] += dpp_f<0x141>(v[c]);    // row_half_mirror: the other quad of the 8
 #pragma unroll
     for (u32 c = 0; c < kGradComps; ++c) v[c] += dpp_f<0x140>(v[c]);    // row_mirror: the other 8 of the 16
+}
+
+// one list entry on its way from the feature records to LDS: fetched a batch ahead, so that the two
+// dependent reads (index, then record) are in flight while the previous batch is walked
+struct Fetched { float4 a, b; float blue; u32 id; };
+__device__ __forceinline__ Fetched fetch_entry(const u32 *__restrict__ vals, const float4 *__restrict__ feat,
+                                               u64 pos, bool valid)
+{
+    Fetched r;
+    r.a = r.b = make_float4(0.f, 0.f, 0.f, 0.f); r.blue = 0.0f; r.id = 0u;
+    if (valid) {
+        r.id = vals[pos];
+        const float4 *f = feat + (size_t)r.id * (LMK_GS_FEAT_STRIDE / 4);
+        r.a = f[0]; r.b = f[1]; r.blue = f[2].x;
+    }
+    return r;
 }
 
 // the survivors of one batch for one wavefront: slots of the entries that pass the block test
@@ -121,9 +144,9 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     __shared__ float4 s_tst[kBwdBatch];          // B', C', b, -B/C
     __shared__ u32 s_id[kBwdBatch];              // primitive index
     __shared__ float s_acc[kBwdBatch][kGradComps];
-    __shared__ slot_t s_list[kBwdThreads / kWave][kBwdBatch];
-    __shared__ slot_t s_list4[kBwdThreads / kWave][4][kBwdBatch];
-    __shared__ u32 s_last[kBwdThreads / kWave];
+    __shared__ slot_t s_list[kBwdWaves][kBwdBatch];
+    __shared__ slot_t s_list4[kBwdWaves][4][kBwdBatch];
+    __shared__ u32 s_last[kBwdWaves];
 
     if (blockIdx.x >= bp.num_tiles) return;
     // the tiles with the longest lists first, when the caller has the hint
@@ -140,7 +163,6 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     const float bx = (float)((wv & 1u) * 8u), by = (float)((wv >> 1) * 8u);
     const float ox = bx + ((float)bi - 3.5f), oy = by + ((float)bj - 3.5f);
     const float X0 = (float)(tx * LMK_GS_TILE) + 4.0f, Y0 = (float)(ty * LMK_GS_TILE) + 4.0f;
-    const float kL2E = 1.4426950408889634f;
     const u64 start = tile_offsets[tile], end = tile_offsets[tile + 1];
     const u64 len64 = end - start;
     const u32 len = len64 < 0xffffff00ull ? (u32)len64 : 0xffffff00u;     // a tile's list is far shorter
@@ -151,16 +173,16 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     float T = 1.0f;
     u32 last = 0;                       // entries of the list up to and including the last composited one
     bool done = !inside;
+    Fetched next = fetch_entry(vals, feat, start + tid, tid < kBwdBatch && tid < len);
     for (u32 base = 0; base < len; base += kBwdBatch) {
         if (__syncthreads_and(done)) break;        // also: everyone is past the previous batch
         const u32 cnt = len - base < kBwdBatch ? len - base : kBwdBatch;
         if (tid < cnt) {
-            const u32 g = vals[start + base + tid];
-            const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
-            const StagedEntry se = stage_entry(f[0], f[1], 0.0f, X0, Y0);
+            const StagedEntry se = stage_entry(next.a, next.b, 0.0f, X0, Y0);
             s_geo[tid] = se.geo; s_cop[tid] = se.cop; s_tst[tid] = se.tst;
         }
         __syncthreads();
+        next = fetch_entry(vals, feat, start + base + kBwdBatch + tid, tid < kBwdBatch && base + kBwdBatch + tid < len);
         if (__builtin_amdgcn_ballot_w64(!done) == 0ull) continue;     // this wavefront is finished
         const u32 n8 = block_survivors(s_geo, s_cop, s_tst, cnt, bx, by, lane, my_list);
         u32 n4[4];
@@ -197,7 +219,7 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     __syncthreads();
     u32 max_last = 0;
 #pragma unroll
-    for (u32 k = 0; k < kBwdThreads / kWave; ++k) max_last = s_last[k] > max_last ? s_last[k] : max_last;
+    for (u32 k = 0; k < kBwdWaves; ++k) max_last = s_last[k] > max_last ? s_last[k] : max_last;
     if (max_last == 0) return;
 
     // ---- pass 2: back to front
@@ -210,22 +232,22 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
     const float gT_end = gT * T_end;
     float Sr = bp.bg0 * T_end, Sg = bp.bg1 * T_end, Sb = bp.bg2 * T_end;
     T = T_end;
-    const bool row_leader = (lane & 15u) == 0u;
-    for (u32 b = (max_last + kBwdBatch - 1) / kBwdBatch; b-- > 0;) {
+    const bool leader = (lane & 15u) == 0u;
+    const u32 batches = (max_last + kBwdBatch - 1) / kBwdBatch;
+    next = fetch_entry(vals, feat, start + (batches - 1u) * kBwdBatch + tid,
+                       tid < kBwdBatch && (batches - 1u) * kBwdBatch + tid < max_last);
+    for (u32 b = batches; b-- > 0;) {
         const u32 base = b * kBwdBatch;
         const u32 cnt = max_last - base < kBwdBatch ? max_last - base : kBwdBatch;
         __syncthreads();                // the previous batch has been flushed
         if (tid < cnt) {
-            const u32 g = vals[start + base + tid];
-            const float4 *f = feat + (size_t)g * (LMK_GS_FEAT_STRIDE / 4);
-            const StagedEntry se = stage_entry(f[0], f[1], f[2].x, X0, Y0);
+            const StagedEntry se = stage_entry(next.a, next.b, next.blue, X0, Y0);
             s_geo[tid] = se.geo; s_cop[tid] = se.cop; s_tst[tid] = se.tst;
-            s_id[tid] = g;
+            s_id[tid] = next.id;
         }
-        if (tid < kBwdBatch) {
-#pragma unroll
-            for (u32 k = 0; k < kGradComps; ++k) s_acc[tid][k] = 0.0f;
-        }
+        // the batch in front of this one (all of its slots lie below max_last)
+        next = fetch_entry(vals, feat, start + base - kBwdBatch + tid, b > 0u && tid < kBwdBatch);
+        for (u32 k = tid; k < kBwdBatch * kGradComps; k += kBwdThreads) (&s_acc[0][0])[k] = 0.0f;
         __syncthreads();
         // a wavefront none of whose pixels walked this far has nothing to add (it still takes part
         // in the barriers and the flush below)
@@ -246,46 +268,51 @@ __global__ __launch_bounds__(kBwdThreads) void blend_backward_kernel(
             const bool hit = in_list && base + j < last && !(alpha < 1.0f / 255.0f);
             const u64 hits = __builtin_amdgcn_ballot_w64(hit);
             if (hits == 0ull) continue;                                  // nothing from this wavefront
+            // a pixel without a contribution goes through the same arithmetic with a = 0: T and S
+            // stay as they are and all nine moments are zero
+            const float a = hit ? alpha : 0.0f;
+            const float blue = s_tst[j].z;
+            const float inv = __builtin_amdgcn_rcpf(1.0f - a);     // 1 - a >= 0.01; one ulp is enough here
+            // dL/da = (dL/dC . (T c - S) - dL/dT_end T_end) / (1 - a), T = transmittance behind the entry
+            const float num = fmaf(gr, fmaf(T, co.z, -Sr), fmaf(gg, fmaf(T, co.w, -Sg), fmaf(gb, fmaf(T, blue, -Sb), -gT_end)));
+            T *= inv;                                              // transmittance in front of this entry
+            const float w = a * T;
+            Sr = fmaf(co.z, w, Sr); Sg = fmaf(co.w, w, Sg); Sb = fmaf(blue, w, Sb);
+            const float m = (raw > 0.99f ? 0.0f : a) * (num * inv);     // a dL/da; a clamped alpha depends on nothing
             float v[kGradComps];
-#pragma unroll
-            for (u32 c = 0; c < kGradComps; ++c) v[c] = 0.0f;
-            if (hit) {
-                const float4 ts = s_tst[j];
-                const float inv = __builtin_amdgcn_rcpf(1.0f - alpha);     // 1 - alpha >= 0.01; one ulp is enough here
-                const float Ti = T * inv;                   // transmittance in front of this entry
-                const float w = alpha * Ti;
-                const float dLda = gr * (Ti * co.z - Sr * inv) + gg * (Ti * co.w - Sg * inv)
-                                 + gb * (Ti * ts.z - Sb * inv) - gT_end * inv;
-                Sr = fmaf(co.z, w, Sr); Sg = fmaf(co.w, w, Sg); Sb = fmaf(ts.z, w, Sb);
-                T = Ti;
-                v[6] = w * gr; v[7] = w * gg; v[8] = w * gb;
-                if (!(raw > 0.99f)) {
-                    v[5] = dLda * (alpha * __builtin_amdgcn_exp2f(-co.y));      // alpha / opacity
-                    const float dLdq = -0.5f * alpha * dLda;
-                    v[2] = dLdq * dx * dx;
-                    v[3] = dLdq * 2.0f * dx * dy;
-                    v[4] = dLdq * dy * dy;
-                    // 2 (A dx + B dy) and 2 (B dx + C dy) from A' = -0.5 log2(e) A, B' = -log2(e) B, C' likewise
-                    const float kInv = -2.0f / kL2E;
-                    v[0] = dLdq * kInv * (2.0f * g.z * dx + ts.x * dy);
-                    v[1] = dLdq * kInv * (ts.x * dx + 2.0f * ts.y * dy);
-                }
-            }
-            // the nine row sums side by side (independent DPP chains), then one guarded group of
-            // LDS atomics from the first lane of every row that had a contribution
-            row_sums(v);
+            v[0] = m * dx; v[1] = m * dy;
+            v[2] = v[0] * dx; v[3] = v[0] * dy; v[4] = v[1] * dy;
+            v[5] = m;
+            v[6] = w * gr; v[7] = w * gg; v[8] = w * gb;
+            group_sums(v);
+            // one group of LDS atomics from the first lane of every row that had a contribution
             const bool row_hit = ((hits >> (lane & 48u)) & 0xffffull) != 0ull;
-            if (row_leader && row_hit) {
+            if (leader && row_hit) {
 #pragma unroll
                 for (u32 c = 0; c < kGradComps; ++c) atomicAdd(&s_acc[j][c], v[c]);
             }
         }
         __syncthreads();
-        // consecutive lanes take the consecutive components of an entry, so that the atomics of one
+        // from the moments of an entry to its gradient: q = A dx^2 + 2 B dx dy + C dy^2, da/dq = -a / 2,
+        // da/do = a / o; the staged A' = -0.5 log2(e) A, B' = -log2(e) B, C' = -0.5 log2(e) C give
+        // d/du = ln 2 (2 A' sum m dx + B' sum m dy), d/dv = ln 2 (B' sum m dx + 2 C' sum m dy).
+        // Consecutive lanes take the consecutive components of an entry, so that the atomics of one
         // instruction fall into few cache lines (nine lanes per 36-byte record)
         for (u32 idx = tid; idx < cnt * kGradComps; idx += kBwdThreads) {
             const u32 e = idx / kGradComps, c = idx - e * kGradComps;
-            const float v = s_acc[e][c];
+            const float kLn2 = 0.6931471805599453f;
+            float v = s_acc[e][c];
+            if (c < 2u) {
+                const float mx = s_acc[e][0], my = s_acc[e][1];
+                const float Aq = s_geo[e].z, Bq = s_tst[e].x, Cq = s_tst[e].y;
+                v = c == 0u ? kLn2 * fmaf(2.0f * Aq, mx, Bq * my) : kLn2 * fmaf(Bq, mx, 2.0f * Cq * my);
+            } else if (c == 2u || c == 4u) {
+                v *= -0.5f;
+            } else if (c == 3u) {
+                v = -v;
+            } else if (c == 5u) {
+                v *= __builtin_amdgcn_exp2f(-s_cop[e].y);       // 1 / opacity
+            }
             if (v != 0.0f) atomicAdd(grad_feat + (size_t)s_id[e] * LMK_GS_FEAT_STRIDE + c, v);
         }
     }
