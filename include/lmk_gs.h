@@ -197,7 +197,10 @@ int32_t lmk_gs_preprocess_culled(const lmk_gs_gaussians *g, const lmk_gs_voxel_i
  * If the pair count D exceeds `capacity`, nothing is emitted: the status word
  * becomes LMK_GS_ERR_CAPACITY, every tile range is empty (lmk_gs_render then gives
  * the background), keys/vals are left as they were, and D (lmk_gs_read_status) tells
- * how much room a retry needs. */
+ * how much room a retry needs.  The call may be repeated for the same frame -- same
+ * proj and scratch, no lmk_gs_preprocess in between, e.g. with larger buffers after an
+ * overflow (the scratch must have been sized for the larger capacity): the status
+ * word is that of the latest call. */
 int32_t lmk_gs_bin_sort(const lmk_gs_projected *proj, uint32_t n, const lmk_gs_camera *cam,
                         const lmk_gs_binned *out,
                         void *scratch, size_t scratch_bytes, void *stream);

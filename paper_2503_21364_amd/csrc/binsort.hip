@@ -372,9 +372,10 @@ __global__ __launch_bounds__(kLargeThreads) void count_large_kernel(
 }
 
 // ---------------------------------------------------------------- scan + order + size classes
-// One workgroup.  (1) D = sum of the per-tile counts; more than the buffers hold: status, and every
-// list is treated as empty from here on.  (2) tile_offsets = exclusive prefix sum of the counts.
-// (3) Tile ids by descending list length, bucketed by the bit length of (length - 1), so that
+// Two workgroups, each of which is a chain of memory round trips and barriers rather than data, so
+// they run side by side.  Both: (1) D = sum of the per-tile counts; more than the buffers hold:
+// status, and every list is treated as empty from here on.  Workgroup 0: (2) tile_offsets =
+// exclusive prefix sum of the counts.  Workgroup 1: (3) tile ids by descending list length, bucketed by the bit length of (length - 1), so that
 // the size classes of the per-tile sort are whole buckets.  From the front of `order`:
 //   classes[0]  lists longer than kHuge pairs          one workgroup each, merges between the pair buffers
 //   classes[3]  kMid + 1 .. kHuge ("long")             cut into chunks of kMid pairs, see below
@@ -385,9 +386,10 @@ __global__ __launch_bounds__(kLargeThreads) void count_large_kernel(
 // starts first, never a result.  A long list is sorted as 2 .. 4 chunks by workgroups of the
 // 512-thread kernel and merged in two rounds by workgroups of the next two kernels, so that it
 // costs no kernel of its own: chunk_list = (tile, chunk) of every such chunk, classes[4] = how many.
-// (4) The counters are left zero for the next call.
-// A single workgroup's time is memory round trips, not data: with SMALL (up to 8192 tiles) every
-// thread reads its eight counters once and everything else works from registers and LDS.
+// The counters stay as they are until both workgroups are done with them; the first kernel of the
+// per-tile sort leaves them zero for the next call.
+// With SMALL (up to 8192 tiles) every thread reads its eight counters once and everything else works
+// from registers and LDS.
 constexpr u32 kSmallThreads = 64, kSmallItems = 8, kSmallCap = kSmallThreads * kSmallItems;   // 512
 constexpr u32 kLowThreads = 256, kLowItems = 8;                                               // 2048
 constexpr u32 kMidThreads = 512, kMidItems = 8, kMid = kMidThreads * kMidItems;               // 4096
@@ -412,7 +414,7 @@ static_assert(kLdsTilesSmall == kScanThreads * kScanItems, "SMALL: one round of 
 
 template <bool SMALL>
 __global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(
-    u32 *__restrict__ tile_count, u32 *__restrict__ large_count, u32 num_tiles, u64 capacity, ScratchHeader *__restrict__ header,
+    const u32 *__restrict__ tile_count, const u32 *__restrict__ large_count, u32 num_tiles, u64 capacity, ScratchHeader *__restrict__ header,
     u64 *__restrict__ tile_offsets, u32 *__restrict__ tile_cursor, u64 *__restrict__ prim_offsets_if_empty,
     u32 *__restrict__ order, u32 *__restrict__ order_copy, u32 *__restrict__ classes,
     uint2 *__restrict__ chunk_list, u64 chunk_capacity)
@@ -456,9 +458,12 @@ __global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(
 #pragma unroll
     for (u32 k = 0; k < kWaves; ++k) D += s_sum[k];
     const bool overflow = D > capacity;
-    if (tid == 0) {
+    // two workgroups share the work: 0 writes D, the status and the ranges, 1 the order, the size
+    // classes and the chunk list; both need the list lengths and D
+    const bool ranges_part = blockIdx.x == 0;
+    if (tid == 0 && ranges_part) {
         header->dup_count = D;
-        if (overflow) header->status = LMK_GS_ERR_CAPACITY;
+        header->status = overflow ? LMK_GS_ERR_CAPACITY : LMK_GS_OK;      // of this call; the frame's earlier calls do not count
         // with no primitives nothing else writes the one-entry prefix sum over the primitives
         if (prim_offsets_if_empty) prim_offsets_if_empty[0] = 0;
     }
@@ -473,7 +478,7 @@ __global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(
 
     // ---- (2) per-tile ranges: kScanItems consecutive tiles per thread, entry num_tiles = the end
     u64 carry = 0;
-    for (u32 base = 0; base <= num_tiles; base += kScanThreads * kScanItems) {
+    for (u32 base = 0; ranges_part && base <= num_tiles; base += kScanThreads * kScanItems) {
         const u32 t0 = base + tid * kScanItems;
         u32 c[kScanItems], runs[kScanItems];
         u64 mine = 0;
@@ -516,6 +521,8 @@ __global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(
         carry = total;
         __syncthreads();                       // s_sum free again
     }
+
+    if (ranges_part) return;
 
     // ---- (3) order and size classes.  Tile of (thread, round j): SMALL tid * kScanItems + j, else
     // base + j * kScanThreads + tid.
@@ -618,10 +625,8 @@ __global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(
         chunk_carry = total;
     }
     if (tid == 0) classes[4] = (u64)chunk_carry < chunk_capacity ? chunk_carry : (u32)chunk_capacity;
-
-    // ---- (4) every read of the counters is done: leave them zero
-    __syncthreads();
-    for (u32 t = tid; t <= num_tiles; t += kScanThreads) { tile_count[t] = 0; large_count[t] = 0; }
+    // the counters are left as they are: the other workgroup may still be reading them; the first
+    // kernel of the per-tile sort zeroes them
 }
 
 // ---------------------------------------------------------------- emit
@@ -1110,12 +1115,16 @@ __global__ __launch_bounds__(kSmallThreads) void tile_sort_small_kernel(
 __global__ __launch_bounds__(kHugeThreads) void tile_sort_huge_kernel(
     u64 *__restrict__ keys, u32 *__restrict__ vals, u64 *__restrict__ keys_alt, u32 *__restrict__ vals_alt,
     const u64 *__restrict__ tile_offsets, const u32 *__restrict__ order, const u32 *__restrict__ classes,
-    u32 num_tiles, ScratchHeader *__restrict__ header)
+    u32 num_tiles, ScratchHeader *__restrict__ header, u32 *__restrict__ tile_count)
 {
     __shared__ u64 s[kHuge + kHuge / 16];
     __shared__ u64 s_split[kHugeThreads / kWave][2];
-    // the emit kernel has consumed the deferred list: empty it for the next call
-    if (blockIdx.x == 0 && threadIdx.x == 0) { header->big_count = 0; header->giant_count = 0; }
+    // the scan has read the per-tile counters (both halves) and the emit kernel has consumed the
+    // deferred list: leave them empty for the next call
+    if (blockIdx.x == 0) {
+        if (threadIdx.x == 0) { header->big_count = 0; header->giant_count = 0; }
+        for (u32 t = threadIdx.x; t < 2u * (num_tiles + 1u); t += kHugeThreads) tile_count[t] = 0;
+    }
     if (blockIdx.x >= classes[0] || blockIdx.x >= num_tiles) return;
     const u32 tile = order[blockIdx.x];
     if (tile >= num_tiles) return;
@@ -1259,12 +1268,12 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
         if (e != hipSuccess) return e;
     }
     if (num_tiles <= kLdsTilesSmall)
-        hipLaunchKernelGGL(tile_scan_kernel<true>, dim3(1), dim3(kScanThreads), 0, stream,
+        hipLaunchKernelGGL(tile_scan_kernel<true>, dim3(2), dim3(kScanThreads), 0, stream,
                            tile_count, large_count, num_tiles, out.capacity, header, out.tile_offsets, tile_cursor,
                            n == 0 ? proj.offsets : nullptr, order, out.tile_order, classes, chunk_list,
                            out.capacity / 2048 + 2);
     else
-        hipLaunchKernelGGL(tile_scan_kernel<false>, dim3(1), dim3(kScanThreads), 0, stream,
+        hipLaunchKernelGGL(tile_scan_kernel<false>, dim3(2), dim3(kScanThreads), 0, stream,
                            tile_count, large_count, num_tiles, out.capacity, header, out.tile_offsets, tile_cursor,
                            n == 0 ? proj.offsets : nullptr, order, out.tile_order, classes, chunk_list,
                            out.capacity / 2048 + 2);
@@ -1304,7 +1313,8 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     const u32 max_low = at_most(out.capacity / (kSmallCap + 1) + 1, num_tiles);
     const u32 merge1 = at_most(2ull * max_mid, kMergeBlocks1), merge2 = at_most(8ull * max_mid, kMergeBlocks2);
     hipLaunchKernelGGL(tile_sort_huge_kernel, dim3(max_huge), dim3(kHugeThreads), 0, stream,
-                       out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes, num_tiles, header);
+                       out.keys, out.vals, out.keys_alt, out.vals_alt, out.tile_offsets, order, classes, num_tiles, header,
+                       tile_count);
     hipLaunchKernelGGL(tile_sort_mid_kernel, dim3(max_mid), dim3(kMidThreads), 0, stream,
                        out.keys, out.vals, out.tile_offsets, order, classes, chunk_list, num_tiles);
     hipLaunchKernelGGL(tile_sort_low_kernel, dim3(merge1 + max_low), dim3(kLowThreads), 0, stream,

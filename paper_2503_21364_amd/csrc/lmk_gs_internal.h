@@ -26,7 +26,7 @@ constexpr u32 kChunk = 4096;            // pairs sorted in LDS by one workgroup 
 // Header at the start of the scratch buffer.
 struct ScratchHeader {
     u64 dup_count;      // D = pairs of the frame = sum of tiles_touched (known when lmk_gs_preprocess is done)
-    int32_t status;     // sticky LMK_GS_* code set by kernels
+    int32_t status;     // LMK_GS_* code of the frame's latest stage 2 (LMK_GS_OK after stage 1)
     int32_t pad;
     u32 big_count;      // stage 2: primitives on the deferred list, from the front (one wavefront each)
     u32 giant_count;    // ... and from the back (one workgroup each)

@@ -262,6 +262,35 @@ def test_capacity_overflow_sets_status_and_stays_in_bounds(n, scale_mul, wh, bin
     P.compare_binned(fr2, ofr.binned)
 
 
+@pytest.mark.parametrize("binning", [0, 1])
+def test_bin_sort_again_on_the_same_scratch_after_an_overflow(binning):
+    """Stage 2 leaves the scratch ready for another stage 2: after a call that overflowed, a second
+    call with enough room -- same scratch, no preprocess in between -- gives the oracle's arrays, and
+    a third call gives them again."""
+    sc = scenes.make_scene(0, n=20000, seed=23)
+    sc["scale"] = sc["scale"] * np.float32(3.0)           # rectangles on all three paths of stage 2
+    cam = dict(scenes.make_cameras(0, 640, 360)[0], binning=binning)
+    ofr = ref.render_frame(sc, cam)
+    dev = B.Scene(sc)
+    fr = B.Frame(dev.n, 640, 360, ofr.binned.D + 7, want_offsets=True)
+    cc = B.make_camera(cam)
+    B.preprocess(dev, cc, fr)
+    full = fr.binned.capacity
+    fr.binned.capacity = ofr.binned.D // 3               # the scratch was sized for the larger capacity
+    B.bin_sort(cc, fr)
+    torch.cuda.synchronize()
+    D, status = B.read_status(fr)
+    assert D == ofr.binned.D and status == B.ERR_CAPACITY
+    assert not P.to_np(fr.tile_offsets).any()
+    fr.binned.capacity = full
+    for _ in range(2):
+        B.bin_sort(cc, fr)
+        torch.cuda.synchronize()
+        D, status = B.read_status(fr)
+        assert D == ofr.binned.D and status == B.OK         # the status is that of the latest call
+        P.compare_binned(fr, ofr.binned)
+
+
 # ------------------------------------------------------------------ stage isolation
 def _upload_projected(fr, pre):
     n = pre.n
