@@ -144,10 +144,13 @@ __device__ __forceinline__ void walk_large(ushort4 r, const float4 *__restrict__
 // counted in LDS, larger ones listed.  LDS_TILES == 0 (images of more tiles): every primitive is
 // listed.
 // A workgroup takes kBinBlock consecutive primitives, kBinBlock / THREADS per thread (primitive
-// tid + j THREADS in round j): with 32 KB of counters, workgroups of 256 threads fit four to a
-// compute unit, and what bounds these kernels is the chain of memory round trips of a workgroup.
+// tid + j THREADS in round j).  What bounds these kernels is the chain of memory round trips of a
+// workgroup, so the compute unit should be full of wavefronts: with 32 KB of counters four
+// workgroups fit, and four workgroups of 512 threads are all the wavefronts it can hold.
+constexpr u32 kRunBits = 11;             // a workgroup's pairs in one tile, minus one, fit these many bits
+static_assert(kBinBlock <= (1u << kRunBits), "(count - 1) of a run is packed into kRunBits bits");
 template <u32 LDS_TILES> struct BinShape {
-    static constexpr u32 kThreads = LDS_TILES == kLdsTilesSmall ? 256u : kBinBlock;
+    static constexpr u32 kThreads = LDS_TILES == kLdsTilesSmall ? kBinBlock / 4u : 1024u;
     static constexpr u32 kPer = kBinBlock / kThreads;
     static constexpr u32 kWaves = kThreads / kWave;
     static constexpr u32 kRounds = LDS_TILES / kThreads;    // counters per thread
@@ -280,7 +283,7 @@ __global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void count_kernel(
         }
     }
     if (!LDS) return;
-    // The tiles this workgroup touched, compacted to the front of s_hist as tile << 11 | (count - 1)
+    // The tiles this workgroup touched, compacted to the front of s_hist as tile << kRunBits | (count - 1)
     // (a workgroup holds 1024 primitives and a primitive has one pair per tile at most): every
     // thread first reads its counters, then, all reads done, the entries are written.
     u32 c[kRounds];
@@ -300,7 +303,7 @@ __global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void count_kernel(
         at = __shfl(at, leader, 64);
         if (c[k] != 0u)
             s_hist[at + __builtin_amdgcn_mbcnt_hi((u32)(nz >> 32), __builtin_amdgcn_mbcnt_lo((u32)nz, 0u))] =
-                ((k * kThreads + tid) << 11) | ((c[k] - 1u) & 2047u);
+                ((k * kThreads + tid) << kRunBits) | ((c[k] - 1u) & ((1u << kRunBits) - 1u));
     }
     __syncthreads();
     const u32 touched = s_next;
@@ -315,12 +318,12 @@ __global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void count_kernel(
         for (u32 q = 0; q < kFlush; ++q) {
             const u32 k = k0 + q * kThreads + tid;
             ent[q] = k < touched ? s_hist[k] : 0u;
-            start[q] = k < touched ? atomicAdd(&tile_count[ent[q] >> 11], (ent[q] & 2047u) + 1u) : 0u;
+            start[q] = k < touched ? atomicAdd(&tile_count[ent[q] >> kRunBits], (ent[q] & ((1u << kRunBits) - 1u)) + 1u) : 0u;
         }
 #pragma unroll
         for (u32 q = 0; q < kFlush; ++q) {
             const u32 k = k0 + q * kThreads + tid;
-            if (k < touched && first + k < list_capacity) list[first + k] = make_uint2(ent[q] >> 11, start[q]);
+            if (k < touched && first + k < list_capacity) list[first + k] = make_uint2(ent[q] >> kRunBits, start[q]);
         }
     }
 }
@@ -1240,7 +1243,7 @@ hipError_t launch_bin_sort(const lmk_gs_projected &proj, u32 n, const ProjParams
     const bool tight = pp.cam.binning == 1u;
     const bool wide = out.capacity > 0xffffffffull;
     const u32 lds_tiles = num_tiles <= kLdsTilesSmall ? kLdsTilesSmall : (num_tiles <= kLdsTilesLarge ? kLdsTilesLarge : 0u);
-    const u32 bin_threads = lds_tiles == kLdsTilesSmall ? BinShape<kLdsTilesSmall>::kThreads : kBinBlock;
+    const u32 bin_threads = lds_tiles == kLdsTilesSmall ? BinShape<kLdsTilesSmall>::kThreads : BinShape<kLdsTilesLarge>::kThreads;
     // the listed primitives are walked by fixed grids striding over the two lists: as workgroups of
     // kLargeThreads threads in the counting pass, as workgroups of the emit kernel behind its own
     const u32 large_blocks = 4u * L.bin_blocks < kLargeBlocks ? 4u * L.bin_blocks : kLargeBlocks;

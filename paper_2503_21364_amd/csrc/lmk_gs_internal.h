@@ -14,7 +14,7 @@ typedef uint32_t u32;
 
 constexpr u32 kWave = 64;               // CDNA wavefront width
 constexpr u32 kPreBlock = LMK_GS_PRE_BLOCK;   // primitives per preprocess workgroup
-constexpr u32 kBinBlock = 1024;         // primitives per workgroup of the counting and emit kernels of stage 2
+constexpr u32 kBinBlock = 2048;         // primitives per workgroup of the counting and emit kernels of stage 2
 constexpr u32 kScanGroup = 256;         // preprocess workgroups per group of the two-level prefix sum
 static_assert(kScanGroup % (kBinBlock / kPreBlock) == 0, "the blocks of one counting workgroup lie in one group");
 // The counting and emit kernels keep one counter per tile in LDS: up to 8192 tiles (1080p has
