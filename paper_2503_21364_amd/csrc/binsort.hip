@@ -7,7 +7,7 @@
 // sort fixes it.  The pairs are therefore written straight into their tile's slice, never
 // partitioned by a sort over the tile bits: count per tile, scan, then write on a second walk.
 //
-//   count    one workgroup per 1024 consecutive primitives.  A rectangle of up to 32 tiles (nearly
+//   count    one workgroup per kBinBlock (2048) consecutive primitives.  A rectangle of up to 32 tiles (nearly
 //            all of them) is walked by its own lane -- binning rule 0: every tile; rule 1: the kept
 //            tiles, from the bit mask the projection kernel left -- and counted per tile in LDS.  A
 //            scene in spatial order puts a workgroup's pairs into few tiles, and the workgroup then
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(BinShape<LDS_TILES>::kThreads) void count_kernel(
     }
     if (!LDS) return;
     // The tiles this workgroup touched, compacted to the front of s_hist as tile << kRunBits | (count - 1)
-    // (a workgroup holds 1024 primitives and a primitive has one pair per tile at most): every
+    // (a workgroup holds kBinBlock primitives and a primitive has one pair per tile at most): every
     // thread first reads its counters, then, all reads done, the entries are written.
     u32 c[kRounds];
 #pragma unroll
@@ -633,7 +633,7 @@ __global__ __launch_bounds__(kScanThreads) void tile_scan_kernel(
 }
 
 // ---------------------------------------------------------------- emit
-// Workgroups [0, bin_blocks) repeat the walk of the small rectangles of their 1024 primitives; the
+// Workgroups [0, bin_blocks) repeat the walk of the small rectangles of their kBinBlock primitives; the
 // LDS counters now start at the tile's range start + the workgroup's run start and hand out
 // positions.  The workgroups behind them walk the listed primitives and advance the tiles'
 // running positions pair by pair.
